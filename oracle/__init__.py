@@ -1,0 +1,22 @@
+"""CPU oracle for the AttentionPack decode hot path.
+
+TEST INFRASTRUCTURE ONLY.  Nothing in the product package may import this
+module; it is used by tests/, by __graft_entry__.smoke() and by the
+cpu_baseline leg of bench.py.  It shares no code with the HIP kernels.
+"""
+from .attnpack_oracle import (  # noqa: F401
+    promote,
+    bases,
+    compact,
+    decode_attn,
+    decode_attn_absorbed,
+    decode_attn_batched,
+    attention_probs,
+    select_ranks,
+    quantize_i8,
+    dequantize_i8,
+    compression_ratio,
+    decompression_flops,
+    cache_bytes,
+    importance_update,
+)

@@ -1,0 +1,312 @@
+"""Plain fp64 CPU oracle for decode attention over a multi-head-compacted,
+low-rank KV cache (AttentionPack).
+
+TEST INFRASTRUCTURE ONLY: slow, obviously-correct NumPy.  The product (the HIP
+library and its Python binding) never imports this file and this file imports
+nothing from the product.
+
+Notation follows the paper: a layer's cache K, V in R^{T x HD} (heads merged
+along the hidden axis, Sec. 3.1) is stored as coefficients  Kbar, Vbar in
+R^{T x R}  ("C_k", "C_v" here) and decompression matrices  D_k, D_v in
+R^{R x HD}  ("B_k", "B_v", the bases).  Head h owns hidden columns
+[h*d, (h+1)*d).
+
+Every function works on ONE sequence of ONE layer unless it says "batched".
+All arithmetic is float64 except `quantize_i8`, whose recipe fixes fp32/fp16.
+"""
+from __future__ import annotations
+
+import math
+from typing import Optional, Sequence, Tuple
+
+import numpy as np
+
+# --------------------------------------------------------------------------
+# exact promotion of stored bits to float64
+# --------------------------------------------------------------------------
+
+def promote(x: np.ndarray, dtype: str) -> np.ndarray:
+    """Stored array -> float64, exactly.
+
+    dtype: "f32" (np.float32 array), "f16" (np.float16 array) or "bf16"
+    (np.uint16 array holding bfloat16 bit patterns: a bfloat16 is the upper
+    half of an IEEE binary32, so shifting left by 16 bits gives its value).
+    """
+    if dtype == "f32":
+        assert x.dtype == np.float32
+        return x.astype(np.float64)
+    if dtype == "f16":
+        assert x.dtype == np.float16
+        return x.astype(np.float64)
+    if dtype == "bf16":
+        assert x.dtype == np.uint16
+        return (x.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
+    raise ValueError(f"unknown dtype tag {dtype!r}")
+
+
+# --------------------------------------------------------------------------
+# compression (Sec. 3.1): K ~= Kbar D_k
+# --------------------------------------------------------------------------
+
+def bases(X: np.ndarray, r: int) -> np.ndarray:
+    """Decompression matrix D in R^{r x HD} of the head-merged cache X [T, HD].
+
+    Sec. 3.1: low-rank SVD of the matrix with all heads concatenated along the
+    hidden axis.  Rows of D are the r leading right singular vectors (plain
+    SVD, no centring), ordered by decreasing singular value.
+    """
+    X = np.asarray(X, dtype=np.float64)
+    _, _, vt = np.linalg.svd(X, full_matrices=False)
+    return vt[:r].copy()
+
+
+def compact(X: np.ndarray, D: np.ndarray) -> np.ndarray:
+    """Coefficients Kbar = X D^T  [T, r]  for a given decompression matrix.
+
+    Sec. 3.1: the first factor of the decomposition has its columns scaled by
+    the singular values, i.e. Kbar = U_r Sigma_r; for D with orthonormal rows
+    (right singular vectors) that equals X D^T.  The same projection is used
+    when a token is appended to a cache whose basis is already fixed.
+    """
+    return np.asarray(X, dtype=np.float64) @ np.asarray(D, dtype=np.float64).T
+
+
+# --------------------------------------------------------------------------
+# decode attention (Alg. 1, retrieve / scores / output steps)
+# --------------------------------------------------------------------------
+
+def _ranks(rank: Optional[np.ndarray], T: int, r: int) -> np.ndarray:
+    if rank is None:
+        return np.full(T, r, dtype=np.int64)
+    rank = np.asarray(rank).astype(np.int64)
+    assert rank.shape == (T,)
+    assert rank.min() >= 0 and rank.max() <= r
+    return rank
+
+
+def _partial_decompress(C: np.ndarray, D: np.ndarray, rank: np.ndarray) -> np.ndarray:
+    """Alg. 1 "retrieve cache": token t is rebuilt from its leading rank[t]
+    coefficient columns and the leading rank[t] rows of D."""
+    T = C.shape[0]
+    X = np.zeros((T, D.shape[1]), dtype=np.float64)
+    for t in range(T):
+        rt = int(rank[t])
+        X[t] = C[t, :rt] @ D[:rt, :]
+    return X
+
+
+def _softmax_rows(s: np.ndarray) -> np.ndarray:
+    m = s.max(axis=-1, keepdims=True)
+    e = np.exp(s - m)
+    return e / e.sum(axis=-1, keepdims=True)
+
+
+def attention_probs(q, Ck, Bk, rank_k=None, sm_scale=None) -> np.ndarray:
+    """Attention weights A [H, T] of one decode query (Alg. 1 score step):
+    softmax over all cached tokens of q_h . Ktilde_h[t] / sqrt(d)."""
+    q = np.asarray(q, np.float64)
+    Ck = np.asarray(Ck, np.float64)
+    Bk = np.asarray(Bk, np.float64)
+    H, d = q.shape
+    T, r = Ck.shape
+    if sm_scale is None:
+        sm_scale = 1.0 / math.sqrt(d)
+    Kt = _partial_decompress(Ck, Bk, _ranks(rank_k, T, r))
+    s = np.empty((H, T))
+    for h in range(H):
+        s[h] = Kt[:, h * d:(h + 1) * d] @ q[h] * sm_scale
+    return _softmax_rows(s)
+
+
+def decode_attn(q, Ck, Cv, Bk, Bv, rank_k=None, rank_v=None, sm_scale=None,
+                return_lse: bool = False):
+    """DEFINITION FORM: reconstruct, then textbook softmax attention.
+
+    q [H, d]; Ck, Cv [T, r]; Bk, Bv [r, H*d]; rank_k, rank_v [T] ints or None
+    (None = every token at full rank r).  Returns out [H, d] float64 (the
+    product A Vtilde of Alg. 1, before the output projection W_o) and, if asked,
+    lse [H] = log sum_t exp(scaled score).
+    """
+    q = np.asarray(q, np.float64)
+    Ck = np.asarray(Ck, np.float64)
+    Cv = np.asarray(Cv, np.float64)
+    Bk = np.asarray(Bk, np.float64)
+    Bv = np.asarray(Bv, np.float64)
+    H, d = q.shape
+    T, r = Ck.shape
+    assert Cv.shape == (T, r) and Bk.shape == (r, H * d) and Bv.shape == (r, H * d)
+    if sm_scale is None:
+        sm_scale = 1.0 / math.sqrt(d)
+    Kt = _partial_decompress(Ck, Bk, _ranks(rank_k, T, r))
+    Vt = _partial_decompress(Cv, Bv, _ranks(rank_v, T, r))
+    out = np.empty((H, d))
+    lse = np.empty(H)
+    for h in range(H):
+        s = Kt[:, h * d:(h + 1) * d] @ q[h] * sm_scale          # [T]
+        m = s.max()
+        e = np.exp(s - m)
+        z = e.sum()
+        p = e / z
+        out[h] = p @ Vt[:, h * d:(h + 1) * d]
+        lse[h] = m + math.log(z)
+    return (out, lse) if return_lse else out
+
+
+def decode_attn_absorbed(q, Ck, Cv, Bk, Bv, rank_k=None, rank_v=None, sm_scale=None,
+                         return_lse: bool = False):
+    """ABSORBED FORM: the same result by associativity, never forming K, V.
+
+    q'_h = D_k[:, head h] q_h;  score[h,t] = Kbar[t,:rk_t] . q'_h[:rk_t];
+    u_h[j] = sum_{t: rv_t > j} p[h,t] Vbar[t,j];  out_h = u_h D_v[:, head h].
+    """
+    q = np.asarray(q, np.float64)
+    Ck = np.asarray(Ck, np.float64)
+    Cv = np.asarray(Cv, np.float64)
+    Bk = np.asarray(Bk, np.float64)
+    Bv = np.asarray(Bv, np.float64)
+    H, d = q.shape
+    T, r = Ck.shape
+    if sm_scale is None:
+        sm_scale = 1.0 / math.sqrt(d)
+    rk = _ranks(rank_k, T, r)
+    rv = _ranks(rank_v, T, r)
+    cols = np.arange(r)
+    Mk = (cols[None, :] < rk[:, None])          # [T, r] column kept for K
+    Mv = (cols[None, :] < rv[:, None])
+    Ckm = np.where(Mk, Ck, 0.0)
+    Cvm = np.where(Mv, Cv, 0.0)
+    out = np.empty((H, d))
+    lse = np.empty(H)
+    for h in range(H):
+        qp = Bk[:, h * d:(h + 1) * d] @ q[h]     # [r]
+        s = Ckm @ qp * sm_scale
+        m = s.max()
+        e = np.exp(s - m)
+        z = e.sum()
+        u = (e / z) @ Cvm                        # [r]
+        out[h] = u @ Bv[:, h * d:(h + 1) * d]
+        lse[h] = m + math.log(z)
+    return (out, lse) if return_lse else out
+
+
+def decode_attn_batched(q, Ck, Cv, Bk, Bv, T: int, rank_k=None, rank_v=None,
+                        sm_scale=None, absorbed: bool = False) -> np.ndarray:
+    """Batched wrapper.  q [B,H,d]; Ck, Cv [B,T_cap,r] (rows >= T ignored);
+    Bk, Bv [B,r,HD] or [r,HD] (shared); ranks [B,T] or None.  -> [B,H,d]."""
+    fn = decode_attn_absorbed if absorbed else decode_attn
+    B = q.shape[0]
+    out = np.empty(q.shape, dtype=np.float64)
+    for b in range(B):
+        bk = Bk[b] if Bk.ndim == 3 else Bk
+        bv = Bv[b] if Bv.ndim == 3 else Bv
+        rk = None if rank_k is None else rank_k[b][:T]
+        rv = None if rank_v is None else rank_v[b][:T]
+        out[b] = fn(q[b], Ck[b, :T], Cv[b, :T], bk, bv, rk, rv, sm_scale)
+    return out
+
+
+# --------------------------------------------------------------------------
+# attention-aware rank groups (Sec. 3.2; Alg. 1 "determine the tokens m_f")
+# --------------------------------------------------------------------------
+
+def select_ranks(mass: np.ndarray, group_rank: Sequence[int], cum_num: Sequence[int],
+                 den: int) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
+    """Tokens ordered by importance, cut into F groups; group f decodes at
+    rank group_rank[f] (group 0 = most important = the compression rank).
+
+    Reading fixed for what the paper leaves open: order = (mass descending,
+    token index ascending); group f holds sorted positions
+    [floor(T*cum_num[f-1]/den), floor(T*cum_num[f]/den)) with cum_num[F-1]==den;
+    inside a group token indices are listed ascending.
+
+    Returns (rank [T] int32, bucket_off [F+1] int32, bucket_idx [T] int32).
+    """
+    mass = np.asarray(mass)
+    assert mass.ndim == 1
+    T = mass.shape[0]
+    F = len(group_rank)
+    assert len(cum_num) == F and int(cum_num[-1]) == int(den)
+    order = np.lexsort((np.arange(T), -mass.astype(np.float64)))  # last key primary
+    bounds = [0] + [(T * int(c)) // int(den) for c in cum_num]
+    rank = np.empty(T, dtype=np.int32)
+    bucket_idx = np.empty(T, dtype=np.int32)
+    for f in range(F):
+        members = np.sort(order[bounds[f]:bounds[f + 1]])
+        rank[members] = int(group_rank[f])
+        bucket_idx[bounds[f]:bounds[f + 1]] = members
+    return rank, np.asarray(bounds, dtype=np.int32), bucket_idx
+
+
+def importance_update(I: np.ndarray, A_new: np.ndarray, alpha: float) -> np.ndarray:
+    """Eq. 1: exponential moving average of head-averaged attention weights.
+
+    I [T] running importance, A_new [T_q, H, T] attention weights of the T_q
+    newest query positions.  I <- alpha^{T_q} I + (1 - alpha^{T_q}) * mean over
+    the T_q new queries of (mean over heads of A).
+    """
+    A_new = np.asarray(A_new, np.float64)
+    Tq = A_new.shape[0]
+    a = float(alpha) ** Tq
+    return a * np.asarray(I, np.float64) + (1.0 - a) * A_new.mean(axis=1).sum(axis=0) / Tq
+
+
+# --------------------------------------------------------------------------
+# int8 coefficients (workload definition; the paper only names 4-bit KVQuant)
+# --------------------------------------------------------------------------
+
+def quantize_i8(C: np.ndarray, block: int = 64) -> Tuple[np.ndarray, np.ndarray]:
+    """Per-token, per-`block`-column symmetric int8 codes with an fp16 scale.
+
+    The recipe is fixed in binary32/binary16 so that integer results are
+    unique:  amax = max|c| over the block;  scale = fp16(fp32(amax) / 127f);
+    scale == 0 -> all codes 0;  code = clamp(rint(fp32(c) / fp32(scale)),
+    -127, 127) with IEEE division and round-half-to-even.
+
+    C [T, r] float16 (or float32), r % block == 0.
+    Returns (codes [T, r] int8, scales [T, r/block] float16).
+    """
+    C = np.asarray(C)
+    T, r = C.shape
+    assert r % block == 0
+    c32 = C.astype(np.float32).reshape(T, r // block, block)
+    amax = np.abs(c32).max(axis=2)                                   # exact
+    scale16 = (amax / np.float32(127.0)).astype(np.float16)          # fp32 divide, RNE to fp16
+    s32 = scale16.astype(np.float32)
+    safe = np.where(s32 == 0, np.float32(1.0), s32)
+    quo = c32 / safe[:, :, None]                                     # fp32 divide
+    code = np.clip(np.rint(quo), -127.0, 127.0)
+    code = np.where((s32 == 0)[:, :, None], 0.0, code)
+    return code.astype(np.int8).reshape(T, r), scale16
+
+
+def dequantize_i8(codes: np.ndarray, scales: np.ndarray, block: int = 64) -> np.ndarray:
+    """codes [T, r] int8, scales [T, r/block] fp16 -> float64 values code*scale."""
+    T, r = codes.shape
+    s = np.repeat(scales.astype(np.float64), block, axis=1)
+    return codes.astype(np.float64) * s
+
+
+# --------------------------------------------------------------------------
+# closed-form accounting used in the paper's text and tables
+# --------------------------------------------------------------------------
+
+def compression_ratio(T: int, HD: int, R: int) -> float:
+    """Sec. 3.1: c = T*HD / (T*R + R*HD) for one matrix of one layer."""
+    return (T * HD) / (T * R + R * HD)
+
+
+def decompression_flops(T: int, HD: int, fractions: Sequence[float],
+                        ranks: Sequence[int]) -> float:
+    """Sec. 3.2: 2*T*HD*sum_f r_f R^(f) flops to rebuild one cache matrix."""
+    return 2.0 * T * HD * sum(f * R for f, R in zip(fractions, ranks))
+
+
+def cache_bytes(L: int, HD: int, T_v: int, T_t: int, R_k: Optional[int],
+                R_v: Optional[int], bytes_per_elt: int = 2) -> float:
+    """Whole-model KV cache of one sample: visual tokens compressed to rank
+    R_k / R_v (None = uncompressed), textual tokens kept uncompressed
+    (experiment setup).  Per layer and per matrix: T_v*R + R*HD (Sec. 3.1)."""
+    def one(R):
+        vis = T_v * HD if R is None else T_v * R + R * HD
+        return vis + T_t * HD
+    return float(L * bytes_per_elt * (one(R_k) + one(R_v)))
