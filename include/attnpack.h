@@ -1,0 +1,181 @@
+/*
+ * attnpack.h -- C ABI of the AttentionPack decode hot path for AMD MI355X (gfx950).
+ *
+ * A layer's KV cache K, V in R^{T x HD} (all H heads merged along the hidden
+ * axis, HD = H*d; paper Sec. 3.1) is held as coefficient rows
+ *     C_k, C_v  [T, r]      (the paper's compressed cache  Kbar, Vbar)
+ * plus decompression matrices ("bases")
+ *     B_k, B_v  [r, HD]     (the paper's D_k, D_v),
+ * with K ~= C_k B_k, V ~= C_v B_v.  Head h owns hidden columns [h*d, (h+1)*d).
+ *
+ * Conventions shared by every call
+ *   - Every pointer is DEVICE memory owned by the caller unless marked "host".
+ *     The library never allocates, frees or retains device memory.
+ *   - All work is enqueued on `stream` (a hipStream_t passed as void*; NULL =
+ *     the default stream).  Calls return without synchronising; outputs are
+ *     valid once the stream reaches that point.
+ *   - Matrices are dense row-major.  Rows of C_k, C_v, B_k, B_v, K, V must start
+ *     on 16-byte boundaries (true for r % 8 == 0 / HD % 8 == 0 in 2-byte types).
+ *   - Errors are return codes; nothing is thrown or aborted.  Everything that can
+ *     be checked on the host is rejected BEFORE any kernel is launched, and then
+ *     no output is written.  ap_last_error() (thread-local, host string) says why.
+ *     Device-side data errors (NaN mass, rank arrays that disagree with the bucket
+ *     lists, ranks that are not multiples of the granularity) are undefined
+ *     behaviour within the caller's buffers: documented, not checked.
+ */
+#ifndef ATTNPACK_H
+#define ATTNPACK_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  AP_OK = 0,
+  AP_ERR_INVALID_ARG = 1, /* NULL pointer, non-positive or inconsistent size, misalignment */
+  AP_ERR_UNSUPPORTED = 2, /* valid request outside what the kernels implement          */
+  AP_ERR_WORKSPACE = 3,   /* workspace missing or smaller than the *_workspace_bytes query */
+  AP_ERR_HIP = 4          /* the HIP runtime reported an error at launch                */
+} ap_status;
+
+typedef enum {
+  AP_F32 = 0, /* IEEE binary32                                   */
+  AP_F16 = 1, /* IEEE binary16                                   */
+  AP_BF16 = 2, /* bfloat16 (upper half of a binary32)            */
+  AP_I8 = 3   /* signed 8-bit codes (coefficients only)          */
+} ap_dtype;
+
+/* Columns per int8 scale (one fp16 scale per token per AP_QBLOCK columns). */
+#define AP_QBLOCK 64
+
+/* ------------------------------------------------------------------------
+ * ap_compact -- multi-head compaction with given bases (paper Sec. 3.1:
+ * Kbar = K D_k^T for D_k with orthonormal rows, i.e. U_r Sigma_r of the SVD).
+ *
+ *   Ck[b, row0 + i, :] = K[b, i, :] . Bk[b]^T      i = 0 .. n-1
+ *   Cv[b, row0 + i, :] = V[b, i, :] . Bv[b]^T
+ *
+ * n = T is the prefill compression; n = 1 appends one decoded token's
+ * coefficients to a cache whose basis is already fixed.
+ *
+ *   K, V     [B, n, HD]  dtype dt_in (AP_F16 | AP_BF16 | AP_F32), contiguous.
+ *   Bk, Bv   [r, HD]     dtype dt_in; batch b uses Bk + b*basis_batch_stride
+ *                        elements (0 = one basis shared by the whole batch).
+ *   Ck, Cv   [B, T_cap, r] dtype dt_out, rows row0 .. row0+n-1 written.
+ *            dt_out == dt_in, or AP_I8 (dt_in must then be AP_F16): the
+ *            projection is rounded to fp16 first and then quantised per token
+ *            and per AP_QBLOCK columns:  amax = max|c|; scale = fp16(fp32(amax) /
+ *            127.0f); code = clamp(rint_even(fp32(c) / fp32(scale)), -127, 127),
+ *            all zero when scale == 0.
+ *   scale_k, scale_v  [B, T_cap, r / AP_QBLOCK] fp16; required iff dt_out == AP_I8.
+ *   Accumulation is fp32; the result is rounded to nearest-even.
+ *   Requires HD % 8 == 0, r % 16 == 0 (r % AP_QBLOCK == 0 for AP_I8),
+ *   0 <= row0, row0 + n <= T_cap.  A K/V pair may be skipped by passing
+ *   K == NULL (then Ck is untouched), likewise V.
+ * ---------------------------------------------------------------------- */
+ap_status ap_compact(const void* K, const void* V, const void* Bk, const void* Bv,
+                     void* Ck, void* Cv, void* scale_k, void* scale_v,
+                     int B, int n, int row0, int T_cap, int HD, int r,
+                     int64_t basis_batch_stride, ap_dtype dt_in, ap_dtype dt_out,
+                     void* stream);
+
+/* ------------------------------------------------------------------------
+ * ap_quantize_i8 -- the int8 coefficient format of ap_compact applied to
+ * coefficients that already exist in fp16 (same recipe, bit for bit).
+ *   C      [B, T_cap, r] fp16, rows 0..T-1 read
+ *   codes  [B, T_cap, r] int8, scales [B, T_cap, r / AP_QBLOCK] fp16
+ * ---------------------------------------------------------------------- */
+ap_status ap_quantize_i8(const void* C, void* codes, void* scales,
+                         int B, int T, int T_cap, int r, void* stream);
+
+/* ------------------------------------------------------------------------
+ * ap_select_ranks -- attention-aware rank groups (paper Sec. 3.2; Alg. 1
+ * "determine the tokens m_f for each group f based on I").
+ *
+ * Per batch row: tokens are ordered by (mass descending, token index
+ * ascending); group g (0 = most important) takes sorted positions
+ * [floor(T*cum_num[g-1]/den), floor(T*cum_num[g]/den)), cum_num[-1] := 0,
+ * and its tokens are decoded at rank group_rank[g].
+ *
+ *   mass        [B, T] fp32, finite, >= 0 (the importance I of Eq. 1)
+ *   group_rank  [F] HOST int32, non-increasing, each > 0 (not validated
+ *               against any r here; ap_decode_attn validates what it is given)
+ *   cum_num     [F] HOST int32, non-decreasing, cum_num[F-1] == den > 0
+ *   rank_out    [B, T] int32: rank of every token
+ *   bucket_off  [B, F+1] int32: group g's tokens are bucket_idx[b, off[g] .. off[g+1])
+ *   bucket_idx  [B, T] int32: token indices, ascending inside each group
+ *   workspace   >= ap_select_workspace_bytes(B, T, F) bytes, 16-byte aligned
+ * 1 <= F <= 8.  Results are unique, so they are comparable bit for bit.
+ * ---------------------------------------------------------------------- */
+ap_status ap_select_ranks(const float* mass, int B, int T, int F,
+                          const int32_t* group_rank, const int32_t* cum_num, int32_t den,
+                          int32_t* rank_out, int32_t* bucket_off, int32_t* bucket_idx,
+                          void* workspace, size_t ws_bytes, void* stream);
+
+size_t ap_select_workspace_bytes(int B, int T, int F);
+
+/* ------------------------------------------------------------------------
+ * ap_decode_attn -- one decode query per sequence attends to every cached
+ * token of the compacted cache (paper Alg. 1: partial decompression, scores,
+ * softmax, output; without the output projection W_o).
+ *
+ * Result (what the kernels compute, by associativity, without rebuilding K, V):
+ *   Ktilde[t] = Ck[t, :rk_t] . Bk[:rk_t],  Vtilde[t] = Cv[t, :rv_t] . Bv[:rv_t]
+ *   out[b,h]  = softmax_t( sm_scale * q[b,h] . Ktilde[t, head h] ) . Vtilde[:, head h]
+ *   lse[b,h]  = log sum_t exp( sm_scale * q[b,h] . Ktilde[t, head h] )   (natural log)
+ *
+ *   q        [B, H, d] dtype dt
+ *   Ck, Cv   [B, T_cap, r] dtype dt_coef (== dt, or AP_I8 with dt == AP_F16);
+ *            rows 0..T-1 are attended (no mask: the newest token is appended
+ *            before attention, as in Alg. 1).
+ *   scale_k, scale_v  [B, T_cap, r / AP_QBLOCK] fp16, required iff dt_coef == AP_I8;
+ *            a coefficient's value is code * scale.
+ *   Bk, Bv   [r, HD] dtype dt, batch b at + b*basis_batch_stride elements (0 = shared)
+ *   rank_k, rank_v  [B, T] int32 per-token ranks, or NULL = every token at rank r.
+ *            One rank per token, shared by all heads.
+ *   bucket_off [B, F+1], bucket_idx [B, T], F: the group lists ap_select_ranks
+ *            produced for these rank arrays (every token of a group has the same
+ *            rank_k and the same rank_v).  Required for AP_F16 / AP_BF16 when a rank
+ *            array is given (the kernels walk rank-uniform token tiles); ranks must
+ *            then be multiples of 64 in [64, r].  AP_F32 reads the rank arrays directly
+ *            (any value in [0, r]) and ignores the bucket lists.
+ *   out      [B, H, d] dtype dt_out: dt (round-to-nearest-even from fp32) or AP_F32.
+ *            bfloat16 keeps 8 significant bits (unit roundoff 2^-8 = 3.9e-3), so a
+ *            bf16 output cannot meet a 2e-3 error bound by rounding alone: callers
+ *            that need the fp32 accumulator's accuracy ask for AP_F32.
+ *   lse      [B, H] fp32 or NULL
+ *   sm_scale softmax scale; pass 1/sqrt(d) for the paper's attention
+ *   workspace >= ap_decode_workspace_bytes(...) bytes, 256-byte aligned.
+ *
+ * Supported shapes: AP_F32: anything (simple kernels, meant for small cases).
+ * AP_F16 / AP_BF16: H <= 64, d in {32, 64, 128, 256}, r % 64 == 0, r <= 640.
+ * Anything else returns AP_ERR_UNSUPPORTED.  1 <= T <= T_cap.
+ * Scores, softmax and every accumulation are fp32 (the paper computes attention
+ * in full precision over a half-precision cache).
+ * ---------------------------------------------------------------------- */
+ap_status ap_decode_attn(const void* q, const void* Ck, const void* Cv,
+                         const void* scale_k, const void* scale_v,
+                         const void* Bk, const void* Bv, int64_t basis_batch_stride,
+                         const int32_t* rank_k, const int32_t* rank_v,
+                         const int32_t* bucket_off, const int32_t* bucket_idx, int F,
+                         void* out, float* lse,
+                         int B, int H, int d, int T, int T_cap, int r, float sm_scale,
+                         ap_dtype dt, ap_dtype dt_coef, ap_dtype dt_out,
+                         void* workspace, size_t ws_bytes, void* stream);
+
+size_t ap_decode_workspace_bytes(int B, int H, int d, int T, int r, ap_dtype dt);
+
+/* Host strings; ap_last_error() is thread-local and describes the most recent
+ * non-AP_OK return on the calling thread ("" if none). */
+const char* ap_status_string(ap_status s);
+const char* ap_last_error(void);
+/* Library version as major*10000 + minor*100 + patch. */
+int ap_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ATTNPACK_H */

@@ -1,0 +1,157 @@
+"""ctypes binding of libattnpack.so: argument marshalling only.
+
+Every function has the name and the argument order of the C entry point it
+calls (see include/attnpack.h); tensors are torch tensors on the GPU whose
+data_ptr() is passed through.  No step of the computation happens in Python,
+and there is no CPU fallback: if the shared library is missing, importing this
+module raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libattnpack.so")
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(
+        f"{LIB_PATH} not found: build it with `python -m paper_2603_23914_amd.build` "
+        "(there is no fallback implementation)")
+
+_lib = ctypes.CDLL(LIB_PATH)
+
+AP_OK, AP_ERR_INVALID_ARG, AP_ERR_UNSUPPORTED, AP_ERR_WORKSPACE, AP_ERR_HIP = range(5)
+AP_F32, AP_F16, AP_BF16, AP_I8 = range(4)
+AP_QBLOCK = 64
+
+_c = ctypes
+_vp, _i, _i64, _sz, _f = _c.c_void_p, _c.c_int, _c.c_int64, _c.c_size_t, _c.c_float
+
+_lib.ap_compact.restype = _i
+_lib.ap_compact.argtypes = [_vp] * 8 + [_i] * 6 + [_i64, _i, _i, _vp]
+_lib.ap_quantize_i8.restype = _i
+_lib.ap_quantize_i8.argtypes = [_vp, _vp, _vp, _i, _i, _i, _i, _vp]
+_lib.ap_select_ranks.restype = _i
+_lib.ap_select_ranks.argtypes = [_vp, _i, _i, _i, _vp, _vp, _c.c_int32, _vp, _vp, _vp, _vp, _sz, _vp]
+_lib.ap_select_workspace_bytes.restype = _sz
+_lib.ap_select_workspace_bytes.argtypes = [_i, _i, _i]
+_lib.ap_decode_attn.restype = _i
+_lib.ap_decode_attn.argtypes = ([_vp] * 7 + [_i64] + [_vp] * 4 + [_i] + [_vp, _vp] + [_i] * 6 +
+                                [_f, _i, _i, _i, _vp, _sz, _vp])
+_lib.ap_decode_workspace_bytes.restype = _sz
+_lib.ap_decode_workspace_bytes.argtypes = [_i] * 6
+_lib.ap_status_string.restype = _c.c_char_p
+_lib.ap_status_string.argtypes = [_i]
+_lib.ap_last_error.restype = _c.c_char_p
+_lib.ap_last_error.argtypes = []
+_lib.ap_version.restype = _i
+_lib.ap_version.argtypes = []
+
+EXPORTS = ("ap_compact", "ap_quantize_i8", "ap_select_ranks", "ap_select_workspace_bytes",
+           "ap_decode_attn", "ap_decode_workspace_bytes", "ap_status_string", "ap_last_error",
+           "ap_version")
+
+_DT = {torch.float32: AP_F32, torch.float16: AP_F16, torch.bfloat16: AP_BF16, torch.int8: AP_I8}
+
+
+class AttnPackError(RuntimeError):
+    def __init__(self, status: int):
+        self.status = status
+        super().__init__(f"{_lib.ap_status_string(status).decode()}: {_lib.ap_last_error().decode()}")
+
+
+def _check(status: int) -> None:
+    if status != AP_OK:
+        raise AttnPackError(status)
+
+
+def _p(t: Optional[torch.Tensor]):
+    if t is None:
+        return None
+    assert t.is_cuda and t.is_contiguous(), "tensors must be contiguous GPU tensors"
+    return t.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return stream.cuda_stream or None
+
+
+def _bstride(Bm: torch.Tensor) -> int:
+    return 0 if Bm.dim() == 2 else Bm.stride(0)
+
+
+def ap_version() -> int:
+    return _lib.ap_version()
+
+
+def ap_status_string(status: int) -> str:
+    return _lib.ap_status_string(status).decode()
+
+
+def ap_last_error() -> str:
+    return _lib.ap_last_error().decode()
+
+
+def ap_decode_workspace_bytes(B: int, H: int, d: int, T: int, r: int, dt: int) -> int:
+    return _lib.ap_decode_workspace_bytes(B, H, d, T, r, dt)
+
+
+def ap_select_workspace_bytes(B: int, T: int, F: int) -> int:
+    return _lib.ap_select_workspace_bytes(B, T, F)
+
+
+def ap_compact(K, V, Bk, Bv, Ck, Cv, scale_k=None, scale_v=None, *, n: int, row0: int,
+               stream=None) -> None:
+    """K, V [B, n, HD] (either may be None); Bk, Bv [r, HD] or [B, r, HD];
+    Ck, Cv [B, T_cap, r] (int8 => scale_k/scale_v [B, T_cap, r/64] fp16)."""
+    X = K if K is not None else V
+    Cx = Ck if K is not None else Cv
+    Bx = Bk if K is not None else Bv
+    B, HD = X.shape[0], X.shape[-1]
+    T_cap, r = Cx.shape[1], Cx.shape[2]
+    _check(_lib.ap_compact(_p(K), _p(V), _p(Bk), _p(Bv), _p(Ck), _p(Cv), _p(scale_k), _p(scale_v),
+                           B, n, row0, T_cap, HD, r, _bstride(Bx), _DT[X.dtype], _DT[Cx.dtype],
+                           _stream(stream)))
+
+
+def ap_quantize_i8(C, codes, scales, *, T: int, stream=None) -> None:
+    B, T_cap, r = C.shape
+    _check(_lib.ap_quantize_i8(_p(C), _p(codes), _p(scales), B, T, T_cap, r, _stream(stream)))
+
+
+def ap_select_ranks(mass, group_rank, cum_num, den: int, rank_out, bucket_off, bucket_idx,
+                    workspace, *, stream=None) -> None:
+    """mass [B, T] fp32 (GPU); group_rank, cum_num: host sequences of ints."""
+    B, T = mass.shape
+    F = len(group_rank)
+    gr = (_c.c_int32 * F)(*[int(x) for x in group_rank])
+    cn = (_c.c_int32 * F)(*[int(x) for x in cum_num])
+    _check(_lib.ap_select_ranks(_p(mass), B, T, F, _c.cast(gr, _vp), _c.cast(cn, _vp), int(den),
+                                _p(rank_out), _p(bucket_off), _p(bucket_idx), _p(workspace),
+                                workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
+def ap_decode_attn(q, Ck, Cv, Bk, Bv, out, workspace, *, T: int, sm_scale: float,
+                   scale_k=None, scale_v=None, rank_k=None, rank_v=None, bucket_off=None,
+                   bucket_idx=None, F: int = 0, lse=None, stream=None) -> None:
+    """q, out [B, H, d] (out in q's dtype or fp32); Ck, Cv [B, T_cap, r];
+    Bk, Bv [r, HD] or [B, r, HD]."""
+    B, H, d = q.shape
+    T_cap, r = Ck.shape[1], Ck.shape[2]
+    _check(_lib.ap_decode_attn(_p(q), _p(Ck), _p(Cv), _p(scale_k), _p(scale_v), _p(Bk), _p(Bv),
+                               _bstride(Bk), _p(rank_k), _p(rank_v), _p(bucket_off),
+                               _p(bucket_idx), F, _p(out), _p(lse), B, H, d, T, T_cap, r,
+                               float(sm_scale), _DT[q.dtype], _DT[Ck.dtype], _DT[out.dtype],
+                               _p(workspace),
+                               workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
+def raw():
+    """The ctypes library handle (tests use it to exercise error paths)."""
+    return _lib

@@ -1,0 +1,127 @@
+// Shared host/device helpers of libattnpack (internal; not part of the ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
+#include <stdint.h>
+#include <stddef.h>
+#include "attnpack.h"
+
+namespace ap {
+
+// ---- error reporting (host) -------------------------------------------------
+void set_error(const char* fmt, ...);
+void clear_error();
+
+#define AP_REQUIRE(cond, code, ...)        \
+  do {                                     \
+    if (!(cond)) {                         \
+      ::ap::set_error(__VA_ARGS__);        \
+      return (code);                       \
+    }                                      \
+  } while (0)
+
+inline size_t dtype_size(ap_dtype dt) {
+  switch (dt) {
+    case AP_F32: return 4;
+    case AP_F16: return 2;
+    case AP_BF16: return 2;
+    case AP_I8: return 1;
+  }
+  return 0;
+}
+inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+inline size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// ---- vector types used with the matrix-core builtins -------------------------
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
+typedef __attribute__((__vector_size__(8 * sizeof(_Float16)))) _Float16 f16x8_t;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4_t;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16_t;
+typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4_t;
+typedef __attribute__((__vector_size__(2 * sizeof(uint32_t)))) uint32_t u32x2_t;
+
+// ---- storage-type traits (device) --------------------------------------------
+struct F16Tag {};
+struct BF16Tag {};
+
+// fp32 -> 16-bit storage, round to nearest even.
+__device__ __forceinline__ uint16_t f32_to_bits(float x, F16Tag) {
+  _Float16 h = (_Float16)x;  // v_cvt_f16_f32: RNE
+  return __builtin_bit_cast(uint16_t, h);
+}
+__device__ __forceinline__ uint16_t f32_to_bits(float x, BF16Tag) {
+  uint32_t u = __builtin_bit_cast(uint32_t, x);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);  // quiet NaN
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+__device__ __forceinline__ float bits_to_f32(uint16_t b, F16Tag) {
+  return (float)__builtin_bit_cast(_Float16, b);
+}
+__device__ __forceinline__ float bits_to_f32(uint16_t b, BF16Tag) {
+  return __builtin_bit_cast(float, (uint32_t)b << 16);
+}
+// two packed 16-bit values in a dword (low half first in memory)
+template <class Tag>
+__device__ __forceinline__ float lo_to_f32(uint32_t w, Tag t) { return bits_to_f32((uint16_t)(w & 0xffffu), t); }
+template <class Tag>
+__device__ __forceinline__ float hi_to_f32(uint32_t w, Tag t) { return bits_to_f32((uint16_t)(w >> 16), t); }
+template <class Tag>
+__device__ __forceinline__ uint32_t pack2(float lo, float hi, Tag t) {
+  return (uint32_t)f32_to_bits(lo, t) | ((uint32_t)f32_to_bits(hi, t) << 16);
+}
+
+// ---- launchers (defined in the .hip files) -------------------------------------
+struct DecodeArgs {
+  const void* q;
+  const void* Ck;
+  const void* Cv;
+  const void* scale_k;
+  const void* scale_v;
+  const void* Bk;
+  const void* Bv;
+  int64_t basis_batch_stride;
+  const int32_t* rank_k;
+  const int32_t* rank_v;
+  const int32_t* bucket_off;
+  const int32_t* bucket_idx;
+  int F;
+  void* out;
+  float* lse;
+  int B, H, d, T, T_cap, r;
+  float sm_scale;
+  ap_dtype dt, dt_coef, dt_out;
+  void* workspace;
+  size_t ws_bytes;
+  hipStream_t stream;
+};
+
+size_t decode_f32_workspace(int B, int H, int d, int T, int r);
+ap_status launch_decode_f32(const DecodeArgs& a);
+
+size_t decode_mfma_workspace(int B, int H, int d, int T, int r, ap_dtype dt);
+ap_status launch_decode_mfma(const DecodeArgs& a);
+
+struct CompactArgs {
+  const void* X;   // [B, n, HD]
+  const void* Bm;  // [r, HD] (+ batch stride)
+  void* C;         // [B, T_cap, r]
+  void* scale;     // [B, T_cap, r/64] or null
+  int B, n, row0, T_cap, HD, r;
+  int64_t basis_batch_stride;
+  ap_dtype dt_in, dt_out;
+  hipStream_t stream;
+};
+ap_status launch_compact(const CompactArgs& a);
+ap_status launch_quantize_i8(const void* C, void* codes, void* scales, int B, int T, int T_cap,
+                             int r, hipStream_t stream);
+
+size_t select_workspace(int B, int T, int F);
+ap_status launch_select_ranks(const float* mass, int B, int T, int F, const int32_t* group_rank,
+                              const int32_t* bounds_num, int32_t den, int32_t* rank_out,
+                              int32_t* bucket_off, int32_t* bucket_idx, void* ws,
+                              hipStream_t stream);
+
+ap_status check_launch(const char* what);
+
+}  // namespace ap

@@ -1,0 +1,219 @@
+// C ABI of libattnpack: host-side validation and dispatch.  No kernel lives here.
+#include "ap_common.hpp"
+
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+
+namespace ap {
+
+static thread_local char g_err[512] = "";
+
+void set_error(const char* fmt, ...) {
+  va_list ap_;
+  va_start(ap_, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap_);
+  va_end(ap_);
+}
+void clear_error() { g_err[0] = 0; }
+
+ap_status check_launch(const char* what) {
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) {
+    set_error("%s: HIP error %d (%s)", what, (int)e, hipGetErrorString(e));
+    return AP_ERR_HIP;
+  }
+  return AP_OK;
+}
+
+static bool half_type(ap_dtype dt) { return dt == AP_F16 || dt == AP_BF16; }
+
+}  // namespace ap
+
+using namespace ap;
+
+extern "C" {
+
+const char* ap_status_string(ap_status s) {
+  switch (s) {
+    case AP_OK: return "AP_OK";
+    case AP_ERR_INVALID_ARG: return "AP_ERR_INVALID_ARG";
+    case AP_ERR_UNSUPPORTED: return "AP_ERR_UNSUPPORTED";
+    case AP_ERR_WORKSPACE: return "AP_ERR_WORKSPACE";
+    case AP_ERR_HIP: return "AP_ERR_HIP";
+  }
+  return "AP_ERR_?";
+}
+
+const char* ap_last_error(void) { return g_err; }
+
+int ap_version(void) { return 100; }
+
+// ---------------------------------------------------------------------------------------------
+ap_status ap_compact(const void* K, const void* V, const void* Bk, const void* Bv, void* Ck,
+                     void* Cv, void* scale_k, void* scale_v, int B, int n, int row0, int T_cap,
+                     int HD, int r, int64_t basis_batch_stride, ap_dtype dt_in, ap_dtype dt_out,
+                     void* stream) {
+  clear_error();
+  AP_REQUIRE(B > 0 && n > 0 && HD > 0 && r > 0 && T_cap > 0, AP_ERR_INVALID_ARG,
+             "ap_compact: B, n, T_cap, HD, r must be positive");
+  AP_REQUIRE(row0 >= 0 && (int64_t)row0 + n <= T_cap, AP_ERR_INVALID_ARG,
+             "ap_compact: rows [%d, %d) outside T_cap=%d", row0, row0 + n, T_cap);
+  AP_REQUIRE(K != nullptr || V != nullptr, AP_ERR_INVALID_ARG, "ap_compact: K and V both NULL");
+  AP_REQUIRE(dt_in == AP_F32 || half_type(dt_in), AP_ERR_INVALID_ARG, "ap_compact: bad dt_in");
+  AP_REQUIRE(dt_out == dt_in || (dt_out == AP_I8 && dt_in == AP_F16), AP_ERR_INVALID_ARG,
+             "ap_compact: dt_out must equal dt_in, or be AP_I8 with dt_in AP_F16");
+  AP_REQUIRE(HD % 8 == 0 && r % 16 == 0, AP_ERR_INVALID_ARG,
+             "ap_compact: need HD %% 8 == 0 and r %% 16 == 0 (HD=%d r=%d)", HD, r);
+  AP_REQUIRE(basis_batch_stride == 0 || basis_batch_stride >= (int64_t)r * HD, AP_ERR_INVALID_ARG,
+             "ap_compact: basis_batch_stride must be 0 or >= r*HD");
+  AP_REQUIRE(basis_batch_stride % 8 == 0, AP_ERR_INVALID_ARG,
+             "ap_compact: basis_batch_stride must keep rows 16-byte aligned");
+  if (dt_out == AP_I8) {
+    AP_REQUIRE(r % AP_QBLOCK == 0, AP_ERR_INVALID_ARG, "ap_compact: AP_I8 needs r %% 64 == 0");
+  }
+  const void* Xs[2] = {K, V};
+  const void* Bs[2] = {Bk, Bv};
+  void* Cs[2] = {Ck, Cv};
+  void* Ss[2] = {scale_k, scale_v};
+  for (int i = 0; i < 2; ++i) {
+    if (!Xs[i]) continue;
+    AP_REQUIRE(Bs[i] && Cs[i], AP_ERR_INVALID_ARG, "ap_compact: basis or output NULL for %s",
+               i ? "V" : "K");
+    AP_REQUIRE(aligned(Xs[i], 16) && aligned(Bs[i], 16) && aligned(Cs[i], 16), AP_ERR_INVALID_ARG,
+               "ap_compact: %s pointers must be 16-byte aligned", i ? "V" : "K");
+    if (dt_out == AP_I8)
+      AP_REQUIRE(Ss[i] && aligned(Ss[i], 2), AP_ERR_INVALID_ARG,
+                 "ap_compact: AP_I8 output needs a scale buffer");
+  }
+  for (int i = 0; i < 2; ++i) {
+    if (!Xs[i]) continue;
+    CompactArgs a{Xs[i], Bs[i], Cs[i], Ss[i], B, n, row0, T_cap, HD, r, basis_batch_stride,
+                  dt_in, dt_out, (hipStream_t)stream};
+    ap_status s = launch_compact(a);
+    if (s != AP_OK) return s;
+  }
+  return AP_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+ap_status ap_quantize_i8(const void* C, void* codes, void* scales, int B, int T, int T_cap, int r,
+                         void* stream) {
+  clear_error();
+  AP_REQUIRE(C && codes && scales, AP_ERR_INVALID_ARG, "ap_quantize_i8: NULL pointer");
+  AP_REQUIRE(B > 0 && T > 0 && T <= T_cap && r > 0, AP_ERR_INVALID_ARG,
+             "ap_quantize_i8: need B > 0, 0 < T <= T_cap, r > 0");
+  AP_REQUIRE(r % AP_QBLOCK == 0, AP_ERR_INVALID_ARG, "ap_quantize_i8: r %% 64 != 0");
+  AP_REQUIRE(aligned(C, 16) && aligned(codes, 16) && aligned(scales, 2), AP_ERR_INVALID_ARG,
+             "ap_quantize_i8: misaligned pointer");
+  return launch_quantize_i8(C, codes, scales, B, T, T_cap, r, (hipStream_t)stream);
+}
+
+// ---------------------------------------------------------------------------------------------
+size_t ap_select_workspace_bytes(int B, int T, int F) {
+  if (B <= 0 || T <= 0 || F <= 0) return 0;
+  return select_workspace(B, T, F);
+}
+
+ap_status ap_select_ranks(const float* mass, int B, int T, int F, const int32_t* group_rank,
+                          const int32_t* cum_num, int32_t den, int32_t* rank_out,
+                          int32_t* bucket_off, int32_t* bucket_idx, void* workspace,
+                          size_t ws_bytes, void* stream) {
+  clear_error();
+  AP_REQUIRE(mass && group_rank && cum_num && rank_out && bucket_off && bucket_idx,
+             AP_ERR_INVALID_ARG, "ap_select_ranks: NULL pointer");
+  AP_REQUIRE(B > 0 && T > 0, AP_ERR_INVALID_ARG, "ap_select_ranks: B and T must be positive");
+  AP_REQUIRE(F >= 1 && F <= 8, AP_ERR_INVALID_ARG, "ap_select_ranks: F must be in [1, 8]");
+  AP_REQUIRE(den > 0, AP_ERR_INVALID_ARG, "ap_select_ranks: den must be positive");
+  for (int g = 0; g < F; ++g) {
+    AP_REQUIRE(group_rank[g] > 0, AP_ERR_INVALID_ARG, "ap_select_ranks: group_rank[%d] <= 0", g);
+    AP_REQUIRE(g == 0 || group_rank[g] <= group_rank[g - 1], AP_ERR_INVALID_ARG,
+               "ap_select_ranks: group_rank must be non-increasing");
+    AP_REQUIRE(cum_num[g] >= (g ? cum_num[g - 1] : 0) && cum_num[g] <= den, AP_ERR_INVALID_ARG,
+               "ap_select_ranks: cum_num must be non-decreasing within [0, den]");
+  }
+  AP_REQUIRE(cum_num[F - 1] == den, AP_ERR_INVALID_ARG, "ap_select_ranks: cum_num[F-1] != den");
+  size_t need = select_workspace(B, T, F);
+  AP_REQUIRE(workspace && ws_bytes >= need, AP_ERR_WORKSPACE,
+             "ap_select_ranks: workspace %zu bytes, need %zu", ws_bytes, need);
+  AP_REQUIRE(aligned(workspace, 16), AP_ERR_INVALID_ARG, "ap_select_ranks: workspace misaligned");
+  return launch_select_ranks(mass, B, T, F, group_rank, cum_num, den, rank_out, bucket_off,
+                             bucket_idx, workspace, (hipStream_t)stream);
+}
+
+// ---------------------------------------------------------------------------------------------
+static ap_status decode_shape_check(int B, int H, int d, int T, int r, ap_dtype dt, bool report) {
+  if (B <= 0 || H <= 0 || d <= 0 || T <= 0 || r <= 0) {
+    if (report) set_error("ap_decode_attn: B, H, d, T, r must be positive");
+    return AP_ERR_INVALID_ARG;
+  }
+  if (dt == AP_F32) return AP_OK;
+  if (!half_type(dt)) {
+    if (report) set_error("ap_decode_attn: dt must be AP_F32, AP_F16 or AP_BF16");
+    return AP_ERR_INVALID_ARG;
+  }
+  bool ok = H <= 64 && (d == 32 || d == 64 || d == 128 || d == 256) && r % 64 == 0 && r <= 640;
+  if (!ok) {
+    if (report)
+      set_error("ap_decode_attn: half-precision path needs H<=64, d in {32,64,128,256}, "
+                "r%%64==0, r<=640 (H=%d d=%d r=%d)", H, d, r);
+    return AP_ERR_UNSUPPORTED;
+  }
+  return AP_OK;
+}
+
+size_t ap_decode_workspace_bytes(int B, int H, int d, int T, int r, ap_dtype dt) {
+  if (decode_shape_check(B, H, d, T, r, dt, false) != AP_OK) return 0;
+  return dt == AP_F32 ? decode_f32_workspace(B, H, d, T, r)
+                      : decode_mfma_workspace(B, H, d, T, r, dt);
+}
+
+ap_status ap_decode_attn(const void* q, const void* Ck, const void* Cv, const void* scale_k,
+                         const void* scale_v, const void* Bk, const void* Bv,
+                         int64_t basis_batch_stride, const int32_t* rank_k, const int32_t* rank_v,
+                         const int32_t* bucket_off, const int32_t* bucket_idx, int F, void* out,
+                         float* lse, int B, int H, int d, int T, int T_cap, int r, float sm_scale,
+                         ap_dtype dt, ap_dtype dt_coef, ap_dtype dt_out, void* workspace,
+                         size_t ws_bytes, void* stream) {
+  clear_error();
+  AP_REQUIRE(q && Ck && Cv && Bk && Bv && out, AP_ERR_INVALID_ARG, "ap_decode_attn: NULL pointer");
+  ap_status s = decode_shape_check(B, H, d, T, r, dt, true);
+  if (s != AP_OK) return s;
+  AP_REQUIRE(T <= T_cap, AP_ERR_INVALID_ARG, "ap_decode_attn: T=%d exceeds T_cap=%d", T, T_cap);
+  AP_REQUIRE(dt_coef == dt || (dt_coef == AP_I8 && dt == AP_F16), AP_ERR_INVALID_ARG,
+             "ap_decode_attn: dt_coef must equal dt, or be AP_I8 with dt AP_F16");
+  AP_REQUIRE(dt_out == dt || dt_out == AP_F32, AP_ERR_INVALID_ARG,
+             "ap_decode_attn: dt_out must equal dt or be AP_F32");
+  AP_REQUIRE(sm_scale == sm_scale && sm_scale > 0.f && sm_scale < 1e30f, AP_ERR_INVALID_ARG,
+             "ap_decode_attn: sm_scale must be finite and positive");
+  const int64_t HD = (int64_t)H * d;
+  AP_REQUIRE(basis_batch_stride == 0 || basis_batch_stride >= (int64_t)r * HD, AP_ERR_INVALID_ARG,
+             "ap_decode_attn: basis_batch_stride must be 0 or >= r*H*d");
+  AP_REQUIRE(aligned(q, 16) && aligned(Ck, 16) && aligned(Cv, 16) && aligned(Bk, 16) &&
+                 aligned(Bv, 16) && aligned(out, 16),
+             AP_ERR_INVALID_ARG, "ap_decode_attn: pointers must be 16-byte aligned");
+  if (dt != AP_F32) {
+    AP_REQUIRE(basis_batch_stride % 8 == 0, AP_ERR_INVALID_ARG,
+               "ap_decode_attn: basis_batch_stride must keep rows 16-byte aligned");
+  }
+  if (dt_coef == AP_I8) {
+    AP_REQUIRE(scale_k && scale_v, AP_ERR_INVALID_ARG, "ap_decode_attn: AP_I8 needs scale buffers");
+  }
+  const bool ragged = rank_k || rank_v;
+  if (ragged && dt != AP_F32) {
+    AP_REQUIRE(bucket_off && bucket_idx && F >= 1 && F <= 8, AP_ERR_INVALID_ARG,
+               "ap_decode_attn: per-token ranks need the bucket lists of ap_select_ranks "
+               "(1 <= F <= 8) in half precision");
+  }
+  size_t need = ap_decode_workspace_bytes(B, H, d, T, r, dt);
+  AP_REQUIRE(workspace && ws_bytes >= need, AP_ERR_WORKSPACE,
+             "ap_decode_attn: workspace %zu bytes, need %zu", ws_bytes, need);
+  AP_REQUIRE(aligned(workspace, 256), AP_ERR_INVALID_ARG,
+             "ap_decode_attn: workspace must be 256-byte aligned");
+  DecodeArgs a{q, Ck, Cv, scale_k, scale_v, Bk, Bv, basis_batch_stride, rank_k, rank_v,
+               bucket_off, bucket_idx, ragged ? F : 0, out, lse, B, H, d, T, T_cap, r, sm_scale,
+               dt, dt_coef, dt_out, workspace, ws_bytes, (hipStream_t)stream};
+  return dt == AP_F32 ? launch_decode_f32(a) : launch_decode_mfma(a);
+}
+
+}  // extern "C"

@@ -1,0 +1,85 @@
+"""GPU parity: fp16 / bf16 decode attention (uniform rank) against the fp64 oracle."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2603_23914_amd import workloads as wl
+from gpu_util import TORCH_DT, assert_close, to_dev, to_host64, workspace
+
+pytestmark = pytest.mark.gpu
+
+
+def run_half(case_dtype, q, Ck, Cv, Bk, Bv, T, want_lse=False, **kw):
+    """All array arguments are stored host arrays (bf16 as uint16 bit patterns)."""
+    from paper_2603_23914_amd import binding as ap
+    B, H, d = q.shape
+    r = Ck.shape[2]
+    dq, dCk, dCv, dBk, dBv = (to_dev(x, case_dtype) for x in (q, Ck, Cv, Bk, Bv))
+    # bf16 keeps 8 significant bits (unit roundoff 3.9e-3 > the 2e-3 bound): take fp32 output there
+    out_dt = torch.float32 if case_dtype == "bf16" and not kw.pop("bf16_out", False) else TORCH_DT[case_dtype]
+    out = torch.empty((B, H, d), dtype=out_dt, device="cuda")
+    lse = torch.empty((B, H), dtype=torch.float32, device="cuda") if want_lse else None
+    ws = workspace(ap.ap_decode_workspace_bytes(B, H, d, T, r, ap._DT[TORCH_DT[case_dtype]]))
+    ap.ap_decode_attn(dq, dCk, dCv, dBk, dBv, out, ws, T=T, sm_scale=1.0 / math.sqrt(d), lse=lse, **kw)
+    torch.cuda.synchronize()
+    return (to_host64(out), to_host64(lse)) if want_lse else to_host64(out)
+
+
+def oracle_out(case_dtype, q, Ck, Cv, Bk, Bv, T, absorbed=True):
+    P = lambda x: oracle.promote(x, case_dtype)
+    return oracle.decode_attn_batched(P(q), P(Ck), P(Cv), P(Bk), P(Bv), T, absorbed=absorbed)
+
+
+SHAPES = [
+    # dtype, B, H,  d,   r,   T   (T spans several 32-token tiles and a ragged tail)
+    ("f16", 2, 32, 128, 512, 333),
+    ("bf16", 2, 40, 128, 640, 301),
+    ("f16", 3, 8, 64, 128, 97),
+    ("bf16", 1, 64, 32, 320, 257),
+    ("f16", 2, 16, 128, 64, 70),
+    ("bf16", 2, 24, 64, 192, 129),
+    ("f16", 1, 40, 128, 640, 31),      # fewer tokens than one tile
+    ("bf16", 1, 40, 128, 576, 1),      # a single cached token
+    ("f16", 1, 5, 256, 256, 64),       # H < 16, d = 256
+]
+
+
+@pytest.mark.parametrize("dtype,B,H,d,r,T", SHAPES)
+def test_decode_uniform_small(dtype, B, H, d, r, T):
+    case = wl.decode_case(dtype, B, H, d, r, T, steps=3, seed=7, append=True)
+    q = wl.step_query(case, 0)
+    print(f"case {dtype} B={B} H={H} d={d} r={r} T={T}", flush=True)
+    ref = oracle_out(dtype, q, case.Ck, case.Cv, case.Bk, case.Bv, T)
+    # the reconstruct-then-attend definition agrees with the absorbed form on this input
+    ref_def = oracle_out(dtype, q[:1], case.Ck[:1], case.Cv[:1], case.Bk[:1], case.Bv[:1], T, absorbed=False)
+    assert np.abs(ref_def - ref[:1]).max() < 1e-9
+    got, lse = run_half(dtype, q, case.Ck, case.Cv, case.Bk, case.Bv, T, want_lse=True)
+    rel = assert_close(got, ref, dtype, f"{dtype} H={H} r={r} T={T}")
+    print(f"  max|err|/||out||inf = {rel:.2e}", flush=True)
+    P = lambda x: oracle.promote(x, dtype)
+    _, ref_lse = oracle.decode_attn_absorbed(P(q)[0], P(case.Ck)[0, :T], P(case.Cv)[0, :T], P(case.Bk)[0],
+                                             P(case.Bv)[0], return_lse=True)
+    assert np.abs(lse[0] - ref_lse).max() < 2e-3 * max(1.0, np.abs(ref_lse).max())
+
+
+def test_decode_shared_basis_and_determinism():
+    case = wl.decode_case("f16", 4, 32, 128, 512, 200, steps=0, seed=3, shared_basis=True, append=False)
+    q = wl.step_query(case, 1)
+    ref = oracle_out("f16", q, case.Ck, case.Cv, case.Bk, case.Bv, 200)
+    a = run_half("f16", q, case.Ck, case.Cv, case.Bk, case.Bv, 200)
+    b = run_half("f16", q, case.Ck, case.Cv, case.Bk, case.Bv, 200)
+    assert_close(a, ref, "f16", "shared basis")
+    assert (a == b).all(), "same inputs twice must give identical bits"
+
+
+def test_decode_peaked_softmax_large_logits():
+    """Scores far from zero and one dominant token: the online softmax must not overflow."""
+    dtype = "bf16"
+    case = wl.decode_case(dtype, 1, 40, 128, 640, 200, steps=0, seed=5, append=False)
+    q = wl.store(8.0 * wl.rng_for(5, 99).standard_normal((1, 40, 128)), dtype)   # logits ~ N(0, 64)
+    ref = oracle_out(dtype, q, case.Ck, case.Cv, case.Bk, case.Bv, 200)
+    got = run_half(dtype, q, case.Ck, case.Cv, case.Bk, case.Bv, 200)
+    assert_close(got, ref, dtype, "peaked softmax")
