@@ -9,16 +9,17 @@
 //   merge:   splits combined with their (max, sum) pairs                   (kernel merge_expand)
 //   expand:  out[h,i] = sum_j u[h,j] Bv[j, h*d+i]
 //
-// attn_partial is the HBM-bound kernel.  One workgroup owns one (sequence, token
-// split); wave w owns heads 16w..16w+15 for ALL r columns.  Coefficient tiles of 32
-// tokens travel HBM -> LDS with direct-to-LDS loads through a 3-deep ring (K tile,
-// V tile, K tile, ...), two stages in flight while one is consumed, so no VGPR is
-// spent on staging.  Every wave reads the whole tile from LDS:
-//   S^T[t,h]  = Ck_tile[t,:] . q'^T      MFMA 16x16x32, A = tile rows (LDS), B = q' (VGPR)
-//   U^T[j,h] += Cv_tile^T[j,t] . P^T     MFMA 16x16x32, A = 8x8 register transpose of the
-//                                         tile (v_perm), B = P (the S^T accumulator layout
-//                                         is exactly the B-operand layout, so P never
-//                                         leaves registers)
+// attn_partial is the HBM-bound kernel.  One workgroup (4 waves, one per SIMD) owns one
+// (sequence, token split).  Coefficient tiles of 32 tokens travel HBM -> LDS with
+// direct-to-LDS loads through a 3-deep ring (K tile, V tile, K tile, ...), two stages in
+// flight while one is consumed, so no VGPR is spent on staging.  Every wave serves all
+// heads on a quarter of the rank axis, so each tile byte is read from LDS exactly once:
+//   S^T[t,h]  = Ck_tile[t,:] . q'^T      MFMA 16x16x32, A = tile rows (LDS), B = q' (VGPR);
+//                                         the four waves' partial sums meet in LDS
+//   U^T[j,h] += Cv_tile^T[j,t] . P^T     MFMA 16x16x32, A = register transpose of the tile
+//                                         (v_perm), B = P (the S^T accumulator layout is
+//                                         exactly the B-operand layout, so P never leaves
+//                                         registers)
 // For bf16 storage q' and P are split into hi+lo bf16 pairs (two MFMAs) so that the
 // operand rounding stays far inside the 2e-3 tolerance; fp16 needs no split.
 #include "ap_common.hpp"
@@ -82,6 +83,20 @@ __device__ __forceinline__ void split_hi_lo(float x, uint16_t& hi, uint16_t& lo)
   lo = f32_to_bits(x - bits_to_f32(hi, Tag{}), Tag{});
 }
 
+
+// Two fp32 -> packed pair of 16-bit storage values, round to nearest even (hardware converts).
+typedef __attribute__((__vector_size__(2 * sizeof(float)))) float f32x2_t;
+typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2_t;
+typedef __attribute__((__vector_size__(2 * sizeof(_Float16)))) _Float16 f16x2_t;
+__device__ __forceinline__ uint32_t cvt_pack(float lo, float hi, BF16Tag) {
+  f32x2_t v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
+}
+__device__ __forceinline__ uint32_t cvt_pack(float lo, float hi, F16Tag) {
+  f32x2_t v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, f16x2_t));
+}
+
 // ------------------------------------------------------------------------------------------
 // fold_query: grid (Hp, B), 256 threads.  Qp[b][0][h][j] = hi, Qp[b][1][h][j] = lo of
 // sm_scale*log2e * (Bk[b][j, head h] . q[b,h]);  heads >= H are zero rows.
@@ -134,61 +149,79 @@ fold_query(const uint16_t* __restrict__ q, const uint16_t* __restrict__ Bk, int6
 // tile kernels, fully unrolled for a compile-time number of steps (selected by a
 // wave-uniform switch on the run-time rank, so the unrolled bodies carry no guards)
 // ------------------------------------------------------------------------------------------
-// Partial scores of one 32-token tile over NKS_*32 coefficient columns.
-template <class Tag, bool SPLIT, int NKS_>
-__device__ __forceinline__ void score_tile(const char* a0, const char* a1, const u32x4_t* qhi,
-                                           const u32x4_t* qlo, f32x4_t& s0, f32x4_t& s1) {
-  f32x4_t sh0 = {0.f, 0.f, 0.f, 0.f}, sh1 = sh0, sl0 = sh0, sl1 = sh0;
+// Partial scores of one 32-token tile over this wave's NK_ score k-steps (32 columns
+// each), for all MT head tiles.  The tile rows are read from LDS once and reused by
+// every head tile.
+template <class Tag, int MT, bool SPLIT, int NKW>
+__device__ __forceinline__ void score_tile(int nk, const char* a0, const char* a1,
+                                           const u32x4_t (&qhi)[NKW][MT],
+                                           const u32x4_t (&qlo)[SPLIT ? NKW : 1][MT],
+                                           f32x4_t (&s)[MT][2]) {
+  u32x4_t A0 = *(const u32x4_t*)a0;
+  u32x4_t A1 = *(const u32x4_t*)a1;
 #pragma unroll
-  for (int ks = 0; ks < NKS_; ++ks) {
-    const u32x4_t A0 = *(const u32x4_t*)(a0 + ks * 64);
-    const u32x4_t A1 = *(const u32x4_t*)(a1 + ks * 64);
-    sh0 = Mfma<Tag>::run(A0, qhi[ks], sh0);
-    sh1 = Mfma<Tag>::run(A1, qhi[ks], sh1);
-    if (SPLIT) {
-      sl0 = Mfma<Tag>::run(A0, qlo[ks], sl0);
-      sl1 = Mfma<Tag>::run(A1, qlo[ks], sl1);
+  for (int i = 0; i < NKW; ++i) {
+    if (i >= nk) break;
+    u32x4_t N0 = A0, N1 = A1;
+    if (i + 1 < nk) {                      // prefetch the next k-step's rows
+      N0 = *(const u32x4_t*)(a0 + (i + 1) * 256);
+      N1 = *(const u32x4_t*)(a1 + (i + 1) * 256);
     }
-  }
-  s0 = SPLIT ? sh0 + sl0 : sh0;
-  s1 = SPLIT ? sh1 + sl1 : sh1;
-}
-
-// One 128-column group of the weighted coefficient sum: Ug[c] += Cv_tile^T . P.
-// `lane_valid` is false for lanes whose 8 columns lie at or beyond the rank.
-template <class Tag, bool SPLIT>
-__device__ __forceinline__ void wsum_group(const char* vb, int pitch, bool lane_valid,
-                                           const u32x4_t& Phi, const u32x4_t& Plo,
-                                           f32x4_t (&Ug)[8]) {
-  u32x4_t v[8];
 #pragma unroll
-  for (int e = 0; e < 8; ++e)
-    v[e] = *(const u32x4_t*)(vb + (16 * (e >> 2) + (e & 3)) * pitch);
-  if (!lane_valid) {
+    for (int mt = 0; mt < MT; ++mt) {
+      s[mt][0] = Mfma<Tag>::run(A0, qhi[i][mt], s[mt][0]);
+      s[mt][1] = Mfma<Tag>::run(A1, qhi[i][mt], s[mt][1]);
+    }
+    if (SPLIT) {
 #pragma unroll
-    for (int e = 0; e < 8; ++e) { u32x4_t z = {0, 0, 0, 0}; v[e] = z; }
-  }
-  // 8x8 transpose of 16-bit elements: operand c holds column 8n+c of the 8 tokens
-#pragma unroll
-  for (int c = 0; c < 8; ++c) {
-    u32x4_t t;
-#pragma unroll
-    for (int k = 0; k < 4; ++k)
-      t[k] = __builtin_amdgcn_perm(v[2 * k + 1][c >> 1], v[2 * k][c >> 1],
-                                   (c & 1) ? 0x07060302u : 0x05040100u);
-    Ug[c] = Mfma<Tag>::run(t, Phi, Ug[c]);
-    if (SPLIT) Ug[c] = Mfma<Tag>::run(t, Plo, Ug[c]);
+      for (int mt = 0; mt < MT; ++mt) {
+        s[mt][0] = Mfma<Tag>::run(A0, qlo[i][mt], s[mt][0]);
+        s[mt][1] = Mfma<Tag>::run(A1, qlo[i][mt], s[mt][1]);
+      }
+    }
+    A0 = N0;
+    A1 = N1;
+    __builtin_amdgcn_sched_barrier(0);
   }
 }
 
-template <class Tag, bool SPLIT, int NG, int NG_>
-__device__ __forceinline__ void wsum_tile(const char* vb, int pitch, int cols_left, int n,
-                                          const u32x4_t& Phi, const u32x4_t& Plo,
-                                          f32x4_t (&U)[NG][8]) {
+// Weighted coefficient sum of one tile over NG_ 128-column groups.  In every group
+// this wave owns the two columns 8n+2w, 8n+2w+1 of each lane's 8: one dword per row.
+template <class Tag, int MT, bool SPLIT, int NGRP>
+__device__ __forceinline__ void wsum_tile(int ng, const char* vb, int pitch, int r, int n,
+                                          const u32x4_t (&Phi)[MT], const u32x4_t (&Plo)[MT],
+                                          f32x4_t (&U)[NGRP][2][MT]) {
 #pragma unroll
-  for (int gi = 0; gi < NG_; ++gi) {
-    const bool valid = gi * 128 + n * 8 < cols_left;
-    wsum_group<Tag, SPLIT>(vb + gi * 256, pitch, valid, Phi, Plo, U[gi]);
+  for (int grp = 0; grp < NGRP; ++grp) {
+    if (grp >= ng) break;
+    uint32_t v[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+      v[e] = *(const uint32_t*)(vb + (16 * (e >> 2) + (e & 3)) * pitch + grp * 256);
+    if (grp * 128 + n * 8 >= r) {   // half-filled last group
+#pragma unroll
+      for (int e = 0; e < 8; ++e) v[e] = 0;
+    }
+    // 8x2 transpose of 16-bit elements: operand j holds column 8n+2w+j of the 8 tokens
+    u32x4_t te, to;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      te[k] = __builtin_amdgcn_perm(v[2 * k + 1], v[2 * k], 0x05040100u);
+      to[k] = __builtin_amdgcn_perm(v[2 * k + 1], v[2 * k], 0x07060302u);
+    }
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      U[grp][0][mt] = Mfma<Tag>::run(te, Phi[mt], U[grp][0][mt]);
+      U[grp][1][mt] = Mfma<Tag>::run(to, Phi[mt], U[grp][1][mt]);
+    }
+    if (SPLIT) {
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) {
+        U[grp][0][mt] = Mfma<Tag>::run(te, Plo[mt], U[grp][0][mt]);
+        U[grp][1][mt] = Mfma<Tag>::run(to, Plo[mt], U[grp][1][mt]);
+      }
+    }
+    __builtin_amdgcn_sched_barrier(0);
   }
 }
 
@@ -204,27 +237,25 @@ struct AttnParams {
   int T, T_cap, r, H, nsplit;
 };
 
-// Waves come in pairs: wave 2*mt+half owns heads 16mt..16mt+15 and one half of the r
-// columns (half of the score k-steps, half of the 128-column groups of the weighted
-// sum).  The two halves of a pair add their partial scores through LDS once per tile.
-template <class Tag, int NW, int RMAX, bool SPLIT>
-__global__ void __launch_bounds__(NW * 128) __attribute__((amdgpu_waves_per_eu(1, 2)))
+// Four waves, one per SIMD.  Every wave serves ALL heads (MT tiles of 16) on a quarter
+// of the rank axis: score k-steps w, w+4, ... and, in every 128-column group of the
+// weighted sum, two of each lane's eight columns.  The four partial score tiles are
+// added through LDS once per token tile; each wave then runs the same softmax.
+template <class Tag, int MT, int RMAX, bool SPLIT>
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
 attn_partial(const AttnParams p) {
-  constexpr int NWV = 2 * NW;                      // waves per workgroup
-  constexpr int NKSH = RMAX / 64;                  // score k-steps (32 columns) per half
-  constexpr int NCB = (RMAX + 127) / 128;          // 128-column groups in all
-  constexpr int NG = (NCB + 1) / 2;                // groups per half (first half gets the odd one)
+  constexpr int NKW = (RMAX / 32 + 3) / 4;         // score k-steps per wave
+  constexpr int NGRP = (RMAX + 127) / 128;         // 128-column groups
   constexpr int MAXBLK = (RMAX / 8 + 1 + 1) / 2;   // 1 KiB blocks per stage, padded rows
-  constexpr int NSLOT = (MAXBLK + NWV - 1) / NWV;
+  constexpr int NSLOT = (MAXBLK + 3) / 4;
   extern __shared__ __attribute__((aligned(1024))) char smem[];
 
   const int tid = threadIdx.x;
-  const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int mt = wv >> 1, half = wv & 1;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int lane = tid & 63, n = lane & 15, g = lane >> 4;
   const int b = blockIdx.y, s = blockIdx.x;
   const int r = p.r, T = p.T, H = p.H;
-  const int Hp = NW * 16;
+  constexpr int Hp = MT * 16;
 
   // ---- stage geometry: 32 rows of (cpr+1) 16-byte chunks (one pad chunk per row keeps
   //      8 consecutive rows on 8 different bank groups for the row-strided operand reads)
@@ -233,14 +264,14 @@ attn_partial(const AttnParams p) {
   const int tot_chunks = kTile * (cpr + 1);
   const int nblk = (tot_chunks + 63) >> 6;
   const int stage_bytes = nblk * 1024;
-  char* xchg = smem + kNBuf * stage_bytes;          // [NWV][64 lanes][32 B] partial scores
+  f32x4_t* xchg = (f32x4_t*)(smem + kNBuf * stage_bytes);   // [4 waves][2*MT][64 lanes]
 
-  // ---- this wave's share of a stage: blocks wv, wv+NWV, ...; per lane (row, byte offset)
+  // ---- this wave's share of a stage: blocks w, w+4, ...; per lane (row, byte offset)
   uint32_t slot[NSLOT];
   int n_issue = 0;
 #pragma unroll
   for (int k = 0; k < NSLOT; ++k) {
-    const int blk = wv + NWV * k;
+    const int blk = w + 4 * k;
     slot[k] = 0;
     if (blk < nblk) {
       ++n_issue;
@@ -269,7 +300,7 @@ attn_partial(const AttnParams p) {
     char* dst = smem + (q % kNBuf) * stage_bytes;
 #pragma unroll
     for (int k = 0; k < NSLOT; ++k) {
-      const int blk = wv + NWV * k;
+      const int blk = w + 4 * k;
       if (blk < nblk) {
         int tok = tok0 + (int)(slot[k] >> 16);
         tok = tok < T ? tok : T - 1;
@@ -282,44 +313,46 @@ attn_partial(const AttnParams p) {
   if (nq > 0) issue(0);
   if (nq > 1) issue(1);
 
-  // ---- this wave's halves
-  const int nks = r >> 5;                // all score k-steps (even: r % 64 == 0)
-  const int my_nks = nks >> 1;
-  const int ks0 = half * my_nks;
-  const int ncb = (r + 127) >> 7;
-  const int ng0 = (ncb + 1) >> 1;
-  const int cb0 = half * ng0;
-  const int my_ng = half ? ncb - ng0 : ng0;
-  const int cols_left = r - cb0 * 128;   // columns from my first group to the rank
+  // ---- this wave's quarter
+  const int nks = r >> 5;                               // all score k-steps
+  const int my_nks = nks > w ? (nks - w + 3) >> 2 : 0;  // k-steps w, w+4, ...
+  const int ngrp = (r + 127) >> 7;
 
   // ---- q' operands (B operand of the score MFMA): lane (h=n, g) holds columns 32ks+8g..+7
-  u32x4_t qhi[NKSH];
-  u32x4_t qlo[SPLIT ? NKSH : 1];
-  {
-    const uint16_t* qrow = p.Qp + (((size_t)b * 2) * Hp + (mt * 16 + n)) * r + ks0 * 32 + g * 8;
+  u32x4_t qhi[NKW][MT];
+  u32x4_t qlo[SPLIT ? NKW : 1][MT];
 #pragma unroll
-    for (int i = 0; i < NKSH; ++i) {
+  for (int i = 0; i < NKW; ++i)
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
       u32x4_t z = {0, 0, 0, 0};
-      qhi[i] = z;
-      if (SPLIT) qlo[i] = z;
+      qhi[i][mt] = z;
+      if (SPLIT) qlo[i][mt] = z;
       if (i < my_nks) {
-        qhi[i] = *(const u32x4_t*)(qrow + i * 32);
-        if (SPLIT) qlo[i] = *(const u32x4_t*)(qrow + (size_t)Hp * r + i * 32);
+        const uint16_t* qrow =
+            p.Qp + (((size_t)b * 2) * Hp + (mt * 16 + n)) * r + (w + 4 * i) * 32 + g * 8;
+        qhi[i][mt] = *(const u32x4_t*)qrow;
+        if (SPLIT) qlo[i][mt] = *(const u32x4_t*)(qrow + (size_t)Hp * r);
       }
     }
+
+  f32x4_t U[NGRP][2][MT];
+#pragma unroll
+  for (int grp = 0; grp < NGRP; ++grp)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) { f32x4_t z = {0.f, 0.f, 0.f, 0.f}; U[grp][j][mt] = z; }
+  float m_run[MT], l_run[MT];   // running max of head 16mt+n; this lane's share of the sum
+  u32x4_t Phi[MT], Plo[MT];
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt) {
+    m_run[mt] = -INFINITY;
+    l_run[mt] = 0.f;
+    u32x4_t z = {0, 0, 0, 0};
+    Phi[mt] = z;
+    Plo[mt] = z;
   }
-
-  f32x4_t U[NG][8];
-#pragma unroll
-  for (int gi = 0; gi < NG; ++gi)
-#pragma unroll
-    for (int c = 0; c < 8; ++c) { f32x4_t z = {0.f, 0.f, 0.f, 0.f}; U[gi][c] = z; }
-  float m_run = -INFINITY;   // running max of head n (same in the 4 lanes that share n)
-  float l_run = 0.f;         // this lane's share of the running sum
-  u32x4_t Phi = {0, 0, 0, 0}, Plo = {0, 0, 0, 0};
-
-  f32x4_t* my_x = (f32x4_t*)(xchg + (wv * 64 + lane) * 32);
-  const f32x4_t* peer_x = (const f32x4_t*)(xchg + ((wv ^ 1) * 64 + lane) * 32);
 
   for (int q = 0; q < nq; ++q) {
     // loads of stage q must have landed; those of stage q+1 may stay in flight
@@ -330,107 +363,107 @@ attn_partial(const AttnParams p) {
     if ((q & 1) == 0) {
       // ================= scores + online softmax for tile q/2 =================
       const int tok0 = (t_lo + (q >> 1)) * kTile;
-      const char* a0 = buf + n * pitch + g * 16 + ks0 * 64;
+      const char* a0 = buf + n * pitch + g * 16 + w * 64;
       const char* a1 = a0 + 16 * pitch;
-      f32x4_t s0 = {0.f, 0.f, 0.f, 0.f}, s1 = s0;
-#define AP_SCORE_CASE(K)                                                             \
-  case K:                                                                            \
-    if constexpr (K <= NKSH) score_tile<Tag, SPLIT, K>(a0, a1, qhi, qlo, s0, s1);    \
-    break;
-      switch (my_nks) {
-        AP_SCORE_CASE(1) AP_SCORE_CASE(2) AP_SCORE_CASE(3) AP_SCORE_CASE(4) AP_SCORE_CASE(5)
-        AP_SCORE_CASE(6) AP_SCORE_CASE(7) AP_SCORE_CASE(8) AP_SCORE_CASE(9) AP_SCORE_CASE(10)
-        default: break;
+      f32x4_t sp[MT][2];
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) { f32x4_t z = {0.f, 0.f, 0.f, 0.f}; sp[mt][0] = z; sp[mt][1] = z; }
+      score_tile<Tag, MT, SPLIT, NKW>(my_nks, a0, a1, qhi, qlo, sp);
+      // add the four waves' partial scores in a fixed order, so that every wave
+      // carries bit-identical maxima, weights and sums from here on
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) {
+        xchg[(w * 2 * MT + 2 * mt + 0) * 64 + lane] = sp[mt][0];
+        xchg[(w * 2 * MT + 2 * mt + 1) * 64 + lane] = sp[mt][1];
       }
-#undef AP_SCORE_CASE
-      // add the other half's partial scores (a+b == b+a bit for bit, so both waves of
-      // the pair carry identical maxima, weights and sums from here on)
-      my_x[0] = s0;
-      my_x[1] = s1;
       wg_barrier();
-      const f32x4_t o0 = peer_x[0], o1 = peer_x[1];
-      float sc[8];
 #pragma unroll
-      for (int i = 0; i < 4; ++i) { sc[i] = s0[i] + o0[i]; sc[4 + i] = s1[i] + o1[i]; }
-      // lane (h=n, g) holds tokens tok0 + 16*tt + 4*g + i
-      float tmax = -INFINITY;
+      for (int mt = 0; mt < MT; ++mt) {
+        f32x4_t t0 = xchg[(0 * 2 * MT + 2 * mt + 0) * 64 + lane];
+        f32x4_t t1 = xchg[(0 * 2 * MT + 2 * mt + 1) * 64 + lane];
 #pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const int tok = tok0 + 16 * (e >> 2) + 4 * g + (e & 3);
-        if (tok >= T) sc[e] = -INFINITY;
-        tmax = fmaxf(tmax, sc[e]);
-      }
-      tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
-      tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
-      const float m_new = fmaxf(m_run, tmax);     // finite: every tile holds a valid token
-      const float alpha = fast_exp2(m_run - m_new);
-      m_run = m_new;
-      float psum = 0.f;
-      uint16_t ph[8], pl[8];
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const float pe = fast_exp2(sc[e] - m_new);
-        ph[e] = f32_to_bits(pe, Tag{});
-        float kept = bits_to_f32(ph[e], Tag{});
-        if (SPLIT) {
-          pl[e] = f32_to_bits(pe - kept, Tag{});
-          kept += bits_to_f32(pl[e], Tag{});
+        for (int ww = 1; ww < 4; ++ww) {
+          t0 += xchg[(ww * 2 * MT + 2 * mt + 0) * 64 + lane];
+          t1 += xchg[(ww * 2 * MT + 2 * mt + 1) * 64 + lane];
         }
-        psum += kept;                              // the sum uses the values the MFMA will see
-      }
-      l_run = l_run * alpha + psum;
+        float sc[8];
 #pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        Phi[k] = (uint32_t)ph[2 * k] | ((uint32_t)ph[2 * k + 1] << 16);
-        if (SPLIT) Plo[k] = (uint32_t)pl[2 * k] | ((uint32_t)pl[2 * k + 1] << 16);
-      }
-      if (__any(alpha != 1.0f)) {
+        for (int i = 0; i < 4; ++i) { sc[i] = t0[i]; sc[4 + i] = t1[i]; }
+        // lane (h=n, g) holds tokens tok0 + 16*tt + 4*g + i
+        float tmax = -INFINITY;
 #pragma unroll
-        for (int gi = 0; gi < NG; ++gi)
+        for (int e = 0; e < 8; ++e) {
+          const int tok = tok0 + 16 * (e >> 2) + 4 * g + (e & 3);
+          if (tok >= T) sc[e] = -INFINITY;
+          tmax = fmaxf(tmax, sc[e]);
+        }
+        tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
+        tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+        const float m_new = fmaxf(m_run[mt], tmax);   // finite: every tile holds a valid token
+        const float alpha = fast_exp2(m_run[mt] - m_new);
+        m_run[mt] = m_new;
+        float psum = 0.f;
 #pragma unroll
-          for (int c = 0; c < 8; ++c) U[gi][c] *= alpha;
+        for (int k = 0; k < 4; ++k) {
+          const float p0 = fast_exp2(sc[2 * k] - m_new), p1 = fast_exp2(sc[2 * k + 1] - m_new);
+          const uint32_t hi = cvt_pack(p0, p1, Tag{});
+          float k0 = lo_to_f32(hi, Tag{}), k1 = hi_to_f32(hi, Tag{});
+          Phi[mt][k] = hi;
+          if (SPLIT) {
+            const uint32_t lo = cvt_pack(p0 - k0, p1 - k1, Tag{});
+            Plo[mt][k] = lo;
+            k0 += lo_to_f32(lo, Tag{});
+            k1 += hi_to_f32(lo, Tag{});
+          }
+          psum += k0 + k1;                             // the sum uses the values the MFMA will see
+        }
+        l_run[mt] = l_run[mt] * alpha + psum;
+#pragma unroll
+          for (int grp = 0; grp < NGRP; ++grp) {
+            U[grp][0][mt] *= alpha;
+            U[grp][1][mt] *= alpha;
+          }
+        __builtin_amdgcn_sched_barrier(0);
       }
     } else {
       // ================= weighted coefficient sum for tile q/2 =================
-      const char* vb = buf + (4 * g) * pitch + n * 16 + cb0 * 256;
-#define AP_WSUM_CASE(K)                                                                         \
-  case K:                                                                                       \
-    if constexpr (K <= NG) wsum_tile<Tag, SPLIT, NG, K>(vb, pitch, cols_left, n, Phi, Plo, U);   \
-    break;
-      switch (my_ng) {
-        AP_WSUM_CASE(1) AP_WSUM_CASE(2) AP_WSUM_CASE(3)
-        default: break;
-      }
-#undef AP_WSUM_CASE
+      const char* vb = buf + (4 * g) * pitch + n * 16 + w * 4;
+      wsum_tile<Tag, MT, SPLIT, NGRP>(ngrp, vb, pitch, r, n, Phi, Plo, U);
     }
   }
 
-  // ---- epilogue: (m, l) and U of this split.  U[gi][c][i] is element
-  //      (head 16mt+n, column 128(cb0+gi) + 32g + 8i + c); transpose through LDS so that
-  //      rows leave coalesced.
-  float l_tot = l_run;
-  l_tot += __shfl_xor(l_tot, 16);
-  l_tot += __shfl_xor(l_tot, 32);
+  // ---- epilogue: (m, l) and U of this split.  U[grp][j][mt][i] is element
+  //      (head 16mt+n, column 128grp + 32g + 8i + 2w + j); one head tile at a time is
+  //      transposed through LDS so that rows leave coalesced.
   const size_t pbase = ((size_t)b * p.nsplit + s) * H;
-  if (half == 0 && g == 0 && mt * 16 + n < H) {
-    p.part_ml[(pbase + mt * 16 + n) * 2 + 0] = m_run;
-    p.part_ml[(pbase + mt * 16 + n) * 2 + 1] = l_tot;
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt) {
+    float l_tot = l_run[mt];
+    l_tot += __shfl_xor(l_tot, 16);
+    l_tot += __shfl_xor(l_tot, 32);
+    if (w == 0 && g == 0 && mt * 16 + n < H) {
+      p.part_ml[(pbase + mt * 16 + n) * 2 + 0] = m_run[mt];
+      p.part_ml[(pbase + mt * 16 + n) * 2 + 1] = l_tot;
+    }
   }
-  wg_barrier();                                   // ring no longer read by anyone
-  float* ul = (float*)smem;                       // [Hp][r+1]
+  float* ul = (float*)smem;                       // [16][r+1]
 #pragma unroll
-  for (int gi = 0; gi < NG; ++gi)
+  for (int mt = 0; mt < MT; ++mt) {
+    wg_barrier();                                 // ring / previous head tile no longer read
 #pragma unroll
-    for (int c = 0; c < 8; ++c)
+    for (int grp = 0; grp < NGRP; ++grp)
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int col = (cb0 + gi) * 128 + g * 32 + i * 8 + c;
-        if (gi < my_ng && col < r) ul[(mt * 16 + n) * (r + 1) + col] = U[gi][c][i];
-      }
-  wg_barrier();
-  for (int hh = wv; hh < H; hh += NWV) {
-    float* dst = p.part_U + (pbase + hh) * r;
-    for (int j = lane; j < r; j += 64) dst[j] = ul[hh * (r + 1) + j];
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int col = grp * 128 + g * 32 + i * 8 + 2 * w + j;
+          if (col < r) ul[n * (r + 1) + col] = U[grp][j][mt][i];
+        }
+    wg_barrier();
+    for (int hh = w; hh < 16 && mt * 16 + hh < H; hh += 4) {
+      float* dst = p.part_U + (pbase + mt * 16 + hh) * r;
+      for (int j = lane; j < r; j += 64) dst[j] = ul[hh * (r + 1) + j];
+    }
   }
 }
 
@@ -536,15 +569,15 @@ WsLayout ws_layout(int B, int H, int T, int r) {
   return w;
 }
 
-template <class Tag, int NW, int RMAX, bool SPLIT>
+template <class Tag, int MT, int RMAX, bool SPLIT>
 ap_status launch_attn(const AttnParams& p, int B, hipStream_t stream) {
   const int cpr = p.r / 8;
   const int nblk = (kTile * (cpr + 1) + 63) / 64;
-  size_t ring = (size_t)kNBuf * nblk * 1024 + (size_t)2 * NW * 64 * 32;
-  size_t epi = (size_t)NW * 16 * (p.r + 1) * 4;
+  size_t ring = (size_t)kNBuf * nblk * 1024 + (size_t)4 * 2 * MT * 64 * 16;
+  size_t epi = (size_t)16 * (p.r + 1) * 4;
   size_t lds = ring > epi ? ring : epi;
   AP_REQUIRE(lds <= 160 * 1024, AP_ERR_UNSUPPORTED, "ap_decode_attn: LDS need %zu > 160 KiB", lds);
-  auto kern = attn_partial<Tag, NW, RMAX, SPLIT>;
+  auto kern = attn_partial<Tag, MT, RMAX, SPLIT>;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -555,7 +588,7 @@ ap_status launch_attn(const AttnParams& p, int B, hipStream_t stream) {
     }
     attr_set = true;
   }
-  hipLaunchKernelGGL(kern, dim3(p.nsplit, B), dim3(NW * 128), lds, stream, p);
+  hipLaunchKernelGGL(kern, dim3(p.nsplit, B), dim3(256), lds, stream, p);
   return AP_OK;
 }
 
