@@ -9,17 +9,16 @@
 //   merge:   splits combined with their (max, sum) pairs                   (kernel merge_expand)
 //   expand:  out[h,i] = sum_j u[h,j] Bv[j, h*d+i]
 //
-// attn_partial is the HBM-bound kernel.  One workgroup (4 waves, one per SIMD) owns one
-// (sequence, token split).  Coefficient tiles of 32 tokens travel HBM -> LDS with
-// direct-to-LDS loads through a 3-deep ring (K tile, V tile, K tile, ...), two stages in
-// flight while one is consumed, so no VGPR is spent on staging.  Every wave serves all
-// heads on a quarter of the rank axis, so each tile byte is read from LDS exactly once:
+// attn_partial is the HBM-bound kernel.  One workgroup (8 waves) owns one (sequence, token
+// split).  Coefficient tiles of 32 tokens travel HBM -> LDS with direct-to-LDS loads
+// through a ring of 16-row units (K rows, K rows, V rows, V rows, ...), several units in
+// flight while two are consumed, so no VGPR is spent on staging.  Every wave serves all
+// heads on an eighth of the rank axis, so each tile byte is read from LDS exactly once:
 //   S^T[t,h]  = Ck_tile[t,:] . q'^T      MFMA 16x16x32, A = tile rows (LDS), B = q' (VGPR);
-//                                         the four waves' partial sums meet in LDS
+//                                         the eight waves' partial sums meet in LDS and
+//                                         each wave finalises the softmax of 1/8 of the heads
 //   U^T[j,h] += Cv_tile^T[j,t] . P^T     MFMA 16x16x32, A = register transpose of the tile
-//                                         (v_perm), B = P (the S^T accumulator layout is
-//                                         exactly the B-operand layout, so P never leaves
-//                                         registers)
+//                                         (v_perm), B = P read back in operand layout
 // For bf16 storage q' and P are split into hi+lo bf16 pairs (two MFMAs) so that the
 // operand rounding stays far inside the 2e-3 tolerance; fp16 needs no split.
 #include "ap_common.hpp"
@@ -28,7 +27,8 @@ namespace ap {
 namespace {
 
 constexpr int kTile = 32;        // tokens per tile
-constexpr int kNBuf = 3;         // LDS ring depth
+constexpr int kHalf = 16;        // rows per LDS ring unit (half a tile of one matrix)
+constexpr float kLazy = 8.0f;    // log2 slack before the softmax reference moves
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 
@@ -146,26 +146,24 @@ fold_query(const uint16_t* __restrict__ q, const uint16_t* __restrict__ Bk, int6
 
 
 // ------------------------------------------------------------------------------------------
-// tile kernels, fully unrolled for a compile-time number of steps (selected by a
-// wave-uniform switch on the run-time rank, so the unrolled bodies carry no guards)
+// tile kernels (unrolled to the compile-time maximum, left early on the run-time count)
 // ------------------------------------------------------------------------------------------
-// Partial scores of one 32-token tile over this wave's NK_ score k-steps (32 columns
-// each), for all MT head tiles.  The tile rows are read from LDS once and reused by
-// every head tile.
+// Partial scores of one 32-token tile over this wave's `nk` score k-steps (32 columns
+// each, 256 bytes apart), for all MT head tiles.  Tile rows 0-15 / 16-31 live in two
+// ring units (a0 / a1).  Rows are read from LDS once and reused by every head tile.
 template <class Tag, int MT, bool SPLIT, int NKW>
 __device__ __forceinline__ void score_tile(int nk, const char* a0, const char* a1,
                                            const u32x4_t (&qhi)[NKW][MT],
                                            const u32x4_t (&qlo)[SPLIT ? NKW : 1][MT],
                                            f32x4_t (&s)[MT][2]) {
-  u32x4_t A0 = *(const u32x4_t*)a0;
-  u32x4_t A1 = *(const u32x4_t*)a1;
 #pragma unroll
   for (int i = 0; i < NKW; ++i) {
-    if (i >= nk) break;
-    u32x4_t N0 = A0, N1 = A1;
-    if (i + 1 < nk) {                      // prefetch the next k-step's rows
-      N0 = *(const u32x4_t*)(a0 + (i + 1) * 256);
-      N1 = *(const u32x4_t*)(a1 + (i + 1) * 256);
+    // k-steps at or beyond nk multiply zero rows by zero q' (no branch: the accumulators
+    // stay in one straight-line live range)
+    u32x4_t A0 = {0, 0, 0, 0}, A1 = {0, 0, 0, 0};
+    if (i < nk) {
+      A0 = *(const u32x4_t*)(a0 + i * 256);
+      A1 = *(const u32x4_t*)(a1 + i * 256);
     }
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
@@ -179,50 +177,63 @@ __device__ __forceinline__ void score_tile(int nk, const char* a0, const char* a
         s[mt][1] = Mfma<Tag>::run(A1, qlo[i][mt], s[mt][1]);
       }
     }
-    A0 = N0;
-    A1 = N1;
-    __builtin_amdgcn_sched_barrier(0);
   }
 }
 
-// Weighted coefficient sum of one tile over NG_ 128-column groups.  In every group
-// this wave owns the two columns 8n+2w, 8n+2w+1 of each lane's 8: one dword per row.
-template <class Tag, int MT, bool SPLIT, int NGRP>
-__device__ __forceinline__ void wsum_tile(int ng, const char* vb, int pitch, int r, int n,
-                                          const u32x4_t (&Phi)[MT], const u32x4_t (&Plo)[MT],
-                                          f32x4_t (&U)[NGRP][2][MT]) {
+// Weighted coefficient sum of one tile over `ng` 128-column groups (256 bytes apart).  In
+// each group the wave owns one dword (two columns) of every lane's 16 bytes.
+// vA / vB: rows 0-15 / 16-31 of the tile.
+template <class Tag, int MT, bool SPLIT, int NGL>
+__device__ __forceinline__ void wsum_tile(const char* vA, const char* vB, int pitch,
+                                          int cols_left, int n, const u32x4_t (&Phi)[MT],
+                                          const u32x4_t (&Plo)[MT], const float (&alpha)[MT],
+                                          f32x4_t (&U)[NGL][2][MT]) {
 #pragma unroll
-  for (int grp = 0; grp < NGRP; ++grp) {
-    if (grp >= ng) break;
-    uint32_t v[8];
+  for (int i = 0; i < NGL; ++i) {
+    // lanes whose columns lie at or beyond the rank contribute zeros (no branch: the
+    // accumulators stay in one straight-line live range)
+    uint32_t v[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    if (i * 128 + n * 8 < cols_left) {
 #pragma unroll
-    for (int e = 0; e < 8; ++e)
-      v[e] = *(const uint32_t*)(vb + (16 * (e >> 2) + (e & 3)) * pitch + grp * 256);
-    if (grp * 128 + n * 8 >= r) {   // half-filled last group
-#pragma unroll
-      for (int e = 0; e < 8; ++e) v[e] = 0;
+      for (int e = 0; e < 4; ++e) {
+        v[e] = *(const uint32_t*)(vA + e * pitch + i * 256);
+        v[4 + e] = *(const uint32_t*)(vB + e * pitch + i * 256);
+      }
     }
-    // 8x2 transpose of 16-bit elements: operand j holds column 8n+2w+j of the 8 tokens
+    // 8x2 transpose of 16-bit elements: operand j holds one column of the 8 tokens
     u32x4_t te, to;
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
       te[k] = __builtin_amdgcn_perm(v[2 * k + 1], v[2 * k], 0x05040100u);
       to[k] = __builtin_amdgcn_perm(v[2 * k + 1], v[2 * k], 0x07060302u);
     }
+    // alpha is 1 except when the softmax reference exponent moved; multiplying always
+    // (and group by group) keeps the accumulators in one short straight-line live range
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
-      U[grp][0][mt] = Mfma<Tag>::run(te, Phi[mt], U[grp][0][mt]);
-      U[grp][1][mt] = Mfma<Tag>::run(to, Phi[mt], U[grp][1][mt]);
+      U[i][0][mt] = Mfma<Tag>::run(te, Phi[mt], U[i][0][mt] * alpha[mt]);
+      U[i][1][mt] = Mfma<Tag>::run(to, Phi[mt], U[i][1][mt] * alpha[mt]);
     }
     if (SPLIT) {
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) {
-        U[grp][0][mt] = Mfma<Tag>::run(te, Plo[mt], U[grp][0][mt]);
-        U[grp][1][mt] = Mfma<Tag>::run(to, Plo[mt], U[grp][1][mt]);
+        U[i][0][mt] = Mfma<Tag>::run(te, Plo[mt], U[i][0][mt]);
+        U[i][1][mt] = Mfma<Tag>::run(to, Plo[mt], U[i][1][mt]);
       }
     }
     __builtin_amdgcn_sched_barrier(0);
   }
+}
+
+// A non-inlined device function receives its arguments in VGPRs, so the compiler treats
+// everything derived from them as divergent.  These put wave-uniform values back into SGPRs.
+__device__ __forceinline__ int uni(int x) { return __builtin_amdgcn_readfirstlane(x); }
+template <class P>
+__device__ __forceinline__ P* uni_ptr(P* ptr) {
+  const uint64_t v = (uint64_t)ptr;
+  const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)v);
+  const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(v >> 32));
+  return (P*)(((uint64_t)hi << 32) | lo);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -232,93 +243,237 @@ struct AttnParams {
   const uint16_t* Qp;   // [B][2][Hp][r]
   const uint16_t* Ck;   // [B][T_cap][r]
   const uint16_t* Cv;
-  float* part_ml;       // [B][S][H][2]   (running max in log2 units, sum)
+  float* part_ml;       // [B][S][H][2]   (softmax reference exponent in log2 units, sum)
   float* part_U;        // [B][S][H][r]
   int T, T_cap, r, H, nsplit;
+  int nh;               // LDS ring depth in 16-row units (>= 4)
 };
 
-// Four waves, one per SIMD.  Every wave serves ALL heads (MT tiles of 16) on a quarter
-// of the rank axis: score k-steps w, w+4, ... and, in every 128-column group of the
-// weighted sum, two of each lane's eight columns.  The four partial score tiles are
-// added through LDS once per token tile; each wave then runs the same softmax.
+// Eight waves (two per SIMD) in two roles, every one serving ALL heads (MT tiles of 16)
+// on a quarter of the rank axis, so a tile byte is read from LDS once:
+//   score waves 0-3:  k-steps w, w+4, ... of S^T = Ck_tile . q'^T; their four partial score
+//                     tiles meet in LDS.  They hold q' (no accumulators).
+//   sum waves 4-7:    dword w-4 (two columns) of every lane's 16 bytes in every 128-column
+//                     group of U^T += Cv_tile^T . P^T.  They hold U (no q').
+//   all eight waves:  issue the direct-to-LDS loads, and finalise the softmax of 2*MT heads
+//                     each (eight lanes per head): they keep (reference exponent, sum) and
+//                     publish the weights in MFMA operand layout plus a rescale factor.
+// The two roles are separate non-inlined functions (same barrier sequence), so q' and U
+// never compete for registers.  The softmax reference exponent only moves when a score
+// exceeds it by more than kLazy, so the rescale factor is 1 on almost every tile.
+//
+// State every wave carries through the token loop, whatever its role.
 template <class Tag, int MT, int RMAX, bool SPLIT>
-__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
-attn_partial(const AttnParams p) {
-  constexpr int NKW = (RMAX / 32 + 3) / 4;         // score k-steps per wave
-  constexpr int NGRP = (RMAX + 127) / 128;         // 128-column groups
-  constexpr int MAXBLK = (RMAX / 8 + 1 + 1) / 2;   // 1 KiB blocks per stage, padded rows
-  constexpr int NSLOT = (MAXBLK + 3) / 4;
-  extern __shared__ __attribute__((aligned(1024))) char smem[];
+struct WaveCtx {
+  static constexpr int MAXBLK = (kHalf * (RMAX / 8 + 1) + 63) / 64;      // 1 KiB blocks per ring unit
+  static constexpr int NSLOT = (MAXBLK + 7) / 8;
+  static constexpr int HPW = 2 * MT;                                     // heads finalised per wave
 
-  const int tid = threadIdx.x;
-  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int lane = tid & 63, n = lane & 15, g = lane >> 4;
-  const int b = blockIdx.y, s = blockIdx.x;
-  const int r = p.r, T = p.T, H = p.H;
-  constexpr int Hp = MT * 16;
+  int w, lane, n, g, b, s;
+  int r, T, H, nh, nsplit;
+  int pitch, nblk, unit_bytes;
+  char* ring;
+  f32x4_t* xchg;     // [4 score waves][2*MT][64 lanes]
+  u32x4_t* Pbuf;     // [MT][hi,lo][64 lanes]
+  float* abuf;       // [16*MT] rescale factors
+  uint32_t row_bytes;
+  uint32_t slot_off[NSLOT];
+  uint32_t slot_row;
+  int n_issue;
+  int t_lo, nsteps, nunits;
+  const char* Ck_b;
+  const char* Cv_b;
+  int iu, islot, cslot;
+  // softmax ownership: lane = 8*head_local + slot, slot = 4*tt + gg covers tokens
+  // 16*tt + 4*gg .. +3 of the tile for head o_hh
+  bool owner;
+  int o_hh, o_tt, o_gg, o_mt, o_lane;
+  float m_ref, l_part;
 
-  // ---- stage geometry: 32 rows of (cpr+1) 16-byte chunks (one pad chunk per row keeps
-  //      8 consecutive rows on 8 different bank groups for the row-strided operand reads)
-  const int cpr = r >> 3;
-  const int pitch = (cpr + 1) * 16;
-  const int tot_chunks = kTile * (cpr + 1);
-  const int nblk = (tot_chunks + 63) >> 6;
-  const int stage_bytes = nblk * 1024;
-  f32x4_t* xchg = (f32x4_t*)(smem + kNBuf * stage_bytes);   // [4 waves][2*MT][64 lanes]
-
-  // ---- this wave's share of a stage: blocks w, w+4, ...; per lane (row, byte offset)
-  uint32_t slot[NSLOT];
-  int n_issue = 0;
+  __device__ __forceinline__ void init(const AttnParams& p) {
+    extern __shared__ __attribute__((aligned(1024))) char smem[];
+    const int tid = threadIdx.x;
+    w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    lane = tid & 63; n = lane & 15; g = lane >> 4;
+    b = uni(blockIdx.y); s = uni(blockIdx.x);
+    r = uni(p.r); T = uni(p.T); H = uni(p.H); nh = uni(p.nh); nsplit = uni(p.nsplit);
+    // ring unit geometry: 16 rows of (cpr+1) 16-byte chunks (one pad chunk per row keeps 8
+    // consecutive rows on 8 different bank groups for the row-strided operand reads)
+    const int cpr = r >> 3;
+    pitch = (cpr + 1) * 16;
+    const int tot_chunks = kHalf * (cpr + 1);
+    nblk = (tot_chunks + 63) >> 6;
+    unit_bytes = nblk * 1024;
+    ring = smem;
+    xchg = (f32x4_t*)(smem + nh * unit_bytes);
+    Pbuf = (u32x4_t*)(xchg + 4 * 2 * MT * 64);
+    abuf = (float*)(Pbuf + MT * 2 * 64);
+    // this wave's share of a unit: blocks w, w+8, ...; per lane the row and the byte offset
+    // of its 16-byte chunk from the unit's first row
+    row_bytes = (uint32_t)r * 2u;
+    slot_row = 0;
+    n_issue = 0;
 #pragma unroll
-  for (int k = 0; k < NSLOT; ++k) {
-    const int blk = w + 4 * k;
-    slot[k] = 0;
-    if (blk < nblk) {
-      ++n_issue;
-      const int L = blk * 64 + lane;
-      int row = L / (cpr + 1);
-      int c = L - row * (cpr + 1);
-      if (L >= tot_chunks) { row = 0; c = 0; }   // tail of the last block: harmless duplicate
-      if (c == cpr) c = 0;                        // pad chunk: harmless duplicate
-      slot[k] = ((uint32_t)row << 16) | (uint32_t)(c * 16);
+    for (int k = 0; k < NSLOT; ++k) {
+      const int blk = w + 8 * k;
+      slot_off[k] = 0;
+      if (blk < nblk) {
+        ++n_issue;
+        const int L = blk * 64 + lane;
+        int row = L / (cpr + 1);
+        int c = L - row * (cpr + 1);
+        if (L >= tot_chunks) { row = 0; c = 0; }   // tail of the last block: harmless duplicate
+        if (c == cpr) c = 0;                        // pad chunk: harmless duplicate
+        slot_off[k] = (uint32_t)row * row_bytes + (uint32_t)(c * 16);
+        slot_row |= (uint32_t)row << (8 * k);
+      }
+    }
+    // token tiles of this split; unit u = 4*tile + 2*isV + half
+    const int ntiles = (T + kTile - 1) / kTile;
+    t_lo = (int)(((int64_t)s * ntiles) / nsplit);
+    const int t_hi = (int)(((int64_t)(s + 1) * ntiles) / nsplit);
+    nsteps = 2 * (t_hi - t_lo);
+    nunits = 2 * nsteps;
+    // per-sequence byte offsets fit 32 bits (checked on the host)
+    const int T_cap = uni(p.T_cap);
+    Ck_b = (const char*)(uni_ptr(p.Ck) + (size_t)b * T_cap * r);
+    Cv_b = (const char*)(uni_ptr(p.Cv) + (size_t)b * T_cap * r);
+    iu = 0; islot = 0; cslot = 0;
+    owner = lane < 8 * HPW;
+    o_hh = w * HPW + (lane >> 3);
+    o_tt = (lane >> 2) & 1; o_gg = lane & 3;
+    o_mt = o_hh >> 4; o_lane = (o_hh & 15) + 16 * o_gg;
+    m_ref = -INFINITY; l_part = 0.f;
+    while (iu < nunits && iu < nh - 2) issue_unit();
+  }
+
+  __device__ __forceinline__ void issue_unit() {
+    const int tok_u = (t_lo + (iu >> 2)) * kTile + (iu & 1) * kHalf;
+    const char* src = (iu & 2) ? Cv_b : Ck_b;
+    char* dst = ring + islot * unit_bytes;
+    const uint32_t base = (uint32_t)tok_u * row_bytes;
+    if (tok_u + kHalf <= T) {
+#pragma unroll
+      for (int k = 0; k < NSLOT; ++k) {
+        const int blk = w + 8 * k;
+        if (blk < nblk) dma16(src + (base + slot_off[k]), dst + blk * 1024);
+      }
+    } else {                                       // rows at or beyond T: clamp to row T-1
+#pragma unroll
+      for (int k = 0; k < NSLOT; ++k) {
+        const int blk = w + 8 * k;
+        if (blk < nblk) {
+          const int row = (int)((slot_row >> (8 * k)) & 0xffu);
+          uint32_t off = base + slot_off[k];
+          if (tok_u + row >= T) off -= (uint32_t)(tok_u + row - (T - 1)) * row_bytes;
+          dma16(src + off, dst + blk * 1024);
+        }
+      }
+    }
+    ++iu;
+    islot = islot + 1 == nh ? 0 : islot + 1;
+  }
+
+  // Start of step c: wait for units 2c, 2c+1 (later units may stay in flight), meet the
+  // other waves, refill the ring; returns the two ring slots.
+  __device__ __forceinline__ void step_begin(int c, int& sa, int& sb) {
+    int later = nh - 4;
+    const int rest = nunits - 2 * c - 2;
+    later = later < rest ? later : rest;
+    wait_vmcnt(later * n_issue);
+    wg_barrier();   // both units complete for every wave; everyone is done with step c-1
+    if (iu < nunits) issue_unit();
+    if (iu < nunits) issue_unit();
+    sa = cslot;
+    sb = cslot + 1 == nh ? 0 : cslot + 1;
+    cslot = sb + 1 == nh ? 0 : sb + 1;
+  }
+
+  // Softmax of this wave's heads for the tile starting at token tok0 (after the score
+  // waves' partial tiles are in xchg).
+  __device__ __forceinline__ void finalize_softmax(int tok0) {
+    if (!owner) return;
+    const int tile_idx = 2 * o_mt + o_tt;
+    f32x4_t sc = xchg[(0 * 2 * MT + tile_idx) * 64 + o_lane];
+#pragma unroll
+    for (int sw = 1; sw < 4; ++sw) sc += xchg[(sw * 2 * MT + tile_idx) * 64 + o_lane];
+    if (tok0 + kTile > T) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        if (tok0 + 16 * o_tt + 4 * o_gg + i >= T) sc[i] = -INFINITY;
+    }
+    float tmax = fmaxf(fmaxf(sc[0], sc[1]), fmaxf(sc[2], sc[3]));
+    tmax = fmaxf(tmax, __shfl_xor(tmax, 1));
+    tmax = fmaxf(tmax, __shfl_xor(tmax, 2));
+    tmax = fmaxf(tmax, __shfl_xor(tmax, 4));
+    float alpha = 1.0f;
+    if (tmax > m_ref + kLazy) {                 // same decision in the 8 lanes of a head
+      const float m_upd = fmaxf(m_ref, tmax);   // finite: every tile holds a valid token
+      alpha = fast_exp2(m_ref - m_upd);
+      m_ref = m_upd;
+      l_part *= alpha;
+    }
+    const float p0 = fast_exp2(sc[0] - m_ref), p1 = fast_exp2(sc[1] - m_ref);
+    const float p2 = fast_exp2(sc[2] - m_ref), p3 = fast_exp2(sc[3] - m_ref);
+    u32x2_t hi, lo = {0, 0};
+    hi[0] = cvt_pack(p0, p1, Tag{});
+    hi[1] = cvt_pack(p2, p3, Tag{});
+    float k0 = lo_to_f32(hi[0], Tag{}), k1 = hi_to_f32(hi[0], Tag{});
+    float k2 = lo_to_f32(hi[1], Tag{}), k3 = hi_to_f32(hi[1], Tag{});
+    if (SPLIT) {
+      lo[0] = cvt_pack(p0 - k0, p1 - k1, Tag{});
+      lo[1] = cvt_pack(p2 - k2, p3 - k3, Tag{});
+      k0 += lo_to_f32(lo[0], Tag{});
+      k1 += hi_to_f32(lo[0], Tag{});
+      k2 += lo_to_f32(lo[1], Tag{});
+      k3 += hi_to_f32(lo[1], Tag{});
+    }
+    l_part += (k0 + k1) + (k2 + k3);            // the sum uses the values the MFMA will see
+    // weights in B-operand layout: lane (n, g) of head tile mt holds tokens 4g..4g+3
+    // (dwords 0,1) and 16+4g..+3 (dwords 2,3)
+    u32x2_t* ph = (u32x2_t*)(Pbuf + (o_mt * 2 + 0) * 64 + o_lane) + o_tt;
+    *ph = hi;
+    if (SPLIT) *(ph + 2 * 64) = lo;             // [o_mt][1][o_lane]
+    if ((lane & 7) == 0) abuf[o_hh] = alpha;
+  }
+
+  // (reference exponent, sum) of the heads this wave finalised.
+  __device__ __forceinline__ void store_ml(float* part_ml) {
+    float l_tot = l_part;
+    l_tot += __shfl_xor(l_tot, 1);
+    l_tot += __shfl_xor(l_tot, 2);
+    l_tot += __shfl_xor(l_tot, 4);
+    if (owner && (lane & 7) == 0 && o_hh < H) {
+      const size_t pb = ((size_t)b * nsplit + s) * H + o_hh;
+      part_ml[pb * 2 + 0] = m_ref;
+      part_ml[pb * 2 + 1] = l_tot;
     }
   }
 
-  // ---- token tiles of this split
-  const int ntiles = (T + kTile - 1) / kTile;
-  const int t_lo = (int)(((int64_t)s * ntiles) / p.nsplit);
-  const int t_hi = (int)(((int64_t)(s + 1) * ntiles) / p.nsplit);
-  const int nq = 2 * (t_hi - t_lo);
-
-  const char* Ck_b = (const char*)(p.Ck + (size_t)b * p.T_cap * r);
-  const char* Cv_b = (const char*)(p.Cv + (size_t)b * p.T_cap * r);
-  const uint32_t row_bytes = (uint32_t)r * 2u;
-
-  auto issue = [&](int q) {
-    const int tok0 = (t_lo + (q >> 1)) * kTile;
-    const char* src = (q & 1) ? Cv_b : Ck_b;
-    char* dst = smem + (q % kNBuf) * stage_bytes;
-#pragma unroll
-    for (int k = 0; k < NSLOT; ++k) {
-      const int blk = w + 4 * k;
-      if (blk < nblk) {
-        int tok = tok0 + (int)(slot[k] >> 16);
-        tok = tok < T ? tok : T - 1;
-        const char* ga = src + (size_t)tok * row_bytes + (slot[k] & 0xffffu);
-        dma16(ga, dst + blk * 1024);
-      }
+  // Rows 16mt+w, 16mt+w+8 of one head tile's U, staged in LDS as [16][r+1], to global memory.
+  __device__ __forceinline__ void copy_out_rows(float* part_U, int mt) {
+    const float* ul = (const float*)ring;
+    const size_t pbase = ((size_t)b * nsplit + s) * H;
+    for (int hh = w; hh < 16 && mt * 16 + hh < H; hh += 8) {
+      float* dst = part_U + (pbase + mt * 16 + hh) * r;
+      for (int j = lane; j < r; j += 64) dst[j] = ul[hh * (r + 1) + j];
     }
-  };
+  }
+};
 
-  if (nq > 0) issue(0);
-  if (nq > 1) issue(1);
-
-  // ---- this wave's quarter
-  const int nks = r >> 5;                               // all score k-steps
-  const int my_nks = nks > w ? (nks - w + 3) >> 2 : 0;  // k-steps w, w+4, ...
-  const int ngrp = (r + 127) >> 7;
-
-  // ---- q' operands (B operand of the score MFMA): lane (h=n, g) holds columns 32ks+8g..+7
+template <class Tag, int MT, int RMAX, bool SPLIT>
+__device__ __noinline__ void score_role(const AttnParams& p) {
+  constexpr int NKW = (RMAX / 32 + 3) / 4;                // score k-steps per score wave
+  constexpr int Hp = MT * 16;
+  WaveCtx<Tag, MT, RMAX, SPLIT> cx;
+  cx.init(p);
+  float* part_U = uni_ptr(p.part_U);
+  float* part_ml = uni_ptr(p.part_ml);
+  const int w = cx.w, n = cx.n, g = cx.g, r = cx.r;
+  const int nks = r >> 5;                                 // all score k-steps
+  const int my_nks = nks > w ? (nks - w + 3) >> 2 : 0;    // k-steps w, w+4, ...
+  // q' operands (B operand of the score MFMA): lane (h=n, g) holds columns 32ks+8g..+7
+  const uint16_t* Qp = uni_ptr(p.Qp);
   u32x4_t qhi[NKW][MT];
   u32x4_t qlo[SPLIT ? NKW : 1][MT];
 #pragma unroll
@@ -330,141 +485,104 @@ attn_partial(const AttnParams p) {
       if (SPLIT) qlo[i][mt] = z;
       if (i < my_nks) {
         const uint16_t* qrow =
-            p.Qp + (((size_t)b * 2) * Hp + (mt * 16 + n)) * r + (w + 4 * i) * 32 + g * 8;
+            Qp + (((size_t)cx.b * 2) * Hp + (mt * 16 + n)) * r + (w + 4 * i) * 32 + g * 8;
         qhi[i][mt] = *(const u32x4_t*)qrow;
         if (SPLIT) qlo[i][mt] = *(const u32x4_t*)(qrow + (size_t)Hp * r);
       }
     }
-
-  f32x4_t U[NGRP][2][MT];
-#pragma unroll
-  for (int grp = 0; grp < NGRP; ++grp)
-#pragma unroll
-    for (int j = 0; j < 2; ++j)
-#pragma unroll
-      for (int mt = 0; mt < MT; ++mt) { f32x4_t z = {0.f, 0.f, 0.f, 0.f}; U[grp][j][mt] = z; }
-  float m_run[MT], l_run[MT];   // running max of head 16mt+n; this lane's share of the sum
-  u32x4_t Phi[MT], Plo[MT];
-#pragma unroll
-  for (int mt = 0; mt < MT; ++mt) {
-    m_run[mt] = -INFINITY;
-    l_run[mt] = 0.f;
-    u32x4_t z = {0, 0, 0, 0};
-    Phi[mt] = z;
-    Plo[mt] = z;
-  }
-
-  for (int q = 0; q < nq; ++q) {
-    // loads of stage q must have landed; those of stage q+1 may stay in flight
-    wait_vmcnt(q + 1 < nq ? n_issue : 0);
-    wg_barrier();   // stage q complete for every wave; everyone is done with stage q-1
-    if (q + 2 < nq) issue(q + 2);
-    const char* buf = smem + (q % kNBuf) * stage_bytes;
-    if ((q & 1) == 0) {
-      // ================= scores + online softmax for tile q/2 =================
-      const int tok0 = (t_lo + (q >> 1)) * kTile;
-      const char* a0 = buf + n * pitch + g * 16 + w * 64;
-      const char* a1 = a0 + 16 * pitch;
+  for (int t = 0; 2 * t < cx.nsteps; ++t) {
+    int sa, sb;
+    cx.step_begin(2 * t, sa, sb);                         // K rows of tile t
+    {
+      const char* a0 = cx.ring + sa * cx.unit_bytes + n * cx.pitch + g * 16 + w * 64;
+      const char* a1 = cx.ring + sb * cx.unit_bytes + n * cx.pitch + g * 16 + w * 64;
       f32x4_t sp[MT][2];
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) { f32x4_t z = {0.f, 0.f, 0.f, 0.f}; sp[mt][0] = z; sp[mt][1] = z; }
       score_tile<Tag, MT, SPLIT, NKW>(my_nks, a0, a1, qhi, qlo, sp);
-      // add the four waves' partial scores in a fixed order, so that every wave
-      // carries bit-identical maxima, weights and sums from here on
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) {
-        xchg[(w * 2 * MT + 2 * mt + 0) * 64 + lane] = sp[mt][0];
-        xchg[(w * 2 * MT + 2 * mt + 1) * 64 + lane] = sp[mt][1];
+        cx.xchg[(w * 2 * MT + 2 * mt + 0) * 64 + cx.lane] = sp[mt][0];
+        cx.xchg[(w * 2 * MT + 2 * mt + 1) * 64 + cx.lane] = sp[mt][1];
       }
       wg_barrier();
-#pragma unroll
-      for (int mt = 0; mt < MT; ++mt) {
-        f32x4_t t0 = xchg[(0 * 2 * MT + 2 * mt + 0) * 64 + lane];
-        f32x4_t t1 = xchg[(0 * 2 * MT + 2 * mt + 1) * 64 + lane];
-#pragma unroll
-        for (int ww = 1; ww < 4; ++ww) {
-          t0 += xchg[(ww * 2 * MT + 2 * mt + 0) * 64 + lane];
-          t1 += xchg[(ww * 2 * MT + 2 * mt + 1) * 64 + lane];
-        }
-        float sc[8];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) { sc[i] = t0[i]; sc[4 + i] = t1[i]; }
-        // lane (h=n, g) holds tokens tok0 + 16*tt + 4*g + i
-        float tmax = -INFINITY;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          const int tok = tok0 + 16 * (e >> 2) + 4 * g + (e & 3);
-          if (tok >= T) sc[e] = -INFINITY;
-          tmax = fmaxf(tmax, sc[e]);
-        }
-        tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
-        tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
-        const float m_new = fmaxf(m_run[mt], tmax);   // finite: every tile holds a valid token
-        const float alpha = fast_exp2(m_run[mt] - m_new);
-        m_run[mt] = m_new;
-        float psum = 0.f;
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-          const float p0 = fast_exp2(sc[2 * k] - m_new), p1 = fast_exp2(sc[2 * k + 1] - m_new);
-          const uint32_t hi = cvt_pack(p0, p1, Tag{});
-          float k0 = lo_to_f32(hi, Tag{}), k1 = hi_to_f32(hi, Tag{});
-          Phi[mt][k] = hi;
-          if (SPLIT) {
-            const uint32_t lo = cvt_pack(p0 - k0, p1 - k1, Tag{});
-            Plo[mt][k] = lo;
-            k0 += lo_to_f32(lo, Tag{});
-            k1 += hi_to_f32(lo, Tag{});
-          }
-          psum += k0 + k1;                             // the sum uses the values the MFMA will see
-        }
-        l_run[mt] = l_run[mt] * alpha + psum;
-#pragma unroll
-          for (int grp = 0; grp < NGRP; ++grp) {
-            U[grp][0][mt] *= alpha;
-            U[grp][1][mt] *= alpha;
-          }
-        __builtin_amdgcn_sched_barrier(0);
-      }
-    } else {
-      // ================= weighted coefficient sum for tile q/2 =================
-      const char* vb = buf + (4 * g) * pitch + n * 16 + w * 4;
-      wsum_tile<Tag, MT, SPLIT, NGRP>(ngrp, vb, pitch, r, n, Phi, Plo, U);
+      cx.finalize_softmax((cx.t_lo + t) * kTile);
     }
+    cx.step_begin(2 * t + 1, sa, sb);                     // V rows of tile t: nothing to do here
   }
+  // the sum waves stage U through LDS one head tile at a time; help copy it out
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt) {
+    wg_barrier();
+    wg_barrier();
+    cx.copy_out_rows(part_U, mt);
+  }
+  cx.store_ml(part_ml);
+}
 
-  // ---- epilogue: (m, l) and U of this split.  U[grp][j][mt][i] is element
-  //      (head 16mt+n, column 128grp + 32g + 8i + 2w + j); one head tile at a time is
-  //      transposed through LDS so that rows leave coalesced.
-  const size_t pbase = ((size_t)b * p.nsplit + s) * H;
+template <class Tag, int MT, int RMAX, bool SPLIT>
+__device__ __noinline__ void sum_role(const AttnParams& p) {
+  constexpr int NGRP = (RMAX + 127) / 128;                // 128-column groups
+  WaveCtx<Tag, MT, RMAX, SPLIT> cx;
+  cx.init(p);
+  float* part_U = uni_ptr(p.part_U);
+  float* part_ml = uni_ptr(p.part_ml);
+  const int n = cx.n, g = cx.g, r = cx.r;
+  const int cp = cx.w - 4;                                // dword of each lane's 16 bytes
+  f32x4_t U[NGRP][2][MT];
 #pragma unroll
-  for (int mt = 0; mt < MT; ++mt) {
-    float l_tot = l_run[mt];
-    l_tot += __shfl_xor(l_tot, 16);
-    l_tot += __shfl_xor(l_tot, 32);
-    if (w == 0 && g == 0 && mt * 16 + n < H) {
-      p.part_ml[(pbase + mt * 16 + n) * 2 + 0] = m_run[mt];
-      p.part_ml[(pbase + mt * 16 + n) * 2 + 1] = l_tot;
+  for (int i = 0; i < NGRP; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) { f32x4_t z = {0.f, 0.f, 0.f, 0.f}; U[i][j][mt] = z; }
+  for (int t = 0; 2 * t < cx.nsteps; ++t) {
+    int sa, sb;
+    cx.step_begin(2 * t, sa, sb);                         // K rows of tile t: score waves work
+    wg_barrier();
+    cx.finalize_softmax((cx.t_lo + t) * kTile);
+    cx.step_begin(2 * t + 1, sa, sb);                     // V rows of tile t
+    u32x4_t Phi[MT], Plo[MT];
+    float alpha[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      alpha[mt] = cx.abuf[mt * 16 + n];
+      Phi[mt] = cx.Pbuf[(mt * 2 + 0) * 64 + cx.lane];
+      if (SPLIT) Plo[mt] = cx.Pbuf[(mt * 2 + 1) * 64 + cx.lane];
+      else { u32x4_t z = {0, 0, 0, 0}; Plo[mt] = z; }
     }
+    const char* vA = cx.ring + sa * cx.unit_bytes + (4 * g) * cx.pitch + n * 16 + cp * 4;
+    const char* vB = cx.ring + sb * cx.unit_bytes + (4 * g) * cx.pitch + n * 16 + cp * 4;
+    wsum_tile<Tag, MT, SPLIT, NGRP>(vA, vB, cx.pitch, r, n, Phi, Plo, alpha, U);
   }
-  float* ul = (float*)smem;                       // [16][r+1]
+  // U of this split.  U[i][j][mt][e] is element (head 16mt+n, column 128i + 32g + 8e +
+  // 2cp + j); one head tile at a time is transposed through LDS so that rows leave coalesced.
+  float* ul = (float*)cx.ring;                      // [16][r+1]
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) {
-    wg_barrier();                                 // ring / previous head tile no longer read
+    wg_barrier();                                   // ring / previous head tile no longer read
 #pragma unroll
-    for (int grp = 0; grp < NGRP; ++grp)
+    for (int i = 0; i < NGRP; ++i)
 #pragma unroll
       for (int j = 0; j < 2; ++j)
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const int col = grp * 128 + g * 32 + i * 8 + 2 * w + j;
-          if (col < r) ul[n * (r + 1) + col] = U[grp][j][mt][i];
+        for (int e = 0; e < 4; ++e) {
+          const int col = i * 128 + g * 32 + e * 8 + 2 * cp + j;
+          if (col < r) ul[n * (r + 1) + col] = U[i][j][mt][e];
         }
     wg_barrier();
-    for (int hh = w; hh < 16 && mt * 16 + hh < H; hh += 4) {
-      float* dst = p.part_U + (pbase + mt * 16 + hh) * r;
-      for (int j = lane; j < r; j += 64) dst[j] = ul[hh * (r + 1) + j];
-    }
+    cx.copy_out_rows(part_U, mt);
   }
+  cx.store_ml(part_ml);
+}
+
+template <class Tag, int MT, int RMAX, bool SPLIT>
+__global__ void __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2)))
+attn_partial(const AttnParams p) {
+  if (__builtin_amdgcn_readfirstlane(threadIdx.x >> 6) < 4)
+    score_role<Tag, MT, RMAX, SPLIT>(p);
+  else
+    sum_role<Tag, MT, RMAX, SPLIT>(p);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -570,25 +688,31 @@ WsLayout ws_layout(int B, int H, int T, int r) {
 }
 
 template <class Tag, int MT, int RMAX, bool SPLIT>
-ap_status launch_attn(const AttnParams& p, int B, hipStream_t stream) {
+ap_status launch_attn(AttnParams p, int B, hipStream_t stream) {
   const int cpr = p.r / 8;
-  const int nblk = (kTile * (cpr + 1) + 63) / 64;
-  size_t ring = (size_t)kNBuf * nblk * 1024 + (size_t)4 * 2 * MT * 64 * 16;
-  size_t epi = (size_t)16 * (p.r + 1) * 4;
-  size_t lds = ring > epi ? ring : epi;
-  AP_REQUIRE(lds <= 160 * 1024, AP_ERR_UNSUPPORTED, "ap_decode_attn: LDS need %zu > 160 KiB", lds);
+  const size_t unit = (size_t)((kHalf * (cpr + 1) + 63) / 64) * 1024;
+  const size_t fixed = (size_t)4 * 2 * MT * 64 * 16 + (size_t)MT * 2 * 64 * 16 + (size_t)MT * 16 * 4;
+  const size_t budget = 160 * 1024;
+  int nh = (int)((budget - fixed) / unit);
+  if (nh > 8) nh = 8;
+  AP_REQUIRE(nh >= 4, AP_ERR_UNSUPPORTED, "ap_decode_attn: H=%d r=%d needs more LDS than 160 KiB",
+             p.H, p.r);
+  p.nh = nh;
+  size_t lds = (size_t)nh * unit + fixed;
+  const size_t epi = (size_t)16 * (p.r + 1) * 4;
+  if (epi > lds) lds = epi;
   auto kern = attn_partial<Tag, MT, RMAX, SPLIT>;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       160 * 1024);
+                                       (int)budget);
     if (e != hipSuccess) {
       set_error("hipFuncSetAttribute: %s", hipGetErrorString(e));
       return AP_ERR_HIP;
     }
     attr_set = true;
   }
-  hipLaunchKernelGGL(kern, dim3(p.nsplit, B), dim3(256), lds, stream, p);
+  hipLaunchKernelGGL(kern, dim3(p.nsplit, B), dim3(512), lds, stream, p);
   return AP_OK;
 }
 
@@ -597,8 +721,9 @@ ap_status dispatch_attn(const AttnParams& p, int B, hipStream_t stream) {
   const int nw = (p.H + 15) / 16;
 #define AP_CASE(NWV)                                                              \
   case NWV:                                                                       \
-    return p.r <= 256 ? launch_attn<Tag, NWV, 256, SPLIT>(p, B, stream)           \
-                      : launch_attn<Tag, NWV, 640, SPLIT>(p, B, stream);
+    return p.r <= 256   ? launch_attn<Tag, NWV, 256, SPLIT>(p, B, stream)         \
+           : p.r <= 512 ? launch_attn<Tag, NWV, 512, SPLIT>(p, B, stream)         \
+                        : launch_attn<Tag, NWV, 640, SPLIT>(p, B, stream);
   switch (nw) {
     AP_CASE(1) AP_CASE(2) AP_CASE(3) AP_CASE(4)
   }
@@ -619,7 +744,7 @@ ap_status run_decode(const DecodeArgs& a) {
   hipLaunchKernelGGL(fold_query<Tag>, dim3(Hp, a.B), dim3(256), 0, a.stream, (const uint16_t*)a.q,
                      (const uint16_t*)a.Bk, a.basis_batch_stride, Qp, a.H, Hp, a.d, a.r,
                      a.sm_scale * kLog2e);
-  AttnParams p{Qp, (const uint16_t*)a.Ck, (const uint16_t*)a.Cv, ml, U, a.T, a.T_cap, a.r, a.H, S};
+  AttnParams p{Qp, (const uint16_t*)a.Ck, (const uint16_t*)a.Cv, ml, U, a.T, a.T_cap, a.r, a.H, S, 0};
   ap_status st = dispatch_attn<Tag, SPLIT>(p, a.B, a.stream);
   if (st != AP_OK) return st;
   const int rows = 256 / (a.d / 8);
