@@ -23,6 +23,8 @@
 // operand rounding stays far inside the 2e-3 tolerance; fp16 needs no split.
 #include "ap_common.hpp"
 
+#include <cstdlib>
+
 namespace ap {
 namespace {
 
@@ -148,56 +150,63 @@ fold_query(const uint16_t* __restrict__ q, const uint16_t* __restrict__ Bk, int6
 // ------------------------------------------------------------------------------------------
 // tile kernels (unrolled to the compile-time maximum, left early on the run-time count)
 // ------------------------------------------------------------------------------------------
-// Partial scores of one 32-token tile over this wave's `nk` score k-steps (32 columns
-// each, 256 bytes apart), for all MT head tiles.  Tile rows 0-15 / 16-31 live in two
-// ring units (a0 / a1).  Rows are read from LDS once and reused by every head tile.
+// Partial scores of one 32-token tile over this wave's score k-steps (32 columns each), for
+// all MT head tiles.  A[i][tt]: rows 16tt..16tt+15 of the tile at k-step i, in registers.
+// k-steps this wave does not own hold zero rows and zero q' (no branch: the accumulators
+// stay in one straight-line live range).
 template <class Tag, int MT, bool SPLIT, int NKW>
-__device__ __forceinline__ void score_tile(int nk, const char* a0, const char* a1,
+__device__ __forceinline__ void score_tile(const u32x4_t (&A)[NKW][2],
                                            const u32x4_t (&qhi)[NKW][MT],
                                            const u32x4_t (&qlo)[SPLIT ? NKW : 1][MT],
                                            f32x4_t (&s)[MT][2]) {
 #pragma unroll
   for (int i = 0; i < NKW; ++i) {
-    // k-steps at or beyond nk multiply zero rows by zero q' (no branch: the accumulators
-    // stay in one straight-line live range)
-    u32x4_t A0 = {0, 0, 0, 0}, A1 = {0, 0, 0, 0};
-    if (i < nk) {
-      A0 = *(const u32x4_t*)(a0 + i * 256);
-      A1 = *(const u32x4_t*)(a1 + i * 256);
-    }
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
-      s[mt][0] = Mfma<Tag>::run(A0, qhi[i][mt], s[mt][0]);
-      s[mt][1] = Mfma<Tag>::run(A1, qhi[i][mt], s[mt][1]);
+      s[mt][0] = Mfma<Tag>::run(A[i][0], qhi[i][mt], s[mt][0]);
+      s[mt][1] = Mfma<Tag>::run(A[i][1], qhi[i][mt], s[mt][1]);
     }
     if (SPLIT) {
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) {
-        s[mt][0] = Mfma<Tag>::run(A0, qlo[i][mt], s[mt][0]);
-        s[mt][1] = Mfma<Tag>::run(A1, qlo[i][mt], s[mt][1]);
+        s[mt][0] = Mfma<Tag>::run(A[i][0], qlo[i][mt], s[mt][0]);
+        s[mt][1] = Mfma<Tag>::run(A[i][1], qlo[i][mt], s[mt][1]);
       }
     }
   }
 }
 
-// Weighted coefficient sum of one tile over `ng` 128-column groups (256 bytes apart).  In
-// each group the wave owns one dword (two columns) of every lane's 16 bytes.
-// vA / vB: rows 0-15 / 16-31 of the tile.
+// Weighted coefficient sum of one tile over all 128-column groups (256 bytes apart).  In
+// each group the wave owns four 16-byte chunks (32 columns): MFMA row m = 4g'+e reads dword
+// e of chunk g', so the 16 lanes of a row group read 64 contiguous bytes and the four row
+// groups fall on different banks (no LDS bank conflicts).  vA / vB: rows 0-15 / 16-31 of
+// the tile, already offset to this lane's dword.
 template <class Tag, int MT, bool SPLIT, int NGL>
 __device__ __forceinline__ void wsum_tile(const char* vA, const char* vB, int pitch,
                                           int cols_left, int n, const u32x4_t (&Phi)[MT],
                                           const u32x4_t (&Plo)[MT], const float (&alpha)[MT],
                                           f32x4_t (&U)[NGL][2][MT]) {
+  // lanes whose columns lie at or beyond the rank contribute zeros (no branch around the
+  // MFMAs: the accumulators stay in one straight-line live range); the rows of group i+1
+  // are fetched while group i is multiplied
+  uint32_t nx[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+  if (n * 2 < cols_left) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      nx[e] = *(const uint32_t*)(vA + e * pitch);
+      nx[4 + e] = *(const uint32_t*)(vB + e * pitch);
+    }
+  }
 #pragma unroll
   for (int i = 0; i < NGL; ++i) {
-    // lanes whose columns lie at or beyond the rank contribute zeros (no branch: the
-    // accumulators stay in one straight-line live range)
-    uint32_t v[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-    if (i * 128 + n * 8 < cols_left) {
+    uint32_t v[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { v[e] = nx[e]; nx[e] = 0; }
+    if (i + 1 < NGL && (i + 1) * 128 + n * 2 < cols_left) {
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
-        v[e] = *(const uint32_t*)(vA + e * pitch + i * 256);
-        v[4 + e] = *(const uint32_t*)(vB + e * pitch + i * 256);
+        nx[e] = *(const uint32_t*)(vA + e * pitch + (i + 1) * 256);
+        nx[4 + e] = *(const uint32_t*)(vB + e * pitch + (i + 1) * 256);
       }
     }
     // 8x2 transpose of 16-bit elements: operand j holds one column of the 8 tokens
@@ -221,8 +230,28 @@ __device__ __forceinline__ void wsum_tile(const char* vA, const char* vB, int pi
         U[i][1][mt] = Mfma<Tag>::run(to, Plo[mt], U[i][1][mt]);
       }
     }
-    __builtin_amdgcn_sched_barrier(0);
   }
+}
+
+// Butterfly steps inside groups of 8 lanes with DPP (VALU speed, no LDS crossbar):
+// xor 1 and xor 2 as quad permutes; the third step mirrors each half-row, which pairs the
+// two quads of an 8-lane group (all lanes of a quad already agree after the first two).
+template <int CTRL>
+__device__ __forceinline__ float dpp_f32(float x) {
+  const int v = __builtin_bit_cast(int, x);
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(v, v, CTRL, 0xf, 0xf, false));
+}
+__device__ __forceinline__ float max8(float x) {
+  x = fmaxf(x, dpp_f32<0xB1>(x));    // quad_perm [1,0,3,2]
+  x = fmaxf(x, dpp_f32<0x4E>(x));    // quad_perm [2,3,0,1]
+  x = fmaxf(x, dpp_f32<0x141>(x));   // row_half_mirror
+  return x;
+}
+__device__ __forceinline__ float sum8(float x) {
+  x += dpp_f32<0xB1>(x);
+  x += dpp_f32<0x4E>(x);
+  x += dpp_f32<0x141>(x);
+  return x;
 }
 
 // A non-inlined device function receives its arguments in VGPRs, so the compiler treats
@@ -246,44 +275,44 @@ struct AttnParams {
   float* part_ml;       // [B][S][H][2]   (softmax reference exponent in log2 units, sum)
   float* part_U;        // [B][S][H][r]
   int T, T_cap, r, H, nsplit;
-  int nh;               // LDS ring depth in 16-row units (>= 4)
+  int nh;               // C_v LDS ring depth in 16-row units (even, >= 2)
+  int dbg;              // experiments: 1 = no loads, 2 = no math, 4 = phase timers
+  unsigned long long* dbg_out;
 };
 
 // Eight waves (two per SIMD) in two roles, every one serving ALL heads (MT tiles of 16)
-// on a quarter of the rank axis, so a tile byte is read from LDS once:
-//   score waves 0-3:  k-steps w, w+4, ... of S^T = Ck_tile . q'^T; their four partial score
-//                     tiles meet in LDS.  They hold q' (no accumulators).
-//   sum waves 4-7:    dword w-4 (two columns) of every lane's 16 bytes in every 128-column
-//                     group of U^T += Cv_tile^T . P^T.  They hold U (no q').
-//   all eight waves:  issue the direct-to-LDS loads, and finalise the softmax of 2*MT heads
-//                     each (eight lanes per head): they keep (reference exponent, sum) and
-//                     publish the weights in MFMA operand layout plus a rescale factor.
-// The two roles are separate non-inlined functions (same barrier sequence), so q' and U
-// never compete for registers.  The softmax reference exponent only moves when a score
-// exceeds it by more than kLazy, so the rescale factor is 1 on almost every tile.
+// on a quarter of the rank axis:
+//   score waves 0-3:  k-steps w, w+4, ... of S^T = Ck_tile . q'^T.  They hold q' and fetch
+//                     their slice of the C_k rows straight from global memory into MFMA
+//                     operand registers (16 rows x 64 B per load instruction), one tile
+//                     ahead; their four partial score tiles meet in LDS.
+//   sum waves 4-7:    32 of every 128 columns of U^T += Cv_tile^T . P^T.  They hold U and
+//                     stream the C_v rows HBM -> LDS with direct-to-LDS loads through a ring
+//                     of 16-row units, several tiles ahead, so no VGPR is spent on staging
+//                     and every LDS byte is read exactly once.
+//   all eight waves:  finalise the softmax of 2*MT heads each (eight lanes per head): they
+//                     keep (reference exponent, sum) and publish the weights in MFMA operand
+//                     layout plus a per-head rescale factor.
+// The score waves work on tile t+1 while the sum waves accumulate tile t; two workgroup
+// barriers per tile ("partial scores ready", "weights ready") keep them in step.  The two
+// roles are separate non-inlined functions (same barrier sequence), so q' and U never
+// compete for registers.  The softmax reference exponent only moves when a score exceeds
+// it by more than kLazy, so the rescale factor is 1 on almost every tile.
 //
 // State every wave carries through the token loop, whatever its role.
-template <class Tag, int MT, int RMAX, bool SPLIT>
+template <class Tag, int MT, bool SPLIT>
 struct WaveCtx {
-  static constexpr int MAXBLK = (kHalf * (RMAX / 8 + 1) + 63) / 64;      // 1 KiB blocks per ring unit
-  static constexpr int NSLOT = (MAXBLK + 7) / 8;
-  static constexpr int HPW = 2 * MT;                                     // heads finalised per wave
+  static constexpr int HPW = 2 * MT;     // heads finalised per wave
 
   int w, lane, n, g, b, s;
-  int r, T, H, nh, nsplit;
+  int r, T, H, nh, nsplit, dbg;
   int pitch, nblk, unit_bytes;
   char* ring;
-  f32x4_t* xchg;     // [4 score waves][2*MT][64 lanes]
+  f32x4_t* xchg;     // [4 score waves][16*MT heads][9]: 8 slots (4*tt+g) + 1 pad per head
   u32x4_t* Pbuf;     // [MT][hi,lo][64 lanes]
   float* abuf;       // [16*MT] rescale factors
   uint32_t row_bytes;
-  uint32_t slot_off[NSLOT];
-  uint32_t slot_row;
-  int n_issue;
-  int t_lo, nsteps, nunits;
-  const char* Ck_b;
-  const char* Cv_b;
-  int iu, islot, cslot;
+  int t_lo, ntl;     // first tile and number of tiles of this split
   // softmax ownership: lane = 8*head_local + slot, slot = 4*tt + gg covers tokens
   // 16*tt + 4*gg .. +3 of the tile for head o_hh
   bool owner;
@@ -296,116 +325,43 @@ struct WaveCtx {
     w = __builtin_amdgcn_readfirstlane(tid >> 6);
     lane = tid & 63; n = lane & 15; g = lane >> 4;
     b = uni(blockIdx.y); s = uni(blockIdx.x);
-    r = uni(p.r); T = uni(p.T); H = uni(p.H); nh = uni(p.nh); nsplit = uni(p.nsplit);
-    // ring unit geometry: 16 rows of (cpr+1) 16-byte chunks (one pad chunk per row keeps 8
-    // consecutive rows on 8 different bank groups for the row-strided operand reads)
+    r = uni(p.r); T = uni(p.T); H = uni(p.H); nh = uni(p.nh); nsplit = uni(p.nsplit); dbg = uni(p.dbg);
+    // ring unit geometry: 16 rows of (cpr+1) 16-byte chunks (one pad chunk per row shifts
+    // consecutive rows across the LDS banks)
     const int cpr = r >> 3;
     pitch = (cpr + 1) * 16;
-    const int tot_chunks = kHalf * (cpr + 1);
-    nblk = (tot_chunks + 63) >> 6;
+    nblk = (kHalf * (cpr + 1) + 63) >> 6;
     unit_bytes = nblk * 1024;
     ring = smem;
     xchg = (f32x4_t*)(smem + nh * unit_bytes);
-    Pbuf = (u32x4_t*)(xchg + 4 * 2 * MT * 64);
+    Pbuf = (u32x4_t*)(xchg + 4 * 16 * MT * 9);
     abuf = (float*)(Pbuf + MT * 2 * 64);
-    // this wave's share of a unit: blocks w, w+8, ...; per lane the row and the byte offset
-    // of its 16-byte chunk from the unit's first row
     row_bytes = (uint32_t)r * 2u;
-    slot_row = 0;
-    n_issue = 0;
-#pragma unroll
-    for (int k = 0; k < NSLOT; ++k) {
-      const int blk = w + 8 * k;
-      slot_off[k] = 0;
-      if (blk < nblk) {
-        ++n_issue;
-        const int L = blk * 64 + lane;
-        int row = L / (cpr + 1);
-        int c = L - row * (cpr + 1);
-        if (L >= tot_chunks) { row = 0; c = 0; }   // tail of the last block: harmless duplicate
-        if (c == cpr) c = 0;                        // pad chunk: harmless duplicate
-        slot_off[k] = (uint32_t)row * row_bytes + (uint32_t)(c * 16);
-        slot_row |= (uint32_t)row << (8 * k);
-      }
-    }
-    // token tiles of this split; unit u = 4*tile + 2*isV + half
     const int ntiles = (T + kTile - 1) / kTile;
     t_lo = (int)(((int64_t)s * ntiles) / nsplit);
-    const int t_hi = (int)(((int64_t)(s + 1) * ntiles) / nsplit);
-    nsteps = 2 * (t_hi - t_lo);
-    nunits = 2 * nsteps;
-    // per-sequence byte offsets fit 32 bits (checked on the host)
-    const int T_cap = uni(p.T_cap);
-    Ck_b = (const char*)(uni_ptr(p.Ck) + (size_t)b * T_cap * r);
-    Cv_b = (const char*)(uni_ptr(p.Cv) + (size_t)b * T_cap * r);
-    iu = 0; islot = 0; cslot = 0;
+    ntl = (int)(((int64_t)(s + 1) * ntiles) / nsplit) - t_lo;
     owner = lane < 8 * HPW;
     o_hh = w * HPW + (lane >> 3);
     o_tt = (lane >> 2) & 1; o_gg = lane & 3;
     o_mt = o_hh >> 4; o_lane = (o_hh & 15) + 16 * o_gg;
     m_ref = -INFINITY; l_part = 0.f;
-    while (iu < nunits && iu < nh - 2) issue_unit();
-  }
-
-  __device__ __forceinline__ void issue_unit() {
-    const int tok_u = (t_lo + (iu >> 2)) * kTile + (iu & 1) * kHalf;
-    const char* src = (iu & 2) ? Cv_b : Ck_b;
-    char* dst = ring + islot * unit_bytes;
-    const uint32_t base = (uint32_t)tok_u * row_bytes;
-    if (tok_u + kHalf <= T) {
-#pragma unroll
-      for (int k = 0; k < NSLOT; ++k) {
-        const int blk = w + 8 * k;
-        if (blk < nblk) dma16(src + (base + slot_off[k]), dst + blk * 1024);
-      }
-    } else {                                       // rows at or beyond T: clamp to row T-1
-#pragma unroll
-      for (int k = 0; k < NSLOT; ++k) {
-        const int blk = w + 8 * k;
-        if (blk < nblk) {
-          const int row = (int)((slot_row >> (8 * k)) & 0xffu);
-          uint32_t off = base + slot_off[k];
-          if (tok_u + row >= T) off -= (uint32_t)(tok_u + row - (T - 1)) * row_bytes;
-          dma16(src + off, dst + blk * 1024);
-        }
-      }
-    }
-    ++iu;
-    islot = islot + 1 == nh ? 0 : islot + 1;
-  }
-
-  // Start of step c: wait for units 2c, 2c+1 (later units may stay in flight), meet the
-  // other waves, refill the ring; returns the two ring slots.
-  __device__ __forceinline__ void step_begin(int c, int& sa, int& sb) {
-    int later = nh - 4;
-    const int rest = nunits - 2 * c - 2;
-    later = later < rest ? later : rest;
-    wait_vmcnt(later * n_issue);
-    wg_barrier();   // both units complete for every wave; everyone is done with step c-1
-    if (iu < nunits) issue_unit();
-    if (iu < nunits) issue_unit();
-    sa = cslot;
-    sb = cslot + 1 == nh ? 0 : cslot + 1;
-    cslot = sb + 1 == nh ? 0 : sb + 1;
   }
 
   // Softmax of this wave's heads for the tile starting at token tok0 (after the score
   // waves' partial tiles are in xchg).
   __device__ __forceinline__ void finalize_softmax(int tok0) {
     if (!owner) return;
-    const int tile_idx = 2 * o_mt + o_tt;
-    f32x4_t sc = xchg[(0 * 2 * MT + tile_idx) * 64 + o_lane];
+    const int xi = o_hh * 9 + (lane & 7);
+    f32x4_t sc = xchg[xi];
 #pragma unroll
-    for (int sw = 1; sw < 4; ++sw) sc += xchg[(sw * 2 * MT + tile_idx) * 64 + o_lane];
+    for (int sw = 1; sw < 4; ++sw) sc += xchg[sw * 16 * MT * 9 + xi];
     if (tok0 + kTile > T) {
 #pragma unroll
       for (int i = 0; i < 4; ++i)
         if (tok0 + 16 * o_tt + 4 * o_gg + i >= T) sc[i] = -INFINITY;
     }
     float tmax = fmaxf(fmaxf(sc[0], sc[1]), fmaxf(sc[2], sc[3]));
-    tmax = fmaxf(tmax, __shfl_xor(tmax, 1));
-    tmax = fmaxf(tmax, __shfl_xor(tmax, 2));
-    tmax = fmaxf(tmax, __shfl_xor(tmax, 4));
+    tmax = max8(tmax);
     float alpha = 1.0f;
     if (tmax > m_ref + kLazy) {                 // same decision in the 8 lanes of a head
       const float m_upd = fmaxf(m_ref, tmax);   // finite: every tile holds a valid token
@@ -439,10 +395,7 @@ struct WaveCtx {
 
   // (reference exponent, sum) of the heads this wave finalised.
   __device__ __forceinline__ void store_ml(float* part_ml) {
-    float l_tot = l_part;
-    l_tot += __shfl_xor(l_tot, 1);
-    l_tot += __shfl_xor(l_tot, 2);
-    l_tot += __shfl_xor(l_tot, 4);
+    const float l_tot = sum8(l_part);
     if (owner && (lane & 7) == 0 && o_hh < H) {
       const size_t pb = ((size_t)b * nsplit + s) * H + o_hh;
       part_ml[pb * 2 + 0] = m_ref;
@@ -465,11 +418,12 @@ template <class Tag, int MT, int RMAX, bool SPLIT>
 __device__ __noinline__ void score_role(const AttnParams& p) {
   constexpr int NKW = (RMAX / 32 + 3) / 4;                // score k-steps per score wave
   constexpr int Hp = MT * 16;
-  WaveCtx<Tag, MT, RMAX, SPLIT> cx;
+  const unsigned long long t_entry_ = __builtin_readcyclecounter();
+  WaveCtx<Tag, MT, SPLIT> cx;
   cx.init(p);
   float* part_U = uni_ptr(p.part_U);
   float* part_ml = uni_ptr(p.part_ml);
-  const int w = cx.w, n = cx.n, g = cx.g, r = cx.r;
+  const int w = cx.w, n = cx.n, g = cx.g, r = cx.r, T = cx.T;
   const int nks = r >> 5;                                 // all score k-steps
   const int my_nks = nks > w ? (nks - w + 3) >> 2 : 0;    // k-steps w, w+4, ...
   // q' operands (B operand of the score MFMA): lane (h=n, g) holds columns 32ks+8g..+7
@@ -490,25 +444,53 @@ __device__ __noinline__ void score_role(const AttnParams& p) {
         if (SPLIT) qlo[i][mt] = *(const u32x4_t*)(qrow + (size_t)Hp * r);
       }
     }
-  for (int t = 0; 2 * t < cx.nsteps; ++t) {
-    int sa, sb;
-    cx.step_begin(2 * t, sa, sb);                         // K rows of tile t
-    {
-      const char* a0 = cx.ring + sa * cx.unit_bytes + n * cx.pitch + g * 16 + w * 64;
-      const char* a1 = cx.ring + sb * cx.unit_bytes + n * cx.pitch + g * 16 + w * 64;
-      f32x4_t sp[MT][2];
+  // C_k operands (A operand): lane (n, g) holds columns 32ks+8g..+7 of token rows n, 16+n
+  // of the tile.  Per-sequence byte offsets fit 32 bits (checked on the host).
+  const char* Ck_b = (const char*)(uni_ptr(p.Ck) + (size_t)cx.b * uni(p.T_cap) * r);
+  // k-steps this wave does not own re-read its first chunk (finite data times zero q'):
+  // the loads carry no branches, so they issue back to back without waits between them
+  const uint32_t lane_off = (uint32_t)((my_nks > 0 ? w * 64 : 0) + g * 16);
+  u32x4_t A[NKW][2];
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt) { f32x4_t z = {0.f, 0.f, 0.f, 0.f}; sp[mt][0] = z; sp[mt][1] = z; }
-      score_tile<Tag, MT, SPLIT, NKW>(my_nks, a0, a1, qhi, qlo, sp);
+  for (int i = 0; i < NKW; ++i) { u32x4_t z = {0, 0, 0, 0}; A[i][0] = z; A[i][1] = z; }
+  uint32_t koff[NKW];
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt) {
-        cx.xchg[(w * 2 * MT + 2 * mt + 0) * 64 + cx.lane] = sp[mt][0];
-        cx.xchg[(w * 2 * MT + 2 * mt + 1) * 64 + cx.lane] = sp[mt][1];
-      }
-      wg_barrier();
-      cx.finalize_softmax((cx.t_lo + t) * kTile);
+  for (int i = 0; i < NKW; ++i) koff[i] = i < my_nks ? (uint32_t)i * 256u : 0u;
+  auto load_A = [&](int tile) {
+    if (cx.dbg & 1) return;
+#pragma unroll
+    for (int tt = 0; tt < 2; ++tt) {
+      int row = tile * kTile + 16 * tt + n;
+      row = row < T ? row : T - 1;                        // rows beyond T are masked later
+      const char* rp = Ck_b + ((uint32_t)row * cx.row_bytes + lane_off);
+#pragma unroll
+      for (int i = 0; i < NKW; ++i) A[i][tt] = *(const u32x4_t*)(rp + koff[i]);
     }
-    cx.step_begin(2 * t + 1, sa, sb);                     // V rows of tile t: nothing to do here
+  };
+  if (cx.ntl > 0) load_A(cx.t_lo);
+
+  unsigned long long tm[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+#define AP_TICK(k) { const unsigned long long now_ = __builtin_readcyclecounter(); tm[k] += now_ - t0_; t0_ = now_; }
+  unsigned long long t0_ = __builtin_readcyclecounter();
+  tm[0] = t0_ - t_entry_;
+  for (int t = 0; t < cx.ntl; ++t) {
+    f32x4_t sp[MT][2];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) { f32x4_t z = {0.f, 0.f, 0.f, 0.f}; sp[mt][0] = z; sp[mt][1] = z; }
+    if (!(cx.dbg & 2)) score_tile<Tag, MT, SPLIT, NKW>(A, qhi, qlo, sp);
+    AP_TICK(1)
+    if (t + 1 < cx.ntl) load_A(cx.t_lo + t + 1);          // lands while the tile is finished
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      cx.xchg[(w * 16 * MT + mt * 16 + n) * 9 + g] = sp[mt][0];
+      cx.xchg[(w * 16 * MT + mt * 16 + n) * 9 + 4 + g] = sp[mt][1];
+    }
+    wg_barrier();                                         // partial scores of tile t ready
+    AP_TICK(2)
+    cx.finalize_softmax((cx.t_lo + t) * kTile);
+    AP_TICK(3)
+    wg_barrier();                                         // weights of tile t ready
+    AP_TICK(4)
   }
   // the sum waves stage U through LDS one head tile at a time; help copy it out
 #pragma unroll
@@ -518,17 +500,84 @@ __device__ __noinline__ void score_role(const AttnParams& p) {
     cx.copy_out_rows(part_U, mt);
   }
   cx.store_ml(part_ml);
+  AP_TICK(6)
+  if ((cx.dbg & 4) && cx.b == 0 && cx.s == 0 && cx.lane == 0) {
+    unsigned long long* out_ = uni_ptr(p.dbg_out);
+    for (int k = 0; k < 8; ++k) out_[cx.w * 8 + k] = tm[k];
+  }
 }
 
 template <class Tag, int MT, int RMAX, bool SPLIT>
 __device__ __noinline__ void sum_role(const AttnParams& p) {
-  constexpr int NGRP = (RMAX + 127) / 128;                // 128-column groups
-  WaveCtx<Tag, MT, RMAX, SPLIT> cx;
+  constexpr int NGRP = (RMAX + 127) / 128;                        // 128-column groups
+  constexpr int MAXBLK = (kHalf * (RMAX / 8 + 1) + 63) / 64;      // 1 KiB blocks per ring unit
+  constexpr int NSLOT = (MAXBLK + 3) / 4;
+  const unsigned long long t_entry_ = __builtin_readcyclecounter();
+  WaveCtx<Tag, MT, SPLIT> cx;
   cx.init(p);
   float* part_U = uni_ptr(p.part_U);
   float* part_ml = uni_ptr(p.part_ml);
-  const int n = cx.n, g = cx.g, r = cx.r;
-  const int cp = cx.w - 4;                                // dword of each lane's 16 bytes
+  const int n = cx.n, g = cx.g, r = cx.r, T = cx.T, lane = cx.lane;
+  const int cp = cx.w - 4;                                // which 32 columns of every group
+  const int RT = cx.nh >> 1;                              // ring capacity in tiles
+
+  // ---- this wave's share of a C_v ring unit: 1 KiB blocks cp, cp+4, ...; per lane the
+  //      row and the byte offset of its 16-byte chunk from the unit's first row
+  const int cpr = r >> 3;
+  const int tot_chunks = kHalf * (cpr + 1);
+  uint32_t slot_off[NSLOT];
+  uint32_t slot_row[(NSLOT + 3) / 4];
+#pragma unroll
+  for (int k = 0; k < (NSLOT + 3) / 4; ++k) slot_row[k] = 0;
+  int n_issue = 0;
+#pragma unroll
+  for (int k = 0; k < NSLOT; ++k) {
+    const int blk = cp + 4 * k;
+    slot_off[k] = 0;
+    if (blk < cx.nblk) {
+      ++n_issue;
+      const int L = blk * 64 + lane;
+      int row = L / (cpr + 1);
+      int c = L - row * (cpr + 1);
+      if (L >= tot_chunks) { row = 0; c = 0; }   // tail of the last block: harmless duplicate
+      if (c == cpr) c = 0;                        // pad chunk: harmless duplicate
+      slot_off[k] = (uint32_t)row * cx.row_bytes + (uint32_t)(c * 16);
+      slot_row[k >> 2] |= (uint32_t)row << (8 * (k & 3));
+    }
+  }
+  const char* Cv_b = (const char*)(uni_ptr(p.Cv) + (size_t)cx.b * uni(p.T_cap) * r);
+  // both 16-row units of local tile lt into ring slots 2*(lt % RT), +1
+  auto issue_tile = [&](int lt) {
+    if (cx.dbg & 1) return;
+    const int slot0 = 2 * (lt % RT);
+#pragma nounroll
+    for (int half = 0; half < 2; ++half) {
+      const int tok_u = (cx.t_lo + lt) * kTile + half * kHalf;
+      char* dst = cx.ring + (slot0 + half) * cx.unit_bytes;
+      const uint32_t base = (uint32_t)tok_u * cx.row_bytes;
+      if (tok_u + kHalf <= T) {
+#pragma unroll
+        for (int k = 0; k < NSLOT; ++k) {
+          const int blk = cp + 4 * k;
+          if (blk < cx.nblk) dma16(Cv_b + (base + slot_off[k]), dst + blk * 1024);
+        }
+      } else {                                     // rows at or beyond T: clamp to row T-1
+#pragma unroll
+        for (int k = 0; k < NSLOT; ++k) {
+          const int blk = cp + 4 * k;
+          if (blk < cx.nblk) {
+            const int row = (int)((slot_row[k >> 2] >> (8 * (k & 3))) & 0xffu);
+            uint32_t off = base + slot_off[k];
+            if (tok_u + row >= T) off -= (uint32_t)(tok_u + row - (T - 1)) * cx.row_bytes;
+            dma16(Cv_b + off, dst + blk * 1024);
+          }
+        }
+      }
+    }
+  };
+#pragma nounroll
+  for (int lt = 0; lt < RT && lt < cx.ntl; ++lt) issue_tile(lt);
+
   f32x4_t U[NGRP][2][MT];
 #pragma unroll
   for (int i = 0; i < NGRP; ++i)
@@ -536,27 +585,42 @@ __device__ __noinline__ void sum_role(const AttnParams& p) {
     for (int j = 0; j < 2; ++j)
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) { f32x4_t z = {0.f, 0.f, 0.f, 0.f}; U[i][j][mt] = z; }
-  for (int t = 0; 2 * t < cx.nsteps; ++t) {
-    int sa, sb;
-    cx.step_begin(2 * t, sa, sb);                         // K rows of tile t: score waves work
-    wg_barrier();
+  unsigned long long tm[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+  unsigned long long t0_ = __builtin_readcyclecounter();
+  tm[0] = t0_ - t_entry_;
+  for (int t = 0; t < cx.ntl; ++t) {
+    wg_barrier();            // partial scores of tile t ready; every sum wave is past tile t-1
+    AP_TICK(2)
+    if (t >= 1 && t - 1 + RT < cx.ntl) issue_tile(t - 1 + RT);   // refill tile t-1's slots
     cx.finalize_softmax((cx.t_lo + t) * kTile);
-    cx.step_begin(2 * t + 1, sa, sb);                     // V rows of tile t
+    AP_TICK(3)
+    {
+      // tile t's rows must have landed; the tiles issued after it may stay in flight
+      int later = cx.ntl - t - 1;
+      later = later < RT - 1 ? later : RT - 1;
+      wait_vmcnt(later * 2 * n_issue);
+    }
+    wg_barrier();            // weights of tile t ready; tile t's rows visible to every wave
+    AP_TICK(4)
     u32x4_t Phi[MT], Plo[MT];
     float alpha[MT];
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
       alpha[mt] = cx.abuf[mt * 16 + n];
-      Phi[mt] = cx.Pbuf[(mt * 2 + 0) * 64 + cx.lane];
-      if (SPLIT) Plo[mt] = cx.Pbuf[(mt * 2 + 1) * 64 + cx.lane];
+      Phi[mt] = cx.Pbuf[(mt * 2 + 0) * 64 + lane];
+      if (SPLIT) Plo[mt] = cx.Pbuf[(mt * 2 + 1) * 64 + lane];
       else { u32x4_t z = {0, 0, 0, 0}; Plo[mt] = z; }
     }
-    const char* vA = cx.ring + sa * cx.unit_bytes + (4 * g) * cx.pitch + n * 16 + cp * 4;
-    const char* vB = cx.ring + sb * cx.unit_bytes + (4 * g) * cx.pitch + n * 16 + cp * 4;
-    wsum_tile<Tag, MT, SPLIT, NGRP>(vA, vB, cx.pitch, r, n, Phi, Plo, alpha, U);
+    // lane (n, g): token rows 4g..4g+3 (and 16+4g..), dword n of this wave's 64 bytes
+    const int slot0 = 2 * (t % RT);
+    const char* vA = cx.ring + slot0 * cx.unit_bytes + (4 * g) * cx.pitch + cp * 64 + n * 4;
+    const char* vB = vA + cx.unit_bytes;
+    if (!(cx.dbg & 2))
+      wsum_tile<Tag, MT, SPLIT, NGRP>(vA, vB, cx.pitch, r - cp * 32, n, Phi, Plo, alpha, U);
+    AP_TICK(5)
   }
-  // U of this split.  U[i][j][mt][e] is element (head 16mt+n, column 128i + 32g + 8e +
-  // 2cp + j); one head tile at a time is transposed through LDS so that rows leave coalesced.
+  // U of this split.  U[i][j][mt][e] is element (head 16mt+n, column 128i + 32cp + 8g +
+  // 2e + j); one head tile at a time is transposed through LDS so that rows leave coalesced.
   float* ul = (float*)cx.ring;                      // [16][r+1]
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) {
@@ -567,14 +631,20 @@ __device__ __noinline__ void sum_role(const AttnParams& p) {
       for (int j = 0; j < 2; ++j)
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          const int col = i * 128 + g * 32 + e * 8 + 2 * cp + j;
+          const int col = i * 128 + cp * 32 + g * 8 + e * 2 + j;
           if (col < r) ul[n * (r + 1) + col] = U[i][j][mt][e];
         }
     wg_barrier();
     cx.copy_out_rows(part_U, mt);
   }
   cx.store_ml(part_ml);
+  AP_TICK(6)
+  if ((cx.dbg & 4) && cx.b == 0 && cx.s == 0 && cx.lane == 0) {
+    unsigned long long* out_ = uni_ptr(p.dbg_out);
+    for (int k = 0; k < 8; ++k) out_[cx.w * 8 + k] = tm[k];
+  }
 }
+#undef AP_TICK
 
 template <class Tag, int MT, int RMAX, bool SPLIT>
 __global__ void __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2)))
@@ -691,11 +761,12 @@ template <class Tag, int MT, int RMAX, bool SPLIT>
 ap_status launch_attn(AttnParams p, int B, hipStream_t stream) {
   const int cpr = p.r / 8;
   const size_t unit = (size_t)((kHalf * (cpr + 1) + 63) / 64) * 1024;
-  const size_t fixed = (size_t)4 * 2 * MT * 64 * 16 + (size_t)MT * 2 * 64 * 16 + (size_t)MT * 16 * 4;
+  const size_t fixed = (size_t)4 * 16 * MT * 9 * 16 + (size_t)MT * 2 * 64 * 16 + (size_t)MT * 16 * 4;
   const size_t budget = 160 * 1024;
   int nh = (int)((budget - fixed) / unit);
-  if (nh > 8) nh = 8;
-  AP_REQUIRE(nh >= 4, AP_ERR_UNSUPPORTED, "ap_decode_attn: H=%d r=%d needs more LDS than 160 KiB",
+  if (nh > 12) nh = 12;
+  nh &= ~1;
+  AP_REQUIRE(nh >= 2, AP_ERR_UNSUPPORTED, "ap_decode_attn: H=%d r=%d needs more LDS than 160 KiB",
              p.H, p.r);
   p.nh = nh;
   size_t lds = (size_t)nh * unit + fixed;
@@ -744,7 +815,9 @@ ap_status run_decode(const DecodeArgs& a) {
   hipLaunchKernelGGL(fold_query<Tag>, dim3(Hp, a.B), dim3(256), 0, a.stream, (const uint16_t*)a.q,
                      (const uint16_t*)a.Bk, a.basis_batch_stride, Qp, a.H, Hp, a.d, a.r,
                      a.sm_scale * kLog2e);
-  AttnParams p{Qp, (const uint16_t*)a.Ck, (const uint16_t*)a.Cv, ml, U, a.T, a.T_cap, a.r, a.H, S, 0};
+  AttnParams p{Qp, (const uint16_t*)a.Ck, (const uint16_t*)a.Cv, ml, U, a.T, a.T_cap, a.r, a.H, S, 0, 0, nullptr};
+  if (const char* e = getenv("AP_DEBUG_ATTN")) p.dbg = atoi(e);
+  p.dbg_out = (unsigned long long*)U;   // timers overwrite the head of part_U (debug only)
   ap_status st = dispatch_attn<Tag, SPLIT>(p, a.B, a.stream);
   if (st != AP_OK) return st;
   const int rows = 256 / (a.d / 8);
