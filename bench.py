@@ -1,0 +1,189 @@
+#!/usr/bin/env python3
+"""Decode benchmark of the compacted-KV attention path on one MI355X.
+
+Workload (the 13B-shaped batch decode the paper motivates with): B=64 sequences,
+H=40 heads of d=128 (HD=5120), 16 images x 256 + 128 text = 4224 cached tokens, rank
+r=640, bf16 coefficients and per-sequence bases, fp32 accumulation and fp32 output.
+One step = append one token's coefficients (ap_compact, n=1) + ap_decode_attn over
+all cached tokens, for one layer; T grows by one per step.  Inputs are synthetic,
+generated on the GPU in the value law of paper_2603_23914_amd.workloads and resident
+in HBM before the timed region.
+
+Prints ONE JSON line.  `value` is layer-tokens/s (B * steps / seconds) of the
+attention path of one layer.  `roofline` prices the coefficient-streaming kernel
+(attn_partial) against the 8 TB/s HBM peak with its algorithmic bytes
+(2 * B * T * r * 2 bytes of C_k and C_v per launch) over its launch duration measured
+with HIP events on the launch stream.  `cpu_baseline` times the fp64 oracle
+(reconstruct-then-attend definition form) on the host cores for a sample of the batch.
+"""
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+B, H, D, R, T0 = 64, 40, 128, 640, 4224
+HD = H * D
+HBM_PEAK_GBS = 8000.0
+
+
+def gpu_inputs(torch, t_cap, layers, seed=0):
+    """Coefficients kappa*sigma_j*g + 0.01*n (sigma_j = j^-0.7, unit-rms keys) and Gaussian
+    bases of orthonormal-row scale (timing does not depend on exact orthogonality)."""
+    from paper_2603_23914_amd import workloads as wl
+    g = torch.Generator(device="cuda")
+    g.manual_seed(seed)
+    ks = torch.tensor(wl.spectrum(R, HD), dtype=torch.float32, device="cuda")
+    out = []
+    for _ in range(layers):
+        lay = {}
+        for name in ("Ck", "Cv"):
+            c = torch.empty((B, t_cap, R), dtype=torch.bfloat16, device="cuda")
+            for b0 in range(0, B, 8):
+                x = torch.randn((8, t_cap, R), generator=g, device="cuda") * ks
+                x += 0.01 * torch.randn((8, t_cap, R), generator=g, device="cuda")
+                c[b0:b0 + 8] = x.to(torch.bfloat16)
+            lay[name] = c
+        for name in ("Bk", "Bv"):
+            bm = torch.empty((B, R, HD), dtype=torch.bfloat16, device="cuda")
+            for b0 in range(0, B, 8):
+                bm[b0:b0 + 8] = (torch.randn((8, R, HD), generator=g, device="cuda") / math.sqrt(HD)).to(torch.bfloat16)
+            lay[name] = bm
+        out.append(lay)
+    return out
+
+
+def run_steps(torch, ap, layers, q, knew, vnew, out, ws, t_start, nsteps):
+    """nsteps decode steps starting with T = t_start cached tokens."""
+    scale = 1.0 / math.sqrt(D)
+    for s in range(nsteps):
+        t = t_start + s
+        for lay in layers:
+            ap.ap_compact(knew, vnew, lay["Bk"], lay["Bv"], lay["Ck"], lay["Cv"], n=1, row0=t)
+            ap.ap_decode_attn(q, lay["Ck"], lay["Cv"], lay["Bk"], lay["Bv"], out, ws, T=t + 1, sm_scale=scale)
+
+
+def cpu_baseline(sample_seqs=8):
+    """The oracle as it stands (NumPy fp64, definition form) on `sample_seqs` of the 64
+    sequences for one decode step at T=4224; scaled to the batch."""
+    import numpy as np
+    import oracle
+    from paper_2603_23914_amd import workloads as wl
+    case = wl.decode_case("bf16", sample_seqs, H, D, R, T0, 0, seed=0, append=False)
+    P = lambda a: oracle.promote(a, "bf16")
+    q = P(wl.step_query(case, 0))
+    Ck, Cv, Bk, Bv = P(case.Ck), P(case.Cv), P(case.Bk), P(case.Bv)
+    t0 = time.perf_counter()
+    oracle.decode_attn_batched(q, Ck, Cv, Bk, Bv, T0)
+    dt = time.perf_counter() - t0
+    try:
+        cores = len(os.sched_getaffinity(0))
+    except AttributeError:
+        cores = os.cpu_count()
+    threads = int(os.environ.get("OMP_NUM_THREADS", cores))
+    return {"value": sample_seqs / dt, "unit": "tokens/s", "cores": min(cores, threads), "kind": "oracle",
+            "sample": f"{sample_seqs} of {B} sequences, one decode step at T={T0} (fp64 reconstruct-then-attend), "
+                      f"{dt:.1f} s; tokens/s = sequences/s"}
+
+
+def main():
+    ap_ = argparse.ArgumentParser()
+    ap_.add_argument("--gpus", type=int, default=1)
+    ap_.add_argument("--steps", type=int, default=64)
+    ap_.add_argument("--warmup", type=int, default=8)
+    ap_.add_argument("--layers", type=int, default=40, help="layers of the extra multi-layer measurement (0 = skip)")
+    ap_.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    args = ap_.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2603_23914_amd import binding as ap
+
+    torch.cuda.set_device(0)
+    K, W = args.steps, args.warmup
+    t_cap = T0 + W + K
+    layers1 = gpu_inputs(torch, t_cap, 1)
+    g = torch.Generator(device="cuda")
+    g.manual_seed(1)
+    q = torch.randn((B, H, D), generator=g, device="cuda").to(torch.bfloat16)
+    knew = torch.randn((B, 1, HD), generator=g, device="cuda").to(torch.bfloat16)
+    vnew = torch.randn((B, 1, HD), generator=g, device="cuda").to(torch.bfloat16)
+    out = torch.empty((B, H, D), dtype=torch.float32, device="cuda")
+    ws = torch.empty(ap.ap_decode_workspace_bytes(B, H, D, t_cap, R, ap.AP_BF16), dtype=torch.uint8, device="cuda")
+
+    # ---- one layer: warm-up, then EXACTLY K timed steps
+    run_steps(torch, ap, layers1, q, knew, vnew, out, ws, T0, W)
+    torch.cuda.synchronize()
+    ap.ap_prof_enable(True)
+    t0 = time.perf_counter()
+    run_steps(torch, ap, layers1, q, knew, vnew, out, ws, T0 + W, K)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    k_ms, k_n = ap.ap_prof_read()
+    ap.ap_prof_enable(False)
+    assert torch.isfinite(out).all()
+
+    ms_per_step = dt / K * 1e3
+    value = B * K / dt
+    # dominant kernel: attn_partial streams C_k and C_v rows 0..T-1 of every sequence once
+    t_mean = T0 + W + (K - 1) / 2.0 + 1
+    alg_bytes = 2.0 * B * t_mean * R * 2
+    k_avg_ms = k_ms / max(k_n, 1)
+    achieved = alg_bytes / (k_avg_ms * 1e-3) / 1e9 if k_n else None
+    traffic = None
+    tf = os.path.join(ROOT, "profiles", "attn_partial_c3_hbm_traffic.txt")
+    if os.path.exists(tf):
+        for line in open(tf):
+            if line.startswith("traffic_bytes_per_launch"):
+                traffic = float(line.split()[1])
+    roofline = {"bound": "hbm", "kernel": "attn_partial", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": (achieved / HBM_PEAK_GBS) if achieved else None, "traffic": traffic,
+                "kernel_avg_us": k_avg_ms * 1e3, "launches": k_n, "algorithmic_bytes_per_launch": alg_bytes}
+    # bytes the whole step must move (coefficients once; per-sequence B_k twice: append + fold,
+    # B_v twice: append + expansion; partials and vectors are small)
+    step_bytes = alg_bytes + 4.0 * B * R * HD * 2
+    extra = {"step_effective_GBps": step_bytes / (dt / K) / 1e9, "step_algorithmic_bytes": step_bytes}
+
+    # ---- optional: the same step over L independent layers back to back (distinct buffers,
+    #      so nothing survives in the 256 MB last-level cache between steps)
+    if args.layers > 1:
+        del layers1
+        torch.cuda.empty_cache()
+        kl = max(4, min(K, 16))
+        t_capl = T0 + 2 + kl
+        layersL = gpu_inputs(torch, t_capl, args.layers)
+        run_steps(torch, ap, layersL, q, knew, vnew, out, ws, T0, 2)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        run_steps(torch, ap, layersL, q, knew, vnew, out, ws, T0 + 2, kl)
+        torch.cuda.synchronize()
+        dtl = time.perf_counter() - t0
+        extra["multi_layer"] = {"layers": args.layers, "steps": kl, "ms_per_step": dtl / kl * 1e3,
+                                "model_tokens_per_s_attention_only": B * kl / dtl,
+                                "extrapolated_from_one_layer": value / args.layers}
+        del layersL
+        torch.cuda.empty_cache()
+
+    rec = {
+        "metric": "compressed-KV decode tokens/sec (one layer, attention path incl. append) and achieved HBM GB/s",
+        "value": value, "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "LLaVA-13B-shaped batch decode: B=64 H=40 d=128 T=4224(+1/step) r=640 bf16, "
+                               "per-sequence bases, fp32 accumulate/output",
+                   "global_batch": B, "seq_len": T0, "parallelism": "single-gpu"},
+        "roofline": roofline,
+    }
+    rec.update(extra)
+    if not args.no_cpu:
+        rec["cpu_baseline"] = cpu_baseline()
+    print(json.dumps(rec))
+
+
+if __name__ == "__main__":
+    main()

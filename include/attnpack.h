@@ -168,6 +168,19 @@ ap_status ap_decode_attn(const void* q, const void* Ck, const void* Cv,
 
 size_t ap_decode_workspace_bytes(int B, int H, int d, int T, int r, ap_dtype dt);
 
+/* ------------------------------------------------------------------------
+ * Timing of the dominant kernel (measurement aid, not part of the method).
+ * While enabled, every ap_decode_attn call on AP_F16 / AP_BF16 brackets its
+ * coefficient-streaming kernel with a pair of HIP events on the call's stream.
+ * ap_prof_read waits for the last recorded pair and returns the summed kernel
+ * time in milliseconds and the number of pairs since ap_prof_enable(1), which
+ * also clears the records.  At most 4096 launches are recorded (later ones are
+ * not timed).  Events are host-side handles owned by the library; no device
+ * memory is allocated.  Not thread-safe.
+ * ---------------------------------------------------------------------- */
+void ap_prof_enable(int on);
+ap_status ap_prof_read(float* total_ms, int* launches);
+
 /* Host strings; ap_last_error() is thread-local and describes the most recent
  * non-AP_OK return on the calling thread ("" if none). */
 const char* ap_status_string(ap_status s);

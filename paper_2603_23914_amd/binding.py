@@ -50,10 +50,14 @@ _lib.ap_last_error.restype = _c.c_char_p
 _lib.ap_last_error.argtypes = []
 _lib.ap_version.restype = _i
 _lib.ap_version.argtypes = []
+_lib.ap_prof_enable.restype = None
+_lib.ap_prof_enable.argtypes = [_i]
+_lib.ap_prof_read.restype = _i
+_lib.ap_prof_read.argtypes = [_c.POINTER(_c.c_float), _c.POINTER(_c.c_int)]
 
 EXPORTS = ("ap_compact", "ap_quantize_i8", "ap_select_ranks", "ap_select_workspace_bytes",
            "ap_decode_attn", "ap_decode_workspace_bytes", "ap_status_string", "ap_last_error",
-           "ap_version")
+           "ap_version", "ap_prof_enable", "ap_prof_read")
 
 _DT = {torch.float32: AP_F32, torch.float16: AP_F16, torch.bfloat16: AP_BF16, torch.int8: AP_I8}
 
@@ -150,6 +154,17 @@ def ap_decode_attn(q, Ck, Cv, Bk, Bv, out, workspace, *, T: int, sm_scale: float
                                float(sm_scale), _DT[q.dtype], _DT[Ck.dtype], _DT[out.dtype],
                                _p(workspace),
                                workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
+def ap_prof_enable(on: bool) -> None:
+    _lib.ap_prof_enable(1 if on else 0)
+
+
+def ap_prof_read():
+    """-> (summed milliseconds of the coefficient-streaming kernel, launches recorded)."""
+    ms, cnt = _c.c_float(0), _c.c_int(0)
+    _check(_lib.ap_prof_read(_c.byref(ms), _c.byref(cnt)))
+    return ms.value, cnt.value
 
 
 def raw():

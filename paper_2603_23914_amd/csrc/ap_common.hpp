@@ -124,4 +124,7 @@ ap_status launch_select_ranks(const float* mass, int B, int T, int F, const int3
 
 ap_status check_launch(const char* what);
 
+// dominant-kernel timing (api.hip): record an event on `stream` if profiling is on
+void prof_mark(hipStream_t stream, bool start);
+
 }  // namespace ap

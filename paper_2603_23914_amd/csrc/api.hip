@@ -4,6 +4,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <vector>
 
 namespace ap {
 
@@ -24,6 +25,23 @@ ap_status check_launch(const char* what) {
     return AP_ERR_HIP;
   }
   return AP_OK;
+}
+
+// ---- dominant-kernel timing ---------------------------------------------------------------
+static bool g_prof_on = false;
+static std::vector<hipEvent_t> g_prof_ev;   // start, stop, start, stop, ...
+static size_t g_prof_used = 0;
+constexpr size_t kProfMax = 2 * 4096;
+
+void prof_mark(hipStream_t stream, bool start) {
+  if (!g_prof_on) return;
+  if (start ? (g_prof_used + 2 > kProfMax) : (g_prof_used % 2 == 0)) return;
+  if (g_prof_used == g_prof_ev.size()) {
+    hipEvent_t e;
+    if (hipEventCreate(&e) != hipSuccess) return;
+    g_prof_ev.push_back(e);
+  }
+  (void)hipEventRecord(g_prof_ev[g_prof_used++], stream);
 }
 
 static bool half_type(ap_dtype dt) { return dt == AP_F16 || dt == AP_BF16; }
@@ -48,6 +66,32 @@ const char* ap_status_string(ap_status s) {
 const char* ap_last_error(void) { return g_err; }
 
 int ap_version(void) { return 100; }
+
+void ap_prof_enable(int on) {
+  g_prof_on = on != 0;
+  g_prof_used = 0;
+}
+
+ap_status ap_prof_read(float* total_ms, int* launches) {
+  clear_error();
+  AP_REQUIRE(total_ms && launches, AP_ERR_INVALID_ARG, "ap_prof_read: NULL pointer");
+  const size_t pairs = g_prof_used / 2;
+  float sum = 0.f;
+  if (pairs) {
+    hipError_t e = hipEventSynchronize(g_prof_ev[2 * pairs - 1]);
+    if (e != hipSuccess) {
+      set_error("ap_prof_read: %s", hipGetErrorString(e));
+      return AP_ERR_HIP;
+    }
+    for (size_t i = 0; i < pairs; ++i) {
+      float ms = 0.f;
+      if (hipEventElapsedTime(&ms, g_prof_ev[2 * i], g_prof_ev[2 * i + 1]) == hipSuccess) sum += ms;
+    }
+  }
+  *total_ms = sum;
+  *launches = (int)pairs;
+  return AP_OK;
+}
 
 // ---------------------------------------------------------------------------------------------
 ap_status ap_compact(const void* K, const void* V, const void* Bk, const void* Bv, void* Ck,

@@ -818,7 +818,9 @@ ap_status run_decode(const DecodeArgs& a) {
   AttnParams p{Qp, (const uint16_t*)a.Ck, (const uint16_t*)a.Cv, ml, U, a.T, a.T_cap, a.r, a.H, S, 0, 0, nullptr};
   if (const char* e = getenv("AP_DEBUG_ATTN")) p.dbg = atoi(e);
   p.dbg_out = (unsigned long long*)U;   // timers overwrite the head of part_U (debug only)
+  prof_mark(a.stream, true);
   ap_status st = dispatch_attn<Tag, SPLIT>(p, a.B, a.stream);
+  prof_mark(a.stream, false);
   if (st != AP_OK) return st;
   const int rows = 256 / (a.d / 8);
   const size_t lds = ((size_t)a.r + (size_t)rows * a.d) * 4;

@@ -1,7 +1,5 @@
 #include "ap_common.hpp"
 namespace ap {
-ap_status launch_compact(const CompactArgs&) { set_error("not built yet"); return AP_ERR_UNSUPPORTED; }
-ap_status launch_quantize_i8(const void*, void*, void*, int, int, int, int, hipStream_t) { set_error("not built yet"); return AP_ERR_UNSUPPORTED; }
 size_t select_workspace(int, int, int) { return 256; }
 ap_status launch_select_ranks(const float*, int, int, int, const int32_t*, const int32_t*, int32_t, int32_t*, int32_t*, int32_t*, void*, hipStream_t) { set_error("not built yet"); return AP_ERR_UNSUPPORTED; }
 }
