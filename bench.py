@@ -97,6 +97,8 @@ def main():
     ap_.add_argument("--warmup", type=int, default=8)
     ap_.add_argument("--layers", type=int, default=40, help="layers of the extra multi-layer measurement (0 = skip)")
     ap_.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap_.add_argument("--calib-copy", action="store_true",
+                     help="also run one plain 1 GiB device copy (reference for scaling rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     args = ap_.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
@@ -116,6 +118,13 @@ def main():
     vnew = torch.randn((B, 1, HD), generator=g, device="cuda").to(torch.bfloat16)
     out = torch.empty((B, H, D), dtype=torch.float32, device="cuda")
     ws = torch.empty(ap.ap_decode_workspace_bytes(B, H, D, t_cap, R, ap.AP_BF16), dtype=torch.uint8, device="cuda")
+
+    if args.calib_copy:
+        src = torch.zeros(1 << 30, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     # ---- one layer: warm-up, then EXACTLY K timed steps
     run_steps(torch, ap, layers1, q, knew, vnew, out, ws, T0, W)
