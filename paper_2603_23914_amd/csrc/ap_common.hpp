@@ -113,6 +113,8 @@ struct CompactArgs {
   hipStream_t stream;
 };
 ap_status launch_compact(const CompactArgs& a);
+bool compact_gemm_applies(const CompactArgs& a);       // matrix-core path (compact_gemm.hip)
+ap_status launch_compact_gemm(const CompactArgs& a);
 ap_status launch_quantize_i8(const void* C, void* codes, void* scales, int B, int T, int T_cap,
                              int r, hipStream_t stream);
 

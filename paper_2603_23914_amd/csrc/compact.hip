@@ -6,6 +6,8 @@
 //                  registers; each wave streams the basis rows of its 16 columns once with
 //                  128-bit loads, so appending one token (n = 1, the per-step case) reads
 //                  every basis byte exactly once: a bandwidth-bound matrix-vector product.
+//                  Row blocks of 32 and more tokens in 16-bit types go to the matrix-core
+//                  GEMM of compact_gemm.hip instead.
 //   quantize     : per token and per 64 columns, amax -> fp16 scale -> int8 codes, in the
 //                  exact fp32 / fp16 arithmetic the format prescribes.
 #include "ap_common.hpp"
@@ -183,6 +185,7 @@ ap_status run_compact(const CompactArgs& a) {
 }  // namespace
 
 ap_status launch_compact(const CompactArgs& a) {
+  if (compact_gemm_applies(a)) return launch_compact_gemm(a);
   AP_REQUIRE(a.B <= 65535 && (a.n + 3) / 4 <= 65535, AP_ERR_UNSUPPORTED,
              "ap_compact: B and n/4 must be <= 65535");
   switch (a.dt_in) {

@@ -1,0 +1,249 @@
+// Prefill compaction as a matrix-core GEMM (paper Sec. 3.1: Kbar = K D_k^T for given D_k).
+//
+//   C[b, row0 + t, j] = sum_c X[b, t, c] * Bm[b][j, c]         X [n, HD], Bm [r, HD], C [T_cap, r]
+//
+// Both operands are contiguous along the contraction axis, so tiles go HBM -> LDS with
+// direct-to-LDS 16-byte loads and come back out as MFMA operands with one ds_read_b128 each.
+// A workgroup (4 waves, 2 x 2) owns a 128-token x 128-column tile and walks the hidden axis
+// in blocks of 64 through a two-stage LDS ring; each wave holds a 64 x 64 accumulator as
+// 2 x 2 MFMA 32x32x16 tiles.  The LDS image of a tile is [row][8 chunks of 16 B] with the
+// chunk index XOR-ed by (row & 7): the loads pick their global source accordingly, and eight
+// consecutive rows of one chunk column then sit in eight different bank groups.
+// The MFMA computes the transposed tile (basis rows as the A operand), so a lane ends up with
+// four consecutive output columns of one token; the tile is rounded to the storage type,
+// staged in LDS and leaves in 16-byte row segments (or, for int8 output, as per-token
+// per-64-column codes and fp16 scales).
+// Workgroups are numbered so that the eight XCDs (round-robin over consecutive workgroup
+// ids) each work through their own run of (sequence, token tile) pairs with the column
+// tiles innermost: a token tile is fetched from HBM once and a sequence's basis stays in
+// that XCD's L2.
+#include "ap_common.hpp"
+
+namespace ap {
+namespace {
+
+constexpr int kBM = 128;   // tokens per tile
+constexpr int kBN = 128;   // output columns (basis rows) per tile
+constexpr int kBK = 64;    // hidden elements per stage
+constexpr int kStageBytes = (kBM + kBN) * kBK * 2;   // 32 KiB
+constexpr int kEpiPitch = kBN + 8;                   // 16-bit elements per staged output row
+
+template <class Tag> struct Mfma32;
+template <> struct Mfma32<F16Tag> {
+  static __device__ __forceinline__ f32x16_t run(u32x4_t a, u32x4_t b, f32x16_t c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8_t, a),
+                                                  __builtin_bit_cast(f16x8_t, b), c, 0, 0, 0);
+  }
+};
+template <> struct Mfma32<BF16Tag> {
+  static __device__ __forceinline__ f32x16_t run(u32x4_t a, u32x4_t b, f32x16_t c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a),
+                                                   __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
+  }
+};
+
+__device__ __forceinline__ void dma16(const void* gsrc, void* lds_uniform) {
+  __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gsrc,
+                                   (__attribute__((address_space(3))) void*)lds_uniform, 16, 0, 0);
+}
+
+struct GemmParams {
+  const uint16_t* X;
+  const uint16_t* Bm;
+  int64_t bstride;
+  void* C;
+  uint16_t* scale;
+  int n, row0, T_cap, HD, r, out_kind;
+  int MT, NT, G;            // token tiles, column tiles, workgroups in all
+};
+
+template <class Tag>
+__global__ void __launch_bounds__(256, 2) compact_gemm(const GemmParams p) {
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+  // XCD-aware numbering: consecutive workgroup ids go to different XCDs
+  const int per_xcd = (p.G + 7) >> 3;
+  const int logical = (int)(blockIdx.x & 7) * per_xcd + (int)(blockIdx.x >> 3);
+  if (logical >= p.G) return;
+  const int nt = logical % p.NT;
+  const int mt = (logical / p.NT) % p.MT;
+  const int b = logical / (p.NT * p.MT);
+  const int m0 = mt * kBM, n0 = nt * kBN;
+  const char* Xb = (const char*)(p.X + (size_t)b * p.n * p.HD);
+  const char* Bb = (const char*)(p.Bm + (size_t)b * p.bstride);
+
+  // ---- direct-to-LDS loads: per stage 16 KiB of X rows then 16 KiB of basis rows; wave w
+  //      issues 1-KiB blocks 4w .. 4w+3 of each.  Block j, lane i -> LDS chunk P = 64 j + i,
+  //      holding (row P>>3, hidden chunk (P&7) ^ (row&7)).
+  uint32_t srcA[4], srcB[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int P = (4 * w + i) * 64 + lane;
+    const int row = P >> 3, kc = (P & 7) ^ (row & 7);
+    int ra = m0 + row;  ra = ra < p.n ? ra : p.n - 1;        // rows past the end: finite duplicates
+    int rb = n0 + row;  rb = rb < p.r ? rb : p.r - 1;
+    srcA[i] = ((uint32_t)ra * (uint32_t)p.HD + (uint32_t)kc * 8u) * 2u;
+    srcB[i] = ((uint32_t)rb * (uint32_t)p.HD + (uint32_t)kc * 8u) * 2u;
+  }
+  auto issue = [&](int stage, int kb) {
+    char* sA = smem + stage * kStageBytes + (4 * w) * 1024;
+    char* sB = sA + kBM * kBK * 2;
+    const uint32_t koff = (uint32_t)kb * (kBK * 2);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) dma16(Xb + (srcA[i] + koff), sA + i * 1024);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) dma16(Bb + (srcB[i] + koff), sB + i * 1024);
+  };
+
+  // ---- MFMA operands: wave (wn, wm) owns columns 64 wn .. and tokens 64 wm ..; operand row
+  //      = lane & 31, hidden chunk of k-step ks = 2 ks + (lane >> 5)
+  const int wn = w & 1, wm = w >> 1;
+  const int orow = lane & 31, ohalf = lane >> 5;
+  uint32_t offN[2], offM[2], kx[4];
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    offN[i] = (uint32_t)(kBM * kBK * 2 + (wn * 64 + i * 32 + orow) * 128);
+    offM[i] = (uint32_t)((wm * 64 + i * 32 + orow) * 128);
+  }
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks) kx[ks] = (uint32_t)(((2 * ks + ohalf) ^ (orow & 7)) * 16);
+
+  f32x16_t acc[2][2];      // [column tile][token tile]
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+  const int nk = p.HD / kBK;
+  issue(0, 0);
+  for (int kb = 0; kb < nk; ++kb) {
+    if (kb + 1 < nk) {
+      issue((kb + 1) & 1, kb + 1);
+      asm volatile("s_waitcnt vmcnt(8)" ::: "memory");     // this wave's loads of block kb landed
+    } else {
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    }
+    __syncthreads();                                       // ... and every other wave's
+    const char* st = smem + (kb & 1) * kStageBytes;
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      u32x4_t fa[2], fb[2];
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        fa[i] = *(const u32x4_t*)(st + offN[i] + kx[ks]);
+        fb[i] = *(const u32x4_t*)(st + offM[i] + kx[ks]);
+      }
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) acc[i][j] = Mfma32<Tag>::run(fa[i], fb[j], acc[i][j]);
+    }
+    __syncthreads();                                       // stage may be overwritten next round
+  }
+
+  // ---- epilogue: round to the storage type, stage [token][column] in LDS
+  uint16_t* epi = (uint16_t*)smem;
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int blk = 0; blk < 4; ++blk) {
+        const int col = wn * 64 + i * 32 + 8 * blk + 4 * ohalf;
+        const int tok = wm * 64 + j * 32 + orow;
+        u32x2_t v;
+        v[0] = pack2(acc[i][j][4 * blk + 0], acc[i][j][4 * blk + 1], Tag{});
+        v[1] = pack2(acc[i][j][4 * blk + 2], acc[i][j][4 * blk + 3], Tag{});
+        *(u32x2_t*)(epi + tok * kEpiPitch + col) = v;
+      }
+  __syncthreads();
+  const int c8 = tid & 15;
+  const int col = n0 + c8 * 8;
+#pragma unroll 1
+  for (int pass = 0; pass < 8; ++pass) {
+    const int tok = pass * 16 + (tid >> 4);
+    const int t = m0 + tok;
+    const u32x4_t v = *(const u32x4_t*)(epi + tok * kEpiPitch + c8 * 8);
+    const bool live = t < p.n && col < p.r;
+    const size_t row = (size_t)b * p.T_cap + p.row0 + t;
+    if (p.out_kind == 0) {
+      if (live) *(u32x4_t*)((uint16_t*)p.C + row * p.r + col) = v;
+    } else {
+      // int8 format: amax over the 64-column block (8 lanes x 8 values), fp16 scale, codes
+      float x[8];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) { x[2 * e] = lo_to_f32(v[e], F16Tag{}); x[2 * e + 1] = hi_to_f32(v[e], F16Tag{}); }
+      float amax = 0.f;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) amax = fmaxf(amax, fabsf(x[e]));
+#pragma unroll
+      for (int o = 1; o < 8; o <<= 1) amax = fmaxf(amax, __shfl_xor(amax, o));
+      const _Float16 sh = (_Float16)(amax / 127.0f);       // IEEE divide, RNE to fp16
+      const float s = (float)sh;
+      uint32_t lo = 0, hi = 0;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        float q = 0.f;
+        if (s != 0.f) q = fminf(fmaxf(rintf(x[e] / s), -127.f), 127.f);
+        const uint32_t byte = (uint32_t)(int)q & 0xffu;
+        if (e < 4) lo |= byte << (8 * e); else hi |= byte << (8 * (e - 4));
+      }
+      if (live) {
+        u32x2_t cw = {lo, hi};
+        *(u32x2_t*)((int8_t*)p.C + row * p.r + col) = cw;
+        if ((c8 & 7) == 0) p.scale[row * (p.r / AP_QBLOCK) + (col >> 6)] = __builtin_bit_cast(uint16_t, sh);
+      }
+    }
+  }
+}
+
+template <class Tag>
+ap_status run_gemm(const CompactArgs& a) {
+  GemmParams p;
+  p.X = (const uint16_t*)a.X;
+  p.Bm = (const uint16_t*)a.Bm;
+  p.bstride = a.basis_batch_stride;
+  p.C = a.C;
+  p.scale = (uint16_t*)a.scale;
+  p.n = a.n; p.row0 = a.row0; p.T_cap = a.T_cap; p.HD = a.HD; p.r = a.r;
+  p.out_kind = a.dt_out == AP_I8 ? 1 : 0;
+  p.MT = (a.n + kBM - 1) / kBM;
+  p.NT = (a.r + kBN - 1) / kBN;
+  const int64_t G = (int64_t)a.B * p.MT * p.NT;
+  AP_REQUIRE(G <= (1 << 28), AP_ERR_UNSUPPORTED, "ap_compact: too many tiles");
+  p.G = (int)G;
+  const int grid = ((p.G + 7) / 8) * 8;
+  auto kern = compact_gemm<Tag>;
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       2 * kStageBytes);
+    if (e != hipSuccess) {
+      set_error("hipFuncSetAttribute: %s", hipGetErrorString(e));
+      return AP_ERR_HIP;
+    }
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(256), 2 * kStageBytes, a.stream, p);
+  return check_launch("ap_compact");
+}
+
+}  // namespace
+
+// The matrix-core path takes 16-bit inputs whose hidden axis is a multiple of 64 and whose
+// per-sequence byte offsets fit 32 bits; anything else stays on the row kernel.
+bool compact_gemm_applies(const CompactArgs& a) {
+  if (a.dt_in != AP_F16 && a.dt_in != AP_BF16) return false;
+  if (a.n < 32 || a.HD % kBK != 0 || a.r % 8 != 0) return false;
+  if ((int64_t)a.n * a.HD * 2 >= (1ll << 32) || (int64_t)a.r * a.HD * 2 >= (1ll << 32)) return false;
+  return true;
+}
+
+ap_status launch_compact_gemm(const CompactArgs& a) {
+  return a.dt_in == AP_F16 ? run_gemm<F16Tag>(a) : run_gemm<BF16Tag>(a);
+}
+
+}  // namespace ap

@@ -37,6 +37,11 @@ def run_compact(dtype, K, V, Bk, Bv, T_cap, row0, out_dtype=None):
     ("bf16", 2, 7, 1024, 192, True),      # ragged row block, shared basis
     ("f32", 1, 64, 128, 16, True),        # configuration 1 shape
     ("f16", 1, 37, 520, 80, False),       # hidden axis not a multiple of 512, r not of 64
+    # 32 and more rows with the hidden axis a multiple of 64: matrix-core GEMM tiles
+    ("f16", 2, 300, 1024, 192, False),    # ragged token tile, ragged column tile
+    ("bf16", 1, 129, 512, 640, True),
+    ("f16", 3, 128, 4096, 512, False),    # whole tiles, configuration 5's hidden axis and rank
+    ("bf16", 2, 32, 5120, 80, False),     # r not a multiple of 64
 ])
 def test_compact_projection(dtype, B, n, HD, r, shared):
     rng = wl.rng_for(11, n, HD)
@@ -77,9 +82,17 @@ def test_quantize_i8_bit_exact():
 
 def test_compact_to_int8_matches_quantized_projection():
     """ap_compact with int8 output == quantising its own fp16 projection (codes bit-exact)."""
+    _int8_vs_quantized_projection(2, 9, 1024, 128)
+
+
+def test_compact_gemm_to_int8_matches_quantized_projection():
+    """The same identity on the matrix-core path (n >= 32), ragged tiles included."""
+    _int8_vs_quantized_projection(2, 200, 1024, 192)
+
+
+def _int8_vs_quantized_projection(B, n, HD, r):
     from paper_2603_23914_amd import binding as ap
-    rng = wl.rng_for(13)
-    B, n, HD, r = 2, 9, 1024, 128
+    rng = wl.rng_for(13, n)
     K = wl.store(rng.standard_normal((B, n, HD)), "f16")
     V = wl.store(rng.standard_normal((B, n, HD)), "f16")
     Bk = wl.store(rng.standard_normal((B, r, HD)) / 32, "f16")
@@ -92,3 +105,30 @@ def test_compact_to_int8_matches_quantized_projection():
             rc, rs = oracle.quantize_i8(h[b])
             assert (C8[b].cpu().numpy() == rc).all()
             assert (s[b].cpu().numpy().view(np.uint16) == rs.view(np.uint16)).all()
+
+
+def test_config5_full_size_sampled():
+    """Configuration 5 at full size (T=4224, HD=4096, r=512, fp16 -> int8) in the launch shape
+    of the benchmark (B=16: two generated sequences, repeated): sampled token rows against the
+    fp64 projection, and the int8 codes / scales of those rows bit-exact against the oracle's
+    quantiser applied to the GPU's own fp16 projection."""
+    from paper_2603_23914_amd import binding as ap
+    T, HD, r, B = 4224, 4096, 512, 16
+    seqs = [wl.config5_sequence(b, seed=0, T=T, HD=HD, r=r) for b in range(2)]
+    print("config 5: inputs generated", flush=True)
+    K = np.stack([seqs[b % 2][0] for b in range(B)])
+    V = np.stack([seqs[b % 2][1] for b in range(B)])
+    Bk = np.stack([seqs[b % 2][2] for b in range(B)])
+    Bv = np.stack([seqs[b % 2][3] for b in range(B)])
+    C16k, C16v, _, _ = run_compact("f16", K, V, Bk, Bv, T, 0)
+    C8k, C8v, sk, sv = run_compact("f16", K, V, Bk, Bv, T, 0, out_dtype=torch.int8)
+    rows = np.unique(np.concatenate([[0, 1, 127, 128, 4095, 4096, T - 1], wl.rng_for(14).integers(0, T, 40)]))
+    for b in (0, 1, 7, 15):
+        for C16, C8, s, X, Bm in ((C16k, C8k, sk, K, Bk), (C16v, C8v, sv, V, Bv)):
+            ref = oracle.compact(X[b][rows].astype(np.float64), Bm[b].astype(np.float64))
+            got16 = C16[b].cpu().numpy()[rows]
+            err = np.abs(got16.astype(np.float64) - ref)
+            assert (err <= ROUND["f16"] * np.abs(ref) + 1e-5 * np.abs(ref).max()).all(), (b, err.max())
+            rc, rs = oracle.quantize_i8(got16)
+            assert (C8[b].cpu().numpy()[rows] == rc).all(), f"codes differ (b={b})"
+            assert (s[b].cpu().numpy()[rows].view(np.uint16) == rs.view(np.uint16)).all(), f"scales differ (b={b})"
