@@ -276,6 +276,13 @@ struct AttnParams {
   float* part_U;        // [B][S][H][r]
   int T, T_cap, r, H, nsplit;
   int nh;               // C_v LDS ring depth in 16-row units (even, >= 2)
+  // rank-ragged launches only: the group lists of ap_select_ranks and the per-token ranks
+  const int32_t* rank_k;      // [B][T] or null (= r)
+  const int32_t* rank_v;
+  const int32_t* bucket_off;  // [B][F+1]
+  const int32_t* bucket_idx;  // [B][T]
+  int F;
+  int ntl_cap;          // most tiles a split can own (sizes the LDS index table)
   int dbg;              // experiments: 1 = no loads, 2 = no math, 4 = phase timers
   unsigned long long* dbg_out;
 };
@@ -300,7 +307,14 @@ struct AttnParams {
 // it by more than kLazy, so the rescale factor is 1 on almost every tile.
 //
 // State every wave carries through the token loop, whatever its role.
-template <class Tag, int MT, bool SPLIT>
+// Rank-ragged launches (RAGGED): a tile is 32 tokens of ONE rank group, taken from the
+// group's index list, so the rank is uniform inside a tile and nothing diverges; tiles are
+// dealt to the splits round-robin (tile s, s + nsplit, ...), which gives every split the
+// same mix of ranks.  Each workgroup first copies the token indices of its tiles and each
+// tile's (token count, key rank, value rank) into LDS; the row loads then gather through
+// that table.  Columns at or beyond a tile's rank are neither fetched from HBM (their loads
+// are redirected to bytes the wave fetches anyway) nor allowed into the products.
+template <class Tag, int MT, bool SPLIT, bool RAGGED>
 struct WaveCtx {
   static constexpr int HPW = 2 * MT;     // heads finalised per wave
 
@@ -311,6 +325,8 @@ struct WaveCtx {
   f32x4_t* xchg;     // [4 score waves][16*MT heads][9]: 8 slots (4*tt+g) + 1 pad per head
   u32x4_t* Pbuf;     // [MT][hi,lo][64 lanes]
   float* abuf;       // [16*MT] rescale factors
+  int* idxb;         // RAGGED: [ntl][32] token index of every tile slot (tail slots repeat the last)
+  int* meta;         // RAGGED: [ntl][4] = tokens in the tile, key rank, value rank, unused
   uint32_t row_bytes;
   int t_lo, ntl;     // first tile and number of tiles of this split
   // softmax ownership: lane = 8*head_local + slot, slot = 4*tt + gg covers tokens
@@ -337,9 +353,15 @@ struct WaveCtx {
     Pbuf = (u32x4_t*)(xchg + 4 * 16 * MT * 9);
     abuf = (float*)(Pbuf + MT * 2 * 64);
     row_bytes = (uint32_t)r * 2u;
-    const int ntiles = (T + kTile - 1) / kTile;
-    t_lo = (int)(((int64_t)s * ntiles) / nsplit);
-    ntl = (int)(((int64_t)(s + 1) * ntiles) / nsplit) - t_lo;
+    if (!RAGGED) {
+      const int ntiles = (T + kTile - 1) / kTile;
+      t_lo = (int)(((int64_t)s * ntiles) / nsplit);
+      ntl = (int)(((int64_t)(s + 1) * ntiles) / nsplit) - t_lo;
+    } else {
+      idxb = (int*)(abuf + 16 * MT);
+      meta = idxb + uni(p.ntl_cap) * kTile;
+      build_tile_table(p);
+    }
     owner = lane < 8 * HPW;
     o_hh = w * HPW + (lane >> 3);
     o_tt = (lane >> 2) & 1; o_gg = lane & 3;
@@ -347,18 +369,76 @@ struct WaveCtx {
     m_ref = -INFINITY; l_part = 0.f;
   }
 
-  // Softmax of this wave's heads for the tile starting at token tok0 (after the score
-  // waves' partial tiles are in xchg).
-  __device__ __forceinline__ void finalize_softmax(int tok0) {
+  // RAGGED: tiles of this split, their token indices and ranks into LDS (all 512 threads).
+  __device__ __forceinline__ void build_tile_table(const AttnParams& p) {
+    const int F = uni(p.F);
+    const int32_t* boff = uni_ptr(p.bucket_off) + (size_t)b * (F + 1);
+    const int32_t* bidx = uni_ptr(p.bucket_idx) + (size_t)b * T;
+    const int32_t* rk_arr = uni_ptr(p.rank_k);
+    const int32_t* rv_arr = uni_ptr(p.rank_v);
+    int off[9], ts[9];                     // group g: list positions off[g]..off[g+1], first tile ts[g]
+    off[0] = boff[0];
+    ts[0] = 0;
+#pragma unroll
+    for (int g2 = 0; g2 < 8; ++g2) {
+      off[g2 + 1] = g2 < F ? boff[g2 + 1] : off[g2];
+      int c = off[g2 + 1] - off[g2];
+      c = c < 0 ? 0 : c;
+      ts[g2 + 1] = ts[g2] + ((c + kTile - 1) >> 5);
+    }
+    const int ntot = ts[8];
+    t_lo = 0;
+    ntl = s < ntot ? (ntot - s + nsplit - 1) / nsplit : 0;
+    const int cap = uni(p.ntl_cap);
+    ntl = ntl < cap ? ntl : cap;           // never beyond the table (host sizes it for the worst case)
+    for (int e = threadIdx.x; e < ntl * kTile; e += 512) {
+      const int i = e >> 5, l = e & 31;
+      const int j = s + i * nsplit;
+      int o0 = off[0], o1 = off[1], t0 = 0;
+#pragma unroll
+      for (int k = 1; k < 8; ++k)
+        if (k < F && j >= ts[k]) { o0 = off[k]; o1 = off[k + 1]; t0 = ts[k]; }
+      const int pos0 = o0 + (j - t0) * kTile;
+      int cnt = o1 - pos0;
+      cnt = cnt > kTile ? kTile : cnt;
+      int pos = pos0 + (l < cnt ? l : cnt - 1);
+      pos = pos < 0 ? 0 : (pos < T ? pos : T - 1);
+      int tok = bidx[pos];
+      tok = tok < 0 ? 0 : (tok < T ? tok : T - 1);
+      idxb[e] = tok;
+      if (l == 0) {
+        int rk = rk_arr ? rk_arr[(size_t)b * T + tok] : r;
+        int rv = rv_arr ? rv_arr[(size_t)b * T + tok] : r;
+        rk = rk < 0 ? 0 : (rk < r ? rk : r);
+        rv = rv < 0 ? 0 : (rv < r ? rv : r);
+        meta[4 * i + 0] = cnt;
+        meta[4 * i + 1] = rk;
+        meta[4 * i + 2] = rv;
+        meta[4 * i + 3] = 0;
+      }
+    }
+    wg_barrier();
+  }
+
+  // Tokens of local tile t that exist (the rest of the 32 slots is masked out of the softmax).
+  __device__ __forceinline__ int tile_valid(int t) const {
+    if (RAGGED) return uni(meta[4 * t]);
+    const int left = T - (t_lo + t) * kTile;
+    return left < kTile ? left : kTile;
+  }
+
+  // Softmax of this wave's heads for a tile whose first `valid` slots hold tokens (after
+  // the score waves' partial tiles are in xchg).
+  __device__ __forceinline__ void finalize_softmax(int valid) {
     if (!owner) return;
     const int xi = o_hh * 9 + (lane & 7);
     f32x4_t sc = xchg[xi];
 #pragma unroll
     for (int sw = 1; sw < 4; ++sw) sc += xchg[sw * 16 * MT * 9 + xi];
-    if (tok0 + kTile > T) {
+    if (valid < kTile) {
 #pragma unroll
       for (int i = 0; i < 4; ++i)
-        if (tok0 + 16 * o_tt + 4 * o_gg + i >= T) sc[i] = -INFINITY;
+        if (16 * o_tt + 4 * o_gg + i >= valid) sc[i] = -INFINITY;
     }
     float tmax = fmaxf(fmaxf(sc[0], sc[1]), fmaxf(sc[2], sc[3]));
     tmax = max8(tmax);
@@ -414,12 +494,12 @@ struct WaveCtx {
   }
 };
 
-template <class Tag, int MT, int RMAX, bool SPLIT>
+template <class Tag, int MT, int RMAX, bool SPLIT, bool RAGGED>
 __device__ __noinline__ void score_role(const AttnParams& p) {
   constexpr int NKW = (RMAX / 32 + 3) / 4;                // score k-steps per score wave
   constexpr int Hp = MT * 16;
   const unsigned long long t_entry_ = __builtin_readcyclecounter();
-  WaveCtx<Tag, MT, SPLIT> cx;
+  WaveCtx<Tag, MT, SPLIT, RAGGED> cx;
   cx.init(p);
   float* part_U = uni_ptr(p.part_U);
   float* part_ml = uni_ptr(p.part_ml);
@@ -456,18 +536,33 @@ __device__ __noinline__ void score_role(const AttnParams& p) {
   uint32_t koff[NKW];
 #pragma unroll
   for (int i = 0; i < NKW; ++i) koff[i] = i < my_nks ? (uint32_t)i * 256u : 0u;
-  auto load_A = [&](int tile) {
+  auto load_A = [&](int tile) {                           // tile: local index in this split
     if (cx.dbg & 1) return;
+    if (!RAGGED) {
 #pragma unroll
-    for (int tt = 0; tt < 2; ++tt) {
-      int row = tile * kTile + 16 * tt + n;
-      row = row < T ? row : T - 1;                        // rows beyond T are masked later
-      const char* rp = Ck_b + ((uint32_t)row * cx.row_bytes + lane_off);
+      for (int tt = 0; tt < 2; ++tt) {
+        int row = (cx.t_lo + tile) * kTile + 16 * tt + n;
+        row = row < T ? row : T - 1;                      // rows beyond T are masked later
+        const char* rp = Ck_b + ((uint32_t)row * cx.row_bytes + lane_off);
 #pragma unroll
-      for (int i = 0; i < NKW; ++i) A[i][tt] = *(const u32x4_t*)(rp + koff[i]);
+        for (int i = 0; i < NKW; ++i) A[i][tt] = *(const u32x4_t*)(rp + koff[i]);
+      }
+    } else {
+      // gathered rows; k-steps at or beyond the tile's key rank re-read bytes this wave
+      // (or, with no k-step left, its neighbours) fetch anyway
+      const int nks_t = uni(cx.meta[4 * tile + 1]) >> 5;
+      const uint32_t loff = (uint32_t)((w < nks_t ? w * 64 : 0) + g * 16);
+#pragma unroll
+      for (int tt = 0; tt < 2; ++tt) {
+        const int row = cx.idxb[tile * kTile + 16 * tt + n];
+        const char* rp = Ck_b + ((uint32_t)row * cx.row_bytes + loff);
+#pragma unroll
+        for (int i = 0; i < NKW; ++i)
+          A[i][tt] = *(const u32x4_t*)(rp + ((w + 4 * i) < nks_t ? (uint32_t)i * 256u : 0u));
+      }
     }
   };
-  if (cx.ntl > 0) load_A(cx.t_lo);
+  if (cx.ntl > 0) load_A(0);
 
   unsigned long long tm[8] = {0, 0, 0, 0, 0, 0, 0, 0};
 #define AP_TICK(k) { const unsigned long long now_ = __builtin_readcyclecounter(); tm[k] += now_ - t0_; t0_ = now_; }
@@ -477,9 +572,15 @@ __device__ __noinline__ void score_role(const AttnParams& p) {
     f32x4_t sp[MT][2];
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) { f32x4_t z = {0.f, 0.f, 0.f, 0.f}; sp[mt][0] = z; sp[mt][1] = z; }
+    if (RAGGED) {                                         // columns beyond the key rank count as zero
+      const int nks_t = uni(cx.meta[4 * t + 1]) >> 5;
+#pragma unroll
+      for (int i = 0; i < NKW; ++i)
+        if ((w + 4 * i) >= nks_t) { u32x4_t z = {0, 0, 0, 0}; A[i][0] = z; A[i][1] = z; }
+    }
     if (!(cx.dbg & 2)) score_tile<Tag, MT, SPLIT, NKW>(A, qhi, qlo, sp);
     AP_TICK(1)
-    if (t + 1 < cx.ntl) load_A(cx.t_lo + t + 1);          // lands while the tile is finished
+    if (t + 1 < cx.ntl) load_A(t + 1);                    // lands while the tile is finished
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
       cx.xchg[(w * 16 * MT + mt * 16 + n) * 9 + g] = sp[mt][0];
@@ -487,7 +588,7 @@ __device__ __noinline__ void score_role(const AttnParams& p) {
     }
     wg_barrier();                                         // partial scores of tile t ready
     AP_TICK(2)
-    cx.finalize_softmax((cx.t_lo + t) * kTile);
+    cx.finalize_softmax(cx.tile_valid(t));
     AP_TICK(3)
     wg_barrier();                                         // weights of tile t ready
     AP_TICK(4)
@@ -507,13 +608,13 @@ __device__ __noinline__ void score_role(const AttnParams& p) {
   }
 }
 
-template <class Tag, int MT, int RMAX, bool SPLIT>
+template <class Tag, int MT, int RMAX, bool SPLIT, bool RAGGED>
 __device__ __noinline__ void sum_role(const AttnParams& p) {
   constexpr int NGRP = (RMAX + 127) / 128;                        // 128-column groups
   constexpr int MAXBLK = (kHalf * (RMAX / 8 + 1) + 63) / 64;      // 1 KiB blocks per ring unit
   constexpr int NSLOT = (MAXBLK + 3) / 4;
   const unsigned long long t_entry_ = __builtin_readcyclecounter();
-  WaveCtx<Tag, MT, SPLIT> cx;
+  WaveCtx<Tag, MT, SPLIT, RAGGED> cx;
   cx.init(p);
   float* part_U = uni_ptr(p.part_U);
   float* part_ml = uni_ptr(p.part_ml);
@@ -527,8 +628,9 @@ __device__ __noinline__ void sum_role(const AttnParams& p) {
   const int tot_chunks = kHalf * (cpr + 1);
   uint32_t slot_off[NSLOT];
   uint32_t slot_row[(NSLOT + 3) / 4];
+  uint32_t slot_chk[(NSLOT + 3) / 4];                     // RAGGED: chunk index of every slot
 #pragma unroll
-  for (int k = 0; k < (NSLOT + 3) / 4; ++k) slot_row[k] = 0;
+  for (int k = 0; k < (NSLOT + 3) / 4; ++k) { slot_row[k] = 0; slot_chk[k] = 0; }
   int n_issue = 0;
 #pragma unroll
   for (int k = 0; k < NSLOT; ++k) {
@@ -543,6 +645,7 @@ __device__ __noinline__ void sum_role(const AttnParams& p) {
       if (c == cpr) c = 0;                        // pad chunk: harmless duplicate
       slot_off[k] = (uint32_t)row * cx.row_bytes + (uint32_t)(c * 16);
       slot_row[k >> 2] |= (uint32_t)row << (8 * (k & 3));
+      slot_chk[k >> 2] |= (uint32_t)c << (8 * (k & 3));
     }
   }
   const char* Cv_b = (const char*)(uni_ptr(p.Cv) + (size_t)cx.b * uni(p.T_cap) * r);
@@ -550,6 +653,26 @@ __device__ __noinline__ void sum_role(const AttnParams& p) {
   auto issue_tile = [&](int lt) {
     if (cx.dbg & 1) return;
     const int slot0 = 2 * (lt % RT);
+    if (RAGGED) {
+      // gathered rows; chunks at or beyond the tile's value rank re-read the row's first chunk
+      const uint32_t rv8 = (uint32_t)uni(cx.meta[4 * lt + 2]) >> 3;
+#pragma nounroll
+      for (int half = 0; half < 2; ++half) {
+        char* dst = cx.ring + (slot0 + half) * cx.unit_bytes;
+        const int* ix = cx.idxb + lt * kTile + half * kHalf;
+#pragma unroll
+        for (int k = 0; k < NSLOT; ++k) {
+          const int blk = cp + 4 * k;
+          if (blk < cx.nblk) {
+            const int row = (int)((slot_row[k >> 2] >> (8 * (k & 3))) & 0xffu);
+            const uint32_t c = (slot_chk[k >> 2] >> (8 * (k & 3))) & 0xffu;
+            const uint32_t off = (uint32_t)ix[row] * cx.row_bytes + (c < rv8 ? c * 16u : 0u);
+            dma16(Cv_b + off, dst + blk * 1024);
+          }
+        }
+      }
+      return;
+    }
 #pragma nounroll
     for (int half = 0; half < 2; ++half) {
       const int tok_u = (cx.t_lo + lt) * kTile + half * kHalf;
@@ -592,7 +715,7 @@ __device__ __noinline__ void sum_role(const AttnParams& p) {
     wg_barrier();            // partial scores of tile t ready; every sum wave is past tile t-1
     AP_TICK(2)
     if (t >= 1 && t - 1 + RT < cx.ntl) issue_tile(t - 1 + RT);   // refill tile t-1's slots
-    cx.finalize_softmax((cx.t_lo + t) * kTile);
+    cx.finalize_softmax(cx.tile_valid(t));
     AP_TICK(3)
     {
       // tile t's rows must have landed; the tiles issued after it may stay in flight
@@ -616,7 +739,9 @@ __device__ __noinline__ void sum_role(const AttnParams& p) {
     const char* vA = cx.ring + slot0 * cx.unit_bytes + (4 * g) * cx.pitch + cp * 64 + n * 4;
     const char* vB = vA + cx.unit_bytes;
     if (!(cx.dbg & 2))
-      wsum_tile<Tag, MT, SPLIT, NGRP>(vA, vB, cx.pitch, r - cp * 32, n, Phi, Plo, alpha, U);
+      wsum_tile<Tag, MT, SPLIT, NGRP>(vA, vB, cx.pitch,
+                                      (RAGGED ? uni(cx.meta[4 * t + 2]) : r) - cp * 32, n, Phi, Plo,
+                                      alpha, U);
     AP_TICK(5)
   }
   // U of this split.  U[i][j][mt][e] is element (head 16mt+n, column 128i + 32cp + 8g +
@@ -646,13 +771,13 @@ __device__ __noinline__ void sum_role(const AttnParams& p) {
 }
 #undef AP_TICK
 
-template <class Tag, int MT, int RMAX, bool SPLIT>
+template <class Tag, int MT, int RMAX, bool SPLIT, bool RAGGED>
 __global__ void __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2)))
 attn_partial(const AttnParams p) {
   if (__builtin_amdgcn_readfirstlane(threadIdx.x >> 6) < 4)
-    score_role<Tag, MT, RMAX, SPLIT>(p);
+    score_role<Tag, MT, RMAX, SPLIT, RAGGED>(p);
   else
-    sum_role<Tag, MT, RMAX, SPLIT>(p);
+    sum_role<Tag, MT, RMAX, SPLIT, RAGGED>(p);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -732,9 +857,14 @@ int device_cus() {
 // Splits of the token axis: enough workgroups to cover every CU once, never finer
 // than one 32-token tile.  The count does not depend on the device, so the workspace
 // query needs no GPU.
+constexpr int kMaxTilesPerSplit = 128;   // bounds the LDS index table of rank-ragged launches
+constexpr int kMaxGroups = 8;
+
 int choose_nsplit(int B, int T) {
   const int ntiles = (T + kTile - 1) / kTile;
   int s = (256 + B - 1) / B;
+  const int by_table = (ntiles + kMaxGroups + kMaxTilesPerSplit - 1) / kMaxTilesPerSplit;
+  if (s < by_table) s = by_table;
   if (s > ntiles) s = ntiles;
   if (s < 1) s = 1;
   return s;
@@ -757,22 +887,28 @@ WsLayout ws_layout(int B, int H, int T, int r) {
   return w;
 }
 
-template <class Tag, int MT, int RMAX, bool SPLIT>
+template <class Tag, int MT, int RMAX, bool SPLIT, bool RAGGED>
 ap_status launch_attn(AttnParams p, int B, hipStream_t stream) {
   const int cpr = p.r / 8;
   const size_t unit = (size_t)((kHalf * (cpr + 1) + 63) / 64) * 1024;
-  const size_t fixed = (size_t)4 * 16 * MT * 9 * 16 + (size_t)MT * 2 * 64 * 16 + (size_t)MT * 16 * 4;
+  size_t fixed = (size_t)4 * 16 * MT * 9 * 16 + (size_t)MT * 2 * 64 * 16 + (size_t)MT * 16 * 4;
+  if (RAGGED) {
+    // every group may end in a partial tile; tiles are dealt round-robin to the splits
+    const int ntiles_max = (p.T + kTile - 1) / kTile + p.F;
+    p.ntl_cap = (ntiles_max + p.nsplit - 1) / p.nsplit;
+    fixed += (size_t)p.ntl_cap * (kTile + 4) * 4;
+  }
   const size_t budget = 160 * 1024;
+  AP_REQUIRE(fixed + 2 * unit <= budget, AP_ERR_UNSUPPORTED,
+             "ap_decode_attn: H=%d r=%d needs more LDS than 160 KiB", p.H, p.r);
   int nh = (int)((budget - fixed) / unit);
   if (nh > 12) nh = 12;
   nh &= ~1;
-  AP_REQUIRE(nh >= 2, AP_ERR_UNSUPPORTED, "ap_decode_attn: H=%d r=%d needs more LDS than 160 KiB",
-             p.H, p.r);
   p.nh = nh;
   size_t lds = (size_t)nh * unit + fixed;
   const size_t epi = (size_t)16 * (p.r + 1) * 4;
   if (epi > lds) lds = epi;
-  auto kern = attn_partial<Tag, MT, RMAX, SPLIT>;
+  auto kern = attn_partial<Tag, MT, RMAX, SPLIT, RAGGED>;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -790,11 +926,15 @@ ap_status launch_attn(AttnParams p, int B, hipStream_t stream) {
 template <class Tag, bool SPLIT>
 ap_status dispatch_attn(const AttnParams& p, int B, hipStream_t stream) {
   const int nw = (p.H + 15) / 16;
-#define AP_CASE(NWV)                                                              \
-  case NWV:                                                                       \
-    return p.r <= 256   ? launch_attn<Tag, NWV, 256, SPLIT>(p, B, stream)         \
-           : p.r <= 512 ? launch_attn<Tag, NWV, 512, SPLIT>(p, B, stream)         \
-                        : launch_attn<Tag, NWV, 640, SPLIT>(p, B, stream);
+#define AP_CASE(NWV)                                                                  \
+  case NWV:                                                                           \
+    if (p.bucket_idx)                                                                 \
+      return p.r <= 256   ? launch_attn<Tag, NWV, 256, SPLIT, true>(p, B, stream)     \
+             : p.r <= 512 ? launch_attn<Tag, NWV, 512, SPLIT, true>(p, B, stream)     \
+                          : launch_attn<Tag, NWV, 640, SPLIT, true>(p, B, stream);    \
+    return p.r <= 256   ? launch_attn<Tag, NWV, 256, SPLIT, false>(p, B, stream)      \
+           : p.r <= 512 ? launch_attn<Tag, NWV, 512, SPLIT, false>(p, B, stream)      \
+                        : launch_attn<Tag, NWV, 640, SPLIT, false>(p, B, stream);
   switch (nw) {
     AP_CASE(1) AP_CASE(2) AP_CASE(3) AP_CASE(4)
   }
@@ -815,7 +955,20 @@ ap_status run_decode(const DecodeArgs& a) {
   hipLaunchKernelGGL(fold_query<Tag>, dim3(Hp, a.B), dim3(256), 0, a.stream, (const uint16_t*)a.q,
                      (const uint16_t*)a.Bk, a.basis_batch_stride, Qp, a.H, Hp, a.d, a.r,
                      a.sm_scale * kLog2e);
-  AttnParams p{Qp, (const uint16_t*)a.Ck, (const uint16_t*)a.Cv, ml, U, a.T, a.T_cap, a.r, a.H, S, 0, 0, nullptr};
+  AttnParams p{};
+  p.Qp = Qp;
+  p.Ck = (const uint16_t*)a.Ck;
+  p.Cv = (const uint16_t*)a.Cv;
+  p.part_ml = ml;
+  p.part_U = U;
+  p.T = a.T; p.T_cap = a.T_cap; p.r = a.r; p.H = a.H; p.nsplit = S;
+  if (a.rank_k || a.rank_v) {             // rank-ragged: walk the group lists
+    p.rank_k = a.rank_k;
+    p.rank_v = a.rank_v;
+    p.bucket_off = a.bucket_off;
+    p.bucket_idx = a.bucket_idx;
+    p.F = a.F;
+  }
   if (const char* e = getenv("AP_DEBUG_ATTN")) p.dbg = atoi(e);
   p.dbg_out = (unsigned long long*)U;   // timers overwrite the head of part_U (debug only)
   prof_mark(a.stream, true);
@@ -844,7 +997,8 @@ size_t decode_mfma_workspace(int B, int H, int d, int T, int r, ap_dtype dt) {
 ap_status launch_decode_mfma(const DecodeArgs& a) {
   AP_REQUIRE(a.B <= 65535, AP_ERR_UNSUPPORTED, "ap_decode_attn: B must be <= 65535");
   AP_REQUIRE(a.dt_coef != AP_I8, AP_ERR_UNSUPPORTED, "ap_decode_attn: int8 coefficients not built yet");
-  AP_REQUIRE(!a.rank_k && !a.rank_v, AP_ERR_UNSUPPORTED, "ap_decode_attn: ragged ranks not built yet");
+  AP_REQUIRE((int64_t)a.T_cap * a.r * 2 < (1ll << 32), AP_ERR_UNSUPPORTED,
+             "ap_decode_attn: one sequence's coefficients must stay below 4 GiB");
   return a.dt == AP_F16 ? run_decode<F16Tag, false>(a) : run_decode<BF16Tag, true>(a);
 }
 

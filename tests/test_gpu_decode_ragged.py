@@ -1,0 +1,117 @@
+"""GPU parity: rank-ragged decode attention (per-token ranks from attention-aware groups)
+against the fp64 oracle, and the configuration-4 workload at full size."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2603_23914_amd import workloads as wl
+from gpu_util import TORCH_DT, assert_close, to_dev, to_host64, workspace
+
+pytestmark = pytest.mark.gpu
+
+
+def gpu_select(mass, group_rank, cum_num, den):
+    """Rank groups on the GPU (checked against the oracle before use)."""
+    from paper_2603_23914_amd import binding as ap
+    B, T = mass.shape
+    F = len(group_rank)
+    dm = torch.from_numpy(np.ascontiguousarray(mass, dtype=np.float32)).cuda()
+    rank = torch.empty((B, T), dtype=torch.int32, device="cuda")
+    off = torch.empty((B, F + 1), dtype=torch.int32, device="cuda")
+    idx = torch.empty((B, T), dtype=torch.int32, device="cuda")
+    ap.ap_select_ranks(dm, group_rank, cum_num, den, rank, off, idx,
+                       workspace(ap.ap_select_workspace_bytes(B, T, F)))
+    torch.cuda.synchronize()
+    for b in range(B):
+        r_ref, o_ref, i_ref = oracle.select_ranks(mass[b], group_rank, cum_num, den)
+        assert (rank[b].cpu().numpy() == r_ref).all() and (off[b].cpu().numpy() == o_ref).all()
+        assert (idx[b].cpu().numpy() == i_ref).all()
+    return rank, off, idx
+
+
+def run_ragged(dtype, case, q, T, rank, off, idx, F, use_k=True, use_v=True):
+    from paper_2603_23914_amd import binding as ap
+    B, H, d = q.shape
+    dq, dCk, dCv, dBk, dBv = (to_dev(x, dtype) for x in (q, case.Ck, case.Cv, case.Bk, case.Bv))
+    out = torch.empty((B, H, d), dtype=torch.float32, device="cuda")
+    ws = workspace(ap.ap_decode_workspace_bytes(B, H, d, T, case.r, ap._DT[TORCH_DT[dtype]]))
+    ap.ap_decode_attn(dq, dCk, dCv, dBk, dBv, out, ws, T=T, sm_scale=1.0 / math.sqrt(d),
+                      rank_k=rank if use_k else None, rank_v=rank if use_v else None,
+                      bucket_off=off, bucket_idx=idx, F=F)
+    torch.cuda.synchronize()
+    return to_host64(out)
+
+
+def oracle_ragged(dtype, case, q, T, rank_np, use_k=True, use_v=True, absorbed=True):
+    P = lambda x: oracle.promote(x, dtype)
+    return oracle.decode_attn_batched(P(q), P(case.Ck), P(case.Cv), P(case.Bk), P(case.Bv), T,
+                                      rank_k=rank_np if use_k else None,
+                                      rank_v=rank_np if use_v else None, absorbed=absorbed)
+
+
+CASES = [
+    # dtype, B, H,  d,   r,   T,  group ranks,           cum_num,      den
+    ("f16", 2, 32, 128, 512, 333, (512, 256, 128, 64), (1, 2, 3, 4), 4),
+    ("bf16", 2, 40, 128, 640, 301, (640, 320, 64), (1, 3, 8), 8),
+    ("f16", 1, 8, 64, 128, 97, (128, 64), (1, 10), 10),          # paper-style two groups
+    ("bf16", 1, 24, 64, 192, 200, (192, 128, 64), (0, 1, 2), 2),  # empty first group
+    ("f16", 3, 16, 128, 256, 20, (256, 64), (1, 2), 2),           # fewer tokens than a tile
+    ("f16", 1, 32, 128, 512, 1000, (512, 448, 384, 320, 256, 192, 128, 64), (1, 2, 3, 4, 5, 6, 7, 8), 8),
+]
+
+
+@pytest.mark.parametrize("dtype,B,H,d,r,T,granks,cum,den", CASES)
+def test_decode_ragged_small(dtype, B, H, d, r, T, granks, cum, den):
+    case = wl.decode_case(dtype, B, H, d, r, T, steps=0, seed=9, append=False)
+    q = wl.step_query(case, 0)
+    mass = wl.rng_for(9, T, r).random((B, T)).astype(np.float32)
+    print(f"ragged {dtype} B={B} H={H} d={d} r={r} T={T} ranks={granks}", flush=True)
+    rank, off, idx = gpu_select(mass, granks, cum, den)
+    rank_np = rank.cpu().numpy()
+    ref = oracle_ragged(dtype, case, q, T, rank_np)
+    if T <= 333:   # the reconstruct-then-attend definition agrees with the absorbed form here
+        ref_def = oracle_ragged(dtype, case, q, T, rank_np, absorbed=False)
+        assert np.abs(ref_def - ref).max() < 1e-9
+    got = run_ragged(dtype, case, q, T, rank, off, idx, len(granks))
+    rel = assert_close(got, ref, dtype, "ragged k+v")
+    print(f"  k+v ragged: max|err|/||out||inf = {rel:.2e}", flush=True)
+    # value ranks only (the paper's main setting) and key ranks only
+    for use_k, use_v in ((False, True), (True, False)):
+        ref1 = oracle_ragged(dtype, case, q, T, rank_np, use_k, use_v)
+        got1 = run_ragged(dtype, case, q, T, rank, off, idx, len(granks), use_k, use_v)
+        assert_close(got1, ref1, dtype, f"ragged k={use_k} v={use_v}")
+    # the truncation matters on this input (otherwise the test could not see a missing mask)
+    full = oracle_ragged(dtype, case, q, T, None)
+    assert np.abs(full - ref).max() > 1e-2 * np.abs(ref).max()
+
+
+def test_ragged_all_full_rank_equals_uniform():
+    """Every group at rank r: the gathered path must give the uniform path's result."""
+    dtype, B, H, d, r, T = "f16", 2, 32, 128, 512, 300
+    case = wl.decode_case(dtype, B, H, d, r, T, steps=0, seed=4, append=False)
+    q = wl.step_query(case, 0)
+    mass = wl.rng_for(4).random((B, T)).astype(np.float32)
+    rank, off, idx = gpu_select(mass, (512, 512), (1, 2), 2)
+    got = run_ragged(dtype, case, q, T, rank, off, idx, 2)
+    ref = oracle_ragged(dtype, case, q, T, None)
+    assert_close(got, ref, dtype, "all groups at full rank")
+
+
+def test_config4_full_size():
+    """Configuration 4 at full size: B=1, H=32, d=128, T=32768, ranks {512,256,128,64} by
+    quartile of a Zipf attention mass; steps either side of a re-selection."""
+    case = wl.config4(seed=0)
+    T = case.T0
+    print("config 4: inputs generated", flush=True)
+    for step in (0, 31, 32, 127):
+        epoch = step // wl.C4_RESELECT_EVERY
+        mass = wl.config4_mass(T, 0, epoch)[None, :]
+        rank, off, idx = gpu_select(mass, wl.C4_GROUP_RANK, wl.C4_CUM_NUM, wl.C4_DEN)
+        q = wl.step_query(case, step)
+        got = run_ragged("f16", case, q, T, rank, off, idx, 4)
+        ref = oracle_ragged("f16", case, q, T, rank.cpu().numpy())
+        rel = assert_close(got, ref, "f16", f"config 4 step {step}")
+        print(f"  step {step}: max|err|/||out||inf = {rel:.2e}", flush=True)
