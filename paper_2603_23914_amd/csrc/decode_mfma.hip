@@ -21,6 +21,9 @@
 //                                         (v_perm), B = P read back in operand layout
 // For bf16 storage q' and P are split into hi+lo bf16 pairs (two MFMAs) so that the
 // operand rounding stays far inside the 2e-3 tolerance; fp16 needs no split.
+// int8 coefficients (one fp16 scale per token per 64 columns) travel as bytes and are
+// turned into fp16 values code*scale in registers, right in front of the MFMA that uses
+// them; everything else is the fp16 path.
 #include "ap_common.hpp"
 
 #include <cstdlib>
@@ -97,6 +100,27 @@ __device__ __forceinline__ uint32_t cvt_pack(float lo, float hi, BF16Tag) {
 __device__ __forceinline__ uint32_t cvt_pack(float lo, float hi, F16Tag) {
   f32x2_t v = {lo, hi};
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, f16x2_t));
+}
+
+// int8 codes -> fp16 values code*scale, two at a time.  A byte b (two's complement) xor 0x80
+// is b+128 as an unsigned byte u; the fp16 bit pattern 0x6400|u is exactly 1024+u, so
+// subtracting 1152 leaves b exactly, and the product with the scale is rounded once.
+typedef _Float16 h2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t deq2(uint32_t biased /* 0x64uu64uu */, uint32_t scale2) {
+  const h2_t off = {(_Float16)-1152.0f, (_Float16)-1152.0f};
+  const h2_t v = (__builtin_bit_cast(h2_t, biased) + off) * __builtin_bit_cast(h2_t, scale2);
+  return __builtin_bit_cast(uint32_t, v);
+}
+// 8 consecutive codes of one row (two dwords) times one scale -> MFMA operand (8 fp16)
+__device__ __forceinline__ u32x4_t deq_row8(uint32_t c0, uint32_t c1, uint32_t scale2) {
+  const uint32_t k = 0x64646464u;
+  const uint32_t x0 = c0 ^ 0x80808080u, x1 = c1 ^ 0x80808080u;
+  u32x4_t o;
+  o[0] = deq2(__builtin_amdgcn_perm(k, x0, 0x04010400u), scale2);
+  o[1] = deq2(__builtin_amdgcn_perm(k, x0, 0x04030402u), scale2);
+  o[2] = deq2(__builtin_amdgcn_perm(k, x1, 0x04010400u), scale2);
+  o[3] = deq2(__builtin_amdgcn_perm(k, x1, 0x04030402u), scale2);
+  return o;
 }
 
 // ------------------------------------------------------------------------------------------
@@ -233,6 +257,75 @@ __device__ __forceinline__ void wsum_tile(const char* vA, const char* vB, int pi
   }
 }
 
+// int8 variant of score_tile.  A wave owns 64-column scale blocks w, w+4, ...; per block and
+// 16-row half it holds the lane's 16 codes (columns 64m + 16g .. +15 of its row) and the
+// row's scale.  Codes 0-7 feed one MFMA and codes 8-15 the next (q' is loaded with the same
+// column order), so a block is two k-steps.
+template <int MT, int NBW>
+__device__ __forceinline__ void score_tile_i8(const u32x4_t (&Araw)[NBW][2],
+                                              const uint32_t (&ksc)[NBW][2],
+                                              const u32x4_t (&qhi)[2 * NBW][MT],
+                                              f32x4_t (&s)[MT][2]) {
+#pragma unroll
+  for (int i = 0; i < NBW; ++i) {
+    u32x4_t a0[2], a1[2];
+#pragma unroll
+    for (int tt = 0; tt < 2; ++tt) {
+      a0[tt] = deq_row8(Araw[i][tt][0], Araw[i][tt][1], ksc[i][tt]);
+      a1[tt] = deq_row8(Araw[i][tt][2], Araw[i][tt][3], ksc[i][tt]);
+    }
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      s[mt][0] = Mfma<F16Tag>::run(a0[0], qhi[2 * i][mt], s[mt][0]);
+      s[mt][1] = Mfma<F16Tag>::run(a0[1], qhi[2 * i][mt], s[mt][1]);
+    }
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      s[mt][0] = Mfma<F16Tag>::run(a1[0], qhi[2 * i + 1][mt], s[mt][0]);
+      s[mt][1] = Mfma<F16Tag>::run(a1[1], qhi[2 * i + 1][mt], s[mt][1]);
+    }
+  }
+}
+
+// int8 variant of wsum_tile.  Column groups are 256 wide; in each the wave owns 64 bytes (one
+// scale block).  Lane (n, g) reads dword n of those bytes for its 8 tokens: four codes, i.e.
+// columns 4n .. 4n+3 of the wave's 64, one MFMA per byte position.  vs: this tile's value
+// scales in LDS as [scale block][32 tokens] fp16.
+template <int MT, int NGL>
+__device__ __forceinline__ void wsum_tile_i8(const char* vA, const char* vB, int pitch, int r,
+                                             int cp, int g, const uint16_t* vs,
+                                             const u32x4_t (&Phi)[MT], const float (&alpha)[MT],
+                                             f32x4_t (&U)[NGL][4][MT]) {
+#pragma unroll
+  for (int i = 0; i < NGL; ++i) {
+    const int blk = 4 * i + cp;
+    uint32_t v[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    u32x2_t s01 = {0, 0}, s23 = {0, 0};
+    if (blk * 64 < r) {                       // wave-uniform: the block exists at this rank
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        v[e] = *(const uint32_t*)(vA + e * pitch + i * 256);
+        v[4 + e] = *(const uint32_t*)(vB + e * pitch + i * 256);
+      }
+      s01 = *(const u32x2_t*)(vs + blk * kTile + 4 * g);          // tokens 4g .. 4g+3
+      s23 = *(const u32x2_t*)(vs + blk * kTile + 16 + 4 * g);     // tokens 16+4g .. +3
+    }
+    const uint32_t sc[4] = {s01[0], s01[1], s23[0], s23[1]};
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      // byte j of two tokens -> low bytes of the two halves, then bias into 0x64uu
+      const uint32_t sel = 0x0c000c00u | ((uint32_t)(4 + j) << 16) | (uint32_t)j;
+      u32x4_t op;
+#pragma unroll
+      for (int k = 0; k < 4; ++k)
+        op[k] = deq2(__builtin_amdgcn_perm(v[2 * k + 1], v[2 * k], sel) ^ 0x64806480u, sc[k]);
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt)
+        U[i][j][mt] = Mfma<F16Tag>::run(op, Phi[mt], U[i][j][mt] * alpha[mt]);
+    }
+  }
+}
+
 // Butterfly steps inside groups of 8 lanes with DPP (VALU speed, no LDS crossbar):
 // xor 1 and xor 2 as quad permutes; the third step mirrors each half-row, which pairs the
 // two quads of an 8-lane group (all lanes of a quad already agree after the first two).
@@ -272,6 +365,8 @@ struct AttnParams {
   const uint16_t* Qp;   // [B][2][Hp][r]
   const uint16_t* Ck;   // [B][T_cap][r]
   const uint16_t* Cv;
+  const uint16_t* Sk;   // int8 coefficients only: fp16 scales [B][T_cap][r/64]
+  const uint16_t* Sv;
   float* part_ml;       // [B][S][H][2]   (softmax reference exponent in log2 units, sum)
   float* part_U;        // [B][S][H][r]
   int T, T_cap, r, H, nsplit;
@@ -314,9 +409,10 @@ struct AttnParams {
 // tile's (token count, key rank, value rank) into LDS; the row loads then gather through
 // that table.  Columns at or beyond a tile's rank are neither fetched from HBM (their loads
 // are redirected to bytes the wave fetches anyway) nor allowed into the products.
-template <class Tag, int MT, bool SPLIT, bool RAGGED>
+template <class Tag, int MT, bool SPLIT, bool RAGGED, bool I8>
 struct WaveCtx {
   static constexpr int HPW = 2 * MT;     // heads finalised per wave
+  static constexpr int EB = I8 ? 1 : 2;  // bytes per stored coefficient
 
   int w, lane, n, g, b, s;
   int r, T, H, nh, nsplit, dbg;
@@ -325,6 +421,7 @@ struct WaveCtx {
   f32x4_t* xchg;     // [4 score waves][16*MT heads][9]: 8 slots (4*tt+g) + 1 pad per head
   u32x4_t* Pbuf;     // [MT][hi,lo][64 lanes]
   float* abuf;       // [16*MT] rescale factors
+  uint16_t* vsb;     // I8: [2][r/64][32] value scales of the tile in flight (fp16 bits)
   int* idxb;         // RAGGED: [ntl][32] token index of every tile slot (tail slots repeat the last)
   int* meta;         // RAGGED: [ntl][4] = tokens in the tile, key rank, value rank, unused
   uint32_t row_bytes;
@@ -344,7 +441,7 @@ struct WaveCtx {
     r = uni(p.r); T = uni(p.T); H = uni(p.H); nh = uni(p.nh); nsplit = uni(p.nsplit); dbg = uni(p.dbg);
     // ring unit geometry: 16 rows of (cpr+1) 16-byte chunks (one pad chunk per row shifts
     // consecutive rows across the LDS banks)
-    const int cpr = r >> 3;
+    const int cpr = (r * EB) >> 4;
     pitch = (cpr + 1) * 16;
     nblk = (kHalf * (cpr + 1) + 63) >> 6;
     unit_bytes = nblk * 1024;
@@ -352,13 +449,14 @@ struct WaveCtx {
     xchg = (f32x4_t*)(smem + nh * unit_bytes);
     Pbuf = (u32x4_t*)(xchg + 4 * 16 * MT * 9);
     abuf = (float*)(Pbuf + MT * 2 * 64);
-    row_bytes = (uint32_t)r * 2u;
+    row_bytes = (uint32_t)(r * EB);
+    vsb = (uint16_t*)(abuf + 16 * MT);
     if (!RAGGED) {
       const int ntiles = (T + kTile - 1) / kTile;
       t_lo = (int)(((int64_t)s * ntiles) / nsplit);
       ntl = (int)(((int64_t)(s + 1) * ntiles) / nsplit) - t_lo;
     } else {
-      idxb = (int*)(abuf + 16 * MT);
+      idxb = (int*)(vsb + (I8 ? 2 * (r >> 6) * kTile : 0));
       meta = idxb + uni(p.ntl_cap) * kTile;
       build_tile_table(p);
     }
@@ -494,19 +592,24 @@ struct WaveCtx {
   }
 };
 
-template <class Tag, int MT, int RMAX, bool SPLIT, bool RAGGED>
+template <class Tag, int MT, int RMAX, bool SPLIT, bool RAGGED, bool I8>
 __device__ __noinline__ void score_role(const AttnParams& p) {
-  constexpr int NKW = (RMAX / 32 + 3) / 4;                // score k-steps per score wave
+  // a score wave owns "units" w, w+4, ... of the rank axis, 64 bytes of a row each:
+  // 32-column k-steps for 16-bit storage, 64-column scale blocks (two k-steps) for int8
+  constexpr int NBW = (RMAX / 64 + 3) / 4;                // int8: scale blocks per score wave
+  constexpr int NKW = I8 ? 2 * NBW : (RMAX / 32 + 3) / 4; // score k-steps per score wave
+  constexpr int NA = I8 ? NBW : NKW;                      // 16-byte row loads per 16-row half
   constexpr int Hp = MT * 16;
   const unsigned long long t_entry_ = __builtin_readcyclecounter();
-  WaveCtx<Tag, MT, SPLIT, RAGGED> cx;
+  WaveCtx<Tag, MT, SPLIT, RAGGED, I8> cx;
   cx.init(p);
   float* part_U = uni_ptr(p.part_U);
   float* part_ml = uni_ptr(p.part_ml);
   const int w = cx.w, n = cx.n, g = cx.g, r = cx.r, T = cx.T;
-  const int nks = r >> 5;                                 // all score k-steps
-  const int my_nks = nks > w ? (nks - w + 3) >> 2 : 0;    // k-steps w, w+4, ...
+  const int nks = I8 ? r >> 6 : r >> 5;                   // all units
+  const int my_nks = nks > w ? (nks - w + 3) >> 2 : 0;    // units w, w+4, ...
   // q' operands (B operand of the score MFMA): lane (h=n, g) holds columns 32ks+8g..+7
+  // (int8: columns 64m+16g..+7 for a block's first k-step, 64m+16g+8..+15 for its second)
   const uint16_t* Qp = uni_ptr(p.Qp);
   u32x4_t qhi[NKW][MT];
   u32x4_t qlo[SPLIT ? NKW : 1][MT];
@@ -517,25 +620,59 @@ __device__ __noinline__ void score_role(const AttnParams& p) {
       u32x4_t z = {0, 0, 0, 0};
       qhi[i][mt] = z;
       if (SPLIT) qlo[i][mt] = z;
-      if (i < my_nks) {
-        const uint16_t* qrow =
-            Qp + (((size_t)cx.b * 2) * Hp + (mt * 16 + n)) * r + (w + 4 * i) * 32 + g * 8;
+      const int unit = I8 ? i >> 1 : i;
+      if (unit < my_nks) {
+        const int col = I8 ? (w + 4 * unit) * 64 + g * 16 + (i & 1) * 8 : (w + 4 * i) * 32 + g * 8;
+        const uint16_t* qrow = Qp + (((size_t)cx.b * 2) * Hp + (mt * 16 + n)) * r + col;
         qhi[i][mt] = *(const u32x4_t*)qrow;
         if (SPLIT) qlo[i][mt] = *(const u32x4_t*)(qrow + (size_t)Hp * r);
       }
     }
-  // C_k operands (A operand): lane (n, g) holds columns 32ks+8g..+7 of token rows n, 16+n
-  // of the tile.  Per-sequence byte offsets fit 32 bits (checked on the host).
-  const char* Ck_b = (const char*)(uni_ptr(p.Ck) + (size_t)cx.b * uni(p.T_cap) * r);
-  // k-steps this wave does not own re-read its first chunk (finite data times zero q'):
+  // C_k operands (A operand): lane (n, g) holds 16 bytes of token rows n, 16+n of the tile
+  // per unit.  Per-sequence byte offsets fit 32 bits (checked on the host).
+  const char* Ck_b = (const char*)uni_ptr(p.Ck) + (size_t)cx.b * uni(p.T_cap) * cx.row_bytes;
+  // units this wave does not own re-read its first chunk (finite data times zero q'):
   // the loads carry no branches, so they issue back to back without waits between them
   const uint32_t lane_off = (uint32_t)((my_nks > 0 ? w * 64 : 0) + g * 16);
-  u32x4_t A[NKW][2];
+  u32x4_t A[NA][2];
 #pragma unroll
-  for (int i = 0; i < NKW; ++i) { u32x4_t z = {0, 0, 0, 0}; A[i][0] = z; A[i][1] = z; }
-  uint32_t koff[NKW];
+  for (int i = 0; i < NA; ++i) { u32x4_t z = {0, 0, 0, 0}; A[i][0] = z; A[i][1] = z; }
+  uint32_t koff[NA];
 #pragma unroll
-  for (int i = 0; i < NKW; ++i) koff[i] = i < my_nks ? (uint32_t)i * 256u : 0u;
+  for (int i = 0; i < NA; ++i) koff[i] = i < my_nks ? (uint32_t)i * 256u : 0u;
+  // int8: the key scale of the lane's row for every owned block (both halves of a packed
+  // pair), and this wave's share of the tile's value scales, which the score waves pass to
+  // the sum waves through LDS as [scale block][32 tokens]
+  const int nsb = r >> 6;
+  const uint16_t* Sk_b = I8 ? uni_ptr(p.Sk) + (size_t)cx.b * uni(p.T_cap) * nsb : nullptr;
+  const uint16_t* Sv_b = I8 ? uni_ptr(p.Sv) + (size_t)cx.b * uni(p.T_cap) * nsb : nullptr;
+  uint32_t ksc[I8 ? NBW : 1][2];
+  uint16_t vsr[2] = {0, 0};
+  const int vs_e0 = w * 64 + cx.lane;                      // entries vs_e0, vs_e0 + 256 of [block][token]
+  auto load_scales = [&](int tile) {
+    if constexpr (I8) {
+#pragma unroll
+      for (int tt = 0; tt < 2; ++tt) {
+        int row = (cx.t_lo + tile) * kTile + 16 * tt + n;
+        row = row < T ? row : T - 1;
+        const uint16_t* sp_ = Sk_b + (size_t)row * nsb + (my_nks > 0 ? w : 0);
+#pragma unroll
+        for (int i = 0; i < NBW; ++i) {
+          const uint32_t sv = sp_[i < my_nks ? 4 * i : 0];
+          ksc[i][tt] = sv | (sv << 16);
+        }
+      }
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const int e = vs_e0 + 256 * j;
+        if (e < nsb * kTile) {
+          int row = (cx.t_lo + tile) * kTile + (e & 31);
+          row = row < T ? row : T - 1;
+          vsr[j] = Sv_b[(size_t)row * nsb + (e >> 5)];
+        }
+      }
+    }
+  };
   auto load_A = [&](int tile) {                           // tile: local index in this split
     if (cx.dbg & 1) return;
     if (!RAGGED) {
@@ -545,8 +682,9 @@ __device__ __noinline__ void score_role(const AttnParams& p) {
         row = row < T ? row : T - 1;                      // rows beyond T are masked later
         const char* rp = Ck_b + ((uint32_t)row * cx.row_bytes + lane_off);
 #pragma unroll
-        for (int i = 0; i < NKW; ++i) A[i][tt] = *(const u32x4_t*)(rp + koff[i]);
+        for (int i = 0; i < NA; ++i) A[i][tt] = *(const u32x4_t*)(rp + koff[i]);
       }
+      load_scales(tile);
     } else {
       // gathered rows; k-steps at or beyond the tile's key rank re-read bytes this wave
       // (or, with no k-step left, its neighbours) fetch anyway
@@ -557,7 +695,7 @@ __device__ __noinline__ void score_role(const AttnParams& p) {
         const int row = cx.idxb[tile * kTile + 16 * tt + n];
         const char* rp = Ck_b + ((uint32_t)row * cx.row_bytes + loff);
 #pragma unroll
-        for (int i = 0; i < NKW; ++i)
+        for (int i = 0; i < NA; ++i)
           A[i][tt] = *(const u32x4_t*)(rp + ((w + 4 * i) < nks_t ? (uint32_t)i * 256u : 0u));
       }
     }
@@ -575,10 +713,20 @@ __device__ __noinline__ void score_role(const AttnParams& p) {
     if (RAGGED) {                                         // columns beyond the key rank count as zero
       const int nks_t = uni(cx.meta[4 * t + 1]) >> 5;
 #pragma unroll
-      for (int i = 0; i < NKW; ++i)
+      for (int i = 0; i < NA; ++i)
         if ((w + 4 * i) >= nks_t) { u32x4_t z = {0, 0, 0, 0}; A[i][0] = z; A[i][1] = z; }
     }
-    if (!(cx.dbg & 2)) score_tile<Tag, MT, SPLIT, NKW>(A, qhi, qlo, sp);
+    if constexpr (I8) {
+      // hand tile t's value scales to the sum waves (buffer t&1: its previous reader, the
+      // weighted sum of tile t-2, ended before the barrier this wave passed in tile t-1)
+      uint16_t* vs = cx.vsb + (t & 1) * nsb * kTile;
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+        if (vs_e0 + 256 * j < nsb * kTile) vs[vs_e0 + 256 * j] = vsr[j];
+      if (!(cx.dbg & 2)) score_tile_i8<MT, NBW>(A, ksc, qhi, sp);
+    } else {
+      if (!(cx.dbg & 2)) score_tile<Tag, MT, SPLIT, NKW>(A, qhi, qlo, sp);
+    }
     AP_TICK(1)
     if (t + 1 < cx.ntl) load_A(t + 1);                    // lands while the tile is finished
 #pragma unroll
@@ -608,23 +756,25 @@ __device__ __noinline__ void score_role(const AttnParams& p) {
   }
 }
 
-template <class Tag, int MT, int RMAX, bool SPLIT, bool RAGGED>
+template <class Tag, int MT, int RMAX, bool SPLIT, bool RAGGED, bool I8>
 __device__ __noinline__ void sum_role(const AttnParams& p) {
-  constexpr int NGRP = (RMAX + 127) / 128;                        // 128-column groups
-  constexpr int MAXBLK = (kHalf * (RMAX / 8 + 1) + 63) / 64;      // 1 KiB blocks per ring unit
+  constexpr int EB = I8 ? 1 : 2;
+  constexpr int NGRP = (RMAX * EB + 255) / 256;                   // 256-byte column groups
+  constexpr int NJ = I8 ? 4 : 2;                                  // columns per LDS dword
+  constexpr int MAXBLK = (kHalf * (RMAX * EB / 16 + 1) + 63) / 64;  // 1 KiB blocks per ring unit
   constexpr int NSLOT = (MAXBLK + 3) / 4;
   const unsigned long long t_entry_ = __builtin_readcyclecounter();
-  WaveCtx<Tag, MT, SPLIT, RAGGED> cx;
+  WaveCtx<Tag, MT, SPLIT, RAGGED, I8> cx;
   cx.init(p);
   float* part_U = uni_ptr(p.part_U);
   float* part_ml = uni_ptr(p.part_ml);
   const int n = cx.n, g = cx.g, r = cx.r, T = cx.T, lane = cx.lane;
-  const int cp = cx.w - 4;                                // which 32 columns of every group
+  const int cp = cx.w - 4;                                // which 64 bytes of every group
   const int RT = cx.nh >> 1;                              // ring capacity in tiles
 
   // ---- this wave's share of a C_v ring unit: 1 KiB blocks cp, cp+4, ...; per lane the
   //      row and the byte offset of its 16-byte chunk from the unit's first row
-  const int cpr = r >> 3;
+  const int cpr = (r * EB) >> 4;
   const int tot_chunks = kHalf * (cpr + 1);
   uint32_t slot_off[NSLOT];
   uint32_t slot_row[(NSLOT + 3) / 4];
@@ -648,7 +798,7 @@ __device__ __noinline__ void sum_role(const AttnParams& p) {
       slot_chk[k >> 2] |= (uint32_t)c << (8 * (k & 3));
     }
   }
-  const char* Cv_b = (const char*)(uni_ptr(p.Cv) + (size_t)cx.b * uni(p.T_cap) * r);
+  const char* Cv_b = (const char*)uni_ptr(p.Cv) + (size_t)cx.b * uni(p.T_cap) * cx.row_bytes;
   // both 16-row units of local tile lt into ring slots 2*(lt % RT), +1
   auto issue_tile = [&](int lt) {
     if (cx.dbg & 1) return;
@@ -701,11 +851,11 @@ __device__ __noinline__ void sum_role(const AttnParams& p) {
 #pragma nounroll
   for (int lt = 0; lt < RT && lt < cx.ntl; ++lt) issue_tile(lt);
 
-  f32x4_t U[NGRP][2][MT];
+  f32x4_t U[NGRP][NJ][MT];
 #pragma unroll
   for (int i = 0; i < NGRP; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < NJ; ++j)
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) { f32x4_t z = {0.f, 0.f, 0.f, 0.f}; U[i][j][mt] = z; }
   unsigned long long tm[8] = {0, 0, 0, 0, 0, 0, 0, 0};
@@ -738,14 +888,21 @@ __device__ __noinline__ void sum_role(const AttnParams& p) {
     const int slot0 = 2 * (t % RT);
     const char* vA = cx.ring + slot0 * cx.unit_bytes + (4 * g) * cx.pitch + cp * 64 + n * 4;
     const char* vB = vA + cx.unit_bytes;
-    if (!(cx.dbg & 2))
-      wsum_tile<Tag, MT, SPLIT, NGRP>(vA, vB, cx.pitch,
-                                      (RAGGED ? uni(cx.meta[4 * t + 2]) : r) - cp * 32, n, Phi, Plo,
-                                      alpha, U);
+    if constexpr (I8) {
+      if (!(cx.dbg & 2))
+        wsum_tile_i8<MT, NGRP>(vA, vB, cx.pitch, r, cp, g, cx.vsb + (t & 1) * (r >> 6) * kTile, Phi,
+                               alpha, U);
+    } else {
+      if (!(cx.dbg & 2))
+        wsum_tile<Tag, MT, SPLIT, NGRP>(vA, vB, cx.pitch,
+                                        (RAGGED ? uni(cx.meta[4 * t + 2]) : r) - cp * 32, n, Phi, Plo,
+                                        alpha, U);
+    }
     AP_TICK(5)
   }
   // U of this split.  U[i][j][mt][e] is element (head 16mt+n, column 128i + 32cp + 8g +
-  // 2e + j); one head tile at a time is transposed through LDS so that rows leave coalesced.
+  // 2e + j) (int8: column 256i + 64cp + 16g + 4e + j); one head tile at a time is transposed
+  // through LDS so that rows leave coalesced.
   float* ul = (float*)cx.ring;                      // [16][r+1]
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) {
@@ -753,10 +910,11 @@ __device__ __noinline__ void sum_role(const AttnParams& p) {
 #pragma unroll
     for (int i = 0; i < NGRP; ++i)
 #pragma unroll
-      for (int j = 0; j < 2; ++j)
+      for (int j = 0; j < NJ; ++j)
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          const int col = i * 128 + cp * 32 + g * 8 + e * 2 + j;
+          const int col = I8 ? i * 256 + cp * 64 + g * 16 + e * 4 + j
+                             : i * 128 + cp * 32 + g * 8 + e * 2 + j;
           if (col < r) ul[n * (r + 1) + col] = U[i][j][mt][e];
         }
     wg_barrier();
@@ -771,13 +929,13 @@ __device__ __noinline__ void sum_role(const AttnParams& p) {
 }
 #undef AP_TICK
 
-template <class Tag, int MT, int RMAX, bool SPLIT, bool RAGGED>
+template <class Tag, int MT, int RMAX, bool SPLIT, bool RAGGED, bool I8>
 __global__ void __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2)))
 attn_partial(const AttnParams p) {
   if (__builtin_amdgcn_readfirstlane(threadIdx.x >> 6) < 4)
-    score_role<Tag, MT, RMAX, SPLIT, RAGGED>(p);
+    score_role<Tag, MT, RMAX, SPLIT, RAGGED, I8>(p);
   else
-    sum_role<Tag, MT, RMAX, SPLIT, RAGGED>(p);
+    sum_role<Tag, MT, RMAX, SPLIT, RAGGED, I8>(p);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -887,11 +1045,12 @@ WsLayout ws_layout(int B, int H, int T, int r) {
   return w;
 }
 
-template <class Tag, int MT, int RMAX, bool SPLIT, bool RAGGED>
+template <class Tag, int MT, int RMAX, bool SPLIT, bool RAGGED, bool I8>
 ap_status launch_attn(AttnParams p, int B, hipStream_t stream) {
-  const int cpr = p.r / 8;
+  const int cpr = p.r * (I8 ? 1 : 2) / 16;
   const size_t unit = (size_t)((kHalf * (cpr + 1) + 63) / 64) * 1024;
   size_t fixed = (size_t)4 * 16 * MT * 9 * 16 + (size_t)MT * 2 * 64 * 16 + (size_t)MT * 16 * 4;
+  if (I8) fixed += (size_t)2 * (p.r / 64) * kTile * 2;     // value scales of two tiles
   if (RAGGED) {
     // every group may end in a partial tile; tiles are dealt round-robin to the splits
     const int ntiles_max = (p.T + kTile - 1) / kTile + p.F;
@@ -908,7 +1067,7 @@ ap_status launch_attn(AttnParams p, int B, hipStream_t stream) {
   size_t lds = (size_t)nh * unit + fixed;
   const size_t epi = (size_t)16 * (p.r + 1) * 4;
   if (epi > lds) lds = epi;
-  auto kern = attn_partial<Tag, MT, RMAX, SPLIT, RAGGED>;
+  auto kern = attn_partial<Tag, MT, RMAX, SPLIT, RAGGED, I8>;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -926,15 +1085,28 @@ ap_status launch_attn(AttnParams p, int B, hipStream_t stream) {
 template <class Tag, bool SPLIT>
 ap_status dispatch_attn(const AttnParams& p, int B, hipStream_t stream) {
   const int nw = (p.H + 15) / 16;
+  if constexpr (!SPLIT) {                 // fp16 arithmetic: int8 coefficients ride on it
+    if (p.Sk) {
+      switch (nw) {
+#define AP_CASE8(NWV)                                                                     \
+  case NWV:                                                                               \
+    return p.r <= 256   ? launch_attn<Tag, NWV, 256, false, false, true>(p, B, stream)    \
+           : p.r <= 512 ? launch_attn<Tag, NWV, 512, false, false, true>(p, B, stream)    \
+                        : launch_attn<Tag, NWV, 640, false, false, true>(p, B, stream);
+        AP_CASE8(1) AP_CASE8(2) AP_CASE8(3) AP_CASE8(4)
+#undef AP_CASE8
+      }
+    }
+  }
 #define AP_CASE(NWV)                                                                  \
   case NWV:                                                                           \
     if (p.bucket_idx)                                                                 \
-      return p.r <= 256   ? launch_attn<Tag, NWV, 256, SPLIT, true>(p, B, stream)     \
-             : p.r <= 512 ? launch_attn<Tag, NWV, 512, SPLIT, true>(p, B, stream)     \
-                          : launch_attn<Tag, NWV, 640, SPLIT, true>(p, B, stream);    \
-    return p.r <= 256   ? launch_attn<Tag, NWV, 256, SPLIT, false>(p, B, stream)      \
-           : p.r <= 512 ? launch_attn<Tag, NWV, 512, SPLIT, false>(p, B, stream)      \
-                        : launch_attn<Tag, NWV, 640, SPLIT, false>(p, B, stream);
+      return p.r <= 256   ? launch_attn<Tag, NWV, 256, SPLIT, true, false>(p, B, stream)     \
+             : p.r <= 512 ? launch_attn<Tag, NWV, 512, SPLIT, true, false>(p, B, stream)     \
+                          : launch_attn<Tag, NWV, 640, SPLIT, true, false>(p, B, stream);    \
+    return p.r <= 256   ? launch_attn<Tag, NWV, 256, SPLIT, false, false>(p, B, stream)      \
+           : p.r <= 512 ? launch_attn<Tag, NWV, 512, SPLIT, false, false>(p, B, stream)      \
+                        : launch_attn<Tag, NWV, 640, SPLIT, false, false>(p, B, stream);
   switch (nw) {
     AP_CASE(1) AP_CASE(2) AP_CASE(3) AP_CASE(4)
   }
@@ -962,6 +1134,10 @@ ap_status run_decode(const DecodeArgs& a) {
   p.part_ml = ml;
   p.part_U = U;
   p.T = a.T; p.T_cap = a.T_cap; p.r = a.r; p.H = a.H; p.nsplit = S;
+  if (a.dt_coef == AP_I8) {
+    p.Sk = (const uint16_t*)a.scale_k;
+    p.Sv = (const uint16_t*)a.scale_v;
+  }
   if (a.rank_k || a.rank_v) {             // rank-ragged: walk the group lists
     p.rank_k = a.rank_k;
     p.rank_v = a.rank_v;
@@ -996,7 +1172,8 @@ size_t decode_mfma_workspace(int B, int H, int d, int T, int r, ap_dtype dt) {
 
 ap_status launch_decode_mfma(const DecodeArgs& a) {
   AP_REQUIRE(a.B <= 65535, AP_ERR_UNSUPPORTED, "ap_decode_attn: B must be <= 65535");
-  AP_REQUIRE(a.dt_coef != AP_I8, AP_ERR_UNSUPPORTED, "ap_decode_attn: int8 coefficients not built yet");
+  AP_REQUIRE(a.dt_coef != AP_I8 || (!a.rank_k && !a.rank_v), AP_ERR_UNSUPPORTED,
+             "ap_decode_attn: int8 coefficients with per-token ranks are not implemented");
   AP_REQUIRE((int64_t)a.T_cap * a.r * 2 < (1ll << 32), AP_ERR_UNSUPPORTED,
              "ap_decode_attn: one sequence's coefficients must stay below 4 GiB");
   return a.dt == AP_F16 ? run_decode<F16Tag, false>(a) : run_decode<BF16Tag, true>(a);
