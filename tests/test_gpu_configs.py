@@ -1,0 +1,91 @@
+"""GPU parity at the benchmark configurations' full sizes and launch shapes: configuration 2
+(B=8, fp16, 128 decode steps with append) and configuration 3 (B=64, bf16, 64 steps with
+append; the workload bench.py times).  Every step runs on the GPU; at the sampled steps the
+cache is read back and the fp64 oracle attends over exactly those stored bits."""
+import math
+import time
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2603_23914_amd import workloads as wl
+from gpu_util import TORCH_DT, TOL, to_dev, to_host64, workspace
+
+pytestmark = pytest.mark.gpu
+
+ROUND = {"f16": 2.0 ** -10, "bf16": 2.0 ** -7}
+
+
+def stored_bits(t: torch.Tensor, dtype: str) -> np.ndarray:
+    """GPU tensor -> host array in the storage convention of workloads.store."""
+    if dtype == "bf16":
+        return t.view(torch.int16).cpu().numpy().view(np.uint16)
+    return t.cpu().numpy()
+
+
+def run_config(case, check_steps, check_seqs_later):
+    from paper_2603_23914_amd import binding as ap
+    dt = case.dtype
+    B, H, d, r = case.B, case.H, case.d, case.r
+    P = lambda x: oracle.promote(x, dt)
+    dCk, dCv, dBk, dBv = (to_dev(x, dt) for x in (case.Ck, case.Cv, case.Bk, case.Bv))
+    Bk64 = Bv64 = None
+    out = torch.empty((B, H, d), dtype=torch.float32, device="cuda")
+    ws = workspace(ap.ap_decode_workspace_bytes(B, H, d, case.T_cap, r, ap._DT[TORCH_DT[dt]]))
+    worst = 0.0
+    for step in range(max(check_steps) + 1):
+        T = case.T0 + step + 1
+        checked = step in check_steps
+        if checked and Bk64 is None:
+            Bk64, Bv64 = P(case.Bk), P(case.Bv)
+        # the appended token: drawn on the host only at checked steps (the draw needs the fp64
+        # bases); other steps append a cheap synthetic row of the same law through the same call
+        if checked:
+            kn, vn = wl.step_new_token(case, step, Bk64, Bv64)
+        else:
+            rng = wl.rng_for(case.seed, 32, step)
+            kn = wl.store(rng.standard_normal((B, case.HD)), dt)
+            vn = wl.store(rng.standard_normal((B, case.HD)), dt)
+        q = wl.step_query(case, step)
+        dkn, dvn, dq = (to_dev(x, dt) for x in (kn[:, None, :], vn[:, None, :], q))
+        ap.ap_compact(dkn, dvn, dBk, dBv, dCk, dCv, n=1, row0=T - 1)
+        ap.ap_decode_attn(dq, dCk, dCv, dBk, dBv, out, ws, T=T, sm_scale=1.0 / math.sqrt(d))
+        torch.cuda.synchronize()
+        if not checked:
+            continue
+        seqs = range(B) if step == check_steps[0] else check_seqs_later
+        got = to_host64(out)
+        Ck_h, Cv_h = stored_bits(dCk, dt), stored_bits(dCv, dt)
+        ref = {}
+        for b in seqs:
+            # appended row against the fp64 projection (one rounding to the storage type)
+            for C_h, x, Bm in ((Ck_h, kn, Bk64), (Cv_h, vn, Bv64)):
+                c_ref = oracle.compact(P(x[b])[None, :], Bm[b])[0]
+                err = np.abs(P(C_h[b, T - 1]) - c_ref)
+                assert (err <= ROUND[dt] * np.abs(c_ref) + 1e-5 * np.abs(c_ref).max()).all(), (step, b)
+            ref[b] = oracle.decode_attn_absorbed(P(q[b]), P(Ck_h[b, :T]), P(Cv_h[b, :T]), Bk64[b], Bv64[b])
+        refs = np.stack([ref[b] for b in seqs])
+        gots = np.stack([got[b] for b in seqs])
+        scale = np.abs(refs).max()
+        err = np.abs(gots - refs).max()
+        assert np.isfinite(got).all()
+        assert err <= TOL[dt] * scale, f"step {step}: max|err|={err:.3e} > {TOL[dt]:g}*{scale:.3e}"
+        worst = max(worst, err / scale)
+        print(f"  step {step} (T={T}, {len(list(seqs))} sequences): max|err|/||out||inf = {err / scale:.2e}", flush=True)
+    return worst
+
+
+def test_config2_full_size():
+    t0 = time.time()
+    case = wl.config2(seed=0)
+    print(f"config 2 generated in {time.time() - t0:.0f} s", flush=True)
+    run_config(case, (0, 63, 127), range(case.B))
+
+
+def test_config3_full_size():
+    t0 = time.time()
+    case = wl.config3(seed=0)
+    print(f"config 3 generated in {time.time() - t0:.0f} s", flush=True)
+    run_config(case, (0, 31, 63), (0, 31, 63))
