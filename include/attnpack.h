@@ -169,6 +169,30 @@ ap_status ap_decode_attn(const void* q, const void* Ck, const void* Cv,
 size_t ap_decode_workspace_bytes(int B, int H, int d, int T, int r, ap_dtype dt);
 
 /* ------------------------------------------------------------------------
+ * ap_decode_step -- one decode step with append (paper Alg. 1: the new token's
+ * key and value join the cache, then the query attends to every cached token).
+ * Same result, bit for bit, as
+ *     ap_compact(k_new, v_new, Bk, Bv, Ck, Cv, ..., n = 1, row0 = T - 1, ...)
+ *     ap_decode_attn(q, Ck, Cv, ..., T, ...)
+ * but the key row's projection and the fold of the query through B_k share one
+ * pass over B_k, so the step reads the key basis once instead of twice.
+ *   k_new, v_new  [B, HD] dtype dt: the new token's merged-head key and value rows.
+ *   Ck, Cv        [B, T_cap, r] dtype dt: row T-1 is WRITTEN, rows 0..T-1 attended.
+ *   T             tokens cached after the append (1 <= T <= T_cap).
+ * AP_F16 / AP_BF16 only (no int8 coefficients).  Rank arrays and group lists, when
+ * given, must already cover the new token.  Everything else as ap_decode_attn;
+ * the workspace query is ap_decode_workspace_bytes.
+ * ---------------------------------------------------------------------- */
+ap_status ap_decode_step(const void* q, const void* k_new, const void* v_new, void* Ck, void* Cv,
+                         const void* Bk, const void* Bv, int64_t basis_batch_stride,
+                         const int32_t* rank_k, const int32_t* rank_v,
+                         const int32_t* bucket_off, const int32_t* bucket_idx, int F,
+                         void* out, float* lse,
+                         int B, int H, int d, int T, int T_cap, int r, float sm_scale,
+                         ap_dtype dt, ap_dtype dt_out,
+                         void* workspace, size_t ws_bytes, void* stream);
+
+/* ------------------------------------------------------------------------
  * Timing of the dominant kernel (measurement aid, not part of the method).
  * While enabled, every ap_decode_attn call on AP_F16 / AP_BF16 brackets its
  * coefficient-streaming kernel with a pair of HIP events on the call's stream.

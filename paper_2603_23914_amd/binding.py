@@ -42,6 +42,9 @@ _lib.ap_select_workspace_bytes.argtypes = [_i, _i, _i]
 _lib.ap_decode_attn.restype = _i
 _lib.ap_decode_attn.argtypes = ([_vp] * 7 + [_i64] + [_vp] * 4 + [_i] + [_vp, _vp] + [_i] * 6 +
                                 [_f, _i, _i, _i, _vp, _sz, _vp])
+_lib.ap_decode_step.restype = _i
+_lib.ap_decode_step.argtypes = ([_vp] * 7 + [_i64] + [_vp] * 4 + [_i] + [_vp, _vp] + [_i] * 6 +
+                                [_f, _i, _i, _vp, _sz, _vp])
 _lib.ap_decode_workspace_bytes.restype = _sz
 _lib.ap_decode_workspace_bytes.argtypes = [_i] * 6
 _lib.ap_status_string.restype = _c.c_char_p
@@ -56,7 +59,7 @@ _lib.ap_prof_read.restype = _i
 _lib.ap_prof_read.argtypes = [_c.POINTER(_c.c_float), _c.POINTER(_c.c_int)]
 
 EXPORTS = ("ap_compact", "ap_quantize_i8", "ap_select_ranks", "ap_select_workspace_bytes",
-           "ap_decode_attn", "ap_decode_workspace_bytes", "ap_status_string", "ap_last_error",
+           "ap_decode_attn", "ap_decode_step", "ap_decode_workspace_bytes", "ap_status_string", "ap_last_error",
            "ap_version", "ap_prof_enable", "ap_prof_read")
 
 _DT = {torch.float32: AP_F32, torch.float16: AP_F16, torch.bfloat16: AP_BF16, torch.int8: AP_I8}
@@ -153,6 +156,19 @@ def ap_decode_attn(q, Ck, Cv, Bk, Bv, out, workspace, *, T: int, sm_scale: float
                                _p(bucket_idx), F, _p(out), _p(lse), B, H, d, T, T_cap, r,
                                float(sm_scale), _DT[q.dtype], _DT[Ck.dtype], _DT[out.dtype],
                                _p(workspace),
+                               workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
+def ap_decode_step(q, k_new, v_new, Ck, Cv, Bk, Bv, out, workspace, *, T: int, sm_scale: float,
+                   rank_k=None, rank_v=None, bucket_off=None, bucket_idx=None, F: int = 0,
+                   lse=None, stream=None) -> None:
+    """Append k_new, v_new [B, HD] at row T-1, then attend over T rows (one fused call)."""
+    B, H, d = q.shape
+    T_cap, r = Ck.shape[1], Ck.shape[2]
+    _check(_lib.ap_decode_step(_p(q), _p(k_new), _p(v_new), _p(Ck), _p(Cv), _p(Bk), _p(Bv),
+                               _bstride(Bk), _p(rank_k), _p(rank_v), _p(bucket_off),
+                               _p(bucket_idx), F, _p(out), _p(lse), B, H, d, T, T_cap, r,
+                               float(sm_scale), _DT[q.dtype], _DT[out.dtype], _p(workspace),
                                workspace.numel() * workspace.element_size(), _stream(stream)))
 
 

@@ -74,6 +74,8 @@ __device__ __forceinline__ uint32_t pack2(float lo, float hi, Tag t) {
 // ---- launchers (defined in the .hip files) -------------------------------------
 struct DecodeArgs {
   const void* q;
+  const void* k_new;   // ap_decode_step only: [B, HD] rows appended at T-1 before attending
+  const void* v_new;
   const void* Ck;
   const void* Cv;
   const void* scale_k;
@@ -117,6 +119,15 @@ bool compact_gemm_applies(const CompactArgs& a);       // matrix-core path (comp
 ap_status launch_compact_gemm(const CompactArgs& a);
 ap_status launch_quantize_i8(const void* C, void* codes, void* scales, int B, int T, int T_cap,
                              int r, hipStream_t stream);
+
+// per-step passes over the bases in 16-bit storage (basis_gemv.hip)
+bool basis_rows_applies(int HD, int B);
+ap_status launch_basis_rows(ap_dtype dt, const void* Bm, int64_t bstride, const void* x,
+                            const void* q, void* C, void* Qp, int B, int H, int Hp, int d, int HD,
+                            int r, int row0, int T_cap, float scale, hipStream_t stream);
+ap_status launch_merge_expand(ap_dtype dt, bool out_f32, const float* part_ml, const float* part_U,
+                              const void* Bv, int64_t bstride, void* out, float* lse, int B, int H,
+                              int d, int r, int nsplit, hipStream_t stream);
 
 size_t select_workspace(int B, int T, int F);
 ap_status launch_select_ranks(const float* mass, int B, int T, int F, const int32_t* group_rank,

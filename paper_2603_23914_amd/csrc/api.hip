@@ -212,6 +212,62 @@ size_t ap_decode_workspace_bytes(int B, int H, int d, int T, int r, ap_dtype dt)
                       : decode_mfma_workspace(B, H, d, T, r, dt);
 }
 
+static ap_status decode_entry(const char* name, const void* q, const void* k_new, const void* v_new,
+                              const void* Ck, const void* Cv, const void* scale_k,
+                              const void* scale_v, const void* Bk, const void* Bv,
+                              int64_t basis_batch_stride, const int32_t* rank_k,
+                              const int32_t* rank_v, const int32_t* bucket_off,
+                              const int32_t* bucket_idx, int F, void* out, float* lse, int B, int H,
+                              int d, int T, int T_cap, int r, float sm_scale, ap_dtype dt,
+                              ap_dtype dt_coef, ap_dtype dt_out, void* workspace, size_t ws_bytes,
+                              void* stream) {
+  clear_error();
+  AP_REQUIRE(q && Ck && Cv && Bk && Bv && out, AP_ERR_INVALID_ARG, "%s: NULL pointer", name);
+  ap_status s = decode_shape_check(B, H, d, T, r, dt, true);
+  if (s != AP_OK) return s;
+  AP_REQUIRE(T <= T_cap, AP_ERR_INVALID_ARG, "%s: T=%d exceeds T_cap=%d", name, T, T_cap);
+  AP_REQUIRE(dt_coef == dt || (dt_coef == AP_I8 && dt == AP_F16), AP_ERR_INVALID_ARG,
+             "%s: dt_coef must equal dt, or be AP_I8 with dt AP_F16", name);
+  AP_REQUIRE(dt_out == dt || dt_out == AP_F32, AP_ERR_INVALID_ARG,
+             "%s: dt_out must equal dt or be AP_F32", name);
+  AP_REQUIRE(sm_scale == sm_scale && sm_scale > 0.f && sm_scale < 1e30f, AP_ERR_INVALID_ARG,
+             "%s: sm_scale must be finite and positive", name);
+  const int64_t HD = (int64_t)H * d;
+  AP_REQUIRE(basis_batch_stride == 0 || basis_batch_stride >= (int64_t)r * HD, AP_ERR_INVALID_ARG,
+             "%s: basis_batch_stride must be 0 or >= r*H*d", name);
+  AP_REQUIRE(aligned(q, 16) && aligned(Ck, 16) && aligned(Cv, 16) && aligned(Bk, 16) &&
+                 aligned(Bv, 16) && aligned(out, 16),
+             AP_ERR_INVALID_ARG, "%s: pointers must be 16-byte aligned", name);
+  if (dt != AP_F32) {
+    AP_REQUIRE(basis_batch_stride % 8 == 0, AP_ERR_INVALID_ARG,
+               "%s: basis_batch_stride must keep rows 16-byte aligned", name);
+  }
+  if (dt_coef == AP_I8) {
+    AP_REQUIRE(scale_k && scale_v, AP_ERR_INVALID_ARG, "%s: AP_I8 needs scale buffers", name);
+  }
+  if (k_new || v_new) {
+    AP_REQUIRE(k_new && v_new && aligned(k_new, 16) && aligned(v_new, 16), AP_ERR_INVALID_ARG,
+               "%s: k_new and v_new must both be given, 16-byte aligned", name);
+    AP_REQUIRE(half_type(dt) && dt_coef == dt, AP_ERR_UNSUPPORTED,
+               "%s: the fused append needs AP_F16 / AP_BF16 coefficients of the same type", name);
+  }
+  const bool ragged = rank_k || rank_v;
+  if (ragged && dt != AP_F32) {
+    AP_REQUIRE(bucket_off && bucket_idx && F >= 1 && F <= 8, AP_ERR_INVALID_ARG,
+               "%s: per-token ranks need the bucket lists of ap_select_ranks "
+               "(1 <= F <= 8) in half precision", name);
+  }
+  size_t need = ap_decode_workspace_bytes(B, H, d, T, r, dt);
+  AP_REQUIRE(workspace && ws_bytes >= need, AP_ERR_WORKSPACE, "%s: workspace %zu bytes, need %zu",
+             name, ws_bytes, need);
+  AP_REQUIRE(aligned(workspace, 256), AP_ERR_INVALID_ARG, "%s: workspace must be 256-byte aligned",
+             name);
+  DecodeArgs a{q, k_new, v_new, Ck, Cv, scale_k, scale_v, Bk, Bv, basis_batch_stride, rank_k, rank_v,
+               bucket_off, bucket_idx, ragged ? F : 0, out, lse, B, H, d, T, T_cap, r, sm_scale,
+               dt, dt_coef, dt_out, workspace, ws_bytes, (hipStream_t)stream};
+  return dt == AP_F32 ? launch_decode_f32(a) : launch_decode_mfma(a);
+}
+
 ap_status ap_decode_attn(const void* q, const void* Ck, const void* Cv, const void* scale_k,
                          const void* scale_v, const void* Bk, const void* Bv,
                          int64_t basis_batch_stride, const int32_t* rank_k, const int32_t* rank_v,
@@ -219,45 +275,22 @@ ap_status ap_decode_attn(const void* q, const void* Ck, const void* Cv, const vo
                          float* lse, int B, int H, int d, int T, int T_cap, int r, float sm_scale,
                          ap_dtype dt, ap_dtype dt_coef, ap_dtype dt_out, void* workspace,
                          size_t ws_bytes, void* stream) {
+  return decode_entry("ap_decode_attn", q, nullptr, nullptr, Ck, Cv, scale_k, scale_v, Bk, Bv,
+                      basis_batch_stride, rank_k, rank_v, bucket_off, bucket_idx, F, out, lse, B, H,
+                      d, T, T_cap, r, sm_scale, dt, dt_coef, dt_out, workspace, ws_bytes, stream);
+}
+
+ap_status ap_decode_step(const void* q, const void* k_new, const void* v_new, void* Ck, void* Cv,
+                         const void* Bk, const void* Bv, int64_t basis_batch_stride,
+                         const int32_t* rank_k, const int32_t* rank_v, const int32_t* bucket_off,
+                         const int32_t* bucket_idx, int F, void* out, float* lse, int B, int H,
+                         int d, int T, int T_cap, int r, float sm_scale, ap_dtype dt,
+                         ap_dtype dt_out, void* workspace, size_t ws_bytes, void* stream) {
   clear_error();
-  AP_REQUIRE(q && Ck && Cv && Bk && Bv && out, AP_ERR_INVALID_ARG, "ap_decode_attn: NULL pointer");
-  ap_status s = decode_shape_check(B, H, d, T, r, dt, true);
-  if (s != AP_OK) return s;
-  AP_REQUIRE(T <= T_cap, AP_ERR_INVALID_ARG, "ap_decode_attn: T=%d exceeds T_cap=%d", T, T_cap);
-  AP_REQUIRE(dt_coef == dt || (dt_coef == AP_I8 && dt == AP_F16), AP_ERR_INVALID_ARG,
-             "ap_decode_attn: dt_coef must equal dt, or be AP_I8 with dt AP_F16");
-  AP_REQUIRE(dt_out == dt || dt_out == AP_F32, AP_ERR_INVALID_ARG,
-             "ap_decode_attn: dt_out must equal dt or be AP_F32");
-  AP_REQUIRE(sm_scale == sm_scale && sm_scale > 0.f && sm_scale < 1e30f, AP_ERR_INVALID_ARG,
-             "ap_decode_attn: sm_scale must be finite and positive");
-  const int64_t HD = (int64_t)H * d;
-  AP_REQUIRE(basis_batch_stride == 0 || basis_batch_stride >= (int64_t)r * HD, AP_ERR_INVALID_ARG,
-             "ap_decode_attn: basis_batch_stride must be 0 or >= r*H*d");
-  AP_REQUIRE(aligned(q, 16) && aligned(Ck, 16) && aligned(Cv, 16) && aligned(Bk, 16) &&
-                 aligned(Bv, 16) && aligned(out, 16),
-             AP_ERR_INVALID_ARG, "ap_decode_attn: pointers must be 16-byte aligned");
-  if (dt != AP_F32) {
-    AP_REQUIRE(basis_batch_stride % 8 == 0, AP_ERR_INVALID_ARG,
-               "ap_decode_attn: basis_batch_stride must keep rows 16-byte aligned");
-  }
-  if (dt_coef == AP_I8) {
-    AP_REQUIRE(scale_k && scale_v, AP_ERR_INVALID_ARG, "ap_decode_attn: AP_I8 needs scale buffers");
-  }
-  const bool ragged = rank_k || rank_v;
-  if (ragged && dt != AP_F32) {
-    AP_REQUIRE(bucket_off && bucket_idx && F >= 1 && F <= 8, AP_ERR_INVALID_ARG,
-               "ap_decode_attn: per-token ranks need the bucket lists of ap_select_ranks "
-               "(1 <= F <= 8) in half precision");
-  }
-  size_t need = ap_decode_workspace_bytes(B, H, d, T, r, dt);
-  AP_REQUIRE(workspace && ws_bytes >= need, AP_ERR_WORKSPACE,
-             "ap_decode_attn: workspace %zu bytes, need %zu", ws_bytes, need);
-  AP_REQUIRE(aligned(workspace, 256), AP_ERR_INVALID_ARG,
-             "ap_decode_attn: workspace must be 256-byte aligned");
-  DecodeArgs a{q, Ck, Cv, scale_k, scale_v, Bk, Bv, basis_batch_stride, rank_k, rank_v,
-               bucket_off, bucket_idx, ragged ? F : 0, out, lse, B, H, d, T, T_cap, r, sm_scale,
-               dt, dt_coef, dt_out, workspace, ws_bytes, (hipStream_t)stream};
-  return dt == AP_F32 ? launch_decode_f32(a) : launch_decode_mfma(a);
+  AP_REQUIRE(k_new && v_new, AP_ERR_INVALID_ARG, "ap_decode_step: NULL pointer");
+  return decode_entry("ap_decode_step", q, k_new, v_new, Ck, Cv, nullptr, nullptr, Bk, Bv,
+                      basis_batch_stride, rank_k, rank_v, bucket_off, bucket_idx, F, out, lse, B, H,
+                      d, T, T_cap, r, sm_scale, dt, dt, dt_out, workspace, ws_bytes, stream);
 }
 
 }  // extern "C"

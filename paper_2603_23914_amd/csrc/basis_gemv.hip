@@ -1,0 +1,291 @@
+// Per-step passes over the decompression matrices (bases) in 16-bit storage: bandwidth-bound
+// matrix-vector products that read every basis byte exactly once, whole rows at a time.
+//
+//   basis_rows<DOT, FOLD>   one pass over Bm [r, HD] of every sequence, each wave streaming
+//                           whole rows (HD contiguous elements, 128-bit loads, several rows
+//                           in flight) and producing, per row j,
+//       DOT :  c[j]     = Bm[j, :] . x                 the appended token's coefficient
+//                                                      (paper Sec. 3.1 projection, one row)
+//       FOLD:  q'[h, j] = scale * Bm[j, head h] . q_h  the query folded through the key basis
+//                                                      (Alg. 1 scores by associativity)
+//                           With both, the append of a key row and the fold of the query
+//                           share one pass over B_k.
+//   merge_expand            combine the token splits of attn_partial and expand through B_v:
+//                           out[h, :] = (sum_s w_s U_s[h, :] / sum_s w_s l_s) . Bv[:, head h]
+//                           (Alg. 1 output by associativity).  A workgroup owns two heads
+//                           (512-byte row segments) and keeps four rows in flight per thread.
+// Products of two 16-bit values are exact in fp32; sums are fp32 (v_dot2c_f32_*).
+#include "ap_common.hpp"
+
+namespace ap {
+namespace {
+
+typedef _Float16 h2_t __attribute__((ext_vector_type(2)));
+typedef __bf16 b2_t __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ float dot2(uint32_t a, uint32_t b, float c, F16Tag) {
+  return __builtin_amdgcn_fdot2(__builtin_bit_cast(h2_t, a), __builtin_bit_cast(h2_t, b), c, false);
+}
+__device__ __forceinline__ float dot2(uint32_t a, uint32_t b, float c, BF16Tag) {
+  return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(b2_t, a), __builtin_bit_cast(b2_t, b), c,
+                                         false);
+}
+template <class Tag>
+__device__ __forceinline__ float dot8(const u32x4_t& a, const u32x4_t& b, float c) {
+#pragma unroll
+  for (int e = 0; e < 4; ++e) c = dot2(a[e], b[e], c, Tag{});
+  return c;
+}
+
+// Sum over groups of `n` consecutive lanes (n = 4, 8, 16 or 32, wave-uniform), every lane of a
+// group receiving the total: DPP butterflies inside a 16-lane row, one shuffle across rows.
+template <int CTRL>
+__device__ __forceinline__ float dpp_f32(float x) {
+  const int v = __builtin_bit_cast(int, x);
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(v, v, CTRL, 0xf, 0xf, false));
+}
+__device__ __forceinline__ float group_sum(float x, int n) {
+  x += dpp_f32<0xB1>(x);                 // quad_perm [1,0,3,2]
+  x += dpp_f32<0x4E>(x);                 // quad_perm [2,3,0,1]
+  if (n >= 8) x += dpp_f32<0x141>(x);    // row_half_mirror: the other quad of an 8-lane group
+  if (n >= 16) x += dpp_f32<0x140>(x);   // row_mirror: the other half of the row
+  if (n >= 32) x += __shfl_xor(x, 16);
+  return x;
+}
+
+constexpr int kRowsPerWave = 4;
+constexpr int kRowsPerWg = 4 * kRowsPerWave;
+
+struct RowsParams {
+  const uint16_t* Bm;     // [B][r][HD] (bstride elements between sequences, 0 = shared)
+  int64_t bstride;
+  const uint16_t* x;      // DOT:  [B][HD] the token row to project
+  const uint16_t* q;      // FOLD: [B][H][d] (= [B][HD])
+  uint16_t* C;            // DOT:  [B][T_cap][r], row `row0` written
+  uint16_t* Qp;           // FOLD: [B][2][Hp][r] hi / lo parts of the folded query
+  int H, Hp, d, HD, r, row0, T_cap;
+  float scale;
+};
+
+template <class Tag>
+__device__ __forceinline__ void split_hi_lo(float x, uint16_t& hi, uint16_t& lo) {
+  hi = f32_to_bits(x, Tag{});
+  lo = f32_to_bits(x - bits_to_f32(hi, Tag{}), Tag{});
+}
+
+// grid (ceil(r / 16), B), 256 threads.  KPC = 512-element passes that cover the hidden axis;
+// RB = rows a wave requests before it uses the first of them.
+template <class Tag, int KPC, int RB, bool DOT, bool FOLD>
+__global__ void __launch_bounds__(256) basis_rows(const RowsParams p) {
+  __shared__ float qtile[FOLD ? 64 : 1][kRowsPerWg + 1];   // [head][row of this workgroup]
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int b = blockIdx.y, j0 = blockIdx.x * kRowsPerWg;
+  const int HD = p.HD, r = p.r;
+  const uint16_t* Bb = p.Bm + (size_t)b * p.bstride;
+
+  // this lane's slices of the vectors: elements 512 pp + 8 lane .. +7 of the hidden axis
+  u32x4_t xs[DOT ? KPC : 1], qs[FOLD ? KPC : 1];
+#pragma unroll
+  for (int pp = 0; pp < KPC; ++pp) {
+    const int e0 = pp * 512 + lane * 8;
+    const u32x4_t z = {0, 0, 0, 0};
+    if (DOT) xs[pp] = e0 < HD ? *(const u32x4_t*)(p.x + (size_t)b * HD + e0) : z;
+    if (FOLD) qs[pp] = e0 < HD ? *(const u32x4_t*)(p.q + (size_t)b * HD + e0) : z;
+  }
+  if (FOLD) {
+    for (int i = tid; i < 64 * (kRowsPerWg + 1); i += 256) (&qtile[0][0])[i] = 0.f;   // padded heads stay 0
+    __syncthreads();
+  }
+
+  const int lanes_per_head = p.d >> 3;            // 4, 8, 16 or 32 lanes share a head
+  const int dshift = 31 - __builtin_clz((unsigned)p.d);   // d is a power of two
+#pragma unroll
+  for (int i0 = 0; i0 < kRowsPerWave; i0 += RB) {
+    u32x4_t rowv[RB][KPC];
+#pragma unroll
+    for (int i = 0; i < RB; ++i) {
+      int j = j0 + w * kRowsPerWave + i0 + i;
+      j = j < r ? j : r - 1;
+      const uint16_t* row = Bb + (size_t)j * HD + lane * 8;
+#pragma unroll
+      for (int pp = 0; pp < KPC; ++pp) {
+        const u32x4_t z = {0, 0, 0, 0};
+        rowv[i][pp] = (pp * 512 + lane * 8) < HD ? *(const u32x4_t*)(row + pp * 512) : z;
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < RB; ++i) {
+      const int jl = w * kRowsPerWave + i0 + i;
+      if (DOT) {
+        float acc = 0.f;
+#pragma unroll
+        for (int pp = 0; pp < KPC; ++pp) acc = dot8<Tag>(rowv[i][pp], xs[pp], acc);
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o);
+        if (lane == 0 && j0 + jl < r)
+          p.C[((size_t)b * p.T_cap + p.row0) * r + j0 + jl] = f32_to_bits(acc, Tag{});
+      }
+      if (FOLD) {
+#pragma unroll
+        for (int pp = 0; pp < KPC; ++pp) {
+          float part = dot8<Tag>(rowv[i][pp], qs[pp], 0.f);
+          part = group_sum(part, lanes_per_head);
+          const int e0 = pp * 512 + lane * 8;
+          if ((lane & (lanes_per_head - 1)) == 0 && e0 < HD) qtile[e0 >> dshift][jl] = part * p.scale;
+        }
+      }
+    }
+  }
+  if (FOLD) {
+    __syncthreads();
+    // 16 consecutive rank positions of one head leave as one 32-byte segment per part
+    for (int i = tid; i < p.Hp * kRowsPerWg; i += 256) {
+      const int h = i / kRowsPerWg, jl = i - h * kRowsPerWg;
+      if (j0 + jl < r) {
+        uint16_t hi, lo;
+        split_hi_lo<Tag>(qtile[h][jl], hi, lo);
+        p.Qp[(((size_t)b * 2 + 0) * p.Hp + h) * r + j0 + jl] = hi;
+        p.Qp[(((size_t)b * 2 + 1) * p.Hp + h) * r + j0 + jl] = lo;
+      }
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// merge_expand: grid (ceil(H / 2), B), 256 threads.
+// ------------------------------------------------------------------------------------------
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+constexpr float kLn2 = 0.6931471805599453f;
+
+template <class Tag, bool OUT_F32>
+__global__ void __launch_bounds__(256)
+merge_expand(const float* __restrict__ part_ml, const float* __restrict__ part_U,
+             const uint16_t* __restrict__ Bv, int64_t bstride, void* __restrict__ out,
+             float* __restrict__ lse, int H, int d, int r, int nsplit) {
+  extern __shared__ __attribute__((aligned(16))) char smem_me[];
+  float* ustar = (float*)smem_me;          // [2][r]
+  float* red = ustar + 2 * r;              // [rows][2 d]
+  const int h0 = blockIdx.x * 2, b = blockIdx.y, tid = threadIdx.x;
+  const int nh = H - h0 < 2 ? H - h0 : 2;  // heads of this workgroup
+  // ---- merged, normalised coefficient sums of the two heads
+  for (int hh = 0; hh < nh; ++hh) {
+    const size_t pb = (size_t)b * nsplit * H + h0 + hh;    // + s*H
+    float mstar = -INFINITY;
+    for (int s = 0; s < nsplit; ++s) mstar = fmaxf(mstar, part_ml[(pb + (size_t)s * H) * 2]);
+    float L = 0.f;
+    for (int s = 0; s < nsplit; ++s)
+      L += part_ml[(pb + (size_t)s * H) * 2 + 1] * fast_exp2(part_ml[(pb + (size_t)s * H) * 2] - mstar);
+    const float invL = 1.0f / L;
+    for (int j = tid; j < r; j += 256) {
+      float acc = 0.f;
+      for (int s = 0; s < nsplit; ++s) {
+        const float ws = fast_exp2(part_ml[(pb + (size_t)s * H) * 2] - mstar);
+        acc = fmaf(ws, part_U[(pb + (size_t)s * H) * r + j], acc);
+      }
+      ustar[hh * r + j] = acc * invL;
+    }
+    if (tid == 0 && lse) lse[(size_t)b * H + h0 + hh] = (mstar + log2f(L)) * kLn2;
+  }
+  __syncthreads();
+  // ---- expansion: thread (rg, cc) owns 8 columns of the 2d-wide slice and rows rg, rg+rows, ..
+  const int tpr = (2 * d) >> 3;            // threads per row segment: 8 .. 64
+  const int rows = 256 / tpr;
+  const int rg = tid / tpr, cc = tid - rg * tpr;
+  const bool live = cc * 8 < nh * d;       // an odd head count leaves the upper half idle
+  const float* us = ustar + (cc * 8 >= d ? r : 0);
+  const size_t HD = (size_t)H * d;
+  const uint16_t* Bb = Bv + (size_t)b * bstride + (size_t)h0 * d + cc * 8;
+  float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  if (live) {
+    int j = rg;
+    for (; j + 3 * rows < r; j += 4 * rows) {              // four rows in flight
+      u32x4_t wv[4];
+#pragma unroll
+      for (int k = 0; k < 4; ++k) wv[k] = *(const u32x4_t*)(Bb + (size_t)(j + k * rows) * HD);
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const float u = us[j + k * rows];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          acc[2 * e] = fmaf(u, lo_to_f32(wv[k][e], Tag{}), acc[2 * e]);
+          acc[2 * e + 1] = fmaf(u, hi_to_f32(wv[k][e], Tag{}), acc[2 * e + 1]);
+        }
+      }
+    }
+    for (; j < r; j += rows) {
+      const u32x4_t wv = *(const u32x4_t*)(Bb + (size_t)j * HD);
+      const float u = us[j];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        acc[2 * e] = fmaf(u, lo_to_f32(wv[e], Tag{}), acc[2 * e]);
+        acc[2 * e + 1] = fmaf(u, hi_to_f32(wv[e], Tag{}), acc[2 * e + 1]);
+      }
+    }
+  }
+#pragma unroll
+  for (int e = 0; e < 8; ++e) red[rg * 2 * d + cc * 8 + e] = acc[e];
+  __syncthreads();
+  for (int i = tid; i < nh * d; i += 256) {
+    float sum = 0.f;
+    for (int k = 0; k < rows; ++k) sum += red[k * 2 * d + i];
+    const size_t o = ((size_t)b * H + h0) * d + i;
+    if (OUT_F32) ((float*)out)[o] = sum;
+    else ((uint16_t*)out)[o] = f32_to_bits(sum, Tag{});
+  }
+}
+
+template <class Tag, bool DOT, bool FOLD>
+ap_status launch_rows(const RowsParams& p, int B, hipStream_t stream) {
+  const dim3 grid((p.r + kRowsPerWg - 1) / kRowsPerWg, B);
+  const int kpc = (p.HD + 511) / 512;
+#define AP_ROWS(K, RB)                                                                       \
+  if (kpc <= K) {                                                                            \
+    hipLaunchKernelGGL((basis_rows<Tag, K, RB, DOT, FOLD>), grid, dim3(256), 0, stream, p);  \
+    return AP_OK;                                                                            \
+  }
+  AP_ROWS(2, 4) AP_ROWS(4, 4) AP_ROWS(8, 2) AP_ROWS(10, 2) AP_ROWS(16, 1)
+#undef AP_ROWS
+  set_error("basis pass: H*d=%d exceeds 8192", p.HD);
+  return AP_ERR_UNSUPPORTED;
+}
+
+}  // namespace
+
+bool basis_rows_applies(int HD, int B) { return HD % 8 == 0 && HD <= 8192 && B <= 65535; }
+
+// Append (x != null) and / or fold (q != null) in one pass over Bm.
+ap_status launch_basis_rows(ap_dtype dt, const void* Bm, int64_t bstride, const void* x,
+                            const void* q, void* C, void* Qp, int B, int H, int Hp, int d, int HD,
+                            int r, int row0, int T_cap, float scale, hipStream_t stream) {
+  RowsParams p{(const uint16_t*)Bm, bstride, (const uint16_t*)x, (const uint16_t*)q,
+               (uint16_t*)C, (uint16_t*)Qp, H, Hp, d, HD, r, row0, T_cap, scale};
+  const bool dot = x != nullptr, fold = q != nullptr;
+  if (dt == AP_F16) {
+    if (dot && fold) return launch_rows<F16Tag, true, true>(p, B, stream);
+    if (dot) return launch_rows<F16Tag, true, false>(p, B, stream);
+    return launch_rows<F16Tag, false, true>(p, B, stream);
+  }
+  if (dot && fold) return launch_rows<BF16Tag, true, true>(p, B, stream);
+  if (dot) return launch_rows<BF16Tag, true, false>(p, B, stream);
+  return launch_rows<BF16Tag, false, true>(p, B, stream);
+}
+
+ap_status launch_merge_expand(ap_dtype dt, bool out_f32, const float* part_ml, const float* part_U,
+                              const void* Bv, int64_t bstride, void* out, float* lse, int B, int H,
+                              int d, int r, int nsplit, hipStream_t stream) {
+  const int rows = 256 / ((2 * d) >> 3);
+  const size_t lds = ((size_t)2 * r + (size_t)rows * 2 * d) * 4;
+  const dim3 grid((H + 1) / 2, B);
+  const uint16_t* bv = (const uint16_t*)Bv;
+  if (dt == AP_F16) {
+    if (out_f32) hipLaunchKernelGGL((merge_expand<F16Tag, true>), grid, dim3(256), lds, stream, part_ml, part_U, bv, bstride, out, lse, H, d, r, nsplit);
+    else hipLaunchKernelGGL((merge_expand<F16Tag, false>), grid, dim3(256), lds, stream, part_ml, part_U, bv, bstride, out, lse, H, d, r, nsplit);
+  } else {
+    if (out_f32) hipLaunchKernelGGL((merge_expand<BF16Tag, true>), grid, dim3(256), lds, stream, part_ml, part_U, bv, bstride, out, lse, H, d, r, nsplit);
+    else hipLaunchKernelGGL((merge_expand<BF16Tag, false>), grid, dim3(256), lds, stream, part_ml, part_U, bv, bstride, out, lse, H, d, r, nsplit);
+  }
+  return AP_OK;
+}
+
+}  // namespace ap

@@ -186,6 +186,12 @@ ap_status run_compact(const CompactArgs& a) {
 
 ap_status launch_compact(const CompactArgs& a) {
   if (compact_gemm_applies(a)) return launch_compact_gemm(a);
+  if (a.n == 1 && a.dt_out == a.dt_in && (a.dt_in == AP_F16 || a.dt_in == AP_BF16) &&
+      basis_rows_applies(a.HD, a.B)) {
+    ap_status st = launch_basis_rows(a.dt_in, a.Bm, a.basis_batch_stride, a.X, nullptr, a.C, nullptr,
+                                     a.B, 0, 0, 8, a.HD, a.r, a.row0, a.T_cap, 1.0f, a.stream);
+    return st != AP_OK ? st : check_launch("ap_compact");
+  }
   AP_REQUIRE(a.B <= 65535 && (a.n + 3) / 4 <= 65535, AP_ERR_UNSUPPORTED,
              "ap_compact: B and n/4 must be <= 65535");
   switch (a.dt_in) {

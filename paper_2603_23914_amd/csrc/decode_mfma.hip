@@ -2,11 +2,11 @@
 //
 // Paper Alg. 1 (partial decompression, scores, softmax, output) with the
 // decompression matrices absorbed by associativity, so K and V are never rebuilt:
-//   fold:    q'[h,j]  = sm_scale*log2(e) * sum_i Bk[j, h*d+i] q[h,i]      (kernel fold_query)
+//   fold:    q'[h,j]  = sm_scale*log2(e) * sum_i Bk[j, h*d+i] q[h,i]      (basis_gemv.hip)
 //   scores:  s[h,t]   = sum_{j<rk_t} Ck[t,j] q'[h,j]                       (kernel attn_partial)
 //   softmax: online, base 2, fp32, per split of the token axis
 //   sum:     u[h,j]   = sum_{t: rv_t>j} p[h,t] Cv[t,j]
-//   merge:   splits combined with their (max, sum) pairs                   (kernel merge_expand)
+//   merge:   splits combined with their (max, sum) pairs                   (basis_gemv.hip)
 //   expand:  out[h,i] = sum_j u[h,j] Bv[j, h*d+i]
 //
 // attn_partial is the HBM-bound kernel.  One workgroup (8 waves) owns one (sequence, token
@@ -122,54 +122,6 @@ __device__ __forceinline__ u32x4_t deq_row8(uint32_t c0, uint32_t c1, uint32_t s
   o[3] = deq2(__builtin_amdgcn_perm(k, x1, 0x04030402u), scale2);
   return o;
 }
-
-// ------------------------------------------------------------------------------------------
-// fold_query: grid (Hp, B), 256 threads.  Qp[b][0][h][j] = hi, Qp[b][1][h][j] = lo of
-// sm_scale*log2e * (Bk[b][j, head h] . q[b,h]);  heads >= H are zero rows.
-// ------------------------------------------------------------------------------------------
-template <class Tag>
-__global__ void __launch_bounds__(256)
-fold_query(const uint16_t* __restrict__ q, const uint16_t* __restrict__ Bk, int64_t bstride,
-           uint16_t* __restrict__ Qp, int H, int Hp, int d, int r, float scale) {
-  const int h = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
-  uint16_t* hi_row = Qp + (((size_t)b * 2 + 0) * Hp + h) * r;
-  uint16_t* lo_row = Qp + (((size_t)b * 2 + 1) * Hp + h) * r;
-  if (h >= H) {
-    for (int j = tid; j < r; j += 256) { hi_row[j] = 0; lo_row[j] = 0; }
-    return;
-  }
-  const int tpr = d >> 3;            // threads per basis row (power of two, <= 32)
-  const int rows = 256 / tpr;
-  const int rg = tid / tpr, cc = tid - rg * tpr;
-  const size_t HD = (size_t)H * d;
-  float qv[8];
-  {
-    const u32x4_t w = *(const u32x4_t*)(q + ((size_t)b * H + h) * d + cc * 8);
-#pragma unroll
-    for (int e = 0; e < 4; ++e) { qv[2 * e] = lo_to_f32(w[e], Tag{}); qv[2 * e + 1] = hi_to_f32(w[e], Tag{}); }
-  }
-  const uint16_t* Bb = Bk + (size_t)b * bstride + (size_t)h * d + cc * 8;
-  for (int j0 = 0; j0 < r; j0 += rows) {
-    const int j = j0 + rg;
-    float acc = 0.f;
-    if (j < r) {
-      const u32x4_t w = *(const u32x4_t*)(Bb + (size_t)j * HD);
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        acc = fmaf(lo_to_f32(w[e], Tag{}), qv[2 * e], acc);
-        acc = fmaf(hi_to_f32(w[e], Tag{}), qv[2 * e + 1], acc);
-      }
-    }
-    for (int o = tpr >> 1; o > 0; o >>= 1) acc += __shfl_xor(acc, o);
-    if (cc == 0 && j < r) {
-      uint16_t hi, lo;
-      split_hi_lo<Tag>(acc * scale, hi, lo);
-      hi_row[j] = hi;
-      lo_row[j] = lo;
-    }
-  }
-}
-
 
 // ------------------------------------------------------------------------------------------
 // tile kernels (unrolled to the compile-time maximum, left early on the run-time count)
@@ -939,64 +891,6 @@ attn_partial(const AttnParams p) {
 }
 
 // ------------------------------------------------------------------------------------------
-// merge_expand: grid (H, B), 256 threads.  Combine the splits of head h, then
-// out[b,h,:] = u . Bv[b][:, head h].
-// ------------------------------------------------------------------------------------------
-template <class Tag, bool OUT_F32>
-__global__ void __launch_bounds__(256)
-merge_expand(const float* __restrict__ part_ml, const float* __restrict__ part_U,
-             const uint16_t* __restrict__ Bv, int64_t bstride, void* __restrict__ out,
-             float* __restrict__ lse, int H, int d, int r, int nsplit) {
-  extern __shared__ __attribute__((aligned(16))) char smem_me[];
-  float* ustar = (float*)smem_me;          // [r]
-  float* red = ustar + r;                  // [rows][d]
-  const int h = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
-  const size_t pb = (size_t)b * nsplit * H + h;    // + s*H
-  float mstar = -INFINITY;
-  for (int s = 0; s < nsplit; ++s) mstar = fmaxf(mstar, part_ml[(pb + (size_t)s * H) * 2]);
-  float L = 0.f;
-  for (int s = 0; s < nsplit; ++s) {
-    const float ms = part_ml[(pb + (size_t)s * H) * 2];
-    const float ls = part_ml[(pb + (size_t)s * H) * 2 + 1];
-    L += ls * fast_exp2(ms - mstar);
-  }
-  const float invL = 1.0f / L;
-  for (int j = tid; j < r; j += 256) {
-    float acc = 0.f;
-    for (int s = 0; s < nsplit; ++s) {
-      const float ws = fast_exp2(part_ml[(pb + (size_t)s * H) * 2] - mstar);
-      acc = fmaf(ws, part_U[(pb + (size_t)s * H) * r + j], acc);
-    }
-    ustar[j] = acc * invL;
-  }
-  __syncthreads();
-  const int tpr = d >> 3, rows = 256 / tpr;
-  const int rg = tid / tpr, cc = tid - rg * tpr;
-  const size_t HD = (size_t)H * d;
-  const uint16_t* Bb = Bv + (size_t)b * bstride + (size_t)h * d + cc * 8;
-  float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-  for (int j = rg; j < r; j += rows) {
-    const u32x4_t wv = *(const u32x4_t*)(Bb + (size_t)j * HD);
-    const float u = ustar[j];
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      acc[2 * e] = fmaf(u, lo_to_f32(wv[e], Tag{}), acc[2 * e]);
-      acc[2 * e + 1] = fmaf(u, hi_to_f32(wv[e], Tag{}), acc[2 * e + 1]);
-    }
-  }
-#pragma unroll
-  for (int e = 0; e < 8; ++e) red[rg * d + cc * 8 + e] = acc[e];
-  __syncthreads();
-  for (int i = tid; i < d; i += 256) {
-    float sum = 0.f;
-    for (int k = 0; k < rows; ++k) sum += red[k * d + i];
-    if (OUT_F32) ((float*)out)[((size_t)b * H + h) * d + i] = sum;
-    else ((uint16_t*)out)[((size_t)b * H + h) * d + i] = f32_to_bits(sum, Tag{});
-  }
-  if (tid == 0 && lse) lse[(size_t)b * H + h] = (mstar + log2f(L)) * kLn2;
-}
-
-// ------------------------------------------------------------------------------------------
 // host side
 // ------------------------------------------------------------------------------------------
 int device_cus() {
@@ -1124,9 +1018,16 @@ ap_status run_decode(const DecodeArgs& a) {
   uint16_t* Qp = (uint16_t*)(ws + wl.qp);
   float* ml = (float*)(ws + wl.ml);
   float* U = (float*)(ws + wl.u);
-  hipLaunchKernelGGL(fold_query<Tag>, dim3(Hp, a.B), dim3(256), 0, a.stream, (const uint16_t*)a.q,
-                     (const uint16_t*)a.Bk, a.basis_batch_stride, Qp, a.H, Hp, a.d, a.r,
-                     a.sm_scale * kLog2e);
+  // fold (and, for a fused step, the append of the key row in the same pass over B_k)
+  ap_status st = launch_basis_rows(a.dt, a.Bk, a.basis_batch_stride, a.k_new, a.q, (void*)a.Ck, Qp,
+                                   a.B, a.H, Hp, a.d, a.H * a.d, a.r, a.T - 1, a.T_cap,
+                                   a.sm_scale * kLog2e, a.stream);
+  if (st != AP_OK) return st;
+  if (a.v_new) {
+    st = launch_basis_rows(a.dt, a.Bv, a.basis_batch_stride, a.v_new, nullptr, (void*)a.Cv, nullptr,
+                           a.B, 0, 0, 8, a.H * a.d, a.r, a.T - 1, a.T_cap, 1.0f, a.stream);
+    if (st != AP_OK) return st;
+  }
   AttnParams p{};
   p.Qp = Qp;
   p.Ck = (const uint16_t*)a.Ck;
@@ -1148,17 +1049,12 @@ ap_status run_decode(const DecodeArgs& a) {
   if (const char* e = getenv("AP_DEBUG_ATTN")) p.dbg = atoi(e);
   p.dbg_out = (unsigned long long*)U;   // timers overwrite the head of part_U (debug only)
   prof_mark(a.stream, true);
-  ap_status st = dispatch_attn<Tag, SPLIT>(p, a.B, a.stream);
+  st = dispatch_attn<Tag, SPLIT>(p, a.B, a.stream);
   prof_mark(a.stream, false);
   if (st != AP_OK) return st;
-  const int rows = 256 / (a.d / 8);
-  const size_t lds = ((size_t)a.r + (size_t)rows * a.d) * 4;
-  if (a.dt_out == AP_F32)
-    hipLaunchKernelGGL((merge_expand<Tag, true>), dim3(a.H, a.B), dim3(256), lds, a.stream, ml, U,
-                       (const uint16_t*)a.Bv, a.basis_batch_stride, a.out, a.lse, a.H, a.d, a.r, S);
-  else
-    hipLaunchKernelGGL((merge_expand<Tag, false>), dim3(a.H, a.B), dim3(256), lds, a.stream, ml, U,
-                       (const uint16_t*)a.Bv, a.basis_batch_stride, a.out, a.lse, a.H, a.d, a.r, S);
+  st = launch_merge_expand(a.dt, a.dt_out == AP_F32, ml, U, a.Bv, a.basis_batch_stride, a.out, a.lse,
+                           a.B, a.H, a.d, a.r, S, a.stream);
+  if (st != AP_OK) return st;
   return check_launch("ap_decode_attn");
 }
 
@@ -1172,6 +1068,8 @@ size_t decode_mfma_workspace(int B, int H, int d, int T, int r, ap_dtype dt) {
 
 ap_status launch_decode_mfma(const DecodeArgs& a) {
   AP_REQUIRE(a.B <= 65535, AP_ERR_UNSUPPORTED, "ap_decode_attn: B must be <= 65535");
+  AP_REQUIRE(basis_rows_applies(a.H * a.d, a.B), AP_ERR_UNSUPPORTED,
+             "ap_decode_attn: H*d must be a multiple of 8 and <= 8192");
   AP_REQUIRE(a.dt_coef != AP_I8 || (!a.rank_k && !a.rank_v), AP_ERR_UNSUPPORTED,
              "ap_decode_attn: int8 coefficients with per-token ranks are not implemented");
   AP_REQUIRE((int64_t)a.T_cap * a.r * 2 < (1ll << 32), AP_ERR_UNSUPPORTED,

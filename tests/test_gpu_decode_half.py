@@ -83,3 +83,36 @@ def test_decode_peaked_softmax_large_logits():
     ref = oracle_out(dtype, q, case.Ck, case.Cv, case.Bk, case.Bv, 200)
     got = run_half(dtype, q, case.Ck, case.Cv, case.Bk, case.Bv, 200)
     assert_close(got, ref, dtype, "peaked softmax")
+
+
+@pytest.mark.parametrize("dtype,B,H,d,r,T0", [("bf16", 2, 40, 128, 640, 150), ("f16", 3, 32, 128, 512, 65),
+                                              ("f16", 2, 8, 64, 192, 31)])
+def test_decode_step_equals_compact_then_attend(dtype, B, H, d, r, T0):
+    """ap_decode_step (append fused with the fold) gives the bits of ap_compact + ap_decode_attn."""
+    from paper_2603_23914_amd import binding as ap
+    case = wl.decode_case(dtype, B, H, d, r, T0, steps=2, seed=21, append=True)
+    P = lambda x: oracle.promote(x, dtype)
+    kn, vn = wl.step_new_token(case, 0, P(case.Bk), P(case.Bv))
+    q = wl.step_query(case, 0)
+    T = T0 + 1
+    res = []
+    for fused in (False, True):
+        dq, dCk, dCv, dBk, dBv, dkn, dvn = (to_dev(x, dtype) for x in (q, case.Ck, case.Cv, case.Bk, case.Bv, kn, vn))
+        out = torch.empty((B, H, d), dtype=torch.float32, device="cuda")
+        ws = workspace(ap.ap_decode_workspace_bytes(B, H, d, T, r, ap._DT[TORCH_DT[dtype]]))
+        if fused:
+            ap.ap_decode_step(dq, dkn, dvn, dCk, dCv, dBk, dBv, out, ws, T=T, sm_scale=1.0 / math.sqrt(d))
+        else:
+            ap.ap_compact(dkn[:, None, :].contiguous(), dvn[:, None, :].contiguous(), dBk, dBv, dCk, dCv, n=1, row0=T0)
+            ap.ap_decode_attn(dq, dCk, dCv, dBk, dBv, out, ws, T=T, sm_scale=1.0 / math.sqrt(d))
+        torch.cuda.synchronize()
+        res.append((out.cpu().numpy(), dCk.view(torch.int16).cpu().numpy(), dCv.view(torch.int16).cpu().numpy()))
+    for a, b in zip(res[0], res[1]):
+        assert (a == b).all()
+    # and the step is right: oracle on the stored bits
+    Ck_h = res[1][1].view(np.uint16) if dtype == "bf16" else res[1][1].view(np.float16)
+    Cv_h = res[1][2].view(np.uint16) if dtype == "bf16" else res[1][2].view(np.float16)
+    ref = oracle.decode_attn_batched(P(q), P(Ck_h), P(Cv_h), P(case.Bk), P(case.Bv), T, absorbed=True)
+    assert_close(res[1][0].astype(np.float64), ref, dtype, "fused step")
+    c_ref = oracle.compact(P(kn)[0][None], P(case.Bk)[0])[0]
+    assert np.abs(P(Ck_h)[0, T0] - c_ref).max() <= 2.0 ** -7 * np.abs(c_ref).max()
