@@ -53,9 +53,6 @@ __device__ __forceinline__ float group_sum(float x, int n) {
   return x;
 }
 
-constexpr int kRowsPerWave = 4;
-constexpr int kRowsPerWg = 4 * kRowsPerWave;
-
 struct RowsParams {
   const uint16_t* Bm;     // [B][r][HD] (bstride elements between sequences, 0 = shared)
   int64_t bstride;
@@ -64,6 +61,7 @@ struct RowsParams {
   uint16_t* C;            // DOT:  [B][T_cap][r], row `row0` written
   uint16_t* Qp;           // FOLD: [B][2][Hp][r] hi / lo parts of the folded query
   int H, Hp, d, HD, r, row0, T_cap;
+  int rpw;                // consecutive rows per wave (a workgroup owns 4 * rpw rows)
   float scale;
 };
 
@@ -73,18 +71,34 @@ __device__ __forceinline__ void split_hi_lo(float x, uint16_t& hi, uint16_t& lo)
   lo = f32_to_bits(x - bits_to_f32(hi, Tag{}), Tag{});
 }
 
-// grid (ceil(r / 16), B), 256 threads.  KPC = 512-element passes that cover the hidden axis;
-// RB = rows a wave requests before it uses the first of them.
-template <class Tag, int KPC, int RB, bool DOT, bool FOLD>
+// grid (ceil(r / (4 rpw)), B), 256 threads.  KPC = 512-element passes that cover the hidden
+// axis; a wave walks its rows through a ring of NBUF row buffers in registers, so NBUF - 1
+// rows (HD * 2 bytes each) are in flight while one is reduced.
+template <class Tag, int KPC, int NBUF, bool DOT, bool FOLD>
 __global__ void __launch_bounds__(256) basis_rows(const RowsParams p) {
-  __shared__ float qtile[FOLD ? 64 : 1][kRowsPerWg + 1];   // [head][row of this workgroup]
+  extern __shared__ __attribute__((aligned(16))) float qtile[];   // FOLD: [Hp][4 rpw + 1]
   const int tid = threadIdx.x, lane = tid & 63;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int b = blockIdx.y, j0 = blockIdx.x * kRowsPerWg;
+  const int rpw = p.rpw, rows_wg = 4 * rpw, pitch = rows_wg + 1;
+  const int b = blockIdx.y, j0 = blockIdx.x * rows_wg;
   const int HD = p.HD, r = p.r;
   const uint16_t* Bb = p.Bm + (size_t)b * p.bstride;
-
-  // this lane's slices of the vectors: elements 512 pp + 8 lane .. +7 of the hidden axis
+  u32x4_t buf[NBUF][KPC];
+  // passes beyond the hidden axis re-read the lane's first chunk (their vector slices are
+  // zero), so the loads carry no branches and issue back to back
+  int eoff[KPC];
+#pragma unroll
+  for (int pp = 0; pp < KPC; ++pp) eoff[pp] = (pp * 512 + lane * 8) < HD ? pp * 512 + lane * 8 : lane * 8;
+  auto load_row = [&](u32x4_t (&dst)[KPC], int i) {         // row i of this wave
+    int j = j0 + w * rpw + i;
+    j = j < r ? j : r - 1;                                  // rows past the end: harmless repeats
+    const uint16_t* row = Bb + (size_t)j * HD;
+#pragma unroll
+    for (int pp = 0; pp < KPC; ++pp) dst[pp] = *(const u32x4_t*)(row + eoff[pp]);
+  };
+  // this lane's slices of the vectors: elements 512 pp + 8 lane .. +7 of the hidden axis.
+  // They are requested BEFORE the first rows, so that a row's arrival implies theirs and no
+  // wait on them ever drains the row ring.
   u32x4_t xs[DOT ? KPC : 1], qs[FOLD ? KPC : 1];
 #pragma unroll
   for (int pp = 0; pp < KPC; ++pp) {
@@ -93,58 +107,59 @@ __global__ void __launch_bounds__(256) basis_rows(const RowsParams p) {
     if (DOT) xs[pp] = e0 < HD ? *(const u32x4_t*)(p.x + (size_t)b * HD + e0) : z;
     if (FOLD) qs[pp] = e0 < HD ? *(const u32x4_t*)(p.q + (size_t)b * HD + e0) : z;
   }
+  const int last = rpw - 1;
+#pragma unroll
+  for (int u = 0; u + 1 < NBUF; ++u) load_row(buf[u], u < last ? u : last);
   if (FOLD) {
-    for (int i = tid; i < 64 * (kRowsPerWg + 1); i += 256) (&qtile[0][0])[i] = 0.f;   // padded heads stay 0
+    for (int i = tid; i < p.Hp * pitch; i += 256) qtile[i] = 0.f;   // padded heads stay 0
     __syncthreads();
   }
-
   const int lanes_per_head = p.d >> 3;            // 4, 8, 16 or 32 lanes share a head
   const int dshift = 31 - __builtin_clz((unsigned)p.d);   // d is a power of two
+
+  auto reduce_row = [&](const u32x4_t (&row)[KPC], int i) {
+    const int jl = w * rpw + i;
+    const bool live = i < rpw && j0 + jl < r;
+    if (DOT) {
+      float acc = 0.f;
 #pragma unroll
-  for (int i0 = 0; i0 < kRowsPerWave; i0 += RB) {
-    u32x4_t rowv[RB][KPC];
+      for (int pp = 0; pp < KPC; ++pp) acc = dot8<Tag>(row[pp], xs[pp], acc);
 #pragma unroll
-    for (int i = 0; i < RB; ++i) {
-      int j = j0 + w * kRowsPerWave + i0 + i;
-      j = j < r ? j : r - 1;
-      const uint16_t* row = Bb + (size_t)j * HD + lane * 8;
+      for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o);
+      if (lane == 0 && live)
+        p.C[((size_t)b * p.T_cap + p.row0) * r + j0 + jl] = f32_to_bits(acc, Tag{});
+    }
+    if (FOLD) {
 #pragma unroll
       for (int pp = 0; pp < KPC; ++pp) {
-        const u32x4_t z = {0, 0, 0, 0};
-        rowv[i][pp] = (pp * 512 + lane * 8) < HD ? *(const u32x4_t*)(row + pp * 512) : z;
+        float part = dot8<Tag>(row[pp], qs[pp], 0.f);
+        part = group_sum(part, lanes_per_head);
+        const int e0 = pp * 512 + lane * 8;
+        if ((lane & (lanes_per_head - 1)) == 0 && e0 < HD && live)
+          qtile[(e0 >> dshift) * pitch + jl] = part * p.scale;
       }
     }
+  };
+  // The ring advances without branches: every slot of the unrolled body requests a row and
+  // reduces one (past the wave's last row the request repeats that row, a cache hit, and the
+  // reduction's result is dropped), so the compiler's wait counts stay exact.
+  const int rpw_pad = (rpw + NBUF - 1) / NBUF * NBUF;
+  for (int i = 0; i < rpw_pad; i += NBUF) {
 #pragma unroll
-    for (int i = 0; i < RB; ++i) {
-      const int jl = w * kRowsPerWave + i0 + i;
-      if (DOT) {
-        float acc = 0.f;
-#pragma unroll
-        for (int pp = 0; pp < KPC; ++pp) acc = dot8<Tag>(rowv[i][pp], xs[pp], acc);
-#pragma unroll
-        for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o);
-        if (lane == 0 && j0 + jl < r)
-          p.C[((size_t)b * p.T_cap + p.row0) * r + j0 + jl] = f32_to_bits(acc, Tag{});
-      }
-      if (FOLD) {
-#pragma unroll
-        for (int pp = 0; pp < KPC; ++pp) {
-          float part = dot8<Tag>(rowv[i][pp], qs[pp], 0.f);
-          part = group_sum(part, lanes_per_head);
-          const int e0 = pp * 512 + lane * 8;
-          if ((lane & (lanes_per_head - 1)) == 0 && e0 < HD) qtile[e0 >> dshift][jl] = part * p.scale;
-        }
-      }
+    for (int u = 0; u < NBUF; ++u) {
+      const int nx = i + u + NBUF - 1;
+      load_row(buf[(u + NBUF - 1) % NBUF], nx < last ? nx : last);
+      reduce_row(buf[u], i + u);
     }
   }
   if (FOLD) {
     __syncthreads();
-    // 16 consecutive rank positions of one head leave as one 32-byte segment per part
-    for (int i = tid; i < p.Hp * kRowsPerWg; i += 256) {
-      const int h = i / kRowsPerWg, jl = i - h * kRowsPerWg;
+    // consecutive rank positions of one head leave as one contiguous segment per part
+    for (int i = tid; i < p.Hp * rows_wg; i += 256) {
+      const int h = i / rows_wg, jl = i - h * rows_wg;
       if (j0 + jl < r) {
         uint16_t hi, lo;
-        split_hi_lo<Tag>(qtile[h][jl], hi, lo);
+        split_hi_lo<Tag>(qtile[h * pitch + jl], hi, lo);
         p.Qp[(((size_t)b * 2 + 0) * p.Hp + h) * r + j0 + jl] = hi;
         p.Qp[(((size_t)b * 2 + 1) * p.Hp + h) * r + j0 + jl] = lo;
       }
@@ -236,15 +251,22 @@ merge_expand(const float* __restrict__ part_ml, const float* __restrict__ part_U
 }
 
 template <class Tag, bool DOT, bool FOLD>
-ap_status launch_rows(const RowsParams& p, int B, hipStream_t stream) {
-  const dim3 grid((p.r + kRowsPerWg - 1) / kRowsPerWg, B);
+ap_status launch_rows(RowsParams p, int B, hipStream_t stream) {
+  // about two workgroups per CU in one round: rows per wave from the total row count
+  int rpw = (int)(((int64_t)B * p.r + 2047) / 2048);
+  rpw = rpw < 4 ? 4 : (rpw > 32 ? 32 : rpw);
+  p.rpw = rpw;
+  const int rows_wg = 4 * rpw;
+  const dim3 grid((p.r + rows_wg - 1) / rows_wg, B);
+  const size_t lds = FOLD ? (size_t)p.Hp * (rows_wg + 1) * 4 : 0;
   const int kpc = (p.HD + 511) / 512;
-#define AP_ROWS(K, RB)                                                                       \
-  if (kpc <= K) {                                                                            \
-    hipLaunchKernelGGL((basis_rows<Tag, K, RB, DOT, FOLD>), grid, dim3(256), 0, stream, p);  \
-    return AP_OK;                                                                            \
+#define AP_ROWS(K, NB)                                                                        \
+  if (kpc <= K) {                                                                             \
+    hipLaunchKernelGGL((basis_rows<Tag, K, NB, DOT, FOLD>), grid, dim3(256), lds, stream, p); \
+    return AP_OK;                                                                             \
   }
-  AP_ROWS(2, 4) AP_ROWS(4, 4) AP_ROWS(8, 2) AP_ROWS(10, 2) AP_ROWS(16, 1)
+  AP_ROWS(2, 3) AP_ROWS(4, 3) AP_ROWS(8, 3) AP_ROWS(10, 3)
+  AP_ROWS(16, (DOT && FOLD) ? 1 : 2)
 #undef AP_ROWS
   set_error("basis pass: H*d=%d exceeds 8192", p.HD);
   return AP_ERR_UNSUPPORTED;
@@ -259,7 +281,7 @@ ap_status launch_basis_rows(ap_dtype dt, const void* Bm, int64_t bstride, const 
                             const void* q, void* C, void* Qp, int B, int H, int Hp, int d, int HD,
                             int r, int row0, int T_cap, float scale, hipStream_t stream) {
   RowsParams p{(const uint16_t*)Bm, bstride, (const uint16_t*)x, (const uint16_t*)q,
-               (uint16_t*)C, (uint16_t*)Qp, H, Hp, d, HD, r, row0, T_cap, scale};
+               (uint16_t*)C, (uint16_t*)Qp, H, Hp, d, HD, r, row0, T_cap, 4, scale};
   const bool dot = x != nullptr, fold = q != nullptr;
   if (dt == AP_F16) {
     if (dot && fold) return launch_rows<F16Tag, true, true>(p, B, stream);

@@ -321,7 +321,7 @@ struct AttnParams {
   const uint16_t* Sv;
   float* part_ml;       // [B][S][H][2]   (softmax reference exponent in log2 units, sum)
   float* part_U;        // [B][S][H][r]
-  int T, T_cap, r, H, nsplit;
+  int B, T, T_cap, r, H, nsplit;
   int nh;               // C_v LDS ring depth in 16-row units (even, >= 2)
   // rank-ragged launches only: the group lists of ap_select_ranks and the per-token ranks
   const int32_t* rank_k;      // [B][T] or null (= r)
@@ -353,6 +353,17 @@ struct AttnParams {
 // compete for registers.  The softmax reference exponent only moves when a score exceeds
 // it by more than kLazy, so the rescale factor is 1 on almost every tile.
 //
+// Workgroup id -> (sequence, split).  Consecutive workgroup ids go to different XCDs (8 of
+// them, each with its own L2), so sequence b lives on XCD b % 8 and its splits are neighbours
+// in that XCD's dispatch order: the folded query of a sequence is fetched from HBM once and
+// found in L2 by the other splits.
+__device__ __forceinline__ void wg_coords(int nsplit, int& b, int& s) {
+  const int id = __builtin_amdgcn_readfirstlane((int)blockIdx.x);
+  const int k = id >> 3;
+  b = (k / nsplit) * 8 + (id & 7);
+  s = k - (k / nsplit) * nsplit;
+}
+
 // State every wave carries through the token loop, whatever its role.
 // Rank-ragged launches (RAGGED): a tile is 32 tokens of ONE rank group, taken from the
 // group's index list, so the rank is uniform inside a tile and nothing diverges; tiles are
@@ -389,8 +400,8 @@ struct WaveCtx {
     const int tid = threadIdx.x;
     w = __builtin_amdgcn_readfirstlane(tid >> 6);
     lane = tid & 63; n = lane & 15; g = lane >> 4;
-    b = uni(blockIdx.y); s = uni(blockIdx.x);
     r = uni(p.r); T = uni(p.T); H = uni(p.H); nh = uni(p.nh); nsplit = uni(p.nsplit); dbg = uni(p.dbg);
+    wg_coords(nsplit, b, s);
     // ring unit geometry: 16 rows of (cpr+1) 16-byte chunks (one pad chunk per row shifts
     // consecutive rows across the LDS banks)
     const int cpr = (r * EB) >> 4;
@@ -470,10 +481,13 @@ struct WaveCtx {
     wg_barrier();
   }
 
+  // Global tile index of local tile t.
+  __device__ __forceinline__ int gtile(int t) const { return t_lo + t; }
+
   // Tokens of local tile t that exist (the rest of the 32 slots is masked out of the softmax).
   __device__ __forceinline__ int tile_valid(int t) const {
     if (RAGGED) return uni(meta[4 * t]);
-    const int left = T - (t_lo + t) * kTile;
+    const int left = T - gtile(t) * kTile;
     return left < kTile ? left : kTile;
   }
 
@@ -530,16 +544,6 @@ struct WaveCtx {
       const size_t pb = ((size_t)b * nsplit + s) * H + o_hh;
       part_ml[pb * 2 + 0] = m_ref;
       part_ml[pb * 2 + 1] = l_tot;
-    }
-  }
-
-  // Rows 16mt+w, 16mt+w+8 of one head tile's U, staged in LDS as [16][r+1], to global memory.
-  __device__ __forceinline__ void copy_out_rows(float* part_U, int mt) {
-    const float* ul = (const float*)ring;
-    const size_t pbase = ((size_t)b * nsplit + s) * H;
-    for (int hh = w; hh < 16 && mt * 16 + hh < H; hh += 8) {
-      float* dst = part_U + (pbase + mt * 16 + hh) * r;
-      for (int j = lane; j < r; j += 64) dst[j] = ul[hh * (r + 1) + j];
     }
   }
 };
@@ -605,7 +609,7 @@ __device__ __noinline__ void score_role(const AttnParams& p) {
     if constexpr (I8) {
 #pragma unroll
       for (int tt = 0; tt < 2; ++tt) {
-        int row = (cx.t_lo + tile) * kTile + 16 * tt + n;
+        int row = cx.gtile(tile) * kTile + 16 * tt + n;
         row = row < T ? row : T - 1;
         const uint16_t* sp_ = Sk_b + (size_t)row * nsb + (my_nks > 0 ? w : 0);
 #pragma unroll
@@ -618,7 +622,7 @@ __device__ __noinline__ void score_role(const AttnParams& p) {
       for (int j = 0; j < 2; ++j) {
         const int e = vs_e0 + 256 * j;
         if (e < nsb * kTile) {
-          int row = (cx.t_lo + tile) * kTile + (e & 31);
+          int row = cx.gtile(tile) * kTile + (e & 31);
           row = row < T ? row : T - 1;
           vsr[j] = Sv_b[(size_t)row * nsb + (e >> 5)];
         }
@@ -630,7 +634,7 @@ __device__ __noinline__ void score_role(const AttnParams& p) {
     if (!RAGGED) {
 #pragma unroll
       for (int tt = 0; tt < 2; ++tt) {
-        int row = (cx.t_lo + tile) * kTile + 16 * tt + n;
+        int row = cx.gtile(tile) * kTile + 16 * tt + n;
         row = row < T ? row : T - 1;                      // rows beyond T are masked later
         const char* rp = Ck_b + ((uint32_t)row * cx.row_bytes + lane_off);
 #pragma unroll
@@ -659,6 +663,8 @@ __device__ __noinline__ void score_role(const AttnParams& p) {
   unsigned long long t0_ = __builtin_readcyclecounter();
   tm[0] = t0_ - t_entry_;
   for (int t = 0; t < cx.ntl; ++t) {
+    if ((cx.dbg & 8) && cx.lane == 0 && t < 64)
+      uni_ptr(p.dbg_out)[1024 + ((cx.b * cx.nsplit + cx.s) * 8 + cx.w) * 64 + t] = __builtin_readcyclecounter();
     f32x4_t sp[MT][2];
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) { f32x4_t z = {0.f, 0.f, 0.f, 0.f}; sp[mt][0] = z; sp[mt][1] = z; }
@@ -692,13 +698,6 @@ __device__ __noinline__ void score_role(const AttnParams& p) {
     AP_TICK(3)
     wg_barrier();                                         // weights of tile t ready
     AP_TICK(4)
-  }
-  // the sum waves stage U through LDS one head tile at a time; help copy it out
-#pragma unroll
-  for (int mt = 0; mt < MT; ++mt) {
-    wg_barrier();
-    wg_barrier();
-    cx.copy_out_rows(part_U, mt);
   }
   cx.store_ml(part_ml);
   AP_TICK(6)
@@ -777,7 +776,7 @@ __device__ __noinline__ void sum_role(const AttnParams& p) {
     }
 #pragma nounroll
     for (int half = 0; half < 2; ++half) {
-      const int tok_u = (cx.t_lo + lt) * kTile + half * kHalf;
+      const int tok_u = cx.gtile(lt) * kTile + half * kHalf;
       char* dst = cx.ring + (slot0 + half) * cx.unit_bytes;
       const uint32_t base = (uint32_t)tok_u * cx.row_bytes;
       if (tok_u + kHalf <= T) {
@@ -814,6 +813,8 @@ __device__ __noinline__ void sum_role(const AttnParams& p) {
   unsigned long long t0_ = __builtin_readcyclecounter();
   tm[0] = t0_ - t_entry_;
   for (int t = 0; t < cx.ntl; ++t) {
+    if ((cx.dbg & 8) && cx.lane == 0 && t < 64)
+      uni_ptr(p.dbg_out)[1024 + ((cx.b * cx.nsplit + cx.s) * 8 + cx.w) * 64 + t] = __builtin_readcyclecounter();
     wg_barrier();            // partial scores of tile t ready; every sum wave is past tile t-1
     AP_TICK(2)
     if (t >= 1 && t - 1 + RT < cx.ntl) issue_tile(t - 1 + RT);   // refill tile t-1's slots
@@ -852,25 +853,39 @@ __device__ __noinline__ void sum_role(const AttnParams& p) {
     }
     AP_TICK(5)
   }
-  // U of this split.  U[i][j][mt][e] is element (head 16mt+n, column 128i + 32cp + 8g +
-  // 2e + j) (int8: column 256i + 64cp + 16g + 4e + j); one head tile at a time is transposed
-  // through LDS so that rows leave coalesced.
-  float* ul = (float*)cx.ring;                      // [16][r+1]
+  // U of this split, straight from the accumulators.  U[i][j][mt][e] is element (head 16mt+n,
+  // column 128i + 32cp + 8g + 2e + j) (int8: column 256i + 64cp + 16g + 4e + j): a lane owns
+  // NJ*4 consecutive columns of one head per column group, stored as 16-byte pieces; the four
+  // lanes g = 0..3 of a head together cover a full 128-byte (int8: 256-byte) run.
+  {
+    float* ubase = part_U + ((size_t)cx.b * cx.nsplit + cx.s) * cx.H * r;
 #pragma unroll
-  for (int mt = 0; mt < MT; ++mt) {
-    wg_barrier();                                   // ring / previous head tile no longer read
+    for (int mt = 0; mt < MT; ++mt) {
+      const int head = mt * 16 + n;
+      if (head < cx.H) {
+        float* urow = ubase + (size_t)head * r;
 #pragma unroll
-    for (int i = 0; i < NGRP; ++i)
+        for (int i = 0; i < NGRP; ++i) {
+          const int col0 = I8 ? i * 256 + cp * 64 + g * 16 : i * 128 + cp * 32 + g * 8;
+          if (col0 < r) {
+            if constexpr (I8) {
 #pragma unroll
-      for (int j = 0; j < NJ; ++j)
+              for (int e = 0; e < 4; ++e) {
+                const f32x4_t v = {U[i][0][mt][e], U[i][1][mt][e], U[i][2][mt][e], U[i][3][mt][e]};
+                *(f32x4_t*)(urow + col0 + 4 * e) = v;
+              }
+            } else {
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const int col = I8 ? i * 256 + cp * 64 + g * 16 + e * 4 + j
-                             : i * 128 + cp * 32 + g * 8 + e * 2 + j;
-          if (col < r) ul[n * (r + 1) + col] = U[i][j][mt][e];
+              for (int e2 = 0; e2 < 2; ++e2) {
+                const f32x4_t v = {U[i][0][mt][2 * e2], U[i][1][mt][2 * e2], U[i][0][mt][2 * e2 + 1],
+                                   U[i][1][mt][2 * e2 + 1]};
+                *(f32x4_t*)(urow + col0 + 4 * e2) = v;
+              }
+            }
+          }
         }
-    wg_barrier();
-    cx.copy_out_rows(part_U, mt);
+      }
+    }
   }
   cx.store_ml(part_ml);
   AP_TICK(6)
@@ -884,6 +899,11 @@ __device__ __noinline__ void sum_role(const AttnParams& p) {
 template <class Tag, int MT, int RMAX, bool SPLIT, bool RAGGED, bool I8>
 __global__ void __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2)))
 attn_partial(const AttnParams p) {
+  {
+    int b, s;
+    wg_coords(p.nsplit, b, s);
+    if (b >= p.B) return;                 // the grid is padded to whole groups of 8 sequences
+  }
   if (__builtin_amdgcn_readfirstlane(threadIdx.x >> 6) < 4)
     score_role<Tag, MT, RMAX, SPLIT, RAGGED, I8>(p);
   else
@@ -959,8 +979,6 @@ ap_status launch_attn(AttnParams p, int B, hipStream_t stream) {
   nh &= ~1;
   p.nh = nh;
   size_t lds = (size_t)nh * unit + fixed;
-  const size_t epi = (size_t)16 * (p.r + 1) * 4;
-  if (epi > lds) lds = epi;
   auto kern = attn_partial<Tag, MT, RMAX, SPLIT, RAGGED, I8>;
   static bool attr_set = false;
   if (!attr_set) {
@@ -972,7 +990,8 @@ ap_status launch_attn(AttnParams p, int B, hipStream_t stream) {
     }
     attr_set = true;
   }
-  hipLaunchKernelGGL(kern, dim3(p.nsplit, B), dim3(512), lds, stream, p);
+  p.B = B;
+  hipLaunchKernelGGL(kern, dim3(8 * ((B + 7) / 8) * p.nsplit), dim3(512), lds, stream, p);
   return AP_OK;
 }
 
@@ -1048,6 +1067,7 @@ ap_status run_decode(const DecodeArgs& a) {
   }
   if (const char* e = getenv("AP_DEBUG_ATTN")) p.dbg = atoi(e);
   p.dbg_out = (unsigned long long*)U;   // timers overwrite the head of part_U (debug only)
+  if (p.dbg & 8) p.dbg_out = (unsigned long long*)(ws + wl.total);   // caller allocated 2 MiB extra
   prof_mark(a.stream, true);
   st = dispatch_attn<Tag, SPLIT>(p, a.B, a.stream);
   prof_mark(a.stream, false);
