@@ -4,9 +4,10 @@
 Workload (the 13B-shaped batch decode the paper motivates with): B=64 sequences,
 H=40 heads of d=128 (HD=5120), 16 images x 256 + 128 text = 4224 cached tokens, rank
 r=640, bf16 coefficients and per-sequence bases, fp32 accumulation and fp32 output.
-One step = ap_decode_step: append one token's coefficients (the key row's projection
-shares its pass over B_k with the fold of the query) + attention over all cached
-tokens, for one layer; T grows by one per step.  Inputs are synthetic,
+One step = ap_decode_step: append one token's coefficients + attention over all cached
+tokens, for one layer; T grows by one per step.  The key row's projection shares its
+pass over B_k with the fold of the query, the value row's projection shares its pass
+over B_v with the expansion of the output, so each basis is read once per step.  Inputs are synthetic,
 generated on the GPU in the value law of paper_2603_23914_amd.workloads and resident
 in HBM before the timed region.
 
@@ -156,8 +157,8 @@ def main():
                 "frac": (achieved / HBM_PEAK_GBS) if achieved else None, "traffic": traffic,
                 "kernel_avg_us": k_avg_ms * 1e3, "launches": k_n, "algorithmic_bytes_per_launch": alg_bytes}
     # bytes the whole step must move (coefficients once; per-sequence B_k once: append + fold in
-    # one pass; B_v twice: append before attention, expansion after; partials and vectors are small)
-    step_bytes = alg_bytes + 3.0 * B * R * HD * 2
+    # one pass; B_v once: append + expansion in one pass; partials and vectors are small)
+    step_bytes = alg_bytes + 2.0 * B * R * HD * 2
     extra = {"step_effective_GBps": step_bytes / (dt / K) / 1e9, "step_algorithmic_bytes": step_bytes}
 
     # ---- optional: the same step over L independent layers back to back (distinct buffers,

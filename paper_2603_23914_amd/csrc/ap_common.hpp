@@ -125,6 +125,12 @@ bool basis_rows_applies(int HD, int B);
 ap_status launch_basis_rows(ap_dtype dt, const void* Bm, int64_t bstride, const void* x,
                             const void* q, void* C, void* Qp, int B, int H, int Hp, int d, int HD,
                             int r, int row0, int T_cap, float scale, hipStream_t stream);
+int expand_row_blocks(int B, int r);   // row blocks (= partial output slices) of expand_append
+ap_status launch_expand_append(ap_dtype dt, bool out_f32, const void* Bv, int64_t bstride,
+                               const void* v_new, void* Cv, const float* part_ml,
+                               const float* part_U, const float* pnew, float* pout, void* out,
+                               float* lse, int B, int H, int d, int r, int T, int T_cap, int nsplit,
+                               hipStream_t stream);
 ap_status launch_merge_expand(ap_dtype dt, bool out_f32, const float* part_ml, const float* part_U,
                               const void* Bv, int64_t bstride, void* out, float* lse, int B, int H,
                               int d, int r, int nsplit, hipStream_t stream);

@@ -30,6 +30,9 @@ __device__ __forceinline__ float dot2(uint32_t a, uint32_t b, float c, BF16Tag) 
   return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(b2_t, a), __builtin_bit_cast(b2_t, b), c,
                                          false);
 }
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+constexpr float kLn2 = 0.6931471805599453f;
+
 template <class Tag>
 __device__ __forceinline__ float dot8(const u32x4_t& a, const u32x4_t& b, float c) {
 #pragma unroll
@@ -170,9 +173,6 @@ __global__ void __launch_bounds__(256) basis_rows(const RowsParams p) {
 // ------------------------------------------------------------------------------------------
 // merge_expand: grid (ceil(H / 2), B), 256 threads.
 // ------------------------------------------------------------------------------------------
-__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
-constexpr float kLn2 = 0.6931471805599453f;
-
 template <class Tag, bool OUT_F32>
 __global__ void __launch_bounds__(256)
 merge_expand(const float* __restrict__ part_ml, const float* __restrict__ part_U,
@@ -250,11 +250,209 @@ merge_expand(const float* __restrict__ part_ml, const float* __restrict__ part_U
   }
 }
 
+
+// ------------------------------------------------------------------------------------------
+// expand_append: the expansion through B_v and the append of the new token's value row in ONE
+// pass over B_v (a fused decode step).  attn_partial has scored all T tokens but summed the
+// value coefficients of the T-1 older ones only, exporting the newest token's softmax weight;
+// that token's weighted coefficient sum is its own coefficient row c_v[j] = B_v[j, :] . v_new,
+// which a whole-row pass produces row by row.  So for basis row j
+//     U*[h, j]  = A[h, j] + beta[h] * c_v[j]
+//     out[h, :] += U*[h, j] * B_v[j, head h]
+// with A the merged, normalised partial sums of the older tokens and beta[h] the new token's
+// softmax weight.  A workgroup owns a block of rows; its per-column sums go to a partial buffer
+// that reduce_out adds up in a fixed order (deterministic).
+//   grid (ceil(r / rpw), B), 128 threads; dynamic LDS: A [H][rpw + 1], statistics.
+// ------------------------------------------------------------------------------------------
+struct ExpandParams {
+  const uint16_t* Bv;
+  int64_t bstride;
+  const uint16_t* v_new;    // [B][HD]
+  uint16_t* Cv;             // [B][T_cap][r]: row T-1 is written
+  const float* part_ml;     // [B][S][H][2] (reference exponent, sum) over all T tokens
+  const float* part_U;      // [B][S][H][r] over tokens 0 .. T-2
+  const float* pnew;        // [B][H] weight of token T-1 relative to split S-1's reference
+  float* pout;              // [B][nob][HD] per-row-block column sums
+  float* lse;               // [B][H] or null
+  int H, d, HD, r, T, T_cap, nsplit, rpw, nob;
+};
+
+template <class Tag, int KPC, int NBUF>
+__global__ void __launch_bounds__(128) expand_append(const ExpandParams p) {
+  // Two waves share the workgroup's rows, each owning KPC / 2 of the 512-element passes over
+  // the hidden axis (so the column sums fit in registers); the two halves of a row's dot
+  // product meet in LDS once per row.
+  constexpr int KH = KPC / 2;
+  extern __shared__ __attribute__((aligned(16))) float lds_ea[];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int half = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int rpw = p.rpw, pitch = rpw + 1;
+  const int b = blockIdx.y, j0 = blockIdx.x * rpw;
+  const int H = p.H, HD = p.HD, r = p.r, S = p.nsplit;
+  float* Atile = lds_ea;                       // [H][pitch]
+  float* mstar = Atile + H * pitch;            // [H]
+  float* invL = mstar + H;                     // [H]
+  float* beta = invL + H;                      // [H]
+  float* dotx = beta + H;                      // [2][2] half dot products, double-buffered
+  float* wsp = dotx + 4;                       // [S][H] split weights (when they fit)
+  const bool wsp_fits = S * H <= 4096;
+  const uint16_t* Bb = p.Bv + (size_t)b * p.bstride;
+
+  // ---- row ring: requests go out first (see basis_rows)
+  u32x4_t buf[NBUF][KH];
+  int eoff[KH];
+  bool inside[KH];
+#pragma unroll
+  for (int pp = 0; pp < KH; ++pp) {
+    const int e0 = (half * KH + pp) * 512 + lane * 8;
+    inside[pp] = e0 < HD;
+    eoff[pp] = inside[pp] ? e0 : lane * 8;
+  }
+  auto load_row = [&](u32x4_t (&dst)[KH], int i) {
+    int j = j0 + i;
+    j = j < r ? j : r - 1;
+    const uint16_t* row = Bb + (size_t)j * HD;
+#pragma unroll
+    for (int pp = 0; pp < KH; ++pp) dst[pp] = *(const u32x4_t*)(row + eoff[pp]);
+  };
+  u32x4_t vs[KH];
+#pragma unroll
+  for (int pp = 0; pp < KH; ++pp) {
+    const u32x4_t z = {0, 0, 0, 0};
+    vs[pp] = inside[pp] ? *(const u32x4_t*)(p.v_new + (size_t)b * HD + eoff[pp]) : z;
+  }
+  const int last = rpw - 1;
+#pragma unroll
+  for (int u = 0; u + 1 < NBUF; ++u) load_row(buf[u], u < last ? u : last);
+
+  // ---- merged softmax statistics: one thread per head
+  if (tid < H) {
+    const int h = tid;
+    const size_t pb = (size_t)b * S * H + h;
+    float m = -INFINITY;
+    for (int s = 0; s < S; ++s) m = fmaxf(m, p.part_ml[(pb + (size_t)s * H) * 2]);
+    float L = 0.f, wlast = 0.f;
+    for (int s = 0; s < S; ++s) {
+      const float ws = fast_exp2(p.part_ml[(pb + (size_t)s * H) * 2] - m);
+      L += p.part_ml[(pb + (size_t)s * H) * 2 + 1] * ws;
+      if (wsp_fits) wsp[s * H + h] = ws;
+      wlast = ws;
+    }
+    mstar[h] = m;
+    invL[h] = 1.0f / L;
+    beta[h] = wlast * p.pnew[(size_t)b * H + h] / L;
+    if (p.lse && blockIdx.x == 0) p.lse[(size_t)b * H + h] = (m + log2f(L)) * kLn2;
+  }
+  __syncthreads();
+  // ---- A[h][jl] = sum_s 2^(m_s - m*) U_s[h, j0 + jl] / L
+  for (int i = tid; i < H * rpw; i += 128) {
+    const int h = i / rpw, jl = i - h * rpw;
+    float acc = 0.f;
+    if (j0 + jl < r) {
+      const size_t pb = (size_t)b * S * H + h;
+      if (wsp_fits) {
+        for (int s = 0; s < S; ++s)
+          acc = fmaf(wsp[s * H + h], p.part_U[(pb + (size_t)s * H) * r + j0 + jl], acc);
+      } else {
+        const float m = mstar[h];
+        for (int s = 0; s < S; ++s)
+          acc = fmaf(fast_exp2(p.part_ml[(pb + (size_t)s * H) * 2] - m),
+                     p.part_U[(pb + (size_t)s * H) * r + j0 + jl], acc);
+      }
+      acc *= invL[h];
+    }
+    Atile[h * pitch + jl] = acc;
+  }
+  __syncthreads();
+
+  const int dshift = 31 - __builtin_clz((unsigned)p.d);
+  float bt[KH];
+  int arow[KH];                                // A row (head) of this lane's chunk in every pass
+#pragma unroll
+  for (int pp = 0; pp < KH; ++pp) {
+    const int h = inside[pp] ? eoff[pp] >> dshift : 0;
+    bt[pp] = inside[pp] ? beta[h] : 0.f;
+    arow[pp] = h * pitch;
+  }
+  float o[KH][8];
+#pragma unroll
+  for (int pp = 0; pp < KH; ++pp)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) o[pp][e] = 0.f;
+
+  auto use_row = [&](const u32x4_t (&row)[KH], int i) {
+    const bool live = i < rpw && j0 + i < r;
+    float acc = 0.f;
+#pragma unroll
+    for (int pp = 0; pp < KH; ++pp) acc = dot8<Tag>(row[pp], vs[pp], acc);
+#pragma unroll
+    for (int o2 = 32; o2 > 0; o2 >>= 1) acc += __shfl_xor(acc, o2);
+    float* slot = dotx + (i & 1) * 2;
+    if (lane == 0) slot[half] = acc;
+    // both waves run the same number of rows.  Only LDS traffic has to be ordered here: a full
+    // __syncthreads() would also wait for the row loads in flight and drain the ring.
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    const float c = slot[0] + slot[1];
+    const uint16_t cbits = f32_to_bits(c, Tag{});
+    if (lane == 0 && half == 0 && live) p.Cv[((size_t)b * p.T_cap + p.T - 1) * r + j0 + i] = cbits;
+    const float cr = live ? bits_to_f32(cbits, Tag{}) : 0.f;   // the stored (rounded) coefficient
+    const int jc = live ? i : 0;
+#pragma unroll
+    for (int pp = 0; pp < KH; ++pp) {
+      const float wgt = live ? fmaf(bt[pp], cr, Atile[arow[pp] + jc]) : 0.f;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        o[pp][2 * e] = fmaf(wgt, lo_to_f32(row[pp][e], Tag{}), o[pp][2 * e]);
+        o[pp][2 * e + 1] = fmaf(wgt, hi_to_f32(row[pp][e], Tag{}), o[pp][2 * e + 1]);
+      }
+    }
+  };
+  const int rpw_pad = (rpw + NBUF - 1) / NBUF * NBUF;
+  for (int i = 0; i < rpw_pad; i += NBUF) {
+#pragma unroll
+    for (int u = 0; u < NBUF; ++u) {
+      const int nx = i + u + NBUF - 1;
+      if (NBUF > 1) load_row(buf[(u + NBUF - 1) % NBUF], nx < last ? nx : last);
+      else load_row(buf[0], i < last ? i : last);
+      use_row(buf[u], i + u);
+    }
+  }
+  // ---- the two waves own disjoint columns: straight to the partial buffer
+  float* dst = p.pout + ((size_t)b * p.nob + blockIdx.x) * HD;
+#pragma unroll
+  for (int pp = 0; pp < KH; ++pp) {
+    if (inside[pp]) {
+      const f32x4_t v0 = {o[pp][0], o[pp][1], o[pp][2], o[pp][3]};
+      const f32x4_t v1 = {o[pp][4], o[pp][5], o[pp][6], o[pp][7]};
+      *(f32x4_t*)(dst + eoff[pp]) = v0;
+      *(f32x4_t*)(dst + eoff[pp] + 4) = v1;
+    }
+  }
+}
+
+// out[b, c] = sum over row blocks of pout[b][blk][c], in block order.  grid (ceil(HD/1024), B).
+template <class Tag, bool OUT_F32>
+__global__ void __launch_bounds__(256)
+reduce_out(const float* __restrict__ pout, void* __restrict__ out, int HD, int nob) {
+  const int b = blockIdx.y, c = (blockIdx.x * 256 + threadIdx.x) * 4;
+  if (c >= HD) return;
+  f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+  for (int k = 0; k < nob; ++k) acc += *(const f32x4_t*)(pout + ((size_t)b * nob + k) * HD + c);
+  if (OUT_F32) {
+    *(f32x4_t*)((float*)out + (size_t)b * HD + c) = acc;
+  } else {
+    u32x2_t v = {pack2(acc[0], acc[1], Tag{}), pack2(acc[2], acc[3], Tag{})};
+    *(u32x2_t*)((uint16_t*)out + (size_t)b * HD + c) = v;
+  }
+}
+
+}  // namespace
+int basis_rows_per_wave(int B, int r);
+namespace {
+
 template <class Tag, bool DOT, bool FOLD>
 ap_status launch_rows(RowsParams p, int B, hipStream_t stream) {
-  // about two workgroups per CU in one round: rows per wave from the total row count
-  int rpw = (int)(((int64_t)B * p.r + 2047) / 2048);
-  rpw = rpw < 4 ? 4 : (rpw > 32 ? 32 : rpw);
+  const int rpw = basis_rows_per_wave(B, p.r);
   p.rpw = rpw;
   const int rows_wg = 4 * rpw;
   const dim3 grid((p.r + rows_wg - 1) / rows_wg, B);
@@ -291,6 +489,52 @@ ap_status launch_basis_rows(ap_dtype dt, const void* Bm, int64_t bstride, const 
   if (dot && fold) return launch_rows<BF16Tag, true, true>(p, B, stream);
   if (dot) return launch_rows<BF16Tag, true, false>(p, B, stream);
   return launch_rows<BF16Tag, false, true>(p, B, stream);
+}
+
+int basis_rows_per_wave(int B, int r) {
+  // about two workgroups per CU in one round
+  int rpw = (int)(((int64_t)B * r + 2047) / 2048);
+  return rpw < 4 ? 4 : (rpw > 32 ? 32 : rpw);
+}
+// expand_append: about four two-wave workgroups per CU in one round; rows per workgroup
+int expand_rows_per_pair(int B, int r) {
+  int rpw = (int)(((int64_t)B * r + 1023) / 1024);
+  return rpw < 4 ? 4 : (rpw > 64 ? 64 : rpw);
+}
+int expand_row_blocks(int B, int r) { return (r + expand_rows_per_pair(B, r) - 1) / expand_rows_per_pair(B, r); }
+
+ap_status launch_expand_append(ap_dtype dt, bool out_f32, const void* Bv, int64_t bstride,
+                               const void* v_new, void* Cv, const float* part_ml,
+                               const float* part_U, const float* pnew, float* pout, void* out,
+                               float* lse, int B, int H, int d, int r, int T, int T_cap, int nsplit,
+                               hipStream_t stream) {
+  ExpandParams p{(const uint16_t*)Bv, bstride, (const uint16_t*)v_new, (uint16_t*)Cv, part_ml, part_U,
+                 pnew, pout, lse, H, d, H * d, r, T, T_cap, nsplit, expand_rows_per_pair(B, r),
+                 expand_row_blocks(B, r)};
+  const dim3 grid(p.nob, B);
+  const size_t lds = ((size_t)H * (p.rpw + 1) + 3 * (size_t)H + 4 + (nsplit * H <= 4096 ? (size_t)nsplit * H : 0)) * 4;
+  const int kpc = (p.HD + 511) / 512;
+#define AP_EA(TAG, K, NB)                                                                        \
+  if (kpc <= K) {                                                                                \
+    hipLaunchKernelGGL((expand_append<TAG, K, NB>), grid, dim3(128), lds, stream, p);            \
+    break;                                                                                       \
+  }
+  do {
+    if (dt == AP_F16) { AP_EA(F16Tag, 2, 3) AP_EA(F16Tag, 4, 3) AP_EA(F16Tag, 8, 3) AP_EA(F16Tag, 10, 3) AP_EA(F16Tag, 16, 2) }
+    else { AP_EA(BF16Tag, 2, 3) AP_EA(BF16Tag, 4, 3) AP_EA(BF16Tag, 8, 3) AP_EA(BF16Tag, 10, 3) AP_EA(BF16Tag, 16, 2) }
+    set_error("expand: H*d=%d exceeds 8192", p.HD);
+    return AP_ERR_UNSUPPORTED;
+  } while (0);
+#undef AP_EA
+  const dim3 g2((p.HD + 1023) / 1024, B);
+  if (dt == AP_F16) {
+    if (out_f32) hipLaunchKernelGGL((reduce_out<F16Tag, true>), g2, dim3(256), 0, stream, pout, out, p.HD, p.nob);
+    else hipLaunchKernelGGL((reduce_out<F16Tag, false>), g2, dim3(256), 0, stream, pout, out, p.HD, p.nob);
+  } else {
+    if (out_f32) hipLaunchKernelGGL((reduce_out<BF16Tag, true>), g2, dim3(256), 0, stream, pout, out, p.HD, p.nob);
+    else hipLaunchKernelGGL((reduce_out<BF16Tag, false>), g2, dim3(256), 0, stream, pout, out, p.HD, p.nob);
+  }
+  return AP_OK;
 }
 
 ap_status launch_merge_expand(ap_dtype dt, bool out_f32, const float* part_ml, const float* part_U,

@@ -330,6 +330,10 @@ struct AttnParams {
   const int32_t* bucket_idx;  // [B][T]
   int F;
   int ntl_cap;          // most tiles a split can own (sizes the LDS index table)
+  // fused decode step: the newest token (row T-1) is scored like every other, but its value
+  // row does not exist yet; its softmax weight is exported and the expansion pass adds it
+  int defer_v;          // 0 or 1
+  float* pnew;          // [B][H] weight of token T-1 relative to the last split's reference
   int dbg;              // experiments: 1 = no loads, 2 = no math, 4 = phase timers
   unsigned long long* dbg_out;
 };
@@ -389,6 +393,8 @@ struct WaveCtx {
   int* meta;         // RAGGED: [ntl][4] = tokens in the tile, key rank, value rank, unused
   uint32_t row_bytes;
   int t_lo, ntl;     // first tile and number of tiles of this split
+  int Tv;            // value rows that exist: T, or T-1 while the newest token's row is deferred
+  float* pnew;
   // softmax ownership: lane = 8*head_local + slot, slot = 4*tt + gg covers tokens
   // 16*tt + 4*gg .. +3 of the tile for head o_hh
   bool owner;
@@ -402,6 +408,8 @@ struct WaveCtx {
     lane = tid & 63; n = lane & 15; g = lane >> 4;
     r = uni(p.r); T = uni(p.T); H = uni(p.H); nh = uni(p.nh); nsplit = uni(p.nsplit); dbg = uni(p.dbg);
     wg_coords(nsplit, b, s);
+    Tv = T - uni(p.defer_v);
+    pnew = uni_ptr(p.pnew);
     // ring unit geometry: 16 rows of (cpr+1) 16-byte chunks (one pad chunk per row shifts
     // consecutive rows across the LDS banks)
     const int cpr = (r * EB) >> 4;
@@ -491,9 +499,16 @@ struct WaveCtx {
     return left < kTile ? left : kTile;
   }
 
+  // Slot of the deferred newest token in local tile t (outside [0, 32): not in this tile).
+  __device__ __forceinline__ int tile_new(int t) const {
+    if (RAGGED || Tv == T) return -1;
+    return T - 1 - gtile(t) * kTile;
+  }
+
   // Softmax of this wave's heads for a tile whose first `valid` slots hold tokens (after
-  // the score waves' partial tiles are in xchg).
-  __device__ __forceinline__ void finalize_softmax(int valid) {
+  // the score waves' partial tiles are in xchg).  newl: slot of the deferred token, if any:
+  // its weight counts in the sum, is exported, and stays out of the value products.
+  __device__ __forceinline__ void finalize_softmax(int valid, int newl) {
     if (!owner) return;
     const int xi = o_hh * 9 + (lane & 7);
     f32x4_t sc = xchg[xi];
@@ -513,8 +528,17 @@ struct WaveCtx {
       m_ref = m_upd;
       l_part *= alpha;
     }
-    const float p0 = fast_exp2(sc[0] - m_ref), p1 = fast_exp2(sc[1] - m_ref);
-    const float p2 = fast_exp2(sc[2] - m_ref), p3 = fast_exp2(sc[3] - m_ref);
+    float p0 = fast_exp2(sc[0] - m_ref), p1 = fast_exp2(sc[1] - m_ref);
+    float p2 = fast_exp2(sc[2] - m_ref), p3 = fast_exp2(sc[3] - m_ref);
+    float pdef = 0.f;
+    if (newl >= 0 && newl < kTile) {            // wave-uniform: this tile holds the deferred token
+      const int li = newl - (16 * o_tt + 4 * o_gg);
+      if (li == 0) { pdef = p0; p0 = 0.f; }
+      if (li == 1) { pdef = p1; p1 = 0.f; }
+      if (li == 2) { pdef = p2; p2 = 0.f; }
+      if (li == 3) { pdef = p3; p3 = 0.f; }
+      if (li >= 0 && li < 4 && o_hh < H) pnew[(size_t)b * H + o_hh] = pdef;
+    }
     u32x2_t hi, lo = {0, 0};
     hi[0] = cvt_pack(p0, p1, Tag{});
     hi[1] = cvt_pack(p2, p3, Tag{});
@@ -528,7 +552,7 @@ struct WaveCtx {
       k2 += lo_to_f32(lo[1], Tag{});
       k3 += hi_to_f32(lo[1], Tag{});
     }
-    l_part += (k0 + k1) + (k2 + k3);            // the sum uses the values the MFMA will see
+    l_part += (k0 + k1) + (k2 + k3) + pdef;     // the sum uses the values the MFMA will see
     // weights in B-operand layout: lane (n, g) of head tile mt holds tokens 4g..4g+3
     // (dwords 0,1) and 16+4g..+3 (dwords 2,3)
     u32x2_t* ph = (u32x2_t*)(Pbuf + (o_mt * 2 + 0) * 64 + o_lane) + o_tt;
@@ -694,7 +718,7 @@ __device__ __noinline__ void score_role(const AttnParams& p) {
     }
     wg_barrier();                                         // partial scores of tile t ready
     AP_TICK(2)
-    cx.finalize_softmax(cx.tile_valid(t));
+    cx.finalize_softmax(cx.tile_valid(t), cx.tile_new(t));
     AP_TICK(3)
     wg_barrier();                                         // weights of tile t ready
     AP_TICK(4)
@@ -779,20 +803,20 @@ __device__ __noinline__ void sum_role(const AttnParams& p) {
       const int tok_u = cx.gtile(lt) * kTile + half * kHalf;
       char* dst = cx.ring + (slot0 + half) * cx.unit_bytes;
       const uint32_t base = (uint32_t)tok_u * cx.row_bytes;
-      if (tok_u + kHalf <= T) {
+      if (tok_u + kHalf <= cx.Tv) {
 #pragma unroll
         for (int k = 0; k < NSLOT; ++k) {
           const int blk = cp + 4 * k;
           if (blk < cx.nblk) dma16(Cv_b + (base + slot_off[k]), dst + blk * 1024);
         }
-      } else {                                     // rows at or beyond T: clamp to row T-1
+      } else {                                     // rows that do not exist: repeat the last that does
 #pragma unroll
         for (int k = 0; k < NSLOT; ++k) {
           const int blk = cp + 4 * k;
           if (blk < cx.nblk) {
             const int row = (int)((slot_row[k >> 2] >> (8 * (k & 3))) & 0xffu);
             uint32_t off = base + slot_off[k];
-            if (tok_u + row >= T) off -= (uint32_t)(tok_u + row - (T - 1)) * cx.row_bytes;
+            if (tok_u + row >= cx.Tv) off -= (uint32_t)(tok_u + row - (cx.Tv - 1)) * cx.row_bytes;
             dma16(Cv_b + off, dst + blk * 1024);
           }
         }
@@ -818,7 +842,7 @@ __device__ __noinline__ void sum_role(const AttnParams& p) {
     wg_barrier();            // partial scores of tile t ready; every sum wave is past tile t-1
     AP_TICK(2)
     if (t >= 1 && t - 1 + RT < cx.ntl) issue_tile(t - 1 + RT);   // refill tile t-1's slots
-    cx.finalize_softmax(cx.tile_valid(t));
+    cx.finalize_softmax(cx.tile_valid(t), cx.tile_new(t));
     AP_TICK(3)
     {
       // tile t's rows must have landed; the tiles issued after it may stay in flight
@@ -943,9 +967,9 @@ int choose_nsplit(int B, int T) {
 }
 
 struct WsLayout {
-  size_t qp, ml, u, total;
+  size_t qp, ml, u, po, pn, total;
 };
-WsLayout ws_layout(int B, int H, int T, int r) {
+WsLayout ws_layout(int B, int H, int d, int T, int r) {
   const int Hp = (H + 15) / 16 * 16;
   const int S = choose_nsplit(B, T);
   WsLayout w;
@@ -955,6 +979,10 @@ WsLayout ws_layout(int B, int H, int T, int r) {
   off += round_up((size_t)B * S * H * 2 * 4, 256);
   w.u = off;
   off += round_up((size_t)B * S * H * r * 4, 256);
+  w.po = off;                              // per-row-block output sums of a fused step
+  off += round_up((size_t)B * expand_row_blocks(B, r) * H * d * 4, 256);
+  w.pn = off;                              // the newest token's softmax weights of a fused step
+  off += round_up((size_t)B * H * 4, 256);
   w.total = off;
   return w;
 }
@@ -1031,8 +1059,12 @@ ap_status dispatch_attn(const AttnParams& p, int B, hipStream_t stream) {
 template <class Tag, bool SPLIT>
 ap_status run_decode(const DecodeArgs& a) {
   const int Hp = (a.H + 15) / 16 * 16;
+  // A fused step with uniform rank scores all T tokens in attn_partial but leaves the newest
+  // token's value row to the expansion pass over B_v, which produces that row and adds its
+  // contribution: B_v is read once per step instead of twice.
+  const bool one_pass_v = a.v_new && !a.rank_k && !a.rank_v && a.T >= 2;
   const int S = choose_nsplit(a.B, a.T);
-  const WsLayout wl = ws_layout(a.B, a.H, a.T, a.r);
+  const WsLayout wl = ws_layout(a.B, a.H, a.d, a.T, a.r);
   char* ws = (char*)a.workspace;
   uint16_t* Qp = (uint16_t*)(ws + wl.qp);
   float* ml = (float*)(ws + wl.ml);
@@ -1042,7 +1074,7 @@ ap_status run_decode(const DecodeArgs& a) {
                                    a.B, a.H, Hp, a.d, a.H * a.d, a.r, a.T - 1, a.T_cap,
                                    a.sm_scale * kLog2e, a.stream);
   if (st != AP_OK) return st;
-  if (a.v_new) {
+  if (a.v_new && !one_pass_v) {
     st = launch_basis_rows(a.dt, a.Bv, a.basis_batch_stride, a.v_new, nullptr, (void*)a.Cv, nullptr,
                            a.B, 0, 0, 8, a.H * a.d, a.r, a.T - 1, a.T_cap, 1.0f, a.stream);
     if (st != AP_OK) return st;
@@ -1054,6 +1086,8 @@ ap_status run_decode(const DecodeArgs& a) {
   p.part_ml = ml;
   p.part_U = U;
   p.T = a.T; p.T_cap = a.T_cap; p.r = a.r; p.H = a.H; p.nsplit = S;
+  p.defer_v = one_pass_v ? 1 : 0;
+  p.pnew = (float*)(ws + wl.pn);
   if (a.dt_coef == AP_I8) {
     p.Sk = (const uint16_t*)a.scale_k;
     p.Sv = (const uint16_t*)a.scale_v;
@@ -1072,8 +1106,13 @@ ap_status run_decode(const DecodeArgs& a) {
   st = dispatch_attn<Tag, SPLIT>(p, a.B, a.stream);
   prof_mark(a.stream, false);
   if (st != AP_OK) return st;
-  st = launch_merge_expand(a.dt, a.dt_out == AP_F32, ml, U, a.Bv, a.basis_batch_stride, a.out, a.lse,
-                           a.B, a.H, a.d, a.r, S, a.stream);
+  if (one_pass_v)
+    st = launch_expand_append(a.dt, a.dt_out == AP_F32, a.Bv, a.basis_batch_stride, a.v_new,
+                              (void*)a.Cv, ml, U, (const float*)(ws + wl.pn), (float*)(ws + wl.po),
+                              a.out, a.lse, a.B, a.H, a.d, a.r, a.T, a.T_cap, S, a.stream);
+  else
+    st = launch_merge_expand(a.dt, a.dt_out == AP_F32, ml, U, a.Bv, a.basis_batch_stride, a.out, a.lse,
+                             a.B, a.H, a.d, a.r, S, a.stream);
   if (st != AP_OK) return st;
   return check_launch("ap_decode_attn");
 }
@@ -1081,9 +1120,8 @@ ap_status run_decode(const DecodeArgs& a) {
 }  // namespace
 
 size_t decode_mfma_workspace(int B, int H, int d, int T, int r, ap_dtype dt) {
-  (void)d;
   (void)dt;
-  return ws_layout(B, H, T, r).total;
+  return ws_layout(B, H, d, T, r).total;
 }
 
 ap_status launch_decode_mfma(const DecodeArgs& a) {
