@@ -823,8 +823,10 @@ __device__ __noinline__ void sum_role(const AttnParams& p) {
       }
     }
   };
-#pragma nounroll
-  for (int lt = 0; lt < RT && lt < cx.ntl; ++lt) issue_tile(lt);
+  // Only the first tile is requested up front: the rest of the ring is filled once the score
+  // waves have their first tile, so the folded query and the first key tile (which everything
+  // waits for) are not queued behind value rows that are needed later.
+  if (cx.ntl > 0) issue_tile(0);
 
   f32x4_t U[NGRP][NJ][MT];
 #pragma unroll
@@ -841,7 +843,12 @@ __device__ __noinline__ void sum_role(const AttnParams& p) {
       uni_ptr(p.dbg_out)[1024 + ((cx.b * cx.nsplit + cx.s) * 8 + cx.w) * 64 + t] = __builtin_readcyclecounter();
     wg_barrier();            // partial scores of tile t ready; every sum wave is past tile t-1
     AP_TICK(2)
-    if (t >= 1 && t - 1 + RT < cx.ntl) issue_tile(t - 1 + RT);   // refill tile t-1's slots
+    if (t == 0) {
+#pragma nounroll
+      for (int lt = 1; lt < RT && lt < cx.ntl; ++lt) issue_tile(lt);
+    } else if (t - 1 + RT < cx.ntl) {
+      issue_tile(t - 1 + RT);                                    // refill tile t-1's slots
+    }
     cx.finalize_softmax(cx.tile_valid(t), cx.tile_new(t));
     AP_TICK(3)
     {
