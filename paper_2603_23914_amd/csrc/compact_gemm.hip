@@ -4,10 +4,10 @@
 //
 // Both operands are contiguous along the contraction axis, so tiles go HBM -> LDS with
 // direct-to-LDS 16-byte loads and come back out as MFMA operands with one ds_read_b128 each.
-// A workgroup (4 waves, 2 x 2) owns a 128-token x 128-column tile and walks the hidden axis
-// in blocks of 64 through a two-stage LDS ring; each wave holds a 64 x 64 accumulator as
-// 2 x 2 MFMA 32x32x16 tiles.  The LDS image of a tile is [row][8 chunks of 16 B] with the
-// chunk index XOR-ed by (row & 7): the loads pick their global source accordingly, and eight
+// A workgroup (8 waves, 4 x 2) owns a 256-token x 128-column tile and walks the hidden axis
+// in blocks of 64 through a three-stage LDS ring (two stages in flight while one is multiplied,
+// one barrier per block); each wave holds a 64 x 64 accumulator as 2 x 2 MFMA 32x32x16 tiles.
+// The LDS image of a tile is [row][8 chunks of 16 B] with the chunk index XOR-ed by (row/2 & 7): the loads pick their global source accordingly, and eight
 // consecutive rows of one chunk column then sit in eight different bank groups.
 // The MFMA computes the transposed tile (basis rows as the A operand), so a lane ends up with
 // four consecutive output columns of one token; the tile is rounded to the storage type,
@@ -22,10 +22,12 @@
 namespace ap {
 namespace {
 
-constexpr int kBM = 128;   // tokens per tile
+constexpr int kBM = 256;   // tokens per tile
 constexpr int kBN = 128;   // output columns (basis rows) per tile
 constexpr int kBK = 64;    // hidden elements per stage
-constexpr int kStageBytes = (kBM + kBN) * kBK * 2;   // 32 KiB
+constexpr int kStageBytes = (kBM + kBN) * kBK * 2;   // 48 KiB
+constexpr int kStages = 3;
+constexpr int kThreads = 512;
 constexpr int kEpiPitch = kBN + 8;                   // 16-bit elements per staged output row
 
 template <class Tag> struct Mfma32;
@@ -58,7 +60,7 @@ struct GemmParams {
 };
 
 template <class Tag>
-__global__ void __launch_bounds__(256, 2) compact_gemm(const GemmParams p) {
+__global__ void __launch_bounds__(kThreads) compact_gemm(const GemmParams p) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   const int tid = threadIdx.x, lane = tid & 63;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -73,32 +75,37 @@ __global__ void __launch_bounds__(256, 2) compact_gemm(const GemmParams p) {
   const char* Xb = (const char*)(p.X + (size_t)b * p.n * p.HD);
   const char* Bb = (const char*)(p.Bm + (size_t)b * p.bstride);
 
-  // ---- direct-to-LDS loads: per stage 16 KiB of X rows then 16 KiB of basis rows; wave w
-  //      issues 1-KiB blocks 4w .. 4w+3 of each.  Block j, lane i -> LDS chunk P = 64 j + i,
-  //      holding (row P>>3, hidden chunk (P&7) ^ (row&7)).
-  uint32_t srcA[4], srcB[4];
+  // ---- direct-to-LDS loads: per stage 32 KiB of X rows then 16 KiB of basis rows; wave w
+  //      issues 1-KiB blocks 4w .. 4w+3 of the former and 2w, 2w+1 of the latter.  Block j,
+  //      lane i -> LDS chunk P = 64 j + i, holding (row P>>3, hidden chunk (P&7) ^ (row/2 & 7)).
+  uint32_t srcA[4], srcB[2];
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const int P = (4 * w + i) * 64 + lane;
-    const int row = P >> 3, kc = (P & 7) ^ (row & 7);
+    const int row = P >> 3, kc = (P & 7) ^ ((row >> 1) & 7);
     int ra = m0 + row;  ra = ra < p.n ? ra : p.n - 1;        // rows past the end: finite duplicates
-    int rb = n0 + row;  rb = rb < p.r ? rb : p.r - 1;
     srcA[i] = ((uint32_t)ra * (uint32_t)p.HD + (uint32_t)kc * 8u) * 2u;
+  }
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int P = (2 * w + i) * 64 + lane;
+    const int row = P >> 3, kc = (P & 7) ^ ((row >> 1) & 7);
+    int rb = n0 + row;  rb = rb < p.r ? rb : p.r - 1;
     srcB[i] = ((uint32_t)rb * (uint32_t)p.HD + (uint32_t)kc * 8u) * 2u;
   }
   auto issue = [&](int stage, int kb) {
     char* sA = smem + stage * kStageBytes + (4 * w) * 1024;
-    char* sB = sA + kBM * kBK * 2;
+    char* sB = smem + stage * kStageBytes + kBM * kBK * 2 + (2 * w) * 1024;
     const uint32_t koff = (uint32_t)kb * (kBK * 2);
 #pragma unroll
     for (int i = 0; i < 4; ++i) dma16(Xb + (srcA[i] + koff), sA + i * 1024);
 #pragma unroll
-    for (int i = 0; i < 4; ++i) dma16(Bb + (srcB[i] + koff), sB + i * 1024);
+    for (int i = 0; i < 2; ++i) dma16(Bb + (srcB[i] + koff), sB + i * 1024);
   };
 
   // ---- MFMA operands: wave (wn, wm) owns columns 64 wn .. and tokens 64 wm ..; operand row
   //      = lane & 31, hidden chunk of k-step ks = 2 ks + (lane >> 5)
-  const int wn = w & 1, wm = w >> 1;
+  const int wn = w & 1, wm = w >> 1;                       // wm = 0 .. 3
   const int orow = lane & 31, ohalf = lane >> 5;
   uint32_t offN[2], offM[2], kx[4];
 #pragma unroll
@@ -107,7 +114,7 @@ __global__ void __launch_bounds__(256, 2) compact_gemm(const GemmParams p) {
     offM[i] = (uint32_t)((wm * 64 + i * 32 + orow) * 128);
   }
 #pragma unroll
-  for (int ks = 0; ks < 4; ++ks) kx[ks] = (uint32_t)(((2 * ks + ohalf) ^ (orow & 7)) * 16);
+  for (int ks = 0; ks < 4; ++ks) kx[ks] = (uint32_t)(((2 * ks + ohalf) ^ ((orow >> 1) & 7)) * 16);
 
   f32x16_t acc[2][2];      // [column tile][token tile]
 #pragma unroll
@@ -117,32 +124,71 @@ __global__ void __launch_bounds__(256, 2) compact_gemm(const GemmParams p) {
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
+  // Software pipeline over the hidden axis, per 64-element block kb (stage kb % 3):
+  //   wait:    this wave's loads of block kb+1 have landed, its operands of block kb are in
+  //            registers
+  //   barrier: the same holds for every wave, so block kb+1 may be read and the stage of
+  //            block kb (fully consumed into registers) may be refilled with block kb+3
+  //   then:    request block kb+3, read the operands of block kb+1 into the other register
+  //            set, and multiply block kb -- the LDS reads and the loads run under the MFMAs.
   const int nk = p.HD / kBK;
-  issue(0, 0);
-  for (int kb = 0; kb < nk; ++kb) {
-    if (kb + 1 < nk) {
-      issue((kb + 1) & 1, kb + 1);
-      asm volatile("s_waitcnt vmcnt(8)" ::: "memory");     // this wave's loads of block kb landed
-    } else {
-      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    }
-    __syncthreads();                                       // ... and every other wave's
-    const char* st = smem + (kb & 1) * kStageBytes;
+  auto read_ops = [&](int stage, u32x4_t (&fa)[4][2], u32x4_t (&fb)[4][2]) {
+    const char* st = smem + stage * kStageBytes;
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-      u32x4_t fa[2], fb[2];
+    for (int ks = 0; ks < 4; ++ks)
 #pragma unroll
       for (int i = 0; i < 2; ++i) {
-        fa[i] = *(const u32x4_t*)(st + offN[i] + kx[ks]);
-        fb[i] = *(const u32x4_t*)(st + offM[i] + kx[ks]);
+        fa[ks][i] = *(const u32x4_t*)(st + offN[i] + kx[ks]);
+        fb[ks][i] = *(const u32x4_t*)(st + offM[i] + kx[ks]);
       }
+  };
+  auto multiply = [&](const u32x4_t (&fa)[4][2], const u32x4_t (&fb)[4][2]) {
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks)
 #pragma unroll
       for (int i = 0; i < 2; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j) acc[i][j] = Mfma32<Tag>::run(fa[i], fb[j], acc[i][j]);
-    }
-    __syncthreads();                                       // stage may be overwritten next round
+        for (int j = 0; j < 2; ++j) acc[i][j] = Mfma32<Tag>::run(fa[ks][i], fb[ks][j], acc[i][j]);
+  };
+  // Wait for this wave's LDS reads and tell the compiler that the operand registers are
+  // settled (it cannot see through the hand-placed wait and would otherwise add its own,
+  // after the NEXT block's reads have been issued, which would serialise them with the MFMAs).
+  auto settle = [&](u32x4_t (&fa)[4][2], u32x4_t (&fb)[4][2]) {
+    asm volatile("s_waitcnt lgkmcnt(0)"
+                 : "+v"(fa[0][0]), "+v"(fa[0][1]), "+v"(fa[1][0]), "+v"(fa[1][1]), "+v"(fa[2][0]),
+                   "+v"(fa[2][1]), "+v"(fa[3][0]), "+v"(fa[3][1]), "+v"(fb[0][0]), "+v"(fb[0][1]),
+                   "+v"(fb[1][0]), "+v"(fb[1][1]), "+v"(fb[2][0]), "+v"(fb[2][1]), "+v"(fb[3][0]),
+                   "+v"(fb[3][1])
+                 :
+                 : "memory");
+  };
+  u32x4_t fa0[4][2], fb0[4][2], fa1[4][2], fb1[4][2];
+  issue(0, 0);
+  if (nk > 1) issue(1, 1);
+  if (nk > 2) issue(2, 2);
+  // block 0: six loads per block and wave; later blocks may stay in flight
+  if (nk > 2) asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
+  else if (nk > 1) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
+  else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+  read_ops(0, fa0, fb0);
+  auto step = [&](int kb, u32x4_t (&fa_cur)[4][2], u32x4_t (&fb_cur)[4][2],
+                  u32x4_t (&fa_nxt)[4][2], u32x4_t (&fb_nxt)[4][2]) {
+    // outstanding loads of this wave at this point: blocks kb+1 and kb+2 (where they exist)
+    if (kb + 2 < nk) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
+    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    settle(fa_cur, fb_cur);
+    asm volatile("s_barrier" ::: "memory");
+    if (kb + 3 < nk) issue(kb % kStages, kb + 3);
+    if (kb + 1 < nk) read_ops((kb + 1) % kStages, fa_nxt, fb_nxt);
+    __builtin_amdgcn_sched_barrier(0);     // keep the requests ahead of the products
+    multiply(fa_cur, fb_cur);
+  };
+  for (int kb = 0; kb < nk; kb += 2) {
+    step(kb, fa0, fb0, fa1, fb1);
+    if (kb + 1 < nk) step(kb + 1, fa1, fb1, fa0, fb0);
   }
+  __syncthreads();                                         // the ring becomes the output staging area
 
   // ---- epilogue: round to the storage type, stage [token][column] in LDS
   uint16_t* epi = (uint16_t*)smem;
@@ -163,8 +209,8 @@ __global__ void __launch_bounds__(256, 2) compact_gemm(const GemmParams p) {
   const int c8 = tid & 15;
   const int col = n0 + c8 * 8;
 #pragma unroll 1
-  for (int pass = 0; pass < 8; ++pass) {
-    const int tok = pass * 16 + (tid >> 4);
+  for (int pass = 0; pass < kBM / 32; ++pass) {
+    const int tok = pass * 32 + (tid >> 4);
     const int t = m0 + tok;
     const u32x4_t v = *(const u32x4_t*)(epi + tok * kEpiPitch + c8 * 8);
     const bool live = t < p.n && col < p.r;
@@ -220,14 +266,14 @@ ap_status run_gemm(const CompactArgs& a) {
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       2 * kStageBytes);
+                                       kStages * kStageBytes);
     if (e != hipSuccess) {
       set_error("hipFuncSetAttribute: %s", hipGetErrorString(e));
       return AP_ERR_HIP;
     }
     attr_set = true;
   }
-  hipLaunchKernelGGL(kern, dim3(grid), dim3(256), 2 * kStageBytes, a.stream, p);
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(kThreads), kStages * kStageBytes, a.stream, p);
   return check_launch("ap_compact");
 }
 
