@@ -101,6 +101,9 @@ def main():
     ap_.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap_.add_argument("--calib-copy", action="store_true",
                      help="also run one plain 1 GiB device copy (reference for scaling rocprofv3 FETCH_SIZE/WRITE_SIZE)")
+    ap_.add_argument("--profile-compact", action="store_true",
+                     help="run only the configuration-5 prefill compaction (B=16, T=4224, HD=4096, r=512, fp16) "
+                          "three times and exit without a JSON line: the workload behind profiles/compact_gemm_c5_mfma.md")
     args = ap_.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
@@ -110,6 +113,15 @@ def main():
     from paper_2603_23914_amd import binding as ap
 
     torch.cuda.set_device(0)
+    if args.profile_compact:
+        b5, t5, hd5, r5 = 16, 4224, 4096, 512
+        x = [torch.randn(b5, t5, hd5, device="cuda", dtype=torch.float16) for _ in range(2)]
+        bm = [(torch.randn(b5, r5, hd5, device="cuda") / 64).half() for _ in range(2)]
+        c = [torch.empty(b5, t5, r5, device="cuda", dtype=torch.float16) for _ in range(2)]
+        for _ in range(3):
+            ap.ap_compact(x[0], x[1], bm[0], bm[1], c[0], c[1], None, None, n=t5, row0=0)
+        torch.cuda.synchronize()
+        return
     K, W = args.steps, args.warmup
     t_cap = T0 + W + K
     layers1 = gpu_inputs(torch, t_cap, 1)
