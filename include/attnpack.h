@@ -171,17 +171,21 @@ size_t ap_decode_workspace_bytes(int B, int H, int d, int T, int r, ap_dtype dt)
 /* ------------------------------------------------------------------------
  * ap_decode_step -- one decode step with append (paper Alg. 1: the new token's
  * key and value join the cache, then the query attends to every cached token).
- * Same result, bit for bit, as
+ * Computes what
  *     ap_compact(k_new, v_new, Bk, Bv, Ck, Cv, ..., n = 1, row0 = T - 1, ...)
  *     ap_decode_attn(q, Ck, Cv, ..., T, ...)
- * but the key row's projection and the fold of the query through B_k share one
- * pass over B_k, so the step reads the key basis once instead of twice.
+ * compute, but reads each basis once instead of twice: the key row's projection
+ * shares its pass over B_k with the fold of the query, and (with uniform rank)
+ * the value row's projection shares its pass over B_v with the expansion of the
+ * output, the new token's own contribution being added there.  The appended key
+ * row has the same bits as ap_compact's; the value row and the outputs agree with
+ * the two-call sequence up to the order of fp32 additions.
  *   k_new, v_new  [B, HD] dtype dt: the new token's merged-head key and value rows.
  *   Ck, Cv        [B, T_cap, r] dtype dt: row T-1 is WRITTEN, rows 0..T-1 attended.
  *   T             tokens cached after the append (1 <= T <= T_cap).
  * AP_F16 / AP_BF16 only (no int8 coefficients).  Rank arrays and group lists, when
- * given, must already cover the new token.  Everything else as ap_decode_attn;
- * the workspace query is ap_decode_workspace_bytes.
+ * given, must already cover the new token (the value basis is then read twice).
+ * Everything else as ap_decode_attn; the workspace query is ap_decode_workspace_bytes.
  * ---------------------------------------------------------------------- */
 ap_status ap_decode_step(const void* q, const void* k_new, const void* v_new, void* Ck, void* Cv,
                          const void* Bk, const void* Bv, int64_t basis_batch_stride,

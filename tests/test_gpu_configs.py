@@ -1,7 +1,8 @@
 """GPU parity at the benchmark configurations' full sizes and launch shapes: configuration 2
 (B=8, fp16, 128 decode steps with append) and configuration 3 (B=64, bf16, 64 steps with
-append; the workload bench.py times).  Every step runs on the GPU; at the sampled steps the
-cache is read back and the fp64 oracle attends over exactly those stored bits."""
+append; the workload bench.py times, through the same fused ap_decode_step call).  Every step
+runs on the GPU; at the sampled steps the cache is read back and the fp64 oracle attends over
+exactly those stored bits."""
 import math
 import time
 
@@ -25,7 +26,7 @@ def stored_bits(t: torch.Tensor, dtype: str) -> np.ndarray:
     return t.cpu().numpy()
 
 
-def run_config(case, check_steps, check_seqs_later):
+def run_config(case, check_steps, check_seqs_later, fused):
     from paper_2603_23914_amd import binding as ap
     dt = case.dtype
     B, H, d, r = case.B, case.H, case.d, case.r
@@ -49,9 +50,13 @@ def run_config(case, check_steps, check_seqs_later):
             kn = wl.store(rng.standard_normal((B, case.HD)), dt)
             vn = wl.store(rng.standard_normal((B, case.HD)), dt)
         q = wl.step_query(case, step)
-        dkn, dvn, dq = (to_dev(x, dt) for x in (kn[:, None, :], vn[:, None, :], q))
-        ap.ap_compact(dkn, dvn, dBk, dBv, dCk, dCv, n=1, row0=T - 1)
-        ap.ap_decode_attn(dq, dCk, dCv, dBk, dBv, out, ws, T=T, sm_scale=1.0 / math.sqrt(d))
+        dkn, dvn, dq = (to_dev(x, dt) for x in (kn, vn, q))
+        if fused:
+            ap.ap_decode_step(dq, dkn, dvn, dCk, dCv, dBk, dBv, out, ws, T=T, sm_scale=1.0 / math.sqrt(d))
+        else:
+            ap.ap_compact(dkn[:, None, :].contiguous(), dvn[:, None, :].contiguous(), dBk, dBv, dCk, dCv,
+                          n=1, row0=T - 1)
+            ap.ap_decode_attn(dq, dCk, dCv, dBk, dBv, out, ws, T=T, sm_scale=1.0 / math.sqrt(d))
         torch.cuda.synchronize()
         if not checked:
             continue
@@ -77,15 +82,16 @@ def run_config(case, check_steps, check_seqs_later):
     return worst
 
 
-def test_config2_full_size():
+@pytest.mark.parametrize("fused", [False, True], ids=["compact+attn", "decode_step"])
+def test_config2_full_size(fused):
     t0 = time.time()
     case = wl.config2(seed=0)
     print(f"config 2 generated in {time.time() - t0:.0f} s", flush=True)
-    run_config(case, (0, 63, 127), range(case.B))
+    run_config(case, (0, 63, 127), range(case.B), fused)
 
 
 def test_config3_full_size():
     t0 = time.time()
     case = wl.config3(seed=0)
     print(f"config 3 generated in {time.time() - t0:.0f} s", flush=True)
-    run_config(case, (0, 31, 63), (0, 31, 63))
+    run_config(case, (0, 31, 63), (0, 31, 63), fused=True)
