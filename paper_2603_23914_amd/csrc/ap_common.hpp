@@ -131,6 +131,8 @@ ap_status launch_expand_append(ap_dtype dt, bool out_f32, const void* Bv, int64_
                                const float* part_U, const float* pnew, float* pout, void* out,
                                float* lse, int B, int H, int d, int r, int T, int T_cap, int nsplit,
                                hipStream_t stream);
+ap_status launch_merge_splits(const float* part_ml, const float* part_U, float* out_ml, float* out_U,
+                              float* pnew, int B, int H, int r, int S, hipStream_t stream);
 ap_status launch_merge_expand(ap_dtype dt, bool out_f32, const float* part_ml, const float* part_U,
                               const void* Bv, int64_t bstride, void* out, float* lse, int B, int H,
                               int d, int r, int nsplit, hipStream_t stream);

@@ -446,6 +446,67 @@ reduce_out(const float* __restrict__ pout, void* __restrict__ out, int HD, int n
   }
 }
 
+
+// ------------------------------------------------------------------------------------------
+// merge_splits: many token splits (small batches) are merged once, in parallel, before the
+// expansion: U'[h, j] = sum_s 2^(m_s - m*) U_s[h, j], l' = sum_s 2^(m_s - m*) l_s, m' = m*, written
+// as a single split, and the deferred token's weight is rescaled to the merged reference.
+//   grid (ceil(r / 64), H, B), 256 threads = 4 groups of splits x 64 columns.
+// ------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(256)
+merge_splits(const float* __restrict__ part_ml, const float* __restrict__ part_U,
+             float* __restrict__ out_ml, float* __restrict__ out_U, float* __restrict__ pnew,
+             int H, int r, int S) {
+  extern __shared__ __attribute__((aligned(16))) float lds_ms[];   // [S] weights, then [4][64]
+  __shared__ float red[8];
+  const int tid = threadIdx.x, lane = tid & 63, grp = tid >> 6;
+  const int h = blockIdx.y, b = blockIdx.z;
+  const size_t pb = (size_t)b * S * H + h;                 // + s*H
+  float* wgt = lds_ms;
+  float* acc4 = lds_ms + S;
+  // m* = max_s m_s
+  float m = -INFINITY;
+  for (int s = tid; s < S; s += 256) m = fmaxf(m, part_ml[(pb + (size_t)s * H) * 2]);
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
+  if (lane == 0) red[grp] = m;
+  __syncthreads();
+  m = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+  float L = 0.f;
+  for (int s = tid; s < S; s += 256) {
+    const float ws = fast_exp2(part_ml[(pb + (size_t)s * H) * 2] - m);
+    wgt[s] = ws;
+    L += ws * part_ml[(pb + (size_t)s * H) * 2 + 1];
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) L += __shfl_xor(L, o);
+  if (lane == 0) red[4 + grp] = L;
+  __syncthreads();
+  L = (red[4] + red[5]) + (red[6] + red[7]);
+  const int j = blockIdx.x * 64 + lane;
+  float acc = 0.f;
+  if (j < r) {
+    int s = grp;
+    for (; s + 28 < S; s += 32) {                          // eight loads in flight
+      float u[8];
+#pragma unroll
+      for (int k = 0; k < 8; ++k) u[k] = part_U[(pb + (size_t)(s + 4 * k) * H) * r + j];
+#pragma unroll
+      for (int k = 0; k < 8; ++k) acc = fmaf(wgt[s + 4 * k], u[k], acc);
+    }
+    for (; s < S; s += 4) acc = fmaf(wgt[s], part_U[(pb + (size_t)s * H) * r + j], acc);
+  }
+  acc4[grp * 64 + lane] = acc;
+  __syncthreads();
+  if (grp == 0 && j < r)
+    out_U[((size_t)b * H + h) * r + j] = (acc4[lane] + acc4[64 + lane]) + (acc4[128 + lane] + acc4[192 + lane]);
+  if (blockIdx.x == 0 && tid == 0) {
+    out_ml[((size_t)b * H + h) * 2] = m;
+    out_ml[((size_t)b * H + h) * 2 + 1] = L;
+    if (pnew) pnew[(size_t)b * H + h] *= wgt[S - 1];        // weight of the last split's reference
+  }
+}
+
 }  // namespace
 int basis_rows_per_wave(int B, int r);
 namespace {
@@ -496,10 +557,21 @@ int basis_rows_per_wave(int B, int r) {
   int rpw = (int)(((int64_t)B * r + 2047) / 2048);
   return rpw < 4 ? 4 : (rpw > 32 ? 32 : rpw);
 }
-// expand_append: about four two-wave workgroups per CU in one round; rows per workgroup
+// expand_append: about four two-wave workgroups per CU in one round, but never more than 16 row
+// blocks per sequence (each block writes an HD-wide partial output that reduce_out reads back)
 int expand_rows_per_pair(int B, int r) {
   int rpw = (int)(((int64_t)B * r + 1023) / 1024);
+  const int floor16 = (r + 15) / 16;
+  if (rpw < floor16) rpw = floor16;
   return rpw < 4 ? 4 : (rpw > 64 ? 64 : rpw);
+}
+
+ap_status launch_merge_splits(const float* part_ml, const float* part_U, float* out_ml, float* out_U,
+                              float* pnew, int B, int H, int r, int S, hipStream_t stream) {
+  const size_t lds = ((size_t)S + 256) * 4;
+  hipLaunchKernelGGL(merge_splits, dim3((r + 63) / 64, H, B), dim3(256), lds, stream, part_ml, part_U,
+                     out_ml, out_U, pnew, H, r, S);
+  return AP_OK;
 }
 int expand_row_blocks(int B, int r) { return (r + expand_rows_per_pair(B, r) - 1) / expand_rows_per_pair(B, r); }
 

@@ -152,18 +152,43 @@ compact_rows(const void* __restrict__ X, const void* __restrict__ Bm, int64_t bs
   }
 }
 
-// grid (r/64, T, B), 64 threads: one scale block per wave.
-__global__ void __launch_bounds__(64)
+// grid (ceil(T / 4), B), 256 threads: a wave owns one token and walks its row 512 columns at a
+// time (16-byte loads; 8 lanes share a 64-column scale block).
+__global__ void __launch_bounds__(256)
 quantize_i8(const uint16_t* __restrict__ C, int8_t* __restrict__ codes,
-            uint16_t* __restrict__ scales, int T_cap, int r) {
-  const int blk = blockIdx.x, t = blockIdx.y, b = blockIdx.z, lane = threadIdx.x;
+            uint16_t* __restrict__ scales, int T, int T_cap, int r) {
+  const int lane = threadIdx.x & 63, t = blockIdx.x * 4 + (threadIdx.x >> 6), b = blockIdx.y;
+  if (t >= T) return;
   const size_t row = (size_t)b * T_cap + t;
-  const float c = bits_to_f32(C[row * r + blk * kCols + lane], F16Tag{});
-  int8_t code;
-  uint16_t sb;
-  quantize_block(c, code, sb);
-  codes[row * r + blk * kCols + lane] = code;
-  if (lane == 0) scales[row * (r / kCols) + blk] = sb;
+  for (int c0 = 0; c0 < r; c0 += 512) {
+    const int col = c0 + lane * 8;
+    const bool live = col < r;
+    u32x4_t v = {0, 0, 0, 0};
+    if (live) v = *(const u32x4_t*)(C + row * r + col);
+    float x[8];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) { x[2 * e] = lo_to_f32(v[e], F16Tag{}); x[2 * e + 1] = hi_to_f32(v[e], F16Tag{}); }
+    float amax = 0.f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) amax = fmaxf(amax, fabsf(x[e]));
+#pragma unroll
+    for (int o = 1; o < 8; o <<= 1) amax = fmaxf(amax, __shfl_xor(amax, o));
+    const _Float16 sh = (_Float16)(amax / 127.0f);          // IEEE divide, RNE to fp16
+    const float s = (float)sh;
+    uint32_t lo = 0, hi = 0;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      float q = 0.f;
+      if (s != 0.f) q = fminf(fmaxf(rintf(x[e] / s), -127.f), 127.f);
+      const uint32_t byte = (uint32_t)(int)q & 0xffu;
+      if (e < 4) lo |= byte << (8 * e); else hi |= byte << (8 * (e - 4));
+    }
+    if (live) {
+      const u32x2_t cw = {lo, hi};
+      *(u32x2_t*)(codes + row * r + col) = cw;
+      if ((lane & 7) == 0) scales[row * (r / kCols) + (col >> 6)] = __builtin_bit_cast(uint16_t, sh);
+    }
+  }
 }
 
 template <class Tag>
@@ -206,9 +231,9 @@ ap_status launch_compact(const CompactArgs& a) {
 
 ap_status launch_quantize_i8(const void* C, void* codes, void* scales, int B, int T, int T_cap,
                              int r, hipStream_t stream) {
-  AP_REQUIRE(B <= 65535 && T <= 65535, AP_ERR_UNSUPPORTED, "ap_quantize_i8: B, T must be <= 65535");
-  hipLaunchKernelGGL(quantize_i8, dim3(r / kCols, T, B), dim3(64), 0, stream, (const uint16_t*)C,
-                     (int8_t*)codes, (uint16_t*)scales, T_cap, r);
+  AP_REQUIRE(B <= 65535, AP_ERR_UNSUPPORTED, "ap_quantize_i8: B must be <= 65535");
+  hipLaunchKernelGGL(quantize_i8, dim3((T + 3) / 4, B), dim3(256), 0, stream, (const uint16_t*)C,
+                     (int8_t*)codes, (uint16_t*)scales, T, T_cap, r);
   return check_launch("ap_quantize_i8");
 }
 

@@ -322,6 +322,7 @@ struct AttnParams {
   float* part_ml;       // [B][S][H][2]   (softmax reference exponent in log2 units, sum)
   float* part_U;        // [B][S][H][r]
   int B, T, T_cap, r, H, nsplit;
+  int xcd_aware;        // workgroup numbering, see wg_coords
   int nh;               // C_v LDS ring depth in 16-row units (even, >= 2)
   // rank-ragged launches only: the group lists of ap_select_ranks and the per-token ranks
   const int32_t* rank_k;      // [B][T] or null (= r)
@@ -358,14 +359,20 @@ struct AttnParams {
 // it by more than kLazy, so the rescale factor is 1 on almost every tile.
 //
 // Workgroup id -> (sequence, split).  Consecutive workgroup ids go to different XCDs (8 of
-// them, each with its own L2), so sequence b lives on XCD b % 8 and its splits are neighbours
-// in that XCD's dispatch order: the folded query of a sequence is fetched from HBM once and
-// found in L2 by the other splits.
-__device__ __forceinline__ void wg_coords(int nsplit, int& b, int& s) {
+// them, each with its own L2).  With whole groups of 8 sequences (xcd_aware), sequence b lives
+// on XCD b % 8 and its splits are neighbours in that XCD's dispatch order: the folded query of
+// a sequence is fetched from HBM once and found in L2 by the other splits.  Smaller batches
+// keep the plain numbering, which spreads a sequence's splits over all XCDs.
+__device__ __forceinline__ void wg_coords(int nsplit, int xcd_aware, int& b, int& s) {
   const int id = __builtin_amdgcn_readfirstlane((int)blockIdx.x);
-  const int k = id >> 3;
-  b = (k / nsplit) * 8 + (id & 7);
-  s = k - (k / nsplit) * nsplit;
+  if (xcd_aware) {
+    const int k = id >> 3;
+    b = (k / nsplit) * 8 + (id & 7);
+    s = k - (k / nsplit) * nsplit;
+  } else {
+    b = id / nsplit;
+    s = id - b * nsplit;
+  }
 }
 
 // State every wave carries through the token loop, whatever its role.
@@ -407,7 +414,7 @@ struct WaveCtx {
     w = __builtin_amdgcn_readfirstlane(tid >> 6);
     lane = tid & 63; n = lane & 15; g = lane >> 4;
     r = uni(p.r); T = uni(p.T); H = uni(p.H); nh = uni(p.nh); nsplit = uni(p.nsplit); dbg = uni(p.dbg);
-    wg_coords(nsplit, b, s);
+    wg_coords(nsplit, uni(p.xcd_aware), b, s);
     Tv = T - uni(p.defer_v);
     pnew = uni_ptr(p.pnew);
     // ring unit geometry: 16 rows of (cpr+1) 16-byte chunks (one pad chunk per row shifts
@@ -932,8 +939,8 @@ __global__ void __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))
 attn_partial(const AttnParams p) {
   {
     int b, s;
-    wg_coords(p.nsplit, b, s);
-    if (b >= p.B) return;                 // the grid is padded to whole groups of 8 sequences
+    wg_coords(p.nsplit, p.xcd_aware, b, s);
+    if (b >= p.B) return;
   }
   if (__builtin_amdgcn_readfirstlane(threadIdx.x >> 6) < 4)
     score_role<Tag, MT, RMAX, SPLIT, RAGGED, I8>(p);
@@ -962,6 +969,7 @@ int device_cus() {
 // query needs no GPU.
 constexpr int kMaxTilesPerSplit = 128;   // bounds the LDS index table of rank-ragged launches
 constexpr int kMaxGroups = 8;
+constexpr int kInlineMergeSplits = 8;    // more splits than this are merged by their own kernel
 
 int choose_nsplit(int B, int T) {
   const int ntiles = (T + kTile - 1) / kTile;
@@ -974,7 +982,7 @@ int choose_nsplit(int B, int T) {
 }
 
 struct WsLayout {
-  size_t qp, ml, u, po, pn, total;
+  size_t qp, ml, u, po, pn, mml, mu, total;
 };
 WsLayout ws_layout(int B, int H, int d, int T, int r) {
   const int Hp = (H + 15) / 16 * 16;
@@ -990,6 +998,10 @@ WsLayout ws_layout(int B, int H, int d, int T, int r) {
   off += round_up((size_t)B * expand_row_blocks(B, r) * H * d * 4, 256);
   w.pn = off;                              // the newest token's softmax weights of a fused step
   off += round_up((size_t)B * H * 4, 256);
+  w.mml = off;                             // many splits: merged (m, l) and U as a single split
+  off += round_up((size_t)B * H * 2 * 4, 256);
+  w.mu = off;
+  off += S > kInlineMergeSplits ? round_up((size_t)B * H * r * 4, 256) : 0;
   w.total = off;
   return w;
 }
@@ -1026,7 +1038,8 @@ ap_status launch_attn(AttnParams p, int B, hipStream_t stream) {
     attr_set = true;
   }
   p.B = B;
-  hipLaunchKernelGGL(kern, dim3(8 * ((B + 7) / 8) * p.nsplit), dim3(512), lds, stream, p);
+  p.xcd_aware = B % 8 == 0 ? 1 : 0;
+  hipLaunchKernelGGL(kern, dim3(B * p.nsplit), dim3(512), lds, stream, p);
   return AP_OK;
 }
 
@@ -1113,13 +1126,24 @@ ap_status run_decode(const DecodeArgs& a) {
   st = dispatch_attn<Tag, SPLIT>(p, a.B, a.stream);
   prof_mark(a.stream, false);
   if (st != AP_OK) return st;
+  int S_exp = S;
+  if (S > kInlineMergeSplits) {            // small batch, many splits: merge them in parallel first
+    float* ml1 = (float*)(ws + wl.mml);
+    float* U1 = (float*)(ws + wl.mu);
+    st = launch_merge_splits(ml, U, ml1, U1, one_pass_v ? (float*)(ws + wl.pn) : nullptr, a.B, a.H, a.r,
+                             S, a.stream);
+    if (st != AP_OK) return st;
+    ml = ml1;
+    U = U1;
+    S_exp = 1;
+  }
   if (one_pass_v)
     st = launch_expand_append(a.dt, a.dt_out == AP_F32, a.Bv, a.basis_batch_stride, a.v_new,
                               (void*)a.Cv, ml, U, (const float*)(ws + wl.pn), (float*)(ws + wl.po),
-                              a.out, a.lse, a.B, a.H, a.d, a.r, a.T, a.T_cap, S, a.stream);
+                              a.out, a.lse, a.B, a.H, a.d, a.r, a.T, a.T_cap, S_exp, a.stream);
   else
     st = launch_merge_expand(a.dt, a.dt_out == AP_F32, ml, U, a.Bv, a.basis_batch_stride, a.out, a.lse,
-                             a.B, a.H, a.d, a.r, S, a.stream);
+                             a.B, a.H, a.d, a.r, S_exp, a.stream);
   if (st != AP_OK) return st;
   return check_launch("ap_decode_attn");
 }

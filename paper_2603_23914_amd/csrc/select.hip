@@ -11,7 +11,9 @@
 //      give each token its position among equal keys, which decides its group;
 //   3. block-wide prefix sums of the group counts give each token its slot in its group's
 //      ascending index list.
-// One workgroup of 1024 threads per batch row; all integer work, results are unique.
+// One workgroup of 1024 threads per batch row; rows of up to 32768 tokens are first copied to
+// LDS as sort keys, so the four radix passes and the two walks read LDS, not memory.  All
+// integer work, results are unique.
 #include "ap_common.hpp"
 
 namespace ap {
@@ -81,7 +83,11 @@ __device__ __forceinline__ int block_excl_scan(int v, int* wave_tot, int* total)
   return base + incl - v;
 }
 
+constexpr int kStagedMax = 32768;      // tokens whose keys fit the dynamic LDS slice (128 KiB)
+
+template <bool STAGED>
 __global__ void __launch_bounds__(kThreads) select_ranks_kernel(const SelectParams p) {
+  extern __shared__ __attribute__((aligned(16))) uint32_t keys_lds[];   // STAGED: [T]
   __shared__ uint32_t hist[kMaxF - 1][256];
   __shared__ uint32_t s_prefix[kMaxF - 1];   // key bits fixed so far (kappa after pass 4)
   __shared__ uint32_t s_need[kMaxF - 1];     // 1-based position still to find (quota after pass 4)
@@ -89,6 +95,11 @@ __global__ void __launch_bounds__(kThreads) select_ranks_kernel(const SelectPara
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int b = blockIdx.x, T = p.T, F = p.F, nb = F - 1;
   const float* m = p.mass + (size_t)b * T;
+  if (STAGED) {
+    for (int t = tid; t < T; t += kThreads) keys_lds[t] = key_of(m[t]);
+    __syncthreads();
+  }
+  auto key_at = [&](int t) -> uint32_t { return STAGED ? keys_lds[t] : key_of(m[t]); };
 
   // a cut at 0 or at T needs no threshold search
   bool active[kMaxF - 1];
@@ -114,15 +125,16 @@ __global__ void __launch_bounds__(kThreads) select_ranks_kernel(const SelectPara
     const int Tpad = (T + 63) & ~63;     // whole waves stay in the loop (hist_add uses ballots)
     for (int t = tid; t < Tpad; t += kThreads) {
       const bool in = t < T;
-      const uint32_t key = in ? key_of(m[t]) : 0u;
+      const uint32_t key = in ? key_at(t) : 0u;
       const uint32_t dig = (key >> shift) & 255u;
       if (pass == 0) {
         hist_add(hist[0], in ? dig : kNone);       // every boundary shares the empty prefix
       } else {
+        // few keys still match a boundary's prefix: plain atomics
         const uint32_t hi = key >> (shift + 8);
 #pragma unroll
         for (int g = 0; g < kMaxF - 1; ++g) {
-          if (active[g]) hist_add(hist[g], (in && hi == (pre[g] >> (shift + 8))) ? dig : kNone);
+          if (active[g] && in && hi == (pre[g] >> (shift + 8))) atomicAdd(&hist[g][dig], 1u);
         }
       }
     }
@@ -179,7 +191,7 @@ __global__ void __launch_bounds__(kThreads) select_ranks_kernel(const SelectPara
 #pragma unroll
   for (int g = 0; g < kMaxF - 1; ++g) eq[g] = 0;
   for (int t = t0; t < t1; ++t) {
-    const uint32_t key = key_of(m[t]);
+    const uint32_t key = key_at(t);
 #pragma unroll
     for (int g = 0; g < kMaxF - 1; ++g) eq[g] += (key == kappa[g]) ? 1 : 0;
   }
@@ -192,7 +204,7 @@ __global__ void __launch_bounds__(kThreads) select_ranks_kernel(const SelectPara
   for (int g = 0; g < kMaxF; ++g) cnt[g] = 0;
   int32_t* rank_row = p.rank_out + (size_t)b * T;
   for (int t = t0; t < t1; ++t) {
-    const uint32_t key = key_of(m[t]);
+    const uint32_t key = key_at(t);
     int grp = nb;
 #pragma unroll
     for (int g = kMaxF - 2; g >= 0; --g) {
@@ -249,7 +261,21 @@ ap_status launch_select_ranks(const float* mass, int B, int T, int F, const int3
   p.rank_out = rank_out;
   p.bucket_off = bucket_off;
   p.bucket_idx = bucket_idx;
-  hipLaunchKernelGGL(select_ranks_kernel, dim3(B), dim3(kThreads), 0, stream, p);
+  if (T <= kStagedMax) {
+    static bool attr_set = false;
+    if (!attr_set) {
+      hipError_t e = hipFuncSetAttribute((const void*)select_ranks_kernel<true>,
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, kStagedMax * 4);
+      if (e != hipSuccess) {
+        set_error("hipFuncSetAttribute: %s", hipGetErrorString(e));
+        return AP_ERR_HIP;
+      }
+      attr_set = true;
+    }
+    hipLaunchKernelGGL(select_ranks_kernel<true>, dim3(B), dim3(kThreads), (size_t)T * 4, stream, p);
+  } else {
+    hipLaunchKernelGGL(select_ranks_kernel<false>, dim3(B), dim3(kThreads), 0, stream, p);
+  }
   return check_launch("ap_select_ranks");
 }
 
