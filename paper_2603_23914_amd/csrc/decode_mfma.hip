@@ -335,7 +335,8 @@ struct AttnParams {
   // row does not exist yet; its softmax weight is exported and the expansion pass adds it
   int defer_v;          // 0 or 1
   float* pnew;          // [B][H] weight of token T-1 relative to the last split's reference
-  int dbg;              // experiments: 1 = no loads, 2 = no math, 4 = phase timers
+  int dbg;              // kernel studies (AP_KERNEL_TIMERS builds only, else 0): 1 = no loads,
+                        // 2 = no math, 4 = phase timers, 8 = per-tile stamps
   unsigned long long* dbg_out;
 };
 
@@ -579,6 +580,32 @@ struct WaveCtx {
   }
 };
 
+// Phase timers and per-tile time stamps for kernel studies (build with -DAP_KERNEL_TIMERS and
+// set AP_DEBUG_ATTN: 4 = phase sums of workgroup (0,0) into the head of part_U, 8 = per-tile
+// stamps into the bytes after the workspace, which the caller must have allocated).
+#ifdef AP_KERNEL_TIMERS
+#define AP_T_ENTRY const unsigned long long t_entry_ = __builtin_readcyclecounter();
+#define AP_T_START                                         \
+  unsigned long long tm[8] = {0, 0, 0, 0, 0, 0, 0, 0};     \
+  unsigned long long t0_ = __builtin_readcyclecounter();   \
+  tm[0] = t0_ - t_entry_;
+#define AP_TICK(k) { const unsigned long long now_ = __builtin_readcyclecounter(); tm[k] += now_ - t0_; t0_ = now_; }
+#define AP_T_STAMP(t)                                                                                    \
+  if ((cx.dbg & 8) && cx.lane == 0 && (t) < 64)                                                          \
+    uni_ptr(p.dbg_out)[1024 + ((cx.b * cx.nsplit + cx.s) * 8 + cx.w) * 64 + (t)] = __builtin_readcyclecounter();
+#define AP_T_REPORT                                                        \
+  if ((cx.dbg & 4) && cx.b == 0 && cx.s == 0 && cx.lane == 0) {            \
+    unsigned long long* out_ = uni_ptr(p.dbg_out);                         \
+    for (int k = 0; k < 8; ++k) out_[cx.w * 8 + k] = tm[k];                \
+  }
+#else
+#define AP_T_ENTRY
+#define AP_T_START
+#define AP_TICK(k)
+#define AP_T_STAMP(t)
+#define AP_T_REPORT
+#endif
+
 template <class Tag, int MT, int RMAX, bool SPLIT, bool RAGGED, bool I8>
 __device__ __noinline__ void score_role(const AttnParams& p) {
   // a score wave owns "units" w, w+4, ... of the rank axis, 64 bytes of a row each:
@@ -587,7 +614,7 @@ __device__ __noinline__ void score_role(const AttnParams& p) {
   constexpr int NKW = I8 ? 2 * NBW : (RMAX / 32 + 3) / 4; // score k-steps per score wave
   constexpr int NA = I8 ? NBW : NKW;                      // 16-byte row loads per 16-row half
   constexpr int Hp = MT * 16;
-  const unsigned long long t_entry_ = __builtin_readcyclecounter();
+  AP_T_ENTRY
   WaveCtx<Tag, MT, SPLIT, RAGGED, I8> cx;
   cx.init(p);
   float* part_U = uni_ptr(p.part_U);
@@ -689,13 +716,9 @@ __device__ __noinline__ void score_role(const AttnParams& p) {
   };
   if (cx.ntl > 0) load_A(0);
 
-  unsigned long long tm[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-#define AP_TICK(k) { const unsigned long long now_ = __builtin_readcyclecounter(); tm[k] += now_ - t0_; t0_ = now_; }
-  unsigned long long t0_ = __builtin_readcyclecounter();
-  tm[0] = t0_ - t_entry_;
+  AP_T_START
   for (int t = 0; t < cx.ntl; ++t) {
-    if ((cx.dbg & 8) && cx.lane == 0 && t < 64)
-      uni_ptr(p.dbg_out)[1024 + ((cx.b * cx.nsplit + cx.s) * 8 + cx.w) * 64 + t] = __builtin_readcyclecounter();
+    AP_T_STAMP(t)
     f32x4_t sp[MT][2];
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) { f32x4_t z = {0.f, 0.f, 0.f, 0.f}; sp[mt][0] = z; sp[mt][1] = z; }
@@ -732,10 +755,7 @@ __device__ __noinline__ void score_role(const AttnParams& p) {
   }
   cx.store_ml(part_ml);
   AP_TICK(6)
-  if ((cx.dbg & 4) && cx.b == 0 && cx.s == 0 && cx.lane == 0) {
-    unsigned long long* out_ = uni_ptr(p.dbg_out);
-    for (int k = 0; k < 8; ++k) out_[cx.w * 8 + k] = tm[k];
-  }
+  AP_T_REPORT
 }
 
 template <class Tag, int MT, int RMAX, bool SPLIT, bool RAGGED, bool I8>
@@ -745,7 +765,7 @@ __device__ __noinline__ void sum_role(const AttnParams& p) {
   constexpr int NJ = I8 ? 4 : 2;                                  // columns per LDS dword
   constexpr int MAXBLK = (kHalf * (RMAX * EB / 16 + 1) + 63) / 64;  // 1 KiB blocks per ring unit
   constexpr int NSLOT = (MAXBLK + 3) / 4;
-  const unsigned long long t_entry_ = __builtin_readcyclecounter();
+  AP_T_ENTRY
   WaveCtx<Tag, MT, SPLIT, RAGGED, I8> cx;
   cx.init(p);
   float* part_U = uni_ptr(p.part_U);
@@ -842,12 +862,9 @@ __device__ __noinline__ void sum_role(const AttnParams& p) {
     for (int j = 0; j < NJ; ++j)
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) { f32x4_t z = {0.f, 0.f, 0.f, 0.f}; U[i][j][mt] = z; }
-  unsigned long long tm[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-  unsigned long long t0_ = __builtin_readcyclecounter();
-  tm[0] = t0_ - t_entry_;
+  AP_T_START
   for (int t = 0; t < cx.ntl; ++t) {
-    if ((cx.dbg & 8) && cx.lane == 0 && t < 64)
-      uni_ptr(p.dbg_out)[1024 + ((cx.b * cx.nsplit + cx.s) * 8 + cx.w) * 64 + t] = __builtin_readcyclecounter();
+    AP_T_STAMP(t)
     wg_barrier();            // partial scores of tile t ready; every sum wave is past tile t-1
     AP_TICK(2)
     if (t == 0) {
@@ -927,12 +944,13 @@ __device__ __noinline__ void sum_role(const AttnParams& p) {
   }
   cx.store_ml(part_ml);
   AP_TICK(6)
-  if ((cx.dbg & 4) && cx.b == 0 && cx.s == 0 && cx.lane == 0) {
-    unsigned long long* out_ = uni_ptr(p.dbg_out);
-    for (int k = 0; k < 8; ++k) out_[cx.w * 8 + k] = tm[k];
-  }
+  AP_T_REPORT
 }
 #undef AP_TICK
+#undef AP_T_ENTRY
+#undef AP_T_START
+#undef AP_T_STAMP
+#undef AP_T_REPORT
 
 template <class Tag, int MT, int RMAX, bool SPLIT, bool RAGGED, bool I8>
 __global__ void __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2)))
@@ -1119,9 +1137,11 @@ ap_status run_decode(const DecodeArgs& a) {
     p.bucket_idx = a.bucket_idx;
     p.F = a.F;
   }
+#ifdef AP_KERNEL_TIMERS
   if (const char* e = getenv("AP_DEBUG_ATTN")) p.dbg = atoi(e);
-  p.dbg_out = (unsigned long long*)U;   // timers overwrite the head of part_U (debug only)
-  if (p.dbg & 8) p.dbg_out = (unsigned long long*)(ws + wl.total);   // caller allocated 2 MiB extra
+  p.dbg_out = (unsigned long long*)U;   // timers overwrite the head of part_U
+  if (p.dbg & 8) p.dbg_out = (unsigned long long*)(ws + wl.total);   // caller allocated extra bytes
+#endif
   prof_mark(a.stream, true);
   st = dispatch_attn<Tag, SPLIT>(p, a.B, a.stream);
   prof_mark(a.stream, false);
