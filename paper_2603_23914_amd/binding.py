@@ -40,11 +40,13 @@ _lib.ap_select_ranks.argtypes = [_vp, _i, _i, _i, _vp, _vp, _c.c_int32, _vp, _vp
 _lib.ap_select_workspace_bytes.restype = _sz
 _lib.ap_select_workspace_bytes.argtypes = [_i, _i, _i]
 _lib.ap_decode_attn.restype = _i
-_lib.ap_decode_attn.argtypes = ([_vp] * 7 + [_i64] + [_vp] * 4 + [_i] + [_vp, _vp] + [_i] * 6 +
+_lib.ap_decode_attn.argtypes = ([_vp] * 7 + [_i64] + [_vp] * 4 + [_i] + [_vp, _vp, _vp] + [_i] * 6 +
                                 [_f, _i, _i, _i, _vp, _sz, _vp])
 _lib.ap_decode_step.restype = _i
-_lib.ap_decode_step.argtypes = ([_vp] * 7 + [_i64] + [_vp] * 4 + [_i] + [_vp, _vp] + [_i] * 6 +
+_lib.ap_decode_step.argtypes = ([_vp] * 7 + [_i64] + [_vp] * 4 + [_i] + [_vp, _vp, _vp] + [_i] * 6 +
                                 [_f, _i, _i, _vp, _sz, _vp])
+_lib.ap_update_importance.restype = _i
+_lib.ap_update_importance.argtypes = [_vp, _vp, _vp, _i, _i, _i, _i, _i64, _f, _vp]
 _lib.ap_decode_workspace_bytes.restype = _sz
 _lib.ap_decode_workspace_bytes.argtypes = [_i] * 6
 _lib.ap_status_string.restype = _c.c_char_p
@@ -59,7 +61,7 @@ _lib.ap_prof_read.restype = _i
 _lib.ap_prof_read.argtypes = [_c.POINTER(_c.c_float), _c.POINTER(_c.c_int)]
 
 EXPORTS = ("ap_compact", "ap_quantize_i8", "ap_select_ranks", "ap_select_workspace_bytes",
-           "ap_decode_attn", "ap_decode_step", "ap_decode_workspace_bytes", "ap_status_string", "ap_last_error",
+           "ap_decode_attn", "ap_decode_step", "ap_update_importance", "ap_decode_workspace_bytes", "ap_status_string", "ap_last_error",
            "ap_version", "ap_prof_enable", "ap_prof_read")
 
 _DT = {torch.float32: AP_F32, torch.float16: AP_F16, torch.bfloat16: AP_BF16, torch.int8: AP_I8}
@@ -146,14 +148,14 @@ def ap_select_ranks(mass, group_rank, cum_num, den: int, rank_out, bucket_off, b
 
 def ap_decode_attn(q, Ck, Cv, Bk, Bv, out, workspace, *, T: int, sm_scale: float,
                    scale_k=None, scale_v=None, rank_k=None, rank_v=None, bucket_off=None,
-                   bucket_idx=None, F: int = 0, lse=None, stream=None) -> None:
+                   bucket_idx=None, F: int = 0, lse=None, scores=None, stream=None) -> None:
     """q, out [B, H, d] (out in q's dtype or fp32); Ck, Cv [B, T_cap, r];
-    Bk, Bv [r, HD] or [B, r, HD]."""
+    Bk, Bv [r, HD] or [B, r, HD]; scores [B, H, T_cap] fp32 (optional output)."""
     B, H, d = q.shape
     T_cap, r = Ck.shape[1], Ck.shape[2]
     _check(_lib.ap_decode_attn(_p(q), _p(Ck), _p(Cv), _p(scale_k), _p(scale_v), _p(Bk), _p(Bv),
                                _bstride(Bk), _p(rank_k), _p(rank_v), _p(bucket_off),
-                               _p(bucket_idx), F, _p(out), _p(lse), B, H, d, T, T_cap, r,
+                               _p(bucket_idx), F, _p(out), _p(lse), _p(scores), B, H, d, T, T_cap, r,
                                float(sm_scale), _DT[q.dtype], _DT[Ck.dtype], _DT[out.dtype],
                                _p(workspace),
                                workspace.numel() * workspace.element_size(), _stream(stream)))
@@ -161,15 +163,22 @@ def ap_decode_attn(q, Ck, Cv, Bk, Bv, out, workspace, *, T: int, sm_scale: float
 
 def ap_decode_step(q, k_new, v_new, Ck, Cv, Bk, Bv, out, workspace, *, T: int, sm_scale: float,
                    rank_k=None, rank_v=None, bucket_off=None, bucket_idx=None, F: int = 0,
-                   lse=None, stream=None) -> None:
+                   lse=None, scores=None, stream=None) -> None:
     """Append k_new, v_new [B, HD] at row T-1, then attend over T rows (one fused call)."""
     B, H, d = q.shape
     T_cap, r = Ck.shape[1], Ck.shape[2]
     _check(_lib.ap_decode_step(_p(q), _p(k_new), _p(v_new), _p(Ck), _p(Cv), _p(Bk), _p(Bv),
                                _bstride(Bk), _p(rank_k), _p(rank_v), _p(bucket_off),
-                               _p(bucket_idx), F, _p(out), _p(lse), B, H, d, T, T_cap, r,
+                               _p(bucket_idx), F, _p(out), _p(lse), _p(scores), B, H, d, T, T_cap, r,
                                float(sm_scale), _DT[q.dtype], _DT[out.dtype], _p(workspace),
                                workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
+def ap_update_importance(scores, lse, mass, *, T: int, alpha: float, stream=None) -> None:
+    """mass [B, >=T] fp32 <- alpha*mass + (1-alpha)*mean_h exp(scores - lse) (Eq. 1, one query)."""
+    B, H, T_cap = scores.shape
+    _check(_lib.ap_update_importance(_p(scores), _p(lse), _p(mass), B, H, T, T_cap, mass.stride(0),
+                                     float(alpha), _stream(stream)))
 
 
 def ap_prof_enable(on: bool) -> None:

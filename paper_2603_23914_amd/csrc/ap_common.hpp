@@ -90,6 +90,7 @@ struct DecodeArgs {
   int F;
   void* out;
   float* lse;
+  float* scores;       // [B, H, T_cap] scaled logits (natural-log units) of every attended token, or null
   int B, H, d, T, T_cap, r;
   float sm_scale;
   ap_dtype dt, dt_coef, dt_out;
@@ -136,6 +137,10 @@ ap_status launch_merge_splits(const float* part_ml, const float* part_U, float* 
 ap_status launch_merge_expand(ap_dtype dt, bool out_f32, const float* part_ml, const float* part_U,
                               const void* Bv, int64_t bstride, void* out, float* lse, int B, int H,
                               int d, int r, int nsplit, hipStream_t stream);
+
+ap_status launch_update_importance(const float* scores, const float* lse, float* mass, int B, int H,
+                                   int T, int T_cap, int64_t mass_stride, float alpha,
+                                   hipStream_t stream);
 
 size_t select_workspace(int B, int T, int F);
 ap_status launch_select_ranks(const float* mass, int B, int T, int F, const int32_t* group_rank,

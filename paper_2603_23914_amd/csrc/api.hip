@@ -217,7 +217,8 @@ static ap_status decode_entry(const char* name, const void* q, const void* k_new
                               const void* scale_v, const void* Bk, const void* Bv,
                               int64_t basis_batch_stride, const int32_t* rank_k,
                               const int32_t* rank_v, const int32_t* bucket_off,
-                              const int32_t* bucket_idx, int F, void* out, float* lse, int B, int H,
+                              const int32_t* bucket_idx, int F, void* out, float* lse, float* scores, int B,
+                              int H,
                               int d, int T, int T_cap, int r, float sm_scale, ap_dtype dt,
                               ap_dtype dt_coef, ap_dtype dt_out, void* workspace, size_t ws_bytes,
                               void* stream) {
@@ -263,7 +264,7 @@ static ap_status decode_entry(const char* name, const void* q, const void* k_new
   AP_REQUIRE(aligned(workspace, 256), AP_ERR_INVALID_ARG, "%s: workspace must be 256-byte aligned",
              name);
   DecodeArgs a{q, k_new, v_new, Ck, Cv, scale_k, scale_v, Bk, Bv, basis_batch_stride, rank_k, rank_v,
-               bucket_off, bucket_idx, ragged ? F : 0, out, lse, B, H, d, T, T_cap, r, sm_scale,
+               bucket_off, bucket_idx, ragged ? F : 0, out, lse, scores, B, H, d, T, T_cap, r, sm_scale,
                dt, dt_coef, dt_out, workspace, ws_bytes, (hipStream_t)stream};
   return dt == AP_F32 ? launch_decode_f32(a) : launch_decode_mfma(a);
 }
@@ -272,25 +273,39 @@ ap_status ap_decode_attn(const void* q, const void* Ck, const void* Cv, const vo
                          const void* scale_v, const void* Bk, const void* Bv,
                          int64_t basis_batch_stride, const int32_t* rank_k, const int32_t* rank_v,
                          const int32_t* bucket_off, const int32_t* bucket_idx, int F, void* out,
-                         float* lse, int B, int H, int d, int T, int T_cap, int r, float sm_scale,
-                         ap_dtype dt, ap_dtype dt_coef, ap_dtype dt_out, void* workspace,
-                         size_t ws_bytes, void* stream) {
+                         float* lse, float* scores, int B, int H, int d, int T, int T_cap, int r,
+                         float sm_scale, ap_dtype dt, ap_dtype dt_coef, ap_dtype dt_out,
+                         void* workspace, size_t ws_bytes, void* stream) {
   return decode_entry("ap_decode_attn", q, nullptr, nullptr, Ck, Cv, scale_k, scale_v, Bk, Bv,
-                      basis_batch_stride, rank_k, rank_v, bucket_off, bucket_idx, F, out, lse, B, H,
+                      basis_batch_stride, rank_k, rank_v, bucket_off, bucket_idx, F, out, lse, scores, B, H,
                       d, T, T_cap, r, sm_scale, dt, dt_coef, dt_out, workspace, ws_bytes, stream);
 }
 
 ap_status ap_decode_step(const void* q, const void* k_new, const void* v_new, void* Ck, void* Cv,
                          const void* Bk, const void* Bv, int64_t basis_batch_stride,
                          const int32_t* rank_k, const int32_t* rank_v, const int32_t* bucket_off,
-                         const int32_t* bucket_idx, int F, void* out, float* lse, int B, int H,
+                         const int32_t* bucket_idx, int F, void* out, float* lse, float* scores, int B,
+                              int H,
                          int d, int T, int T_cap, int r, float sm_scale, ap_dtype dt,
                          ap_dtype dt_out, void* workspace, size_t ws_bytes, void* stream) {
   clear_error();
   AP_REQUIRE(k_new && v_new, AP_ERR_INVALID_ARG, "ap_decode_step: NULL pointer");
   return decode_entry("ap_decode_step", q, k_new, v_new, Ck, Cv, nullptr, nullptr, Bk, Bv,
-                      basis_batch_stride, rank_k, rank_v, bucket_off, bucket_idx, F, out, lse, B, H,
+                      basis_batch_stride, rank_k, rank_v, bucket_off, bucket_idx, F, out, lse, scores, B, H,
                       d, T, T_cap, r, sm_scale, dt, dt, dt_out, workspace, ws_bytes, stream);
+}
+
+ap_status ap_update_importance(const float* scores, const float* lse, float* mass, int B, int H,
+                               int T, int T_cap, int64_t mass_stride, float alpha, void* stream) {
+  clear_error();
+  AP_REQUIRE(scores && lse && mass, AP_ERR_INVALID_ARG, "ap_update_importance: NULL pointer");
+  AP_REQUIRE(B > 0 && H > 0 && T > 0 && T <= T_cap && mass_stride >= T, AP_ERR_INVALID_ARG,
+             "ap_update_importance: need B, H > 0, 0 < T <= T_cap, mass_stride >= T");
+  AP_REQUIRE(alpha >= 0.f && alpha <= 1.f, AP_ERR_INVALID_ARG,
+             "ap_update_importance: alpha must lie in [0, 1]");
+  AP_REQUIRE(B <= 65535, AP_ERR_UNSUPPORTED, "ap_update_importance: B must be <= 65535");
+  return launch_update_importance(scores, lse, mass, B, H, T, T_cap, mass_stride, alpha,
+                                  (hipStream_t)stream);
 }
 
 }  // extern "C"

@@ -60,8 +60,8 @@ f32_fold(const float* __restrict__ q, const float* __restrict__ Bk, int64_t bstr
 // grid (ceil(T/kThreads), H, B): scores.
 __global__ void __launch_bounds__(kThreads)
 f32_scores(const float* __restrict__ Ck, const float* __restrict__ qp,
-           const int32_t* __restrict__ rank_k, float* __restrict__ S, int H, int T, int T_cap,
-           int r) {
+           const int32_t* __restrict__ rank_k, float* __restrict__ S,
+           float* __restrict__ scores, int H, int T, int T_cap, int r) {
   const int t = blockIdx.x * kThreads + threadIdx.x;
   const int h = blockIdx.y, b = blockIdx.z;
   if (t >= T) return;
@@ -72,6 +72,7 @@ f32_scores(const float* __restrict__ Ck, const float* __restrict__ qp,
   double acc = 0.0;
   for (int j = 0; j < rk; ++j) acc += (double)row[j] * (double)qh[j];
   S[((size_t)b * H + h) * T + t] = (float)acc;
+  if (scores) scores[((size_t)b * H + h) * T_cap + t] = (float)acc;
 }
 
 // grid (H, B): softmax, weighted coefficient sum, expansion through Bv.
@@ -138,7 +139,7 @@ ap_status launch_decode_f32(const DecodeArgs& a) {
   hipLaunchKernelGGL(f32_fold, dim3(a.H, a.B), dim3(kThreads), 0, a.stream, (const float*)a.q,
                      (const float*)a.Bk, a.basis_batch_stride, qp, a.H, a.d, a.r, a.sm_scale);
   hipLaunchKernelGGL(f32_scores, dim3((a.T + kThreads - 1) / kThreads, a.H, a.B), dim3(kThreads), 0,
-                     a.stream, (const float*)a.Ck, qp, a.rank_k, S, a.H, a.T, a.T_cap, a.r);
+                     a.stream, (const float*)a.Ck, qp, a.rank_k, S, a.scores, a.H, a.T, a.T_cap, a.r);
   hipLaunchKernelGGL(f32_softmax_out, dim3(a.H, a.B), dim3(kThreads), 0, a.stream,
                      (const float*)a.Cv, (const float*)a.Bv, a.basis_batch_stride, a.rank_v, S, U,
                      (float*)a.out, a.lse, a.H, a.d, a.T, a.T_cap, a.r);

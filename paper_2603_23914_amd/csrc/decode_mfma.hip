@@ -335,6 +335,7 @@ struct AttnParams {
   // row does not exist yet; its softmax weight is exported and the expansion pass adds it
   int defer_v;          // 0 or 1
   float* pnew;          // [B][H] weight of token T-1 relative to the last split's reference
+  float* scores;        // [B][H][T_cap] scaled logits in natural-log units, or null
   int dbg;              // kernel studies (AP_KERNEL_TIMERS builds only, else 0): 1 = no loads,
                         // 2 = no math, 4 = phase timers, 8 = per-tile stamps
   unsigned long long* dbg_out;
@@ -403,6 +404,8 @@ struct WaveCtx {
   int t_lo, ntl;     // first tile and number of tiles of this split
   int Tv;            // value rows that exist: T, or T-1 while the newest token's row is deferred
   float* pnew;
+  float* scores;     // this sequence's [H][T_cap] logit rows, or null
+  int T_cap;
   // softmax ownership: lane = 8*head_local + slot, slot = 4*tt + gg covers tokens
   // 16*tt + 4*gg .. +3 of the tile for head o_hh
   bool owner;
@@ -418,6 +421,9 @@ struct WaveCtx {
     wg_coords(nsplit, uni(p.xcd_aware), b, s);
     Tv = T - uni(p.defer_v);
     pnew = uni_ptr(p.pnew);
+    T_cap = uni(p.T_cap);
+    scores = uni_ptr(p.scores);
+    if (scores) scores += (size_t)b * H * T_cap;
     // ring unit geometry: 16 rows of (cpr+1) 16-byte chunks (one pad chunk per row shifts
     // consecutive rows across the LDS banks)
     const int cpr = (r * EB) >> 4;
@@ -516,12 +522,22 @@ struct WaveCtx {
   // Softmax of this wave's heads for a tile whose first `valid` slots hold tokens (after
   // the score waves' partial tiles are in xchg).  newl: slot of the deferred token, if any:
   // its weight counts in the sum, is exported, and stays out of the value products.
-  __device__ __forceinline__ void finalize_softmax(int valid, int newl) {
+  __device__ __forceinline__ void finalize_softmax(int valid, int newl, int t) {
     if (!owner) return;
     const int xi = o_hh * 9 + (lane & 7);
     f32x4_t sc = xchg[xi];
 #pragma unroll
     for (int sw = 1; sw < 4; ++sw) sc += xchg[sw * 16 * MT * 9 + xi];
+    if (scores && o_hh < H) {                   // logits out, for importance tracking
+      const int slot = 16 * o_tt + 4 * o_gg;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        if (slot + i < valid) {
+          const int tok = RAGGED ? idxb[t * kTile + slot + i] : gtile(t) * kTile + slot + i;
+          scores[(size_t)o_hh * T_cap + tok] = sc[i] * kLn2;
+        }
+      }
+    }
     if (valid < kTile) {
 #pragma unroll
       for (int i = 0; i < 4; ++i)
@@ -748,7 +764,7 @@ __device__ __noinline__ void score_role(const AttnParams& p) {
     }
     wg_barrier();                                         // partial scores of tile t ready
     AP_TICK(2)
-    cx.finalize_softmax(cx.tile_valid(t), cx.tile_new(t));
+    cx.finalize_softmax(cx.tile_valid(t), cx.tile_new(t), t);
     AP_TICK(3)
     wg_barrier();                                         // weights of tile t ready
     AP_TICK(4)
@@ -873,7 +889,7 @@ __device__ __noinline__ void sum_role(const AttnParams& p) {
     } else if (t - 1 + RT < cx.ntl) {
       issue_tile(t - 1 + RT);                                    // refill tile t-1's slots
     }
-    cx.finalize_softmax(cx.tile_valid(t), cx.tile_new(t));
+    cx.finalize_softmax(cx.tile_valid(t), cx.tile_new(t), t);
     AP_TICK(3)
     {
       // tile t's rows must have landed; the tiles issued after it may stay in flight
@@ -1124,6 +1140,7 @@ ap_status run_decode(const DecodeArgs& a) {
   p.part_ml = ml;
   p.part_U = U;
   p.T = a.T; p.T_cap = a.T_cap; p.r = a.r; p.H = a.H; p.nsplit = S;
+  p.scores = a.scores;
   p.defer_v = one_pass_v ? 1 : 0;
   p.pnew = (float*)(ws + wl.pn);
   if (a.dt_coef == AP_I8) {

@@ -239,7 +239,39 @@ __global__ void __launch_bounds__(kThreads) select_ranks_kernel(const SelectPara
   if (tid <= F) p.bucket_off[(size_t)b * (F + 1) + tid] = cut;
 }
 
+// Importance update of Eq. 1 for one new query: the attention weights of the query, averaged
+// over the heads, enter the moving average.  grid (ceil(T / 256), B), one thread per token.
+__global__ void __launch_bounds__(256)
+update_importance_kernel(const float* __restrict__ scores, const float* __restrict__ lse,
+                         float* __restrict__ mass, int H, int T, int T_cap, int64_t mass_stride,
+                         float alpha) {
+  const int t = blockIdx.x * 256 + threadIdx.x, b = blockIdx.y;
+  if (t >= T) return;
+  const float* s = scores + (size_t)b * H * T_cap + t;
+  const float* l = lse + (size_t)b * H;
+  float acc = 0.f;
+  int h = 0;
+  for (; h + 8 <= H; h += 8) {                 // 8 independent loads in flight per thread
+    float v[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] = s[(size_t)(h + i) * T_cap];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc += __expf(v[i] - l[h + i]);
+  }
+  for (; h < H; ++h) acc += __expf(s[(size_t)h * T_cap] - l[h]);
+  float* m = mass + (size_t)b * mass_stride + t;
+  *m = alpha * *m + (1.0f - alpha) * (acc / (float)H);
+}
+
 }  // namespace
+
+ap_status launch_update_importance(const float* scores, const float* lse, float* mass, int B, int H,
+                                   int T, int T_cap, int64_t mass_stride, float alpha,
+                                   hipStream_t stream) {
+  hipLaunchKernelGGL(update_importance_kernel, dim3((T + 255) / 256, B), dim3(256), 0, stream, scores,
+                     lse, mass, H, T, T_cap, mass_stride, alpha);
+  return check_launch("ap_update_importance");
+}
 
 size_t select_workspace(int, int, int) { return 256; }   // every intermediate lives in LDS
 

@@ -43,10 +43,10 @@ def test_argument_validation_without_gpu():
     lib.ap_last_error.restype = ctypes.c_char_p
     vp = ctypes.c_void_p
     lib.ap_decode_attn.argtypes = ([vp] * 7 + [ctypes.c_int64] + [vp] * 4 + [ctypes.c_int] +
-                                   [vp, vp] + [ctypes.c_int] * 6 +
+                                   [vp, vp, vp] + [ctypes.c_int] * 6 +
                                    [ctypes.c_float, ctypes.c_int, ctypes.c_int, ctypes.c_int, vp, ctypes.c_size_t, vp])
     st = lib.ap_decode_attn(None, None, None, None, None, None, None, 0, None, None, None, None, 0,
-                            None, None, 1, 4, 32, 64, 64, 16, 0.1, 0, 0, 0, None, 0, None)
+                            None, None, None, 1, 4, 32, 64, 64, 16, 0.1, 0, 0, 0, None, 0, None)
     assert st == 1 and b"NULL" in lib.ap_last_error()
     gr = (ctypes.c_int32 * 2)(64, 128)                                     # increasing: invalid
     cn = (ctypes.c_int32 * 2)(1, 2)
@@ -56,3 +56,8 @@ def test_argument_validation_without_gpu():
     st = lib.ap_select_ranks(one, 1, 8, 2, ctypes.cast(gr, vp), ctypes.cast(cn, vp), 2, one, one,
                              one, one, 1 << 20, None)
     assert st == 1 and b"non-increasing" in lib.ap_last_error()
+    lib.ap_update_importance.argtypes = [vp, vp, vp] + [ctypes.c_int] * 4 + [ctypes.c_int64, ctypes.c_float, vp]
+    assert lib.ap_update_importance(None, one, one, 1, 4, 8, 8, 8, 0.5, None) == 1
+    assert lib.ap_update_importance(one, one, one, 1, 4, 9, 8, 9, 0.5, None) == 1     # T > T_cap
+    assert lib.ap_update_importance(one, one, one, 1, 4, 8, 8, 8, 1.5, None) == 1     # alpha > 1
+    assert b"alpha" in lib.ap_last_error()

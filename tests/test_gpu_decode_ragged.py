@@ -115,3 +115,27 @@ def test_config4_full_size():
         ref = oracle_ragged("f16", case, q, T, rank.cpu().numpy())
         rel = assert_close(got, ref, "f16", f"config 4 step {step}")
         print(f"  step {step}: max|err|/||out||inf = {rel:.2e}", flush=True)
+
+
+def test_eviction_variant_drops_the_last_group():
+    """The paper's eviction variant (low-importance group evicted instead of decoded at low
+    rank): passing only the first F-1 group lists makes the kernel walk only the kept tokens.
+    Oracle: attention over the kept tokens alone."""
+    from paper_2603_23914_amd import binding as ap
+    dtype, B, H, d, r, T = "f16", 2, 32, 128, 512, 500
+    case = wl.decode_case(dtype, B, H, d, r, T, steps=0, seed=12, append=False)
+    q = wl.step_query(case, 0)
+    mass = wl.rng_for(12).random((B, T)).astype(np.float32)
+    granks, cum, den = (512, 256, 64), (1, 2, 4), 4          # half of the tokens in the last group
+    rank, off, idx = gpu_select(mass, granks, cum, den)
+    got = run_ragged(dtype, case, q, T, rank, off[:, :3].contiguous(), idx, F=2)  # groups 0 and 1 only
+    P = lambda x: oracle.promote(x, dtype)
+    rank_np, off_np, idx_np = rank.cpu().numpy(), off.cpu().numpy(), idx.cpu().numpy()
+    ref = np.empty_like(got)
+    for b in range(B):
+        kept = np.sort(idx_np[b, :off_np[b, 2]])
+        ref[b] = oracle.decode_attn(P(q[b]), P(case.Ck[b])[kept], P(case.Cv[b])[kept], P(case.Bk[b]), P(case.Bv[b]),
+                                    rank_k=rank_np[b][kept], rank_v=rank_np[b][kept])
+    assert_close(got, ref, dtype, "eviction of the last group")
+    full = oracle_ragged(dtype, case, q, T, rank_np)
+    assert np.abs(full - ref).max() > 1e-2 * np.abs(ref).max()   # evicting is not truncating
