@@ -40,20 +40,33 @@ __device__ __forceinline__ float dot8(const u32x4_t& a, const u32x4_t& b, float 
   return c;
 }
 
-// Sum over groups of `n` consecutive lanes (n = 4, 8, 16 or 32, wave-uniform), every lane of a
-// group receiving the total: DPP butterflies inside a 16-lane row, one shuffle across rows.
-template <int CTRL>
-__device__ __forceinline__ float dpp_f32(float x) {
+// Lane-crossing sums on the DPP path of the vector ALU (no LDS traffic).  dpp_add<CTRL> is
+// x + x[permuted]; written with a zero fill value and bound_ctrl so that the compiler folds
+// the permutation into the add itself.
+template <int CTRL, int ROW_MASK = 0xf>
+__device__ __forceinline__ float dpp_add(float x) {
   const int v = __builtin_bit_cast(int, x);
-  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(v, v, CTRL, 0xf, 0xf, false));
+  return x + __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, v, CTRL, ROW_MASK, 0xf, true));
 }
-__device__ __forceinline__ float group_sum(float x, int n) {
-  x += dpp_f32<0xB1>(x);                 // quad_perm [1,0,3,2]
-  x += dpp_f32<0x4E>(x);                 // quad_perm [2,3,0,1]
-  if (n >= 8) x += dpp_f32<0x141>(x);    // row_half_mirror: the other quad of an 8-lane group
-  if (n >= 16) x += dpp_f32<0x140>(x);   // row_mirror: the other half of the row
-  if (n >= 32) x += __shfl_xor(x, 16);
+// Sum over groups of N consecutive lanes (N = 4, 8, 16 or 32), every lane of a group
+// receiving the total: butterflies inside a 16-lane row, one shuffle across rows.
+template <int N>
+__device__ __forceinline__ float group_sum(float x) {
+  x = dpp_add<0xB1>(x);                  // quad_perm [1,0,3,2]
+  x = dpp_add<0x4E>(x);                  // quad_perm [2,3,0,1]
+  if (N >= 8) x = dpp_add<0x141>(x);     // row_half_mirror: the other quad of an 8-lane group
+  if (N >= 16) x = dpp_add<0x140>(x);    // row_mirror: the other half of the row
+  if (N >= 32) x += __shfl_xor(x, 16);
   return x;
+}
+// Sum over the 64 lanes, returned wave-uniform: row totals, then rows 1 and 3 take the
+// previous row's total (row_bcast15), then rows 2 and 3 take lane 31's (row_bcast31); lane 63
+// ends with everything.
+__device__ __forceinline__ float wave_sum(float x) {
+  x = group_sum<16>(x);
+  x = dpp_add<0x142, 0xa>(x);
+  x = dpp_add<0x143, 0xc>(x);
+  return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), 63));
 }
 
 struct RowsParams {
@@ -77,7 +90,8 @@ __device__ __forceinline__ void split_hi_lo(float x, uint16_t& hi, uint16_t& lo)
 // grid (ceil(r / (4 rpw)), B), 256 threads.  KPC = 512-element passes that cover the hidden
 // axis; a wave walks its rows through a ring of NBUF row buffers in registers, so NBUF - 1
 // rows (HD * 2 bytes each) are in flight while one is reduced.
-template <class Tag, int KPC, int NBUF, bool DOT, bool FOLD>
+// LPH = d / 8 lanes share a head (FOLD; 1 when the kernel does not fold).
+template <class Tag, int KPC, int NBUF, bool DOT, bool FOLD, int LPH>
 __global__ void __launch_bounds__(256) basis_rows(const RowsParams p) {
   extern __shared__ __attribute__((aligned(16))) float qtile[];   // FOLD: [Hp][4 rpw + 1]
   const int tid = threadIdx.x, lane = tid & 63;
@@ -117,8 +131,7 @@ __global__ void __launch_bounds__(256) basis_rows(const RowsParams p) {
     for (int i = tid; i < p.Hp * pitch; i += 256) qtile[i] = 0.f;   // padded heads stay 0
     __syncthreads();
   }
-  const int lanes_per_head = p.d >> 3;            // 4, 8, 16 or 32 lanes share a head
-  const int dshift = 31 - __builtin_clz((unsigned)p.d);   // d is a power of two
+  constexpr int dshift = FOLD ? 31 - __builtin_clz((unsigned)(LPH * 8)) : 0;   // log2(d)
 
   auto reduce_row = [&](const u32x4_t (&row)[KPC], int i) {
     const int jl = w * rpw + i;
@@ -127,8 +140,7 @@ __global__ void __launch_bounds__(256) basis_rows(const RowsParams p) {
       float acc = 0.f;
 #pragma unroll
       for (int pp = 0; pp < KPC; ++pp) acc = dot8<Tag>(row[pp], xs[pp], acc);
-#pragma unroll
-      for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o);
+      acc = wave_sum(acc);
       if (lane == 0 && live)
         p.C[((size_t)b * p.T_cap + p.row0) * r + j0 + jl] = f32_to_bits(acc, Tag{});
     }
@@ -136,9 +148,9 @@ __global__ void __launch_bounds__(256) basis_rows(const RowsParams p) {
 #pragma unroll
       for (int pp = 0; pp < KPC; ++pp) {
         float part = dot8<Tag>(row[pp], qs[pp], 0.f);
-        part = group_sum(part, lanes_per_head);
+        part = group_sum<LPH>(part);
         const int e0 = pp * 512 + lane * 8;
-        if ((lane & (lanes_per_head - 1)) == 0 && e0 < HD && live)
+        if ((lane & (LPH - 1)) == 0 && e0 < HD && live)
           qtile[(e0 >> dshift) * pitch + jl] = part * p.scale;
       }
     }
@@ -385,8 +397,7 @@ __global__ void __launch_bounds__(128) expand_append(const ExpandParams p) {
     float acc = 0.f;
 #pragma unroll
     for (int pp = 0; pp < KH; ++pp) acc = dot8<Tag>(row[pp], vs[pp], acc);
-#pragma unroll
-    for (int o2 = 32; o2 > 0; o2 >>= 1) acc += __shfl_xor(acc, o2);
+    acc = wave_sum(acc);
     float* slot = dotx + (i & 1) * 2;
     if (lane == 0) slot[half] = acc;
     // both waves run the same number of rows.  Only LDS traffic has to be ordered here: a full
@@ -521,7 +532,11 @@ ap_status launch_rows(RowsParams p, int B, hipStream_t stream) {
   const int kpc = (p.HD + 511) / 512;
 #define AP_ROWS(K, NB)                                                                        \
   if (kpc <= K) {                                                                             \
-    hipLaunchKernelGGL((basis_rows<Tag, K, NB, DOT, FOLD>), grid, dim3(256), lds, stream, p); \
+    if (!FOLD) hipLaunchKernelGGL((basis_rows<Tag, K, NB, DOT, FOLD, 1>), grid, dim3(256), lds, stream, p);            \
+    else if (p.d == 128) hipLaunchKernelGGL((basis_rows<Tag, K, NB, DOT, FOLD, FOLD ? 16 : 1>), grid, dim3(256), lds, stream, p); \
+    else if (p.d == 64) hipLaunchKernelGGL((basis_rows<Tag, K, NB, DOT, FOLD, FOLD ? 8 : 1>), grid, dim3(256), lds, stream, p);   \
+    else if (p.d == 256) hipLaunchKernelGGL((basis_rows<Tag, K, NB, DOT, FOLD, FOLD ? 32 : 1>), grid, dim3(256), lds, stream, p); \
+    else hipLaunchKernelGGL((basis_rows<Tag, K, NB, DOT, FOLD, FOLD ? 4 : 1>), grid, dim3(256), lds, stream, p);                  \
     return AP_OK;                                                                             \
   }
   AP_ROWS(2, 3) AP_ROWS(4, 3) AP_ROWS(8, 3) AP_ROWS(10, 3)
@@ -553,8 +568,9 @@ ap_status launch_basis_rows(ap_dtype dt, const void* Bm, int64_t bstride, const 
 }
 
 int basis_rows_per_wave(int B, int r) {
-  // about two workgroups per CU in one round
-  int rpw = (int)(((int64_t)B * r + 2047) / 2048);
+  // about five workgroups per CU, two of them resident at a time: the start and the end of a
+  // workgroup (vector slices in, folded tile out) then overlap other workgroups' streaming
+  int rpw = (int)(((int64_t)B * r + 5119) / 5120);
   return rpw < 4 ? 4 : (rpw > 32 ? 32 : rpw);
 }
 // expand_append: about four two-wave workgroups per CU in one round, but never more than 16 row

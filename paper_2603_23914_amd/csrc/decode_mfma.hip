@@ -623,7 +623,7 @@ struct WaveCtx {
 #endif
 
 template <class Tag, int MT, int RMAX, bool SPLIT, bool RAGGED, bool I8>
-__device__ __noinline__ void score_role(const AttnParams& p) {
+__device__ __forceinline__ void score_role(const AttnParams& p) {
   // a score wave owns "units" w, w+4, ... of the rank axis, 64 bytes of a row each:
   // 32-column k-steps for 16-bit storage, 64-column scale blocks (two k-steps) for int8
   constexpr int NBW = (RMAX / 64 + 3) / 4;                // int8: scale blocks per score wave
@@ -775,7 +775,7 @@ __device__ __noinline__ void score_role(const AttnParams& p) {
 }
 
 template <class Tag, int MT, int RMAX, bool SPLIT, bool RAGGED, bool I8>
-__device__ __noinline__ void sum_role(const AttnParams& p) {
+__device__ __forceinline__ void sum_role(const AttnParams& p) {
   constexpr int EB = I8 ? 1 : 2;
   constexpr int NGRP = (RMAX * EB + 255) / 256;                   // 256-byte column groups
   constexpr int NJ = I8 ? 4 : 2;                                  // columns per LDS dword
@@ -969,6 +969,15 @@ __device__ __noinline__ void sum_role(const AttnParams& p) {
 #undef AP_T_REPORT
 
 template <class Tag, int MT, int RMAX, bool SPLIT, bool RAGGED, bool I8>
+__device__ __noinline__ void score_role_call(const AttnParams& p) {
+  score_role<Tag, MT, RMAX, SPLIT, RAGGED, I8>(p);
+}
+template <class Tag, int MT, int RMAX, bool SPLIT, bool RAGGED, bool I8>
+__device__ __noinline__ void sum_role_call(const AttnParams& p) {
+  sum_role<Tag, MT, RMAX, SPLIT, RAGGED, I8>(p);
+}
+
+template <class Tag, int MT, int RMAX, bool SPLIT, bool RAGGED, bool I8>
 __global__ void __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2)))
 attn_partial(const AttnParams p) {
   {
@@ -976,10 +985,18 @@ attn_partial(const AttnParams p) {
     wg_coords(p.nsplit, p.xcd_aware, b, s);
     if (b >= p.B) return;
   }
-  if (__builtin_amdgcn_readfirstlane(threadIdx.x >> 6) < 4)
-    score_role<Tag, MT, RMAX, SPLIT, RAGGED, I8>(p);
-  else
-    sum_role<Tag, MT, RMAX, SPLIT, RAGGED, I8>(p);
+  // The roles are inlined: called as functions they would spill their callee-saved registers
+  // and read the launch parameters back from a scratch copy, a dozen serial memory round trips
+  // at the start of every wave.  Only the largest shape (64 heads at rank 640), whose two roles
+  // do not fit one register allocation without spilling inside the tile loop, keeps the calls.
+  constexpr bool kOutline = MT == 4 && RMAX > 512;
+  if (__builtin_amdgcn_readfirstlane(threadIdx.x >> 6) < 4) {
+    if constexpr (kOutline) score_role_call<Tag, MT, RMAX, SPLIT, RAGGED, I8>(p);
+    else score_role<Tag, MT, RMAX, SPLIT, RAGGED, I8>(p);
+  } else {
+    if constexpr (kOutline) sum_role_call<Tag, MT, RMAX, SPLIT, RAGGED, I8>(p);
+    else sum_role<Tag, MT, RMAX, SPLIT, RAGGED, I8>(p);
+  }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -1009,7 +1026,15 @@ int choose_nsplit(int B, int T) {
   const int ntiles = (T + kTile - 1) / kTile;
   int s = (256 + B - 1) / B;
   const int by_table = (ntiles + kMaxGroups + kMaxTilesPerSplit - 1) / kMaxTilesPerSplit;
-  if (s < by_table) s = by_table;
+  if (s < by_table) {
+    // more workgroups than CUs: whole rounds of 256 (a partial last round would run alone)
+    s = by_table;
+    int g = 256, x = B;
+    while (x) { const int t = g % x; g = x; x = t; }          // gcd(256, B)
+    const int step = 256 / g;
+    const int s_up = (s + step - 1) / step * step;
+    if (s_up <= 2 * s) s = s_up;
+  }
   if (s > ntiles) s = ntiles;
   if (s < 1) s = 1;
   return s;
