@@ -165,6 +165,19 @@ __device__ __forceinline__ void wsum_tile(const char* vA, const char* vB, int pi
   // lanes whose columns lie at or beyond the rank contribute zeros (no branch around the
   // MFMAs: the accumulators stay in one straight-line live range); the rows of group i+1
   // are fetched while group i is multiplied
+  // alpha is 1 except when a head's softmax reference exponent moved (rare: the reference
+  // follows the maximum lazily), so the rescaling of the sums is skipped wave-wide otherwise
+  {
+    bool moved = false;
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) moved |= alpha[mt] != 1.0f;
+    if (__builtin_amdgcn_ballot_w64(moved) != 0) {
+#pragma unroll
+      for (int i = 0; i < NGL; ++i)
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) { U[i][0][mt] *= alpha[mt]; U[i][1][mt] *= alpha[mt]; }
+    }
+  }
   uint32_t nx[8] = {0, 0, 0, 0, 0, 0, 0, 0};
   if (n * 2 < cols_left) {
 #pragma unroll
@@ -192,12 +205,10 @@ __device__ __forceinline__ void wsum_tile(const char* vA, const char* vB, int pi
       te[k] = __builtin_amdgcn_perm(v[2 * k + 1], v[2 * k], 0x05040100u);
       to[k] = __builtin_amdgcn_perm(v[2 * k + 1], v[2 * k], 0x07060302u);
     }
-    // alpha is 1 except when the softmax reference exponent moved; multiplying always
-    // (and group by group) keeps the accumulators in one short straight-line live range
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
-      U[i][0][mt] = Mfma<Tag>::run(te, Phi[mt], U[i][0][mt] * alpha[mt]);
-      U[i][1][mt] = Mfma<Tag>::run(to, Phi[mt], U[i][1][mt] * alpha[mt]);
+      U[i][0][mt] = Mfma<Tag>::run(te, Phi[mt], U[i][0][mt]);
+      U[i][1][mt] = Mfma<Tag>::run(to, Phi[mt], U[i][1][mt]);
     }
     if (SPLIT) {
 #pragma unroll
