@@ -12,6 +12,9 @@ from .attnpack_oracle import (  # noqa: F401
     decode_attn_absorbed,
     decode_attn_batched,
     attention_probs,
+    raw_attn,
+    decode_attn_segments,
+    merge_segments,
     select_ranks,
     quantize_i8,
     dequantize_i8,

@@ -206,6 +206,72 @@ def decode_attn_batched(q, Ck, Cv, Bk, Bv, T: int, rank_k=None, rank_v=None,
 
 
 # --------------------------------------------------------------------------
+# the cache the paper's Alg. 1 keeps: compressed segments next to an
+# uncompressed one (text tokens, and new tokens until the next compression)
+# --------------------------------------------------------------------------
+
+def raw_attn(q, K, V, sm_scale=None, return_lse: bool = False):
+    """Textbook softmax attention of one decode query over an uncompressed
+    cache K, V [T, H*d] (the C_u of Alg. 1).  T = 0 gives out = 0, lse = -inf."""
+    q = np.asarray(q, np.float64)
+    K = np.asarray(K, np.float64)
+    V = np.asarray(V, np.float64)
+    H, d = q.shape
+    if sm_scale is None:
+        sm_scale = 1.0 / math.sqrt(d)
+    out = np.zeros((H, d))
+    lse = np.full(H, -np.inf)
+    if K.shape[0] > 0:
+        for h in range(H):
+            s = K[:, h * d:(h + 1) * d] @ q[h] * sm_scale
+            m = s.max()
+            e = np.exp(s - m)
+            out[h] = (e / e.sum()) @ V[:, h * d:(h + 1) * d]
+            lse[h] = m + math.log(e.sum())
+    return (out, lse) if return_lse else out
+
+
+def decode_attn_segments(q, segments, sm_scale=None, return_lse: bool = False):
+    """Alg. 1's attention over a cache made of several segments, by its
+    definition: every compressed segment is (partially) decompressed, all keys
+    and all values are concatenated along the token axis (Ktilde = (+)_f
+    Kbar[m_f, :R_f] D_k[:R_f] (+) K), and one softmax runs over the lot.
+
+    segments: sequence of dicts, either
+      {"Ck", "Cv", "Bk", "Bv"[, "rank_k", "rank_v"]}   compressed, own bases
+      {"K", "V"}                                        uncompressed [T_u, H*d]
+    """
+    q = np.asarray(q, np.float64)
+    H, d = q.shape
+    Ks, Vs = [], []
+    for seg in segments:
+        if "K" in seg:
+            Ks.append(np.asarray(seg["K"], np.float64).reshape(-1, H * d))
+            Vs.append(np.asarray(seg["V"], np.float64).reshape(-1, H * d))
+        else:
+            Ck = np.asarray(seg["Ck"], np.float64)
+            Cv = np.asarray(seg["Cv"], np.float64)
+            T, r = Ck.shape
+            Ks.append(_partial_decompress(Ck, np.asarray(seg["Bk"], np.float64), _ranks(seg.get("rank_k"), T, r)))
+            Vs.append(_partial_decompress(Cv, np.asarray(seg["Bv"], np.float64), _ranks(seg.get("rank_v"), T, r)))
+    return raw_attn(q, np.concatenate(Ks, axis=0), np.concatenate(Vs, axis=0), sm_scale, return_lse)
+
+
+def merge_segments(outs, lses):
+    """Outputs and log-sum-exps of attention over disjoint token sets ->
+    those of attention over their union: softmax weights of the union are the
+    per-set weights scaled by exp(lse_i - lse), lse = log sum_i exp(lse_i).
+    outs [N, H, d], lses [N, H]; a set may be empty (lse = -inf)."""
+    outs = np.asarray(outs, np.float64)
+    lses = np.asarray(lses, np.float64)
+    m = lses.max(axis=0)                                  # [H]
+    w = np.exp(lses - m[None, :])                         # [N, H]
+    z = w.sum(axis=0)
+    out = (w[:, :, None] * outs).sum(axis=0) / z[:, None]
+    return out, m + np.log(z)
+
+
+# --------------------------------------------------------------------------
 # attention-aware rank groups (Sec. 3.2; Alg. 1 "determine the tokens m_f")
 # --------------------------------------------------------------------------
 

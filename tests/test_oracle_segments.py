@@ -1,0 +1,119 @@
+"""Pins for the multi-segment oracle (Alg. 1's cache: compressed segments next to an
+uncompressed one under a single softmax): library softmax, brute force, invariances."""
+import math
+
+import numpy as np
+import pytest
+import scipy.special
+
+import oracle
+
+
+def rand_case(seed, H=3, d=8, T=13, r=6, Tu=7):
+    rng = np.random.default_rng(seed)
+    HD = H * d
+    return dict(q=rng.standard_normal((H, d)),
+                Ck=rng.standard_normal((T, r)), Cv=rng.standard_normal((T, r)),
+                Bk=rng.standard_normal((r, HD)), Bv=rng.standard_normal((r, HD)),
+                K=rng.standard_normal((Tu, HD)), V=rng.standard_normal((Tu, HD)))
+
+
+def test_raw_attn_is_library_softmax_attention():
+    c = rand_case(1, H=4, d=16, Tu=29)
+    H, d = c["q"].shape
+    out, lse = oracle.raw_attn(c["q"], c["K"], c["V"], return_lse=True)
+    for h in range(H):
+        s = c["K"][:, h * d:(h + 1) * d] @ c["q"][h] / math.sqrt(d)
+        assert np.abs(out[h] - scipy.special.softmax(s) @ c["V"][:, h * d:(h + 1) * d]).max() < 1e-13
+        assert abs(lse[h] - scipy.special.logsumexp(s)) < 1e-12
+
+
+def test_raw_attn_empty_cache():
+    c = rand_case(2)
+    out, lse = oracle.raw_attn(c["q"], c["K"][:0], c["V"][:0], return_lse=True)
+    assert (out == 0).all() and np.isneginf(lse).all()
+
+
+def test_segments_brute_force_loops():
+    """Scalar loops written from Alg. 1: decompress the compressed tokens at their ranks, append
+    the uncompressed ones, one softmax over all of them."""
+    c = rand_case(3, H=2, d=4, T=5, r=3, Tu=4)
+    H, d = c["q"].shape
+    rk, rv = [3, 1, 0, 2, 3], [2, 3, 1, 0, 3]
+    scale = 1.0 / math.sqrt(d)
+    ref = np.zeros((H, d))
+    for h in range(H):
+        keys, vals = [], []
+        for t in range(5):
+            keys.append([sum(c["Ck"][t, j] * c["Bk"][j, h * d + i] for j in range(rk[t])) for i in range(d)])
+            vals.append([sum(c["Cv"][t, j] * c["Bv"][j, h * d + i] for j in range(rv[t])) for i in range(d)])
+        for t in range(4):
+            keys.append([c["K"][t, h * d + i] for i in range(d)])
+            vals.append([c["V"][t, h * d + i] for i in range(d)])
+        sc = [scale * sum(c["q"][h, i] * k[i] for i in range(d)) for k in keys]
+        mx = max(sc)
+        ex = [math.exp(x - mx) for x in sc]
+        for i in range(d):
+            ref[h, i] = sum(e * v[i] for e, v in zip(ex, vals)) / sum(ex)
+    got = oracle.decode_attn_segments(c["q"], [
+        dict(Ck=c["Ck"], Cv=c["Cv"], Bk=c["Bk"], Bv=c["Bv"], rank_k=np.array(rk), rank_v=np.array(rv)),
+        dict(K=c["K"], V=c["V"])])
+    assert np.abs(got - ref).max() < 1e-13
+
+
+def test_one_compressed_segment_is_decode_attn():
+    c = rand_case(4)
+    a = oracle.decode_attn_segments(c["q"], [dict(Ck=c["Ck"], Cv=c["Cv"], Bk=c["Bk"], Bv=c["Bv"])])
+    assert np.abs(a - oracle.decode_attn(c["q"], c["Ck"], c["Cv"], c["Bk"], c["Bv"])).max() < 1e-14
+
+
+def test_splitting_a_segment_changes_nothing():
+    """Token sets are just concatenated: cutting a compressed segment in two, or moving its
+    reconstructed rows into the uncompressed segment, gives the same attention."""
+    c = rand_case(5, T=17)
+    whole = oracle.decode_attn(c["q"], c["Ck"], c["Cv"], c["Bk"], c["Bv"])
+    cut = oracle.decode_attn_segments(c["q"], [
+        dict(Ck=c["Ck"][:6], Cv=c["Cv"][:6], Bk=c["Bk"], Bv=c["Bv"]),
+        dict(Ck=c["Ck"][6:], Cv=c["Cv"][6:], Bk=c["Bk"], Bv=c["Bv"])])
+    assert np.abs(cut - whole).max() < 1e-13
+    moved = oracle.decode_attn_segments(c["q"], [
+        dict(Ck=c["Ck"][:6], Cv=c["Cv"][:6], Bk=c["Bk"], Bv=c["Bv"]),
+        dict(K=c["Ck"][6:] @ c["Bk"], V=c["Cv"][6:] @ c["Bv"])])
+    assert np.abs(moved - whole).max() < 1e-13
+
+
+def test_segment_order_does_not_matter():
+    c = rand_case(6)
+    seg_c = dict(Ck=c["Ck"], Cv=c["Cv"], Bk=c["Bk"], Bv=c["Bv"])
+    seg_u = dict(K=c["K"], V=c["V"])
+    a = oracle.decode_attn_segments(c["q"], [seg_c, seg_u])
+    b = oracle.decode_attn_segments(c["q"], [seg_u, seg_c])
+    assert np.abs(a - b).max() < 1e-13
+
+
+@pytest.mark.parametrize("seed", [7, 8])
+def test_merge_of_parts_equals_attention_over_the_union(seed):
+    """merge_segments is the log-sum-exp identity: checked against the concatenation."""
+    c = rand_case(seed, H=4, d=8, T=19, Tu=9)
+    o1, l1 = oracle.decode_attn(c["q"], c["Ck"], c["Cv"], c["Bk"], c["Bv"], return_lse=True)
+    o2, l2 = oracle.raw_attn(c["q"], c["K"], c["V"], return_lse=True)
+    ref, ref_lse = oracle.decode_attn_segments(c["q"], [dict(Ck=c["Ck"], Cv=c["Cv"], Bk=c["Bk"], Bv=c["Bv"]),
+                                                        dict(K=c["K"], V=c["V"])], return_lse=True)
+    out, lse = oracle.merge_segments([o1, o2], [l1, l2])
+    assert np.abs(out - ref).max() < 1e-13 and np.abs(lse - ref_lse).max() < 1e-12
+    # an empty part drops out
+    o0, l0 = oracle.raw_attn(c["q"], c["K"][:0], c["V"][:0], return_lse=True)
+    out3, lse3 = oracle.merge_segments([o1, o0, o2], [l1, l0, l2])
+    assert np.abs(out3 - ref).max() < 1e-13 and np.abs(lse3 - ref_lse).max() < 1e-12
+
+
+def test_dominant_uncompressed_token_takes_over():
+    """A key aligned with the query and scaled up wins the softmax: the output tends to that
+    token's value row whatever the compressed segment holds."""
+    c = rand_case(9, H=2, d=8)
+    H, d = c["q"].shape
+    K = c["K"].copy()
+    K[3] = 60.0 * c["q"].reshape(-1)
+    out = oracle.decode_attn_segments(c["q"], [dict(Ck=c["Ck"], Cv=c["Cv"], Bk=c["Bk"], Bv=c["Bv"]),
+                                               dict(K=K, V=c["V"])])
+    assert np.abs(out - c["V"][3].reshape(H, d)).max() < 1e-9
