@@ -215,6 +215,45 @@ ap_status ap_update_importance(const float* scores, const float* lse, float* mas
                                float alpha, void* stream);
 
 /* ------------------------------------------------------------------------
+ * The uncompressed segment of the cache (Alg. 1: C_u = {K, V}; in the paper's
+ * experiments the text tokens, and every generated token until the next
+ * compression) and the merge of segments under one softmax.
+ *
+ * ap_raw_attn -- softmax attention of one decode query per sequence over raw
+ * keys and values:  out[b,h,:] = softmax_t(sm_scale q[b,h].K[b,t,head h]) V[b,t,head h]
+ *   q    [B, H, d]          dt (fp16 or bf16)
+ *   K, V [B, T_u_cap, H*d]  dt; rows 0..T_u-1 are attended
+ *   out  [B, H, d] fp32; lse [B, H] fp32 natural log-sum-exp of the scaled
+ *        logits, or NULL.  T_u = 0 gives out = 0 and lse = -inf.
+ *   d in {32, 64, 128, 256}; workspace of ap_raw_workspace_bytes(B, H, d, T_u).
+ *
+ * ap_merge_segments -- attention over two disjoint token sets to attention over
+ * their union (Alg. 1 concatenates the decompressed and the uncompressed tokens
+ * before the softmax; the softmax of a concatenation is the mean of the
+ * per-segment results weighted by exp(lse_i)):
+ *     w_i = exp(lse_i - max(lse_a, lse_b)),  out = (w_a out_a + w_b out_b) / (w_a + w_b),
+ *     lse = max + log(w_a + w_b)
+ *   out_a, out_b [B, H, d] fp32 (e.g. from ap_decode_attn with dt_out = AP_F32 and
+ *   from ap_raw_attn), lse_a, lse_b [B, H] fp32; out [B, H, d] in dt_out (may be
+ *   out_a or out_b itself when dt_out is AP_F32), lse [B, H] or NULL (a buffer of
+ *   its own: not lse_a or lse_b).  A segment with lse = -inf drops out.  More than
+ *   two segments: call repeatedly.
+ *
+ * ap_raw_append -- k_new, v_new [B, HD] (either may be NULL) copied to row `row`
+ * of K, V [B, T_u_cap, HD].
+ * ---------------------------------------------------------------------- */
+size_t ap_raw_workspace_bytes(int B, int H, int d, int T_u);
+ap_status ap_raw_attn(const void* q, const void* K, const void* V, float* out, float* lse,
+                      int B, int H, int d, int T_u, int T_u_cap, float sm_scale,
+                      ap_dtype dt, void* workspace, size_t ws_bytes, void* stream);
+ap_status ap_merge_segments(const float* out_a, const float* lse_a,
+                            const float* out_b, const float* lse_b,
+                            void* out, float* lse, int B, int H, int d,
+                            ap_dtype dt_out, void* stream);
+ap_status ap_raw_append(const void* k_new, const void* v_new, void* K, void* V,
+                        int B, int HD, int row, int T_u_cap, ap_dtype dt, void* stream);
+
+/* ------------------------------------------------------------------------
  * Timing of the dominant kernel (measurement aid, not part of the method).
  * While enabled, every ap_decode_attn call on AP_F16 / AP_BF16 brackets its
  * coefficient-streaming kernel with a pair of HIP events on the call's stream.

@@ -47,6 +47,14 @@ _lib.ap_decode_step.argtypes = ([_vp] * 7 + [_i64] + [_vp] * 4 + [_i] + [_vp, _v
                                 [_f, _i, _i, _vp, _sz, _vp])
 _lib.ap_update_importance.restype = _i
 _lib.ap_update_importance.argtypes = [_vp, _vp, _vp, _i, _i, _i, _i, _i64, _f, _vp]
+_lib.ap_raw_workspace_bytes.restype = _sz
+_lib.ap_raw_workspace_bytes.argtypes = [_i] * 4
+_lib.ap_raw_attn.restype = _i
+_lib.ap_raw_attn.argtypes = [_vp] * 5 + [_i] * 5 + [_f, _i, _vp, _sz, _vp]
+_lib.ap_merge_segments.restype = _i
+_lib.ap_merge_segments.argtypes = [_vp] * 6 + [_i] * 4 + [_vp]
+_lib.ap_raw_append.restype = _i
+_lib.ap_raw_append.argtypes = [_vp] * 4 + [_i] * 5 + [_vp]
 _lib.ap_decode_workspace_bytes.restype = _sz
 _lib.ap_decode_workspace_bytes.argtypes = [_i] * 6
 _lib.ap_status_string.restype = _c.c_char_p
@@ -61,7 +69,8 @@ _lib.ap_prof_read.restype = _i
 _lib.ap_prof_read.argtypes = [_c.POINTER(_c.c_float), _c.POINTER(_c.c_int)]
 
 EXPORTS = ("ap_compact", "ap_quantize_i8", "ap_select_ranks", "ap_select_workspace_bytes",
-           "ap_decode_attn", "ap_decode_step", "ap_update_importance", "ap_decode_workspace_bytes", "ap_status_string", "ap_last_error",
+           "ap_decode_attn", "ap_decode_step", "ap_update_importance", "ap_decode_workspace_bytes",
+           "ap_raw_workspace_bytes", "ap_raw_attn", "ap_merge_segments", "ap_raw_append", "ap_status_string", "ap_last_error",
            "ap_version", "ap_prof_enable", "ap_prof_read")
 
 _DT = {torch.float32: AP_F32, torch.float16: AP_F16, torch.bfloat16: AP_BF16, torch.int8: AP_I8}
@@ -179,6 +188,33 @@ def ap_update_importance(scores, lse, mass, *, T: int, alpha: float, stream=None
     B, H, T_cap = scores.shape
     _check(_lib.ap_update_importance(_p(scores), _p(lse), _p(mass), B, H, T, T_cap, mass.stride(0),
                                      float(alpha), _stream(stream)))
+
+
+def ap_raw_workspace_bytes(B: int, H: int, d: int, T_u: int) -> int:
+    return _lib.ap_raw_workspace_bytes(B, H, d, T_u)
+
+
+def ap_raw_attn(q, K, V, out, workspace, *, T_u: int, sm_scale: float, lse=None, stream=None) -> None:
+    """q [B, H, d]; K, V [B, T_u_cap, H*d] (same 16-bit dtype); out [B, H, d] fp32."""
+    B, H, d = q.shape
+    _check(_lib.ap_raw_attn(_p(q), _p(K), _p(V), _p(out), _p(lse), B, H, d, T_u, K.shape[1],
+                            float(sm_scale), _DT[q.dtype], _p(workspace),
+                            workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
+def ap_merge_segments(out_a, lse_a, out_b, lse_b, out, *, lse=None, stream=None) -> None:
+    """out_a, out_b [B, H, d] fp32 with lse_a, lse_b [B, H] -> out (any supported dtype)."""
+    B, H, d = out_a.shape
+    _check(_lib.ap_merge_segments(_p(out_a), _p(lse_a), _p(out_b), _p(lse_b), _p(out), _p(lse), B, H, d,
+                                  _DT[out.dtype], _stream(stream)))
+
+
+def ap_raw_append(k_new, v_new, K, V, *, row: int, stream=None) -> None:
+    """k_new, v_new [B, HD] -> row `row` of K, V [B, T_u_cap, HD]."""
+    X = K if K is not None else V
+    B, T_cap, HD = X.shape
+    _check(_lib.ap_raw_append(_p(k_new), _p(v_new), _p(K), _p(V), B, HD, row, T_cap, _DT[X.dtype],
+                              _stream(stream)))
 
 
 def ap_prof_enable(on: bool) -> None:

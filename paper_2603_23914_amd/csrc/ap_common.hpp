@@ -142,6 +142,16 @@ ap_status launch_update_importance(const float* scores, const float* lse, float*
                                    int T, int T_cap, int64_t mass_stride, float alpha,
                                    hipStream_t stream);
 
+size_t raw_attn_workspace(int B, int H, int d, int T);
+ap_status launch_raw_attn(const void* q, const void* K, const void* V, float* out, float* lse, int B,
+                          int H, int d, int T, int T_cap, float sm_scale, ap_dtype dt, void* workspace,
+                          hipStream_t stream);
+ap_status launch_merge_segments(const float* out_a, const float* lse_a, const float* out_b,
+                                const float* lse_b, void* out, float* lse, int B, int H, int d,
+                                ap_dtype dt_out, hipStream_t stream);
+ap_status launch_raw_append(const void* k_new, const void* v_new, void* K, void* V, int B, int HD, int row,
+                            int T_cap, hipStream_t stream);
+
 size_t select_workspace(int B, int T, int F);
 ap_status launch_select_ranks(const float* mass, int B, int T, int F, const int32_t* group_rank,
                               const int32_t* bounds_num, int32_t den, int32_t* rank_out,

@@ -295,6 +295,60 @@ ap_status ap_decode_step(const void* q, const void* k_new, const void* v_new, vo
                       d, T, T_cap, r, sm_scale, dt, dt, dt_out, workspace, ws_bytes, stream);
 }
 
+static bool raw_shape_ok(int B, int H, int d) {
+  return B > 0 && B <= 65535 && H > 0 && H <= 65535 && (d == 32 || d == 64 || d == 128 || d == 256);
+}
+
+size_t ap_raw_workspace_bytes(int B, int H, int d, int T_u) {
+  if (!raw_shape_ok(B, H, d) || T_u < 0) return 0;
+  return raw_attn_workspace(B, H, d, T_u);
+}
+
+ap_status ap_raw_attn(const void* q, const void* K, const void* V, float* out, float* lse, int B, int H,
+                      int d, int T_u, int T_u_cap, float sm_scale, ap_dtype dt, void* workspace,
+                      size_t ws_bytes, void* stream) {
+  clear_error();
+  AP_REQUIRE(q && out && workspace, AP_ERR_INVALID_ARG, "ap_raw_attn: NULL pointer");
+  AP_REQUIRE(raw_shape_ok(B, H, d), AP_ERR_UNSUPPORTED,
+             "ap_raw_attn: need 0 < B, H <= 65535 and d in {32, 64, 128, 256}");
+  AP_REQUIRE(dt == AP_F16 || dt == AP_BF16, AP_ERR_UNSUPPORTED, "ap_raw_attn: fp16 or bf16 storage only");
+  AP_REQUIRE(T_u >= 0 && T_u <= T_u_cap, AP_ERR_INVALID_ARG, "ap_raw_attn: need 0 <= T_u <= T_u_cap");
+  AP_REQUIRE(T_u == 0 || (K && V), AP_ERR_INVALID_ARG, "ap_raw_attn: NULL cache with T_u > 0");
+  AP_REQUIRE(aligned(q, 16) && aligned(K, 16) && aligned(V, 16), AP_ERR_INVALID_ARG,
+             "ap_raw_attn: q, K, V must be 16-byte aligned");
+  AP_REQUIRE(ws_bytes >= raw_attn_workspace(B, H, d, T_u), AP_ERR_WORKSPACE,
+             "ap_raw_attn: workspace too small (%zu < %zu bytes)", ws_bytes,
+             raw_attn_workspace(B, H, d, T_u));
+  return launch_raw_attn(q, K, V, out, lse, B, H, d, T_u, T_u_cap, sm_scale, dt, workspace,
+                         (hipStream_t)stream);
+}
+
+ap_status ap_merge_segments(const float* out_a, const float* lse_a, const float* out_b,
+                            const float* lse_b, void* out, float* lse, int B, int H, int d,
+                            ap_dtype dt_out, void* stream) {
+  clear_error();
+  AP_REQUIRE(out_a && lse_a && out_b && lse_b && out, AP_ERR_INVALID_ARG, "ap_merge_segments: NULL pointer");
+  AP_REQUIRE(B > 0 && B <= 65535 && H > 0 && d > 0, AP_ERR_INVALID_ARG,
+             "ap_merge_segments: need 0 < B <= 65535, H > 0, d > 0");
+  AP_REQUIRE(dt_out == AP_F32 || dt_out == AP_F16 || dt_out == AP_BF16, AP_ERR_UNSUPPORTED,
+             "ap_merge_segments: output type must be fp32, fp16 or bf16");
+  return launch_merge_segments(out_a, lse_a, out_b, lse_b, out, lse, B, H, d, dt_out, (hipStream_t)stream);
+}
+
+ap_status ap_raw_append(const void* k_new, const void* v_new, void* K, void* V, int B, int HD, int row,
+                        int T_u_cap, ap_dtype dt, void* stream) {
+  clear_error();
+  AP_REQUIRE((k_new && K) || (v_new && V), AP_ERR_INVALID_ARG, "ap_raw_append: nothing to append");
+  AP_REQUIRE((!k_new || K) && (!v_new || V), AP_ERR_INVALID_ARG, "ap_raw_append: row without its cache");
+  AP_REQUIRE(dt == AP_F16 || dt == AP_BF16, AP_ERR_UNSUPPORTED, "ap_raw_append: fp16 or bf16 storage only");
+  AP_REQUIRE(B > 0 && B <= 65535 && HD > 0 && HD % 8 == 0, AP_ERR_INVALID_ARG,
+             "ap_raw_append: need 0 < B <= 65535 and HD a positive multiple of 8");
+  AP_REQUIRE(row >= 0 && row < T_u_cap, AP_ERR_INVALID_ARG, "ap_raw_append: need 0 <= row < T_u_cap");
+  AP_REQUIRE(aligned(k_new, 16) && aligned(v_new, 16) && aligned(K, 16) && aligned(V, 16),
+             AP_ERR_INVALID_ARG, "ap_raw_append: pointers must be 16-byte aligned");
+  return launch_raw_append(k_new, v_new, K, V, B, HD, row, T_u_cap, (hipStream_t)stream);
+}
+
 ap_status ap_update_importance(const float* scores, const float* lse, float* mass, int B, int H,
                                int T, int T_cap, int64_t mass_stride, float alpha, void* stream) {
   clear_error();
