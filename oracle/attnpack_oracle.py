@@ -11,6 +11,11 @@ R^{T x R}  ("C_k", "C_v" here) and decompression matrices  D_k, D_v in
 R^{R x HD}  ("B_k", "B_v", the bases).  Head h owns hidden columns
 [h*d, (h+1)*d).
 
+Grouped-query attention (Sec. 4.5: models whose H query heads share H_kv < H
+key/value heads): the cache and the bases then have H_kv*d hidden columns and
+query head h reads the slice of key/value head h // (H / H_kv).  Functions
+that take `kv_heads` implement this; None means H_kv = H.
+
 Every function works on ONE sequence of ONE layer unless it says "batched".
 All arithmetic is float64 except `quantize_i8`, whose recipe fixes fp32/fp16.
 """
@@ -95,13 +100,22 @@ def _partial_decompress(C: np.ndarray, D: np.ndarray, rank: np.ndarray) -> np.nd
     return X
 
 
+def _kv_slice(h: int, H: int, d: int, kv_heads: Optional[int]) -> slice:
+    """Hidden columns that query head h reads (grouped-query attention: consecutive
+    groups of H / H_kv query heads share one key/value head)."""
+    Hkv = H if kv_heads is None else int(kv_heads)
+    assert Hkv >= 1 and H % Hkv == 0
+    g = h // (H // Hkv)
+    return slice(g * d, (g + 1) * d)
+
+
 def _softmax_rows(s: np.ndarray) -> np.ndarray:
     m = s.max(axis=-1, keepdims=True)
     e = np.exp(s - m)
     return e / e.sum(axis=-1, keepdims=True)
 
 
-def attention_probs(q, Ck, Bk, rank_k=None, sm_scale=None) -> np.ndarray:
+def attention_probs(q, Ck, Bk, rank_k=None, sm_scale=None, kv_heads=None) -> np.ndarray:
     """Attention weights A [H, T] of one decode query (Alg. 1 score step):
     softmax over all cached tokens of q_h . Ktilde_h[t] / sqrt(d)."""
     q = np.asarray(q, np.float64)
@@ -114,12 +128,12 @@ def attention_probs(q, Ck, Bk, rank_k=None, sm_scale=None) -> np.ndarray:
     Kt = _partial_decompress(Ck, Bk, _ranks(rank_k, T, r))
     s = np.empty((H, T))
     for h in range(H):
-        s[h] = Kt[:, h * d:(h + 1) * d] @ q[h] * sm_scale
+        s[h] = Kt[:, _kv_slice(h, H, d, kv_heads)] @ q[h] * sm_scale
     return _softmax_rows(s)
 
 
 def decode_attn(q, Ck, Cv, Bk, Bv, rank_k=None, rank_v=None, sm_scale=None,
-                return_lse: bool = False):
+                return_lse: bool = False, kv_heads=None):
     """DEFINITION FORM: reconstruct, then textbook softmax attention.
 
     q [H, d]; Ck, Cv [T, r]; Bk, Bv [r, H*d]; rank_k, rank_v [T] ints or None
@@ -134,7 +148,8 @@ def decode_attn(q, Ck, Cv, Bk, Bv, rank_k=None, rank_v=None, sm_scale=None,
     Bv = np.asarray(Bv, np.float64)
     H, d = q.shape
     T, r = Ck.shape
-    assert Cv.shape == (T, r) and Bk.shape == (r, H * d) and Bv.shape == (r, H * d)
+    HDkv = (H if kv_heads is None else int(kv_heads)) * d
+    assert Cv.shape == (T, r) and Bk.shape == (r, HDkv) and Bv.shape == (r, HDkv)
     if sm_scale is None:
         sm_scale = 1.0 / math.sqrt(d)
     Kt = _partial_decompress(Ck, Bk, _ranks(rank_k, T, r))
@@ -142,18 +157,19 @@ def decode_attn(q, Ck, Cv, Bk, Bv, rank_k=None, rank_v=None, sm_scale=None,
     out = np.empty((H, d))
     lse = np.empty(H)
     for h in range(H):
-        s = Kt[:, h * d:(h + 1) * d] @ q[h] * sm_scale          # [T]
+        sl = _kv_slice(h, H, d, kv_heads)
+        s = Kt[:, sl] @ q[h] * sm_scale                          # [T]
         m = s.max()
         e = np.exp(s - m)
         z = e.sum()
         p = e / z
-        out[h] = p @ Vt[:, h * d:(h + 1) * d]
+        out[h] = p @ Vt[:, sl]
         lse[h] = m + math.log(z)
     return (out, lse) if return_lse else out
 
 
 def decode_attn_absorbed(q, Ck, Cv, Bk, Bv, rank_k=None, rank_v=None, sm_scale=None,
-                         return_lse: bool = False):
+                         return_lse: bool = False, kv_heads=None):
     """ABSORBED FORM: the same result by associativity, never forming K, V.
 
     q'_h = D_k[:, head h] q_h;  score[h,t] = Kbar[t,:rk_t] . q'_h[:rk_t];
@@ -178,19 +194,20 @@ def decode_attn_absorbed(q, Ck, Cv, Bk, Bv, rank_k=None, rank_v=None, sm_scale=N
     out = np.empty((H, d))
     lse = np.empty(H)
     for h in range(H):
-        qp = Bk[:, h * d:(h + 1) * d] @ q[h]     # [r]
+        sl = _kv_slice(h, H, d, kv_heads)
+        qp = Bk[:, sl] @ q[h]                    # [r]
         s = Ckm @ qp * sm_scale
         m = s.max()
         e = np.exp(s - m)
         z = e.sum()
         u = (e / z) @ Cvm                        # [r]
-        out[h] = u @ Bv[:, h * d:(h + 1) * d]
+        out[h] = u @ Bv[:, sl]
         lse[h] = m + math.log(z)
     return (out, lse) if return_lse else out
 
 
 def decode_attn_batched(q, Ck, Cv, Bk, Bv, T: int, rank_k=None, rank_v=None,
-                        sm_scale=None, absorbed: bool = False) -> np.ndarray:
+                        sm_scale=None, absorbed: bool = False, kv_heads=None) -> np.ndarray:
     """Batched wrapper.  q [B,H,d]; Ck, Cv [B,T_cap,r] (rows >= T ignored);
     Bk, Bv [B,r,HD] or [r,HD] (shared); ranks [B,T] or None.  -> [B,H,d]."""
     fn = decode_attn_absorbed if absorbed else decode_attn
@@ -201,7 +218,7 @@ def decode_attn_batched(q, Ck, Cv, Bk, Bv, T: int, rank_k=None, rank_v=None,
         bv = Bv[b] if Bv.ndim == 3 else Bv
         rk = None if rank_k is None else rank_k[b][:T]
         rv = None if rank_v is None else rank_v[b][:T]
-        out[b] = fn(q[b], Ck[b, :T], Cv[b, :T], bk, bv, rk, rv, sm_scale)
+        out[b] = fn(q[b], Ck[b, :T], Cv[b, :T], bk, bv, rk, rv, sm_scale, kv_heads=kv_heads)
     return out
 
 
@@ -210,7 +227,7 @@ def decode_attn_batched(q, Ck, Cv, Bk, Bv, T: int, rank_k=None, rank_v=None,
 # uncompressed one (text tokens, and new tokens until the next compression)
 # --------------------------------------------------------------------------
 
-def raw_attn(q, K, V, sm_scale=None, return_lse: bool = False):
+def raw_attn(q, K, V, sm_scale=None, return_lse: bool = False, kv_heads=None):
     """Textbook softmax attention of one decode query over an uncompressed
     cache K, V [T, H*d] (the C_u of Alg. 1).  T = 0 gives out = 0, lse = -inf."""
     q = np.asarray(q, np.float64)
@@ -223,15 +240,16 @@ def raw_attn(q, K, V, sm_scale=None, return_lse: bool = False):
     lse = np.full(H, -np.inf)
     if K.shape[0] > 0:
         for h in range(H):
-            s = K[:, h * d:(h + 1) * d] @ q[h] * sm_scale
+            sl = _kv_slice(h, H, d, kv_heads)
+            s = K[:, sl] @ q[h] * sm_scale
             m = s.max()
             e = np.exp(s - m)
-            out[h] = (e / e.sum()) @ V[:, h * d:(h + 1) * d]
+            out[h] = (e / e.sum()) @ V[:, sl]
             lse[h] = m + math.log(e.sum())
     return (out, lse) if return_lse else out
 
 
-def decode_attn_segments(q, segments, sm_scale=None, return_lse: bool = False):
+def decode_attn_segments(q, segments, sm_scale=None, return_lse: bool = False, kv_heads=None):
     """Alg. 1's attention over a cache made of several segments, by its
     definition: every compressed segment is (partially) decompressed, all keys
     and all values are concatenated along the token axis (Ktilde = (+)_f
@@ -243,18 +261,20 @@ def decode_attn_segments(q, segments, sm_scale=None, return_lse: bool = False):
     """
     q = np.asarray(q, np.float64)
     H, d = q.shape
+    HDkv = (H if kv_heads is None else int(kv_heads)) * d
     Ks, Vs = [], []
     for seg in segments:
         if "K" in seg:
-            Ks.append(np.asarray(seg["K"], np.float64).reshape(-1, H * d))
-            Vs.append(np.asarray(seg["V"], np.float64).reshape(-1, H * d))
+            Ks.append(np.asarray(seg["K"], np.float64).reshape(-1, HDkv))
+            Vs.append(np.asarray(seg["V"], np.float64).reshape(-1, HDkv))
         else:
             Ck = np.asarray(seg["Ck"], np.float64)
             Cv = np.asarray(seg["Cv"], np.float64)
             T, r = Ck.shape
             Ks.append(_partial_decompress(Ck, np.asarray(seg["Bk"], np.float64), _ranks(seg.get("rank_k"), T, r)))
             Vs.append(_partial_decompress(Cv, np.asarray(seg["Bv"], np.float64), _ranks(seg.get("rank_v"), T, r)))
-    return raw_attn(q, np.concatenate(Ks, axis=0), np.concatenate(Vs, axis=0), sm_scale, return_lse)
+    return raw_attn(q, np.concatenate(Ks, axis=0), np.concatenate(Vs, axis=0), sm_scale, return_lse,
+                    kv_heads=kv_heads)
 
 
 def merge_segments(outs, lses):

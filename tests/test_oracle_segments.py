@@ -117,3 +117,64 @@ def test_dominant_uncompressed_token_takes_over():
     out = oracle.decode_attn_segments(c["q"], [dict(Ck=c["Ck"], Cv=c["Cv"], Bk=c["Bk"], Bv=c["Bv"]),
                                                dict(K=K, V=c["V"])])
     assert np.abs(out - c["V"][3].reshape(H, d)).max() < 1e-9
+
+
+# ---------------------------------------------------------------- grouped-query attention
+
+def gqa_case(seed, H=6, Hkv=2, d=8, T=15, r=5, Tu=6):
+    rng = np.random.default_rng(seed)
+    HDkv = Hkv * d
+    return dict(q=rng.standard_normal((H, d)),
+                Ck=rng.standard_normal((T, r)), Cv=rng.standard_normal((T, r)),
+                Bk=rng.standard_normal((r, HDkv)), Bv=rng.standard_normal((r, HDkv)),
+                K=rng.standard_normal((Tu, HDkv)), V=rng.standard_normal((Tu, HDkv)))
+
+
+def repeat_kv(M, H, Hkv, d):
+    """[.., Hkv*d] -> [.., H*d]: every key/value head's slice copied to the query heads that
+    share it (what a model without grouped queries would store)."""
+    g = H // Hkv
+    parts = [M[..., (h // g) * d:(h // g + 1) * d] for h in range(H)]
+    return np.concatenate(parts, axis=-1)
+
+
+@pytest.mark.parametrize("H,Hkv", [(6, 2), (8, 1), (4, 4), (12, 3)])
+def test_grouped_queries_equal_multi_head_on_repeated_kv_heads(H, Hkv):
+    """Grouped-query attention is multi-head attention whose key/value heads are shared: with
+    the shared slices written out once per query head the plain functions must agree."""
+    d = 8
+    c = gqa_case(11, H=H, Hkv=Hkv, d=d)
+    rk = np.array([5, 3, 1, 0, 2, 5, 4, 4, 3, 2, 1, 5, 5, 0, 2])
+    Bk_r, Bv_r = repeat_kv(c["Bk"], H, Hkv, d), repeat_kv(c["Bv"], H, Hkv, d)
+    for fn in (oracle.decode_attn, oracle.decode_attn_absorbed):
+        a, la = fn(c["q"], c["Ck"], c["Cv"], c["Bk"], c["Bv"], rk, rk, return_lse=True, kv_heads=Hkv)
+        b, lb = oracle.decode_attn(c["q"], c["Ck"], c["Cv"], Bk_r, Bv_r, rk, rk, return_lse=True)
+        assert np.abs(a - b).max() < 1e-13 and np.abs(la - lb).max() < 1e-12
+    pa = oracle.attention_probs(c["q"], c["Ck"], c["Bk"], rk, kv_heads=Hkv)
+    pb = oracle.attention_probs(c["q"], c["Ck"], Bk_r, rk)
+    assert np.abs(pa - pb).max() < 1e-14
+    ra = oracle.raw_attn(c["q"], c["K"], c["V"], kv_heads=Hkv)
+    rb = oracle.raw_attn(c["q"], repeat_kv(c["K"], H, Hkv, d), repeat_kv(c["V"], H, Hkv, d))
+    assert np.abs(ra - rb).max() < 1e-13
+    sa = oracle.decode_attn_segments(c["q"], [dict(Ck=c["Ck"], Cv=c["Cv"], Bk=c["Bk"], Bv=c["Bv"]),
+                                              dict(K=c["K"], V=c["V"])], kv_heads=Hkv)
+    sb = oracle.decode_attn_segments(c["q"], [dict(Ck=c["Ck"], Cv=c["Cv"], Bk=Bk_r, Bv=Bv_r),
+                                              dict(K=repeat_kv(c["K"], H, Hkv, d), V=repeat_kv(c["V"], H, Hkv, d))])
+    assert np.abs(sa - sb).max() < 1e-13
+
+
+def test_grouped_queries_head_mapping_is_by_consecutive_groups():
+    """Query heads 0..g-1 read key/value head 0, the next g read head 1, ...: make one
+    key/value head's keys huge for one token and see which query heads follow it."""
+    H, Hkv, d = 6, 3, 4
+    c = gqa_case(12, H=H, Hkv=Hkv, d=d, T=1, r=2, Tu=5)
+    q = np.ones((H, d))
+    K = np.zeros((5, Hkv * d))
+    K[2, 1 * d:2 * d] = 50.0                      # token 2 dominates for key/value head 1 only
+    out = oracle.raw_attn(q, K, c["V"], kv_heads=Hkv)
+    for h in range(H):
+        kv = h // 2
+        if kv == 1:
+            assert np.abs(out[h] - c["V"][2, d:2 * d]).max() < 1e-9
+        else:
+            assert np.abs(out[h] - c["V"][:, kv * d:(kv + 1) * d].mean(axis=0)).max() < 1e-12
