@@ -7,6 +7,10 @@
  * plus decompression matrices ("bases")
  *     B_k, B_v  [r, HD]     (the paper's D_k, D_v),
  * with K ~= C_k B_k, V ~= C_v B_v.  Head h owns hidden columns [h*d, (h+1)*d).
+ * Grouped-query models (the paper's Sec. 4.5: fewer key/value heads than query
+ * heads): the cache has H_kv heads, HD = H_kv*d, and query head h reads the
+ * columns of key/value head h / (H / H_kv).  The decode calls take both H (query
+ * heads) and H_kv; H_kv == H is ordinary multi-head attention.
  *
  * Conventions shared by every call
  *   - Every pointer is DEVICE memory owned by the caller unless marked "host".
@@ -133,7 +137,9 @@ size_t ap_select_workspace_bytes(int B, int T, int F);
  *            before attention, as in Alg. 1).
  *   scale_k, scale_v  [B, T_cap, r / AP_QBLOCK] fp16, required iff dt_coef == AP_I8;
  *            a coefficient's value is code * scale.
- *   Bk, Bv   [r, HD] dtype dt, batch b at + b*basis_batch_stride elements (0 = shared)
+ *   Bk, Bv   [r, H_kv*d] dtype dt, batch b at + b*basis_batch_stride elements (0 = shared)
+ *   H_kv     key/value heads; must divide H.  With H_kv < H the fused step of
+ *            ap_decode_step appends with a pass of its own over each basis.
  *   rank_k, rank_v  [B, T] int32 per-token ranks, or NULL = every token at rank r.
  *            One rank per token, shared by all heads.
  *   bucket_off [B, F+1], bucket_idx [B, T], F: the group lists ap_select_ranks
@@ -165,7 +171,7 @@ ap_status ap_decode_attn(const void* q, const void* Ck, const void* Cv,
                          const int32_t* rank_k, const int32_t* rank_v,
                          const int32_t* bucket_off, const int32_t* bucket_idx, int F,
                          void* out, float* lse, float* scores,
-                         int B, int H, int d, int T, int T_cap, int r, float sm_scale,
+                         int B, int H, int H_kv, int d, int T, int T_cap, int r, float sm_scale,
                          ap_dtype dt, ap_dtype dt_coef, ap_dtype dt_out,
                          void* workspace, size_t ws_bytes, void* stream);
 
@@ -195,7 +201,7 @@ ap_status ap_decode_step(const void* q, const void* k_new, const void* v_new, vo
                          const int32_t* rank_k, const int32_t* rank_v,
                          const int32_t* bucket_off, const int32_t* bucket_idx, int F,
                          void* out, float* lse, float* scores,
-                         int B, int H, int d, int T, int T_cap, int r, float sm_scale,
+                         int B, int H, int H_kv, int d, int T, int T_cap, int r, float sm_scale,
                          ap_dtype dt, ap_dtype dt_out,
                          void* workspace, size_t ws_bytes, void* stream);
 
@@ -222,7 +228,8 @@ ap_status ap_update_importance(const float* scores, const float* lse, float* mas
  * ap_raw_attn -- softmax attention of one decode query per sequence over raw
  * keys and values:  out[b,h,:] = softmax_t(sm_scale q[b,h].K[b,t,head h]) V[b,t,head h]
  *   q    [B, H, d]          dt (fp16 or bf16)
- *   K, V [B, T_u_cap, H*d]  dt; rows 0..T_u-1 are attended
+ *   K, V [B, T_u_cap, H_kv*d]  dt; rows 0..T_u-1 are attended; query head h reads
+ *        the columns of key/value head h / (H / H_kv)
  *   out  [B, H, d] fp32; lse [B, H] fp32 natural log-sum-exp of the scaled
  *        logits, or NULL.  T_u = 0 gives out = 0 and lse = -inf.
  *   d in {32, 64, 128, 256}; workspace of ap_raw_workspace_bytes(B, H, d, T_u).
@@ -244,7 +251,7 @@ ap_status ap_update_importance(const float* scores, const float* lse, float* mas
  * ---------------------------------------------------------------------- */
 size_t ap_raw_workspace_bytes(int B, int H, int d, int T_u);
 ap_status ap_raw_attn(const void* q, const void* K, const void* V, float* out, float* lse,
-                      int B, int H, int d, int T_u, int T_u_cap, float sm_scale,
+                      int B, int H, int H_kv, int d, int T_u, int T_u_cap, float sm_scale,
                       ap_dtype dt, void* workspace, size_t ws_bytes, void* stream);
 ap_status ap_merge_segments(const float* out_a, const float* lse_a,
                             const float* out_b, const float* lse_b,

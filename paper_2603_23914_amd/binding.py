@@ -40,17 +40,17 @@ _lib.ap_select_ranks.argtypes = [_vp, _i, _i, _i, _vp, _vp, _c.c_int32, _vp, _vp
 _lib.ap_select_workspace_bytes.restype = _sz
 _lib.ap_select_workspace_bytes.argtypes = [_i, _i, _i]
 _lib.ap_decode_attn.restype = _i
-_lib.ap_decode_attn.argtypes = ([_vp] * 7 + [_i64] + [_vp] * 4 + [_i] + [_vp, _vp, _vp] + [_i] * 6 +
+_lib.ap_decode_attn.argtypes = ([_vp] * 7 + [_i64] + [_vp] * 4 + [_i] + [_vp, _vp, _vp] + [_i] * 7 +
                                 [_f, _i, _i, _i, _vp, _sz, _vp])
 _lib.ap_decode_step.restype = _i
-_lib.ap_decode_step.argtypes = ([_vp] * 7 + [_i64] + [_vp] * 4 + [_i] + [_vp, _vp, _vp] + [_i] * 6 +
+_lib.ap_decode_step.argtypes = ([_vp] * 7 + [_i64] + [_vp] * 4 + [_i] + [_vp, _vp, _vp] + [_i] * 7 +
                                 [_f, _i, _i, _vp, _sz, _vp])
 _lib.ap_update_importance.restype = _i
 _lib.ap_update_importance.argtypes = [_vp, _vp, _vp, _i, _i, _i, _i, _i64, _f, _vp]
 _lib.ap_raw_workspace_bytes.restype = _sz
 _lib.ap_raw_workspace_bytes.argtypes = [_i] * 4
 _lib.ap_raw_attn.restype = _i
-_lib.ap_raw_attn.argtypes = [_vp] * 5 + [_i] * 5 + [_f, _i, _vp, _sz, _vp]
+_lib.ap_raw_attn.argtypes = [_vp] * 5 + [_i] * 6 + [_f, _i, _vp, _sz, _vp]
 _lib.ap_merge_segments.restype = _i
 _lib.ap_merge_segments.argtypes = [_vp] * 6 + [_i] * 4 + [_vp]
 _lib.ap_raw_append.restype = _i
@@ -159,12 +159,14 @@ def ap_decode_attn(q, Ck, Cv, Bk, Bv, out, workspace, *, T: int, sm_scale: float
                    scale_k=None, scale_v=None, rank_k=None, rank_v=None, bucket_off=None,
                    bucket_idx=None, F: int = 0, lse=None, scores=None, stream=None) -> None:
     """q, out [B, H, d] (out in q's dtype or fp32); Ck, Cv [B, T_cap, r];
-    Bk, Bv [r, HD] or [B, r, HD]; scores [B, H, T_cap] fp32 (optional output)."""
+    Bk, Bv [r, H_kv*d] or [B, r, H_kv*d] (H_kv is read off their width);
+    scores [B, H, T_cap] fp32 (optional output)."""
     B, H, d = q.shape
     T_cap, r = Ck.shape[1], Ck.shape[2]
+    H_kv = Bk.shape[-1] // d
     _check(_lib.ap_decode_attn(_p(q), _p(Ck), _p(Cv), _p(scale_k), _p(scale_v), _p(Bk), _p(Bv),
                                _bstride(Bk), _p(rank_k), _p(rank_v), _p(bucket_off),
-                               _p(bucket_idx), F, _p(out), _p(lse), _p(scores), B, H, d, T, T_cap, r,
+                               _p(bucket_idx), F, _p(out), _p(lse), _p(scores), B, H, H_kv, d, T, T_cap, r,
                                float(sm_scale), _DT[q.dtype], _DT[Ck.dtype], _DT[out.dtype],
                                _p(workspace),
                                workspace.numel() * workspace.element_size(), _stream(stream)))
@@ -173,12 +175,13 @@ def ap_decode_attn(q, Ck, Cv, Bk, Bv, out, workspace, *, T: int, sm_scale: float
 def ap_decode_step(q, k_new, v_new, Ck, Cv, Bk, Bv, out, workspace, *, T: int, sm_scale: float,
                    rank_k=None, rank_v=None, bucket_off=None, bucket_idx=None, F: int = 0,
                    lse=None, scores=None, stream=None) -> None:
-    """Append k_new, v_new [B, HD] at row T-1, then attend over T rows (one fused call)."""
+    """Append k_new, v_new [B, H_kv*d] at row T-1, then attend over T rows (one fused call)."""
     B, H, d = q.shape
     T_cap, r = Ck.shape[1], Ck.shape[2]
+    H_kv = Bk.shape[-1] // d
     _check(_lib.ap_decode_step(_p(q), _p(k_new), _p(v_new), _p(Ck), _p(Cv), _p(Bk), _p(Bv),
                                _bstride(Bk), _p(rank_k), _p(rank_v), _p(bucket_off),
-                               _p(bucket_idx), F, _p(out), _p(lse), _p(scores), B, H, d, T, T_cap, r,
+                               _p(bucket_idx), F, _p(out), _p(lse), _p(scores), B, H, H_kv, d, T, T_cap, r,
                                float(sm_scale), _DT[q.dtype], _DT[out.dtype], _p(workspace),
                                workspace.numel() * workspace.element_size(), _stream(stream)))
 
@@ -195,9 +198,9 @@ def ap_raw_workspace_bytes(B: int, H: int, d: int, T_u: int) -> int:
 
 
 def ap_raw_attn(q, K, V, out, workspace, *, T_u: int, sm_scale: float, lse=None, stream=None) -> None:
-    """q [B, H, d]; K, V [B, T_u_cap, H*d] (same 16-bit dtype); out [B, H, d] fp32."""
+    """q [B, H, d]; K, V [B, T_u_cap, H_kv*d] (same 16-bit dtype); out [B, H, d] fp32."""
     B, H, d = q.shape
-    _check(_lib.ap_raw_attn(_p(q), _p(K), _p(V), _p(out), _p(lse), B, H, d, T_u, K.shape[1],
+    _check(_lib.ap_raw_attn(_p(q), _p(K), _p(V), _p(out), _p(lse), B, H, K.shape[2] // d, d, T_u, K.shape[1],
                             float(sm_scale), _DT[q.dtype], _p(workspace),
                             workspace.numel() * workspace.element_size(), _stream(stream)))
 

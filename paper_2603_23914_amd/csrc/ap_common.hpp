@@ -91,6 +91,7 @@ struct DecodeArgs {
   void* out;
   float* lse;
   float* scores;       // [B, H, T_cap] scaled logits (natural-log units) of every attended token, or null
+  int H_kv;            // key/value heads (grouped queries: H / H_kv query heads share one); bases are [r, H_kv*d]
   int B, H, d, T, T_cap, r;
   float sm_scale;
   ap_dtype dt, dt_coef, dt_out;
@@ -136,7 +137,9 @@ ap_status launch_merge_splits(const float* part_ml, const float* part_U, float* 
                               float* pnew, int B, int H, int r, int S, hipStream_t stream);
 ap_status launch_merge_expand(ap_dtype dt, bool out_f32, const float* part_ml, const float* part_U,
                               const void* Bv, int64_t bstride, void* out, float* lse, int B, int H,
-                              int d, int r, int nsplit, hipStream_t stream);
+                              int H_kv, int d, int r, int nsplit, hipStream_t stream);
+ap_status launch_fold_heads(ap_dtype dt, const void* Bk, int64_t bstride, const void* q, void* Qp, int B,
+                            int H, int H_kv, int Hp, int d, int r, float scale, hipStream_t stream);
 
 ap_status launch_update_importance(const float* scores, const float* lse, float* mass, int B, int H,
                                    int T, int T_cap, int64_t mass_stride, float alpha,
@@ -144,8 +147,8 @@ ap_status launch_update_importance(const float* scores, const float* lse, float*
 
 size_t raw_attn_workspace(int B, int H, int d, int T);
 ap_status launch_raw_attn(const void* q, const void* K, const void* V, float* out, float* lse, int B,
-                          int H, int d, int T, int T_cap, float sm_scale, ap_dtype dt, void* workspace,
-                          hipStream_t stream);
+                          int H, int H_kv, int d, int T, int T_cap, float sm_scale, ap_dtype dt,
+                          void* workspace, hipStream_t stream);
 ap_status launch_merge_segments(const float* out_a, const float* lse_a, const float* out_b,
                                 const float* lse_b, void* out, float* lse, int B, int H, int d,
                                 ap_dtype dt_out, hipStream_t stream);

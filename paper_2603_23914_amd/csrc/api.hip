@@ -217,9 +217,9 @@ static ap_status decode_entry(const char* name, const void* q, const void* k_new
                               const void* scale_v, const void* Bk, const void* Bv,
                               int64_t basis_batch_stride, const int32_t* rank_k,
                               const int32_t* rank_v, const int32_t* bucket_off,
-                              const int32_t* bucket_idx, int F, void* out, float* lse, float* scores, int B,
-                              int H,
-                              int d, int T, int T_cap, int r, float sm_scale, ap_dtype dt,
+                              const int32_t* bucket_idx, int F, void* out, float* lse, float* scores,
+                              int B, int H, int H_kv, int d, int T, int T_cap, int r, float sm_scale,
+                              ap_dtype dt,
                               ap_dtype dt_coef, ap_dtype dt_out, void* workspace, size_t ws_bytes,
                               void* stream) {
   clear_error();
@@ -233,9 +233,11 @@ static ap_status decode_entry(const char* name, const void* q, const void* k_new
              "%s: dt_out must equal dt or be AP_F32", name);
   AP_REQUIRE(sm_scale == sm_scale && sm_scale > 0.f && sm_scale < 1e30f, AP_ERR_INVALID_ARG,
              "%s: sm_scale must be finite and positive", name);
-  const int64_t HD = (int64_t)H * d;
+  AP_REQUIRE(H_kv >= 1 && H % H_kv == 0, AP_ERR_INVALID_ARG,
+             "%s: H_kv=%d must be positive and divide H=%d", name, H_kv, H);
+  const int64_t HD = (int64_t)H_kv * d;
   AP_REQUIRE(basis_batch_stride == 0 || basis_batch_stride >= (int64_t)r * HD, AP_ERR_INVALID_ARG,
-             "%s: basis_batch_stride must be 0 or >= r*H*d", name);
+             "%s: basis_batch_stride must be 0 or >= r*H_kv*d", name);
   AP_REQUIRE(aligned(q, 16) && aligned(Ck, 16) && aligned(Cv, 16) && aligned(Bk, 16) &&
                  aligned(Bv, 16) && aligned(out, 16),
              AP_ERR_INVALID_ARG, "%s: pointers must be 16-byte aligned", name);
@@ -264,7 +266,7 @@ static ap_status decode_entry(const char* name, const void* q, const void* k_new
   AP_REQUIRE(aligned(workspace, 256), AP_ERR_INVALID_ARG, "%s: workspace must be 256-byte aligned",
              name);
   DecodeArgs a{q, k_new, v_new, Ck, Cv, scale_k, scale_v, Bk, Bv, basis_batch_stride, rank_k, rank_v,
-               bucket_off, bucket_idx, ragged ? F : 0, out, lse, scores, B, H, d, T, T_cap, r, sm_scale,
+               bucket_off, bucket_idx, ragged ? F : 0, out, lse, scores, H_kv, B, H, d, T, T_cap, r, sm_scale,
                dt, dt_coef, dt_out, workspace, ws_bytes, (hipStream_t)stream};
   return dt == AP_F32 ? launch_decode_f32(a) : launch_decode_mfma(a);
 }
@@ -273,25 +275,24 @@ ap_status ap_decode_attn(const void* q, const void* Ck, const void* Cv, const vo
                          const void* scale_v, const void* Bk, const void* Bv,
                          int64_t basis_batch_stride, const int32_t* rank_k, const int32_t* rank_v,
                          const int32_t* bucket_off, const int32_t* bucket_idx, int F, void* out,
-                         float* lse, float* scores, int B, int H, int d, int T, int T_cap, int r,
-                         float sm_scale, ap_dtype dt, ap_dtype dt_coef, ap_dtype dt_out,
+                         float* lse, float* scores, int B, int H, int H_kv, int d, int T, int T_cap,
+                         int r, float sm_scale, ap_dtype dt, ap_dtype dt_coef, ap_dtype dt_out,
                          void* workspace, size_t ws_bytes, void* stream) {
   return decode_entry("ap_decode_attn", q, nullptr, nullptr, Ck, Cv, scale_k, scale_v, Bk, Bv,
-                      basis_batch_stride, rank_k, rank_v, bucket_off, bucket_idx, F, out, lse, scores, B, H,
+                      basis_batch_stride, rank_k, rank_v, bucket_off, bucket_idx, F, out, lse, scores, B, H, H_kv,
                       d, T, T_cap, r, sm_scale, dt, dt_coef, dt_out, workspace, ws_bytes, stream);
 }
 
 ap_status ap_decode_step(const void* q, const void* k_new, const void* v_new, void* Ck, void* Cv,
                          const void* Bk, const void* Bv, int64_t basis_batch_stride,
                          const int32_t* rank_k, const int32_t* rank_v, const int32_t* bucket_off,
-                         const int32_t* bucket_idx, int F, void* out, float* lse, float* scores, int B,
-                              int H,
-                         int d, int T, int T_cap, int r, float sm_scale, ap_dtype dt,
-                         ap_dtype dt_out, void* workspace, size_t ws_bytes, void* stream) {
+                         const int32_t* bucket_idx, int F, void* out, float* lse, float* scores,
+                         int B, int H, int H_kv, int d, int T, int T_cap, int r, float sm_scale,
+                         ap_dtype dt, ap_dtype dt_out, void* workspace, size_t ws_bytes, void* stream) {
   clear_error();
   AP_REQUIRE(k_new && v_new, AP_ERR_INVALID_ARG, "ap_decode_step: NULL pointer");
   return decode_entry("ap_decode_step", q, k_new, v_new, Ck, Cv, nullptr, nullptr, Bk, Bv,
-                      basis_batch_stride, rank_k, rank_v, bucket_off, bucket_idx, F, out, lse, scores, B, H,
+                      basis_batch_stride, rank_k, rank_v, bucket_off, bucket_idx, F, out, lse, scores, B, H, H_kv,
                       d, T, T_cap, r, sm_scale, dt, dt, dt_out, workspace, ws_bytes, stream);
 }
 
@@ -305,12 +306,14 @@ size_t ap_raw_workspace_bytes(int B, int H, int d, int T_u) {
 }
 
 ap_status ap_raw_attn(const void* q, const void* K, const void* V, float* out, float* lse, int B, int H,
-                      int d, int T_u, int T_u_cap, float sm_scale, ap_dtype dt, void* workspace,
+                      int H_kv, int d, int T_u, int T_u_cap, float sm_scale, ap_dtype dt, void* workspace,
                       size_t ws_bytes, void* stream) {
   clear_error();
   AP_REQUIRE(q && out && workspace, AP_ERR_INVALID_ARG, "ap_raw_attn: NULL pointer");
   AP_REQUIRE(raw_shape_ok(B, H, d), AP_ERR_UNSUPPORTED,
              "ap_raw_attn: need 0 < B, H <= 65535 and d in {32, 64, 128, 256}");
+  AP_REQUIRE(H_kv >= 1 && H % H_kv == 0, AP_ERR_INVALID_ARG,
+             "ap_raw_attn: H_kv=%d must be positive and divide H=%d", H_kv, H);
   AP_REQUIRE(dt == AP_F16 || dt == AP_BF16, AP_ERR_UNSUPPORTED, "ap_raw_attn: fp16 or bf16 storage only");
   AP_REQUIRE(T_u >= 0 && T_u <= T_u_cap, AP_ERR_INVALID_ARG, "ap_raw_attn: need 0 <= T_u <= T_u_cap");
   AP_REQUIRE(T_u == 0 || (K && V), AP_ERR_INVALID_ARG, "ap_raw_attn: NULL cache with T_u > 0");
@@ -319,7 +322,7 @@ ap_status ap_raw_attn(const void* q, const void* K, const void* V, float* out, f
   AP_REQUIRE(ws_bytes >= raw_attn_workspace(B, H, d, T_u), AP_ERR_WORKSPACE,
              "ap_raw_attn: workspace too small (%zu < %zu bytes)", ws_bytes,
              raw_attn_workspace(B, H, d, T_u));
-  return launch_raw_attn(q, K, V, out, lse, B, H, d, T_u, T_u_cap, sm_scale, dt, workspace,
+  return launch_raw_attn(q, K, V, out, lse, B, H, H_kv, d, T_u, T_u_cap, sm_scale, dt, workspace,
                          (hipStream_t)stream);
 }
 

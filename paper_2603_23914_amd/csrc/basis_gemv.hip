@@ -57,7 +57,8 @@ __global__ void __launch_bounds__(256) basis_rows(const RowsParams p) {
   // zero), so the loads carry no branches and issue back to back
   int eoff[KPC];
 #pragma unroll
-  for (int pp = 0; pp < KPC; ++pp) eoff[pp] = (pp * 512 + lane * 8) < HD ? pp * 512 + lane * 8 : lane * 8;
+  for (int pp = 0; pp < KPC; ++pp)
+    eoff[pp] = (pp * 512 + lane * 8) < HD ? pp * 512 + lane * 8 : (lane * 8 < HD ? lane * 8 : 0);
   auto load_row = [&](u32x4_t (&dst)[KPC], int i) {         // row i of this wave
     int j = j0 + w * rpw + i;
     j = j < r ? j : r - 1;                                  // rows past the end: harmless repeats
@@ -135,13 +136,62 @@ __global__ void __launch_bounds__(256) basis_rows(const RowsParams p) {
 }
 
 // ------------------------------------------------------------------------------------------
+// fold_heads: the fold for grouped queries, q'[h, j] = scale * Bk[j, slice of key/value head
+// h / G] . q_h.  The G query heads of a group read the same slice of every basis row (from
+// HBM once, then from cache), so the work is laid out by query head: a workgroup owns one head
+// and a block of rows, groups of LPH = d / 8 lanes take one row each, four rows in flight.
+//   grid (Hp, ceil(r / 256), B), 256 threads; heads H .. Hp-1 (padding) are written as zeros.
+// ------------------------------------------------------------------------------------------
+template <class Tag, int LPH>
+__global__ void __launch_bounds__(256)
+fold_heads(const uint16_t* __restrict__ Bk, int64_t bstride, const uint16_t* __restrict__ q,
+           uint16_t* __restrict__ Qp, int H, int G, int Hp, int r, float scale) {
+  constexpr int d = LPH * 8;
+  constexpr int NG = 256 / LPH;
+  const int h = blockIdx.x, b = blockIdx.z, tid = threadIdx.x;
+  const int jb = blockIdx.y * 256;
+  int jend = jb + 256;
+  jend = jend < r ? jend : r;
+  uint16_t* hi_row = Qp + (((size_t)b * 2 + 0) * Hp + h) * r;
+  uint16_t* lo_row = Qp + (((size_t)b * 2 + 1) * Hp + h) * r;
+  if (h >= H) {
+    for (int j = jb + tid; j < jend; j += 256) { hi_row[j] = 0; lo_row[j] = 0; }
+    return;
+  }
+  const int g = tid / LPH, li = tid % LPH;
+  const size_t HD = (size_t)(H / G) * d;
+  const u32x4_t qv = *(const u32x4_t*)(q + ((size_t)b * H + h) * d + li * 8);
+  const uint16_t* col = Bk + (size_t)b * bstride + (size_t)(h / G) * d + li * 8;
+  for (int j0 = jb; j0 < jend; j0 += NG * 4) {
+    u32x4_t rowv[4];
+    int j[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      j[u] = j0 + u * NG + g;
+      const int jc = j[u] < jend ? j[u] : jend - 1;          // in-bounds repeat, result dropped
+      rowv[u] = *(const u32x4_t*)(col + (size_t)jc * HD);
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const float v = group_sum<LPH>(dot8<Tag>(rowv[u], qv, 0.f)) * scale;
+      if (li == 0 && j[u] < jend) {
+        uint16_t hi, lo;
+        split_hi_lo<Tag>(v, hi, lo);
+        hi_row[j[u]] = hi;
+        lo_row[j[u]] = lo;
+      }
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------
 // merge_expand: grid (ceil(H / 2), B), 256 threads.
 // ------------------------------------------------------------------------------------------
 template <class Tag, bool OUT_F32>
 __global__ void __launch_bounds__(256)
 merge_expand(const float* __restrict__ part_ml, const float* __restrict__ part_U,
              const uint16_t* __restrict__ Bv, int64_t bstride, void* __restrict__ out,
-             float* __restrict__ lse, int H, int d, int r, int nsplit) {
+             float* __restrict__ lse, int H, int G, int d, int r, int nsplit) {
   extern __shared__ __attribute__((aligned(16))) char smem_me[];
   float* ustar = (float*)smem_me;          // [2][r]
   float* red = ustar + 2 * r;              // [rows][2 d]
@@ -173,8 +223,10 @@ merge_expand(const float* __restrict__ part_ml, const float* __restrict__ part_U
   const int rg = tid / tpr, cc = tid - rg * tpr;
   const bool live = cc * 8 < nh * d;       // an odd head count leaves the upper half idle
   const float* us = ustar + (cc * 8 >= d ? r : 0);
-  const size_t HD = (size_t)H * d;
-  const uint16_t* Bb = Bv + (size_t)b * bstride + (size_t)h0 * d + cc * 8;
+  // grouped queries: G consecutive query heads read the same d-wide slice of the basis rows
+  const size_t HD = (size_t)(H / G) * d;
+  const int hsel = cc * 8 >= d ? 1 : 0;
+  const uint16_t* Bb = Bv + (size_t)b * bstride + (size_t)((h0 + hsel) / G) * d + (cc * 8 - hsel * d);
   float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   if (live) {
     int j = rg;
@@ -270,7 +322,7 @@ __global__ void __launch_bounds__(128) expand_append(const ExpandParams p) {
   for (int pp = 0; pp < KH; ++pp) {
     const int e0 = (half * KH + pp) * 512 + lane * 8;
     inside[pp] = e0 < HD;
-    eoff[pp] = inside[pp] ? e0 : lane * 8;
+    eoff[pp] = inside[pp] ? e0 : (lane * 8 < HD ? lane * 8 : 0);
   }
   auto load_row = [&](u32x4_t (&dst)[KH], int i) {
     int j = j0 + i;
@@ -519,6 +571,24 @@ ap_status launch_basis_rows(ap_dtype dt, const void* Bm, int64_t bstride, const 
   return launch_rows<BF16Tag, false, true>(p, B, stream);
 }
 
+ap_status launch_fold_heads(ap_dtype dt, const void* Bk, int64_t bstride, const void* q, void* Qp, int B,
+                            int H, int H_kv, int Hp, int d, int r, float scale, hipStream_t stream) {
+  const dim3 grid(Hp, (r + 255) / 256, B);
+  const int G = H / H_kv;
+#define AP_FH(TAG, L)                                                                                   \
+  hipLaunchKernelGGL((fold_heads<TAG, L>), grid, dim3(256), 0, stream, (const uint16_t*)Bk, bstride,    \
+                     (const uint16_t*)q, (uint16_t*)Qp, H, G, Hp, r, scale)
+  if (dt == AP_F16) {
+    switch (d) { case 32: AP_FH(F16Tag, 4); break; case 64: AP_FH(F16Tag, 8); break;
+                 case 128: AP_FH(F16Tag, 16); break; default: AP_FH(F16Tag, 32); break; }
+  } else {
+    switch (d) { case 32: AP_FH(BF16Tag, 4); break; case 64: AP_FH(BF16Tag, 8); break;
+                 case 128: AP_FH(BF16Tag, 16); break; default: AP_FH(BF16Tag, 32); break; }
+  }
+#undef AP_FH
+  return AP_OK;
+}
+
 int basis_rows_per_wave(int B, int r) {
   // about five workgroups per CU, two of them resident at a time: the start and the end of a
   // workgroup (vector slices in, folded tile out) then overlap other workgroups' streaming
@@ -579,17 +649,18 @@ ap_status launch_expand_append(ap_dtype dt, bool out_f32, const void* Bv, int64_
 
 ap_status launch_merge_expand(ap_dtype dt, bool out_f32, const float* part_ml, const float* part_U,
                               const void* Bv, int64_t bstride, void* out, float* lse, int B, int H,
-                              int d, int r, int nsplit, hipStream_t stream) {
+                              int H_kv, int d, int r, int nsplit, hipStream_t stream) {
+  const int G = H / H_kv;
   const int rows = 256 / ((2 * d) >> 3);
   const size_t lds = ((size_t)2 * r + (size_t)rows * 2 * d) * 4;
   const dim3 grid((H + 1) / 2, B);
   const uint16_t* bv = (const uint16_t*)Bv;
   if (dt == AP_F16) {
-    if (out_f32) hipLaunchKernelGGL((merge_expand<F16Tag, true>), grid, dim3(256), lds, stream, part_ml, part_U, bv, bstride, out, lse, H, d, r, nsplit);
-    else hipLaunchKernelGGL((merge_expand<F16Tag, false>), grid, dim3(256), lds, stream, part_ml, part_U, bv, bstride, out, lse, H, d, r, nsplit);
+    if (out_f32) hipLaunchKernelGGL((merge_expand<F16Tag, true>), grid, dim3(256), lds, stream, part_ml, part_U, bv, bstride, out, lse, H, G, d, r, nsplit);
+    else hipLaunchKernelGGL((merge_expand<F16Tag, false>), grid, dim3(256), lds, stream, part_ml, part_U, bv, bstride, out, lse, H, G, d, r, nsplit);
   } else {
-    if (out_f32) hipLaunchKernelGGL((merge_expand<BF16Tag, true>), grid, dim3(256), lds, stream, part_ml, part_U, bv, bstride, out, lse, H, d, r, nsplit);
-    else hipLaunchKernelGGL((merge_expand<BF16Tag, false>), grid, dim3(256), lds, stream, part_ml, part_U, bv, bstride, out, lse, H, d, r, nsplit);
+    if (out_f32) hipLaunchKernelGGL((merge_expand<BF16Tag, true>), grid, dim3(256), lds, stream, part_ml, part_U, bv, bstride, out, lse, H, G, d, r, nsplit);
+    else hipLaunchKernelGGL((merge_expand<BF16Tag, false>), grid, dim3(256), lds, stream, part_ml, part_U, bv, bstride, out, lse, H, G, d, r, nsplit);
   }
   return AP_OK;
 }

@@ -44,13 +44,13 @@ __device__ __forceinline__ float block_reduce_max(float v, float* sh) {
 // grid (H, B): q' for one head.
 __global__ void __launch_bounds__(kThreads)
 f32_fold(const float* __restrict__ q, const float* __restrict__ Bk, int64_t bstride,
-         float* __restrict__ qp, int H, int d, int r, float sm_scale) {
+         float* __restrict__ qp, int H, int G, int d, int r, float sm_scale) {
   const int h = blockIdx.x, b = blockIdx.y;
   const float* qh = q + ((size_t)b * H + h) * d;
   const float* Bb = Bk + (size_t)b * bstride;
-  const size_t HD = (size_t)H * d;
+  const size_t HD = (size_t)(H / G) * d;          // G query heads share a key/value head
   for (int j = threadIdx.x; j < r; j += kThreads) {
-    const float* row = Bb + (size_t)j * HD + (size_t)h * d;
+    const float* row = Bb + (size_t)j * HD + (size_t)(h / G) * d;
     double acc = 0.0;
     for (int i = 0; i < d; ++i) acc += (double)row[i] * (double)qh[i];
     qp[((size_t)b * H + h) * r + j] = (float)(acc * (double)sm_scale);
@@ -80,7 +80,7 @@ __global__ void __launch_bounds__(kThreads)
 f32_softmax_out(const float* __restrict__ Cv, const float* __restrict__ Bv, int64_t bstride,
                 const int32_t* __restrict__ rank_v, float* __restrict__ S,
                 float* __restrict__ U, float* __restrict__ out, float* __restrict__ lse, int H,
-                int d, int T, int T_cap, int r) {
+                int G, int d, int T, int T_cap, int r) {
   __shared__ double shd[kThreads];
   __shared__ float shf[kThreads];
   const int h = blockIdx.x, b = blockIdx.y;
@@ -109,10 +109,10 @@ f32_softmax_out(const float* __restrict__ Cv, const float* __restrict__ Bv, int6
   }
   __syncthreads();
   const float* Bb = Bv + (size_t)b * bstride;
-  const size_t HD = (size_t)H * d;
+  const size_t HD = (size_t)(H / G) * d;
   for (int i = threadIdx.x; i < d; i += kThreads) {
     double acc = 0.0;
-    for (int j = 0; j < r; ++j) acc += (double)u[j] * (double)Bb[(size_t)j * HD + (size_t)h * d + i];
+    for (int j = 0; j < r; ++j) acc += (double)u[j] * (double)Bb[(size_t)j * HD + (size_t)(h / G) * d + i];
     out[((size_t)b * H + h) * d + i] = (float)acc;
   }
 }
@@ -137,12 +137,12 @@ ap_status launch_decode_f32(const DecodeArgs& a) {
   ws += round_up((size_t)a.B * a.H * a.T * 4, 256);
   float* U = (float*)ws;
   hipLaunchKernelGGL(f32_fold, dim3(a.H, a.B), dim3(kThreads), 0, a.stream, (const float*)a.q,
-                     (const float*)a.Bk, a.basis_batch_stride, qp, a.H, a.d, a.r, a.sm_scale);
+                     (const float*)a.Bk, a.basis_batch_stride, qp, a.H, a.H / a.H_kv, a.d, a.r, a.sm_scale);
   hipLaunchKernelGGL(f32_scores, dim3((a.T + kThreads - 1) / kThreads, a.H, a.B), dim3(kThreads), 0,
                      a.stream, (const float*)a.Ck, qp, a.rank_k, S, a.scores, a.H, a.T, a.T_cap, a.r);
   hipLaunchKernelGGL(f32_softmax_out, dim3(a.H, a.B), dim3(kThreads), 0, a.stream,
                      (const float*)a.Cv, (const float*)a.Bv, a.basis_batch_stride, a.rank_v, S, U,
-                     (float*)a.out, a.lse, a.H, a.d, a.T, a.T_cap, a.r);
+                     (float*)a.out, a.lse, a.H, a.H / a.H_kv, a.d, a.T, a.T_cap, a.r);
   return check_launch("ap_decode_attn(fp32)");
 }
 

@@ -1152,7 +1152,9 @@ ap_status run_decode(const DecodeArgs& a) {
   // A fused step with uniform rank scores all T tokens in attn_partial but leaves the newest
   // token's value row to the expansion pass over B_v, which produces that row and adds its
   // contribution: B_v is read once per step instead of twice.
-  const bool one_pass_v = a.v_new && !a.rank_k && !a.rank_v && a.T >= 2;
+  const int Hkv = a.H_kv;
+  const int HDkv = Hkv * a.d;              // hidden columns of the cache and of the basis rows
+  const bool one_pass_v = a.v_new && !a.rank_k && !a.rank_v && a.T >= 2 && Hkv == a.H;
   const int S = choose_nsplit(a.B, a.T);
   const WsLayout wl = ws_layout(a.B, a.H, a.d, a.T, a.r);
   char* ws = (char*)a.workspace;
@@ -1160,13 +1162,25 @@ ap_status run_decode(const DecodeArgs& a) {
   float* ml = (float*)(ws + wl.ml);
   float* U = (float*)(ws + wl.u);
   // fold (and, for a fused step, the append of the key row in the same pass over B_k)
-  ap_status st = launch_basis_rows(a.dt, a.Bk, a.basis_batch_stride, a.k_new, a.q, (void*)a.Ck, Qp,
-                                   a.B, a.H, Hp, a.d, a.H * a.d, a.r, a.T - 1, a.T_cap,
-                                   a.sm_scale * kLog2e, a.stream);
+  ap_status st;
+  if (Hkv == a.H) {
+    st = launch_basis_rows(a.dt, a.Bk, a.basis_batch_stride, a.k_new, a.q, (void*)a.Ck, Qp, a.B, a.H, Hp,
+                           a.d, a.H * a.d, a.r, a.T - 1, a.T_cap, a.sm_scale * kLog2e, a.stream);
+  } else {
+    // grouped queries: the key row is appended by a pass of its own over the (small) basis,
+    // the fold runs per query head
+    st = AP_OK;
+    if (a.k_new)
+      st = launch_basis_rows(a.dt, a.Bk, a.basis_batch_stride, a.k_new, nullptr, (void*)a.Ck, nullptr,
+                             a.B, 0, 0, 8, HDkv, a.r, a.T - 1, a.T_cap, 1.0f, a.stream);
+    if (st != AP_OK) return st;
+    st = launch_fold_heads(a.dt, a.Bk, a.basis_batch_stride, a.q, Qp, a.B, a.H, Hkv, Hp, a.d, a.r,
+                           a.sm_scale * kLog2e, a.stream);
+  }
   if (st != AP_OK) return st;
   if (a.v_new && !one_pass_v) {
     st = launch_basis_rows(a.dt, a.Bv, a.basis_batch_stride, a.v_new, nullptr, (void*)a.Cv, nullptr,
-                           a.B, 0, 0, 8, a.H * a.d, a.r, a.T - 1, a.T_cap, 1.0f, a.stream);
+                           a.B, 0, 0, 8, HDkv, a.r, a.T - 1, a.T_cap, 1.0f, a.stream);
     if (st != AP_OK) return st;
   }
   AttnParams p{};
@@ -1216,7 +1230,7 @@ ap_status run_decode(const DecodeArgs& a) {
                               a.out, a.lse, a.B, a.H, a.d, a.r, a.T, a.T_cap, S_exp, a.stream);
   else
     st = launch_merge_expand(a.dt, a.dt_out == AP_F32, ml, U, a.Bv, a.basis_batch_stride, a.out, a.lse,
-                             a.B, a.H, a.d, a.r, S_exp, a.stream);
+                             a.B, a.H, Hkv, a.d, a.r, S_exp, a.stream);
   if (st != AP_OK) return st;
   return check_launch("ap_decode_attn");
 }
@@ -1230,7 +1244,7 @@ size_t decode_mfma_workspace(int B, int H, int d, int T, int r, ap_dtype dt) {
 
 ap_status launch_decode_mfma(const DecodeArgs& a) {
   AP_REQUIRE(a.B <= 65535, AP_ERR_UNSUPPORTED, "ap_decode_attn: B must be <= 65535");
-  AP_REQUIRE(basis_rows_applies(a.H * a.d, a.B), AP_ERR_UNSUPPORTED,
+  AP_REQUIRE(basis_rows_applies(a.H_kv * a.d, a.B), AP_ERR_UNSUPPORTED,
              "ap_decode_attn: H*d must be a multiple of 8 and <= 8192");
   AP_REQUIRE(a.dt_coef != AP_I8 || (!a.rank_k && !a.rank_v), AP_ERR_UNSUPPORTED,
              "ap_decode_attn: int8 coefficients with per-token ranks are not implemented");

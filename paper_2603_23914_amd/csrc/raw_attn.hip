@@ -22,24 +22,25 @@ namespace {
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr int kUnroll = 4;       // tokens in flight per lane group
 
-// grid (H, S, B), 256 threads.  LPH = d / 8 lanes form a group; G = 256 / LPH groups.
+// grid (H, S, B), 256 threads.  LPH = d / 8 lanes form a group; G = 256 / LPH groups.  QG query
+// heads share one key/value head (grouped queries; 1 = every head has its own).
 // Split su covers tokens [su * per, min(T, (su + 1) * per)); group g takes every G-th of them.
 // Writes the normalised partial output [su][b][h][d] and its log-sum-exp [su][b][h].
 template <class Tag, int LPH>
 __global__ void __launch_bounds__(256)
 raw_attn_partial(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K,
                  const uint16_t* __restrict__ V, float* __restrict__ out_part,
-                 float* __restrict__ lse_part, int B, int H, int T, int T_cap, int per,
+                 float* __restrict__ lse_part, int B, int H, int QG, int T, int T_cap, int per,
                  float scale_log2) {
   constexpr int d = LPH * 8;
   constexpr int G = 256 / LPH;
   __shared__ float red[G][d + 2];
   const int h = blockIdx.x, su = blockIdx.y, b = blockIdx.z;
   const int tid = threadIdx.x, g = tid / LPH, li = tid % LPH;
-  const size_t HD = (size_t)H * d;
+  const size_t HD = (size_t)(H / QG) * d;         // QG query heads share a key/value head
   const u32x4_t qv = *(const u32x4_t*)(q + ((size_t)b * H + h) * d + li * 8);
-  const uint16_t* Kb = K + (size_t)b * T_cap * HD + (size_t)h * d + li * 8;
-  const uint16_t* Vb = V + (size_t)b * T_cap * HD + (size_t)h * d + li * 8;
+  const uint16_t* Kb = K + (size_t)b * T_cap * HD + (size_t)(h / QG) * d + li * 8;
+  const uint16_t* Vb = V + (size_t)b * T_cap * HD + (size_t)(h / QG) * d + li * 8;
   const int t0 = su * per;
   int t1 = t0 + per;
   t1 = t1 < T ? t1 : T;
@@ -162,13 +163,13 @@ int raw_splits(int B, int H, int d, int T) {
 
 template <class Tag>
 void launch_raw_partial(const void* q, const void* K, const void* V, float* op, float* lp, int B, int H,
-                        int d, int T, int T_cap, int S, float sm_scale, hipStream_t stream) {
+                        int G, int d, int T, int T_cap, int S, float sm_scale, hipStream_t stream) {
   const int per = (T + S - 1) / S;
   const dim3 grid(H, S, B);
   const float sc = sm_scale * kLog2e;
 #define AP_RAW(L)                                                                               \
   hipLaunchKernelGGL((raw_attn_partial<Tag, L>), grid, dim3(256), 0, stream, (const uint16_t*)q, \
-                     (const uint16_t*)K, (const uint16_t*)V, op, lp, B, H, T, T_cap, per, sc)
+                     (const uint16_t*)K, (const uint16_t*)V, op, lp, B, H, G, T, T_cap, per, sc)
   switch (d) {
     case 32: AP_RAW(4); break;
     case 64: AP_RAW(8); break;
@@ -194,8 +195,9 @@ size_t raw_attn_workspace(int B, int H, int d, int T) {
 }
 
 ap_status launch_raw_attn(const void* q, const void* K, const void* V, float* out, float* lse, int B,
-                          int H, int d, int T, int T_cap, float sm_scale, ap_dtype dt, void* workspace,
-                          hipStream_t stream) {
+                          int H, int H_kv, int d, int T, int T_cap, float sm_scale, ap_dtype dt,
+                          void* workspace, hipStream_t stream) {
+  const int G = H / H_kv;
   const int S = raw_splits(B, H, d, T);
   float* op = out;
   float* lp = lse;
@@ -203,8 +205,8 @@ ap_status launch_raw_attn(const void* q, const void* K, const void* V, float* ou
     op = S > 1 ? (float*)workspace : out;
     lp = (float*)((char*)workspace + round_up((size_t)S * B * H * d * 4, 256));
   }
-  if (dt == AP_F16) launch_raw_partial<F16Tag>(q, K, V, op, lp, B, H, d, T, T_cap, S, sm_scale, stream);
-  else launch_raw_partial<BF16Tag>(q, K, V, op, lp, B, H, d, T, T_cap, S, sm_scale, stream);
+  if (dt == AP_F16) launch_raw_partial<F16Tag>(q, K, V, op, lp, B, H, G, d, T, T_cap, S, sm_scale, stream);
+  else launch_raw_partial<BF16Tag>(q, K, V, op, lp, B, H, G, d, T, T_cap, S, sm_scale, stream);
   if (S > 1) {
     MergeArgs a{{op, nullptr}, {lp, nullptr}, {S, 0}, (size_t)B * H * d, (size_t)B * H};
     launch_merge<F16Tag>(a, out, true, lse, B, H, d, stream);

@@ -43,10 +43,10 @@ def test_argument_validation_without_gpu():
     lib.ap_last_error.restype = ctypes.c_char_p
     vp = ctypes.c_void_p
     lib.ap_decode_attn.argtypes = ([vp] * 7 + [ctypes.c_int64] + [vp] * 4 + [ctypes.c_int] +
-                                   [vp, vp, vp] + [ctypes.c_int] * 6 +
+                                   [vp, vp, vp] + [ctypes.c_int] * 7 +
                                    [ctypes.c_float, ctypes.c_int, ctypes.c_int, ctypes.c_int, vp, ctypes.c_size_t, vp])
     st = lib.ap_decode_attn(None, None, None, None, None, None, None, 0, None, None, None, None, 0,
-                            None, None, None, 1, 4, 32, 64, 64, 16, 0.1, 0, 0, 0, None, 0, None)
+                            None, None, None, 1, 4, 4, 32, 64, 64, 16, 0.1, 0, 0, 0, None, 0, None)
     assert st == 1 and b"NULL" in lib.ap_last_error()
     gr = (ctypes.c_int32 * 2)(64, 128)                                     # increasing: invalid
     cn = (ctypes.c_int32 * 2)(1, 2)
