@@ -137,31 +137,43 @@ __global__ void __launch_bounds__(256) basis_rows(const RowsParams p) {
 
 // ------------------------------------------------------------------------------------------
 // fold_heads: the fold for grouped queries, q'[h, j] = scale * Bk[j, slice of key/value head
-// h / G] . q_h.  The G query heads of a group read the same slice of every basis row (from
-// HBM once, then from cache), so the work is laid out by query head: a workgroup owns one head
-// and a block of rows, groups of LPH = d / 8 lanes take one row each, four rows in flight.
-//   grid (Hp, ceil(r / 256), B), 256 threads; heads H .. Hp-1 (padding) are written as zeros.
+// h / G] . q_h.  A workgroup owns one key/value head and 64 basis rows; groups of LPH = d / 8
+// lanes take one row each (four rows in flight per group) and dot it with the queries of all
+// G heads that share the slice, so every basis byte is loaded once.
+//   grid (H_kv * ceil(G / 8), ceil(r / 64), B), 256 threads; the workgroups of key/value
+//   head 0 also write the padding heads H .. Hp-1 as zeros.
 // ------------------------------------------------------------------------------------------
 template <class Tag, int LPH>
 __global__ void __launch_bounds__(256)
 fold_heads(const uint16_t* __restrict__ Bk, int64_t bstride, const uint16_t* __restrict__ q,
            uint16_t* __restrict__ Qp, int H, int G, int Hp, int r, float scale) {
   constexpr int d = LPH * 8;
-  constexpr int NG = 256 / LPH;
-  const int h = blockIdx.x, b = blockIdx.z, tid = threadIdx.x;
-  const int jb = blockIdx.y * 256;
-  int jend = jb + 256;
+  constexpr int NG = 256 / LPH;                 // rows per pass of the workgroup
+  const int nsub = (G + 7) >> 3;                // query heads are taken eight at a time
+  const int kvh = blockIdx.x / nsub, sub = blockIdx.x - kvh * nsub;
+  const int b = blockIdx.z, tid = threadIdx.x;
+  const int jb = blockIdx.y * 64;
+  int jend = jb + 64;
   jend = jend < r ? jend : r;
-  uint16_t* hi_row = Qp + (((size_t)b * 2 + 0) * Hp + h) * r;
-  uint16_t* lo_row = Qp + (((size_t)b * 2 + 1) * Hp + h) * r;
-  if (h >= H) {
-    for (int j = jb + tid; j < jend; j += 256) { hi_row[j] = 0; lo_row[j] = 0; }
-    return;
+  if (blockIdx.x == 0) {
+    for (int i = tid; i < (Hp - H) * (jend - jb); i += 256) {
+      const int h = H + i / (jend - jb), j = jb + i % (jend - jb);
+      Qp[(((size_t)b * 2 + 0) * Hp + h) * r + j] = 0;
+      Qp[(((size_t)b * 2 + 1) * Hp + h) * r + j] = 0;
+    }
   }
   const int g = tid / LPH, li = tid % LPH;
   const size_t HD = (size_t)(H / G) * d;
-  const u32x4_t qv = *(const u32x4_t*)(q + ((size_t)b * H + h) * d + li * 8);
-  const uint16_t* col = Bk + (size_t)b * bstride + (size_t)(h / G) * d + li * 8;
+  const int h0 = kvh * G + sub * 8;             // first query head of this workgroup
+  int nq = G - sub * 8;
+  nq = nq < 8 ? nq : 8;
+  u32x4_t qv[8];
+#pragma unroll
+  for (int k = 0; k < 8; ++k) {
+    const int hk = k < nq ? h0 + k : h0;        // unused slots repeat the first head
+    qv[k] = *(const u32x4_t*)(q + ((size_t)b * H + hk) * d + li * 8);
+  }
+  const uint16_t* col = Bk + (size_t)b * bstride + (size_t)kvh * d + li * 8;
   for (int j0 = jb; j0 < jend; j0 += NG * 4) {
     u32x4_t rowv[4];
     int j[4];
@@ -173,12 +185,17 @@ fold_heads(const uint16_t* __restrict__ Bk, int64_t bstride, const uint16_t* __r
     }
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
-      const float v = group_sum<LPH>(dot8<Tag>(rowv[u], qv, 0.f)) * scale;
-      if (li == 0 && j[u] < jend) {
-        uint16_t hi, lo;
-        split_hi_lo<Tag>(v, hi, lo);
-        hi_row[j[u]] = hi;
-        lo_row[j[u]] = lo;
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        if (k < nq) {                                         // wave-uniform
+          const float v = group_sum<LPH>(dot8<Tag>(rowv[u], qv[k], 0.f)) * scale;
+          if (li == 0 && j[u] < jend) {
+            uint16_t hi, lo;
+            split_hi_lo<Tag>(v, hi, lo);
+            Qp[(((size_t)b * 2 + 0) * Hp + h0 + k) * r + j[u]] = hi;
+            Qp[(((size_t)b * 2 + 1) * Hp + h0 + k) * r + j[u]] = lo;
+          }
+        }
       }
     }
   }
@@ -197,24 +214,35 @@ merge_expand(const float* __restrict__ part_ml, const float* __restrict__ part_U
   float* red = ustar + 2 * r;              // [rows][2 d]
   const int h0 = blockIdx.x * 2, b = blockIdx.y, tid = threadIdx.x;
   const int nh = H - h0 < 2 ? H - h0 : 2;  // heads of this workgroup
-  // ---- merged, normalised coefficient sums of the two heads
-  for (int hh = 0; hh < nh; ++hh) {
+  // ---- merged, normalised coefficient sums of the two heads.  At most 8 splits arrive here
+  //      (more are merged beforehand); every load of a thread is issued before the first is
+  //      used, so the prologue costs two memory round trips, not one per split.
+  constexpr int kS = 8;
+  for (int i = tid; i < nh * r; i += 256) {
+    const int hh = i >= r ? 1 : 0, j = i - hh * r;
     const size_t pb = (size_t)b * nsplit * H + h0 + hh;    // + s*H
-    float mstar = -INFINITY;
-    for (int s = 0; s < nsplit; ++s) mstar = fmaxf(mstar, part_ml[(pb + (size_t)s * H) * 2]);
-    float L = 0.f;
-    for (int s = 0; s < nsplit; ++s)
-      L += part_ml[(pb + (size_t)s * H) * 2 + 1] * fast_exp2(part_ml[(pb + (size_t)s * H) * 2] - mstar);
-    const float invL = 1.0f / L;
-    for (int j = tid; j < r; j += 256) {
-      float acc = 0.f;
-      for (int s = 0; s < nsplit; ++s) {
-        const float ws = fast_exp2(part_ml[(pb + (size_t)s * H) * 2] - mstar);
-        acc = fmaf(ws, part_U[(pb + (size_t)s * H) * r + j], acc);
-      }
-      ustar[hh * r + j] = acc * invL;
+    float ms[kS], ls[kS], us_[kS];
+#pragma unroll
+    for (int s = 0; s < kS; ++s) {
+      const size_t ps = pb + (size_t)(s < nsplit ? s : 0) * H;
+      ms[s] = part_ml[ps * 2];
+      ls[s] = part_ml[ps * 2 + 1];
+      us_[s] = part_U[ps * r + j];
     }
-    if (tid == 0 && lse) lse[(size_t)b * H + h0 + hh] = (mstar + log2f(L)) * kLn2;
+    float mstar = -INFINITY;
+#pragma unroll
+    for (int s = 0; s < kS; ++s) if (s < nsplit) mstar = fmaxf(mstar, ms[s]);
+    float L = 0.f, acc = 0.f;
+#pragma unroll
+    for (int s = 0; s < kS; ++s) {
+      if (s < nsplit) {
+        const float ws = fast_exp2(ms[s] - mstar);
+        L = fmaf(ls[s], ws, L);
+        acc = fmaf(ws, us_[s], acc);
+      }
+    }
+    ustar[hh * r + j] = acc / L;
+    if (j == 0 && lse) lse[(size_t)b * H + h0 + hh] = (mstar + log2f(L)) * kLn2;
   }
   __syncthreads();
   // ---- expansion: thread (rg, cc) owns 8 columns of the 2d-wide slice and rows rg, rg+rows, ..
@@ -230,6 +258,20 @@ merge_expand(const float* __restrict__ part_ml, const float* __restrict__ part_U
   float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   if (live) {
     int j = rg;
+    for (; j + 7 * rows < r; j += 8 * rows) {              // eight rows in flight
+      u32x4_t wv[8];
+#pragma unroll
+      for (int k = 0; k < 8; ++k) wv[k] = *(const u32x4_t*)(Bb + (size_t)(j + k * rows) * HD);
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        const float u = us[j + k * rows];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          acc[2 * e] = fmaf(u, lo_to_f32(wv[k][e], Tag{}), acc[2 * e]);
+          acc[2 * e + 1] = fmaf(u, hi_to_f32(wv[k][e], Tag{}), acc[2 * e + 1]);
+        }
+      }
+    }
     for (; j + 3 * rows < r; j += 4 * rows) {              // four rows in flight
       u32x4_t wv[4];
 #pragma unroll
@@ -573,8 +615,8 @@ ap_status launch_basis_rows(ap_dtype dt, const void* Bm, int64_t bstride, const 
 
 ap_status launch_fold_heads(ap_dtype dt, const void* Bk, int64_t bstride, const void* q, void* Qp, int B,
                             int H, int H_kv, int Hp, int d, int r, float scale, hipStream_t stream) {
-  const dim3 grid(Hp, (r + 255) / 256, B);
   const int G = H / H_kv;
+  const dim3 grid(H_kv * ((G + 7) / 8), (r + 63) / 64, B);
 #define AP_FH(TAG, L)                                                                                   \
   hipLaunchKernelGGL((fold_heads<TAG, L>), grid, dim3(256), 0, stream, (const uint16_t*)Bk, bstride,    \
                      (const uint16_t*)q, (uint16_t*)Qp, H, G, Hp, r, scale)
