@@ -69,7 +69,7 @@ def run_steps(torch, ap, layers, q, knew, vnew, out, ws, t_start, nsteps):
                               T=t + 1, sm_scale=scale)
 
 
-def cpu_baseline(sample_seqs=8):
+def cpu_baseline(sample_seqs=24):
     """The oracle as it stands (NumPy fp64, definition form) on `sample_seqs` of the 64
     sequences for one decode step at T=4224; scaled to the batch."""
     import numpy as np
