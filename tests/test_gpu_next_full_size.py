@@ -1,0 +1,127 @@
+"""GPU parity at full batch size for the rows built after the hot path: importance tracking,
+the uncompressed segment and grouped queries, in the launch shapes a 64-sequence decode uses.
+Inputs are drawn on the GPU with torch (seeded, the law of the benchmark's coefficients); the
+sampled sequences are read back bit for bit and the fp64 oracle computes their results alone."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from gpu_util import assert_close, to_host64, workspace
+
+pytestmark = pytest.mark.gpu
+
+SAMPLE = (0, 37)
+
+
+def bits(t: torch.Tensor) -> np.ndarray:
+    """bf16 GPU tensor -> uint16 bit patterns on the host (what oracle.promote(.., "bf16") takes)."""
+    return t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+def P(t: torch.Tensor) -> np.ndarray:
+    return oracle.promote(bits(t), "bf16")
+
+
+def draw_cache(B, T_cap, r, HD, seed):
+    g = torch.Generator(device="cuda")
+    g.manual_seed(seed)
+    sig = torch.arange(1, r + 1, device="cuda", dtype=torch.float32) ** -0.7
+    ks = sig * math.sqrt(HD / float((sig ** 2).sum()))
+    out = []
+    for _ in range(2):                                   # C_k, C_v
+        c = torch.empty((B, T_cap, r), dtype=torch.bfloat16, device="cuda")
+        for b0 in range(0, B, 8):
+            x = torch.randn((8, T_cap, r), generator=g, device="cuda") * ks
+            x += 0.01 * torch.randn((8, T_cap, r), generator=g, device="cuda")
+            c[b0:b0 + 8] = x.to(torch.bfloat16)
+        out.append(c)
+    for _ in range(2):                                   # B_k, B_v: rows of unit norm on average
+        out.append((torch.randn((B, r, HD), generator=g, device="cuda") / math.sqrt(HD)).to(torch.bfloat16))
+    return out, g
+
+
+def test_importance_tracking_full_size():
+    from paper_2603_23914_amd import binding as ap
+    B, H, d, r, T0 = 64, 40, 128, 640, 4223
+    T, HD = T0 + 1, H * d
+    (Ck, Cv, Bk, Bv), g = draw_cache(B, T, r, HD, 61)
+    q = torch.randn((B, H, d), generator=g, device="cuda").to(torch.bfloat16)
+    kn = torch.randn((B, HD), generator=g, device="cuda").to(torch.bfloat16)
+    vn = torch.randn((B, HD), generator=g, device="cuda").to(torch.bfloat16)
+    mass = torch.rand((B, T), generator=g, device="cuda") / T
+    mass[:, T - 1] = 0.0                                  # the token being appended has no history
+    mass0 = mass.clone()
+    out = torch.empty((B, H, d), dtype=torch.float32, device="cuda")
+    lse = torch.empty((B, H), dtype=torch.float32, device="cuda")
+    scores = torch.empty((B, H, T), dtype=torch.float32, device="cuda")
+    ws = workspace(ap.ap_decode_workspace_bytes(B, H, d, T, r, ap.AP_BF16))
+    print("importance, 64 sequences at T=4224", flush=True)
+    ap.ap_decode_step(q, kn, vn, Ck, Cv, Bk, Bv, out, ws, T=T, sm_scale=1.0 / math.sqrt(d), lse=lse, scores=scores)
+    ap.ap_update_importance(scores, lse, mass, T=T, alpha=0.9)
+    granks, cum, den = (640, 320, 128, 64), (1, 2, 3, 4), 4
+    rank = torch.empty((B, T), dtype=torch.int32, device="cuda")
+    off = torch.empty((B, 5), dtype=torch.int32, device="cuda")
+    idx = torch.empty((B, T), dtype=torch.int32, device="cuda")
+    ap.ap_select_ranks(mass, granks, cum, den, rank, off, idx, workspace(ap.ap_select_workspace_bytes(B, T, 4)))
+    torch.cuda.synchronize()
+    for b in SAMPLE:
+        A = oracle.attention_probs(P(q[b]), P(Ck[b, :T]), P(Bk[b]))
+        ref = oracle.importance_update(mass0[b].cpu().numpy(), A[None], 0.9)
+        got = mass[b].cpu().numpy()
+        assert np.abs(got - ref).max() <= 2e-3 * ref.max(), f"b={b}"
+        r_ref, o_ref, i_ref = oracle.select_ranks(got, granks, cum, den)      # same fp32 mass on both sides
+        assert (rank[b].cpu().numpy() == r_ref).all() and (off[b].cpu().numpy() == o_ref).all()
+        assert (idx[b].cpu().numpy() == i_ref).all()
+        ref_out = oracle.decode_attn_absorbed(P(q[b]), P(Ck[b, :T]), P(Cv[b, :T]), P(Bk[b]), P(Bv[b]))
+        assert_close(to_host64(out[b]), ref_out, "bf16", f"output with logits stored, b={b}")
+
+
+def test_uncompressed_segment_full_size():
+    from paper_2603_23914_amd import binding as ap
+    B, H, d, r, T, T_u = 64, 40, 128, 640, 4224, 256
+    HD = H * d
+    (Ck, Cv, Bk, Bv), g = draw_cache(B, T, r, HD, 62)
+    q = torch.randn((B, H, d), generator=g, device="cuda").to(torch.bfloat16)
+    K = torch.randn((B, T_u, HD), generator=g, device="cuda").to(torch.bfloat16)
+    V = torch.randn((B, T_u, HD), generator=g, device="cuda").to(torch.bfloat16)
+    out_c = torch.empty((B, H, d), dtype=torch.float32, device="cuda")
+    lse_c = torch.empty((B, H), dtype=torch.float32, device="cuda")
+    out_u, lse_u = torch.empty_like(out_c), torch.empty_like(lse_c)
+    out = torch.empty_like(out_c)
+    print("compressed 4224 + uncompressed 256 tokens, 64 sequences", flush=True)
+    ap.ap_decode_attn(q, Ck, Cv, Bk, Bv, out_c, workspace(ap.ap_decode_workspace_bytes(B, H, d, T, r, ap.AP_BF16)),
+                      T=T, sm_scale=1.0 / math.sqrt(d), lse=lse_c)
+    ap.ap_raw_attn(q, K, V, out_u, workspace(ap.ap_raw_workspace_bytes(B, H, d, T_u)), T_u=T_u,
+                   sm_scale=1.0 / math.sqrt(d), lse=lse_u)
+    ap.ap_merge_segments(out_c, lse_c, out_u, lse_u, out)
+    torch.cuda.synchronize()
+    for b in SAMPLE:
+        ref = oracle.decode_attn_segments(P(q[b]), [dict(Ck=P(Ck[b]), Cv=P(Cv[b]), Bk=P(Bk[b]), Bv=P(Bv[b])),
+                                                    dict(K=P(K[b]), V=P(V[b]))])
+        assert_close(to_host64(out[b]), ref, "bf16", f"two segments, b={b}")
+        ref_u = oracle.raw_attn(P(q[b]), P(K[b]), P(V[b]))
+        assert_close(to_host64(out_u[b]), ref_u, "bf16", f"uncompressed segment alone, b={b}")
+
+
+def test_grouped_queries_full_size():
+    from paper_2603_23914_amd import binding as ap
+    B, H, Hkv, d, r, T0 = 64, 32, 8, 128, 256, 4223
+    T, HD = T0 + 1, Hkv * d
+    (Ck, Cv, Bk, Bv), g = draw_cache(B, T, r, HD, 63)
+    q = torch.randn((B, H, d), generator=g, device="cuda").to(torch.bfloat16)
+    kn = torch.randn((B, HD), generator=g, device="cuda").to(torch.bfloat16)
+    vn = torch.randn((B, HD), generator=g, device="cuda").to(torch.bfloat16)
+    out = torch.empty((B, H, d), dtype=torch.float32, device="cuda")
+    ws = workspace(ap.ap_decode_workspace_bytes(B, H, d, T, r, ap.AP_BF16))
+    print("grouped queries 32/8 heads, 64 sequences at T=4224", flush=True)
+    ap.ap_decode_step(q, kn, vn, Ck, Cv, Bk, Bv, out, ws, T=T, sm_scale=1.0 / math.sqrt(d))
+    torch.cuda.synchronize()
+    for b in SAMPLE:
+        ref = oracle.decode_attn_absorbed(P(q[b]), P(Ck[b, :T]), P(Cv[b, :T]), P(Bk[b]), P(Bv[b]), kv_heads=Hkv)
+        assert_close(to_host64(out[b]), ref, "bf16", f"grouped queries, b={b}")
+        c_ref = oracle.compact(P(kn[b])[None, :], P(Bk[b]))[0]
+        err = np.abs(P(Ck[b, T - 1]) - c_ref)
+        assert (err <= 2.0 ** -7 * np.abs(c_ref) + 1e-5 * np.abs(c_ref).max()).all()
