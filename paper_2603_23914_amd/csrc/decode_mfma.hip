@@ -694,8 +694,13 @@ __device__ __forceinline__ void score_role(const AttnParams& p) {
     if constexpr (I8) {
 #pragma unroll
       for (int tt = 0; tt < 2; ++tt) {
-        int row = cx.gtile(tile) * kTile + 16 * tt + n;
-        row = row < T ? row : T - 1;
+        int row;
+        if (RAGGED) {
+          row = cx.idxb[tile * kTile + 16 * tt + n];
+        } else {
+          row = cx.gtile(tile) * kTile + 16 * tt + n;
+          row = row < T ? row : T - 1;
+        }
         const uint16_t* sp_ = Sk_b + (size_t)row * nsb + (my_nks > 0 ? w : 0);
 #pragma unroll
         for (int i = 0; i < NBW; ++i) {
@@ -707,8 +712,13 @@ __device__ __forceinline__ void score_role(const AttnParams& p) {
       for (int j = 0; j < 2; ++j) {
         const int e = vs_e0 + 256 * j;
         if (e < nsb * kTile) {
-          int row = cx.gtile(tile) * kTile + (e & 31);
-          row = row < T ? row : T - 1;
+          int row;
+          if (RAGGED) {
+            row = cx.idxb[tile * kTile + (e & 31)];
+          } else {
+            row = cx.gtile(tile) * kTile + (e & 31);
+            row = row < T ? row : T - 1;
+          }
           vsr[j] = Sv_b[(size_t)row * nsb + (e >> 5)];
         }
       }
@@ -729,7 +739,7 @@ __device__ __forceinline__ void score_role(const AttnParams& p) {
     } else {
       // gathered rows; k-steps at or beyond the tile's key rank re-read bytes this wave
       // (or, with no k-step left, its neighbours) fetch anyway
-      const int nks_t = uni(cx.meta[4 * tile + 1]) >> 5;
+      const int nks_t = uni(cx.meta[4 * tile + 1]) >> (I8 ? 6 : 5);   // units of 64 bytes
       const uint32_t loff = (uint32_t)((w < nks_t ? w * 64 : 0) + g * 16);
 #pragma unroll
       for (int tt = 0; tt < 2; ++tt) {
@@ -739,6 +749,7 @@ __device__ __forceinline__ void score_role(const AttnParams& p) {
         for (int i = 0; i < NA; ++i)
           A[i][tt] = *(const u32x4_t*)(rp + ((w + 4 * i) < nks_t ? (uint32_t)i * 256u : 0u));
       }
+      load_scales(tile);
     }
   };
   if (cx.ntl > 0) load_A(0);
@@ -750,7 +761,7 @@ __device__ __forceinline__ void score_role(const AttnParams& p) {
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) { f32x4_t z = {0.f, 0.f, 0.f, 0.f}; sp[mt][0] = z; sp[mt][1] = z; }
     if (RAGGED) {                                         // columns beyond the key rank count as zero
-      const int nks_t = uni(cx.meta[4 * t + 1]) >> 5;
+      const int nks_t = uni(cx.meta[4 * t + 1]) >> (I8 ? 6 : 5);
 #pragma unroll
       for (int i = 0; i < NA; ++i)
         if ((w + 4 * i) >= nks_t) { u32x4_t z = {0, 0, 0, 0}; A[i][0] = z; A[i][1] = z; }
@@ -834,7 +845,7 @@ __device__ __forceinline__ void sum_role(const AttnParams& p) {
     const int slot0 = 2 * (lt % RT);
     if (RAGGED) {
       // gathered rows; chunks at or beyond the tile's value rank re-read the row's first chunk
-      const uint32_t rv8 = (uint32_t)uni(cx.meta[4 * lt + 2]) >> 3;
+      const uint32_t rv8 = (uint32_t)uni(cx.meta[4 * lt + 2]) >> (I8 ? 4 : 3);   // 16-byte chunks
 #pragma nounroll
       for (int half = 0; half < 2; ++half) {
         char* dst = cx.ring + (slot0 + half) * cx.unit_bytes;
@@ -925,8 +936,8 @@ __device__ __forceinline__ void sum_role(const AttnParams& p) {
     const char* vB = vA + cx.unit_bytes;
     if constexpr (I8) {
       if (!(cx.dbg & 2))
-        wsum_tile_i8<MT, NGRP>(vA, vB, cx.pitch, r, cp, g, cx.vsb + (t & 1) * (r >> 6) * kTile, Phi,
-                               alpha, U);
+        wsum_tile_i8<MT, NGRP>(vA, vB, cx.pitch, RAGGED ? uni(cx.meta[4 * t + 2]) : r, cp, g,
+                               cx.vsb + (t & 1) * (r >> 6) * kTile, Phi, alpha, U);
     } else {
       if (!(cx.dbg & 2))
         wsum_tile<Tag, MT, SPLIT, NGRP>(vA, vB, cx.pitch,
@@ -1121,6 +1132,10 @@ ap_status dispatch_attn(const AttnParams& p, int B, hipStream_t stream) {
       switch (nw) {
 #define AP_CASE8(NWV)                                                                     \
   case NWV:                                                                               \
+    if (p.bucket_idx)                                                                     \
+      return p.r <= 256   ? launch_attn<Tag, NWV, 256, false, true, true>(p, B, stream)   \
+             : p.r <= 512 ? launch_attn<Tag, NWV, 512, false, true, true>(p, B, stream)   \
+                          : launch_attn<Tag, NWV, 640, false, true, true>(p, B, stream);  \
     return p.r <= 256   ? launch_attn<Tag, NWV, 256, false, false, true>(p, B, stream)    \
            : p.r <= 512 ? launch_attn<Tag, NWV, 512, false, false, true>(p, B, stream)    \
                         : launch_attn<Tag, NWV, 640, false, false, true>(p, B, stream);
@@ -1246,8 +1261,6 @@ ap_status launch_decode_mfma(const DecodeArgs& a) {
   AP_REQUIRE(a.B <= 65535, AP_ERR_UNSUPPORTED, "ap_decode_attn: B must be <= 65535");
   AP_REQUIRE(basis_rows_applies(a.H_kv * a.d, a.B), AP_ERR_UNSUPPORTED,
              "ap_decode_attn: H*d must be a multiple of 8 and <= 8192");
-  AP_REQUIRE(a.dt_coef != AP_I8 || (!a.rank_k && !a.rank_v), AP_ERR_UNSUPPORTED,
-             "ap_decode_attn: int8 coefficients with per-token ranks are not implemented");
   AP_REQUIRE((int64_t)a.T_cap * a.r * 2 < (1ll << 32), AP_ERR_UNSUPPORTED,
              "ap_decode_attn: one sequence's coefficients must stay below 4 GiB");
   return a.dt == AP_F16 ? run_decode<F16Tag, false>(a) : run_decode<BF16Tag, true>(a);

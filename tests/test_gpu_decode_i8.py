@@ -104,3 +104,46 @@ def test_config5_decode_full_size():
     ref = np.stack([ref[b] for b in range(B)])
     rel = assert_close(got, ref, "f16", "config 5 decode")
     print(f"  max|err|/||out||inf = {rel:.2e}", flush=True)
+
+
+@pytest.mark.parametrize("B,H,d,r,T,granks,cum,den,use_k,use_v", [
+    (2, 32, 128, 512, 333, (512, 256, 128, 64), (1, 2, 3, 4), 4, True, True),
+    (1, 40, 128, 640, 301, (640, 320, 64), (1, 3, 8), 8, True, True),
+    (2, 16, 64, 192, 200, (192, 128, 64), (0, 1, 2), 2, False, True),     # values only, empty first group
+    (1, 8, 128, 256, 20, (256, 64), (1, 2), 2, True, False),              # keys only, fewer tokens than a tile
+])
+def test_decode_i8_with_per_token_ranks(B, H, d, r, T, granks, cum, den, use_k, use_v):
+    """int8 coefficients read at attention-chosen ranks (multiples of the 64-column scale block)."""
+    from paper_2603_23914_amd import binding as ap
+    case = wl.decode_case("f16", B, H, d, r, T, steps=0, seed=18, append=False)
+    q = wl.step_query(case, 0)
+    Ck8, sk, Cv8, sv = quantize_case(case, T)
+    mass = wl.rng_for(18, T, r).random((B, T)).astype(np.float32)
+    F = len(granks)
+    dm = torch.from_numpy(mass).cuda()
+    rank = torch.empty((B, T), dtype=torch.int32, device="cuda")
+    off = torch.empty((B, F + 1), dtype=torch.int32, device="cuda")
+    idx = torch.empty((B, T), dtype=torch.int32, device="cuda")
+    ap.ap_select_ranks(dm, granks, cum, den, rank, off, idx, workspace(ap.ap_select_workspace_bytes(B, T, F)))
+    dq, dBk, dBv = (to_dev(x, "f16") for x in (q, case.Bk, case.Bv))
+    dCk, dCv = torch.from_numpy(Ck8).cuda(), torch.from_numpy(Cv8).cuda()
+    dsk, dsv = torch.from_numpy(sk).cuda(), torch.from_numpy(sv).cuda()
+    out = torch.empty((B, H, d), dtype=torch.float32, device="cuda")
+    ws = workspace(ap.ap_decode_workspace_bytes(B, H, d, T, r, ap.AP_F16))
+    print(f"int8 ragged B={B} H={H} d={d} r={r} T={T} F={F}", flush=True)
+    ap.ap_decode_attn(dq, dCk, dCv, dBk, dBv, out, ws, T=T, sm_scale=1.0 / math.sqrt(d), scale_k=dsk,
+                      scale_v=dsv, rank_k=rank if use_k else None, rank_v=rank if use_v else None,
+                      bucket_off=off, bucket_idx=idx, F=F)
+    torch.cuda.synchronize()
+    rank_np = rank.cpu().numpy()
+    ref = np.empty((B, H, d))
+    for b in range(B):
+        r_ref, _, _ = oracle.select_ranks(mass[b], granks, cum, den)
+        assert (rank_np[b] == r_ref).all()
+        ck = oracle.dequantize_i8(Ck8[b, :T], sk[b, :T])
+        cv = oracle.dequantize_i8(Cv8[b, :T], sv[b, :T])
+        ref[b] = oracle.decode_attn_absorbed(q[b].astype(np.float64), ck, cv, case.Bk[b].astype(np.float64),
+                                             case.Bv[b].astype(np.float64),
+                                             rank_k=rank_np[b] if use_k else None,
+                                             rank_v=rank_np[b] if use_v else None)
+    assert_close(to_host64(out), ref, "f16", "int8 with per-token ranks")
