@@ -5,15 +5,18 @@
 // and cut at fixed sorted positions into F groups.  Nothing is sorted: a group boundary at
 // sorted position p is fully described by the p-th largest key kappa and by how many of the
 // tokens whose key equals kappa still fall in front of it (the quota), so
-//   1. an 8-bit-digit radix select finds (kappa, quota) of all F-1 boundaries at once
-//      (four passes over the row, histograms in LDS);
+//   1. a radix select finds (kappa, quota) of all F-1 boundaries at once (four passes over
+//      the row with digits of 12, 8, 8 and 4 bits, histograms in LDS);
 //   2. every thread owns a contiguous run of tokens; block-wide prefix sums of "key == kappa"
 //      give each token its position among equal keys, which decides its group;
 //   3. block-wide prefix sums of the group counts give each token its slot in its group's
 //      ascending index list.
 // One workgroup of 1024 threads per batch row; rows of up to 32768 tokens are first copied to
-// LDS as sort keys, so the four radix passes and the two walks read LDS, not memory.  All
-// integer work, results are unique.
+// LDS as sort keys, so the four radix passes and the two walks read LDS, not memory.  The LDS
+// copy skips one word after every 32 tokens: a thread's contiguous run of tokens then starts
+// in a different bank than its neighbours' and the walks are free of bank conflicts.  Group
+// ids replace the keys in that copy once they are known, and the ranks leave in a coalesced
+// pass.  All integer work, results are unique.
 #include "ap_common.hpp"
 
 namespace ap {
@@ -41,24 +44,6 @@ __device__ __forceinline__ uint32_t key_of(float m) {
   return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
-// Histogram increment with same-digit lanes of a wave combined (importance values share
-// their leading bits, so the first passes would otherwise serialise on a few counters).
-// Every lane of the wave must call this; d == kNone means "nothing to count".
-__device__ __forceinline__ void hist_add(uint32_t* h, uint32_t d) {
-  const int lane = threadIdx.x & 63;
-#pragma unroll 1
-  for (int it = 0; it < 4; ++it) {
-    const unsigned long long act = __ballot(d != kNone);
-    if (act == 0ull) return;
-    const int leader = __ffsll((long long)act) - 1;
-    const uint32_t dl = (uint32_t)__shfl((int)d, leader);
-    const unsigned long long same = __ballot(d == dl);
-    if (lane == leader) atomicAdd(&h[dl], (uint32_t)__popcll(same));
-    if (d == dl) d = kNone;
-  }
-  if (d != kNone) atomicAdd(&h[d], 1u);
-}
-
 // Exclusive prefix sum of one int per thread over the workgroup (thread order); *total
 // receives the workgroup sum.  wave_tot: kWaves ints of LDS.  Two barriers.
 __device__ __forceinline__ int block_excl_scan(int v, int* wave_tot, int* total) {
@@ -83,23 +68,71 @@ __device__ __forceinline__ int block_excl_scan(int v, int* wave_tot, int* total)
   return base + incl - v;
 }
 
-constexpr int kStagedMax = 32768;      // tokens whose keys fit the dynamic LDS slice (128 KiB)
+// The same for N values per thread at once (two barriers for all of them).  wave_tot: N * kWaves ints.
+template <int N>
+__device__ __forceinline__ void block_excl_scan_n(int (&v)[N], int* wave_tot) {
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  int incl[N];
+#pragma unroll
+  for (int k = 0; k < N; ++k) incl[k] = v[k];
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+#pragma unroll
+    for (int k = 0; k < N; ++k) {
+      const int up = __shfl_up(incl[k], o);
+      if (lane >= o) incl[k] += up;
+    }
+  }
+  __syncthreads();                       // previous use of wave_tot is over
+  if (lane == 63) {
+#pragma unroll
+    for (int k = 0; k < N; ++k) wave_tot[k * kWaves + w] = incl[k];
+  }
+  __syncthreads();
+#pragma unroll
+  for (int k = 0; k < N; ++k) {
+    int base = 0;
+#pragma unroll
+    for (int i = 0; i < kWaves; ++i) {
+      const int x = wave_tot[k * kWaves + i];
+      if (i < w) base += x;
+    }
+    v[k] = base + incl[k] - v[k];
+  }
+}
+
+constexpr int kStagedMax = 32768;      // tokens whose keys fit the dynamic LDS slice (132 KiB with padding)
 
 template <bool STAGED>
 __global__ void __launch_bounds__(kThreads) select_ranks_kernel(const SelectParams p) {
   extern __shared__ __attribute__((aligned(16))) uint32_t keys_lds[];   // STAGED: [T]
   __shared__ uint32_t hist[kMaxF - 1][256];
+  __shared__ uint32_t hist0[4096];           // first pass: 12-bit digits, shared by all boundaries
+  __shared__ uint32_t mark[128];             // one bit per first digit: some boundary's prefix
   __shared__ uint32_t s_prefix[kMaxF - 1];   // key bits fixed so far (kappa after pass 4)
   __shared__ uint32_t s_need[kMaxF - 1];     // 1-based position still to find (quota after pass 4)
-  __shared__ int wave_tot[kWaves];
+  __shared__ int wave_tot[kMaxF * kWaves];
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int b = blockIdx.x, T = p.T, F = p.F, nb = F - 1;
   const float* m = p.mass + (size_t)b * T;
+  auto slot_of = [](int t) -> int { return t + (t >> 5); };      // one pad word per 32 tokens
   if (STAGED) {
-    for (int t = tid; t < T; t += kThreads) keys_lds[t] = key_of(m[t]);
+    for (int t0 = tid; t0 < T; t0 += 8 * kThreads) {        // eight loads in flight per thread
+      float v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int t = t0 + u * kThreads;
+        v[u] = m[t < T ? t : T - 1];
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int t = t0 + u * kThreads;
+        if (t < T) keys_lds[slot_of(t)] = key_of(v[u]);
+      }
+    }
     __syncthreads();
   }
-  auto key_at = [&](int t) -> uint32_t { return STAGED ? keys_lds[t] : key_of(m[t]); };
+  auto key_at = [&](int t) -> uint32_t { return STAGED ? keys_lds[slot_of(t)] : key_of(m[t]); };
 
   // a cut at 0 or at T needs no threshold search
   bool active[kMaxF - 1];
@@ -113,42 +146,54 @@ __global__ void __launch_bounds__(kThreads) select_ranks_kernel(const SelectPara
     s_need[tid] = need;
   }
 
-  // ---- 1. radix select, most significant digit first
+  // ---- 1. radix select, most significant digit first: digits of 12, 8, 8 and 4 bits.  The
+  //      first digit is wide (sign, exponent and three mantissa bits) because importance values
+  //      share their leading bits: with an 8-bit digit most lanes of a wave would hit the same
+  //      counter and the LDS would serialise them.  Every boundary shares the empty prefix in
+  //      the first pass (one histogram); later passes count only keys that match a boundary's
+  //      prefix, which are few.
 #pragma unroll 1
   for (int pass = 0; pass < 4; ++pass) {
-    const int shift = 24 - 8 * pass;
-    for (int i = tid; i < (kMaxF - 1) * 256; i += kThreads) (&hist[0][0])[i] = 0u;
+    const int shift = pass == 0 ? 20 : (pass == 1 ? 12 : (pass == 2 ? 4 : 0));
+    const int width = pass == 0 ? 12 : (pass == 3 ? 4 : 8);
+    const uint32_t dmask = (1u << width) - 1u;
+    if (pass == 0) {
+      for (int i = tid; i < 4096; i += kThreads) hist0[i] = 0u;
+      if (tid < 128) mark[tid] = 0u;
+    } else {
+      for (int i = tid; i < (kMaxF - 1) * 256; i += kThreads) (&hist[0][0])[i] = 0u;
+    }
     __syncthreads();
     uint32_t pre[kMaxF - 1];
 #pragma unroll
     for (int g = 0; g < kMaxF - 1; ++g) pre[g] = s_prefix[g];
-    const int Tpad = (T + 63) & ~63;     // whole waves stay in the loop (hist_add uses ballots)
-    for (int t = tid; t < Tpad; t += kThreads) {
-      const bool in = t < T;
-      const uint32_t key = in ? key_at(t) : 0u;
-      const uint32_t dig = (key >> shift) & 255u;
+    for (int t = tid; t < T; t += kThreads) {
+      const uint32_t key = key_at(t);
+      const uint32_t dig = (key >> shift) & dmask;
       if (pass == 0) {
-        hist_add(hist[0], in ? dig : kNone);       // every boundary shares the empty prefix
-      } else {
-        // few keys still match a boundary's prefix: plain atomics
-        const uint32_t hi = key >> (shift + 8);
+        atomicAdd(&hist0[dig], 1u);
+      } else if ((mark[key >> 25] >> ((key >> 20) & 31u)) & 1u) {
+        // one key in hundreds shares its first digit with a boundary; the rest stop here
+        const uint32_t hi = key >> (shift + width);
 #pragma unroll
         for (int g = 0; g < kMaxF - 1; ++g) {
-          if (active[g] && in && hi == (pre[g] >> (shift + 8))) atomicAdd(&hist[g][dig], 1u);
+          if (active[g] && hi == (pre[g] >> (shift + width))) atomicAdd(&hist[g][dig], 1u);
         }
       }
     }
     __syncthreads();
-    // wave g walks boundary g's histogram from the top: lane l owns digits 4l .. 4l+3
+    // wave g walks boundary g's histogram from the top: lane l owns `per` consecutive digits
     bool act_w = false;
 #pragma unroll
     for (int g = 0; g < kMaxF - 1; ++g) act_w = act_w || (w == g && active[g]);
     if (act_w) {
-      const uint32_t* h = hist[pass == 0 ? 0 : w];
-      uint32_t c[4];
-#pragma unroll
-      for (int j = 0; j < 4; ++j) c[j] = h[4 * lane + j];
-      const uint32_t tot = c[0] + c[1] + c[2] + c[3];
+      const uint32_t* h = pass == 0 ? hist0 : hist[w];
+      const int nbins = 1 << width;
+      const int per = nbins >= 64 ? nbins >> 6 : 1;
+      const int d0 = lane * per;
+      uint32_t tot = 0;
+      if (d0 < nbins)
+        for (int j = 0; j < per; ++j) tot += h[d0 + j];
       uint32_t incl = tot;               // sum over lanes >= lane
 #pragma unroll
       for (int o = 1; o < 64; o <<= 1) {
@@ -159,16 +204,14 @@ __global__ void __launch_bounds__(kThreads) select_ranks_kernel(const SelectPara
       const uint32_t k = s_need[w];
       if (above < k && k <= incl) {      // exactly one lane
         uint32_t acc = above, digit = 0, left = k;
-        bool found = false;
-#pragma unroll
-        for (int j = 3; j >= 0; --j) {
-          if (!found) {
-            if (k <= acc + c[j]) { digit = 4 * lane + j; left = k - acc; found = true; }
-            else acc += c[j];
-          }
+        for (int j = per - 1; j >= 0; --j) {
+          const uint32_t c = h[d0 + j];
+          if (k <= acc + c) { digit = (uint32_t)(d0 + j); left = k - acc; break; }
+          acc += c;
         }
         s_prefix[w] = s_prefix[w] | (digit << shift);
         s_need[w] = left;
+        if (pass == 0) atomicOr(&mark[digit >> 5], 1u << (digit & 31u));
       }
     }
     __syncthreads();
@@ -195,10 +238,7 @@ __global__ void __launch_bounds__(kThreads) select_ranks_kernel(const SelectPara
 #pragma unroll
     for (int g = 0; g < kMaxF - 1; ++g) eq[g] += (key == kappa[g]) ? 1 : 0;
   }
-  int dummy;
-#pragma unroll
-  for (int g = 0; g < kMaxF - 1; ++g)
-    if (g < nb) eq[g] = block_excl_scan(eq[g], wave_tot, &dummy);   // now: equal keys before t0
+  block_excl_scan_n<kMaxF - 1>(eq, wave_tot);               // now: equal keys before t0
   int cnt[kMaxF];
 #pragma unroll
   for (int g = 0; g < kMaxF; ++g) cnt[g] = 0;
@@ -213,25 +253,34 @@ __global__ void __launch_bounds__(kThreads) select_ranks_kernel(const SelectPara
       if (g < nb && in_front) grp = g;                      // membership is nested: keep the smallest
       eq[g] += same ? 1 : 0;
     }
-    rank_row[t] = grp;                                      // group id for now, rank below
+    if (STAGED) keys_lds[slot_of(t)] = (uint32_t)grp;       // the key is not needed again
+    else rank_row[t] = grp;                                 // group id for now, rank below
 #pragma unroll
     for (int g = 0; g < kMaxF; ++g) cnt[g] += (grp == g) ? 1 : 0;
   }
 
   // ---- 3. slot inside the group's ascending index list
-#pragma unroll
-  for (int g = 0; g < kMaxF; ++g)
-    if (g < F) cnt[g] = block_excl_scan(cnt[g], wave_tot, &dummy);
+  block_excl_scan_n<kMaxF>(cnt, wave_tot);
   int32_t* idx_row = p.bucket_idx + (size_t)b * T;
   for (int t = t0; t < t1; ++t) {
-    const int grp = rank_row[t];
+    const int grp = STAGED ? (int)keys_lds[slot_of(t)] : rank_row[t];
     int slot = 0, rk = 0;
 #pragma unroll
     for (int g = 0; g < kMaxF; ++g) {
       if (grp == g) { slot = p.bound[g] + cnt[g]; rk = p.grank[g]; cnt[g] += 1; }
     }
-    rank_row[t] = rk;
+    if (!STAGED) rank_row[t] = rk;
     if (slot < T) idx_row[slot] = t;    // always true; keeps a logic error inside the buffer
+  }
+  if (STAGED) {                         // ranks out, consecutive threads to consecutive tokens
+    __syncthreads();
+    for (int t = tid; t < T; t += kThreads) {
+      const int grp = (int)keys_lds[slot_of(t)];
+      int rk = 0;
+#pragma unroll
+      for (int g = 0; g < kMaxF; ++g) rk = grp == g ? p.grank[g] : rk;
+      rank_row[t] = rk;
+    }
   }
   int cut = 0;
 #pragma unroll
@@ -297,14 +346,16 @@ ap_status launch_select_ranks(const float* mass, int B, int T, int F, const int3
     static bool attr_set = false;
     if (!attr_set) {
       hipError_t e = hipFuncSetAttribute((const void*)select_ranks_kernel<true>,
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, kStagedMax * 4);
+                                         hipFuncAttributeMaxDynamicSharedMemorySize,
+                                         (kStagedMax + kStagedMax / 32 + 1) * 4);
       if (e != hipSuccess) {
         set_error("hipFuncSetAttribute: %s", hipGetErrorString(e));
         return AP_ERR_HIP;
       }
       attr_set = true;
     }
-    hipLaunchKernelGGL(select_ranks_kernel<true>, dim3(B), dim3(kThreads), (size_t)T * 4, stream, p);
+    hipLaunchKernelGGL(select_ranks_kernel<true>, dim3(B), dim3(kThreads), ((size_t)T + T / 32 + 1) * 4,
+                       stream, p);
   } else {
     hipLaunchKernelGGL(select_ranks_kernel<false>, dim3(B), dim3(kThreads), 0, stream, p);
   }
