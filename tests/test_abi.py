@@ -4,6 +4,8 @@ import ctypes
 import os
 import re
 
+import torch  # noqa: F401  (first: its HIP runtime must be the one the library binds to)
+
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 LIB = os.path.join(ROOT, "paper_2603_23914_amd", "libattnpack.so")
 
