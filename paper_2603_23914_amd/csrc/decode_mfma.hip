@@ -396,8 +396,13 @@ __device__ __forceinline__ void wg_coords(int nsplit, int xcd_aware, int& b, int
 // tile's (token count, key rank, value rank) into LDS; the row loads then gather through
 // that table.  Columns at or beyond a tile's rank are neither fetched from HBM (their loads
 // are redirected to bytes the wave fetches anyway) nor allowed into the products.
-template <class Tag, int MT, bool SPLIT, bool RAGGED, bool I8>
+// Token-split mode (TS, ranks up to 128): the four score waves each own every fourth TILE and
+// all of the rank axis, instead of a quarter of the rank axis of every tile.  A score wave's
+// tile is then complete without the other waves' partial sums, and one pair of barriers covers
+// four tiles: at small ranks the tile loop is bound by that dependency chain, not by memory.
+template <class Tag, int MT, bool SPLIT, bool RAGGED, bool I8, bool TS = false>
 struct WaveCtx {
+  static constexpr int NSUB = TS ? 4 : 1;   // tiles per barrier pair
   static constexpr int HPW = 2 * MT;     // heads finalised per wave
   static constexpr int EB = I8 ? 1 : 2;  // bytes per stored coefficient
 
@@ -444,9 +449,9 @@ struct WaveCtx {
     ring = smem;
     xchg = (f32x4_t*)(smem + nh * unit_bytes);
     Pbuf = (u32x4_t*)(xchg + 4 * 16 * MT * 9);
-    abuf = (float*)(Pbuf + MT * 2 * 64);
+    abuf = (float*)(Pbuf + NSUB * MT * 2 * 64);
     row_bytes = (uint32_t)(r * EB);
-    vsb = (uint16_t*)(abuf + 16 * MT);
+    vsb = (uint16_t*)(abuf + NSUB * 16 * MT);
     if (!RAGGED) {
       const int ntiles = (T + kTile - 1) / kTile;
       t_lo = (int)(((int64_t)s * ntiles) / nsplit);
@@ -519,6 +524,7 @@ struct WaveCtx {
 
   // Tokens of local tile t that exist (the rest of the 32 slots is masked out of the softmax).
   __device__ __forceinline__ int tile_valid(int t) const {
+    if (TS && t >= ntl) return 0;        // a slot of the last round without a tile
     if (RAGGED) return uni(meta[4 * t]);
     const int left = T - gtile(t) * kTile;
     return left < kTile ? left : kTile;
@@ -526,19 +532,26 @@ struct WaveCtx {
 
   // Slot of the deferred newest token in local tile t (outside [0, 32): not in this tile).
   __device__ __forceinline__ int tile_new(int t) const {
-    if (RAGGED || Tv == T) return -1;
+    if (RAGGED || Tv == T || (TS && t >= ntl)) return -1;
     return T - 1 - gtile(t) * kTile;
   }
 
   // Softmax of this wave's heads for a tile whose first `valid` slots hold tokens (after
   // the score waves' partial tiles are in xchg).  newl: slot of the deferred token, if any:
   // its weight counts in the sum, is exported, and stays out of the value products.
-  __device__ __forceinline__ void finalize_softmax(int valid, int newl, int t) {
+  // sub: which of the NSUB tiles of this barrier pair (its scores sit in slot `sub` of xchg,
+  // its weights go to slot `sub` of Pbuf / abuf).
+  __device__ __forceinline__ void finalize_softmax(int valid, int newl, int t, int sub = 0) {
     if (!owner) return;
     const int xi = o_hh * 9 + (lane & 7);
-    f32x4_t sc = xchg[xi];
+    f32x4_t sc;
+    if (TS) {
+      sc = xchg[sub * 16 * MT * 9 + xi];          // complete: one wave scored the whole rank axis
+    } else {
+      sc = xchg[xi];
 #pragma unroll
-    for (int sw = 1; sw < 4; ++sw) sc += xchg[sw * 16 * MT * 9 + xi];
+      for (int sw = 1; sw < 4; ++sw) sc += xchg[sw * 16 * MT * 9 + xi];
+    }
     if (scores && o_hh < H) {                   // logits out, for importance tracking
       const int slot = 16 * o_tt + 4 * o_gg;
 #pragma unroll
@@ -590,10 +603,10 @@ struct WaveCtx {
     l_part += (k0 + k1) + (k2 + k3) + pdef;     // the sum uses the values the MFMA will see
     // weights in B-operand layout: lane (n, g) of head tile mt holds tokens 4g..4g+3
     // (dwords 0,1) and 16+4g..+3 (dwords 2,3)
-    u32x2_t* ph = (u32x2_t*)(Pbuf + (o_mt * 2 + 0) * 64 + o_lane) + o_tt;
+    u32x2_t* ph = (u32x2_t*)(Pbuf + ((sub * MT + o_mt) * 2 + 0) * 64 + o_lane) + o_tt;
     *ph = hi;
-    if (SPLIT) *(ph + 2 * 64) = lo;             // [o_mt][1][o_lane]
-    if ((lane & 7) == 0) abuf[o_hh] = alpha;
+    if (SPLIT) *(ph + 2 * 64) = lo;             // [sub][o_mt][1][o_lane]
+    if ((lane & 7) == 0) abuf[sub * 16 * MT + o_hh] = alpha;
   }
 
   // (reference exponent, sum) of the heads this wave finalised.
@@ -637,18 +650,21 @@ template <class Tag, int MT, int RMAX, bool SPLIT, bool RAGGED, bool I8>
 __device__ __forceinline__ void score_role(const AttnParams& p) {
   // a score wave owns "units" w, w+4, ... of the rank axis, 64 bytes of a row each:
   // 32-column k-steps for 16-bit storage, 64-column scale blocks (two k-steps) for int8
+  constexpr bool TS = !RAGGED && !I8 && RMAX == 128;      // token-split mode (see WaveCtx)
   constexpr int NBW = (RMAX / 64 + 3) / 4;                // int8: scale blocks per score wave
-  constexpr int NKW = I8 ? 2 * NBW : (RMAX / 32 + 3) / 4; // score k-steps per score wave
+  constexpr int NKW = TS ? RMAX / 32 : (I8 ? 2 * NBW : (RMAX / 32 + 3) / 4);   // score k-steps per score wave
   constexpr int NA = I8 ? NBW : NKW;                      // 16-byte row loads per 16-row half
   constexpr int Hp = MT * 16;
   AP_T_ENTRY
-  WaveCtx<Tag, MT, SPLIT, RAGGED, I8> cx;
+  WaveCtx<Tag, MT, SPLIT, RAGGED, I8, TS> cx;
   cx.init(p);
   float* part_U = uni_ptr(p.part_U);
   float* part_ml = uni_ptr(p.part_ml);
   const int w = cx.w, n = cx.n, g = cx.g, r = cx.r, T = cx.T;
   const int nks = I8 ? r >> 6 : r >> 5;                   // all units
-  const int my_nks = nks > w ? (nks - w + 3) >> 2 : 0;    // units w, w+4, ...
+  // units of this wave: w, w+4, ... of every tile, or (token-split) all units of its tiles
+  const int my_nks = TS ? nks : (nks > w ? (nks - w + 3) >> 2 : 0);
+  const int ustep = TS ? 1 : 4, ufirst = TS ? 0 : w;      // unit index = ufirst + ustep * i
   // q' operands (B operand of the score MFMA): lane (h=n, g) holds columns 32ks+8g..+7
   // (int8: columns 64m+16g..+7 for a block's first k-step, 64m+16g+8..+15 for its second)
   const uint16_t* Qp = uni_ptr(p.Qp);
@@ -663,7 +679,7 @@ __device__ __forceinline__ void score_role(const AttnParams& p) {
       if (SPLIT) qlo[i][mt] = z;
       const int unit = I8 ? i >> 1 : i;
       if (unit < my_nks) {
-        const int col = I8 ? (w + 4 * unit) * 64 + g * 16 + (i & 1) * 8 : (w + 4 * i) * 32 + g * 8;
+        const int col = I8 ? (w + 4 * unit) * 64 + g * 16 + (i & 1) * 8 : (ufirst + ustep * i) * 32 + g * 8;
         const uint16_t* qrow = Qp + (((size_t)cx.b * 2) * Hp + (mt * 16 + n)) * r + col;
         qhi[i][mt] = *(const u32x4_t*)qrow;
         if (SPLIT) qlo[i][mt] = *(const u32x4_t*)(qrow + (size_t)Hp * r);
@@ -674,13 +690,13 @@ __device__ __forceinline__ void score_role(const AttnParams& p) {
   const char* Ck_b = (const char*)uni_ptr(p.Ck) + (size_t)cx.b * uni(p.T_cap) * cx.row_bytes;
   // units this wave does not own re-read its first chunk (finite data times zero q'):
   // the loads carry no branches, so they issue back to back without waits between them
-  const uint32_t lane_off = (uint32_t)((my_nks > 0 ? w * 64 : 0) + g * 16);
+  const uint32_t lane_off = (uint32_t)((my_nks > 0 ? ufirst * 64 : 0) + g * 16);
   u32x4_t A[NA][2];
 #pragma unroll
   for (int i = 0; i < NA; ++i) { u32x4_t z = {0, 0, 0, 0}; A[i][0] = z; A[i][1] = z; }
   uint32_t koff[NA];
 #pragma unroll
-  for (int i = 0; i < NA; ++i) koff[i] = i < my_nks ? (uint32_t)i * 256u : 0u;
+  for (int i = 0; i < NA; ++i) koff[i] = i < my_nks ? (uint32_t)(i * ustep) * 64u : 0u;
   // int8: the key scale of the lane's row for every owned block (both halves of a packed
   // pair), and this wave's share of the tile's value scales, which the score waves pass to
   // the sum waves through LDS as [scale block][32 tokens]
@@ -752,6 +768,38 @@ __device__ __forceinline__ void score_role(const AttnParams& p) {
       load_scales(tile);
     }
   };
+  if constexpr (TS) {
+    // ---- token-split: this wave scores tiles w, w + 4, ... completely; four tiles per round
+    const int rounds = (cx.ntl + 3) >> 2;
+    if (w < cx.ntl) load_A(w);
+    AP_T_START
+    for (int it = 0; it < rounds; ++it) {
+      const int lt = 4 * it + w;
+      f32x4_t sp[MT][2];
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) { f32x4_t z = {0.f, 0.f, 0.f, 0.f}; sp[mt][0] = z; sp[mt][1] = z; }
+      score_tile<Tag, MT, SPLIT, NKW>(A, qhi, qlo, sp);     // a slot without a tile: masked below
+      AP_TICK(1)
+      if (lt + 4 < cx.ntl) load_A(lt + 4);                  // lands while the round is finished
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) {
+        cx.xchg[(w * 16 * MT + mt * 16 + n) * 9 + g] = sp[mt][0];
+        cx.xchg[(w * 16 * MT + mt * 16 + n) * 9 + 4 + g] = sp[mt][1];
+      }
+      wg_barrier();                                         // scores of the round's tiles ready
+      AP_TICK(2)
+#pragma unroll
+      for (int sub = 0; sub < 4; ++sub)
+        cx.finalize_softmax(cx.tile_valid(4 * it + sub), cx.tile_new(4 * it + sub), 4 * it + sub, sub);
+      AP_TICK(3)
+      wg_barrier();                                         // weights of the round's tiles ready
+      AP_TICK(4)
+    }
+    cx.store_ml(part_ml);
+    AP_TICK(6)
+    AP_T_REPORT
+    return;
+  }
   if (cx.ntl > 0) load_A(0);
 
   AP_T_START
@@ -798,13 +846,14 @@ __device__ __forceinline__ void score_role(const AttnParams& p) {
 
 template <class Tag, int MT, int RMAX, bool SPLIT, bool RAGGED, bool I8>
 __device__ __forceinline__ void sum_role(const AttnParams& p) {
+  constexpr bool TS = !RAGGED && !I8 && RMAX == 128;              // token-split mode (see WaveCtx)
   constexpr int EB = I8 ? 1 : 2;
   constexpr int NGRP = (RMAX * EB + 255) / 256;                   // 256-byte column groups
   constexpr int NJ = I8 ? 4 : 2;                                  // columns per LDS dword
   constexpr int MAXBLK = (kHalf * (RMAX * EB / 16 + 1) + 63) / 64;  // 1 KiB blocks per ring unit
   constexpr int NSLOT = (MAXBLK + 3) / 4;
   AP_T_ENTRY
-  WaveCtx<Tag, MT, SPLIT, RAGGED, I8> cx;
+  WaveCtx<Tag, MT, SPLIT, RAGGED, I8, TS> cx;
   cx.init(p);
   float* part_U = uni_ptr(p.part_U);
   float* part_ml = uni_ptr(p.part_ml);
@@ -901,6 +950,56 @@ __device__ __forceinline__ void sum_role(const AttnParams& p) {
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) { f32x4_t z = {0.f, 0.f, 0.f, 0.f}; U[i][j][mt] = z; }
   AP_T_START
+  if constexpr (TS) {
+    // ---- token-split: four tiles per round (the host sizes the ring for at least eight)
+    const int rounds = (cx.ntl + 3) >> 2;
+    for (int it = 0; it < rounds; ++it) {
+      wg_barrier();          // scores of this round ready; every sum wave is past the last round
+      AP_TICK(2)
+      // tiles requested so far: 0 (before the loop), then up to 4 it + RT - 1
+      if (it == 0) {
+#pragma nounroll
+        for (int lt = 1; lt < RT && lt < cx.ntl; ++lt) issue_tile(lt);
+      } else {
+#pragma nounroll
+        for (int lt = 4 * it + RT - 4; lt < 4 * it + RT && lt < cx.ntl; ++lt) issue_tile(lt);   // refill the last round's slots
+      }
+#pragma unroll
+      for (int sub = 0; sub < 4; ++sub)
+        cx.finalize_softmax(cx.tile_valid(4 * it + sub), cx.tile_new(4 * it + sub), 4 * it + sub, sub);
+      AP_TICK(3)
+      {
+        // this round's tiles must have landed; those requested beyond it may stay in flight
+        int upto = 4 * it + RT;
+        upto = upto < cx.ntl ? upto : cx.ntl;
+        int need = 4 * it + 4;
+        need = need < cx.ntl ? need : cx.ntl;
+        wait_vmcnt((upto - need) * 2 * n_issue);
+      }
+      wg_barrier();          // weights of this round ready; its rows visible to every wave
+      AP_TICK(4)
+#pragma unroll
+      for (int sub = 0; sub < 4; ++sub) {
+        const int t = 4 * it + sub;
+        if (t < cx.ntl) {
+          u32x4_t Phi[MT], Plo[MT];
+          float alpha[MT];
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt) {
+            alpha[mt] = cx.abuf[sub * 16 * MT + mt * 16 + n];
+            Phi[mt] = cx.Pbuf[((sub * MT + mt) * 2 + 0) * 64 + lane];
+            if (SPLIT) Plo[mt] = cx.Pbuf[((sub * MT + mt) * 2 + 1) * 64 + lane];
+            else { u32x4_t z = {0, 0, 0, 0}; Plo[mt] = z; }
+          }
+          const int slot0 = 2 * (t % RT);
+          const char* vA = cx.ring + slot0 * cx.unit_bytes + (4 * g) * cx.pitch + cp * 64 + n * 4;
+          const char* vB = vA + cx.unit_bytes;
+          wsum_tile<Tag, MT, SPLIT, NGRP>(vA, vB, cx.pitch, r - cp * 32, n, Phi, Plo, alpha, U);
+        }
+      }
+      AP_TICK(5)
+    }
+  } else {
   for (int t = 0; t < cx.ntl; ++t) {
     AP_T_STAMP(t)
     wg_barrier();            // partial scores of tile t ready; every sum wave is past tile t-1
@@ -945,6 +1044,7 @@ __device__ __forceinline__ void sum_role(const AttnParams& p) {
                                         alpha, U);
     }
     AP_TICK(5)
+  }
   }
   // U of this split, straight from the accumulators.  U[i][j][mt][e] is element (head 16mt+n,
   // column 128i + 32cp + 8g + 2e + j) (int8: column 256i + 64cp + 16g + 4e + j): a lane owns
@@ -1091,7 +1191,9 @@ template <class Tag, int MT, int RMAX, bool SPLIT, bool RAGGED, bool I8>
 ap_status launch_attn(AttnParams p, int B, hipStream_t stream) {
   const int cpr = p.r * (I8 ? 1 : 2) / 16;
   const size_t unit = (size_t)((kHalf * (cpr + 1) + 63) / 64) * 1024;
-  size_t fixed = (size_t)4 * 16 * MT * 9 * 16 + (size_t)MT * 2 * 64 * 16 + (size_t)MT * 16 * 4;
+  constexpr bool TS = !RAGGED && !I8 && RMAX == 128;
+  constexpr int NSUB = TS ? 4 : 1;
+  size_t fixed = (size_t)4 * 16 * MT * 9 * 16 + (size_t)NSUB * MT * 2 * 64 * 16 + (size_t)NSUB * MT * 16 * 4;
   if (I8) fixed += (size_t)2 * (p.r / 64) * kTile * 2;     // value scales of two tiles
   if (RAGGED) {
     // every group may end in a partial tile; tiles are dealt round-robin to the splits
@@ -1103,8 +1205,15 @@ ap_status launch_attn(AttnParams p, int B, hipStream_t stream) {
   AP_REQUIRE(fixed + 2 * unit <= budget, AP_ERR_UNSUPPORTED,
              "ap_decode_attn: H=%d r=%d needs more LDS than 160 KiB", p.H, p.r);
   int nh = (int)((budget - fixed) / unit);
-  if (nh > 12) nh = 12;
-  nh &= ~1;
+  if (TS) {
+    // four tiles are consumed per round: a ring of 8 or 12 tiles (16-row units come in pairs)
+    nh = nh >= 24 ? 24 : 16;
+    AP_REQUIRE(fixed + (size_t)nh * unit <= budget, AP_ERR_UNSUPPORTED,
+               "ap_decode_attn: H=%d r=%d needs more LDS than 160 KiB", p.H, p.r);
+  } else {
+    if (nh > 12) nh = 12;
+    nh &= ~1;
+  }
   p.nh = nh;
   size_t lds = (size_t)nh * unit + fixed;
   auto kern = attn_partial<Tag, MT, RMAX, SPLIT, RAGGED, I8>;
@@ -1150,6 +1259,7 @@ ap_status dispatch_attn(const AttnParams& p, int B, hipStream_t stream) {
       return p.r <= 256   ? launch_attn<Tag, NWV, 256, SPLIT, true, false>(p, B, stream)     \
              : p.r <= 512 ? launch_attn<Tag, NWV, 512, SPLIT, true, false>(p, B, stream)     \
                           : launch_attn<Tag, NWV, 640, SPLIT, true, false>(p, B, stream);    \
+    if (p.r <= 128) return launch_attn<Tag, NWV, 128, SPLIT, false, false>(p, B, stream);    \
     return p.r <= 256   ? launch_attn<Tag, NWV, 256, SPLIT, false, false>(p, B, stream)      \
            : p.r <= 512 ? launch_attn<Tag, NWV, 512, SPLIT, false, false>(p, B, stream)      \
                         : launch_attn<Tag, NWV, 640, SPLIT, false, false>(p, B, stream);

@@ -122,3 +122,47 @@ def test_decode_step_equals_compact_then_attend(dtype, B, H, d, r, T0):
     assert_close(res[1][0].astype(np.float64), ref, dtype, "fused step")
     c_ref = oracle.compact(P(kn)[0][None], P(case.Bk)[0])[0]
     assert np.abs(P(Ck_h)[0, T0] - c_ref).max() <= 2.0 ** -7 * np.abs(c_ref).max()
+
+
+@pytest.mark.parametrize("dtype,B,H,d,r,T", [
+    ("bf16", 2, 40, 128, 128, 1000),    # many rounds of four tiles and a ragged tail
+    ("f16", 2, 32, 128, 64, 333),
+    ("bf16", 1, 64, 32, 128, 129),      # four head tiles
+    ("f16", 3, 5, 256, 64, 97),         # fewer tiles than one round
+    ("bf16", 2, 40, 128, 64, 31),       # a single partial tile
+    ("f16", 1, 16, 64, 128, 1),
+    ("bf16", 64, 40, 128, 128, 520),    # every split has tiles in some slots only
+])
+def test_decode_small_rank(dtype, B, H, d, r, T):
+    """Ranks up to 128 run the token-split variant of the kernel (score waves own whole tiles)."""
+    from paper_2603_23914_amd import binding as ap
+    case = wl.decode_case(dtype, B, H, d, r, T, steps=1, seed=27, append=True,
+                          batch_subset=range(min(B, 3)), shared_basis=B > 3)
+    q = wl.step_query(case, 0)
+    nb = min(B, 3)
+    print(f"small rank {dtype} B={B} H={H} d={d} r={r} T={T}", flush=True)
+    got, lse = run_half(dtype, q, case.Ck, case.Cv, case.Bk, case.Bv, T, want_lse=True)
+    Bks = case.Bk if case.Bk.ndim == 2 else case.Bk[:nb]
+    Bvs = case.Bv if case.Bv.ndim == 2 else case.Bv[:nb]
+    ref = oracle_out(dtype, q[:nb], case.Ck[:nb], case.Cv[:nb], Bks, Bvs, T)
+    assert_close(got[:nb], ref, dtype, f"small rank r={r} T={T}")
+    assert np.isfinite(got).all()
+    # fused step with logits out: one more token, all through the same variant
+    P = lambda x: oracle.promote(x, dtype)
+    kn, vn = wl.step_new_token(case, 0, P(case.Bk), P(case.Bv))
+    dq, dCk, dCv, dBk, dBv, dkn, dvn = (to_dev(x, dtype) for x in (q, case.Ck, case.Cv, case.Bk, case.Bv, kn, vn))
+    out = torch.empty((B, H, d), dtype=torch.float32, device="cuda")
+    lse_t = torch.empty((B, H), dtype=torch.float32, device="cuda")
+    scores = torch.full((B, H, case.T_cap), float("nan"), dtype=torch.float32, device="cuda")
+    ws = workspace(ap.ap_decode_workspace_bytes(B, H, d, T + 1, r, ap._DT[TORCH_DT[dtype]]))
+    ap.ap_decode_step(dq, dkn, dvn, dCk, dCv, dBk, dBv, out, ws, T=T + 1, sm_scale=1.0 / math.sqrt(d),
+                      lse=lse_t, scores=scores)
+    torch.cuda.synchronize()
+    Ck_h = dCk.view(torch.int16).cpu().numpy().view(np.uint16) if dtype == "bf16" else dCk.cpu().numpy()
+    Cv_h = dCv.view(torch.int16).cpu().numpy().view(np.uint16) if dtype == "bf16" else dCv.cpu().numpy()
+    ref2 = oracle_out(dtype, q[:nb], Ck_h[:nb], Cv_h[:nb], Bks, Bvs, T + 1)
+    assert_close(to_host64(out[:nb]), ref2, dtype, "small rank fused step")
+    A = np.exp(to_host64(scores[0, :, :T + 1]) - to_host64(lse_t[0])[:, None])
+    Bk0 = P(case.Bk) if case.Bk.ndim == 2 else P(case.Bk)[0]
+    A_ref = oracle.attention_probs(P(q)[0], P(Ck_h)[0, :T + 1], Bk0)
+    assert np.abs(A - A_ref).max() <= 2e-3 * A_ref.max()
