@@ -609,6 +609,80 @@ struct WaveCtx {
     if ((lane & 7) == 0) abuf[sub * 16 * MT + o_hh] = alpha;
   }
 
+  // Token-split mode: the softmax of the four tiles t0 .. t0+3 of a round in one go (one
+  // maximum, one move of the reference exponent, sixteen independent exponentials per lane)
+  // instead of four dependent passes.  The rescale factor goes with the first tile; the
+  // other three carry 1.
+  __device__ __forceinline__ void finalize_softmax4(int t0) {
+    if (!owner) return;
+    const int xi = o_hh * 9 + (lane & 7);
+    const int slot = 16 * o_tt + 4 * o_gg;       // this lane's first token slot in a tile
+    f32x4_t sc[4];
+    int valid[4], newl[4];
+#pragma unroll
+    for (int sub = 0; sub < 4; ++sub) {
+      sc[sub] = xchg[sub * 16 * MT * 9 + xi];
+      valid[sub] = tile_valid(t0 + sub);
+      newl[sub] = tile_new(t0 + sub);
+    }
+    if (scores && o_hh < H) {                   // logits out, for importance tracking
+#pragma unroll
+      for (int sub = 0; sub < 4; ++sub)
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          if (slot + i < valid[sub])
+            scores[(size_t)o_hh * T_cap + gtile(t0 + sub) * kTile + slot + i] = sc[sub][i] * kLn2;
+    }
+    float tmax = -INFINITY;
+#pragma unroll
+    for (int sub = 0; sub < 4; ++sub)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        if (slot + i >= valid[sub]) sc[sub][i] = -INFINITY;
+        tmax = fmaxf(tmax, sc[sub][i]);
+      }
+    tmax = max8(tmax);
+    float alpha = 1.0f;
+    if (tmax > m_ref + kLazy) {                 // same decision in the 8 lanes of a head
+      const float m_upd = fmaxf(m_ref, tmax);   // finite: the round's first tile holds a token
+      alpha = fast_exp2(m_ref - m_upd);
+      m_ref = m_upd;
+      l_part *= alpha;
+    }
+#pragma unroll
+    for (int sub = 0; sub < 4; ++sub) {
+      float p0 = fast_exp2(sc[sub][0] - m_ref), p1 = fast_exp2(sc[sub][1] - m_ref);
+      float p2 = fast_exp2(sc[sub][2] - m_ref), p3 = fast_exp2(sc[sub][3] - m_ref);
+      float pdef = 0.f;
+      if (newl[sub] >= 0 && newl[sub] < kTile) {  // wave-uniform: this tile holds the deferred token
+        const int li = newl[sub] - slot;
+        if (li == 0) { pdef = p0; p0 = 0.f; }
+        if (li == 1) { pdef = p1; p1 = 0.f; }
+        if (li == 2) { pdef = p2; p2 = 0.f; }
+        if (li == 3) { pdef = p3; p3 = 0.f; }
+        if (li >= 0 && li < 4 && o_hh < H) pnew[(size_t)b * H + o_hh] = pdef;
+      }
+      u32x2_t hi, lo = {0, 0};
+      hi[0] = cvt_pack(p0, p1, Tag{});
+      hi[1] = cvt_pack(p2, p3, Tag{});
+      float k0 = lo_to_f32(hi[0], Tag{}), k1 = hi_to_f32(hi[0], Tag{});
+      float k2 = lo_to_f32(hi[1], Tag{}), k3 = hi_to_f32(hi[1], Tag{});
+      if (SPLIT) {
+        lo[0] = cvt_pack(p0 - k0, p1 - k1, Tag{});
+        lo[1] = cvt_pack(p2 - k2, p3 - k3, Tag{});
+        k0 += lo_to_f32(lo[0], Tag{});
+        k1 += hi_to_f32(lo[0], Tag{});
+        k2 += lo_to_f32(lo[1], Tag{});
+        k3 += hi_to_f32(lo[1], Tag{});
+      }
+      l_part += (k0 + k1) + (k2 + k3) + pdef;   // the sum uses the values the MFMA will see
+      u32x2_t* ph = (u32x2_t*)(Pbuf + ((sub * MT + o_mt) * 2 + 0) * 64 + o_lane) + o_tt;
+      *ph = hi;
+      if (SPLIT) *(ph + 2 * 64) = lo;
+      if ((lane & 7) == 0) abuf[sub * 16 * MT + o_hh] = sub == 0 ? alpha : 1.0f;
+    }
+  }
+
   // (reference exponent, sum) of the heads this wave finalised.
   __device__ __forceinline__ void store_ml(float* part_ml) {
     const float l_tot = sum8(l_part);
@@ -788,9 +862,7 @@ __device__ __forceinline__ void score_role(const AttnParams& p) {
       }
       wg_barrier();                                         // scores of the round's tiles ready
       AP_TICK(2)
-#pragma unroll
-      for (int sub = 0; sub < 4; ++sub)
-        cx.finalize_softmax(cx.tile_valid(4 * it + sub), cx.tile_new(4 * it + sub), 4 * it + sub, sub);
+      cx.finalize_softmax4(4 * it);
       AP_TICK(3)
       wg_barrier();                                         // weights of the round's tiles ready
       AP_TICK(4)
@@ -964,9 +1036,7 @@ __device__ __forceinline__ void sum_role(const AttnParams& p) {
 #pragma nounroll
         for (int lt = 4 * it + RT - 4; lt < 4 * it + RT && lt < cx.ntl; ++lt) issue_tile(lt);   // refill the last round's slots
       }
-#pragma unroll
-      for (int sub = 0; sub < 4; ++sub)
-        cx.finalize_softmax(cx.tile_valid(4 * it + sub), cx.tile_new(4 * it + sub), 4 * it + sub, sub);
+      cx.finalize_softmax4(4 * it);
       AP_TICK(3)
       {
         // this round's tiles must have landed; those requested beyond it may stay in flight
