@@ -104,6 +104,12 @@ def main():
     ap_.add_argument("--profile-compact", action="store_true",
                      help="run only the configuration-5 prefill compaction (B=16, T=4224, HD=4096, r=512, fp16) "
                           "three times and exit without a JSON line: the workload behind profiles/compact_gemm_c5_mfma.md")
+    ap_.add_argument("--profile-next", action="store_true",
+                     help="run only the rows built after the hot path, ten times each at batch 64, and exit "
+                          "without a JSON line: importance tracking (decode step with logits out, moving "
+                          "average, rank groups), the uncompressed segment (T_u=256) with its merge, a "
+                          "grouped-query step (32/8 heads, r=256) and a small-rank step (r=128): the "
+                          "workload behind profiles/next_rows_kernel_trace.md")
     args = ap_.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
@@ -120,6 +126,63 @@ def main():
         c = [torch.empty(b5, t5, r5, device="cuda", dtype=torch.float16) for _ in range(2)]
         for _ in range(3):
             ap.ap_compact(x[0], x[1], bm[0], bm[1], c[0], c[1], None, None, n=t5, row0=0)
+        torch.cuda.synchronize()
+        return
+    if args.profile_next:
+        bf = torch.bfloat16
+        scale = 1.0 / math.sqrt(D)
+
+        def cache(b, t, r, hd):
+            ck = torch.randn(b, t, r, device="cuda", dtype=bf)
+            bk = (torch.randn(b, r, hd, device="cuda") / math.sqrt(hd)).to(bf)
+            return ck, ck.clone(), bk, bk.clone()
+
+        def buf(b, h, t, r):
+            return torch.empty(ap.ap_decode_workspace_bytes(b, h, D, t, r, ap.AP_BF16), dtype=torch.uint8, device="cuda")
+
+        t = T0 + 128
+        # importance tracking in the loop
+        ck, cv, bk, bv = cache(B, t, R, H * D)
+        q = torch.randn(B, H, D, device="cuda", dtype=bf)
+        kn = torch.randn(B, H * D, device="cuda", dtype=bf)
+        out = torch.empty(B, H, D, device="cuda")
+        lse = torch.empty(B, H, device="cuda")
+        sc = torch.empty(B, H, t, device="cuda")
+        mass = torch.zeros(B, t, device="cuda")
+        rank = torch.empty(B, t, dtype=torch.int32, device="cuda")
+        off = torch.empty(B, 5, dtype=torch.int32, device="cuda")
+        idx = torch.empty(B, t, dtype=torch.int32, device="cuda")
+        ws, wsel = buf(B, H, t, R), torch.empty(4096, dtype=torch.uint8, device="cuda")
+        for _ in range(10):
+            ap.ap_decode_step(q, kn, kn, ck, cv, bk, bv, out, ws, T=t, sm_scale=scale, lse=lse, scores=sc)
+            ap.ap_update_importance(sc, lse, mass, T=t, alpha=0.9)
+            ap.ap_select_ranks(mass, (R, R // 2, 128, 64), (1, 2, 3, 4), 4, rank, off, idx, wsel)
+        # uncompressed segment next to the compressed one
+        tu = 256
+        ku = torch.randn(B, tu, H * D, device="cuda", dtype=bf)
+        vu = torch.randn(B, tu, H * D, device="cuda", dtype=bf)
+        out_u, lse_u, out_m = torch.empty_like(out), torch.empty_like(lse), torch.empty_like(out)
+        wsr = torch.empty(max(256, ap.ap_raw_workspace_bytes(B, H, D, tu)), dtype=torch.uint8, device="cuda")
+        for _ in range(10):
+            ap.ap_decode_attn(q, ck, cv, bk, bv, out, ws, T=t, sm_scale=scale, lse=lse)
+            ap.ap_raw_attn(q, ku, vu, out_u, wsr, T_u=tu, sm_scale=scale, lse=lse_u)
+            ap.ap_merge_segments(out, lse, out_u, lse_u, out_m)
+        del ck, cv, bk, bv, ku, vu, sc
+        # grouped queries: 32 query heads on 8 key/value heads, r = 256
+        hq, hkv, rg = 32, 8, 256
+        ck, cv, bk, bv = cache(B, t, rg, hkv * D)
+        qg = torch.randn(B, hq, D, device="cuda", dtype=bf)
+        kg = torch.randn(B, hkv * D, device="cuda", dtype=bf)
+        outg = torch.empty(B, hq, D, device="cuda")
+        wsg = buf(B, hq, t, rg)
+        for _ in range(10):
+            ap.ap_decode_step(qg, kg, kg, ck, cv, bk, bv, outg, wsg, T=t, sm_scale=scale)
+        # small rank: r = 128 (the token-split mode of the kernel)
+        rs = 128
+        ck, cv, bk, bv = cache(B, t, rs, H * D)
+        wss = buf(B, H, t, rs)
+        for _ in range(10):
+            ap.ap_decode_step(q, kn, kn, ck, cv, bk, bv, out, wss, T=t, sm_scale=scale)
         torch.cuda.synchronize()
         return
     K, W = args.steps, args.warmup
