@@ -241,6 +241,7 @@ static ap_status decode_entry(const char* name, const void* q, const void* k_new
   AP_REQUIRE(aligned(q, 16) && aligned(Ck, 16) && aligned(Cv, 16) && aligned(Bk, 16) &&
                  aligned(Bv, 16) && aligned(out, 16),
              AP_ERR_INVALID_ARG, "%s: pointers must be 16-byte aligned", name);
+  AP_REQUIRE(aligned(scores, 16), AP_ERR_INVALID_ARG, "%s: scores must be 16-byte aligned", name);
   if (dt != AP_F32) {
     AP_REQUIRE(basis_batch_stride % 8 == 0, AP_ERR_INVALID_ARG,
                "%s: basis_batch_stride must keep rows 16-byte aligned", name);

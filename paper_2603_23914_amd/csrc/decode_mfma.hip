@@ -554,11 +554,18 @@ struct WaveCtx {
     }
     if (scores && o_hh < H) {                   // logits out, for importance tracking
       const int slot = 16 * o_tt + 4 * o_gg;
+      if (!RAGGED && (T_cap & 3) == 0 && slot + 3 < valid) {
+        // four consecutive tokens of one head: one 16-byte store (the eight lanes of a head
+        // then write a contiguous 128-byte run)
+        const f32x4_t v = {sc[0] * kLn2, sc[1] * kLn2, sc[2] * kLn2, sc[3] * kLn2};
+        *(f32x4_t*)(scores + (size_t)o_hh * T_cap + gtile(t) * kTile + slot) = v;
+      } else {
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        if (slot + i < valid) {
-          const int tok = RAGGED ? idxb[t * kTile + slot + i] : gtile(t) * kTile + slot + i;
-          scores[(size_t)o_hh * T_cap + tok] = sc[i] * kLn2;
+        for (int i = 0; i < 4; ++i) {
+          if (slot + i < valid) {
+            const int tok = RAGGED ? idxb[t * kTile + slot + i] : gtile(t) * kTile + slot + i;
+            scores[(size_t)o_hh * T_cap + tok] = sc[i] * kLn2;
+          }
         }
       }
     }
@@ -627,11 +634,17 @@ struct WaveCtx {
     }
     if (scores && o_hh < H) {                   // logits out, for importance tracking
 #pragma unroll
-      for (int sub = 0; sub < 4; ++sub)
+      for (int sub = 0; sub < 4; ++sub) {
+        if ((T_cap & 3) == 0 && slot + 3 < valid[sub]) {
+          const f32x4_t v = {sc[sub][0] * kLn2, sc[sub][1] * kLn2, sc[sub][2] * kLn2, sc[sub][3] * kLn2};
+          *(f32x4_t*)(scores + (size_t)o_hh * T_cap + gtile(t0 + sub) * kTile + slot) = v;
+        } else {
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
-          if (slot + i < valid[sub])
-            scores[(size_t)o_hh * T_cap + gtile(t0 + sub) * kTile + slot + i] = sc[sub][i] * kLn2;
+          for (int i = 0; i < 4; ++i)
+            if (slot + i < valid[sub])
+              scores[(size_t)o_hh * T_cap + gtile(t0 + sub) * kTile + slot + i] = sc[sub][i] * kLn2;
+        }
+      }
     }
     float tmax = -INFINITY;
 #pragma unroll
