@@ -1229,7 +1229,8 @@ constexpr int kInlineMergeSplits = 8;    // more splits than this are merged by 
 
 int choose_nsplit(int B, int T) {
   const int ntiles = (T + kTile - 1) / kTile;
-  int s = (256 + B - 1) / B;
+  int s = 256 / B;                         // one workgroup per CU at most: a second, partial round
+                                           // of workgroups would double the kernel's time
   const int by_table = (ntiles + kMaxGroups + kMaxTilesPerSplit - 1) / kMaxTilesPerSplit;
   if (s < by_table) {
     // more workgroups than CUs: whole rounds of 256 (a partial last round would run alone)
