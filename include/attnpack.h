@@ -18,6 +18,10 @@
  *   - All work is enqueued on `stream` (a hipStream_t passed as void*; NULL =
  *     the default stream).  Calls return without synchronising; outputs are
  *     valid once the stream reaches that point.
+ *   - The calls enqueue kernels only: no allocation, no memset, no synchronisation.  They may
+ *     be captured in a HIP graph, provided a call with the same shapes has run once before the
+ *     capture (the first launch of a kernel variant sets its shared-memory limit, which is not
+ *     a stream operation) and timing (ap_prof_enable) is off.
  *   - Matrices are dense row-major.  Rows of C_k, C_v, B_k, B_v, K, V must start
  *     on 16-byte boundaries (true for r % 8 == 0 / HD % 8 == 0 in 2-byte types).
  *   - Errors are return codes; nothing is thrown or aborted.  Everything that can
