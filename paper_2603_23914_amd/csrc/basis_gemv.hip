@@ -13,7 +13,7 @@
 //   merge_expand            combine the token splits of attn_partial and expand through B_v:
 //                           out[h, :] = (sum_s w_s U_s[h, :] / sum_s w_s l_s) . Bv[:, head h]
 //                           (Alg. 1 output by associativity).  A workgroup owns two heads
-//                           (512-byte row segments) and keeps four rows in flight per thread.
+//                           (512-byte row segments) and keeps eight rows in flight per thread.
 // Products of two 16-bit values are exact in fp32; sums are fp32 (v_dot2c_f32_*).
 #include "ap_common.hpp"
 #include "lane_ops.hpp"
