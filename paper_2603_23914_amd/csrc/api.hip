@@ -65,7 +65,7 @@ const char* ap_status_string(ap_status s) {
 
 const char* ap_last_error(void) { return g_err; }
 
-int ap_version(void) { return 100; }
+int ap_version(void) { return 300; }   // 0.3.0: H_kv, scores, raw segment, merge entries
 
 void ap_prof_enable(int on) {
   g_prof_on = on != 0;
