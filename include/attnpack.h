@@ -266,11 +266,13 @@ ap_status ap_raw_append(const void* k_new, const void* v_new, void* K, void* V,
 
 /* ------------------------------------------------------------------------
  * Timing of the dominant kernel (measurement aid, not part of the method).
- * While enabled, every ap_decode_attn call on AP_F16 / AP_BF16 brackets its
- * coefficient-streaming kernel with a pair of HIP events on the call's stream.
- * ap_prof_read waits for the last recorded pair and returns the summed kernel
- * time in milliseconds and the number of pairs since ap_prof_enable(1), which
- * also clears the records.  At most 4096 launches are recorded (later ones are
+ * While enabled, every ap_decode_attn / ap_decode_step call on AP_F16 / AP_BF16
+ * attaches a pair of HIP events to the launch of its coefficient-streaming
+ * kernel (hipExtLaunchKernelGGL: the events carry that kernel's own start and
+ * end, not the gap to the kernel before it, so the time is the one a kernel
+ * trace reports).  ap_prof_read waits for the last pair and returns the summed
+ * kernel time in milliseconds and the number of pairs since ap_prof_enable(1),
+ * which also clears the records.  At most 4096 launches are recorded (later ones are
  * not timed).  Events are host-side handles owned by the library; no device
  * memory is allocated.  Not thread-safe.
  * ---------------------------------------------------------------------- */

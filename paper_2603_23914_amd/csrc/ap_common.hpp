@@ -163,7 +163,9 @@ ap_status launch_select_ranks(const float* mass, int B, int T, int F, const int3
 
 ap_status check_launch(const char* what);
 
-// dominant-kernel timing (api.hip): record an event on `stream` if profiling is on
-void prof_mark(hipStream_t stream, bool start);
+// dominant-kernel timing (api.hip): while timing is on, hands out the next pair of events; the
+// caller attaches them to ONE kernel launch (hipExtLaunchKernelGGL), so their difference is
+// that kernel's own start-to-end time, without the gap to the kernel before it
+bool prof_events(hipEvent_t* start, hipEvent_t* stop);
 
 }  // namespace ap

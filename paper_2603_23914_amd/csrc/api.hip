@@ -33,15 +33,17 @@ static std::vector<hipEvent_t> g_prof_ev;   // start, stop, start, stop, ...
 static size_t g_prof_used = 0;
 constexpr size_t kProfMax = 2 * 4096;
 
-void prof_mark(hipStream_t stream, bool start) {
-  if (!g_prof_on) return;
-  if (start ? (g_prof_used + 2 > kProfMax) : (g_prof_used % 2 == 0)) return;
-  if (g_prof_used == g_prof_ev.size()) {
+bool prof_events(hipEvent_t* start, hipEvent_t* stop) {
+  if (!g_prof_on || g_prof_used + 2 > kProfMax) return false;
+  while (g_prof_ev.size() < g_prof_used + 2) {
     hipEvent_t e;
-    if (hipEventCreate(&e) != hipSuccess) return;
+    if (hipEventCreate(&e) != hipSuccess) return false;
     g_prof_ev.push_back(e);
   }
-  (void)hipEventRecord(g_prof_ev[g_prof_used++], stream);
+  *start = g_prof_ev[g_prof_used];
+  *stop = g_prof_ev[g_prof_used + 1];
+  g_prof_used += 2;
+  return true;
 }
 
 static bool half_type(ap_dtype dt) { return dt == AP_F16 || dt == AP_BF16; }

@@ -25,6 +25,7 @@
 // turned into fp16 values code*scale in registers, right in front of the MFMA that uses
 // them; everything else is the fp16 path.
 #include "ap_common.hpp"
+#include <hip/hip_ext.h>
 
 #include <cstdlib>
 
@@ -1313,7 +1314,11 @@ ap_status launch_attn(AttnParams p, int B, hipStream_t stream) {
   }
   p.B = B;
   p.xcd_aware = B % 8 == 0 ? 1 : 0;
-  hipLaunchKernelGGL(kern, dim3(B * p.nsplit), dim3(512), lds, stream, p);
+  hipEvent_t ev0, ev1;
+  if (prof_events(&ev0, &ev1))             // timing on: the events carry this launch's own start and end
+    hipExtLaunchKernelGGL(kern, dim3(B * p.nsplit), dim3(512), (uint32_t)lds, stream, ev0, ev1, 0u, p);
+  else
+    hipLaunchKernelGGL(kern, dim3(B * p.nsplit), dim3(512), lds, stream, p);
   return AP_OK;
 }
 
@@ -1418,9 +1423,7 @@ ap_status run_decode(const DecodeArgs& a) {
   p.dbg_out = (unsigned long long*)U;   // timers overwrite the head of part_U
   if (p.dbg & 8) p.dbg_out = (unsigned long long*)(ws + wl.total);   // caller allocated extra bytes
 #endif
-  prof_mark(a.stream, true);
   st = dispatch_attn<Tag, SPLIT>(p, a.B, a.stream);
-  prof_mark(a.stream, false);
   if (st != AP_OK) return st;
   int S_exp = S;
   if (S > kInlineMergeSplits) {            // small batch, many splits: merge them in parallel first

@@ -1,0 +1,43 @@
+"""GPU: the kernel timer of the library (ap_prof_enable / ap_prof_read) counts one launch per decode
+call, reports a time that lies inside the wall time of those calls, and leaves results unchanged."""
+import math
+import time
+
+import pytest
+import torch
+
+from paper_2603_23914_amd import workloads as wl
+from gpu_util import to_dev, workspace
+
+pytestmark = pytest.mark.gpu
+
+
+def test_kernel_timer_counts_launches_and_stays_inside_wall_time():
+    from paper_2603_23914_amd import binding as ap
+    dtype, B, H, d, r, T = "bf16", 8, 16, 64, 256, 1500
+    case = wl.decode_case(dtype, B, H, d, r, T, steps=0, seed=71, append=False)
+    q = wl.step_query(case, 0)
+    dq, dCk, dCv, dBk, dBv = (to_dev(x, dtype) for x in (q, case.Ck, case.Cv, case.Bk, case.Bv))
+    out0 = torch.empty((B, H, d), dtype=torch.float32, device="cuda")
+    out1 = torch.empty_like(out0)
+    ws = workspace(ap.ap_decode_workspace_bytes(B, H, d, T, r, ap.AP_BF16))
+    scale = 1.0 / math.sqrt(d)
+    ap.ap_decode_attn(dq, dCk, dCv, dBk, dBv, out0, ws, T=T, sm_scale=scale)     # untimed, also warms up
+    torch.cuda.synchronize()
+    print("timed launches", flush=True)
+    ap.ap_prof_enable(True)
+    t0 = time.perf_counter()
+    for _ in range(5):
+        ap.ap_decode_attn(dq, dCk, dCv, dBk, dBv, out1, ws, T=T, sm_scale=scale)
+    ms, n = ap.ap_prof_read()                                                   # waits for the last launch
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    ap.ap_prof_enable(False)
+    assert n == 5
+    assert 0.0 < ms < wall_ms
+    assert ms / n < 1.0                     # a few MB of coefficients: microseconds, not milliseconds
+    assert torch.equal(out0, out1)
+    ap.ap_prof_enable(True)                 # enabling clears the records
+    ms, n = ap.ap_prof_read()
+    ap.ap_prof_enable(False)
+    assert n == 0 and ms == 0.0
