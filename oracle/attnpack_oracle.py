@@ -255,24 +255,30 @@ def decode_attn_segments(q, segments, sm_scale=None, return_lse: bool = False, k
     and all values are concatenated along the token axis (Ktilde = (+)_f
     Kbar[m_f, :R_f] D_k[:R_f] (+) K), and one softmax runs over the lot.
 
-    segments: sequence of dicts, either
-      {"Ck", "Cv", "Bk", "Bv"[, "rank_k", "rank_v"]}   compressed, own bases
-      {"K", "V"}                                        uncompressed [T_u, H*d]
+    segments: sequence of dicts; the key side and the value side of a segment
+    are given independently, each either compressed or uncompressed:
+      keys    {"Ck", "Bk"[, "rank_k"]}  coefficients and own basis   or  {"K"} [T, H_kv*d]
+      values  {"Cv", "Bv"[, "rank_v"]}                                or  {"V"} [T, H_kv*d]
+    A segment with compressed keys and raw values is the key-only compression
+    of the text-domain experiment (Sec. 4, LongBench: R_k = 64, values kept).
     """
     q = np.asarray(q, np.float64)
     H, d = q.shape
     HDkv = (H if kv_heads is None else int(kv_heads)) * d
+
+    def side(seg, raw, coef, basis, rank):
+        if raw in seg:
+            return np.asarray(seg[raw], np.float64).reshape(-1, HDkv)
+        C = np.asarray(seg[coef], np.float64)
+        T, r = C.shape
+        return _partial_decompress(C, np.asarray(seg[basis], np.float64), _ranks(seg.get(rank), T, r))
+
     Ks, Vs = [], []
     for seg in segments:
-        if "K" in seg:
-            Ks.append(np.asarray(seg["K"], np.float64).reshape(-1, HDkv))
-            Vs.append(np.asarray(seg["V"], np.float64).reshape(-1, HDkv))
-        else:
-            Ck = np.asarray(seg["Ck"], np.float64)
-            Cv = np.asarray(seg["Cv"], np.float64)
-            T, r = Ck.shape
-            Ks.append(_partial_decompress(Ck, np.asarray(seg["Bk"], np.float64), _ranks(seg.get("rank_k"), T, r)))
-            Vs.append(_partial_decompress(Cv, np.asarray(seg["Bv"], np.float64), _ranks(seg.get("rank_v"), T, r)))
+        Ks.append(side(seg, "K", "Ck", "Bk", "rank_k"))
+        Vs.append(side(seg, "V", "Cv", "Bv", "rank_v"))
+        if Ks[-1].shape[0] != Vs[-1].shape[0]:
+            raise ValueError("a segment's keys and values must cover the same tokens")
     return raw_attn(q, np.concatenate(Ks, axis=0), np.concatenate(Vs, axis=0), sm_scale, return_lse,
                     kv_heads=kv_heads)
 

@@ -178,3 +178,78 @@ def test_grouped_queries_head_mapping_is_by_consecutive_groups():
             assert np.abs(out[h] - c["V"][2, d:2 * d]).max() < 1e-9
         else:
             assert np.abs(out[h] - c["V"][:, kv * d:(kv + 1) * d].mean(axis=0)).max() < 1e-12
+
+
+# ---- one-sided compression (Sec. 4, text-domain experiment: keys at R_k = 64, values kept) ----
+def test_key_only_segment_brute_force_loops():
+    """Scalar loops: keys rebuilt from their coefficients, values taken as stored, grouped heads."""
+    rng = np.random.default_rng(21)
+    H, Hkv, d, T, r = 4, 2, 3, 6, 4
+    q = rng.standard_normal((H, d))
+    Ck = rng.standard_normal((T, r))
+    Bk = rng.standard_normal((r, Hkv * d))
+    V = rng.standard_normal((T, Hkv * d))
+    scale = 1.0 / math.sqrt(d)
+    ref = np.zeros((H, d))
+    ref_lse = np.zeros(H)
+    for h in range(H):
+        kvh = h // (H // Hkv)
+        sc = []
+        for t in range(T):
+            key = [sum(Ck[t, j] * Bk[j, kvh * d + i] for j in range(r)) for i in range(d)]
+            sc.append(scale * sum(q[h, i] * key[i] for i in range(d)))
+        mx = max(sc)
+        ex = [math.exp(x - mx) for x in sc]
+        for i in range(d):
+            ref[h, i] = sum(e * V[t, kvh * d + i] for t, e in enumerate(ex)) / sum(ex)
+        ref_lse[h] = mx + math.log(sum(ex))
+    got, lse = oracle.decode_attn_segments(q, [dict(Ck=Ck, Bk=Bk, V=V)], return_lse=True, kv_heads=Hkv)
+    assert np.abs(got - ref).max() < 1e-13 and np.abs(lse - ref_lse).max() < 1e-13
+
+
+def test_value_only_segment_brute_force_loops():
+    rng = np.random.default_rng(22)
+    H, d, T, r = 2, 4, 5, 3
+    q = rng.standard_normal((H, d))
+    K = rng.standard_normal((T, H * d))
+    Cv = rng.standard_normal((T, r))
+    Bv = rng.standard_normal((r, H * d))
+    rv = [3, 0, 2, 1, 3]
+    scale = 1.0 / math.sqrt(d)
+    ref = np.zeros((H, d))
+    for h in range(H):
+        sc = [scale * sum(q[h, i] * K[t, h * d + i] for i in range(d)) for t in range(T)]
+        mx = max(sc)
+        ex = [math.exp(x - mx) for x in sc]
+        for i in range(d):
+            vals = [sum(Cv[t, j] * Bv[j, h * d + i] for j in range(rv[t])) for t in range(T)]
+            ref[h, i] = sum(e * v for e, v in zip(ex, vals)) / sum(ex)
+    got = oracle.decode_attn_segments(q, [dict(K=K, Cv=Cv, Bv=Bv, rank_v=np.array(rv))])
+    assert np.abs(got - ref).max() < 1e-13
+
+
+def test_one_sided_segments_reduce_to_the_known_cases():
+    """Keys in a complete orthonormal basis lose nothing: key-only compression at r = H*d equals
+    plain attention on the raw keys; and a two-sided segment equals the compressed decode."""
+    c = rand_case(23, H=3, d=4, T=9, r=12, Tu=9)
+    HD = 12
+    Qm, _ = np.linalg.qr(np.random.default_rng(5).standard_normal((HD, HD)))
+    Bk = Qm.T                                             # orthonormal rows, complete
+    Ck = c["K"] @ Bk.T                                    # then Ck Bk = K exactly (up to rounding)
+    got = oracle.decode_attn_segments(c["q"], [dict(Ck=Ck, Bk=Bk, V=c["V"])])
+    assert np.abs(got - oracle.raw_attn(c["q"], c["K"], c["V"])).max() < 1e-12
+    both = oracle.decode_attn_segments(c["q"], [dict(Ck=c["Ck"], Bk=c["Bk"], Cv=c["Cv"], Bv=c["Bv"])])
+    assert np.abs(both - oracle.decode_attn(c["q"], c["Ck"], c["Cv"], c["Bk"], c["Bv"])).max() < 1e-12
+    with pytest.raises(ValueError):
+        oracle.decode_attn_segments(c["q"], [dict(Ck=c["Ck"], Bk=c["Bk"], V=c["V"][:5])])
+
+
+def test_key_only_segment_next_to_a_raw_tail_is_the_merge_of_the_two():
+    c = rand_case(24, H=2, d=8, T=11, r=5, Tu=6)
+    Vc = np.random.default_rng(6).standard_normal((11, 16))
+    whole, lse = oracle.decode_attn_segments(c["q"], [dict(Ck=c["Ck"], Bk=c["Bk"], V=Vc), dict(K=c["K"], V=c["V"])],
+                                             return_lse=True)
+    o1, l1 = oracle.decode_attn_segments(c["q"], [dict(Ck=c["Ck"], Bk=c["Bk"], V=Vc)], return_lse=True)
+    o2, l2 = oracle.raw_attn(c["q"], c["K"], c["V"], return_lse=True)
+    om, lm = oracle.merge_segments([o1, o2], [l1, l2])
+    assert np.abs(om - whole).max() < 1e-13 and np.abs(lm - lse).max() < 1e-13
