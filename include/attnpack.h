@@ -265,6 +265,37 @@ ap_status ap_raw_append(const void* k_new, const void* v_new, void* K, void* V,
                         int B, int HD, int row, int T_u_cap, ap_dtype dt, void* stream);
 
 /* ------------------------------------------------------------------------
+ * ap_keyonly_attn -- decode attention over a cache whose KEYS are compressed
+ * while its values are kept as they are (paper Sec. 4, text-domain experiment:
+ * values need a higher rank than keys there, so only the keys are compressed,
+ * R_k = 64).  The same segment algebra as above applies: keys Ktilde = Ck Bk,
+ *
+ *   out[b, h] = softmax_t( sm_scale * q[b, h] . Ktilde[b, t, slice(h)] ) V[b, t, slice(h)]
+ *
+ * computed with the basis folded into the query (q' = Bk[:, slice] q, one dot
+ * product of length r per token and head instead of a rebuilt key).
+ *
+ *   q        [B, H, d]           dt (AP_F16 | AP_BF16)
+ *   Ck       [B, T_cap, r]       dt, rows 0 .. T-1 read
+ *   Bk       [r, H_kv*d]         dt; batch b uses Bk + b*basis_batch_stride elements (0 = shared)
+ *   V        [B, T_cap, H_kv*d]  dt, rows 0 .. T-1 read (same T_cap as Ck)
+ *   out      [B, H, d] fp32; lse [B, H] fp32 natural-log sum of exponentials, or NULL.
+ *            T == 0 gives out = 0, lse = -inf.  (out, lse) can be joined with other
+ *            segments by ap_merge_segments.
+ *   workspace  ap_keyonly_workspace_bytes(B, H, d, T, r) bytes, 256-byte aligned
+ *            (0 from the query = unsupported shape).
+ *   Requires d in {32, 64, 128, 256}, r % 8 == 0, r <= 640, H % H_kv == 0.
+ *   A generated token is added with ap_compact (K only, n = 1) and ap_raw_append
+ *   (v_new only).
+ * ---------------------------------------------------------------------- */
+size_t ap_keyonly_workspace_bytes(int B, int H, int d, int T, int r);
+ap_status ap_keyonly_attn(const void* q, const void* Ck, const void* Bk,
+                          int64_t basis_batch_stride, const void* V,
+                          float* out, float* lse, int B, int H, int H_kv, int d,
+                          int T, int T_cap, int r, float sm_scale, ap_dtype dt,
+                          void* workspace, size_t ws_bytes, void* stream);
+
+/* ------------------------------------------------------------------------
  * Timing of the dominant kernel (measurement aid, not part of the method).
  * While enabled, every ap_decode_attn / ap_decode_step call on AP_F16 / AP_BF16
  * attaches a pair of HIP events to the launch of its coefficient-streaming

@@ -329,6 +329,40 @@ ap_status ap_raw_attn(const void* q, const void* K, const void* V, float* out, f
                          (hipStream_t)stream);
 }
 
+size_t ap_keyonly_workspace_bytes(int B, int H, int d, int T, int r) {
+  if (!raw_shape_ok(B, H, d) || T < 0 || r <= 0 || r > 640 || r % 8 != 0) return 0;
+  return keyonly_attn_workspace(B, H, d, T, r);
+}
+
+ap_status ap_keyonly_attn(const void* q, const void* Ck, const void* Bk, int64_t basis_batch_stride,
+                          const void* V, float* out, float* lse, int B, int H, int H_kv, int d, int T,
+                          int T_cap, int r, float sm_scale, ap_dtype dt, void* workspace, size_t ws_bytes,
+                          void* stream) {
+  clear_error();
+  AP_REQUIRE(q && Bk && out && workspace, AP_ERR_INVALID_ARG, "ap_keyonly_attn: NULL pointer");
+  AP_REQUIRE(raw_shape_ok(B, H, d), AP_ERR_UNSUPPORTED,
+             "ap_keyonly_attn: need 0 < B, H <= 65535 and d in {32, 64, 128, 256}");
+  AP_REQUIRE(H_kv >= 1 && H % H_kv == 0, AP_ERR_INVALID_ARG,
+             "ap_keyonly_attn: H_kv=%d must be positive and divide H=%d", H_kv, H);
+  AP_REQUIRE(dt == AP_F16 || dt == AP_BF16, AP_ERR_UNSUPPORTED, "ap_keyonly_attn: fp16 or bf16 storage only");
+  AP_REQUIRE(r > 0 && r % 8 == 0, AP_ERR_INVALID_ARG, "ap_keyonly_attn: r=%d must be a positive multiple of 8", r);
+  AP_REQUIRE(r <= 640, AP_ERR_UNSUPPORTED, "ap_keyonly_attn: r=%d exceeds 640", r);
+  AP_REQUIRE(T >= 0 && T <= T_cap, AP_ERR_INVALID_ARG, "ap_keyonly_attn: need 0 <= T <= T_cap");
+  AP_REQUIRE(T == 0 || (Ck && V), AP_ERR_INVALID_ARG, "ap_keyonly_attn: NULL cache with T > 0");
+  const int64_t HDkv = (int64_t)H_kv * d;
+  AP_REQUIRE(basis_batch_stride == 0 || basis_batch_stride >= (int64_t)r * HDkv, AP_ERR_INVALID_ARG,
+             "ap_keyonly_attn: basis_batch_stride must be 0 or >= r*H_kv*d");
+  AP_REQUIRE(basis_batch_stride % 8 == 0, AP_ERR_INVALID_ARG,
+             "ap_keyonly_attn: basis_batch_stride must keep rows 16-byte aligned");
+  AP_REQUIRE(aligned(q, 16) && aligned(Ck, 16) && aligned(Bk, 16) && aligned(V, 16) && aligned(workspace, 256),
+             AP_ERR_INVALID_ARG, "ap_keyonly_attn: q, Ck, Bk, V must be 16-byte aligned, the workspace 256-byte");
+  AP_REQUIRE(ws_bytes >= keyonly_attn_workspace(B, H, d, T, r), AP_ERR_WORKSPACE,
+             "ap_keyonly_attn: workspace too small (%zu < %zu bytes)", ws_bytes,
+             keyonly_attn_workspace(B, H, d, T, r));
+  return launch_keyonly_attn(q, Ck, Bk, basis_batch_stride, V, out, lse, B, H, H_kv, d, T, T_cap, r, sm_scale,
+                             dt, workspace, (hipStream_t)stream);
+}
+
 ap_status ap_merge_segments(const float* out_a, const float* lse_a, const float* out_b,
                             const float* lse_b, void* out, float* lse, int B, int H, int d,
                             ap_dtype dt_out, void* stream) {
