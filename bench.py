@@ -108,8 +108,9 @@ def main():
                      help="run only the rows built after the hot path, ten times each at batch 64, and exit "
                           "without a JSON line: importance tracking (decode step with logits out, moving "
                           "average, rank groups), the uncompressed segment (T_u=256) with its merge, a "
-                          "grouped-query step (32/8 heads, r=256) and a small-rank step (r=128): the "
-                          "workload behind profiles/next_rows_kernel_trace.md")
+                          "grouped-query step (32/8 heads, r=256), a small-rank step (r=128), and key-only "
+                          "compression (32/8 heads, R_k=64, 8 sequences of 8192 tokens) next to plain attention "
+                          "over the same tokens: the workload behind profiles/next_rows_kernel_trace.md")
     args = ap_.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
@@ -183,6 +184,22 @@ def main():
         wss = buf(B, H, t, rs)
         for _ in range(10):
             ap.ap_decode_step(q, kn, kn, ck, cv, bk, bv, out, wss, T=t, sm_scale=scale)
+        del ck, cv, bk, bv
+        # key-only compression at the head layout and rank of the text-domain experiment (32 query
+        # heads on 8 key/value heads, R_k = 64), 8 sequences of 8192 tokens, next to plain attention
+        # over the same tokens uncompressed
+        bl, tl, rl = 8, 8192, 64
+        ckl = torch.randn(bl, tl, rl, device="cuda", dtype=bf)
+        bkl = (torch.randn(bl, rl, hkv * D, device="cuda") / math.sqrt(hkv * D)).to(bf)
+        kl = torch.randn(bl, tl, hkv * D, device="cuda", dtype=bf)
+        vl = torch.randn(bl, tl, hkv * D, device="cuda", dtype=bf)
+        ql = torch.randn(bl, hq, D, device="cuda", dtype=bf)
+        outl = torch.empty(bl, hq, D, device="cuda")
+        wsk = torch.empty(ap.ap_keyonly_workspace_bytes(bl, hq, hkv, D, tl, rl), dtype=torch.uint8, device="cuda")
+        wsl = torch.empty(max(256, ap.ap_raw_workspace_bytes(bl, hq, D, tl)), dtype=torch.uint8, device="cuda")
+        for _ in range(10):
+            ap.ap_keyonly_attn(ql, ckl, bkl, vl, outl, wsk, T=tl, sm_scale=scale)
+            ap.ap_raw_attn(ql, kl, vl, outl, wsl, T_u=tl, sm_scale=scale)
         torch.cuda.synchronize()
         return
     K, W = args.steps, args.warmup

@@ -282,13 +282,13 @@ ap_status ap_raw_append(const void* k_new, const void* v_new, void* K, void* V,
  *   out      [B, H, d] fp32; lse [B, H] fp32 natural-log sum of exponentials, or NULL.
  *            T == 0 gives out = 0, lse = -inf.  (out, lse) can be joined with other
  *            segments by ap_merge_segments.
- *   workspace  ap_keyonly_workspace_bytes(B, H, d, T, r) bytes, 256-byte aligned
+ *   workspace  ap_keyonly_workspace_bytes(B, H, H_kv, d, T, r) bytes, 256-byte aligned
  *            (0 from the query = unsupported shape).
  *   Requires d in {32, 64, 128, 256}, r % 8 == 0, r <= 640, H % H_kv == 0.
  *   A generated token is added with ap_compact (K only, n = 1) and ap_raw_append
  *   (v_new only).
  * ---------------------------------------------------------------------- */
-size_t ap_keyonly_workspace_bytes(int B, int H, int d, int T, int r);
+size_t ap_keyonly_workspace_bytes(int B, int H, int H_kv, int d, int T, int r);
 ap_status ap_keyonly_attn(const void* q, const void* Ck, const void* Bk,
                           int64_t basis_batch_stride, const void* V,
                           float* out, float* lse, int B, int H, int H_kv, int d,

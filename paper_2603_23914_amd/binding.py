@@ -54,7 +54,7 @@ _lib.ap_raw_attn.argtypes = [_vp] * 5 + [_i] * 6 + [_f, _i, _vp, _sz, _vp]
 _lib.ap_merge_segments.restype = _i
 _lib.ap_merge_segments.argtypes = [_vp] * 6 + [_i] * 4 + [_vp]
 _lib.ap_keyonly_workspace_bytes.restype = _sz
-_lib.ap_keyonly_workspace_bytes.argtypes = [_i] * 5
+_lib.ap_keyonly_workspace_bytes.argtypes = [_i] * 6
 _lib.ap_keyonly_attn.restype = _i
 _lib.ap_keyonly_attn.argtypes = [_vp] * 3 + [_c.c_int64] + [_vp] * 3 + [_i] * 7 + [_f, _i, _vp, _sz, _vp]
 _lib.ap_raw_append.restype = _i
@@ -209,8 +209,8 @@ def ap_raw_attn(q, K, V, out, workspace, *, T_u: int, sm_scale: float, lse=None,
                             workspace.numel() * workspace.element_size(), _stream(stream)))
 
 
-def ap_keyonly_workspace_bytes(B: int, H: int, d: int, T: int, r: int) -> int:
-    return _lib.ap_keyonly_workspace_bytes(B, H, d, T, r)
+def ap_keyonly_workspace_bytes(B: int, H: int, H_kv: int, d: int, T: int, r: int) -> int:
+    return _lib.ap_keyonly_workspace_bytes(B, H, H_kv, d, T, r)
 
 
 def ap_keyonly_attn(q, Ck, Bk, V, out, workspace, *, T: int, sm_scale: float, lse=None, stream=None) -> None:

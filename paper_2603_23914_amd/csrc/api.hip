@@ -329,9 +329,10 @@ ap_status ap_raw_attn(const void* q, const void* K, const void* V, float* out, f
                          (hipStream_t)stream);
 }
 
-size_t ap_keyonly_workspace_bytes(int B, int H, int d, int T, int r) {
+size_t ap_keyonly_workspace_bytes(int B, int H, int H_kv, int d, int T, int r) {
   if (!raw_shape_ok(B, H, d) || T < 0 || r <= 0 || r > 640 || r % 8 != 0) return 0;
-  return keyonly_attn_workspace(B, H, d, T, r);
+  if (H_kv < 1 || H % H_kv != 0) return 0;
+  return keyonly_attn_workspace(B, H, H_kv, d, T, r);
 }
 
 ap_status ap_keyonly_attn(const void* q, const void* Ck, const void* Bk, int64_t basis_batch_stride,
@@ -356,9 +357,9 @@ ap_status ap_keyonly_attn(const void* q, const void* Ck, const void* Bk, int64_t
              "ap_keyonly_attn: basis_batch_stride must keep rows 16-byte aligned");
   AP_REQUIRE(aligned(q, 16) && aligned(Ck, 16) && aligned(Bk, 16) && aligned(V, 16) && aligned(workspace, 256),
              AP_ERR_INVALID_ARG, "ap_keyonly_attn: q, Ck, Bk, V must be 16-byte aligned, the workspace 256-byte");
-  AP_REQUIRE(ws_bytes >= keyonly_attn_workspace(B, H, d, T, r), AP_ERR_WORKSPACE,
+  AP_REQUIRE(ws_bytes >= keyonly_attn_workspace(B, H, H_kv, d, T, r), AP_ERR_WORKSPACE,
              "ap_keyonly_attn: workspace too small (%zu < %zu bytes)", ws_bytes,
-             keyonly_attn_workspace(B, H, d, T, r));
+             keyonly_attn_workspace(B, H, H_kv, d, T, r));
   return launch_keyonly_attn(q, Ck, Bk, basis_batch_stride, V, out, lse, B, H, H_kv, d, T, T_cap, r, sm_scale,
                              dt, workspace, (hipStream_t)stream);
 }

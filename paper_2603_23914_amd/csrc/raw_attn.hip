@@ -2,10 +2,12 @@
 // tokens generated since the last compression) and the merge of segments under one softmax.
 //
 //   raw_attn_partial   flash-decode over raw K, V [B, T_u_cap, HD] in 16-bit storage: a
-//                      workgroup owns one head of one sequence and a range of tokens; groups
-//                      of d/8 lanes take one token each (one 16-byte chunk of the head's key
-//                      and value slice per lane), several tokens in flight per group, online
-//                      softmax per group, groups combined through LDS at the end.
+//                      workgroup owns the query heads that share one key/value head (up to
+//                      eight; every head alone without grouped queries) of one sequence and
+//                      a range of tokens; groups of d/8 lanes take one token each (one
+//                      16-byte chunk of the key and value slice per lane, loaded once for all
+//                      the heads), several tokens in flight per group, online softmax per
+//                      group and head, groups combined through LDS at the end.
 //   keyonly_partial    the same flash-decode for a cache whose KEYS are compressed (coefficients
 //                      C_k [B, T_cap, r] and a basis) while its values stay raw (Sec. 4, the
 //                      text-domain experiment compresses keys only, R_k = 64): the basis is
@@ -27,11 +29,101 @@ namespace {
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr int kUnroll = 4;       // tokens in flight per lane group
 
-// grid (H, S, B), 256 threads.  LPH = d / 8 lanes form a group; G = 256 / LPH groups.  QG query
-// heads share one key/value head (grouped queries; 1 = every head has its own).
+// Heads of one workgroup: NQ query heads that share a key/value head (grouped queries), so a
+// key or value chunk is loaded once and used NQ times.  A key/value head with QG query heads
+// is covered by ceil(QG / NQ) workgroups; the last may hold fewer than NQ heads (its unused
+// slots repeat the first head and write nothing).
+constexpr int heads_per_wg(int QG) { return QG >= 5 ? 8 : QG >= 3 ? 4 : QG >= 2 ? 2 : 1; }
+
+struct HeadBlock {
+  int h0, nq, kvh;
+};
+template <int NQ>
+__device__ __forceinline__ HeadBlock head_block(int idx, int QG) {
+  const int nsub = (QG + NQ - 1) / NQ;
+  const int kvh = idx / nsub, sub = idx - kvh * nsub;
+  int nq = QG - sub * NQ;
+  nq = nq < NQ ? nq : NQ;
+  return {kvh * QG + sub * NQ, nq, kvh};
+}
+
+// The contribution of N tokens to the online softmax of one head: one maximum over the N
+// scores, at most one move of the reference exponent (the accumulators are rescaled under a
+// branch that is rarely taken after the first tokens), N independent exponentials.
+template <int N>
+__device__ __forceinline__ void softmax_steps(const float (&s)[N], const bool (&valid)[N], const float (&vf)[N][8],
+                                              float& m, float& l, float (&o)[8]) {
+  float mx = -INFINITY;
+#pragma unroll
+  for (int u = 0; u < N; ++u) mx = fmaxf(mx, valid[u] ? s[u] : -INFINITY);
+  if (mx > m) {
+    const float alpha = fast_exp2(m - mx);               // 0 on the first tokens (m = -inf)
+    l *= alpha;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) o[e] *= alpha;
+    m = mx;
+  }
+#pragma unroll
+  for (int u = 0; u < N; ++u) {
+    const float pw = valid[u] ? fast_exp2(s[u] - m) : 0.f;   // m is finite wherever a token is valid
+    l += pw;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) o[e] = fmaf(pw, vf[u][e], o[e]);
+  }
+}
+
+// 16 bytes of 16-bit values -> eight floats.
+template <class Tag>
+__device__ __forceinline__ void widen8(const u32x4_t& v, float (&f)[8]) {
+#pragma unroll
+  for (int e = 0; e < 4; ++e) { f[2 * e] = lo_to_f32(v[e], Tag{}); f[2 * e + 1] = hi_to_f32(v[e], Tag{}); }
+}
+
+// The groups of a workgroup hold partial (m, l, o) of the same heads over different tokens:
+// combine them through LDS, one head at a time, and write the normalised partial output
+// [su][b][h][d] and its log-sum-exp [su][b][h].
+template <int LPH, int NQ>
+__device__ __forceinline__ void combine_groups(const float (&m)[NQ], const float (&l)[NQ], const float (&o)[NQ][8],
+                                               const HeadBlock& hb, int su, int b, int B, int H,
+                                               float* __restrict__ out_part, float* __restrict__ lse_part) {
+  constexpr int d = LPH * 8;
+  constexpr int G = 256 / LPH;
+  __shared__ float red[G][d + 2];
+  const int tid = threadIdx.x, g = tid / LPH, li = tid % LPH;
+#pragma unroll
+  for (int k = 0; k < NQ; ++k) {
+    if (k < hb.nq) {                                     // same for the whole workgroup
+#pragma unroll
+      for (int e = 0; e < 8; ++e) red[g][li * 8 + e] = o[k][e];
+      if (li == 0) { red[g][d] = m[k]; red[g][d + 1] = l[k]; }
+    }
+    __syncthreads();
+    if (k < hb.nq) {
+      float mstar = -INFINITY;
+      for (int i = 0; i < G; ++i) mstar = fmaxf(mstar, red[i][d]);
+      const size_t po = ((size_t)su * B + b) * H + hb.h0 + k;
+      if (mstar == -INFINITY) {                          // no token in this range
+        if (tid < d) out_part[po * d + tid] = 0.f;
+        if (tid == 0) lse_part[po] = -INFINITY;
+      } else if (tid < d) {
+        float acc = 0.f, L = 0.f;
+        for (int i = 0; i < G; ++i) {
+          const float w = fast_exp2(red[i][d] - mstar);  // 0 for a group without tokens
+          acc = fmaf(w, red[i][tid], acc);
+          L = fmaf(w, red[i][d + 1], L);
+        }
+        out_part[po * d + tid] = acc / L;
+        if (tid == 0) lse_part[po] = (mstar + log2f(L)) * kLn2;
+      }
+    }
+    __syncthreads();
+  }
+}
+
+// grid (H_kv * ceil(QG / NQ), S, B), 256 threads.  LPH = d / 8 lanes form a group; G = 256 / LPH
+// groups.  QG query heads share one key/value head (1 = every head has its own).
 // Split su covers tokens [su * per, min(T, (su + 1) * per)); group g takes every G-th of them.
-// Writes the normalised partial output [su][b][h][d] and its log-sum-exp [su][b][h].
-template <class Tag, int LPH>
+template <class Tag, int LPH, int NQ>
 __global__ void __launch_bounds__(256)
 raw_attn_partial(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K,
                  const uint16_t* __restrict__ V, float* __restrict__ out_part,
@@ -39,19 +131,27 @@ raw_attn_partial(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K,
                  float scale_log2) {
   constexpr int d = LPH * 8;
   constexpr int G = 256 / LPH;
-  __shared__ float red[G][d + 2];
-  const int h = blockIdx.x, su = blockIdx.y, b = blockIdx.z;
+  const HeadBlock hb = head_block<NQ>(blockIdx.x, QG);
+  const int su = blockIdx.y, b = blockIdx.z;
   const int tid = threadIdx.x, g = tid / LPH, li = tid % LPH;
-  const size_t HD = (size_t)(H / QG) * d;         // QG query heads share a key/value head
-  const u32x4_t qv = *(const u32x4_t*)(q + ((size_t)b * H + h) * d + li * 8);
-  const uint16_t* Kb = K + (size_t)b * T_cap * HD + (size_t)(h / QG) * d + li * 8;
-  const uint16_t* Vb = V + (size_t)b * T_cap * HD + (size_t)(h / QG) * d + li * 8;
+  const size_t HD = (size_t)(H / QG) * d;
+  u32x4_t qv[NQ];
+#pragma unroll
+  for (int k = 0; k < NQ; ++k)
+    qv[k] = *(const u32x4_t*)(q + ((size_t)b * H + hb.h0 + (k < hb.nq ? k : 0)) * d + li * 8);
+  const uint16_t* Kb = K + (size_t)b * T_cap * HD + (size_t)hb.kvh * d + li * 8;
+  const uint16_t* Vb = V + (size_t)b * T_cap * HD + (size_t)hb.kvh * d + li * 8;
   const int t0 = su * per;
   int t1 = t0 + per;
   t1 = t1 < T ? t1 : T;
 
-  float m = -INFINITY, l = 0.f;
-  float o[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  float m[NQ], l[NQ], o[NQ][8];
+#pragma unroll
+  for (int k = 0; k < NQ; ++k) {
+    m[k] = -INFINITY; l[k] = 0.f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) o[k][e] = 0.f;
+  }
   // every group runs the same number of rounds; a round's tokens beyond the range are clamped
   // to the last token of the range (an in-bounds repeat) and masked out of the softmax
   const int ntok = t1 - t0;
@@ -66,91 +166,74 @@ raw_attn_partial(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K,
       kv[u] = *(const u32x4_t*)(Kb + (size_t)tc * HD);
       vv[u] = *(const u32x4_t*)(Vb + (size_t)tc * HD);
     }
+    float vf[kUnroll][8];
+    bool valid[kUnroll];
 #pragma unroll
     for (int u = 0; u < kUnroll; ++u) {
-      float s = group_sum<LPH>(dot8<Tag>(kv[u], qv, 0.f)) * scale_log2;
-      if (tok[u] >= t1) s = -INFINITY;                 // same decision in all lanes of the group
-      const float m_new = fmaxf(m, s);
-      if (m_new > -INFINITY) {
-        const float alpha = fast_exp2(m - m_new);
-        const float pw = fast_exp2(s - m_new);
-        l = l * alpha + pw;
+      widen8<Tag>(vv[u], vf[u]);
+      valid[u] = tok[u] < t1;                            // same decision in all lanes of the group
+    }
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          o[2 * e] = o[2 * e] * alpha + pw * lo_to_f32(vv[u][e], Tag{});
-          o[2 * e + 1] = o[2 * e + 1] * alpha + pw * hi_to_f32(vv[u][e], Tag{});
-        }
-        m = m_new;
-      }
+    for (int k = 0; k < NQ; ++k) {
+      float sc[kUnroll];
+#pragma unroll
+      for (int u = 0; u < kUnroll; ++u) sc[u] = group_sum<LPH>(dot8<Tag>(kv[u], qv[k], 0.f)) * scale_log2;
+      softmax_steps<kUnroll>(sc, valid, vf, m[k], l[k], o[k]);
     }
   }
-  // ---- combine the groups
-#pragma unroll
-  for (int e = 0; e < 8; ++e) red[g][li * 8 + e] = o[e];
-  if (li == 0) { red[g][d] = m; red[g][d + 1] = l; }
-  __syncthreads();
-  float mstar = -INFINITY;
-  for (int k = 0; k < G; ++k) mstar = fmaxf(mstar, red[k][d]);
-  const size_t po = ((size_t)su * B + b) * H + h;
-  if (mstar == -INFINITY) {                              // no token in this range
-    if (tid < d) out_part[po * d + tid] = 0.f;
-    if (tid == 0) lse_part[po] = -INFINITY;
-    return;
-  }
-  if (tid < d) {
-    float acc = 0.f, L = 0.f;
-    for (int k = 0; k < G; ++k) {
-      const float w = fast_exp2(red[k][d] - mstar);       // 0 for a group without tokens
-      acc = fmaf(w, red[k][tid], acc);
-      L = fmaf(w, red[k][d + 1], L);
-    }
-    out_part[po * d + tid] = acc / L;
-    if (tid == 0) lse_part[po] = (mstar + log2f(L)) * kLn2;
-  }
+  combine_groups<LPH, NQ>(m, l, o, hb, su, b, B, H, out_part, lse_part);
 }
 
-// Key-only compression.  grid (S, H, B), 256 threads; the split index varies fastest, and S is a
-// multiple of 8 whenever there is more than one split, so the workgroups of all heads that
-// walk one token range sit on the same XCD and find its coefficient rows (shared by every
-// head) and value slices (shared by the heads of a group) in that XCD's L2.
+// Key-only compression.  grid (S, H_kv * ceil(QG / NQ), B), 256 threads; the split index varies
+// fastest, and S is a multiple of 8 whenever there is more than one split, so the workgroups
+// of all heads that walk one token range sit on the same XCD and find its coefficient rows
+// (shared by every head) in that XCD's L2.
 // Qp [B][2][H][r]: the folded queries as hi + lo 16-bit pairs, softmax scale and log2(e)
 // included.  A group of LPH lanes takes a token: lane li holds the value chunk li and the
 // coefficient chunks li, li + LPH, ... (16 bytes each; NCH of them, those at or beyond r / 8
 // re-read chunk 0 against a zero query).  KU tokens are in flight per group.
-template <class Tag, int LPH, int NCH, int KU>
+template <class Tag, int LPH, int NCH, int KU, int NQ>
 __global__ void __launch_bounds__(256)
 keyonly_partial(const uint16_t* __restrict__ Qp, const uint16_t* __restrict__ Ck,
                 const uint16_t* __restrict__ V, float* __restrict__ out_part,
                 float* __restrict__ lse_part, int B, int H, int QG, int T, int T_cap, int r, int per) {
   constexpr int d = LPH * 8;
   constexpr int G = 256 / LPH;
-  __shared__ float red[G][d + 2];
-  const int su = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  const HeadBlock hb = head_block<NQ>(blockIdx.y, QG);
+  const int su = blockIdx.x, b = blockIdx.z;
   const int tid = threadIdx.x, g = tid / LPH, li = tid % LPH;
   const size_t HD = (size_t)(H / QG) * d;
   const int nchunk = r >> 3;
-  u32x4_t qh[NCH], ql[NCH];
+  u32x4_t qh[NQ][NCH], ql[NQ][NCH];
   uint32_t coff[NCH];                               // element offset of the lane's chunks in a row
 #pragma unroll
   for (int c = 0; c < NCH; ++c) {
-    const int k = li + LPH * c;
-    const u32x4_t z = {0, 0, 0, 0};
-    qh[c] = z; ql[c] = z; coff[c] = 0;
-    if (k < nchunk) {
-      const uint16_t* qp = Qp + (((size_t)b * 2) * H + h) * r + k * 8;
-      qh[c] = *(const u32x4_t*)qp;
-      ql[c] = *(const u32x4_t*)(qp + (size_t)H * r);
-      coff[c] = (uint32_t)k * 8u;
+    const int kc = li + LPH * c;
+    coff[c] = kc < nchunk ? (uint32_t)kc * 8u : 0u;
+#pragma unroll
+    for (int k = 0; k < NQ; ++k) {
+      const u32x4_t z = {0, 0, 0, 0};
+      qh[k][c] = z; ql[k][c] = z;
+      if (kc < nchunk) {
+        const uint16_t* qp = Qp + (((size_t)b * 2) * H + hb.h0 + (k < hb.nq ? k : 0)) * r + kc * 8;
+        qh[k][c] = *(const u32x4_t*)qp;
+        ql[k][c] = *(const u32x4_t*)(qp + (size_t)H * r);
+      }
     }
   }
   const uint16_t* Cb = Ck + (size_t)b * T_cap * r;
-  const uint16_t* Vb = V + (size_t)b * T_cap * HD + (size_t)(h / QG) * d + li * 8;
+  const uint16_t* Vb = V + (size_t)b * T_cap * HD + (size_t)hb.kvh * d + li * 8;
   const int t0 = su * per;
   int t1 = t0 + per;
   t1 = t1 < T ? t1 : T;
 
-  float m = -INFINITY, l = 0.f;
-  float o[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  float m[NQ], l[NQ], o[NQ][8];
+#pragma unroll
+  for (int k = 0; k < NQ; ++k) {
+    m[k] = -INFINITY; l[k] = 0.f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) o[k][e] = 0.f;
+  }
   const int ntok = t1 - t0;
   const int rounds = ntok > 0 ? (ntok + G * KU - 1) / (G * KU) : 0;
   for (int rd = 0; rd < rounds; ++rd) {
@@ -165,50 +248,28 @@ keyonly_partial(const uint16_t* __restrict__ Qp, const uint16_t* __restrict__ Ck
       for (int c = 0; c < NCH; ++c) cv[u][c] = *(const u32x4_t*)(crow + coff[c]);
       vv[u] = *(const u32x4_t*)(Vb + (size_t)tc * HD);
     }
+    float vf[KU][8];
+    bool valid[KU];
 #pragma unroll
     for (int u = 0; u < KU; ++u) {
-      float part = 0.f;
+      widen8<Tag>(vv[u], vf[u]);
+      valid[u] = tok[u] < t1;                            // same decision in all lanes of the group
+    }
 #pragma unroll
-      for (int c = 0; c < NCH; ++c) part = dot8<Tag>(cv[u][c], ql[c], dot8<Tag>(cv[u][c], qh[c], part));
-      float s = group_sum<LPH>(part);
-      if (tok[u] >= t1) s = -INFINITY;                   // same decision in all lanes of the group
-      const float m_new = fmaxf(m, s);
-      if (m_new > -INFINITY) {
-        const float alpha = fast_exp2(m - m_new);
-        const float pw = fast_exp2(s - m_new);
-        l = l * alpha + pw;
+    for (int k = 0; k < NQ; ++k) {
+      float sc[KU];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          o[2 * e] = o[2 * e] * alpha + pw * lo_to_f32(vv[u][e], Tag{});
-          o[2 * e + 1] = o[2 * e + 1] * alpha + pw * hi_to_f32(vv[u][e], Tag{});
-        }
-        m = m_new;
+      for (int u = 0; u < KU; ++u) {
+        float part = 0.f;
+#pragma unroll
+        for (int c = 0; c < NCH; ++c)
+          part = dot8<Tag>(cv[u][c], ql[k][c], dot8<Tag>(cv[u][c], qh[k][c], part));
+        sc[u] = group_sum<LPH>(part);
       }
+      softmax_steps<KU>(sc, valid, vf, m[k], l[k], o[k]);
     }
   }
-  // ---- combine the groups (as raw_attn_partial)
-#pragma unroll
-  for (int e = 0; e < 8; ++e) red[g][li * 8 + e] = o[e];
-  if (li == 0) { red[g][d] = m; red[g][d + 1] = l; }
-  __syncthreads();
-  float mstar = -INFINITY;
-  for (int k = 0; k < G; ++k) mstar = fmaxf(mstar, red[k][d]);
-  const size_t po = ((size_t)su * B + b) * H + h;
-  if (mstar == -INFINITY) {                              // no token in this range
-    if (tid < d) out_part[po * d + tid] = 0.f;
-    if (tid == 0) lse_part[po] = -INFINITY;
-    return;
-  }
-  if (tid < d) {
-    float acc = 0.f, L = 0.f;
-    for (int k = 0; k < G; ++k) {
-      const float w = fast_exp2(red[k][d] - mstar);
-      acc = fmaf(w, red[k][tid], acc);
-      L = fmaf(w, red[k][d + 1], L);
-    }
-    out_part[po * d + tid] = acc / L;
-    if (tid == 0) lse_part[po] = (mstar + log2f(L)) * kLn2;
-  }
+  combine_groups<LPH, NQ>(m, l, o, hb, su, b, B, H, out_part, lse_part);
 }
 
 // Up to kMaxLists lists of parts; list i holds cnt[i] parts, `ostride` floats apart in out and
@@ -221,7 +282,8 @@ struct MergeArgs {
   size_t ostride, lstride;
 };
 
-// grid (ceil(H d / 256), B), 256 threads: one output element per thread.
+// grid (ceil(H d / 256), B), 256 threads: one output element per thread.  Parts are taken eight
+// at a time so that their loads are in flight together (a list can hold 64 splits).
 template <class Tag, bool OUT_F32>
 __global__ void __launch_bounds__(256)
 merge_parts(const MergeArgs a, void* __restrict__ out, float* __restrict__ lse, int H, int d) {
@@ -231,14 +293,30 @@ merge_parts(const MergeArgs a, void* __restrict__ out, float* __restrict__ lse, 
   const size_t lo = (size_t)b * H + h, oo = (size_t)b * H * d + i;
   float m = -INFINITY;
   for (int k = 0; k < kMaxLists; ++k)
-    for (int c = 0; c < a.cnt[k]; ++c) m = fmaxf(m, a.lse[k][lo + c * a.lstride]);
+    for (int c0 = 0; c0 < a.cnt[k]; c0 += 8) {
+      float v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[u] = c0 + u < a.cnt[k] ? a.lse[k][lo + (c0 + u) * a.lstride] : -INFINITY;
+#pragma unroll
+      for (int u = 0; u < 8; ++u) m = fmaxf(m, v[u]);
+    }
   float acc = 0.f, z = 0.f;
   if (m > -INFINITY) {
     for (int k = 0; k < kMaxLists; ++k)
-      for (int c = 0; c < a.cnt[k]; ++c) {
-        const float w = __expf(a.lse[k][lo + c * a.lstride] - m);
-        acc = fmaf(w, a.out[k][oo + c * a.ostride], acc);
-        z += w;
+      for (int c0 = 0; c0 < a.cnt[k]; c0 += 8) {
+        float v[8], x[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          const bool on = c0 + u < a.cnt[k];
+          v[u] = on ? a.lse[k][lo + (c0 + u) * a.lstride] : -INFINITY;
+          x[u] = on ? a.out[k][oo + (c0 + u) * a.ostride] : 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          const float w = __expf(v[u] - m);               // 0 for an empty part and beyond the list
+          acc = fmaf(w, x[u], acc);
+          z += w;
+        }
       }
     acc /= z;
   }
@@ -258,32 +336,47 @@ raw_append(const uint16_t* __restrict__ k_new, const uint16_t* __restrict__ v_ne
   if (v_new) *(u32x4_t*)(V + dst) = *(const u32x4_t*)(v_new + src);
 }
 
-int raw_splits(int B, int H, int d, int T) {
-  // about four workgroups per CU; a split holds at least one round of every group
+// Splits of the token axis for `wgs` workgroups per split: about two workgroups per CU
+// (measured: four per CU are 10 % slower at batch 64, one per CU 25 % slower at batch 8); a
+// split holds at least one round of every group.
+int raw_splits(int wgs, int d, int T) {
   const int G = 256 / (d / 8);
-  int s = (1024 + B * H - 1) / (B * H);
+  int s = (512 + wgs - 1) / wgs;
   const int by_len = (T + G * kUnroll - 1) / (G * kUnroll);
   if (s > by_len) s = by_len;
   if (s > 64) s = 64;
   return s < 1 ? 1 : s;
 }
+// Workgroups per split: one per block of query heads that share a key/value head.
+int raw_wgs(int B, int H, int H_kv) {
+  const int QG = H / H_kv, nq = heads_per_wg(QG);
+  return B * H_kv * ((QG + nq - 1) / nq);
+}
+// The workspace query does not know H_kv: it assumes the fewest workgroups per split any H_kv
+// can give (eight heads each), hence the most splits.
+int raw_splits_most(int B, int H, int d, int T) { return raw_splits(B * ((H + 7) / 8), d, T); }
 
 template <class Tag>
 void launch_raw_partial(const void* q, const void* K, const void* V, float* op, float* lp, int B, int H,
-                        int G, int d, int T, int T_cap, int S, float sm_scale, hipStream_t stream) {
+                        int QG, int d, int T, int T_cap, int S, float sm_scale, hipStream_t stream) {
   const int per = (T + S - 1) / S;
-  const dim3 grid(H, S, B);
+  const int nq = heads_per_wg(QG);
+  const dim3 grid((H / QG) * ((QG + nq - 1) / nq), S, B);
   const float sc = sm_scale * kLog2e;
-#define AP_RAW(L)                                                                               \
-  hipLaunchKernelGGL((raw_attn_partial<Tag, L>), grid, dim3(256), 0, stream, (const uint16_t*)q, \
-                     (const uint16_t*)K, (const uint16_t*)V, op, lp, B, H, G, T, T_cap, per, sc)
+#define AP_RAW2(L, N)                                                                              \
+  hipLaunchKernelGGL((raw_attn_partial<Tag, L, N>), grid, dim3(256), 0, stream, (const uint16_t*)q, \
+                     (const uint16_t*)K, (const uint16_t*)V, op, lp, B, H, QG, T, T_cap, per, sc)
+#define AP_RAW(L)                                                                                  \
+  switch (nq) { case 1: AP_RAW2(L, 1); break; case 2: AP_RAW2(L, 2); break; case 4: AP_RAW2(L, 4); break; \
+                default: AP_RAW2(L, 8); break; }
   switch (d) {
-    case 32: AP_RAW(4); break;
-    case 64: AP_RAW(8); break;
-    case 128: AP_RAW(16); break;
-    default: AP_RAW(32); break;
+    case 32: AP_RAW(4) break;
+    case 64: AP_RAW(8) break;
+    case 128: AP_RAW(16) break;
+    default: AP_RAW(32) break;
   }
 #undef AP_RAW
+#undef AP_RAW2
 }
 
 template <class Tag>
@@ -296,9 +389,16 @@ void launch_merge(const MergeArgs& a, void* out, bool out_f32, float* lse, int B
 
 // Key-only compression: about four workgroups per CU, a multiple of 8 splits (see the kernel),
 // every split at least one round of the widest variant's groups.
-int keyonly_splits(int B, int H, int d, int T) {
-  const int G = 256 / (d / 8);
-  int s = (1024 + B * H - 1) / (B * H);
+int keyonly_heads_per_wg(int QG, int nch) {
+  int nq = heads_per_wg(QG);
+  const int cap = nch <= 1 ? 8 : nch <= 2 ? 4 : nch <= 3 ? 2 : 1;   // folded queries held in registers
+  return nq < cap ? nq : cap;
+}
+int keyonly_splits(int B, int H, int H_kv, int d, int T, int r) {
+  const int LPH = d / 8, G = 256 / LPH, QG = H / H_kv;
+  const int nq = keyonly_heads_per_wg(QG, ((r >> 3) + LPH - 1) / LPH);
+  const int wgs = B * H_kv * ((QG + nq - 1) / nq);
+  int s = (1024 + wgs - 1) / wgs;
   const int by_len = (T + G * 4 - 1) / (G * 4);
   if (s > by_len) s = by_len;
   if (s > 64) s = 64;
@@ -310,19 +410,29 @@ template <class Tag, int LPH>
 ap_status launch_keyonly_partial(const uint16_t* Qp, const void* Ck, const void* V, float* op, float* lp,
                                  int B, int H, int QG, int T, int T_cap, int r, int S, hipStream_t stream) {
   const int per = (T + S - 1) / S;
-  const dim3 grid(S, H, B);
   const int nch = ((r >> 3) + LPH - 1) / LPH;          // 16-byte coefficient chunks per lane
-#define AP_KO(N, U)                                                                                  \
-  if (nch <= N) {                                                                                    \
-    hipLaunchKernelGGL((keyonly_partial<Tag, LPH, N, U>), grid, dim3(256), 0, stream, Qp,            \
-                       (const uint16_t*)Ck, (const uint16_t*)V, op, lp, B, H, QG, T, T_cap, r, per); \
-    return AP_OK;                                                                                    \
+  const int nq = keyonly_heads_per_wg(QG, nch);
+  const dim3 grid(S, (H / QG) * ((QG + nq - 1) / nq), B);
+#define AP_KO2(N, U, Q)                                                                              \
+  hipLaunchKernelGGL((keyonly_partial<Tag, LPH, N, U, Q>), grid, dim3(256), 0, stream, Qp,           \
+                     (const uint16_t*)Ck, (const uint16_t*)V, op, lp, B, H, QG, T, T_cap, r, per)
+  if (nch <= 1) {
+    switch (nq) { case 1: AP_KO2(1, 4, 1); break; case 2: AP_KO2(1, 4, 2); break; case 4: AP_KO2(1, 4, 4); break;
+                  default: AP_KO2(1, 2, 8); break; }
+    return AP_OK;
   }
-  AP_KO(1, 4) AP_KO(2, 4) AP_KO(3, 2)
-  if constexpr (LPH <= 16) { AP_KO(5, 2) }
-  if constexpr (LPH <= 8) { AP_KO(10, 1) }
-  if constexpr (LPH <= 4) { AP_KO(20, 1) }
-#undef AP_KO
+  if (nch <= 2) {
+    switch (nq) { case 1: AP_KO2(2, 4, 1); break; case 2: AP_KO2(2, 4, 2); break; default: AP_KO2(2, 2, 4); break; }
+    return AP_OK;
+  }
+  if (nch <= 3) {
+    if (nq == 1) AP_KO2(3, 2, 1); else AP_KO2(3, 2, 2);
+    return AP_OK;
+  }
+  if constexpr (LPH <= 16) { if (nch <= 5) { AP_KO2(5, 2, 1); return AP_OK; } }
+  if constexpr (LPH <= 8) { if (nch <= 10) { AP_KO2(10, 1, 1); return AP_OK; } }
+  if constexpr (LPH <= 4) { if (nch <= 20) { AP_KO2(20, 1, 1); return AP_OK; } }
+#undef AP_KO2
   set_error("ap_keyonly_attn: r=%d too large for d=%d", r, LPH * 8);
   return AP_ERR_UNSUPPORTED;
 }
@@ -330,7 +440,7 @@ ap_status launch_keyonly_partial(const uint16_t* Qp, const void* Ck, const void*
 }  // namespace
 
 size_t raw_attn_workspace(int B, int H, int d, int T) {
-  const int S = raw_splits(B, H, d, T);
+  const int S = raw_splits_most(B, H, d, T);
   return round_up((size_t)S * B * H * d * 4, 256) + round_up((size_t)S * B * H * 4, 256);
 }
 
@@ -338,7 +448,7 @@ ap_status launch_raw_attn(const void* q, const void* K, const void* V, float* ou
                           int H, int H_kv, int d, int T, int T_cap, float sm_scale, ap_dtype dt,
                           void* workspace, hipStream_t stream) {
   const int G = H / H_kv;
-  const int S = raw_splits(B, H, d, T);
+  const int S = raw_splits(raw_wgs(B, H, H_kv), d, T);        // never more than the workspace query assumes
   float* op = out;
   float* lp = lse;
   if (S > 1 || !lse) {                     // partial results (or an unwanted lse) go to the workspace
@@ -356,8 +466,8 @@ ap_status launch_raw_attn(const void* q, const void* K, const void* V, float* ou
 
 static size_t keyonly_qp_bytes(int B, int H, int r) { return round_up((size_t)B * 2 * H * r * 2, 256); }
 
-size_t keyonly_attn_workspace(int B, int H, int d, int T, int r) {
-  const int S = keyonly_splits(B, H, d, T);
+size_t keyonly_attn_workspace(int B, int H, int H_kv, int d, int T, int r) {
+  const int S = keyonly_splits(B, H, H_kv, d, T, r);
   return keyonly_qp_bytes(B, H, r) + round_up((size_t)S * B * H * d * 4, 256) +
          round_up((size_t)S * B * H * 4, 256);
 }
@@ -366,7 +476,7 @@ ap_status launch_keyonly_attn(const void* q, const void* Ck, const void* Bk, int
                               float* out, float* lse, int B, int H, int H_kv, int d, int T, int T_cap, int r,
                               float sm_scale, ap_dtype dt, void* workspace, hipStream_t stream) {
   const int QG = H / H_kv;
-  const int S = keyonly_splits(B, H, d, T);
+  const int S = keyonly_splits(B, H, H_kv, d, T, r);
   char* ws = (char*)workspace;
   uint16_t* Qp = (uint16_t*)ws;
   float* parts = (float*)(ws + keyonly_qp_bytes(B, H, r));

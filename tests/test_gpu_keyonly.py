@@ -43,7 +43,7 @@ def test_keyonly_attn(dtype, B, H, Hkv, d, r, T):
     dq, dCk, dBk, dV = (to_dev(x, dtype) for x in (q, case.Ck, case.Bk, V))
     out = torch.full((B, H, d), float("nan"), dtype=torch.float32, device="cuda")
     lse = torch.full((B, H), float("nan"), dtype=torch.float32, device="cuda")
-    ws = workspace(ap.ap_keyonly_workspace_bytes(B, H, d, T, r))
+    ws = workspace(ap.ap_keyonly_workspace_bytes(B, H, Hkv, d, T, r))
     ap.ap_keyonly_attn(dq, dCk, dBk, dV, out, ws, T=T, sm_scale=1.0 / math.sqrt(d), lse=lse)
     torch.cuda.synchronize()
     P = lambda x: oracle.promote(x, dtype)
@@ -63,7 +63,7 @@ def test_keyonly_shared_basis_and_no_lse():
     V = wl.store(rng.standard_normal((B, T, Hkv * d)), dtype)
     dq, dCk, dBk, dV = (to_dev(x, dtype) for x in (q, case.Ck, case.Bk, V))
     out = torch.empty((B, H, d), dtype=torch.float32, device="cuda")
-    ws = workspace(ap.ap_keyonly_workspace_bytes(B, H, d, T, r))
+    ws = workspace(ap.ap_keyonly_workspace_bytes(B, H, Hkv, d, T, r))
     ap.ap_keyonly_attn(dq, dCk, dBk, dV, out, ws, T=T, sm_scale=0.07)
     torch.cuda.synchronize()
     P = lambda x: oracle.promote(x, dtype)
@@ -80,7 +80,7 @@ def test_keyonly_empty_cache():
     dq, dCk, dBk, dV = (to_dev(x, dtype) for x in (q, case.Ck, case.Bk, V))
     out = torch.full((B, H, d), float("nan"), dtype=torch.float32, device="cuda")
     lse = torch.full((B, H), float("nan"), dtype=torch.float32, device="cuda")
-    ap.ap_keyonly_attn(dq, dCk, dBk, dV, out, workspace(ap.ap_keyonly_workspace_bytes(B, H, d, 0, r)), T=0,
+    ap.ap_keyonly_attn(dq, dCk, dBk, dV, out, workspace(ap.ap_keyonly_workspace_bytes(B, H, Hkv, d, 0, r)), T=0,
                        sm_scale=0.125, lse=lse)
     torch.cuda.synchronize()
     assert (out == 0).all() and torch.isneginf(lse).all()
@@ -111,7 +111,7 @@ def test_keyonly_decode_loop_with_raw_tail():
         dq, dkn, dvn = (to_dev(x, dtype) for x in (q, kn, vn))
         ap.ap_compact(dkn[:, None, :].contiguous(), None, dBk, None, dCk, None, n=1, row0=T - 1)
         ap.ap_raw_append(None, dvn, None, dV, row=T - 1)
-        ap.ap_keyonly_attn(dq, dCk, dBk, dV, out_c, workspace(ap.ap_keyonly_workspace_bytes(B, H, d, T, r)), T=T,
+        ap.ap_keyonly_attn(dq, dCk, dBk, dV, out_c, workspace(ap.ap_keyonly_workspace_bytes(B, H, Hkv, d, T, r)), T=T,
                            sm_scale=scale, lse=lse_c)
         ap.ap_raw_attn(dq, dKu, dVu, out_u, workspace(ap.ap_raw_workspace_bytes(B, H, d, T_u)), T_u=T_u,
                        sm_scale=scale, lse=lse_u)
@@ -138,5 +138,6 @@ def test_keyonly_rejects_bad_arguments():
         ap.ap_keyonly_attn(q, Ck, Bk, V, out, torch.empty(256, dtype=torch.uint8, device="cuda"), T=16, sm_scale=1.0)
     with pytest.raises(RuntimeError):                      # more tokens than the cache holds
         ap.ap_keyonly_attn(q, Ck, Bk, V, out, workspace(1 << 20), T=17, sm_scale=1.0)
-    assert ap.ap_keyonly_workspace_bytes(1, 8, 64, 16, 644) == 0      # rank not a multiple of 8
-    assert ap.ap_keyonly_workspace_bytes(1, 8, 48, 16, 64) == 0       # head width not supported
+    assert ap.ap_keyonly_workspace_bytes(1, 8, 2, 64, 16, 644) == 0      # rank not a multiple of 8
+    assert ap.ap_keyonly_workspace_bytes(1, 8, 2, 48, 16, 64) == 0    # head width not supported
+    assert ap.ap_keyonly_workspace_bytes(1, 8, 3, 64, 16, 64) == 0    # key/value heads must divide the heads

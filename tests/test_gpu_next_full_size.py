@@ -125,3 +125,29 @@ def test_grouped_queries_full_size():
         c_ref = oracle.compact(P(kn[b])[None, :], P(Bk[b]))[0]
         err = np.abs(P(Ck[b, T - 1]) - c_ref)
         assert (err <= 2.0 ** -7 * np.abs(c_ref) + 1e-5 * np.abs(c_ref).max()).all()
+
+
+def test_key_only_compression_full_size():
+    """Head layout and key rank of the text-domain experiment (32 query heads on 8 key/value heads,
+    R_k = 64), 8 sequences of 8192 tokens: the launch shape profiles/next_rows_kernel_trace.md times."""
+    from paper_2603_23914_amd import binding as ap
+    B, H, Hkv, d, r, T = 8, 32, 8, 128, 64, 8192
+    HD = Hkv * d
+    g = torch.Generator(device="cuda")
+    g.manual_seed(64)
+    sig = torch.arange(1, r + 1, device="cuda", dtype=torch.float32) ** -0.7
+    Ck = (torch.randn((B, T, r), generator=g, device="cuda") * (sig * math.sqrt(HD / float((sig ** 2).sum())))).to(torch.bfloat16)
+    Bk = (torch.randn((B, r, HD), generator=g, device="cuda") / math.sqrt(HD)).to(torch.bfloat16)
+    V = torch.randn((B, T, HD), generator=g, device="cuda").to(torch.bfloat16)
+    q = torch.randn((B, H, d), generator=g, device="cuda").to(torch.bfloat16)
+    out = torch.empty((B, H, d), dtype=torch.float32, device="cuda")
+    lse = torch.empty((B, H), dtype=torch.float32, device="cuda")
+    print("key-only compression, 8 sequences at T=8192", flush=True)
+    ap.ap_keyonly_attn(q, Ck, Bk, V, out, workspace(ap.ap_keyonly_workspace_bytes(B, H, Hkv, d, T, r)), T=T,
+                       sm_scale=1.0 / math.sqrt(d), lse=lse)
+    torch.cuda.synchronize()
+    for b in (0, 5):
+        ref, ref_lse = oracle.decode_attn_segments(P(q[b]), [dict(Ck=P(Ck[b]), Bk=P(Bk[b]), V=P(V[b]))],
+                                                   return_lse=True, kv_heads=Hkv)
+        assert_close(to_host64(out[b]), ref, "bf16", f"key-only, b={b}")
+        assert np.abs(to_host64(lse[b]) - ref_lse).max() <= 2e-3 * max(1.0, np.abs(ref_lse).max())
