@@ -33,16 +33,26 @@ __device__ __forceinline__ float dpp_add(float x) {
   const int v = __builtin_bit_cast(int, x);
   return x + __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, v, CTRL, ROW_MASK, 0xf, true));
 }
-// Sum over groups of N consecutive lanes (N = 4, 8, 16 or 32), every lane of a group
+// Sum over groups of N consecutive lanes (N = 2, 4, 8, 16 or 32), every lane of a group
 // receiving the total: butterflies inside a 16-lane row, one shuffle across rows.
 template <int N>
 __device__ __forceinline__ float group_sum(float x) {
   x = dpp_add<0xB1>(x);                  // quad_perm [1,0,3,2]
-  x = dpp_add<0x4E>(x);                  // quad_perm [2,3,0,1]
+  if (N >= 4) x = dpp_add<0x4E>(x);      // quad_perm [2,3,0,1]
   if (N >= 8) x = dpp_add<0x141>(x);     // row_half_mirror: the other quad of an 8-lane group
   if (N >= 16) x = dpp_add<0x140>(x);    // row_mirror: the other half of the row
   if (N >= 32) x += __shfl_xor(x, 16);
   return x;
+}
+// The value held by the other half of a group of N consecutive lanes (N = 4, 8, 16 or 32), for
+// values that are uniform inside each half: lane i reads its mirror image in the group.
+template <int N>
+__device__ __forceinline__ float other_half(float x) {
+  const int v = __builtin_bit_cast(int, x);
+  if (N == 4) return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, v, 0x4E, 0xf, 0xf, true));
+  if (N == 8) return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, v, 0x141, 0xf, 0xf, true));
+  if (N == 16) return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, v, 0x140, 0xf, 0xf, true));
+  return __shfl_xor(x, 16);
 }
 // Sum over the 64 lanes, returned wave-uniform: row totals, then rows 1 and 3 take the
 // previous row's total (row_bcast15), then rows 2 and 3 take lane 31's (row_bcast31); lane 63

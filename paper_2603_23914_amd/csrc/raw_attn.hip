@@ -192,7 +192,10 @@ raw_attn_partial(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K,
 // included.  A group of LPH lanes takes a token: lane li holds the value chunk li and the
 // coefficient chunks li, li + LPH, ... (16 bytes each; NCH of them, those at or beyond r / 8
 // re-read chunk 0 against a zero query).  KU tokens are in flight per group.
-template <class Tag, int LPH, int NCH, int KU, int NQ>
+// PAIR (a coefficient row fills at most half a group: r / 8 <= LPH / 2, NCH = 1): the two halves
+// of a group score two different tokens at once, each half summing its own row, and swap the
+// results; half the score arithmetic and half the coefficient loads per token.
+template <class Tag, int LPH, int NCH, int KU, int NQ, bool PAIR>
 __global__ void __launch_bounds__(256)
 keyonly_partial(const uint16_t* __restrict__ Qp, const uint16_t* __restrict__ Ck,
                 const uint16_t* __restrict__ V, float* __restrict__ out_part,
@@ -204,11 +207,14 @@ keyonly_partial(const uint16_t* __restrict__ Qp, const uint16_t* __restrict__ Ck
   const int tid = threadIdx.x, g = tid / LPH, li = tid % LPH;
   const size_t HD = (size_t)(H / QG) * d;
   const int nchunk = r >> 3;
+  static_assert(!PAIR || (NCH == 1 && KU % 2 == 0), "pairing needs one chunk per lane and whole pairs");
+  constexpr int LS = PAIR ? LPH / 2 : LPH;          // lanes that share a coefficient row
+  const int half = PAIR ? li / LS : 0;
   u32x4_t qh[NQ][NCH], ql[NQ][NCH];
   uint32_t coff[NCH];                               // element offset of the lane's chunks in a row
 #pragma unroll
   for (int c = 0; c < NCH; ++c) {
-    const int kc = li + LPH * c;
+    const int kc = (PAIR ? li % LS : li) + LPH * c;
     coff[c] = kc < nchunk ? (uint32_t)kc * 8u : 0u;
 #pragma unroll
     for (int k = 0; k < NQ; ++k) {
@@ -237,16 +243,25 @@ keyonly_partial(const uint16_t* __restrict__ Qp, const uint16_t* __restrict__ Ck
   const int ntok = t1 - t0;
   const int rounds = ntok > 0 ? (ntok + G * KU - 1) / (G * KU) : 0;
   for (int rd = 0; rd < rounds; ++rd) {
-    u32x4_t cv[KU][NCH], vv[KU];
+    constexpr int NR = PAIR ? KU / 2 : KU;             // coefficient rows a lane loads per round
+    u32x4_t cv[NR][NCH], vv[KU];
     int tok[KU];
+    // slot u of a lane holds token (rd KU + u') G + g of the split; u' = u, except that with PAIR
+    // the second half of a group swaps the two slots of every pair, so that slot 2p is the
+    // token whose coefficient row this lane's half scores
 #pragma unroll
     for (int u = 0; u < KU; ++u) {
-      tok[u] = t0 + (rd * KU + u) * G + g;
+      tok[u] = t0 + (rd * KU + (PAIR ? u ^ half : u)) * G + g;
       const int tc = tok[u] < t1 ? tok[u] : t1 - 1;      // in-bounds repeat, masked below
+      vv[u] = *(const u32x4_t*)(Vb + (size_t)tc * HD);
+    }
+#pragma unroll
+    for (int p = 0; p < NR; ++p) {
+      const int tk = tok[PAIR ? 2 * p : p];
+      const int tc = tk < t1 ? tk : t1 - 1;
       const uint16_t* crow = Cb + (size_t)tc * r;
 #pragma unroll
-      for (int c = 0; c < NCH; ++c) cv[u][c] = *(const u32x4_t*)(crow + coff[c]);
-      vv[u] = *(const u32x4_t*)(Vb + (size_t)tc * HD);
+      for (int c = 0; c < NCH; ++c) cv[p][c] = *(const u32x4_t*)(crow + coff[c]);
     }
     float vf[KU][8];
     bool valid[KU];
@@ -259,12 +274,17 @@ keyonly_partial(const uint16_t* __restrict__ Qp, const uint16_t* __restrict__ Ck
     for (int k = 0; k < NQ; ++k) {
       float sc[KU];
 #pragma unroll
-      for (int u = 0; u < KU; ++u) {
+      for (int p = 0; p < NR; ++p) {
         float part = 0.f;
 #pragma unroll
         for (int c = 0; c < NCH; ++c)
-          part = dot8<Tag>(cv[u][c], ql[k][c], dot8<Tag>(cv[u][c], qh[k][c], part));
-        sc[u] = group_sum<LPH>(part);
+          part = dot8<Tag>(cv[p][c], ql[k][c], dot8<Tag>(cv[p][c], qh[k][c], part));
+        if constexpr (PAIR) {
+          sc[2 * p] = group_sum<LS>(part);               // this half's token: slot 2p
+          sc[2 * p + 1] = other_half<LPH>(sc[2 * p]);    // the other half's token: slot 2p + 1
+        } else {
+          sc[p] = group_sum<LPH>(part);
+        }
       }
       softmax_steps<KU>(sc, valid, vf, m[k], l[k], o[k]);
     }
@@ -413,9 +433,15 @@ ap_status launch_keyonly_partial(const uint16_t* Qp, const void* Ck, const void*
   const int nch = ((r >> 3) + LPH - 1) / LPH;          // 16-byte coefficient chunks per lane
   const int nq = keyonly_heads_per_wg(QG, nch);
   const dim3 grid(S, (H / QG) * ((QG + nq - 1) / nq), B);
-#define AP_KO2(N, U, Q)                                                                              \
-  hipLaunchKernelGGL((keyonly_partial<Tag, LPH, N, U, Q>), grid, dim3(256), 0, stream, Qp,           \
+#define AP_KO3(N, U, Q, P)                                                                           \
+  hipLaunchKernelGGL((keyonly_partial<Tag, LPH, N, U, Q, P>), grid, dim3(256), 0, stream, Qp,        \
                      (const uint16_t*)Ck, (const uint16_t*)V, op, lp, B, H, QG, T, T_cap, r, per)
+#define AP_KO2(N, U, Q) AP_KO3(N, U, Q, false)
+  if (nch <= 1 && 2 * (r >> 3) <= LPH) {               // a row fills half a group: score tokens in pairs
+    switch (nq) { case 1: AP_KO3(1, 4, 1, true); break; case 2: AP_KO3(1, 4, 2, true); break;
+                  case 4: AP_KO3(1, 4, 4, true); break; default: AP_KO3(1, 2, 8, true); break; }
+    return AP_OK;
+  }
   if (nch <= 1) {
     switch (nq) { case 1: AP_KO2(1, 4, 1); break; case 2: AP_KO2(1, 4, 2); break; case 4: AP_KO2(1, 4, 4); break;
                   default: AP_KO2(1, 2, 8); break; }
@@ -433,6 +459,7 @@ ap_status launch_keyonly_partial(const uint16_t* Qp, const void* Ck, const void*
   if constexpr (LPH <= 8) { if (nch <= 10) { AP_KO2(10, 1, 1); return AP_OK; } }
   if constexpr (LPH <= 4) { if (nch <= 20) { AP_KO2(20, 1, 1); return AP_OK; } }
 #undef AP_KO2
+#undef AP_KO3
   set_error("ap_keyonly_attn: r=%d too large for d=%d", r, LPH * 8);
   return AP_ERR_UNSUPPORTED;
 }
