@@ -296,6 +296,34 @@ ap_status ap_keyonly_attn(const void* q, const void* Ck, const void* Bk,
                           void* workspace, size_t ws_bytes, void* stream);
 
 /* ------------------------------------------------------------------------
+ * ap_valueonly_attn -- the mirror image: keys kept as they are, VALUES
+ * compressed (Vtilde = Cv Bv; one of the one-sided variants the paper weighs
+ * in Sec. 4 before settling on compressed keys for the text domain):
+ *
+ *   out[b, h] = softmax_t( sm_scale * q[b, h] . K[b, t, slice(h)] ) Vtilde[b, t, slice(h)]
+ *
+ * computed as (sum_t p[h, t] Cv[t, :]) Bv[:, slice(h)]: the weighted sum runs over
+ * coefficient rows, the basis is applied once at the end.
+ *
+ *   q        [B, H, d]           dt (AP_F16 | AP_BF16)
+ *   K        [B, T_cap, H_kv*d]  dt, rows 0 .. T-1 read
+ *   Cv       [B, T_cap, r]       dt (same T_cap)
+ *   Bv       [r, H_kv*d]         dt; batch b uses Bv + b*basis_batch_stride elements (0 = shared)
+ *   out      [B, H, d] fp32; lse [B, H] fp32 or NULL.
+ *   workspace  ap_valueonly_workspace_bytes(B, H, H_kv, d, T, r) bytes, 256-byte aligned
+ *            (0 from the query = unsupported shape).
+ *   Requires T >= 1, d in {32, 64, 128, 256}, r % 8 == 0, r <= 640 (320 at d = 32),
+ *   H % H_kv == 0, H_kv*d <= 8192.  A generated token is added with ap_raw_append
+ *   (k_new only) and ap_compact (V only, n = 1).
+ * ---------------------------------------------------------------------- */
+size_t ap_valueonly_workspace_bytes(int B, int H, int H_kv, int d, int T, int r);
+ap_status ap_valueonly_attn(const void* q, const void* K, const void* Cv, const void* Bv,
+                            int64_t basis_batch_stride, float* out, float* lse,
+                            int B, int H, int H_kv, int d, int T, int T_cap, int r,
+                            float sm_scale, ap_dtype dt, void* workspace,
+                            size_t ws_bytes, void* stream);
+
+/* ------------------------------------------------------------------------
  * Timing of the dominant kernel (measurement aid, not part of the method).
  * While enabled, every ap_decode_attn / ap_decode_step call on AP_F16 / AP_BF16
  * attaches a pair of HIP events to the launch of its coefficient-streaming

@@ -57,6 +57,10 @@ _lib.ap_keyonly_workspace_bytes.restype = _sz
 _lib.ap_keyonly_workspace_bytes.argtypes = [_i] * 6
 _lib.ap_keyonly_attn.restype = _i
 _lib.ap_keyonly_attn.argtypes = [_vp] * 3 + [_c.c_int64] + [_vp] * 3 + [_i] * 7 + [_f, _i, _vp, _sz, _vp]
+_lib.ap_valueonly_workspace_bytes.restype = _sz
+_lib.ap_valueonly_workspace_bytes.argtypes = [_i] * 6
+_lib.ap_valueonly_attn.restype = _i
+_lib.ap_valueonly_attn.argtypes = [_vp] * 4 + [_c.c_int64] + [_vp] * 2 + [_i] * 7 + [_f, _i, _vp, _sz, _vp]
 _lib.ap_raw_append.restype = _i
 _lib.ap_raw_append.argtypes = [_vp] * 4 + [_i] * 5 + [_vp]
 _lib.ap_decode_workspace_bytes.restype = _sz
@@ -74,7 +78,8 @@ _lib.ap_prof_read.argtypes = [_c.POINTER(_c.c_float), _c.POINTER(_c.c_int)]
 
 EXPORTS = ("ap_compact", "ap_quantize_i8", "ap_select_ranks", "ap_select_workspace_bytes",
            "ap_decode_attn", "ap_decode_step", "ap_update_importance", "ap_decode_workspace_bytes",
-           "ap_raw_workspace_bytes", "ap_raw_attn", "ap_keyonly_workspace_bytes", "ap_keyonly_attn", "ap_merge_segments", "ap_raw_append", "ap_status_string", "ap_last_error",
+           "ap_raw_workspace_bytes", "ap_raw_attn", "ap_keyonly_workspace_bytes", "ap_keyonly_attn",
+           "ap_valueonly_workspace_bytes", "ap_valueonly_attn", "ap_merge_segments", "ap_raw_append", "ap_status_string", "ap_last_error",
            "ap_version", "ap_prof_enable", "ap_prof_read")
 
 _DT = {torch.float32: AP_F32, torch.float16: AP_F16, torch.bfloat16: AP_BF16, torch.int8: AP_I8}
@@ -221,6 +226,19 @@ def ap_keyonly_attn(q, Ck, Bk, V, out, workspace, *, T: int, sm_scale: float, ls
     _check(_lib.ap_keyonly_attn(_p(q), _p(Ck), _p(Bk), _bstride(Bk), _p(V), _p(out), _p(lse), B, H, V.shape[2] // d, d,
                                 T, Ck.shape[1], r, float(sm_scale), _DT[q.dtype], _p(workspace),
                                 workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
+def ap_valueonly_workspace_bytes(B: int, H: int, H_kv: int, d: int, T: int, r: int) -> int:
+    return _lib.ap_valueonly_workspace_bytes(B, H, H_kv, d, T, r)
+
+
+def ap_valueonly_attn(q, K, Cv, Bv, out, workspace, *, T: int, sm_scale: float, lse=None, stream=None) -> None:
+    """Raw keys, compressed values.  q [B, H, d]; K [B, T_cap, H_kv*d]; Cv [B, T_cap, r];
+    Bv [r, H_kv*d] or [B, r, H_kv*d]; out [B, H, d] fp32."""
+    B, H, d = q.shape
+    _check(_lib.ap_valueonly_attn(_p(q), _p(K), _p(Cv), _p(Bv), _bstride(Bv), _p(out), _p(lse), B, H,
+                                  K.shape[2] // d, d, T, K.shape[1], Cv.shape[2], float(sm_scale), _DT[q.dtype],
+                                  _p(workspace), workspace.numel() * workspace.element_size(), _stream(stream)))
 
 
 def ap_merge_segments(out_a, lse_a, out_b, lse_b, out, *, lse=None, stream=None) -> None:

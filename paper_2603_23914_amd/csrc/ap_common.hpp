@@ -145,6 +145,11 @@ ap_status launch_update_importance(const float* scores, const float* lse, float*
                                    int T, int T_cap, int64_t mass_stride, float alpha,
                                    hipStream_t stream);
 
+size_t valueonly_attn_workspace(int B, int H, int H_kv, int d, int T, int r);
+bool valueonly_rank_ok(int d, int r);
+ap_status launch_valueonly_attn(const void* q, const void* K, const void* Cv, const void* Bv, int64_t bstride,
+                                float* out, float* lse, int B, int H, int H_kv, int d, int T, int T_cap, int r,
+                                float sm_scale, ap_dtype dt, void* workspace, hipStream_t stream);
 size_t keyonly_attn_workspace(int B, int H, int H_kv, int d, int T, int r);
 ap_status launch_keyonly_attn(const void* q, const void* Ck, const void* Bk, int64_t bstride, const void* V,
                               float* out, float* lse, int B, int H, int H_kv, int d, int T, int T_cap, int r,

@@ -364,6 +364,42 @@ ap_status ap_keyonly_attn(const void* q, const void* Ck, const void* Bk, int64_t
                              dt, workspace, (hipStream_t)stream);
 }
 
+size_t ap_valueonly_workspace_bytes(int B, int H, int H_kv, int d, int T, int r) {
+  if (!raw_shape_ok(B, H, d) || T < 1 || r <= 0 || r % 8 != 0 || !valueonly_rank_ok(d, r)) return 0;
+  if (H_kv < 1 || H % H_kv != 0) return 0;
+  return valueonly_attn_workspace(B, H, H_kv, d, T, r);
+}
+
+ap_status ap_valueonly_attn(const void* q, const void* K, const void* Cv, const void* Bv,
+                            int64_t basis_batch_stride, float* out, float* lse, int B, int H, int H_kv,
+                            int d, int T, int T_cap, int r, float sm_scale, ap_dtype dt, void* workspace,
+                            size_t ws_bytes, void* stream) {
+  clear_error();
+  AP_REQUIRE(q && K && Cv && Bv && out && workspace, AP_ERR_INVALID_ARG, "ap_valueonly_attn: NULL pointer");
+  AP_REQUIRE(raw_shape_ok(B, H, d), AP_ERR_UNSUPPORTED,
+             "ap_valueonly_attn: need 0 < B, H <= 65535 and d in {32, 64, 128, 256}");
+  AP_REQUIRE(H_kv >= 1 && H % H_kv == 0, AP_ERR_INVALID_ARG,
+             "ap_valueonly_attn: H_kv=%d must be positive and divide H=%d", H_kv, H);
+  AP_REQUIRE(dt == AP_F16 || dt == AP_BF16, AP_ERR_UNSUPPORTED, "ap_valueonly_attn: fp16 or bf16 storage only");
+  AP_REQUIRE(r > 0 && r % 8 == 0, AP_ERR_INVALID_ARG, "ap_valueonly_attn: r=%d must be a positive multiple of 8", r);
+  AP_REQUIRE(valueonly_rank_ok(d, r), AP_ERR_UNSUPPORTED,
+             "ap_valueonly_attn: r=%d exceeds the limit for d=%d (640; 320 at d=32)", r, d);
+  AP_REQUIRE(T >= 1 && T <= T_cap, AP_ERR_INVALID_ARG, "ap_valueonly_attn: need 1 <= T <= T_cap");
+  const int64_t HDkv = (int64_t)H_kv * d;
+  AP_REQUIRE(HDkv <= 8192, AP_ERR_UNSUPPORTED, "ap_valueonly_attn: H_kv*d must be <= 8192");
+  AP_REQUIRE(basis_batch_stride == 0 || basis_batch_stride >= (int64_t)r * HDkv, AP_ERR_INVALID_ARG,
+             "ap_valueonly_attn: basis_batch_stride must be 0 or >= r*H_kv*d");
+  AP_REQUIRE(basis_batch_stride % 8 == 0, AP_ERR_INVALID_ARG,
+             "ap_valueonly_attn: basis_batch_stride must keep rows 16-byte aligned");
+  AP_REQUIRE(aligned(q, 16) && aligned(K, 16) && aligned(Cv, 16) && aligned(Bv, 16) && aligned(workspace, 256),
+             AP_ERR_INVALID_ARG, "ap_valueonly_attn: q, K, Cv, Bv must be 16-byte aligned, the workspace 256-byte");
+  AP_REQUIRE(ws_bytes >= valueonly_attn_workspace(B, H, H_kv, d, T, r), AP_ERR_WORKSPACE,
+             "ap_valueonly_attn: workspace too small (%zu < %zu bytes)", ws_bytes,
+             valueonly_attn_workspace(B, H, H_kv, d, T, r));
+  return launch_valueonly_attn(q, K, Cv, Bv, basis_batch_stride, out, lse, B, H, H_kv, d, T, T_cap, r, sm_scale,
+                               dt, workspace, (hipStream_t)stream);
+}
+
 ap_status ap_merge_segments(const float* out_a, const float* lse_a, const float* out_b,
                             const float* lse_b, void* out, float* lse, int B, int H, int d,
                             ap_dtype dt_out, void* stream) {

@@ -50,9 +50,9 @@ __device__ __forceinline__ HeadBlock head_block(int idx, int QG) {
 // The contribution of N tokens to the online softmax of one head: one maximum over the N
 // scores, at most one move of the reference exponent (the accumulators are rescaled under a
 // branch that is rarely taken after the first tokens), N independent exponentials.
-template <int N>
-__device__ __forceinline__ void softmax_steps(const float (&s)[N], const bool (&valid)[N], const float (&vf)[N][8],
-                                              float& m, float& l, float (&o)[8]) {
+template <int N, int W = 8>
+__device__ __forceinline__ void softmax_steps(const float (&s)[N], const bool (&valid)[N], const float (&vf)[N][W],
+                                              float& m, float& l, float (&o)[W]) {
   float mx = -INFINITY;
 #pragma unroll
   for (int u = 0; u < N; ++u) mx = fmaxf(mx, valid[u] ? s[u] : -INFINITY);
@@ -60,7 +60,7 @@ __device__ __forceinline__ void softmax_steps(const float (&s)[N], const bool (&
     const float alpha = fast_exp2(m - mx);               // 0 on the first tokens (m = -inf)
     l *= alpha;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) o[e] *= alpha;
+    for (int e = 0; e < W; ++e) o[e] *= alpha;
     m = mx;
   }
 #pragma unroll
@@ -68,7 +68,7 @@ __device__ __forceinline__ void softmax_steps(const float (&s)[N], const bool (&
     const float pw = valid[u] ? fast_exp2(s[u] - m) : 0.f;   // m is finite wherever a token is valid
     l += pw;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) o[e] = fmaf(pw, vf[u][e], o[e]);
+    for (int e = 0; e < W; ++e) o[e] = fmaf(pw, vf[u][e], o[e]);
   }
 }
 
@@ -292,6 +292,114 @@ keyonly_partial(const uint16_t* __restrict__ Qp, const uint16_t* __restrict__ Ck
   combine_groups<LPH, NQ>(m, l, o, hb, su, b, B, H, out_part, lse_part);
 }
 
+// Value-only compression (raw keys, compressed values): scores as in raw_attn_partial, the
+// weighted sum runs over the value COEFFICIENT rows, U[h, j] = sum_t p[h, t] C_v[t, j], and the
+// expansion through B_v is left to merge_expand.  grid (S, H_kv * ceil(QG / NQ), B) as for
+// key-only compression (the coefficient rows are shared by every head).  Lane li of a group
+// holds the key chunk li of a token and the coefficient chunks li, li + LPH, ... (NCH of them),
+// i.e. columns [c d + 8 li, c d + 8 li + 8) for c < NCH.  Writes what merge_expand reads: per
+// split and head the reference exponent (log2 units) and the sum, part_ml [B][S][H][2], and the
+// unnormalised coefficient sums part_U [B][S][H][r].
+template <class Tag, int LPH, int NCH, int KU, int NQ>
+__global__ void __launch_bounds__(256)
+valueonly_partial(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K,
+                  const uint16_t* __restrict__ Cv, float* __restrict__ part_ml,
+                  float* __restrict__ part_U, int H, int QG, int T, int T_cap, int r, int per,
+                  float scale_log2) {
+  constexpr int d = LPH * 8;
+  constexpr int G = 256 / LPH;
+  constexpr int W = NCH * 8;
+  __shared__ float red[G][d + 2];
+  const HeadBlock hb = head_block<NQ>(blockIdx.y, QG);
+  const int su = blockIdx.x, S = gridDim.x, b = blockIdx.z;
+  const int tid = threadIdx.x, g = tid / LPH, li = tid % LPH;
+  const size_t HD = (size_t)(H / QG) * d;
+  const int nchunk = r >> 3;
+  u32x4_t qv[NQ];
+#pragma unroll
+  for (int k = 0; k < NQ; ++k)
+    qv[k] = *(const u32x4_t*)(q + ((size_t)b * H + hb.h0 + (k < hb.nq ? k : 0)) * d + li * 8);
+  uint32_t coff[NCH];                               // chunks beyond the row re-read chunk 0; never stored
+#pragma unroll
+  for (int c = 0; c < NCH; ++c) coff[c] = li + LPH * c < nchunk ? (uint32_t)(li + LPH * c) * 8u : 0u;
+  const uint16_t* Kb = K + (size_t)b * T_cap * HD + (size_t)hb.kvh * d + li * 8;
+  const uint16_t* Cb = Cv + (size_t)b * T_cap * r;
+  const int t0 = su * per;
+  int t1 = t0 + per;
+  t1 = t1 < T ? t1 : T;
+
+  float m[NQ], l[NQ], u[NQ][W];
+#pragma unroll
+  for (int k = 0; k < NQ; ++k) {
+    m[k] = -INFINITY; l[k] = 0.f;
+#pragma unroll
+    for (int e = 0; e < W; ++e) u[k][e] = 0.f;
+  }
+  const int ntok = t1 - t0;
+  const int rounds = ntok > 0 ? (ntok + G * KU - 1) / (G * KU) : 0;
+  for (int rd = 0; rd < rounds; ++rd) {
+    u32x4_t kv[KU], cv[KU][NCH];
+    bool valid[KU];
+#pragma unroll
+    for (int t = 0; t < KU; ++t) {
+      const int tok = t0 + (rd * KU + t) * G + g;
+      valid[t] = tok < t1;                               // same decision in all lanes of the group
+      const int tc = valid[t] ? tok : t1 - 1;            // in-bounds repeat, masked in the softmax
+      kv[t] = *(const u32x4_t*)(Kb + (size_t)tc * HD);
+      const uint16_t* crow = Cb + (size_t)tc * r;
+#pragma unroll
+      for (int c = 0; c < NCH; ++c) cv[t][c] = *(const u32x4_t*)(crow + coff[c]);
+    }
+    float cf[KU][W];
+#pragma unroll
+    for (int t = 0; t < KU; ++t)
+#pragma unroll
+      for (int c = 0; c < NCH; ++c)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          cf[t][c * 8 + 2 * e] = lo_to_f32(cv[t][c][e], Tag{});
+          cf[t][c * 8 + 2 * e + 1] = hi_to_f32(cv[t][c][e], Tag{});
+        }
+#pragma unroll
+    for (int k = 0; k < NQ; ++k) {
+      float sc[KU];
+#pragma unroll
+      for (int t = 0; t < KU; ++t) sc[t] = group_sum<LPH>(dot8<Tag>(kv[t], qv[k], 0.f)) * scale_log2;
+      softmax_steps<KU, W>(sc, valid, cf, m[k], l[k], u[k]);
+    }
+  }
+  // ---- combine the groups: one head and one block of d columns at a time
+#pragma unroll
+  for (int k = 0; k < NQ; ++k) {
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+      if (k < hb.nq) {                                   // same for the whole workgroup
+#pragma unroll
+        for (int e = 0; e < 8; ++e) red[g][li * 8 + e] = u[k][c * 8 + e];
+        if (li == 0) { red[g][d] = m[k]; red[g][d + 1] = l[k]; }
+      }
+      __syncthreads();
+      if (k < hb.nq && tid < d) {
+        float mstar = -INFINITY;
+        for (int i = 0; i < G; ++i) mstar = fmaxf(mstar, red[i][d]);
+        float acc = 0.f, L = 0.f;
+        if (mstar > -INFINITY) {
+          for (int i = 0; i < G; ++i) {
+            const float w = fast_exp2(red[i][d] - mstar);   // 0 for a group without tokens
+            acc = fmaf(w, red[i][tid], acc);
+            L = fmaf(w, red[i][d + 1], L);
+          }
+        }
+        const size_t ps = ((size_t)b * S + su) * H + hb.h0 + k;
+        const int col = c * d + tid;
+        if (col < r) part_U[ps * r + col] = acc;
+        if (c == 0 && tid == 0) { part_ml[ps * 2] = mstar; part_ml[ps * 2 + 1] = L; }
+      }
+      __syncthreads();
+    }
+  }
+}
+
 // Up to kMaxLists lists of parts; list i holds cnt[i] parts, `ostride` floats apart in out and
 // `lstride` floats apart in lse (a single [B, H, d] segment is a list of one part).
 constexpr int kMaxLists = 2;
@@ -464,6 +572,58 @@ ap_status launch_keyonly_partial(const uint16_t* Qp, const void* Ck, const void*
   return AP_ERR_UNSUPPORTED;
 }
 
+// Value-only compression: heads per workgroup (their coefficient sums live in registers),
+// splits as for key-only compression.
+int valueonly_heads_per_wg(int QG, int nch) {
+  int nq = heads_per_wg(QG);
+  const int cap = nch <= 1 ? 8 : nch <= 2 ? 4 : nch <= 3 ? 2 : 1;
+  return nq < cap ? nq : cap;
+}
+int valueonly_splits(int B, int H, int H_kv, int d, int T, int r) {
+  const int LPH = d / 8, G = 256 / LPH, QG = H / H_kv;
+  const int nq = valueonly_heads_per_wg(QG, ((r >> 3) + LPH - 1) / LPH);
+  const int wgs = B * H_kv * ((QG + nq - 1) / nq);
+  int s = (1024 + wgs - 1) / wgs;
+  const int by_len = (T + G * 4 - 1) / (G * 4);
+  if (s > by_len) s = by_len;
+  if (s > 64) s = 64;
+  if (s > 1) s = (s + 7) & ~7;
+  return s < 1 ? 1 : s;
+}
+
+template <class Tag, int LPH>
+ap_status launch_valueonly_partial(const void* q, const void* K, const void* Cv, float* ml, float* U, int B,
+                                   int H, int QG, int T, int T_cap, int r, int S, float sm_scale,
+                                   hipStream_t stream) {
+  const int per = (T + S - 1) / S;
+  const int nch = ((r >> 3) + LPH - 1) / LPH;
+  const int nq = valueonly_heads_per_wg(QG, nch);
+  const dim3 grid(S, (H / QG) * ((QG + nq - 1) / nq), B);
+  const float sc = sm_scale * kLog2e;
+#define AP_VO(N, U_, Q)                                                                             \
+  hipLaunchKernelGGL((valueonly_partial<Tag, LPH, N, U_, Q>), grid, dim3(256), 0, stream,           \
+                     (const uint16_t*)q, (const uint16_t*)K, (const uint16_t*)Cv, ml, U, H, QG, T,  \
+                     T_cap, r, per, sc)
+  if (nch <= 1) {
+    switch (nq) { case 1: AP_VO(1, 4, 1); break; case 2: AP_VO(1, 4, 2); break; case 4: AP_VO(1, 4, 4); break;
+                  default: AP_VO(1, 2, 8); break; }
+    return AP_OK;
+  }
+  if (nch <= 2) {
+    switch (nq) { case 1: AP_VO(2, 2, 1); break; case 2: AP_VO(2, 2, 2); break; default: AP_VO(2, 2, 4); break; }
+    return AP_OK;
+  }
+  if (nch <= 3) {
+    if (nq == 1) AP_VO(3, 1, 1); else AP_VO(3, 1, 2);
+    return AP_OK;
+  }
+  if constexpr (LPH <= 16) { if (nch <= 5) { AP_VO(5, 1, 1); return AP_OK; } }
+  if constexpr (LPH <= 8) { if (nch <= 10) { AP_VO(10, 1, 1); return AP_OK; } }
+#undef AP_VO
+  set_error("ap_valueonly_attn: r=%d too large for d=%d", r, LPH * 8);
+  return AP_ERR_UNSUPPORTED;
+}
+
 }  // namespace
 
 size_t raw_attn_workspace(int B, int H, int d, int T) {
@@ -528,6 +688,58 @@ ap_status launch_keyonly_attn(const void* q, const void* Ck, const void* Bk, int
     launch_merge<F16Tag>(a, out, true, lse, B, H, d, stream);
   }
   return check_launch("ap_keyonly_attn");
+}
+
+// value-only compression: [part_ml | part_U | merged ml | merged U (only with more than 8 splits)]
+constexpr int kValueOnlyInlineSplits = 8;               // what merge_expand merges by itself
+struct ValueOnlyWs { size_t ml, u, mml, mu, total; };
+static ValueOnlyWs valueonly_layout(int B, int H, int H_kv, int d, int T, int r) {
+  const int S = valueonly_splits(B, H, H_kv, d, T, r);
+  ValueOnlyWs w;
+  size_t off = 0;
+  w.ml = off; off += round_up((size_t)B * S * H * 2 * 4, 256);
+  w.u = off; off += round_up((size_t)B * S * H * r * 4, 256);
+  w.mml = off; off += round_up((size_t)B * H * 2 * 4, 256);
+  w.mu = off; off += S > kValueOnlyInlineSplits ? round_up((size_t)B * H * r * 4, 256) : 0;
+  w.total = off;
+  return w;
+}
+size_t valueonly_attn_workspace(int B, int H, int H_kv, int d, int T, int r) {
+  return valueonly_layout(B, H, H_kv, d, T, r).total;
+}
+bool valueonly_rank_ok(int d, int r) { return r <= (d >= 128 ? 640 : d == 64 ? 640 : 320); }
+
+ap_status launch_valueonly_attn(const void* q, const void* K, const void* Cv, const void* Bv, int64_t bstride,
+                                float* out, float* lse, int B, int H, int H_kv, int d, int T, int T_cap, int r,
+                                float sm_scale, ap_dtype dt, void* workspace, hipStream_t stream) {
+  const int QG = H / H_kv;
+  const int S = valueonly_splits(B, H, H_kv, d, T, r);
+  const ValueOnlyWs w = valueonly_layout(B, H, H_kv, d, T, r);
+  char* ws = (char*)workspace;
+  float* ml = (float*)(ws + w.ml);
+  float* U = (float*)(ws + w.u);
+  ap_status st = AP_OK;
+#define AP_VL(TAG)                                                                                            \
+  switch (d) {                                                                                                \
+    case 32: st = launch_valueonly_partial<TAG, 4>(q, K, Cv, ml, U, B, H, QG, T, T_cap, r, S, sm_scale, stream); break;   \
+    case 64: st = launch_valueonly_partial<TAG, 8>(q, K, Cv, ml, U, B, H, QG, T, T_cap, r, S, sm_scale, stream); break;   \
+    case 128: st = launch_valueonly_partial<TAG, 16>(q, K, Cv, ml, U, B, H, QG, T, T_cap, r, S, sm_scale, stream); break; \
+    default: st = launch_valueonly_partial<TAG, 32>(q, K, Cv, ml, U, B, H, QG, T, T_cap, r, S, sm_scale, stream); break;  \
+  }
+  if (dt == AP_F16) { AP_VL(F16Tag) } else { AP_VL(BF16Tag) }
+#undef AP_VL
+  if (st != AP_OK) return st;
+  int S_exp = S;
+  if (S > kValueOnlyInlineSplits) {
+    float* ml1 = (float*)(ws + w.mml);
+    float* U1 = (float*)(ws + w.mu);
+    st = launch_merge_splits(ml, U, ml1, U1, nullptr, B, H, r, S, stream);
+    if (st != AP_OK) return st;
+    ml = ml1; U = U1; S_exp = 1;
+  }
+  st = launch_merge_expand(dt, true, ml, U, Bv, bstride, out, lse, B, H, H_kv, d, r, S_exp, stream);
+  if (st != AP_OK) return st;
+  return check_launch("ap_valueonly_attn");
 }
 
 ap_status launch_merge_segments(const float* out_a, const float* lse_a, const float* out_b,
