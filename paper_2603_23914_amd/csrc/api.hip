@@ -67,7 +67,7 @@ const char* ap_status_string(ap_status s) {
 
 const char* ap_last_error(void) { return g_err; }
 
-int ap_version(void) { return 300; }   // 0.3.0: H_kv, scores, raw segment, merge entries
+int ap_version(void) { return 400; }   // 0.4.0: key-only and value-only compression
 
 void ap_prof_enable(int on) {
   g_prof_on = on != 0;

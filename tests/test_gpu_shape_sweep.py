@@ -97,3 +97,57 @@ def test_shape_sweep(dtype, B, H, d, r, T, mode):
         torch.cuda.synchronize()
         ref = oracle.decode_attn_batched(P(q), ck, cv, P(case.Bk), P(case.Bv), T, absorbed=True)
     assert_close(to_host64(out), ref, dtype, f"{mode} H={H} d={d} r={r} T={T}")
+
+
+def one_sided_cases(n, seed):
+    rng = np.random.default_rng(seed)
+    cases = []
+    while len(cases) < n:
+        d = int(rng.choice([32, 64, 128, 256]))
+        Hkv = int(rng.integers(1, min(16, 4096 // d) + 1))
+        G = int(rng.choice([1, 1, 2, 3, 4, 5, 8, 12]))          # query heads per key/value head
+        r = 8 * int(rng.integers(1, 81))
+        mode = str(rng.choice(["raw", "key-only", "value-only"]))
+        if r > Hkv * d or (mode == "value-only" and d == 32 and r > 320):
+            continue
+        T = int(rng.choice([1, 2, 15, 16, 17, 63, 64, 65, 127, 129, 255, 257, 400, 513, 700, 1100]))
+        B = int(rng.integers(1, 4))
+        dtype = str(rng.choice(["f16", "bf16"]))
+        cases.append((mode, dtype, B, Hkv * G, Hkv, d, r, T))
+    return cases
+
+
+@pytest.mark.parametrize("mode,dtype,B,H,Hkv,d,r,T", one_sided_cases(60, 2025))
+def test_one_sided_shape_sweep(mode, dtype, B, H, Hkv, d, r, T):
+    """The flash-decode entry points (uncompressed segment, key-only and value-only compression)
+    over head groupings of every workgroup shape (1, 2, 4 and 8 heads per workgroup, with and
+    without a partial last block), ranks that are any multiple of 8, token counts around the
+    round and split boundaries."""
+    from paper_2603_23914_amd import binding as ap
+    print(f"sweep {mode} {dtype} B={B} H={H} Hkv={Hkv} d={d} r={r} T={T}", flush=True)
+    case = wl.decode_case(dtype, B, Hkv, d, r, T, steps=0, seed=Hkv * 17 + T, append=False)
+    rng = wl.rng_for(2025, H, T, r)
+    q = wl.store(rng.standard_normal((B, H, d)), dtype)
+    K = wl.store(rng.standard_normal((B, T, Hkv * d)), dtype)
+    V = wl.store(rng.standard_normal((B, T, Hkv * d)), dtype)
+    P = lambda x: oracle.promote(x, dtype)
+    dq, dK, dV = (to_dev(x, dtype) for x in (q, K, V))
+    out = torch.full((B, H, d), float("nan"), dtype=torch.float32, device="cuda")
+    lse = torch.full((B, H), float("nan"), dtype=torch.float32, device="cuda")
+    scale = 1.0 / math.sqrt(d)
+    if mode == "raw":
+        ap.ap_raw_attn(dq, dK, dV, out, workspace(ap.ap_raw_workspace_bytes(B, H, d, T)), T_u=T, sm_scale=scale, lse=lse)
+        seg = lambda b: dict(K=P(K)[b], V=P(V)[b])
+    elif mode == "key-only":
+        ap.ap_keyonly_attn(dq, to_dev(case.Ck, dtype), to_dev(case.Bk, dtype), dV, out,
+                           workspace(ap.ap_keyonly_workspace_bytes(B, H, Hkv, d, T, r)), T=T, sm_scale=scale, lse=lse)
+        seg = lambda b: dict(Ck=P(case.Ck)[b], Bk=P(case.Bk)[b], V=P(V)[b])
+    else:
+        ap.ap_valueonly_attn(dq, dK, to_dev(case.Cv, dtype), to_dev(case.Bv, dtype), out,
+                             workspace(ap.ap_valueonly_workspace_bytes(B, H, Hkv, d, T, r)), T=T, sm_scale=scale, lse=lse)
+        seg = lambda b: dict(K=P(K)[b], Cv=P(case.Cv)[b], Bv=P(case.Bv)[b])
+    torch.cuda.synchronize()
+    for b in range(B):
+        ref, ref_lse = oracle.decode_attn_segments(P(q)[b], [seg(b)], return_lse=True, kv_heads=Hkv)
+        assert_close(to_host64(out[b]), ref, dtype, f"{mode} b={b}")
+        assert np.abs(to_host64(lse[b]) - ref_lse).max() <= 2e-3 * max(1.0, np.abs(ref_lse).max())
