@@ -253,6 +253,31 @@ def main():
     step_bytes = alg_bytes + 2.0 * B * R * HD * 2
     extra = {"step_effective_GBps": step_bytes / (dt / K) / 1e9, "step_algorithmic_bytes": step_bytes}
 
+    # ---- yardsticks measured in this run on this machine: a plain device copy (torch) and a plain
+    #      streaming read (the library's probe kernel) over one layer's coefficient cache
+    src = layers1[0]["Ck"].view(torch.uint8).reshape(-1)
+    gran = ap.ap_probe_read_granule()
+    nb = src.numel() // gran * gran
+    sink = torch.zeros(8192, dtype=torch.int32, device="cuda")
+    dst = torch.empty(nb, dtype=torch.uint8, device="cuda")
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+    for _ in range(3):
+        ap.ap_probe_read(src, nb, sink)
+        dst.copy_(src[:nb])
+    ev[0].record()
+    for _ in range(10):
+        ap.ap_probe_read(src, nb, sink)
+    ev[1].record()
+    ev[2].record()
+    for _ in range(10):
+        dst.copy_(src[:nb])
+    ev[3].record()
+    torch.cuda.synchronize()
+    extra["stream_read_GBps"] = nb * 10 / (ev[0].elapsed_time(ev[1]) * 1e-3) / 1e9
+    extra["device_copy_GBps"] = 2.0 * nb * 10 / (ev[2].elapsed_time(ev[3]) * 1e-3) / 1e9
+    extra["yardstick_bytes"] = nb
+    del dst, src
+
     # ---- optional: the same step over L independent layers back to back (distinct buffers,
     #      so nothing survives in the 256 MB last-level cache between steps)
     if args.layers > 1:

@@ -338,6 +338,20 @@ ap_status ap_valueonly_attn(const void* q, const void* K, const void* Cv, const 
 void ap_prof_enable(int on);
 ap_status ap_prof_read(float* total_ms, int* launches);
 
+/* ------------------------------------------------------------------------
+ * Streaming-read yardstick (measurement aid, not part of the method).
+ * ap_probe_read enqueues one kernel that reads `bytes` bytes from src with
+ * plain 16-byte loads (2048 workgroups, eight loads in flight per thread) and
+ * writes the XOR of what each wave read to sink; timing it gives the read bandwidth a kernel
+ * can actually reach on this machine, next to which the bandwidth-bound
+ * kernels of the library are reported.
+ *   src    device buffer of at least `bytes` bytes, 16-byte aligned
+ *   bytes  positive multiple of ap_probe_read_granule()
+ *   sink   device buffer of 8192 uint32 (32 KiB), overwritten
+ * ---------------------------------------------------------------------- */
+size_t ap_probe_read_granule(void);
+ap_status ap_probe_read(const void* src, size_t bytes, void* sink, void* stream);
+
 /* Host strings; ap_last_error() is thread-local and describes the most recent
  * non-AP_OK return on the calling thread ("" if none). */
 const char* ap_status_string(ap_status s);

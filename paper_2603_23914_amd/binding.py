@@ -71,6 +71,10 @@ _lib.ap_last_error.restype = _c.c_char_p
 _lib.ap_last_error.argtypes = []
 _lib.ap_version.restype = _i
 _lib.ap_version.argtypes = []
+_lib.ap_probe_read_granule.restype = _sz
+_lib.ap_probe_read_granule.argtypes = []
+_lib.ap_probe_read.restype = _i
+_lib.ap_probe_read.argtypes = [_vp, _sz, _vp, _vp]
 _lib.ap_prof_enable.restype = None
 _lib.ap_prof_enable.argtypes = [_i]
 _lib.ap_prof_read.restype = _i
@@ -80,7 +84,7 @@ EXPORTS = ("ap_compact", "ap_quantize_i8", "ap_select_ranks", "ap_select_workspa
            "ap_decode_attn", "ap_decode_step", "ap_update_importance", "ap_decode_workspace_bytes",
            "ap_raw_workspace_bytes", "ap_raw_attn", "ap_keyonly_workspace_bytes", "ap_keyonly_attn",
            "ap_valueonly_workspace_bytes", "ap_valueonly_attn", "ap_merge_segments", "ap_raw_append", "ap_status_string", "ap_last_error",
-           "ap_version", "ap_prof_enable", "ap_prof_read")
+           "ap_version", "ap_prof_enable", "ap_prof_read", "ap_probe_read_granule", "ap_probe_read")
 
 _DT = {torch.float32: AP_F32, torch.float16: AP_F16, torch.bfloat16: AP_BF16, torch.int8: AP_I8}
 
@@ -254,6 +258,15 @@ def ap_raw_append(k_new, v_new, K, V, *, row: int, stream=None) -> None:
     B, T_cap, HD = X.shape
     _check(_lib.ap_raw_append(_p(k_new), _p(v_new), _p(K), _p(V), B, HD, row, T_cap, _DT[X.dtype],
                               _stream(stream)))
+
+
+def ap_probe_read_granule() -> int:
+    return _lib.ap_probe_read_granule()
+
+
+def ap_probe_read(src, nbytes: int, sink, *, stream=None) -> None:
+    """Plain streaming read of the first nbytes of src (measurement aid); sink: 8192 int32."""
+    _check(_lib.ap_probe_read(_p(src), nbytes, _p(sink), _stream(stream)))
 
 
 def ap_prof_enable(on: bool) -> None:

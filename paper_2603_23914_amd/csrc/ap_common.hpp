@@ -145,6 +145,10 @@ ap_status launch_update_importance(const float* scores, const float* lse, float*
                                    int T, int T_cap, int64_t mass_stride, float alpha,
                                    hipStream_t stream);
 
+// measurement aid (probe.hip): plain streaming read
+size_t probe_read_granule();
+ap_status launch_probe_read(const void* src, size_t bytes, uint32_t* sink, hipStream_t stream);
+
 size_t valueonly_attn_workspace(int B, int H, int H_kv, int d, int T, int r);
 bool valueonly_rank_ok(int d, int r);
 ap_status launch_valueonly_attn(const void* q, const void* K, const void* Cv, const void* Bv, int64_t bstride,

@@ -69,6 +69,17 @@ const char* ap_last_error(void) { return g_err; }
 
 int ap_version(void) { return 400; }   // 0.4.0: key-only and value-only compression
 
+size_t ap_probe_read_granule(void) { return probe_read_granule(); }
+
+ap_status ap_probe_read(const void* src, size_t bytes, void* sink, void* stream) {
+  clear_error();
+  AP_REQUIRE(src && sink, AP_ERR_INVALID_ARG, "ap_probe_read: NULL pointer");
+  AP_REQUIRE(bytes > 0 && bytes % probe_read_granule() == 0, AP_ERR_INVALID_ARG,
+             "ap_probe_read: bytes must be a positive multiple of %zu", probe_read_granule());
+  AP_REQUIRE(aligned(src, 16) && aligned(sink, 4), AP_ERR_INVALID_ARG, "ap_probe_read: misaligned pointer");
+  return launch_probe_read(src, bytes, (uint32_t*)sink, (hipStream_t)stream);
+}
+
 void ap_prof_enable(int on) {
   g_prof_on = on != 0;
   g_prof_used = 0;

@@ -3,6 +3,7 @@ call, reports a time that lies inside the wall time of those calls, and leaves r
 import math
 import time
 
+import numpy as np
 import pytest
 import torch
 
@@ -41,3 +42,27 @@ def test_kernel_timer_counts_launches_and_stays_inside_wall_time():
     ms, n = ap.ap_prof_read()
     ap.ap_prof_enable(False)
     assert n == 0 and ms == 0.0
+
+
+def test_stream_read_probe_reads_every_byte():
+    """The yardstick kernel XORs what it reads: flipping one word anywhere in the buffer flips the
+    same bits of exactly one of its outputs."""
+    from paper_2603_23914_amd import binding as ap
+    gran = ap.ap_probe_read_granule()
+    g = torch.Generator(device="cuda")
+    g.manual_seed(5)
+    buf = torch.randint(-2 ** 31, 2 ** 31 - 1, (gran // 4,), generator=g, dtype=torch.int32, device="cuda")
+    s0 = torch.zeros(8192, dtype=torch.int32, device="cuda")
+    s1 = torch.zeros_like(s0)
+    ap.ap_probe_read(buf, gran, s0)
+    for pos in (0, gran // 8 + 5, gran // 4 - 1):
+        buf[pos] ^= 0x5A5A
+        ap.ap_probe_read(buf, gran, s1)
+        torch.cuda.synchronize()
+        diff = (s0 ^ s1).cpu().numpy()
+        assert (diff != 0).sum() == 1 and int(diff[diff != 0][0]) == 0x5A5A
+        buf[pos] ^= 0x5A5A
+    ref = np.bitwise_xor.reduce(buf.cpu().numpy().view(np.uint32))
+    assert np.bitwise_xor.reduce(s0.cpu().numpy().view(np.uint32)) == ref
+    with pytest.raises(RuntimeError):
+        ap.ap_probe_read(buf, gran - 16, s1)
