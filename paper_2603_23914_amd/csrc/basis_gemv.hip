@@ -387,14 +387,33 @@ __global__ void __launch_bounds__(128) expand_append(const ExpandParams p) {
   if (tid < H) {
     const int h = tid;
     const size_t pb = (size_t)b * S * H + h;
+    // the splits' (reference exponent, sum) pairs, eight loads in flight at a time
     float m = -INFINITY;
-    for (int s = 0; s < S; ++s) m = fmaxf(m, p.part_ml[(pb + (size_t)s * H) * 2]);
+    for (int s0 = 0; s0 < S; s0 += 8) {
+      float v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[u] = s0 + u < S ? p.part_ml[(pb + (size_t)(s0 + u) * H) * 2] : -INFINITY;
+#pragma unroll
+      for (int u = 0; u < 8; ++u) m = fmaxf(m, v[u]);
+    }
     float L = 0.f, wlast = 0.f;
-    for (int s = 0; s < S; ++s) {
-      const float ws = fast_exp2(p.part_ml[(pb + (size_t)s * H) * 2] - m);
-      L += p.part_ml[(pb + (size_t)s * H) * 2 + 1] * ws;
-      if (wsp_fits) wsp[s * H + h] = ws;
-      wlast = ws;
+    for (int s0 = 0; s0 < S; s0 += 8) {
+      float v[8], lv[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const bool on = s0 + u < S;
+        v[u] = on ? p.part_ml[(pb + (size_t)(s0 + u) * H) * 2] : -INFINITY;
+        lv[u] = on ? p.part_ml[(pb + (size_t)(s0 + u) * H) * 2 + 1] : 0.f;
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        if (s0 + u < S) {
+          const float ws = fast_exp2(v[u] - m);
+          L += lv[u] * ws;
+          if (wsp_fits) wsp[(s0 + u) * H + h] = ws;
+          wlast = ws;
+        }
+      }
     }
     mstar[h] = m;
     invL[h] = 1.0f / L;
@@ -409,8 +428,15 @@ __global__ void __launch_bounds__(128) expand_append(const ExpandParams p) {
     if (j0 + jl < r) {
       const size_t pb = (size_t)b * S * H + h;
       if (wsp_fits) {
-        for (int s = 0; s < S; ++s)
-          acc = fmaf(wsp[s * H + h], p.part_U[(pb + (size_t)s * H) * r + j0 + jl], acc);
+        for (int s0 = 0; s0 < S; s0 += 8) {              // eight loads in flight at a time
+          float uv[8];
+#pragma unroll
+          for (int u = 0; u < 8; ++u)
+            uv[u] = s0 + u < S ? p.part_U[(pb + (size_t)(s0 + u) * H) * r + j0 + jl] : 0.f;
+#pragma unroll
+          for (int u = 0; u < 8; ++u)
+            if (s0 + u < S) acc = fmaf(wsp[(s0 + u) * H + h], uv[u], acc);
+        }
       } else {
         const float m = mstar[h];
         for (int s = 0; s < S; ++s)
@@ -494,7 +520,15 @@ reduce_out(const float* __restrict__ pout, void* __restrict__ out, int HD, int n
   const int b = blockIdx.y, c = (blockIdx.x * 256 + threadIdx.x) * 4;
   if (c >= HD) return;
   f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
-  for (int k = 0; k < nob; ++k) acc += *(const f32x4_t*)(pout + ((size_t)b * nob + k) * HD + c);
+  int k = 0;
+  for (; k + 8 <= nob; k += 8) {                         // eight loads in flight, summed in block order
+    f32x4_t v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = *(const f32x4_t*)(pout + ((size_t)b * nob + k + u) * HD + c);
+#pragma unroll
+    for (int u = 0; u < 8; ++u) acc += v[u];
+  }
+  for (; k < nob; ++k) acc += *(const f32x4_t*)(pout + ((size_t)b * nob + k) * HD + c);
   if (OUT_F32) {
     *(f32x4_t*)((float*)out + (size_t)b * HD + c) = acc;
   } else {
@@ -638,11 +672,14 @@ int basis_rows_per_wave(int B, int r) {
   return rpw < 4 ? 4 : (rpw > 32 ? 32 : rpw);
 }
 // expand_append: about four two-wave workgroups per CU in one round, but never more than 16 row
-// blocks per sequence (each block writes an HD-wide partial output that reduce_out reads back)
+// blocks per sequence at large batches (each block writes an HD-wide partial output that
+// reduce_out reads back); small batches, whose partial outputs are small anyway, take up to
+// 64 blocks so that the launch still fills the chip.
 int expand_rows_per_pair(int B, int r) {
   int rpw = (int)(((int64_t)B * r + 1023) / 1024);
-  const int floor16 = (r + 15) / 16;
-  if (rpw < floor16) rpw = floor16;
+  const int nob_max = B >= 32 ? 16 : B >= 16 ? 32 : 64;
+  const int floor_rows = (r + nob_max - 1) / nob_max;
+  if (rpw < floor_rows) rpw = floor_rows;
   return rpw < 4 ? 4 : (rpw > 64 ? 64 : rpw);
 }
 

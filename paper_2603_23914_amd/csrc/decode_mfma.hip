@@ -1227,6 +1227,8 @@ int device_cus() {
 constexpr int kMaxTilesPerSplit = 128;   // bounds the LDS index table of rank-ragged launches
 constexpr int kMaxGroups = 8;
 constexpr int kInlineMergeSplits = 8;    // more splits than this are merged by their own kernel
+constexpr int kFusedInlineSplits = 16;   // the same limit inside a fused step (measured: merging
+                                         // 16 splits inline saves 6-8 us, merging 32 costs 5)
 
 int choose_nsplit(int B, int T) {
   const int ntiles = (T + kTile - 1) / kTile;
@@ -1426,7 +1428,10 @@ ap_status run_decode(const DecodeArgs& a) {
   st = dispatch_attn<Tag, SPLIT>(p, a.B, a.stream);
   if (st != AP_OK) return st;
   int S_exp = S;
-  if (S > kInlineMergeSplits) {            // small batch, many splits: merge them in parallel first
+  // many splits (small batches): merge_expand takes at most kInlineMergeSplits, so they are merged
+  // by a kernel of their own first; the fused step's expansion merges up to kFusedInlineSplits
+  // itself (its row blocks partition the columns, so no column is merged twice)
+  if (S > (one_pass_v ? kFusedInlineSplits : kInlineMergeSplits)) {
     float* ml1 = (float*)(ws + wl.mml);
     float* U1 = (float*)(ws + wl.mu);
     st = launch_merge_splits(ml, U, ml1, U1, one_pass_v ? (float*)(ws + wl.pn) : nullptr, a.B, a.H, a.r,
