@@ -142,3 +142,33 @@ def test_raw_segment_grouped_queries(dtype, B, H, Hkv, d, T_u):
         ref, ref_lse = oracle.raw_attn(P(q)[b], P(K)[b], P(V)[b], return_lse=True, kv_heads=Hkv)
         assert_close(to_host64(out[b]), ref, dtype, f"raw grouped queries b={b}")
         assert np.abs(to_host64(lse[b]) - ref_lse).max() <= 2e-3 * max(1.0, np.abs(ref_lse).max())
+
+
+def test_int8_coefficients_grouped_queries():
+    """int8 coefficients with grouped queries: the dequantising kernel sees folded queries and
+    coefficient sums per query head only, the head map lives in the fold and the expansion."""
+    from paper_2603_23914_amd import binding as ap
+    dtype, B, H, Hkv, d, r, T = "f16", 2, 32, 8, 128, 256, 300
+    case, qs = gqa_case(dtype, B, H, Hkv, d, r, T, 0, 56, False)
+    q = qs[0]
+    Ck8 = np.zeros(case.Ck.shape, np.int8)
+    Cv8 = np.zeros(case.Cv.shape, np.int8)
+    sk = np.zeros(case.Ck.shape[:2] + (r // 64,), np.float16)
+    sv = np.zeros_like(sk)
+    ck = np.zeros(case.Ck.shape)
+    cv = np.zeros(case.Cv.shape)
+    for b in range(B):
+        Ck8[b, :T], sk[b, :T] = oracle.quantize_i8(case.Ck[b, :T])
+        Cv8[b, :T], sv[b, :T] = oracle.quantize_i8(case.Cv[b, :T])
+        ck[b, :T] = oracle.dequantize_i8(Ck8[b, :T], sk[b, :T])
+        cv[b, :T] = oracle.dequantize_i8(Cv8[b, :T], sv[b, :T])
+    dq, dBk, dBv = (to_dev(x, dtype) for x in (q, case.Bk, case.Bv))
+    out = torch.empty((B, H, d), dtype=torch.float32, device="cuda")
+    ws = workspace(ap.ap_decode_workspace_bytes(B, H, d, T, r, ap.AP_F16))
+    ap.ap_decode_attn(dq, torch.from_numpy(Ck8).cuda(), torch.from_numpy(Cv8).cuda(), dBk, dBv, out, ws, T=T,
+                      sm_scale=1.0 / math.sqrt(d), scale_k=torch.from_numpy(sk).cuda(),
+                      scale_v=torch.from_numpy(sv).cuda())
+    torch.cuda.synchronize()
+    P = lambda x: oracle.promote(x, dtype)
+    ref = oracle.decode_attn_batched(P(q), ck, cv, P(case.Bk), P(case.Bv), T, absorbed=True, kv_heads=Hkv)
+    assert_close(to_host64(out), ref, dtype, "int8 grouped queries")
