@@ -31,6 +31,7 @@ sys.path.insert(0, ROOT)
 B, H, D, R, T0 = 64, 40, 128, 640, 4224
 HD = H * D
 HBM_PEAK_GBS = 8000.0
+PROF_EVERY = 4          # the dominant kernel carries timing events on every 4th step of the timed region
 
 
 def gpu_inputs(torch, t_cap, layers, seed=0):
@@ -223,8 +224,8 @@ def main():
     # ---- one layer: warm-up, then EXACTLY K timed steps
     run_steps(torch, ap, layers1, q, knew, vnew, out, ws, T0, W)
     torch.cuda.synchronize()
-    ap.ap_prof_enable(True)
-    t0 = time.perf_counter()
+    ap.ap_prof_enable(PROF_EVERY)       # kernel events on every 4th step: each timed launch costs the
+    t0 = time.perf_counter()            # step about 5 us of pipeline bubble, which is part of `value`
     run_steps(torch, ap, layers1, q, knew, vnew, out, ws, T0 + W, K)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
@@ -235,7 +236,7 @@ def main():
     ms_per_step = dt / K * 1e3
     value = B * K / dt
     # dominant kernel: attn_partial streams C_k and C_v rows 0..T-1 of every sequence once
-    t_mean = T0 + W + (K - 1) / 2.0 + 1
+    t_mean = T0 + W + (PROF_EVERY * ((K - 1) // PROF_EVERY)) / 2.0 + 1     # mean T over the timed launches
     alg_bytes = 2.0 * B * t_mean * R * 2
     k_avg_ms = k_ms / max(k_n, 1)
     achieved = alg_bytes / (k_avg_ms * 1e-3) / 1e9 if k_n else None
@@ -247,7 +248,8 @@ def main():
                 traffic = float(line.split()[1])
     roofline = {"bound": "hbm", "kernel": "attn_partial", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": (achieved / HBM_PEAK_GBS) if achieved else None, "traffic": traffic,
-                "kernel_avg_us": k_avg_ms * 1e3, "launches": k_n, "algorithmic_bytes_per_launch": alg_bytes}
+                "kernel_avg_us": k_avg_ms * 1e3, "launches": k_n, "timed_every": PROF_EVERY,
+                "algorithmic_bytes_per_launch": alg_bytes}
     # bytes the whole step must move (coefficients once; per-sequence B_k once: append + fold in
     # one pass; B_v once: append + expansion in one pass; partials and vectors are small)
     step_bytes = alg_bytes + 2.0 * B * R * HD * 2

@@ -331,7 +331,10 @@ ap_status ap_valueonly_attn(const void* q, const void* K, const void* Cv, const 
  * end, not the gap to the kernel before it, so the time is the one a kernel
  * trace reports).  ap_prof_read waits for the last pair and returns the summed
  * kernel time in milliseconds and the number of pairs since ap_prof_enable(1),
- * which also clears the records.  At most 4096 launches are recorded (later ones are
+ * which also clears the records.  ap_prof_enable(n) with n > 1 times every n-th
+ * launch only (the first, the (n+1)-th, ...): the events cost a few microseconds
+ * of pipeline bubble per timed launch, which a throughput measurement running
+ * at the same time would otherwise pay on every step; ap_prof_enable(0) is off.  At most 4096 launches are recorded (later ones are
  * not timed).  Events are host-side handles owned by the library; no device
  * memory is allocated.  Not thread-safe.
  * ---------------------------------------------------------------------- */

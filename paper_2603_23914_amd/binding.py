@@ -269,8 +269,9 @@ def ap_probe_read(src, nbytes: int, sink, *, stream=None) -> None:
     _check(_lib.ap_probe_read(_p(src), nbytes, _p(sink), _stream(stream)))
 
 
-def ap_prof_enable(on: bool) -> None:
-    _lib.ap_prof_enable(1 if on else 0)
+def ap_prof_enable(on) -> None:
+    """False / 0: off; True / 1: time every launch; n > 1: every n-th launch."""
+    _lib.ap_prof_enable(int(on))
 
 
 def ap_prof_read():

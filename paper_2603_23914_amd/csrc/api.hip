@@ -31,10 +31,12 @@ ap_status check_launch(const char* what) {
 static bool g_prof_on = false;
 static std::vector<hipEvent_t> g_prof_ev;   // start, stop, start, stop, ...
 static size_t g_prof_used = 0;
+static unsigned g_prof_every = 1, g_prof_seen = 0;
 constexpr size_t kProfMax = 2 * 4096;
 
 bool prof_events(hipEvent_t* start, hipEvent_t* stop) {
   if (!g_prof_on || g_prof_used + 2 > kProfMax) return false;
+  if (g_prof_seen++ % g_prof_every != 0) return false;     // only every n-th launch carries events
   while (g_prof_ev.size() < g_prof_used + 2) {
     hipEvent_t e;
     if (hipEventCreate(&e) != hipSuccess) return false;
@@ -81,7 +83,9 @@ ap_status ap_probe_read(const void* src, size_t bytes, void* sink, void* stream)
 }
 
 void ap_prof_enable(int on) {
-  g_prof_on = on != 0;
+  g_prof_on = on > 0;
+  g_prof_every = on > 0 ? (unsigned)on : 1u;
+  g_prof_seen = 0;
   g_prof_used = 0;
 }
 

@@ -38,6 +38,12 @@ def test_kernel_timer_counts_launches_and_stays_inside_wall_time():
     assert 0.0 < ms < wall_ms
     assert ms / n < 1.0                     # a few MB of coefficients: microseconds, not milliseconds
     assert torch.equal(out0, out1)
+    ap.ap_prof_enable(3)                    # every third launch: 7 launches -> the 1st, 4th and 7th
+    for _ in range(7):
+        ap.ap_decode_attn(dq, dCk, dCv, dBk, dBv, out1, ws, T=T, sm_scale=scale)
+    ms3, n3 = ap.ap_prof_read()
+    ap.ap_prof_enable(False)
+    assert n3 == 3 and 0.0 < ms3 / n3 < 1.0
     ap.ap_prof_enable(True)                 # enabling clears the records
     ms, n = ap.ap_prof_read()
     ap.ap_prof_enable(False)
