@@ -150,3 +150,57 @@ def test_decode_loop_with_uncompressed_tail():
                 dict(K=K_h[b], V=V_h[b])])
             assert_close(to_host64(out[b]), ref, dtype, f"step {step} b={b}")
     assert torch.equal(dK[:, :steps].cpu(), torch.stack([to_dev(wl.step_new_token(case, s, P(case.Bk), P(case.Bv))[0], dtype).cpu() for s in range(steps)], dim=1))
+
+
+def test_tail_joins_the_compressed_cache_every_tp_steps():
+    """Alg. 1's periodic step with the bases kept: generated tokens wait in the uncompressed
+    segment; once T_p of them are there they are projected onto the sequence's bases in one
+    ap_compact call (rows appended to the coefficient cache) and the segment starts over.  The
+    oracle keeps the same three things: the coefficient rows the GPU holds (read back bit for bit
+    after every compaction), the raw tail, and the definition of attention over their union."""
+    from paper_2603_23914_amd import binding as ap
+    dtype, B, H, d, r, T0, T_p, steps = "f16", 2, 16, 64, 128, 150, 3, 8
+    case = wl.decode_case(dtype, B, H, d, r, T0, steps=steps, seed=47, append=True)
+    P = lambda x: oracle.promote(x, dtype)
+    dCk, dCv, dBk, dBv = (to_dev(x, dtype) for x in (case.Ck, case.Cv, case.Bk, case.Bv))
+    dK = torch.zeros((B, T_p, H * d), dtype=TORCH_DT[dtype], device="cuda")
+    dV = torch.zeros_like(dK)
+    out_c = torch.empty((B, H, d), dtype=torch.float32, device="cuda")
+    lse_c = torch.empty((B, H), dtype=torch.float32, device="cuda")
+    out_u, lse_u, out = torch.empty_like(out_c), torch.empty_like(lse_c), torch.empty_like(out_c)
+    scale = 1.0 / math.sqrt(d)
+    T, T_u = T0, 0                      # rows in the compressed cache, rows in the tail
+    tail_k, tail_v = [], []
+    compactions = 0
+    for step in range(steps):
+        kn, vn = wl.step_new_token(case, step, P(case.Bk), P(case.Bv))
+        q = wl.step_query(case, step)
+        dq, dkn, dvn = (to_dev(x, dtype) for x in (q, kn, vn))
+        ap.ap_raw_append(dkn, dvn, dK, dV, row=T_u)
+        T_u += 1
+        tail_k.append(P(kn))
+        tail_v.append(P(vn))
+        print(f"T_p loop step {step}: {T} compressed + {T_u} raw tokens", flush=True)
+        ap.ap_decode_attn(dq, dCk, dCv, dBk, dBv, out_c, workspace(ap.ap_decode_workspace_bytes(B, H, d, T, r, ap.AP_F16)),
+                          T=T, sm_scale=scale, lse=lse_c)
+        ap.ap_raw_attn(dq, dK, dV, out_u, workspace(ap.ap_raw_workspace_bytes(B, H, d, T_u)), T_u=T_u, sm_scale=scale,
+                       lse=lse_u)
+        ap.ap_merge_segments(out_c, lse_c, out_u, lse_u, out)
+        torch.cuda.synchronize()
+        Ck_h, Cv_h = P(dCk.cpu().numpy()), P(dCv.cpu().numpy())
+        for b in range(B):
+            ref = oracle.decode_attn_segments(P(q)[b], [
+                dict(Ck=Ck_h[b, :T], Cv=Cv_h[b, :T], Bk=P(case.Bk)[b], Bv=P(case.Bv)[b]),
+                dict(K=np.stack([k[b] for k in tail_k]), V=np.stack([v[b] for v in tail_v]))])
+            assert_close(to_host64(out[b]), ref, dtype, f"step {step} b={b}")
+        if T_u == T_p:                  # the trigger: the tail joins the compressed cache
+            ap.ap_compact(dK, dV, dBk, dBv, dCk, dCv, n=T_p, row0=T)
+            torch.cuda.synchronize()
+            c_ref = oracle.compact(np.stack([k[0] for k in tail_k]), P(case.Bk)[0])
+            got = P(dCk.cpu().numpy())[0, T:T + T_p]
+            assert np.abs(got - c_ref).max() <= 2.0 ** -10 * np.abs(c_ref).max() + 1e-6
+            T += T_p
+            T_u = 0
+            tail_k, tail_v = [], []
+            compactions += 1
+    assert compactions == 2 and T == T0 + 6 and T_u == 2
