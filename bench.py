@@ -255,6 +255,22 @@ def main():
     step_bytes = alg_bytes + 2.0 * B * R * HD * 2
     extra = {"step_effective_GBps": step_bytes / (dt / K) / 1e9, "step_algorithmic_bytes": step_bytes}
 
+    # ---- secondary mode: one basis pair per layer shared by the whole batch (basis_batch_stride 0)
+    #      instead of one per sequence; same coefficient caches, same step
+    shared = [{"Ck": layers1[0]["Ck"], "Cv": layers1[0]["Cv"],
+               "Bk": layers1[0]["Bk"][0].contiguous(), "Bv": layers1[0]["Bv"][0].contiguous()}]
+    ks = max(4, min(K, 32))
+    run_steps(torch, ap, shared, q, knew, vnew, out, ws, T0, 2)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run_steps(torch, ap, shared, q, knew, vnew, out, ws, T0 + 2, ks)
+    torch.cuda.synchronize()
+    dts = time.perf_counter() - t0
+    sh_bytes = 2.0 * B * (T0 + 2 + (ks - 1) / 2.0 + 1) * R * 2 + 2.0 * R * HD * 2
+    extra["shared_basis"] = {"steps": ks, "ms_per_step": dts / ks * 1e3, "tokens_per_s": B * ks / dts,
+                             "step_effective_GBps": sh_bytes / (dts / ks) / 1e9}
+    del shared
+
     # ---- yardsticks measured in this run on this machine: a plain device copy (torch) and a plain
     #      streaming read (the library's probe kernel) over one layer's coefficient cache
     src = layers1[0]["Ck"].view(torch.uint8).reshape(-1)
