@@ -266,7 +266,8 @@ ap_status ap_raw_append(const void* k_new, const void* v_new, void* K, void* V,
 
 /* ------------------------------------------------------------------------
  * ap_keyonly_attn -- decode attention over a cache whose KEYS are compressed
- * while its values are kept as they are (paper Sec. 4, text-domain experiment:
+ * while its values are kept as they are (paper appendix "Analysis of Textual
+ * Token Compression", the text-domain experiment:
  * values need a higher rank than keys there, so only the keys are compressed,
  * R_k = 64).  The same segment algebra as above applies: keys Ktilde = Ck Bk,
  *
@@ -297,8 +298,8 @@ ap_status ap_keyonly_attn(const void* q, const void* Ck, const void* Bk,
 
 /* ------------------------------------------------------------------------
  * ap_valueonly_attn -- the mirror image: keys kept as they are, VALUES
- * compressed (Vtilde = Cv Bv; one of the one-sided variants the paper weighs
- * in Sec. 4 before settling on compressed keys for the text domain):
+ * compressed (Vtilde = Cv Bv; the other one-sided variant, which the same
+ * appendix passage sets aside because values need the higher rank):
  *
  *   out[b, h] = softmax_t( sm_scale * q[b, h] . K[b, t, slice(h)] ) Vtilde[b, t, slice(h)]
  *

@@ -260,7 +260,8 @@ def decode_attn_segments(q, segments, sm_scale=None, return_lse: bool = False, k
       keys    {"Ck", "Bk"[, "rank_k"]}  coefficients and own basis   or  {"K"} [T, H_kv*d]
       values  {"Cv", "Bv"[, "rank_v"]}                                or  {"V"} [T, H_kv*d]
     A segment with compressed keys and raw values is the key-only compression
-    of the text-domain experiment (Sec. 4, LongBench: R_k = 64, values kept).
+    of the text-domain experiment (appendix "Analysis of Textual Token
+    Compression": R_k = 64, values kept).
     """
     q = np.asarray(q, np.float64)
     H, d = q.shape

@@ -9,8 +9,8 @@
 //                      the heads), several tokens in flight per group, online softmax per
 //                      group and head, groups combined through LDS at the end.
 //   keyonly_partial    the same flash-decode for a cache whose KEYS are compressed (coefficients
-//                      C_k [B, T_cap, r] and a basis) while its values stay raw (Sec. 4, the
-//                      text-domain experiment compresses keys only, R_k = 64): the basis is
+//                      C_k [B, T_cap, r] and a basis) while its values stay raw (appendix "Analysis of
+//                      Textual Token Compression": keys only, R_k = 64): the basis is
 //                      folded into the query beforehand, a token's score is the dot product
 //                      of its coefficient row with the folded query of the head.
 //   merge_parts        attention over disjoint token sets -> attention over their union:

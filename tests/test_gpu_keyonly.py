@@ -1,5 +1,5 @@
-"""GPU parity: key-only compression (compressed keys, raw values: the text-domain experiment of
-Sec. 4 compresses keys only, R_k = 64) against the fp64 oracle's definition (rebuild the keys,
+"""GPU parity: key-only compression (compressed keys, raw values: the text-domain experiment of the
+appendix "Analysis of Textual Token Compression" compresses keys only, R_k = 64) against the fp64 oracle's definition (rebuild the keys,
 attend), alone, joined with an uncompressed tail, and over a decode loop that appends."""
 import math
 

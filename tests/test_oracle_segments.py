@@ -180,7 +180,7 @@ def test_grouped_queries_head_mapping_is_by_consecutive_groups():
             assert np.abs(out[h] - c["V"][:, kv * d:(kv + 1) * d].mean(axis=0)).max() < 1e-12
 
 
-# ---- one-sided compression (Sec. 4, text-domain experiment: keys at R_k = 64, values kept) ----
+# ---- one-sided compression (appendix "Analysis of Textual Token Compression": keys at R_k = 64, values kept) ----
 def test_key_only_segment_brute_force_loops():
     """Scalar loops: keys rebuilt from their coefficients, values taken as stored, grouped heads."""
     rng = np.random.default_rng(21)
