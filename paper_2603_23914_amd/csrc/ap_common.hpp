@@ -154,6 +154,12 @@ bool valueonly_rank_ok(int d, int r);
 ap_status launch_valueonly_attn(const void* q, const void* K, const void* Cv, const void* Bv, int64_t bstride,
                                 float* out, float* lse, int B, int H, int H_kv, int d, int T, int T_cap, int r,
                                 float sm_scale, ap_dtype dt, void* workspace, hipStream_t stream);
+// key-only compression on the matrix cores (keyonly_mfma.hip)
+bool keyonly_mfma_applies(int H, int H_kv, int d, int r);
+int keyonly_mfma_splits(int B, int H_kv, int T);
+ap_status launch_keyonly_mfma(ap_dtype dt, const uint16_t* Qp, const void* Ck, const void* V, float* out_part,
+                              float* lse_part, int B, int H, int H_kv, int T, int T_cap, int r, int S,
+                              hipStream_t stream);
 size_t keyonly_attn_workspace(int B, int H, int H_kv, int d, int T, int r);
 ap_status launch_keyonly_attn(const void* q, const void* Ck, const void* Bk, int64_t bstride, const void* V,
                               float* out, float* lse, int B, int H, int H_kv, int d, int T, int T_cap, int r,

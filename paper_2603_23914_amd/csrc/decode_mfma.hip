@@ -25,6 +25,7 @@
 // turned into fp16 values code*scale in registers, right in front of the MFMA that uses
 // them; everything else is the fp16 path.
 #include "ap_common.hpp"
+#include "mfma_ops.hpp"
 #include <hip/hip_ext.h>
 
 #include <cstdlib>
@@ -37,20 +38,6 @@ constexpr int kHalf = 16;        // rows per LDS ring unit (half a tile of one m
 constexpr float kLazy = 8.0f;    // log2 slack before the softmax reference moves
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
-
-template <class Tag> struct Mfma;
-template <> struct Mfma<F16Tag> {
-  static __device__ __forceinline__ f32x4_t run(u32x4_t a, u32x4_t b, f32x4_t c) {
-    return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8_t, a),
-                                                  __builtin_bit_cast(f16x8_t, b), c, 0, 0, 0);
-  }
-};
-template <> struct Mfma<BF16Tag> {
-  static __device__ __forceinline__ f32x4_t run(u32x4_t a, u32x4_t b, f32x4_t c) {
-    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a),
-                                                   __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
-  }
-};
 
 __device__ __forceinline__ void dma16(const void* gsrc, void* lds_uniform) {
   __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gsrc,
@@ -89,19 +76,6 @@ __device__ __forceinline__ void split_hi_lo(float x, uint16_t& hi, uint16_t& lo)
   lo = f32_to_bits(x - bits_to_f32(hi, Tag{}), Tag{});
 }
 
-
-// Two fp32 -> packed pair of 16-bit storage values, round to nearest even (hardware converts).
-typedef __attribute__((__vector_size__(2 * sizeof(float)))) float f32x2_t;
-typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2_t;
-typedef __attribute__((__vector_size__(2 * sizeof(_Float16)))) _Float16 f16x2_t;
-__device__ __forceinline__ uint32_t cvt_pack(float lo, float hi, BF16Tag) {
-  f32x2_t v = {lo, hi};
-  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
-}
-__device__ __forceinline__ uint32_t cvt_pack(float lo, float hi, F16Tag) {
-  f32x2_t v = {lo, hi};
-  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, f16x2_t));
-}
 
 // int8 codes -> fp16 values code*scale, two at a time.  A byte b (two's complement) xor 0x80
 // is b+128 as an unsigned byte u; the fp16 bit pattern 0x6400|u is exactly 1024+u, so

@@ -653,38 +653,49 @@ ap_status launch_raw_attn(const void* q, const void* K, const void* V, float* ou
 
 static size_t keyonly_qp_bytes(int B, int H, int r) { return round_up((size_t)B * 2 * H * r * 2, 256); }
 
+// parts of a key-only call: the matrix-core kernel writes four per split (one per wave)
+static int keyonly_parts(int B, int H, int H_kv, int d, int T, int r) {
+  return keyonly_mfma_applies(H, H_kv, d, r) ? 4 * keyonly_mfma_splits(B, H_kv, T)
+                                             : keyonly_splits(B, H, H_kv, d, T, r);
+}
+
 size_t keyonly_attn_workspace(int B, int H, int H_kv, int d, int T, int r) {
-  const int S = keyonly_splits(B, H, H_kv, d, T, r);
-  return keyonly_qp_bytes(B, H, r) + round_up((size_t)S * B * H * d * 4, 256) +
-         round_up((size_t)S * B * H * 4, 256);
+  const int P = keyonly_parts(B, H, H_kv, d, T, r);
+  return keyonly_qp_bytes(B, H, r) + round_up((size_t)P * B * H * d * 4, 256) +
+         round_up((size_t)P * B * H * 4, 256);
 }
 
 ap_status launch_keyonly_attn(const void* q, const void* Ck, const void* Bk, int64_t bstride, const void* V,
                               float* out, float* lse, int B, int H, int H_kv, int d, int T, int T_cap, int r,
                               float sm_scale, ap_dtype dt, void* workspace, hipStream_t stream) {
   const int QG = H / H_kv;
-  const int S = keyonly_splits(B, H, H_kv, d, T, r);
+  const bool mfma = keyonly_mfma_applies(H, H_kv, d, r);
+  const int P = keyonly_parts(B, H, H_kv, d, T, r);
   char* ws = (char*)workspace;
   uint16_t* Qp = (uint16_t*)ws;
   float* parts = (float*)(ws + keyonly_qp_bytes(B, H, r));
-  float* lparts = (float*)(ws + keyonly_qp_bytes(B, H, r) + round_up((size_t)S * B * H * d * 4, 256));
+  float* lparts = (float*)(ws + keyonly_qp_bytes(B, H, r) + round_up((size_t)P * B * H * d * 4, 256));
   // q' = scale * log2(e) * B_k[:, slice] q_h for every head, written as hi + lo pairs
   ap_status st = launch_fold_heads(dt, Bk, bstride, q, Qp, B, H, H_kv, H, d, r, sm_scale * kLog2e, stream);
   if (st != AP_OK) return st;
-  float* op = S > 1 ? parts : out;
-  float* lp = (S > 1 || !lse) ? lparts : lse;
+  float* op = P > 1 ? parts : out;
+  float* lp = (P > 1 || !lse) ? lparts : lse;
+  if (mfma) {
+    st = launch_keyonly_mfma(dt, Qp, Ck, V, op, lp, B, H, H_kv, T, T_cap, r, P / 4, stream);
+  } else {
 #define AP_KL(TAG)                                                                                          \
   switch (d) {                                                                                              \
-    case 32: st = launch_keyonly_partial<TAG, 4>(Qp, Ck, V, op, lp, B, H, QG, T, T_cap, r, S, stream); break;  \
-    case 64: st = launch_keyonly_partial<TAG, 8>(Qp, Ck, V, op, lp, B, H, QG, T, T_cap, r, S, stream); break;  \
-    case 128: st = launch_keyonly_partial<TAG, 16>(Qp, Ck, V, op, lp, B, H, QG, T, T_cap, r, S, stream); break; \
-    default: st = launch_keyonly_partial<TAG, 32>(Qp, Ck, V, op, lp, B, H, QG, T, T_cap, r, S, stream); break; \
+    case 32: st = launch_keyonly_partial<TAG, 4>(Qp, Ck, V, op, lp, B, H, QG, T, T_cap, r, P, stream); break;  \
+    case 64: st = launch_keyonly_partial<TAG, 8>(Qp, Ck, V, op, lp, B, H, QG, T, T_cap, r, P, stream); break;  \
+    case 128: st = launch_keyonly_partial<TAG, 16>(Qp, Ck, V, op, lp, B, H, QG, T, T_cap, r, P, stream); break; \
+    default: st = launch_keyonly_partial<TAG, 32>(Qp, Ck, V, op, lp, B, H, QG, T, T_cap, r, P, stream); break; \
   }
-  if (dt == AP_F16) { AP_KL(F16Tag) } else { AP_KL(BF16Tag) }
+    if (dt == AP_F16) { AP_KL(F16Tag) } else { AP_KL(BF16Tag) }
 #undef AP_KL
+  }
   if (st != AP_OK) return st;
-  if (S > 1) {
-    MergeArgs a{{op, nullptr}, {lp, nullptr}, {S, 0}, (size_t)B * H * d, (size_t)B * H};
+  if (P > 1) {
+    MergeArgs a{{op, nullptr}, {lp, nullptr}, {P, 0}, (size_t)B * H * d, (size_t)B * H};
     launch_merge<F16Tag>(a, out, true, lse, B, H, d, stream);
   }
   return check_launch("ap_keyonly_attn");

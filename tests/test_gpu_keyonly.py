@@ -35,6 +35,13 @@ def keyonly_case(dtype, B, H, Hkv, d, r, T, seed, T_cap=None):
     ("f16", 2, 40, 40, 128, 640, 200),
     ("bf16", 1, 6, 3, 64, 192, 1),          # a single token
     ("f16", 1, 64, 8, 128, 384, 2100),      # many splits
+    # head width 128 with ranks up to 128 and at most 16 heads per group: the matrix-core kernel
+    ("f16", 2, 32, 8, 128, 64, 257),        # a tile with a single token at the end
+    ("bf16", 3, 16, 1, 128, 72, 95),        # 16 heads on one key/value head; rank no multiple of 32
+    ("f16", 2, 10, 2, 128, 8, 33),          # five heads per group, one coefficient chunk
+    ("bf16", 1, 24, 8, 128, 128, 5000),     # several splits, four rank steps
+    ("f16", 4, 4, 4, 128, 96, 31),          # every head its own keys; less than one tile
+    ("bf16", 2, 34, 2, 128, 64, 300),       # 17 heads per group: back on the vector kernel
 ])
 def test_keyonly_attn(dtype, B, H, Hkv, d, r, T):
     from paper_2603_23914_amd import binding as ap
