@@ -132,9 +132,15 @@ def test_decode_step_equals_compact_then_attend(dtype, B, H, d, r, T0):
     ("bf16", 2, 40, 128, 64, 31),       # a single partial tile
     ("f16", 1, 16, 64, 128, 1),
     ("bf16", 64, 40, 128, 128, 520),    # every split has tiles in some slots only
+    ("f16", 2, 64, 64, 64, 200),        # four head tiles at rank 64
+    ("bf16", 2, 32, 128, 128, 32),      # the appended token opens a new tile
+    ("f16", 8, 32, 128, 64, 4000),      # whole groups of 8 sequences, long
 ])
 def test_decode_small_rank(dtype, B, H, d, r, T):
-    """Ranks up to 128 run the token-split variant of the kernel (score waves own whole tiles)."""
+    """Ranks 64 and 128: calls without logits run attn_small (waves work alone on whole tiles),
+    calls that want the logits the token-split variant of the two-role kernel; both are checked
+    against the oracle, on the plain call and on the fused step (whose newest token's value row
+    does not exist while the kernel runs)."""
     from paper_2603_23914_amd import binding as ap
     case = wl.decode_case(dtype, B, H, d, r, T, steps=1, seed=27, append=True,
                           batch_subset=range(min(B, 3)), shared_basis=B > 3)
@@ -151,6 +157,7 @@ def test_decode_small_rank(dtype, B, H, d, r, T):
     P = lambda x: oracle.promote(x, dtype)
     kn, vn = wl.step_new_token(case, 0, P(case.Bk), P(case.Bv))
     dq, dCk, dCv, dBk, dBv, dkn, dvn = (to_dev(x, dtype) for x in (q, case.Ck, case.Cv, case.Bk, case.Bv, kn, vn))
+    dCk2, dCv2 = dCk.clone(), dCv.clone()
     out = torch.empty((B, H, d), dtype=torch.float32, device="cuda")
     lse_t = torch.empty((B, H), dtype=torch.float32, device="cuda")
     scores = torch.full((B, H, case.T_cap), float("nan"), dtype=torch.float32, device="cuda")
@@ -162,6 +169,15 @@ def test_decode_small_rank(dtype, B, H, d, r, T):
     Cv_h = dCv.view(torch.int16).cpu().numpy().view(np.uint16) if dtype == "bf16" else dCv.cpu().numpy()
     ref2 = oracle_out(dtype, q[:nb], Ck_h[:nb], Cv_h[:nb], Bks, Bvs, T + 1)
     assert_close(to_host64(out[:nb]), ref2, dtype, "small rank fused step")
+    # the same fused step without the logits (the other kernel): same appended rows, same result
+    out2 = torch.full((B, H, d), float("nan"), dtype=torch.float32, device="cuda")
+    lse2 = torch.empty((B, H), dtype=torch.float32, device="cuda")
+    ap.ap_decode_step(dq, dkn, dvn, dCk2, dCv2, dBk, dBv, out2, ws, T=T + 1, sm_scale=1.0 / math.sqrt(d), lse=lse2)
+    torch.cuda.synchronize()
+    assert torch.equal(dCk2.view(torch.int16), dCk.view(torch.int16))
+    assert torch.equal(dCv2.view(torch.int16), dCv.view(torch.int16))
+    assert_close(to_host64(out2[:nb]), ref2, dtype, "small rank fused step, no logits")
+    assert np.abs(to_host64(lse2) - to_host64(lse_t)).max() <= 2e-3 * max(1.0, float(lse_t.abs().max()))
     A = np.exp(to_host64(scores[0, :, :T + 1]) - to_host64(lse_t[0])[:, None])
     Bk0 = P(case.Bk) if case.Bk.ndim == 2 else P(case.Bk)[0]
     A_ref = oracle.attention_probs(P(q)[0], P(Ck_h)[0, :T + 1], Bk0)
