@@ -20,6 +20,7 @@
 #include "lane_ops.hpp"
 #include "mfma_ops.hpp"
 #include <hip/hip_ext.h>
+#include <type_traits>
 
 namespace ap {
 namespace {
@@ -27,6 +28,11 @@ namespace {
 constexpr int kTok = 32;
 constexpr int kWaves = 4;
 constexpr int kTileBytesMax = kTok * (2 * 128 + 16);     // a wave's LDS region (r = 128)
+
+// Registers are capped for two waves per SIMD where a wave's q' and U (all heads) leave room
+// for it without spilling (rank 64 up to 48 heads, rank 128 up to 16 heads): measured 5-7 %
+// faster there, 25 % slower where the cap forces spills.
+#define AP_SMALL_WPE (MT * NKS <= 6 ? 2 : 1)
 
 struct SmallParams {
   const uint16_t* Qp;   // [B][2][Hp][r] folded queries, hi + lo
@@ -39,12 +45,17 @@ struct SmallParams {
 };
 
 template <class Tag, int MT, int NKS>
-__global__ void __launch_bounds__(256) attn_small(const SmallParams p) {
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(AP_SMALL_WPE)))
+attn_small(const SmallParams p) {
   constexpr int Hp = MT * 16;
+  // bf16 carries 8 significant bits: folded queries and weights go to the matrix cores as hi + lo
+  // pairs; fp16 (11 bits) needs no second half, as in attn_partial
+  constexpr bool SPLIT = std::is_same<Tag, BF16Tag>::value;
   constexpr int R = NKS * 32;                        // the rank, a multiple of 32
   constexpr int CPR = R / 8;                         // 16-byte chunks per coefficient row
   constexpr int NV = CPR / 2;                        // value chunks per lane and tile (32 rows / 64 lanes)
   constexpr int kPitch = 2 * R + 16;                 // LDS row pitch: consecutive row quads on different banks
+  constexpr int kDepth = 1;                          // tiles in flight per wave (two measured no faster)
   __shared__ __attribute__((aligned(16))) char vt[kWaves][kTileBytesMax];
   __shared__ float st_m[kWaves][Hp], st_l[kWaves][Hp], st_p[kWaves][Hp];
   static_assert(kWaves * kTileBytesMax >= Hp * R * 4, "the combine buffer reuses the tile regions");
@@ -66,14 +77,14 @@ __global__ void __launch_bounds__(256) attn_small(const SmallParams p) {
   const int Tv = T - p.defer_v;                      // value rows that exist
 
   // folded queries: B operand of the score product, lane (head n of tile mt, g): columns 32 ks + 8 g ..
-  u32x4_t qh[NKS][MT], ql[NKS][MT];
+  u32x4_t qh[NKS][MT], ql[SPLIT ? NKS : 1][MT];
 #pragma unroll
   for (int ks = 0; ks < NKS; ++ks)
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
       const uint16_t* qp = p.Qp + (((size_t)b * 2) * Hp + mt * 16 + n) * R + ks * 32 + g * 8;
       qh[ks][mt] = *(const u32x4_t*)qp;
-      ql[ks][mt] = *(const u32x4_t*)(qp + (size_t)Hp * R);
+      if (SPLIT) ql[ks][mt] = *(const u32x4_t*)(qp + (size_t)Hp * R);
     }
   const uint16_t* Cb = p.Ck + (size_t)b * p.T_cap * R + g * 8;
   const uint16_t* Vb = p.Cv + (size_t)b * p.T_cap * R;
@@ -82,8 +93,11 @@ __global__ void __launch_bounds__(256) attn_small(const SmallParams p) {
   const int t_lo = (int)(((int64_t)su * ntiles) / S);
   const int ntl = (int)(((int64_t)(su + 1) * ntiles) / S) - t_lo;
 
-  u32x4_t A[NKS][2], Vr[NV];
-  auto load_tile = [&](int lt) {
+  // a tile's rows in registers; kDepth tiles per wave are in flight
+  struct TileRegs { u32x4_t A[NKS][2]; u32x4_t Vr[NV]; };
+  auto load_tile = [&](TileRegs& tr, int lt) {
+    u32x4_t (&A)[NKS][2] = tr.A;
+    u32x4_t (&Vr)[NV] = tr.Vr;
     const int base = (t_lo + lt) * kTok;
 #pragma unroll
     for (int tt = 0; tt < 2; ++tt) {
@@ -112,9 +126,9 @@ __global__ void __launch_bounds__(256) attn_small(const SmallParams p) {
   }
   char* my = vt[wave];
 
-  int lt = wave;
-  if (lt < ntl) load_tile(lt);
-  for (; lt < ntl; lt += kWaves) {
+  auto process = [&](TileRegs& tr, int lt) {
+    u32x4_t (&A)[NKS][2] = tr.A;
+    u32x4_t (&Vr)[NV] = tr.Vr;
     const int base = (t_lo + lt) * kTok;
     const int cnt = T - base;                          // tokens of this tile that exist (>= 1; may exceed 32)
     const int slot_new = p.defer_v ? T - 1 - base : -1;  // the deferred token's slot, if it is in [0, 32)
@@ -133,12 +147,12 @@ __global__ void __launch_bounds__(256) attn_small(const SmallParams p) {
 #pragma unroll
         for (int ks = 0; ks < NKS; ++ks) {
           sp[mt][tt] = Mfma<Tag>::run(A[ks][tt], qh[ks][mt], sp[mt][tt]);
-          sp[mt][tt] = Mfma<Tag>::run(A[ks][tt], ql[ks][mt], sp[mt][tt]);
+          if (SPLIT) sp[mt][tt] = Mfma<Tag>::run(A[ks][tt], ql[ks][mt], sp[mt][tt]);
         }
       }
-    if (lt + kWaves < ntl) load_tile(lt + kWaves);     // lands while this tile is finished
+    if (lt + kDepth * kWaves < ntl) load_tile(tr, lt + kDepth * kWaves);   // the registers are free again
     // ---- softmax of head 16 mt + n: this lane holds tokens 4g+e (tt = 0) and 16+4g+e (tt = 1)
-    u32x4_t Phi[MT], Plo[MT];
+    u32x4_t Phi[MT], Plo[SPLIT ? MT : 1];
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
       float s[8];
@@ -172,9 +186,13 @@ __global__ void __launch_bounds__(256) attn_small(const SmallParams p) {
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
         Phi[mt][c] = cvt_pack(pw[2 * c], pw[2 * c + 1], Tag{});
-        const float k0 = lo_to_f32(Phi[mt][c], Tag{}), k1 = hi_to_f32(Phi[mt][c], Tag{});
-        Plo[mt][c] = cvt_pack(pw[2 * c] - k0, pw[2 * c + 1] - k1, Tag{});
-        l[mt] += (k0 + lo_to_f32(Plo[mt][c], Tag{})) + (k1 + hi_to_f32(Plo[mt][c], Tag{}));   // what the MFMA sees
+        float k0 = lo_to_f32(Phi[mt][c], Tag{}), k1 = hi_to_f32(Phi[mt][c], Tag{});
+        if (SPLIT) {
+          Plo[mt][c] = cvt_pack(pw[2 * c] - k0, pw[2 * c + 1] - k1, Tag{});
+          k0 += lo_to_f32(Plo[mt][c], Tag{});
+          k1 += hi_to_f32(Plo[mt][c], Tag{});
+        }
+        l[mt] += k0 + k1;                                // the sum uses the values the MFMA will see
       }
     }
     // ---- U^T += C_v^T . P^T, 32 columns (16 dwords) at a time
@@ -199,11 +217,20 @@ __global__ void __launch_bounds__(256) attn_small(const SmallParams p) {
       for (int mt = 0; mt < MT; ++mt) {
         U[i][0][mt] = Mfma<Tag>::run(te, Phi[mt], U[i][0][mt]);
         U[i][1][mt] = Mfma<Tag>::run(to, Phi[mt], U[i][1][mt]);
-        U[i][0][mt] = Mfma<Tag>::run(te, Plo[mt], U[i][0][mt]);
-        U[i][1][mt] = Mfma<Tag>::run(to, Plo[mt], U[i][1][mt]);
+        if (SPLIT) {
+          U[i][0][mt] = Mfma<Tag>::run(te, Plo[mt], U[i][0][mt]);
+          U[i][1][mt] = Mfma<Tag>::run(to, Plo[mt], U[i][1][mt]);
+        }
       }
     }
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // reads done before the next tile is written
+  };
+  TileRegs tr0, tr1;
+  if (wave < ntl) load_tile(tr0, wave);
+  if (kDepth > 1 && wave + kWaves < ntl) load_tile(tr1, wave + kWaves);
+  for (int lt = wave; lt < ntl; lt += kDepth * kWaves) {
+    process(tr0, lt);
+    if (kDepth > 1 && lt + kWaves < ntl) process(tr1, lt + kWaves);
   }
 
   // ---- combine the four waves: statistics first, then the sums, one wave after the other
@@ -290,7 +317,7 @@ ap_status launch_attn_small(ap_dtype dt, const uint16_t* Qp, const void* Ck, con
   switch (nks) { case 2: AP_AS2(TAG, M, 2); break; default: AP_AS2(TAG, M, 4); break; }
 #define AP_AS0(TAG)                                                                                    \
   switch (mt) { case 1: AP_AS1(TAG, 1) break; case 2: AP_AS1(TAG, 2) break; case 3: AP_AS1(TAG, 3) break; \
-                default: AP_AS1(TAG, 4) break; }
+                default: AP_AS2(TAG, 4, 2); break; }          /* 64 heads: rank 64 only (see attn_small_applies) */
   if (dt == AP_F16) { AP_AS0(F16Tag) } else { AP_AS0(BF16Tag) }
 #undef AP_AS0
 #undef AP_AS1

@@ -1348,7 +1348,7 @@ ap_status run_decode(const DecodeArgs& a) {
   const bool small = !a.rank_k && !a.rank_v && a.dt_coef != AP_I8 && !a.scores &&
                      attn_small_applies(a.H, a.r, a.T, one_pass_v);
   const int S = choose_nsplit(a.B, a.T);     // the same count for both kernels (twice the splits for
-                                             // the small-rank kernel measured no faster)
+                                             // the small-rank kernel measured slower)
   const WsLayout wl = ws_layout(a.B, a.H, a.d, a.T, a.r);
   char* ws = (char*)a.workspace;
   uint16_t* Qp = (uint16_t*)(ws + wl.qp);
