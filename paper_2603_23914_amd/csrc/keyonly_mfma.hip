@@ -7,7 +7,7 @@
 // tile of 32 tokens of ONE key/value head and all the query heads that share it:
 //   scores   S[token, head] = C_k[token, :r] . q'[head, :r]   MFMA 16x16x32, coefficient rows
 //            straight from global memory into the A operand (16 rows x 64 bytes per load),
-//            the folded queries (hi + lo halves) resident as B operands;
+//            the folded queries (hi + lo halves for bf16) resident as B operands;
 //   softmax  the MFMA result already has the layout of the next product's B operand (lane
 //            (head, g) holds tokens 4g..4g+3 and 16+4g..16+4g+3), so the weights never leave
 //            the registers: one maximum over the four lanes of a head, exponentials, hi + lo
@@ -22,6 +22,7 @@
 #include "ap_common.hpp"
 #include "lane_ops.hpp"
 #include "mfma_ops.hpp"
+#include <type_traits>
 
 namespace ap {
 namespace {
@@ -40,6 +41,9 @@ keyonly_mfma(const uint16_t* __restrict__ Qp, const uint16_t* __restrict__ Ck,
              const uint16_t* __restrict__ V, float* __restrict__ out_part, float* __restrict__ lse_part,
              int B, int H, int QG, int T, int T_cap, int r, int S, int per) {
   __shared__ __attribute__((aligned(16))) char vt[kWaves][kTok * kPitch];
+  // bf16 carries 8 significant bits: folded queries and weights go to the matrix cores as hi + lo
+  // pairs; fp16 (11 bits) needs no second half
+  constexpr bool SPLIT = std::is_same<Tag, BF16Tag>::value;
   const int Hkv = H / QG;
   const int id = blockIdx.x, k = id >> 3;
   const int kvh = k % Hkv, p = (k / Hkv) * 8 + (id & 7);
@@ -51,18 +55,19 @@ keyonly_mfma(const uint16_t* __restrict__ Qp, const uint16_t* __restrict__ Ck,
   const size_t HD = (size_t)Hkv * 128;
 
   // folded queries of head h0 + n (zero beyond the heads of the group and beyond the rank)
-  u32x4_t qh[NKS], ql[NKS];
+  u32x4_t qh[NKS], ql[SPLIT ? NKS : 1];
   uint32_t koff[NKS];
 #pragma unroll
   for (int ks = 0; ks < NKS; ++ks) {
     const int col = ks * 32 + g * 8;
     const u32x4_t z = {0, 0, 0, 0};
-    qh[ks] = z; ql[ks] = z;
+    qh[ks] = z;
+    if (SPLIT) ql[ks] = z;
     koff[ks] = col < r ? (uint32_t)col : 0u;          // columns beyond the rank re-read column 0
     if (n < QG && col < r) {
       const uint16_t* qp = Qp + (((size_t)b * 2) * H + h0 + n) * r + col;
       qh[ks] = *(const u32x4_t*)qp;
-      ql[ks] = *(const u32x4_t*)(qp + (size_t)H * r);
+      if (SPLIT) ql[ks] = *(const u32x4_t*)(qp + (size_t)H * r);
     }
   }
   const uint16_t* Cb = Ck + (size_t)b * T_cap * r;
@@ -114,7 +119,7 @@ keyonly_mfma(const uint16_t* __restrict__ Qp, const uint16_t* __restrict__ Ck,
 #pragma unroll
       for (int ks = 0; ks < NKS; ++ks) {
         sp[tt] = Mfma<Tag>::run(A[ks][tt], qh[ks], sp[tt]);
-        sp[tt] = Mfma<Tag>::run(A[ks][tt], ql[ks], sp[tt]);
+        if (SPLIT) sp[tt] = Mfma<Tag>::run(A[ks][tt], ql[ks], sp[tt]);
       }
     }
     if (t + kWaves < ntiles) load_tile(t + kWaves);     // lands while this tile is finished
@@ -135,14 +140,18 @@ keyonly_mfma(const uint16_t* __restrict__ Qp, const uint16_t* __restrict__ Ck,
 #pragma unroll
       for (int i = 0; i < 4; ++i) { O[i][0] *= alpha; O[i][1] *= alpha; }
     }
-    u32x4_t Phi, Plo;
+    u32x4_t Phi, Plo = {0, 0, 0, 0};
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
       const float p0 = fast_exp2(s[2 * c] - m), p1 = fast_exp2(s[2 * c + 1] - m);
       Phi[c] = cvt_pack(p0, p1, Tag{});
-      const float k0 = lo_to_f32(Phi[c], Tag{}), k1 = hi_to_f32(Phi[c], Tag{});
-      Plo[c] = cvt_pack(p0 - k0, p1 - k1, Tag{});
-      l += (k0 + lo_to_f32(Plo[c], Tag{})) + (k1 + hi_to_f32(Plo[c], Tag{}));   // what the MFMA sees
+      float k0 = lo_to_f32(Phi[c], Tag{}), k1 = hi_to_f32(Phi[c], Tag{});
+      if (SPLIT) {
+        Plo[c] = cvt_pack(p0 - k0, p1 - k1, Tag{});
+        k0 += lo_to_f32(Plo[c], Tag{});
+        k1 += hi_to_f32(Plo[c], Tag{});
+      }
+      l += k0 + k1;                                      // the sum uses the values the MFMA will see
     }
     // ---- O^T += V^T . P^T, 32 columns (16 dwords) at a time
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // the tile is in LDS for every lane of the wave
@@ -164,8 +173,10 @@ keyonly_mfma(const uint16_t* __restrict__ Qp, const uint16_t* __restrict__ Ck,
       }
       O[i][0] = Mfma<Tag>::run(te, Phi, O[i][0]);
       O[i][1] = Mfma<Tag>::run(to, Phi, O[i][1]);
-      O[i][0] = Mfma<Tag>::run(te, Plo, O[i][0]);
-      O[i][1] = Mfma<Tag>::run(to, Plo, O[i][1]);
+      if (SPLIT) {
+        O[i][0] = Mfma<Tag>::run(te, Plo, O[i][0]);
+        O[i][1] = Mfma<Tag>::run(to, Plo, O[i][1]);
+      }
     }
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // reads done before the next tile is written
   }
