@@ -41,6 +41,7 @@ struct SmallParams {
   float* part_ml;       // [B][S][H][2]
   float* part_U;        // [B][S][H][r]
   float* pnew;          // [B][H] weight of the deferred newest token (fused step)
+  float* scores;        // [B][H][T_cap] scaled logits in natural-log units, or null
   int B, T, T_cap, r, H, nsplit, xcd_aware, defer_v;
 };
 
@@ -86,6 +87,7 @@ attn_small(const SmallParams p) {
       qh[ks][mt] = *(const u32x4_t*)qp;
       if (SPLIT) ql[ks][mt] = *(const u32x4_t*)(qp + (size_t)Hp * R);
     }
+  float* logits = p.scores ? p.scores + (size_t)b * H * p.T_cap : nullptr;
   const uint16_t* Cb = p.Ck + (size_t)b * p.T_cap * R + g * 8;
   const uint16_t* Vb = p.Cv + (size_t)b * p.T_cap * R;
   // tiles of this split (the same cut as attn_partial's)
@@ -160,6 +162,22 @@ attn_small(const SmallParams p) {
       for (int e = 0; e < 4; ++e) {
         s[e] = 4 * g + e < cnt ? sp[mt][0][e] : -INFINITY;
         s[4 + e] = 16 + 4 * g + e < cnt ? sp[mt][1][e] : -INFINITY;
+      }
+      if (logits && mt * 16 + n < H) {                 // logits out, for importance tracking
+        float* row = logits + (size_t)(mt * 16 + n) * p.T_cap + base + 4 * g;
+#pragma unroll
+        for (int tt = 0; tt < 2; ++tt) {
+          if ((p.T_cap & 3) == 0 && 16 * tt + 4 * g + 3 < cnt) {
+            // four consecutive tokens of one head: one 16-byte store (the four lanes of a head
+            // write two contiguous 64-byte runs)
+            const f32x4_t v = {s[4 * tt] * kLn2, s[4 * tt + 1] * kLn2, s[4 * tt + 2] * kLn2, s[4 * tt + 3] * kLn2};
+            *(f32x4_t*)(row + 16 * tt) = v;
+          } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+              if (16 * tt + 4 * g + e < cnt) row[16 * tt + e] = s[4 * tt + e] * kLn2;
+          }
+        }
       }
       float tmax = fmaxf(fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])), fmaxf(fmaxf(s[4], s[5]), fmaxf(s[6], s[7])));
       tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
@@ -300,9 +318,9 @@ bool attn_small_applies(int H, int r, int T, bool defer_v) {
 }
 
 ap_status launch_attn_small(ap_dtype dt, const uint16_t* Qp, const void* Ck, const void* Cv, float* part_ml,
-                            float* part_U, float* pnew, int B, int H, int T, int T_cap, int r, int nsplit,
-                            bool defer_v, hipStream_t stream) {
-  SmallParams p{Qp, (const uint16_t*)Ck, (const uint16_t*)Cv, part_ml, part_U, pnew,
+                            float* part_U, float* pnew, float* scores, int B, int H, int T, int T_cap, int r,
+                            int nsplit, bool defer_v, hipStream_t stream) {
+  SmallParams p{Qp, (const uint16_t*)Ck, (const uint16_t*)Cv, part_ml, part_U, pnew, scores,
                 B, T, T_cap, r, H, nsplit, B % 8 == 0 ? 1 : 0, defer_v ? 1 : 0};
   const int nb = B * nsplit;
   const int mt = (H + 15) / 16, nks = r / 32;

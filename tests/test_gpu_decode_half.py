@@ -137,10 +137,10 @@ def test_decode_step_equals_compact_then_attend(dtype, B, H, d, r, T0):
     ("f16", 8, 32, 128, 64, 4000),      # whole groups of 8 sequences, long
 ])
 def test_decode_small_rank(dtype, B, H, d, r, T):
-    """Ranks 64 and 128: calls without logits run attn_small (waves work alone on whole tiles),
-    calls that want the logits the token-split variant of the two-role kernel; both are checked
-    against the oracle, on the plain call and on the fused step (whose newest token's value row
-    does not exist while the kernel runs)."""
+    """Ranks 64 and 128 run attn_small (waves work alone on whole tiles), except 64 heads at rank
+    128, which stay on the token-split variant of the two-role kernel; checked against the
+    oracle on the plain call and on the fused step (whose newest token's value row does not
+    exist while the kernel runs), with and without the logits output."""
     from paper_2603_23914_amd import binding as ap
     case = wl.decode_case(dtype, B, H, d, r, T, steps=1, seed=27, append=True,
                           batch_subset=range(min(B, 3)), shared_basis=B > 3)
@@ -169,7 +169,7 @@ def test_decode_small_rank(dtype, B, H, d, r, T):
     Cv_h = dCv.view(torch.int16).cpu().numpy().view(np.uint16) if dtype == "bf16" else dCv.cpu().numpy()
     ref2 = oracle_out(dtype, q[:nb], Ck_h[:nb], Cv_h[:nb], Bks, Bvs, T + 1)
     assert_close(to_host64(out[:nb]), ref2, dtype, "small rank fused step")
-    # the same fused step without the logits (the other kernel): same appended rows, same result
+    # the same fused step without the logits: same appended rows, same result
     out2 = torch.full((B, H, d), float("nan"), dtype=torch.float32, device="cuda")
     lse2 = torch.empty((B, H), dtype=torch.float32, device="cuda")
     ap.ap_decode_step(dq, dkn, dvn, dCk2, dCv2, dBk, dBv, out2, ws, T=T + 1, sm_scale=1.0 / math.sqrt(d), lse=lse2)
