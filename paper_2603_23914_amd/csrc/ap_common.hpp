@@ -157,8 +157,10 @@ ap_status launch_valueonly_attn(const void* q, const void* K, const void* Cv, co
 // small uniform ranks (attn_small.hip): partial results in attn_partial's layout
 bool attn_small_applies(int H, int r, int T, bool defer_v);
 ap_status launch_attn_small(ap_dtype dt, const uint16_t* Qp, const void* Ck, const void* Cv, float* part_ml,
-                            float* part_U, float* pnew, float* scores, int B, int H, int T, int T_cap, int r,
-                            int nsplit, bool defer_v, hipStream_t stream);
+                            float* part_U, float* pnew, float* scores, const int32_t* rank_k,
+                            const int32_t* rank_v, const int32_t* bucket_off, const int32_t* bucket_idx, int F,
+                            int B, int H, int T, int T_cap, int r, int nsplit, bool defer_v,
+                            hipStream_t stream);
 // key-only compression on the matrix cores (keyonly_mfma.hip)
 bool keyonly_mfma_applies(int H, int H_kv, int d, int r);
 int keyonly_mfma_splits(int B, int H_kv, int T);

@@ -1,5 +1,5 @@
-// attn_small: the coefficient-streaming kernel for small ranks (r = 64 or 128, uniform over the
-// tokens, 16-bit storage), the paper's own operating point (R = 64 ... 128).
+// attn_small: the coefficient-streaming kernel for small ranks (r = 64 or 128, 16-bit storage,
+// uniform or per-token ranks), the paper's own operating point (R = 64 ... 128, low group 16).
 //
 // attn_partial splits a tile of 32 tokens over eight waves in two roles, which costs two
 // workgroup barriers and an LDS round trip of the scores per tile: at small ranks its tile loop
@@ -43,9 +43,22 @@ struct SmallParams {
   float* pnew;          // [B][H] weight of the deferred newest token (fused step)
   float* scores;        // [B][H][T_cap] scaled logits in natural-log units, or null
   int B, T, T_cap, r, H, nsplit, xcd_aware, defer_v;
+  // per-token ranks (RAGGED): the group lists of ap_select_ranks and the rank arrays
+  const int32_t* rank_k;      // [B][T] or null (= r)
+  const int32_t* rank_v;
+  const int32_t* bucket_off;  // [B][F+1]
+  const int32_t* bucket_idx;  // [B][T]
+  int F;
 };
+constexpr int kMaxSmallTiles = 136;     // tiles a split can own with per-token ranks (128 + one per group)
 
-template <class Tag, int MT, int NKS>
+// RAGGED (per-token ranks): a tile is 32 tokens of ONE rank group, taken from the group's index
+// list, so the rank is uniform inside a tile; tiles are dealt to the splits round-robin (tile su,
+// su + S, ...), as in attn_partial.  The workgroup first writes (token count, key rank, value rank,
+// list position) of its tiles into LDS; a wave then gathers a tile's rows through the index
+// list.  Columns at or beyond a tile's rank are not fetched (their loads are redirected to the
+// row's first chunk) and enter the products as zeros.
+template <class Tag, int MT, int NKS, bool RAGGED>
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(AP_SMALL_WPE)))
 attn_small(const SmallParams p) {
   constexpr int Hp = MT * 16;
@@ -60,6 +73,7 @@ attn_small(const SmallParams p) {
   __shared__ __attribute__((aligned(16))) char vt[kWaves][kTileBytesMax];
   __shared__ float st_m[kWaves][Hp], st_l[kWaves][Hp], st_p[kWaves][Hp];
   static_assert(kWaves * kTileBytesMax >= Hp * R * 4, "the combine buffer reuses the tile regions");
+  __shared__ int meta[RAGGED ? kMaxSmallTiles : 1][4];
 
   const int id = __builtin_amdgcn_readfirstlane((int)blockIdx.x);
   int b, su;
@@ -90,31 +104,111 @@ attn_small(const SmallParams p) {
   float* logits = p.scores ? p.scores + (size_t)b * H * p.T_cap : nullptr;
   const uint16_t* Cb = p.Ck + (size_t)b * p.T_cap * R + g * 8;
   const uint16_t* Vb = p.Cv + (size_t)b * p.T_cap * R;
-  // tiles of this split (the same cut as attn_partial's)
-  const int ntiles = (T + kTok - 1) / kTok;
-  const int t_lo = (int)(((int64_t)su * ntiles) / S);
-  const int ntl = (int)(((int64_t)(su + 1) * ntiles) / S) - t_lo;
+  // tiles of this split (the same cuts as attn_partial's)
+  int t_lo = 0, ntl = 0;
+  const int32_t* bidx = nullptr;
+  if constexpr (!RAGGED) {
+    const int ntiles = (T + kTok - 1) / kTok;
+    t_lo = (int)(((int64_t)su * ntiles) / S);
+    ntl = (int)(((int64_t)(su + 1) * ntiles) / S) - t_lo;
+  } else {
+    const int F = p.F;
+    const int32_t* boff = p.bucket_off + (size_t)b * (F + 1);
+    bidx = p.bucket_idx + (size_t)b * T;
+    int off[9], ts[9];                               // group f: list positions off[f]..off[f+1], first tile ts[f]
+    off[0] = boff[0];
+    ts[0] = 0;
+#pragma unroll
+    for (int f = 0; f < 8; ++f) {
+      off[f + 1] = f < F ? boff[f + 1] : off[f];
+      int c = off[f + 1] - off[f];
+      c = c < 0 ? 0 : c;
+      ts[f + 1] = ts[f] + ((c + kTok - 1) >> 5);
+    }
+    const int ntot = ts[8];
+    ntl = su < ntot ? (ntot - su + S - 1) / S : 0;
+    ntl = ntl < kMaxSmallTiles ? ntl : kMaxSmallTiles;   // the host sizes the splits so that this never cuts
+    for (int i = threadIdx.x; i < ntl; i += 256) {
+      const int j = su + i * S;
+      int o0 = off[0], o1 = off[1], tf = 0;
+#pragma unroll
+      for (int f = 1; f < 8; ++f)
+        if (f < F && j >= ts[f]) { o0 = off[f]; o1 = off[f + 1]; tf = ts[f]; }
+      int pos0 = o0 + (j - tf) * kTok;
+      int cnt = o1 - pos0;
+      cnt = cnt > kTok ? kTok : cnt;
+      pos0 = pos0 < 0 ? 0 : (pos0 < T ? pos0 : T - 1);
+      cnt = cnt < 1 ? 1 : (pos0 + cnt > T ? T - pos0 : cnt);   // inconsistent lists stay inside the buffers
+      int tok = bidx[pos0];
+      tok = tok < 0 ? 0 : (tok < T ? tok : T - 1);
+      int rk = p.rank_k ? p.rank_k[(size_t)b * T + tok] : R;
+      int rv = p.rank_v ? p.rank_v[(size_t)b * T + tok] : R;
+      meta[i][0] = cnt;
+      meta[i][1] = rk < 0 ? 0 : (rk < R ? rk : R);
+      meta[i][2] = rv < 0 ? 0 : (rv < R ? rv : R);
+      meta[i][3] = pos0;
+    }
+    __syncthreads();
+  }
 
-  // a tile's rows in registers; kDepth tiles per wave are in flight
+  // a tile's rows in registers, and (RAGGED) the token indices of the NEXT tile's rows
   struct TileRegs { u32x4_t A[NKS][2]; u32x4_t Vr[NV]; };
+  int tokA[2] = {0, 0}, tokV[NV], tokS[8];           // rows of the A operand, of the value chunks, of the score slots
+#pragma unroll
+  for (int k2 = 0; k2 < NV; ++k2) tokV[k2] = 0;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) tokS[e] = 0;
+  auto fetch_idx = [&](int lt) {                     // RAGGED: token indices of local tile lt for this lane
+    const int cnt = __builtin_amdgcn_readfirstlane(meta[lt][0]);
+    const int32_t* lst = bidx + __builtin_amdgcn_readfirstlane(meta[lt][3]);
+    auto at = [&](int slot) {
+      int tok = lst[slot < cnt ? slot : cnt - 1];    // slots beyond the tile repeat its last token (masked)
+      return tok < 0 ? 0 : (tok < T ? tok : T - 1);
+    };
+    tokA[0] = at(n);
+    tokA[1] = at(16 + n);
+#pragma unroll
+    for (int k2 = 0; k2 < NV; ++k2) tokV[k2] = at((lane + 64 * k2) / CPR);
+    if (logits) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) { tokS[e] = at(4 * g + e); tokS[4 + e] = at(16 + 4 * g + e); }
+    }
+  };
   auto load_tile = [&](TileRegs& tr, int lt) {
     u32x4_t (&A)[NKS][2] = tr.A;
     u32x4_t (&Vr)[NV] = tr.Vr;
-    const int base = (t_lo + lt) * kTok;
+    if constexpr (!RAGGED) {
+      const int base = (t_lo + lt) * kTok;
 #pragma unroll
-    for (int tt = 0; tt < 2; ++tt) {
-      int row = base + 16 * tt + n;
-      row = row < T ? row : T - 1;                   // rows beyond T are masked in the softmax
-      const uint16_t* crow = Cb + (size_t)row * R;
+      for (int tt = 0; tt < 2; ++tt) {
+        int row = base + 16 * tt + n;
+        row = row < T ? row : T - 1;                 // rows beyond T are masked in the softmax
+        const uint16_t* crow = Cb + (size_t)row * R;
 #pragma unroll
-      for (int ks = 0; ks < NKS; ++ks) A[ks][tt] = *(const u32x4_t*)(crow + ks * 32);
-    }
+        for (int ks = 0; ks < NKS; ++ks) A[ks][tt] = *(const u32x4_t*)(crow + ks * 32);
+      }
 #pragma unroll
-    for (int k2 = 0; k2 < NV; ++k2) {
-      const int c = lane + 64 * k2;
-      int row = base + c / CPR;
-      row = row < Tv ? row : Tv - 1;                 // rows that do not exist repeat the last that does
-      Vr[k2] = *(const u32x4_t*)(Vb + (size_t)row * R + (c % CPR) * 8);
+      for (int k2 = 0; k2 < NV; ++k2) {
+        const int c = lane + 64 * k2;
+        int row = base + c / CPR;
+        row = row < Tv ? row : Tv - 1;               // rows that do not exist repeat the last that does
+        Vr[k2] = *(const u32x4_t*)(Vb + (size_t)row * R + (c % CPR) * 8);
+      }
+    } else {
+      const int rk = __builtin_amdgcn_readfirstlane(meta[lt][1]);
+      const int rv = __builtin_amdgcn_readfirstlane(meta[lt][2]);
+#pragma unroll
+      for (int tt = 0; tt < 2; ++tt) {
+        const uint16_t* crow = Cb + (size_t)tokA[tt] * R;
+#pragma unroll
+        for (int ks = 0; ks < NKS; ++ks)
+          A[ks][tt] = *(const u32x4_t*)(crow + (ks * 32 + g * 8 < rk ? ks * 32 : -g * 8));
+      }
+#pragma unroll
+      for (int k2 = 0; k2 < NV; ++k2) {
+        const int cc = (lane + 64 * k2) % CPR;
+        Vr[k2] = *(const u32x4_t*)(Vb + (size_t)tokV[k2] * R + (cc * 8 < rv ? cc * 8 : 0));
+      }
     }
   };
 
@@ -131,13 +225,29 @@ attn_small(const SmallParams p) {
   auto process = [&](TileRegs& tr, int lt) {
     u32x4_t (&A)[NKS][2] = tr.A;
     u32x4_t (&Vr)[NV] = tr.Vr;
-    const int base = (t_lo + lt) * kTok;
-    const int cnt = T - base;                          // tokens of this tile that exist (>= 1; may exceed 32)
-    const int slot_new = p.defer_v ? T - 1 - base : -1;  // the deferred token's slot, if it is in [0, 32)
+    const int base = (t_lo + lt) * kTok;               // (not RAGGED) first token of the tile
+    // tokens of this tile that exist (>= 1; without per-token ranks it may exceed 32)
+    const int cnt = RAGGED ? __builtin_amdgcn_readfirstlane(meta[lt][0]) : T - base;
+    const int rk = RAGGED ? __builtin_amdgcn_readfirstlane(meta[lt][1]) : R;
+    const int rv = RAGGED ? __builtin_amdgcn_readfirstlane(meta[lt][2]) : R;
+    const int slot_new = !RAGGED && p.defer_v ? T - 1 - base : -1;  // the deferred token's slot, if in [0, 32)
+    int tokC[8];                                       // RAGGED: this tile's tokens of the lane's score slots
+    if constexpr (RAGGED) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) tokC[e] = tokS[e];
+      if (lt + kWaves < ntl) fetch_idx(lt + kWaves);   // indices of the next tile's rows, used below
+    }
 #pragma unroll
     for (int k2 = 0; k2 < NV; ++k2) {
       const int c = lane + 64 * k2;
-      *(u32x4_t*)(my + (c / CPR) * kPitch + (c % CPR) * 16) = Vr[k2];
+      u32x4_t v = Vr[k2];
+      if (RAGGED && (c % CPR) * 8 >= rv) { const u32x4_t z = {0, 0, 0, 0}; v = z; }   // beyond the value rank
+      *(u32x4_t*)(my + (c / CPR) * kPitch + (c % CPR) * 16) = v;
+    }
+    if constexpr (RAGGED) {                            // columns beyond the key rank count as zero
+#pragma unroll
+      for (int ks = 0; ks < NKS; ++ks)
+        if (ks * 32 + g * 8 >= rk) { const u32x4_t z = {0, 0, 0, 0}; A[ks][0] = z; A[ks][1] = z; }
     }
     f32x4_t sp[MT][2];
 #pragma unroll
@@ -163,7 +273,15 @@ attn_small(const SmallParams p) {
         s[e] = 4 * g + e < cnt ? sp[mt][0][e] : -INFINITY;
         s[4 + e] = 16 + 4 * g + e < cnt ? sp[mt][1][e] : -INFINITY;
       }
-      if (logits && mt * 16 + n < H) {                 // logits out, for importance tracking
+      if (RAGGED && logits && mt * 16 + n < H) {       // logits out, scattered to the gathered tokens
+        float* hrow = logits + (size_t)(mt * 16 + n) * p.T_cap;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          if (4 * g + e < cnt) hrow[tokC[e]] = s[e] * kLn2;
+          if (16 + 4 * g + e < cnt) hrow[tokC[4 + e]] = s[4 + e] * kLn2;
+        }
+      }
+      if (!RAGGED && logits && mt * 16 + n < H) {      // logits out, for importance tracking
         float* row = logits + (size_t)(mt * 16 + n) * p.T_cap + base + 4 * g;
 #pragma unroll
         for (int tt = 0; tt < 2; ++tt) {
@@ -219,6 +337,7 @@ attn_small(const SmallParams p) {
     const char* vB = vA + 16 * kPitch;
 #pragma unroll
     for (int i = 0; i < NKS; ++i) {
+      if (RAGGED && i * 32 >= rv) continue;              // columns beyond the value rank: nothing to add
       uint32_t v[8];
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
@@ -244,6 +363,7 @@ attn_small(const SmallParams p) {
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // reads done before the next tile is written
   };
   TileRegs tr0, tr1;
+  if (RAGGED && wave < ntl) fetch_idx(wave);
   if (wave < ntl) load_tile(tr0, wave);
   if (kDepth > 1 && wave + kWaves < ntl) load_tile(tr1, wave + kWaves);
   for (int lt = wave; lt < ntl; lt += kDepth * kWaves) {
@@ -318,19 +438,25 @@ bool attn_small_applies(int H, int r, int T, bool defer_v) {
 }
 
 ap_status launch_attn_small(ap_dtype dt, const uint16_t* Qp, const void* Ck, const void* Cv, float* part_ml,
-                            float* part_U, float* pnew, float* scores, int B, int H, int T, int T_cap, int r,
-                            int nsplit, bool defer_v, hipStream_t stream) {
+                            float* part_U, float* pnew, float* scores, const int32_t* rank_k,
+                            const int32_t* rank_v, const int32_t* bucket_off, const int32_t* bucket_idx, int F,
+                            int B, int H, int T, int T_cap, int r, int nsplit, bool defer_v,
+                            hipStream_t stream) {
   SmallParams p{Qp, (const uint16_t*)Ck, (const uint16_t*)Cv, part_ml, part_U, pnew, scores,
-                B, T, T_cap, r, H, nsplit, B % 8 == 0 ? 1 : 0, defer_v ? 1 : 0};
+                B, T, T_cap, r, H, nsplit, B % 8 == 0 ? 1 : 0, defer_v ? 1 : 0,
+                rank_k, rank_v, bucket_off, bucket_idx, F};
+  const bool ragged = rank_k != nullptr || rank_v != nullptr;   // as everywhere in the library
   const int nb = B * nsplit;
   const int mt = (H + 15) / 16, nks = r / 32;
   hipEvent_t ev0, ev1;
   const bool timed = prof_events(&ev0, &ev1);          // the coefficient-streaming kernel of this call
-#define AP_AS2(TAG, M, N)                                                                              \
+#define AP_AS3(TAG, M, N, RG)                                                                          \
   do {                                                                                                 \
-    if (timed) hipExtLaunchKernelGGL((attn_small<TAG, M, N>), dim3(nb), dim3(256), 0, stream, ev0, ev1, 0u, p); \
-    else hipLaunchKernelGGL((attn_small<TAG, M, N>), dim3(nb), dim3(256), 0, stream, p);               \
+    if (timed) hipExtLaunchKernelGGL((attn_small<TAG, M, N, RG>), dim3(nb), dim3(256), 0, stream, ev0, ev1, 0u, p); \
+    else hipLaunchKernelGGL((attn_small<TAG, M, N, RG>), dim3(nb), dim3(256), 0, stream, p);           \
   } while (0)
+#define AP_AS2(TAG, M, N)                                                                              \
+  do { if (ragged) AP_AS3(TAG, M, N, true); else AP_AS3(TAG, M, N, false); } while (0)
 #define AP_AS1(TAG, M)                                                                                 \
   switch (nks) { case 2: AP_AS2(TAG, M, 2); break; default: AP_AS2(TAG, M, 4); break; }
 #define AP_AS0(TAG)                                                                                    \
@@ -340,6 +466,7 @@ ap_status launch_attn_small(ap_dtype dt, const uint16_t* Qp, const void* Ck, con
 #undef AP_AS0
 #undef AP_AS1
 #undef AP_AS2
+#undef AP_AS3
   return AP_OK;
 }
 

@@ -1345,8 +1345,7 @@ ap_status run_decode(const DecodeArgs& a) {
   const int Hkv = a.H_kv;
   const int HDkv = Hkv * a.d;              // hidden columns of the cache and of the basis rows
   const bool one_pass_v = a.v_new && !a.rank_k && !a.rank_v && a.T >= 2 && Hkv == a.H;
-  const bool small = !a.rank_k && !a.rank_v && a.dt_coef != AP_I8 &&
-                     attn_small_applies(a.H, a.r, a.T, one_pass_v);
+  const bool small = a.dt_coef != AP_I8 && attn_small_applies(a.H, a.r, a.T, one_pass_v);
   const int S = choose_nsplit(a.B, a.T);     // the same count for both kernels (twice the splits for
                                              // the small-rank kernel measured slower)
   const WsLayout wl = ws_layout(a.B, a.H, a.d, a.T, a.r);
@@ -1405,8 +1404,8 @@ ap_status run_decode(const DecodeArgs& a) {
   // small uniform ranks take the kernel whose waves work alone on whole tiles (attn_small.hip);
   // everything else the two-role kernel
   if (small)
-    st = launch_attn_small(a.dt, Qp, a.Ck, a.Cv, ml, U, (float*)(ws + wl.pn), a.scores, a.B, a.H, a.T, a.T_cap,
-                           a.r, S, one_pass_v, a.stream);
+    st = launch_attn_small(a.dt, Qp, a.Ck, a.Cv, ml, U, (float*)(ws + wl.pn), a.scores, a.rank_k, a.rank_v,
+                           a.bucket_off, a.bucket_idx, a.F, a.B, a.H, a.T, a.T_cap, a.r, S, one_pass_v, a.stream);
   else
     st = dispatch_attn<Tag, SPLIT>(p, a.B, a.stream);
   if (st != AP_OK) return st;

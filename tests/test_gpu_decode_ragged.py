@@ -60,6 +60,13 @@ CASES = [
     ("bf16", 1, 24, 64, 192, 200, (192, 128, 64), (0, 1, 2), 2),  # empty first group
     ("f16", 3, 16, 128, 256, 20, (256, 64), (1, 2), 2),           # fewer tokens than a tile
     ("f16", 1, 32, 128, 512, 1000, (512, 448, 384, 320, 256, 192, 128, 64), (1, 2, 3, 4, 5, 6, 7, 8), 8),
+    # the paper's own setting: rank 64 with a quarter of the tokens at full rank, the rest at 16
+    ("bf16", 2, 32, 128, 64, 700, (64, 16), (1, 4), 4),
+    ("f16", 3, 40, 128, 128, 333, (128, 64, 32), (1, 2, 4), 4),
+    ("bf16", 1, 16, 64, 64, 97, (64, 48, 32, 16), (1, 3, 5, 8), 8),
+    ("f16", 2, 64, 32, 64, 1500, (64, 32), (1, 10), 10),          # four head tiles, many tiles per wave
+    ("bf16", 8, 32, 128, 128, 2000, (128, 16), (1, 4), 4),         # whole groups of 8 sequences
+    ("f16", 1, 8, 128, 64, 20, (64, 16), (1, 2), 2),               # fewer tokens than a tile
 ]
 
 
@@ -139,3 +146,34 @@ def test_eviction_variant_drops_the_last_group():
     assert_close(got, ref, dtype, "eviction of the last group")
     full = oracle_ragged(dtype, case, q, T, rank_np)
     assert np.abs(full - ref).max() > 1e-2 * np.abs(ref).max()   # evicting is not truncating
+
+
+@pytest.mark.parametrize("dtype,B,H,d,r,T,granks,cum,den", [
+    ("bf16", 2, 32, 128, 64, 300, (64, 16), (1, 4), 4),
+    ("f16", 2, 40, 128, 128, 257, (128, 64, 32), (1, 2, 4), 4),
+])
+def test_ragged_small_rank_writes_the_logits(dtype, B, H, d, r, T, granks, cum, den):
+    """Per-token ranks at the paper's operating point, with the logits out (the loop of Alg. 1
+    updates the importance from every step's weights): exp(scores - lse) are the attention
+    weights of the truncated keys, at the gathered token positions."""
+    from paper_2603_23914_amd import binding as ap
+    case = wl.decode_case(dtype, B, H, d, r, T, steps=0, seed=19, append=False)
+    q = wl.step_query(case, 0)
+    mass = wl.rng_for(19, T, r).random((B, T)).astype(np.float32)
+    rank, off, idx = gpu_select(mass, granks, cum, den)
+    rank_np = rank.cpu().numpy()
+    dq, dCk, dCv, dBk, dBv = (to_dev(x, dtype) for x in (q, case.Ck, case.Cv, case.Bk, case.Bv))
+    out = torch.empty((B, H, d), dtype=torch.float32, device="cuda")
+    lse = torch.empty((B, H), dtype=torch.float32, device="cuda")
+    scores = torch.full((B, H, T), float("nan"), dtype=torch.float32, device="cuda")
+    ws = workspace(ap.ap_decode_workspace_bytes(B, H, d, T, r, ap._DT[TORCH_DT[dtype]]))
+    ap.ap_decode_attn(dq, dCk, dCv, dBk, dBv, out, ws, T=T, sm_scale=1.0 / math.sqrt(d), rank_k=rank, rank_v=rank,
+                      bucket_off=off, bucket_idx=idx, F=len(granks), lse=lse, scores=scores)
+    torch.cuda.synchronize()
+    assert_close(to_host64(out), oracle_ragged(dtype, case, q, T, rank_np), dtype, "ragged with logits")
+    P = lambda x: oracle.promote(x, dtype)
+    assert torch.isfinite(scores).all()
+    for b in range(B):
+        A = np.exp(to_host64(scores[b]) - to_host64(lse[b])[:, None])
+        A_ref = oracle.attention_probs(P(q)[b], P(case.Ck)[b, :T], P(case.Bk)[b], rank_k=rank_np[b])
+        assert np.abs(A - A_ref).max() <= 2e-3 * A_ref.max()
