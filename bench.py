@@ -111,7 +111,9 @@ def main():
                           "average, rank groups), the uncompressed segment (T_u=256) with its merge, a "
                           "grouped-query step (32/8 heads, r=256), a small-rank step (r=128), and key-only "
                           "compression (32/8 heads, R_k=64, 8 sequences of 8192 tokens) next to plain attention "
-                          "over the same tokens: the workload behind profiles/next_rows_kernel_trace.md")
+                          "over the same tokens, and the paper's loop at its operating point (32 heads, R=64, "
+                          "value ranks 64/16, importance tracked every step): the workload behind "
+                          "profiles/next_rows_kernel_trace.md")
     args = ap_.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
@@ -201,6 +203,25 @@ def main():
         for _ in range(10):
             ap.ap_keyonly_attn(ql, ckl, bkl, vl, outl, wsk, T=tl, sm_scale=scale)
             ap.ap_raw_attn(ql, kl, vl, outl, wsl, T_u=tl, sm_scale=scale)
+        del ckl, bkl, kl, vl
+        # the paper's own loop at its operating point (LLaVA-7B-like: 32 heads, R = 64, a quarter of the
+        # tokens at full value rank and the rest at 16, importance tracked on every step): group
+        # selection, fused step with per-token value ranks and logits out, importance update
+        hp, rp = 32, 64
+        ck, cv, bk, bv = cache(B, t, rp, hp * D)
+        qp = torch.randn(B, hp, D, device="cuda", dtype=bf)
+        kp = torch.randn(B, hp * D, device="cuda", dtype=bf)
+        outp = torch.empty(B, hp, D, device="cuda")
+        lsep = torch.empty(B, hp, device="cuda")
+        scp = torch.empty(B, hp, t, device="cuda")
+        massp = torch.rand(B, t, device="cuda")
+        offp = torch.empty(B, 3, dtype=torch.int32, device="cuda")
+        wsp = buf(B, hp, t, rp)
+        for _ in range(10):
+            ap.ap_select_ranks(massp, (rp, 16), (1, 4), 4, rank, offp, idx, wsel)
+            ap.ap_decode_step(qp, kp, kp, ck, cv, bk, bv, outp, wsp, T=t, sm_scale=scale, rank_v=rank,
+                              bucket_off=offp, bucket_idx=idx, F=2, lse=lsep, scores=scp)
+            ap.ap_update_importance(scp, lsep, massp, T=t, alpha=0.9)
         torch.cuda.synchronize()
         return
     K, W = args.steps, args.warmup
