@@ -151,7 +151,7 @@ def main():
         kn = torch.randn(B, H * D, device="cuda", dtype=bf)
         out = torch.empty(B, H, D, device="cuda")
         lse = torch.empty(B, H, device="cuda")
-        sc = torch.empty(B, H, t, device="cuda")
+        sc = torch.empty(B, t, H, device="cuda")
         mass = torch.zeros(B, t, device="cuda")
         rank = torch.empty(B, t, dtype=torch.int32, device="cuda")
         off = torch.empty(B, 5, dtype=torch.int32, device="cuda")
@@ -213,7 +213,7 @@ def main():
         kp = torch.randn(B, hp * D, device="cuda", dtype=bf)
         outp = torch.empty(B, hp, D, device="cuda")
         lsep = torch.empty(B, hp, device="cuda")
-        scp = torch.empty(B, hp, t, device="cuda")
+        scp = torch.empty(B, t, hp, device="cuda")
         massp = torch.rand(B, t, device="cuda")
         offp = torch.empty(B, 3, dtype=torch.int32, device="cuda")
         wsp = buf(B, hp, t, rp)

@@ -157,8 +157,8 @@ size_t ap_select_workspace_bytes(int B, int T, int F);
  *            bf16 output cannot meet a 2e-3 error bound by rounding alone: callers
  *            that need the fp32 accumulator's accuracy ask for AP_F32.
  *   lse      [B, H] fp32 or NULL
- *   scores   [B, H, T_cap] fp32 or NULL: the scaled logits sm_scale * q[b,h] . Ktilde[t, head h]
- *            of the attended tokens (columns 0..T-1; with group lists only the listed tokens
+ *   scores   [B, T_cap, H] fp32 or NULL: the scaled logits sm_scale * q[b,h] . Ktilde[t, head h]
+ *            of the attended tokens (rows 0..T-1; with group lists only the listed tokens
  *            are written), for ap_update_importance.
  *   sm_scale softmax scale; pass 1/sqrt(d) for the paper's attention
  *   workspace >= ap_decode_workspace_bytes(...) bytes, 256-byte aligned.
@@ -212,9 +212,9 @@ ap_status ap_decode_step(const void* q, const void* k_new, const void* v_new, vo
 /* ------------------------------------------------------------------------
  * ap_update_importance -- the paper's importance update (Eq. 1) for one new
  * query (T_q = 1), from the logits and log-sum-exp a decode call returned:
- *     A[b,h,t]   = exp(scores[b,h,t] - lse[b,h])             attention weights
+ *     A[b,h,t]   = exp(scores[b,t,h] - lse[b,h])             attention weights
  *     mass[b,t] <- alpha * mass[b,t] + (1 - alpha) * mean_h A[b,h,t]     t < T
- *   scores  [B, H, T_cap] fp32, lse [B, H] fp32 (natural log), as written by
+ *   scores  [B, T_cap, H] fp32, lse [B, H] fp32 (natural log), as written by
  *           ap_decode_attn / ap_decode_step with all T tokens attended
  *   mass    [B, mass_stride] fp32, updated in place; a token that has just been
  *           appended should enter with mass 0 (the caller's initialisation)

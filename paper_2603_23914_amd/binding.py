@@ -173,7 +173,7 @@ def ap_decode_attn(q, Ck, Cv, Bk, Bv, out, workspace, *, T: int, sm_scale: float
                    bucket_idx=None, F: int = 0, lse=None, scores=None, stream=None) -> None:
     """q, out [B, H, d] (out in q's dtype or fp32); Ck, Cv [B, T_cap, r];
     Bk, Bv [r, H_kv*d] or [B, r, H_kv*d] (H_kv is read off their width);
-    scores [B, H, T_cap] fp32 (optional output)."""
+    scores [B, T_cap, H] fp32 (optional output)."""
     B, H, d = q.shape
     T_cap, r = Ck.shape[1], Ck.shape[2]
     H_kv = Bk.shape[-1] // d
@@ -200,8 +200,9 @@ def ap_decode_step(q, k_new, v_new, Ck, Cv, Bk, Bv, out, workspace, *, T: int, s
 
 
 def ap_update_importance(scores, lse, mass, *, T: int, alpha: float, stream=None) -> None:
-    """mass [B, >=T] fp32 <- alpha*mass + (1-alpha)*mean_h exp(scores - lse) (Eq. 1, one query)."""
-    B, H, T_cap = scores.shape
+    """mass [B, >=T] fp32 <- alpha*mass + (1-alpha)*mean_h exp(scores - lse) (Eq. 1, one query);
+    scores [B, T_cap, H] as the decode entry points write them."""
+    B, T_cap, H = scores.shape
     _check(_lib.ap_update_importance(_p(scores), _p(lse), _p(mass), B, H, T, T_cap, mass.stride(0),
                                      float(alpha), _stream(stream)))
 

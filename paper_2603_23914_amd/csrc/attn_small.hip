@@ -41,7 +41,7 @@ struct SmallParams {
   float* part_ml;       // [B][S][H][2]
   float* part_U;        // [B][S][H][r]
   float* pnew;          // [B][H] weight of the deferred newest token (fused step)
-  float* scores;        // [B][H][T_cap] scaled logits in natural-log units, or null
+  float* scores;        // [B][T_cap][H] scaled logits in natural-log units, or null
   int B, T, T_cap, r, H, nsplit, xcd_aware, defer_v;
   // per-token ranks (RAGGED): the group lists of ap_select_ranks and the rank arrays
   const int32_t* rank_k;      // [B][T] or null (= r)
@@ -273,28 +273,16 @@ attn_small(const SmallParams p) {
         s[e] = 4 * g + e < cnt ? sp[mt][0][e] : -INFINITY;
         s[4 + e] = 16 + 4 * g + e < cnt ? sp[mt][1][e] : -INFINITY;
       }
-      if (RAGGED && logits && mt * 16 + n < H) {       // logits out, scattered to the gathered tokens
-        float* hrow = logits + (size_t)(mt * 16 + n) * p.T_cap;
+      if (logits && mt * 16 + n < H) {
+        // logits out, for importance tracking: [token][head], so the sixteen lanes of a row group
+        // write 64 contiguous bytes per token, also when the tile's tokens are gathered
+        float* hcol = logits + (mt * 16 + n);
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          if (4 * g + e < cnt) hrow[tokC[e]] = s[e] * kLn2;
-          if (16 + 4 * g + e < cnt) hrow[tokC[4 + e]] = s[4 + e] * kLn2;
-        }
-      }
-      if (!RAGGED && logits && mt * 16 + n < H) {      // logits out, for importance tracking
-        float* row = logits + (size_t)(mt * 16 + n) * p.T_cap + base + 4 * g;
-#pragma unroll
-        for (int tt = 0; tt < 2; ++tt) {
-          if ((p.T_cap & 3) == 0 && 16 * tt + 4 * g + 3 < cnt) {
-            // four consecutive tokens of one head: one 16-byte store (the four lanes of a head
-            // write two contiguous 64-byte runs)
-            const f32x4_t v = {s[4 * tt] * kLn2, s[4 * tt + 1] * kLn2, s[4 * tt + 2] * kLn2, s[4 * tt + 3] * kLn2};
-            *(f32x4_t*)(row + 16 * tt) = v;
-          } else {
-#pragma unroll
-            for (int e = 0; e < 4; ++e)
-              if (16 * tt + 4 * g + e < cnt) row[16 * tt + e] = s[4 * tt + e] * kLn2;
-          }
+          const int ta = RAGGED ? tokC[e] : base + 4 * g + e;
+          const int tb = RAGGED ? tokC[4 + e] : base + 16 + 4 * g + e;
+          if (4 * g + e < cnt) hcol[(size_t)ta * H] = s[e] * kLn2;
+          if (16 + 4 * g + e < cnt) hcol[(size_t)tb * H] = s[4 + e] * kLn2;
         }
       }
       float tmax = fmaxf(fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])), fmaxf(fmaxf(s[4], s[5]), fmaxf(s[6], s[7])));

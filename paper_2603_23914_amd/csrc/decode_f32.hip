@@ -72,7 +72,7 @@ f32_scores(const float* __restrict__ Ck, const float* __restrict__ qp,
   double acc = 0.0;
   for (int j = 0; j < rk; ++j) acc += (double)row[j] * (double)qh[j];
   S[((size_t)b * H + h) * T + t] = (float)acc;
-  if (scores) scores[((size_t)b * H + h) * T_cap + t] = (float)acc;
+  if (scores) scores[((size_t)b * T_cap + t) * H + h] = (float)acc;     // [B][T_cap][H]
 }
 
 // grid (H, B): softmax, weighted coefficient sum, expansion through Bv.

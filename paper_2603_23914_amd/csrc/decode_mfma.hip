@@ -321,7 +321,7 @@ struct AttnParams {
   // row does not exist yet; its softmax weight is exported and the expansion pass adds it
   int defer_v;          // 0 or 1
   float* pnew;          // [B][H] weight of token T-1 relative to the last split's reference
-  float* scores;        // [B][H][T_cap] scaled logits in natural-log units, or null
+  float* scores;        // [B][T_cap][H] scaled logits in natural-log units, or null
   int dbg;              // kernel studies (AP_KERNEL_TIMERS builds only, else 0): 1 = no loads,
                         // 2 = no math, 4 = phase timers, 8 = per-tile stamps
   unsigned long long* dbg_out;
@@ -395,7 +395,7 @@ struct WaveCtx {
   int t_lo, ntl;     // first tile and number of tiles of this split
   int Tv;            // value rows that exist: T, or T-1 while the newest token's row is deferred
   float* pnew;
-  float* scores;     // this sequence's [H][T_cap] logit rows, or null
+  float* scores;     // this sequence's [T_cap][H] logits, or null
   int T_cap;
   // softmax ownership: lane = 8*head_local + slot, slot = 4*tt + gg covers tokens
   // 16*tt + 4*gg .. +3 of the tile for head o_hh
@@ -527,20 +527,13 @@ struct WaveCtx {
 #pragma unroll
       for (int sw = 1; sw < 4; ++sw) sc += xchg[sw * 16 * MT * 9 + xi];
     }
-    if (scores && o_hh < H) {                   // logits out, for importance tracking
+    if (scores && o_hh < H) {                   // logits out, for importance tracking: [token][head]
       const int slot = 16 * o_tt + 4 * o_gg;
-      if (!RAGGED && (T_cap & 3) == 0 && slot + 3 < valid) {
-        // four consecutive tokens of one head: one 16-byte store (the eight lanes of a head
-        // then write a contiguous 128-byte run)
-        const f32x4_t v = {sc[0] * kLn2, sc[1] * kLn2, sc[2] * kLn2, sc[3] * kLn2};
-        *(f32x4_t*)(scores + (size_t)o_hh * T_cap + gtile(t) * kTile + slot) = v;
-      } else {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          if (slot + i < valid) {
-            const int tok = RAGGED ? idxb[t * kTile + slot + i] : gtile(t) * kTile + slot + i;
-            scores[(size_t)o_hh * T_cap + tok] = sc[i] * kLn2;
-          }
+      for (int i = 0; i < 4; ++i) {
+        if (slot + i < valid) {
+          const int tok = RAGGED ? idxb[t * kTile + slot + i] : gtile(t) * kTile + slot + i;
+          scores[(size_t)tok * H + o_hh] = sc[i] * kLn2;
         }
       }
     }
@@ -607,19 +600,13 @@ struct WaveCtx {
       valid[sub] = tile_valid(t0 + sub);
       newl[sub] = tile_new(t0 + sub);
     }
-    if (scores && o_hh < H) {                   // logits out, for importance tracking
+    if (scores && o_hh < H) {                   // logits out, for importance tracking: [token][head]
 #pragma unroll
-      for (int sub = 0; sub < 4; ++sub) {
-        if ((T_cap & 3) == 0 && slot + 3 < valid[sub]) {
-          const f32x4_t v = {sc[sub][0] * kLn2, sc[sub][1] * kLn2, sc[sub][2] * kLn2, sc[sub][3] * kLn2};
-          *(f32x4_t*)(scores + (size_t)o_hh * T_cap + gtile(t0 + sub) * kTile + slot) = v;
-        } else {
+      for (int sub = 0; sub < 4; ++sub)
 #pragma unroll
-          for (int i = 0; i < 4; ++i)
-            if (slot + i < valid[sub])
-              scores[(size_t)o_hh * T_cap + gtile(t0 + sub) * kTile + slot + i] = sc[sub][i] * kLn2;
-        }
-      }
+        for (int i = 0; i < 4; ++i)
+          if (slot + i < valid[sub])
+            scores[(size_t)(gtile(t0 + sub) * kTile + slot + i) * H + o_hh] = sc[sub][i] * kLn2;
     }
     float tmax = -INFINITY;
 #pragma unroll

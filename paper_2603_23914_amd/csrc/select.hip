@@ -18,6 +18,7 @@
 // ids replace the keys in that copy once they are known, and the ranks leave in a coalesced
 // pass.  All integer work, results are unique.
 #include "ap_common.hpp"
+#include "lane_ops.hpp"
 
 namespace ap {
 namespace {
@@ -35,7 +36,16 @@ struct SelectParams {
   int32_t* rank_out;
   int32_t* bucket_off;
   int32_t* bucket_idx;
+#ifdef AP_KERNEL_TIMERS
+  unsigned long long* stamps;   // kernel studies: 16 time stamps of row 0 (100 MHz counter)
+#endif
 };
+
+#ifdef AP_KERNEL_TIMERS
+#define AP_SELECT_STAMP(i) do { if (blockIdx.x == 0 && threadIdx.x == 0) p.stamps[i] = wall_clock64(); } while (0)
+#else
+#define AP_SELECT_STAMP(i) do { } while (0)
+#endif
 
 // Order-preserving map float -> uint32 (larger value, larger key); -0 and +0 share a key.
 __device__ __forceinline__ uint32_t key_of(float m) {
@@ -44,60 +54,43 @@ __device__ __forceinline__ uint32_t key_of(float m) {
   return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
-// Exclusive prefix sum of one int per thread over the workgroup (thread order); *total
-// receives the workgroup sum.  wave_tot: kWaves ints of LDS.  Two barriers.
-__device__ __forceinline__ int block_excl_scan(int v, int* wave_tot, int* total) {
-  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-  int incl = v;
-#pragma unroll
-  for (int o = 1; o < 64; o <<= 1) {
-    const int up = __shfl_up(incl, o);
-    if (lane >= o) incl += up;
-  }
-  __syncthreads();                       // previous use of wave_tot is over
-  if (lane == 63) wave_tot[w] = incl;
-  __syncthreads();
-  int base = 0, tot = 0;
-#pragma unroll
-  for (int i = 0; i < kWaves; ++i) {
-    const int x = wave_tot[i];
-    if (i < w) base += x;
-    tot += x;
-  }
-  *total = tot;
-  return base + incl - v;
-}
-
-// The same for N values per thread at once (two barriers for all of them).  wave_tot: N * kWaves ints.
+// Exclusive prefix sums over the workgroup (thread order) of the first n of N values per thread
+// at once (two barriers for all of them; n is the same for every thread, v[k] stays as it is
+// for k >= n).  wave_tot: N * kWaves ints.
 template <int N>
-__device__ __forceinline__ void block_excl_scan_n(int (&v)[N], int* wave_tot) {
+__device__ __forceinline__ void block_excl_scan_n(int (&v)[N], int n, int* wave_tot) {
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   int incl[N];
 #pragma unroll
   for (int k = 0; k < N; ++k) incl[k] = v[k];
 #pragma unroll
-  for (int o = 1; o < 64; o <<= 1) {
+  for (int k = 0; k < N; ++k) {
+    if (k < n) {
 #pragma unroll
-    for (int k = 0; k < N; ++k) {
-      const int up = __shfl_up(incl[k], o);
-      if (lane >= o) incl[k] += up;
+      for (int o = 1; o < 64; o <<= 1) {
+        const int up = __shfl_up(incl[k], o);
+        if (lane >= o) incl[k] += up;
+      }
     }
   }
   __syncthreads();                       // previous use of wave_tot is over
   if (lane == 63) {
 #pragma unroll
-    for (int k = 0; k < N; ++k) wave_tot[k * kWaves + w] = incl[k];
+    for (int k = 0; k < N; ++k)
+      if (k < n) wave_tot[k * kWaves + w] = incl[k];
   }
   __syncthreads();
 #pragma unroll
   for (int k = 0; k < N; ++k) {
-    int base = 0;
+    if (k < n) {
+      int base = 0;
 #pragma unroll
-    for (int i = 0; i < kWaves; ++i) {
-      const int x = wave_tot[k * kWaves + i];
-      if (i < w) base += x;
+      for (int i = 0; i < kWaves; ++i) {
+        const int x = wave_tot[k * kWaves + i];
+        if (i < w) base += x;
+      }
+      v[k] = base + incl[k] - v[k];
     }
-    v[k] = base + incl[k] - v[k];
   }
 }
 
@@ -115,6 +108,7 @@ __global__ void __launch_bounds__(kThreads) select_ranks_kernel(const SelectPara
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int b = blockIdx.x, T = p.T, F = p.F, nb = F - 1;
   const float* m = p.mass + (size_t)b * T;
+  AP_SELECT_STAMP(0);
   auto slot_of = [](int t) -> int { return t + (t >> 5); };      // one pad word per 32 tokens
   if (STAGED) {
     for (int t0 = tid; t0 < T; t0 += 8 * kThreads) {        // eight loads in flight per thread
@@ -133,6 +127,7 @@ __global__ void __launch_bounds__(kThreads) select_ranks_kernel(const SelectPara
     __syncthreads();
   }
   auto key_at = [&](int t) -> uint32_t { return STAGED ? keys_lds[slot_of(t)] : key_of(m[t]); };
+  AP_SELECT_STAMP(1);
 
   // a cut at 0 or at T needs no threshold search
   bool active[kMaxF - 1];
@@ -182,6 +177,7 @@ __global__ void __launch_bounds__(kThreads) select_ranks_kernel(const SelectPara
       }
     }
     __syncthreads();
+    AP_SELECT_STAMP(2 + 2 * pass);
     // wave g walks boundary g's histogram from the top: lane l owns `per` consecutive digits
     bool act_w = false;
 #pragma unroll
@@ -189,32 +185,49 @@ __global__ void __launch_bounds__(kThreads) select_ranks_kernel(const SelectPara
     if (act_w) {
       const uint32_t* h = pass == 0 ? hist0 : hist[w];
       const int nbins = 1 << width;
-      const int per = nbins >= 64 ? nbins >> 6 : 1;
+      const int per = nbins >= 64 ? nbins >> 6 : 1;          // 64, 4, 4, 1: a power of two
+      auto suffix = [&](uint32_t v) -> uint32_t {            // sum over lanes >= lane
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+          const uint32_t dn = (uint32_t)__shfl_down((int)v, o);
+          if (lane + o < 64) v += dn;
+        }
+        return v;
+      };
+      // first level: lane l sums its `per` consecutive digits (read in an order rotated by the
+      // lane, so the lanes of a wave touch different banks) ...
       const int d0 = lane * per;
       uint32_t tot = 0;
-      if (d0 < nbins)
-        for (int j = 0; j < per; ++j) tot += h[d0 + j];
-      uint32_t incl = tot;               // sum over lanes >= lane
+      if (pass == 0) {                                       // 64 loads in flight, then one sum
+        uint32_t c64[64];
 #pragma unroll
-      for (int o = 1; o < 64; o <<= 1) {
-        const uint32_t dn = (uint32_t)__shfl_down((int)incl, o);
-        if (lane + o < 64) incl += dn;
+        for (int j = 0; j < 64; ++j) c64[j] = h[d0 + ((j + lane) & 63)];
+#pragma unroll
+        for (int j = 0; j < 64; ++j) tot += c64[j];
+      } else if (d0 < nbins) {
+        for (int j = 0; j < per; ++j) tot += h[d0 + ((j + lane) & (per - 1))];
       }
+      const uint32_t incl = suffix(tot);
       const uint32_t above = incl - tot;
       const uint32_t k = s_need[w];
-      if (above < k && k <= incl) {      // exactly one lane
-        uint32_t acc = above, digit = 0, left = k;
-        for (int j = per - 1; j >= 0; --j) {
-          const uint32_t c = h[d0 + j];
-          if (k <= acc + c) { digit = (uint32_t)(d0 + j); left = k - acc; break; }
-          acc += c;
+      const unsigned long long owner = __ballot(above < k && k <= incl);   // exactly one lane
+      if (owner) {
+        // ... second level: the digits of the owning lane's block, one per lane
+        const int L = __ffsll(owner) - 1;
+        const uint32_t k2 = k - (uint32_t)__shfl((int)above, L);
+        const uint32_t c = lane < per ? h[L * per + lane] : 0u;
+        const uint32_t incl2 = suffix(c);
+        const uint32_t above2 = incl2 - c;
+        if (lane < per && above2 < k2 && k2 <= incl2) {                    // exactly one lane
+          const uint32_t digit = (uint32_t)(L * per + lane);
+          s_prefix[w] = s_prefix[w] | (digit << shift);
+          s_need[w] = k2 - above2;
+          if (pass == 0) atomicOr(&mark[digit >> 5], 1u << (digit & 31u));
         }
-        s_prefix[w] = s_prefix[w] | (digit << shift);
-        s_need[w] = left;
-        if (pass == 0) atomicOr(&mark[digit >> 5], 1u << (digit & 31u));
       }
     }
     __syncthreads();
+    AP_SELECT_STAMP(3 + 2 * pass);
   }
 
   uint32_t kappa[kMaxF - 1], quota[kMaxF - 1];
@@ -238,7 +251,9 @@ __global__ void __launch_bounds__(kThreads) select_ranks_kernel(const SelectPara
 #pragma unroll
     for (int g = 0; g < kMaxF - 1; ++g) eq[g] += (key == kappa[g]) ? 1 : 0;
   }
-  block_excl_scan_n<kMaxF - 1>(eq, wave_tot);               // now: equal keys before t0
+  AP_SELECT_STAMP(10);
+  block_excl_scan_n<kMaxF - 1>(eq, nb, wave_tot);               // now: equal keys before t0
+  AP_SELECT_STAMP(11);
   int cnt[kMaxF];
 #pragma unroll
   for (int g = 0; g < kMaxF; ++g) cnt[g] = 0;
@@ -260,7 +275,9 @@ __global__ void __launch_bounds__(kThreads) select_ranks_kernel(const SelectPara
   }
 
   // ---- 3. slot inside the group's ascending index list
-  block_excl_scan_n<kMaxF>(cnt, wave_tot);
+  AP_SELECT_STAMP(12);
+  block_excl_scan_n<kMaxF>(cnt, F, wave_tot);
+  AP_SELECT_STAMP(13);
   int32_t* idx_row = p.bucket_idx + (size_t)b * T;
   for (int t = t0; t < t1; ++t) {
     const int grp = STAGED ? (int)keys_lds[slot_of(t)] : rank_row[t];
@@ -272,6 +289,7 @@ __global__ void __launch_bounds__(kThreads) select_ranks_kernel(const SelectPara
     if (!STAGED) rank_row[t] = rk;
     if (slot < T) idx_row[slot] = t;    // always true; keeps a logic error inside the buffer
   }
+  AP_SELECT_STAMP(14);
   if (STAGED) {                         // ranks out, consecutive threads to consecutive tokens
     __syncthreads();
     for (int t = tid; t < T; t += kThreads) {
@@ -286,28 +304,67 @@ __global__ void __launch_bounds__(kThreads) select_ranks_kernel(const SelectPara
 #pragma unroll
   for (int g = 0; g <= kMaxF; ++g) cut = tid == g ? p.bound[g] : cut;
   if (tid <= F) p.bucket_off[(size_t)b * (F + 1) + tid] = cut;
+  AP_SELECT_STAMP(15);
 }
 
 // Importance update of Eq. 1 for one new query: the attention weights of the query, averaged
-// over the heads, enter the moving average.  grid (ceil(T / 256), B), one thread per token.
+// over the heads, enter the moving average.  scores [B][T_cap][H]: the H logits of a token are
+// contiguous.
+//
+// update_importance_rows (H a multiple of 4, at most 256, 16-byte aligned pointers): grid
+// (ceil(T / 128), B), 256 threads.  A workgroup's 128 tokens are one contiguous run of 128 H
+// logits; thread i takes the i-th 16-byte word of it (four heads of one token), turns it into
+// the sum of four weights and leaves that in LDS; one thread per token then adds the token's
+// H / 4 partial sums in head order.
+constexpr int kImpTokens = 128;
+constexpr int kImpMaxH = 256;
 __global__ void __launch_bounds__(256)
-update_importance_kernel(const float* __restrict__ scores, const float* __restrict__ lse,
-                         float* __restrict__ mass, int H, int T, int T_cap, int64_t mass_stride,
-                         float alpha) {
+update_importance_rows(const float* __restrict__ scores, const float* __restrict__ lse,
+                       float* __restrict__ mass, int H, int T, int T_cap, int64_t mass_stride,
+                       float alpha) {
+  extern __shared__ float part[];                // [128 tokens][H / 4]
+  const int tid = threadIdx.x, b = blockIdx.y;
+  const int t0 = blockIdx.x * kImpTokens;
+  int nt = T - t0;
+  nt = nt < kImpTokens ? nt : kImpTokens;
+  const int H4 = H >> 2, n4 = nt * H4;
+  const f32x4_t* s4 = (const f32x4_t*)(scores + ((size_t)b * T_cap + t0) * H);
+  const f32x4_t* l4 = (const f32x4_t*)(lse + (size_t)b * H);
+  const float inv_h4 = 1.0f / (float)H4;         // i / H4 below: exact, i < 2^14
+  float* m = mass + (size_t)b * mass_stride + t0 + tid;
+  const float m_old = tid < nt ? *m : 0.f;       // asked for early, needed last
+  for (int i0 = tid; i0 < n4; i0 += 256 * 4) {   // four 16-byte loads in flight per thread
+    f32x4_t v[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) v[k] = i0 + 256 * k < n4 ? s4[i0 + 256 * k] : f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const int i = i0 + 256 * k;
+      if (i < n4) {
+        const f32x4_t l = l4[i - (int)(((float)i + 0.5f) * inv_h4) * H4];
+        part[i] = (__expf(v[k][0] - l[0]) + __expf(v[k][1] - l[1])) + (__expf(v[k][2] - l[2]) + __expf(v[k][3] - l[3]));
+      }
+    }
+  }
+  __syncthreads();
+  if (tid < nt) {
+    float acc = 0.f;
+    for (int j = 0; j < H4; ++j) acc += part[tid * H4 + j];
+    *m = alpha * m_old + (1.0f - alpha) * (acc / (float)H);
+  }
+}
+
+// Any H: one thread per token walks the token's H logits.  grid (ceil(T / 256), B).
+__global__ void __launch_bounds__(256)
+update_importance_any(const float* __restrict__ scores, const float* __restrict__ lse,
+                      float* __restrict__ mass, int H, int T, int T_cap, int64_t mass_stride,
+                      float alpha) {
   const int t = blockIdx.x * 256 + threadIdx.x, b = blockIdx.y;
   if (t >= T) return;
-  const float* s = scores + (size_t)b * H * T_cap + t;
+  const float* s = scores + ((size_t)b * T_cap + t) * H;
   const float* l = lse + (size_t)b * H;
   float acc = 0.f;
-  int h = 0;
-  for (; h + 8 <= H; h += 8) {                 // 8 independent loads in flight per thread
-    float v[8];
-#pragma unroll
-    for (int i = 0; i < 8; ++i) v[i] = s[(size_t)(h + i) * T_cap];
-#pragma unroll
-    for (int i = 0; i < 8; ++i) acc += __expf(v[i] - l[h + i]);
-  }
-  for (; h < H; ++h) acc += __expf(s[(size_t)h * T_cap] - l[h]);
+  for (int h = 0; h < H; ++h) acc += __expf(s[h] - l[h]);
   float* m = mass + (size_t)b * mass_stride + t;
   *m = alpha * *m + (1.0f - alpha) * (acc / (float)H);
 }
@@ -317,8 +374,14 @@ update_importance_kernel(const float* __restrict__ scores, const float* __restri
 ap_status launch_update_importance(const float* scores, const float* lse, float* mass, int B, int H,
                                    int T, int T_cap, int64_t mass_stride, float alpha,
                                    hipStream_t stream) {
-  hipLaunchKernelGGL(update_importance_kernel, dim3((T + 255) / 256, B), dim3(256), 0, stream, scores,
-                     lse, mass, H, T, T_cap, mass_stride, alpha);
+  const bool rows = (H & 3) == 0 && H <= kImpMaxH && (((uintptr_t)scores | (uintptr_t)lse) & 15) == 0;
+  if (rows) {
+    hipLaunchKernelGGL(update_importance_rows, dim3((T + kImpTokens - 1) / kImpTokens, B), dim3(256),
+                       (size_t)kImpTokens * H, stream, scores, lse, mass, H, T, T_cap, mass_stride, alpha);
+  } else {
+    hipLaunchKernelGGL(update_importance_any, dim3((T + 255) / 256, B), dim3(256), 0, stream, scores, lse,
+                       mass, H, T, T_cap, mass_stride, alpha);
+  }
   return check_launch("ap_update_importance");
 }
 
@@ -328,7 +391,6 @@ ap_status launch_select_ranks(const float* mass, int B, int T, int F, const int3
                               const int32_t* cum_num, int32_t den, int32_t* rank_out,
                               int32_t* bucket_off, int32_t* bucket_idx, void* ws,
                               hipStream_t stream) {
-  (void)ws;
   AP_REQUIRE(T <= (1 << 30), AP_ERR_UNSUPPORTED, "ap_select_ranks: T must be <= 2^30");
   SelectParams p;
   p.mass = mass;
@@ -342,6 +404,11 @@ ap_status launch_select_ranks(const float* mass, int B, int T, int F, const int3
   p.rank_out = rank_out;
   p.bucket_off = bucket_off;
   p.bucket_idx = bucket_idx;
+#ifdef AP_KERNEL_TIMERS
+  p.stamps = (unsigned long long*)ws;
+#else
+  (void)ws;
+#endif
   if (T <= kStagedMax) {
     static bool attr_set = false;
     if (!attr_set) {

@@ -160,7 +160,7 @@ def test_decode_small_rank(dtype, B, H, d, r, T):
     dCk2, dCv2 = dCk.clone(), dCv.clone()
     out = torch.empty((B, H, d), dtype=torch.float32, device="cuda")
     lse_t = torch.empty((B, H), dtype=torch.float32, device="cuda")
-    scores = torch.full((B, H, case.T_cap), float("nan"), dtype=torch.float32, device="cuda")
+    scores = torch.full((B, case.T_cap, H), float("nan"), dtype=torch.float32, device="cuda")
     ws = workspace(ap.ap_decode_workspace_bytes(B, H, d, T + 1, r, ap._DT[TORCH_DT[dtype]]))
     ap.ap_decode_step(dq, dkn, dvn, dCk, dCv, dBk, dBv, out, ws, T=T + 1, sm_scale=1.0 / math.sqrt(d),
                       lse=lse_t, scores=scores)
@@ -178,7 +178,7 @@ def test_decode_small_rank(dtype, B, H, d, r, T):
     assert torch.equal(dCv2.view(torch.int16), dCv.view(torch.int16))
     assert_close(to_host64(out2[:nb]), ref2, dtype, "small rank fused step, no logits")
     assert np.abs(to_host64(lse2) - to_host64(lse_t)).max() <= 2e-3 * max(1.0, float(lse_t.abs().max()))
-    A = np.exp(to_host64(scores[0, :, :T + 1]) - to_host64(lse_t[0])[:, None])
+    A = np.exp(to_host64(scores[0, :T + 1, :]).T - to_host64(lse_t[0])[:, None])
     Bk0 = P(case.Bk) if case.Bk.ndim == 2 else P(case.Bk)[0]
     A_ref = oracle.attention_probs(P(q)[0], P(Ck_h)[0, :T + 1], Bk0)
     assert np.abs(A - A_ref).max() <= 2e-3 * A_ref.max()

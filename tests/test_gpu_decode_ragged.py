@@ -165,7 +165,7 @@ def test_ragged_small_rank_writes_the_logits(dtype, B, H, d, r, T, granks, cum, 
     dq, dCk, dCv, dBk, dBv = (to_dev(x, dtype) for x in (q, case.Ck, case.Cv, case.Bk, case.Bv))
     out = torch.empty((B, H, d), dtype=torch.float32, device="cuda")
     lse = torch.empty((B, H), dtype=torch.float32, device="cuda")
-    scores = torch.full((B, H, T), float("nan"), dtype=torch.float32, device="cuda")
+    scores = torch.full((B, T, H), float("nan"), dtype=torch.float32, device="cuda")
     ws = workspace(ap.ap_decode_workspace_bytes(B, H, d, T, r, ap._DT[TORCH_DT[dtype]]))
     ap.ap_decode_attn(dq, dCk, dCv, dBk, dBv, out, ws, T=T, sm_scale=1.0 / math.sqrt(d), rank_k=rank, rank_v=rank,
                       bucket_off=off, bucket_idx=idx, F=len(granks), lse=lse, scores=scores)
@@ -174,6 +174,6 @@ def test_ragged_small_rank_writes_the_logits(dtype, B, H, d, r, T, granks, cum, 
     P = lambda x: oracle.promote(x, dtype)
     assert torch.isfinite(scores).all()
     for b in range(B):
-        A = np.exp(to_host64(scores[b]) - to_host64(lse[b])[:, None])
+        A = np.exp(to_host64(scores[b]).T - to_host64(lse[b])[:, None])
         A_ref = oracle.attention_probs(P(q)[b], P(case.Ck)[b, :T], P(case.Bk)[b], rank_k=rank_np[b])
         assert np.abs(A - A_ref).max() <= 2e-3 * A_ref.max()

@@ -32,7 +32,7 @@ def test_decode_calls_in_a_captured_graph(dtype, B, H, d, r, T):
     def fresh():
         return (dCk0.clone(), dCv0.clone(), torch.zeros((B, H, d), dtype=torch.float32, device="cuda"),
                 torch.zeros((B, H), dtype=torch.float32, device="cuda"),
-                torch.zeros((B, H, case.T_cap), dtype=torch.float32, device="cuda"))
+                torch.zeros((B, case.T_cap, H), dtype=torch.float32, device="cuda"))
 
     eager = fresh()
     run(*eager)

@@ -47,12 +47,12 @@ def test_scores_give_the_attention_weights(dtype, B, H, d, r, T):
     T_cap = case.Ck.shape[1]
     out = torch.empty((B, H, d), dtype=torch.float32, device="cuda")
     lse = torch.empty((B, H), dtype=torch.float32, device="cuda")
-    scores = torch.full((B, H, T_cap), float("nan"), dtype=torch.float32, device="cuda")
+    scores = torch.full((B, T_cap, H), float("nan"), dtype=torch.float32, device="cuda")
     ws = workspace(ap.ap_decode_workspace_bytes(B, H, d, T, r, ap._DT[TORCH_DT[dtype]]))
     ap.ap_decode_attn(dq, dCk, dCv, dBk, dBv, out, ws, T=T, sm_scale=1.0 / math.sqrt(d), lse=lse,
                       scores=scores)
     torch.cuda.synchronize()
-    s = to_host64(scores)[:, :, :T]
+    s = to_host64(scores)[:, :T, :].transpose(0, 2, 1)
     assert np.isfinite(s).all(), "a logit of an attended token was not written"
     A = np.exp(s - to_host64(lse)[:, :, None])
     ref = oracle_probs(dtype, q, case.Ck, case.Bk, T)
@@ -67,7 +67,8 @@ def test_scores_give_the_attention_weights(dtype, B, H, d, r, T):
 
 
 @pytest.mark.parametrize("B,H,T,T_cap,stride,alpha", [(3, 40, 1000, 1024, 1100, 0.9), (1, 7, 5, 5, 5, 0.0),
-                                                      (2, 32, 257, 300, 257, 1.0), (2, 8, 4224, 4224, 4224, 0.5)])
+                                                      (2, 32, 257, 300, 257, 1.0), (2, 8, 4224, 4224, 4224, 0.5),
+                                                      (1, 256, 200, 200, 200, 0.3), (1, 260, 130, 131, 130, 0.3)])
 def test_update_importance_kernel(B, H, T, T_cap, stride, alpha):
     """The moving average alone, on logits and log-sum-exp made on the host."""
     from paper_2603_23914_amd import binding as ap
@@ -76,7 +77,7 @@ def test_update_importance_kernel(B, H, T, T_cap, stride, alpha):
     m = s[:, :, :T].astype(np.float64)
     lse = (np.log(np.exp(m - m.max(axis=2, keepdims=True)).sum(axis=2)) + m.max(axis=2)).astype(np.float32)
     mass0 = rng.random((B, stride)).astype(np.float32)
-    ds, dl, dm = (torch.from_numpy(x).cuda() for x in (s, lse, mass0))
+    ds, dl, dm = (torch.from_numpy(x).cuda() for x in (np.ascontiguousarray(s.transpose(0, 2, 1)), lse, mass0))
     ap.ap_update_importance(ds, dl, dm, T=T, alpha=alpha)
     torch.cuda.synchronize()
     got = dm.cpu().numpy()
@@ -104,7 +105,7 @@ def test_importance_loop_feeds_rank_selection():
     ref_mass = mass0.astype(np.float64)
     out = torch.empty((B, H, d), dtype=torch.float32, device="cuda")
     lse = torch.empty((B, H), dtype=torch.float32, device="cuda")
-    scores = torch.empty((B, H, T_cap), dtype=torch.float32, device="cuda")
+    scores = torch.empty((B, T_cap, H), dtype=torch.float32, device="cuda")
     rank_np = None
     rank = off = idx = None
     for step in range(steps):

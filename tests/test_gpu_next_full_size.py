@@ -56,7 +56,7 @@ def test_importance_tracking_full_size():
     mass0 = mass.clone()
     out = torch.empty((B, H, d), dtype=torch.float32, device="cuda")
     lse = torch.empty((B, H), dtype=torch.float32, device="cuda")
-    scores = torch.empty((B, H, T), dtype=torch.float32, device="cuda")
+    scores = torch.empty((B, T, H), dtype=torch.float32, device="cuda")
     ws = workspace(ap.ap_decode_workspace_bytes(B, H, d, T, r, ap.AP_BF16))
     print("importance, 64 sequences at T=4224", flush=True)
     ap.ap_decode_step(q, kn, vn, Ck, Cv, Bk, Bv, out, ws, T=T, sm_scale=1.0 / math.sqrt(d), lse=lse, scores=scores)
