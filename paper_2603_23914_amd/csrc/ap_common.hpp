@@ -126,7 +126,8 @@ ap_status launch_quantize_i8(const void* C, void* codes, void* scales, int B, in
 bool basis_rows_applies(int HD, int B);
 ap_status launch_basis_rows(ap_dtype dt, const void* Bm, int64_t bstride, const void* x,
                             const void* q, void* C, void* Qp, int B, int H, int Hp, int d, int HD,
-                            int r, int row0, int T_cap, float scale, hipStream_t stream);
+                            int r, int row0, int T_cap, float scale, hipStream_t stream,
+                            const void* Bm2 = nullptr, const void* x2 = nullptr, void* C2 = nullptr);
 int expand_row_blocks(int B, int r);   // row blocks (= partial output slices) of expand_append
 ap_status launch_expand_append(ap_dtype dt, bool out_f32, const void* Bv, int64_t bstride,
                                const void* v_new, void* Cv, const float* part_ml,

@@ -31,6 +31,11 @@ struct RowsParams {
   int H, Hp, d, HD, r, row0, T_cap;
   int rpw;                // consecutive rows per wave (a workgroup owns 4 * rpw rows)
   float scale;
+  // PAIR: a second DOT job of the same shape in the same launch (blockIdx.z = 1), e.g. the
+  // value row of a step appended next to the key row
+  const uint16_t* Bm2;
+  const uint16_t* x2;
+  uint16_t* C2;
 };
 
 template <class Tag>
@@ -43,7 +48,8 @@ __device__ __forceinline__ void split_hi_lo(float x, uint16_t& hi, uint16_t& lo)
 // axis; a wave walks its rows through a ring of NBUF row buffers in registers, so NBUF - 1
 // rows (HD * 2 bytes each) are in flight while one is reduced.
 // LPH = d / 8 lanes share a head (FOLD; 1 when the kernel does not fold).
-template <class Tag, int KPC, int NBUF, bool DOT, bool FOLD, int LPH>
+// PAIR: grid.z = 2; the workgroups of z = 1 run the second job (DOT only) on Bm2, x2, C2.
+template <class Tag, int KPC, int NBUF, bool DOT, bool FOLD, int LPH, bool PAIR = false>
 __global__ void __launch_bounds__(256) basis_rows(const RowsParams p) {
   extern __shared__ __attribute__((aligned(16))) float qtile[];   // FOLD: [Hp][4 rpw + 1]
   const int tid = threadIdx.x, lane = tid & 63;
@@ -51,7 +57,11 @@ __global__ void __launch_bounds__(256) basis_rows(const RowsParams p) {
   const int rpw = p.rpw, rows_wg = 4 * rpw, pitch = rows_wg + 1;
   const int b = blockIdx.y, j0 = blockIdx.x * rows_wg;
   const int HD = p.HD, r = p.r;
-  const uint16_t* Bb = p.Bm + (size_t)b * p.bstride;
+  const bool second = PAIR && blockIdx.z == 1;
+  const bool fold = FOLD && !second;
+  const uint16_t* Bb = (second ? p.Bm2 : p.Bm) + (size_t)b * p.bstride;
+  const uint16_t* xv = second ? p.x2 : p.x;
+  uint16_t* Cb = second ? p.C2 : p.C;
   u32x4_t buf[NBUF][KPC];
   // passes beyond the hidden axis re-read the lane's first chunk (their vector slices are
   // zero), so the loads carry no branches and issue back to back
@@ -74,13 +84,13 @@ __global__ void __launch_bounds__(256) basis_rows(const RowsParams p) {
   for (int pp = 0; pp < KPC; ++pp) {
     const int e0 = pp * 512 + lane * 8;
     const u32x4_t z = {0, 0, 0, 0};
-    if (DOT) xs[pp] = e0 < HD ? *(const u32x4_t*)(p.x + (size_t)b * HD + e0) : z;
-    if (FOLD) qs[pp] = e0 < HD ? *(const u32x4_t*)(p.q + (size_t)b * HD + e0) : z;
+    if (DOT) xs[pp] = e0 < HD ? *(const u32x4_t*)(xv + (size_t)b * HD + e0) : z;
+    if (FOLD) qs[pp] = e0 < HD && fold ? *(const u32x4_t*)(p.q + (size_t)b * HD + e0) : z;
   }
   const int last = rpw - 1;
 #pragma unroll
   for (int u = 0; u + 1 < NBUF; ++u) load_row(buf[u], u < last ? u : last);
-  if (FOLD) {
+  if (fold) {
     for (int i = tid; i < p.Hp * pitch; i += 256) qtile[i] = 0.f;   // padded heads stay 0
     __syncthreads();
   }
@@ -95,9 +105,9 @@ __global__ void __launch_bounds__(256) basis_rows(const RowsParams p) {
       for (int pp = 0; pp < KPC; ++pp) acc = dot8<Tag>(row[pp], xs[pp], acc);
       acc = wave_sum(acc);
       if (lane == 0 && live)
-        p.C[((size_t)b * p.T_cap + p.row0) * r + j0 + jl] = f32_to_bits(acc, Tag{});
+        Cb[((size_t)b * p.T_cap + p.row0) * r + j0 + jl] = f32_to_bits(acc, Tag{});
     }
-    if (FOLD) {
+    if (fold) {
 #pragma unroll
       for (int pp = 0; pp < KPC; ++pp) {
         float part = dot8<Tag>(row[pp], qs[pp], 0.f);
@@ -120,7 +130,7 @@ __global__ void __launch_bounds__(256) basis_rows(const RowsParams p) {
       reduce_row(buf[u], i + u);
     }
   }
-  if (FOLD) {
+  if (fold) {
     __syncthreads();
     // consecutive rank positions of one head leave as one contiguous segment per part
     for (int i = tid; i < p.Hp * rows_wg; i += 256) {
@@ -602,21 +612,21 @@ merge_splits(const float* __restrict__ part_ml, const float* __restrict__ part_U
 int basis_rows_per_wave(int B, int r);
 namespace {
 
-template <class Tag, bool DOT, bool FOLD>
+template <class Tag, bool DOT, bool FOLD, bool PAIR>
 ap_status launch_rows(RowsParams p, int B, hipStream_t stream) {
   const int rpw = basis_rows_per_wave(B, p.r);
   p.rpw = rpw;
   const int rows_wg = 4 * rpw;
-  const dim3 grid((p.r + rows_wg - 1) / rows_wg, B);
+  const dim3 grid((p.r + rows_wg - 1) / rows_wg, B, PAIR ? 2 : 1);
   const size_t lds = FOLD ? (size_t)p.Hp * (rows_wg + 1) * 4 : 0;
   const int kpc = (p.HD + 511) / 512;
 #define AP_ROWS(K, NB)                                                                        \
   if (kpc <= K) {                                                                             \
-    if (!FOLD) hipLaunchKernelGGL((basis_rows<Tag, K, NB, DOT, FOLD, 1>), grid, dim3(256), lds, stream, p);            \
-    else if (p.d == 128) hipLaunchKernelGGL((basis_rows<Tag, K, NB, DOT, FOLD, FOLD ? 16 : 1>), grid, dim3(256), lds, stream, p); \
-    else if (p.d == 64) hipLaunchKernelGGL((basis_rows<Tag, K, NB, DOT, FOLD, FOLD ? 8 : 1>), grid, dim3(256), lds, stream, p);   \
-    else if (p.d == 256) hipLaunchKernelGGL((basis_rows<Tag, K, NB, DOT, FOLD, FOLD ? 32 : 1>), grid, dim3(256), lds, stream, p); \
-    else hipLaunchKernelGGL((basis_rows<Tag, K, NB, DOT, FOLD, FOLD ? 4 : 1>), grid, dim3(256), lds, stream, p);                  \
+    if (!FOLD) hipLaunchKernelGGL((basis_rows<Tag, K, NB, DOT, FOLD, 1, PAIR>), grid, dim3(256), lds, stream, p);            \
+    else if (p.d == 128) hipLaunchKernelGGL((basis_rows<Tag, K, NB, DOT, FOLD, FOLD ? 16 : 1, PAIR>), grid, dim3(256), lds, stream, p); \
+    else if (p.d == 64) hipLaunchKernelGGL((basis_rows<Tag, K, NB, DOT, FOLD, FOLD ? 8 : 1, PAIR>), grid, dim3(256), lds, stream, p);   \
+    else if (p.d == 256) hipLaunchKernelGGL((basis_rows<Tag, K, NB, DOT, FOLD, FOLD ? 32 : 1, PAIR>), grid, dim3(256), lds, stream, p); \
+    else hipLaunchKernelGGL((basis_rows<Tag, K, NB, DOT, FOLD, FOLD ? 4 : 1, PAIR>), grid, dim3(256), lds, stream, p);                  \
     return AP_OK;                                                                             \
   }
   AP_ROWS(2, 3) AP_ROWS(4, 3) AP_ROWS(8, 3) AP_ROWS(10, 3)
@@ -630,21 +640,30 @@ ap_status launch_rows(RowsParams p, int B, hipStream_t stream) {
 
 bool basis_rows_applies(int HD, int B) { return HD % 8 == 0 && HD <= 8192 && B <= 65535; }
 
-// Append (x != null) and / or fold (q != null) in one pass over Bm.
+// Append (x != null) and / or fold (q != null) in one pass over Bm.  With Bm2, x2, C2 (and x)
+// given, a second append of the same shape (C2's row row0 = Bm2 . x2) runs in the same launch.
 ap_status launch_basis_rows(ap_dtype dt, const void* Bm, int64_t bstride, const void* x,
                             const void* q, void* C, void* Qp, int B, int H, int Hp, int d, int HD,
-                            int r, int row0, int T_cap, float scale, hipStream_t stream) {
+                            int r, int row0, int T_cap, float scale, hipStream_t stream,
+                            const void* Bm2, const void* x2, void* C2) {
   RowsParams p{(const uint16_t*)Bm, bstride, (const uint16_t*)x, (const uint16_t*)q,
-               (uint16_t*)C, (uint16_t*)Qp, H, Hp, d, HD, r, row0, T_cap, 4, scale};
-  const bool dot = x != nullptr, fold = q != nullptr;
-  if (dt == AP_F16) {
-    if (dot && fold) return launch_rows<F16Tag, true, true>(p, B, stream);
-    if (dot) return launch_rows<F16Tag, true, false>(p, B, stream);
-    return launch_rows<F16Tag, false, true>(p, B, stream);
+               (uint16_t*)C, (uint16_t*)Qp, H, Hp, d, HD, r, row0, T_cap, 4, scale,
+               (const uint16_t*)Bm2, (const uint16_t*)x2, (uint16_t*)C2};
+  const bool dot = x != nullptr, fold = q != nullptr, pair = Bm2 != nullptr;
+  if (pair && !(dot && x2 && C2)) {
+    set_error("basis pass: a second append needs a first one and all of Bm2, x2, C2");
+    return AP_ERR_INVALID_ARG;
   }
-  if (dot && fold) return launch_rows<BF16Tag, true, true>(p, B, stream);
-  if (dot) return launch_rows<BF16Tag, true, false>(p, B, stream);
-  return launch_rows<BF16Tag, false, true>(p, B, stream);
+  if (dt == AP_F16) {
+    if (pair) return fold ? launch_rows<F16Tag, true, true, true>(p, B, stream) : launch_rows<F16Tag, true, false, true>(p, B, stream);
+    if (dot && fold) return launch_rows<F16Tag, true, true, false>(p, B, stream);
+    if (dot) return launch_rows<F16Tag, true, false, false>(p, B, stream);
+    return launch_rows<F16Tag, false, true, false>(p, B, stream);
+  }
+  if (pair) return fold ? launch_rows<BF16Tag, true, true, true>(p, B, stream) : launch_rows<BF16Tag, true, false, true>(p, B, stream);
+  if (dot && fold) return launch_rows<BF16Tag, true, true, false>(p, B, stream);
+  if (dot) return launch_rows<BF16Tag, true, false, false>(p, B, stream);
+  return launch_rows<BF16Tag, false, true, false>(p, B, stream);
 }
 
 ap_status launch_fold_heads(ap_dtype dt, const void* Bk, int64_t bstride, const void* q, void* Qp, int B,

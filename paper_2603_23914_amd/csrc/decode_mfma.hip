@@ -1342,22 +1342,27 @@ ap_status run_decode(const DecodeArgs& a) {
   float* U = (float*)(ws + wl.u);
   // fold (and, for a fused step, the append of the key row in the same pass over B_k)
   ap_status st;
+  // a value row that the expansion pass does not produce is appended in the same launch as the
+  // key row (second job of the basis pass)
+  const bool pair_v = a.v_new && !one_pass_v && a.k_new;
   if (Hkv == a.H) {
     st = launch_basis_rows(a.dt, a.Bk, a.basis_batch_stride, a.k_new, a.q, (void*)a.Ck, Qp, a.B, a.H, Hp,
-                           a.d, a.H * a.d, a.r, a.T - 1, a.T_cap, a.sm_scale * kLog2e, a.stream);
+                           a.d, a.H * a.d, a.r, a.T - 1, a.T_cap, a.sm_scale * kLog2e, a.stream,
+                           pair_v ? a.Bv : nullptr, pair_v ? a.v_new : nullptr, pair_v ? (void*)a.Cv : nullptr);
   } else {
     // grouped queries: the key row is appended by a pass of its own over the (small) basis,
     // the fold runs per query head
     st = AP_OK;
     if (a.k_new)
       st = launch_basis_rows(a.dt, a.Bk, a.basis_batch_stride, a.k_new, nullptr, (void*)a.Ck, nullptr,
-                             a.B, 0, 0, 8, HDkv, a.r, a.T - 1, a.T_cap, 1.0f, a.stream);
+                             a.B, 0, 0, 8, HDkv, a.r, a.T - 1, a.T_cap, 1.0f, a.stream,
+                             pair_v ? a.Bv : nullptr, pair_v ? a.v_new : nullptr, pair_v ? (void*)a.Cv : nullptr);
     if (st != AP_OK) return st;
     st = launch_fold_heads(a.dt, a.Bk, a.basis_batch_stride, a.q, Qp, a.B, a.H, Hkv, Hp, a.d, a.r,
                            a.sm_scale * kLog2e, a.stream);
   }
   if (st != AP_OK) return st;
-  if (a.v_new && !one_pass_v) {
+  if (a.v_new && !one_pass_v && !pair_v) {
     st = launch_basis_rows(a.dt, a.Bv, a.basis_batch_stride, a.v_new, nullptr, (void*)a.Cv, nullptr,
                            a.B, 0, 0, 8, HDkv, a.r, a.T - 1, a.T_cap, 1.0f, a.stream);
     if (st != AP_OK) return st;
