@@ -432,30 +432,56 @@ __global__ void __launch_bounds__(128) expand_append(const ExpandParams p) {
   }
   __syncthreads();
   // ---- A[h][jl] = sum_s 2^(m_s - m*) U_s[h, j0 + jl] / L
-  for (int i = tid; i < H * rpw; i += 128) {
-    const int h = i / rpw, jl = i - h * rpw;
-    float acc = 0.f;
-    if (j0 + jl < r) {
-      const size_t pb = (size_t)b * S * H + h;
-      if (wsp_fits) {
-        for (int s0 = 0; s0 < S; s0 += 8) {              // eight loads in flight at a time
-          float uv[8];
+  if (wsp_fits) {
+    // four (head, row) pairs and four splits at a time: sixteen loads in flight per thread, so
+    // the whole tile takes a few round trips to memory (the row ring stands still meanwhile)
+    const int n = H * rpw;
+    for (int i0 = tid; i0 < n; i0 += 4 * 128) {
+      int hh[4], jj[4];
+      bool ok[4];
+      size_t base[4];
+      float acc[4];
 #pragma unroll
-          for (int u = 0; u < 8; ++u)
-            uv[u] = s0 + u < S ? p.part_U[(pb + (size_t)(s0 + u) * H) * r + j0 + jl] : 0.f;
+      for (int u = 0; u < 4; ++u) {
+        const int i = i0 + 128 * u;
+        const int h = i < n ? i / rpw : 0, jl = i < n ? i - h * rpw : 0;
+        hh[u] = h;
+        jj[u] = jl;
+        ok[u] = i < n && j0 + jl < r;
+        base[u] = ((size_t)b * S * H + h) * r + (ok[u] ? j0 + jl : 0);
+        acc[u] = 0.f;
+      }
+      for (int s0 = 0; s0 < S; s0 += 4) {
+        float uv[4][4];
 #pragma unroll
-          for (int u = 0; u < 8; ++u)
-            if (s0 + u < S) acc = fmaf(wsp[(s0 + u) * H + h], uv[u], acc);
-        }
-      } else {
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+          for (int k = 0; k < 4; ++k)
+            uv[u][k] = s0 + k < S ? p.part_U[base[u] + (size_t)(s0 + k) * H * r] : 0.f;
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+          for (int k = 0; k < 4; ++k)
+            if (s0 + k < S) acc[u] = fmaf(wsp[(s0 + k) * H + hh[u]], uv[u][k], acc[u]);
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+        if (i0 + 128 * u < n) Atile[hh[u] * pitch + jj[u]] = ok[u] ? acc[u] * invL[hh[u]] : 0.f;
+    }
+  } else {
+    for (int i = tid; i < H * rpw; i += 128) {
+      const int h = i / rpw, jl = i - h * rpw;
+      float acc = 0.f;
+      if (j0 + jl < r) {
+        const size_t pb = (size_t)b * S * H + h;
         const float m = mstar[h];
         for (int s = 0; s < S; ++s)
           acc = fmaf(fast_exp2(p.part_ml[(pb + (size_t)s * H) * 2] - m),
                      p.part_U[(pb + (size_t)s * H) * r + j0 + jl], acc);
+        acc *= invL[h];
       }
-      acc *= invL[h];
+      Atile[h * pitch + jl] = acc;
     }
-    Atile[h * pitch + jl] = acc;
   }
   __syncthreads();
 
