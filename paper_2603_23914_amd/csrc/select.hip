@@ -37,12 +37,12 @@ struct SelectParams {
   int32_t* bucket_off;
   int32_t* bucket_idx;
 #ifdef AP_KERNEL_TIMERS
-  unsigned long long* stamps;   // kernel studies: 16 time stamps of row 0 (100 MHz counter)
+  unsigned long long* stamps;   // kernel studies: 16 time stamps of row 0's first and last thread (100 MHz counter)
 #endif
 };
 
 #ifdef AP_KERNEL_TIMERS
-#define AP_SELECT_STAMP(i) do { if (blockIdx.x == 0 && threadIdx.x == 0) p.stamps[i] = wall_clock64(); } while (0)
+#define AP_SELECT_STAMP(i) do { if (blockIdx.x == 0 && (threadIdx.x == 0 || threadIdx.x == 1023)) p.stamps[(threadIdx.x ? 16 : 0) + (i)] = wall_clock64(); } while (0)
 #else
 #define AP_SELECT_STAMP(i) do { } while (0)
 #endif
@@ -172,7 +172,7 @@ __global__ void __launch_bounds__(kThreads) select_ranks_kernel(const SelectPara
         const uint32_t hi = key >> (shift + width);
 #pragma unroll
         for (int g = 0; g < kMaxF - 1; ++g) {
-          if (active[g] && hi == (pre[g] >> (shift + width))) atomicAdd(&hist[g][dig], 1u);
+          if (g < nb && active[g] && hi == (pre[g] >> (shift + width))) atomicAdd(&hist[g][dig], 1u);
         }
       }
     }
@@ -249,7 +249,8 @@ __global__ void __launch_bounds__(kThreads) select_ranks_kernel(const SelectPara
   for (int t = t0; t < t1; ++t) {
     const uint32_t key = key_at(t);
 #pragma unroll
-    for (int g = 0; g < kMaxF - 1; ++g) eq[g] += (key == kappa[g]) ? 1 : 0;
+    for (int g = 0; g < kMaxF - 1; ++g)
+      if (g < nb) eq[g] += (key == kappa[g]) ? 1 : 0;       // nb is the same for all: a scalar branch
   }
   AP_SELECT_STAMP(10);
   block_excl_scan_n<kMaxF - 1>(eq, nb, wave_tot);               // now: equal keys before t0
@@ -263,15 +264,18 @@ __global__ void __launch_bounds__(kThreads) select_ranks_kernel(const SelectPara
     int grp = nb;
 #pragma unroll
     for (int g = kMaxF - 2; g >= 0; --g) {
-      const bool same = key == kappa[g];
-      const bool in_front = key > kappa[g] || (same && (uint32_t)eq[g] < quota[g]);
-      if (g < nb && in_front) grp = g;                      // membership is nested: keep the smallest
-      eq[g] += same ? 1 : 0;
+      if (g < nb) {
+        const bool same = key == kappa[g];
+        const bool in_front = key > kappa[g] || (same && (uint32_t)eq[g] < quota[g]);
+        if (in_front) grp = g;                              // membership is nested: keep the smallest
+        eq[g] += same ? 1 : 0;
+      }
     }
     if (STAGED) keys_lds[slot_of(t)] = (uint32_t)grp;       // the key is not needed again
     else rank_row[t] = grp;                                 // group id for now, rank below
 #pragma unroll
-    for (int g = 0; g < kMaxF; ++g) cnt[g] += (grp == g) ? 1 : 0;
+    for (int g = 0; g < kMaxF; ++g)
+      if (g < F) cnt[g] += (grp == g) ? 1 : 0;
   }
 
   // ---- 3. slot inside the group's ascending index list
@@ -284,7 +288,7 @@ __global__ void __launch_bounds__(kThreads) select_ranks_kernel(const SelectPara
     int slot = 0, rk = 0;
 #pragma unroll
     for (int g = 0; g < kMaxF; ++g) {
-      if (grp == g) { slot = p.bound[g] + cnt[g]; rk = p.grank[g]; cnt[g] += 1; }
+      if (g < F && grp == g) { slot = p.bound[g] + cnt[g]; rk = p.grank[g]; cnt[g] += 1; }
     }
     if (!STAGED) rank_row[t] = rk;
     if (slot < T) idx_row[slot] = t;    // always true; keeps a logic error inside the buffer
@@ -296,7 +300,8 @@ __global__ void __launch_bounds__(kThreads) select_ranks_kernel(const SelectPara
       const int grp = (int)keys_lds[slot_of(t)];
       int rk = 0;
 #pragma unroll
-      for (int g = 0; g < kMaxF; ++g) rk = grp == g ? p.grank[g] : rk;
+      for (int g = 0; g < kMaxF; ++g)
+        if (g < F) rk = grp == g ? p.grank[g] : rk;
       rank_row[t] = rk;
     }
   }
