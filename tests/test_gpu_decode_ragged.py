@@ -177,3 +177,52 @@ def test_ragged_small_rank_writes_the_logits(dtype, B, H, d, r, T, granks, cum, 
         A = np.exp(to_host64(scores[b]).T - to_host64(lse[b])[:, None])
         A_ref = oracle.attention_probs(P(q)[b], P(case.Ck)[b, :T], P(case.Bk)[b], rank_k=rank_np[b])
         assert np.abs(A - A_ref).max() <= 2e-3 * A_ref.max()
+
+
+
+@pytest.mark.parametrize("dtype,B,H,Hkv,d,r,T0,granks,cum,den", [
+    ("f16", 2, 8, 8, 64, 128, 70, (128, 64), (1, 4), 4),
+    ("bf16", 1, 4, 4, 256, 64, 33, (64, 16), (1, 2), 2),
+    ("f16", 2, 16, 16, 32, 192, 150, (192, 64), (1, 3), 3),
+    ("bf16", 3, 40, 40, 128, 640, 90, (640, 128), (1, 4), 4),
+    ("f16", 2, 32, 8, 128, 128, 120, (128, 64), (1, 2), 2),        # grouped queries
+    ("bf16", 2, 16, 4, 64, 64, 75, (64, 32), (1, 4), 4),           # grouped queries, small rank
+])
+def test_decode_step_with_per_token_ranks(dtype, B, H, Hkv, d, r, T0, granks, cum, den):
+    """Fused steps under per-token ranks: the expansion pass does not produce the new value row
+    then, so it is appended next to the key row.  Both appended rows equal those of ap_compact bit
+    for bit (the same whole-row pass) and the projection of Sec. 3.1 within rounding; the output
+    matches the oracle on the stored bits."""
+    from paper_2603_23914_amd import binding as ap
+    steps, F = 3, len(granks)
+    case = wl.decode_case(dtype, B, Hkv, d, r, T0, steps=steps, seed=47, append=True)
+    P = lambda x: oracle.promote(x, dtype)
+    bits = lambda t: t.view(torch.int16).cpu().numpy().view(np.uint16) if dtype == "bf16" else t.cpu().numpy()
+    dCk, dCv, dBk, dBv = (to_dev(x, dtype) for x in (case.Ck, case.Cv, case.Bk, case.Bv))
+    dCk2, dCv2 = dCk.clone(), dCv.clone()
+    out = torch.empty((B, H, d), dtype=torch.float32, device="cuda")
+    rng = wl.rng_for(47, B, T0, r)
+    for step in range(steps):
+        T = T0 + step + 1
+        print(f"step with ranks {dtype} B={B} H={H}/{Hkv} d={d} r={r} T={T}", flush=True)
+        mass = rng.random((B, T)).astype(np.float32)
+        mass[:, T - 1] = 2.0                                  # the token being appended: full rank
+        rank, off, idx = gpu_select(mass, granks, cum, den)
+        rank_np = rank.cpu().numpy()
+        kn, vn = wl.step_new_token(case, step, P(case.Bk), P(case.Bv))
+        q = wl.store(wl.rng_for(47, 77, step).standard_normal((B, H, d)), dtype)
+        dq, dkn, dvn = (to_dev(x, dtype) for x in (q, kn, vn))
+        ws = workspace(ap.ap_decode_workspace_bytes(B, H, d, T, r, ap._DT[TORCH_DT[dtype]]))
+        ap.ap_decode_step(dq, dkn, dvn, dCk, dCv, dBk, dBv, out, ws, T=T, sm_scale=1.0 / math.sqrt(d),
+                          rank_k=rank, rank_v=rank, bucket_off=off, bucket_idx=idx, F=F)
+        ap.ap_compact(dkn[:, None, :].contiguous(), dvn[:, None, :].contiguous(), dBk, dBv, dCk2, dCv2, n=1, row0=T - 1)
+        torch.cuda.synchronize()
+        assert torch.equal(dCk.view(torch.int16), dCk2.view(torch.int16)), f"step {step}: appended key row"
+        assert torch.equal(dCv.view(torch.int16), dCv2.view(torch.int16)), f"step {step}: appended value row"
+        Ck_h, Cv_h = bits(dCk), bits(dCv)
+        for C_h, Bm, x in ((Ck_h, case.Bk, kn), (Cv_h, case.Bv, vn)):
+            c_ref = oracle.compact(P(x)[0][None], P(Bm)[0])[0]
+            assert np.abs(P(C_h)[0, T - 1] - c_ref).max() <= 2.0 ** -7 * np.abs(c_ref).max()
+        ref_out = oracle.decode_attn_batched(P(q), P(Ck_h), P(Cv_h), P(case.Bk), P(case.Bv), T,
+                                             rank_k=rank_np, rank_v=rank_np, absorbed=True, kv_heads=Hkv)
+        assert_close(to_host64(out), ref_out, dtype, f"step {step} output")
