@@ -6,7 +6,9 @@
 // sorted position p is fully described by the p-th largest key kappa and by how many of the
 // tokens whose key equals kappa still fall in front of it (the quota), so
 //   1. a radix select finds (kappa, quota) of all F-1 boundaries at once (four passes over
-//      the row with digits of 12, 8, 8 and 4 bits, histograms in LDS);
+//      the row with digits of 12, 8, 8 and 4 bits, histograms in LDS; when few keys share the
+//      boundaries' first digits, the last three passes give way to a bit-by-bit search over
+//      those few keys in registers);
 //   2. every thread owns a contiguous run of tokens; block-wide prefix sums of "key == kappa"
 //      give each token its position among equal keys, which decides its group;
 //   3. block-wide prefix sums of the group counts give each token its slot in its group's
@@ -94,6 +96,7 @@ __device__ __forceinline__ void block_excl_scan_n(int (&v)[N], int n, int* wave_
   }
 }
 
+constexpr int kCand = 256;             // candidate keys per boundary that the short cut after the first pass takes
 constexpr int kStagedMax = 32768;      // tokens whose keys fit the dynamic LDS slice (132 KiB with padding)
 
 template <bool STAGED>
@@ -105,6 +108,7 @@ __global__ void __launch_bounds__(kThreads) select_ranks_kernel(const SelectPara
   __shared__ uint32_t s_prefix[kMaxF - 1];   // key bits fixed so far (kappa after pass 4)
   __shared__ uint32_t s_need[kMaxF - 1];     // 1-based position still to find (quota after pass 4)
   __shared__ int wave_tot[kMaxF * kWaves];
+  __shared__ uint32_t s_ncand[kMaxF - 1];    // short cut after the first pass: candidates listed so far
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int b = blockIdx.x, T = p.T, F = p.F, nb = F - 1;
   const float* m = p.mass + (size_t)b * T;
@@ -139,6 +143,7 @@ __global__ void __launch_bounds__(kThreads) select_ranks_kernel(const SelectPara
     for (int g = 0; g < kMaxF - 1; ++g) need = (tid == g && g < nb) ? (uint32_t)p.bound[g + 1] : need;
     s_prefix[tid] = 0u;
     s_need[tid] = need;
+    s_ncand[tid] = 0u;
   }
 
   // ---- 1. radix select, most significant digit first: digits of 12, 8, 8 and 4 bits.  The
@@ -228,6 +233,61 @@ __global__ void __launch_bounds__(kThreads) select_ranks_kernel(const SelectPara
     }
     __syncthreads();
     AP_SELECT_STAMP(3 + 2 * pass);
+    if (pass == 0) {
+      // ---- short cut: when at most kCand keys share the first digit of every boundary (the
+      //      usual case: one key in hundreds does), the remaining 20 bits are not found by
+      //      three more histogram passes.  The few candidate keys of a boundary are listed in
+      //      LDS (in the space of its later histograms), its wave takes them into registers and
+      //      fixes the 20 bits one at a time, counting with wave-wide ballots.
+      bool few = true;
+#pragma unroll
+      for (int g = 0; g < kMaxF - 1; ++g)
+        if (g < nb && active[g]) few = few && hist0[s_prefix[g] >> 20] <= (uint32_t)kCand;
+      if (few) {
+        uint32_t dig[kMaxF - 1];
+#pragma unroll
+        for (int g = 0; g < kMaxF - 1; ++g) dig[g] = s_prefix[g] >> 20;
+        for (int t = tid; t < T; t += kThreads) {
+          const uint32_t key = key_at(t);
+          if ((mark[key >> 25] >> ((key >> 20) & 31u)) & 1u) {
+#pragma unroll
+            for (int g = 0; g < kMaxF - 1; ++g) {
+              if (g < nb && active[g] && (key >> 20) == dig[g]) {
+                const uint32_t at = atomicAdd(&s_ncand[g], 1u);
+                if (at < (uint32_t)kCand) hist[g][at] = key & 0xfffffu;   // always true: the count was checked
+              }
+            }
+          }
+        }
+        __syncthreads();
+        if (act_w) {
+          const uint32_t n = hist0[s_prefix[w] >> 20];
+          uint32_t c[kCand / 64];
+          bool have[kCand / 64];
+#pragma unroll
+          for (int k = 0; k < kCand / 64; ++k) {
+            have[k] = (uint32_t)(lane + 64 * k) < n;
+            c[k] = have[k] ? hist[w][lane + 64 * k] : 0u;
+          }
+          uint32_t low = 0u, need = s_need[w];
+          for (int bit = 19; bit >= 0; --bit) {
+            const uint32_t trial = (low | (1u << bit)) >> bit;   // the bits above `bit` as fixed, this one set
+            uint32_t n1 = 0;
+#pragma unroll
+            for (int k = 0; k < kCand / 64; ++k) n1 += (uint32_t)__popcll(__ballot(have[k] && (c[k] >> bit) == trial));
+            if (need <= n1) low |= 1u << bit;                     // the wanted key has this bit set
+            else need -= n1;                                      // all of those lie in front of it
+          }
+          if (lane == 0) {
+            s_prefix[w] = s_prefix[w] | low;
+            s_need[w] = need;
+          }
+        }
+        __syncthreads();
+        AP_SELECT_STAMP(9);
+        break;
+      }
+    }
   }
 
   uint32_t kappa[kMaxF - 1], quota[kMaxF - 1];
