@@ -292,6 +292,48 @@ def main():
                              "step_effective_GBps": sh_bytes / (dts / ks) / 1e9}
     del shared
 
+    # ---- the paper's own loop at its operating point, for context (not part of `value`): 32 heads,
+    #      R = 64, a quarter of the tokens at the full value rank and the rest at 16 (Sec. 3.2),
+    #      importance tracked on every step (Eq. 1): group selection, fused step with per-token
+    #      ranks and the logits written out, importance update.  T stays at T0 (the step rewrites
+    #      row T0 - 1), so the group arrays keep their shape and nothing is allocated in the loop.
+    hp, rp, bf = 32, 64, torch.bfloat16
+    ckp = torch.randn(B, T0, rp, device="cuda").to(bf)
+    cvp = torch.randn(B, T0, rp, device="cuda").to(bf)
+    bkp = (torch.randn(B, rp, hp * D, device="cuda") / math.sqrt(hp * D)).to(bf)
+    bvp = (torch.randn(B, rp, hp * D, device="cuda") / math.sqrt(hp * D)).to(bf)
+    qp = torch.randn(B, hp, D, device="cuda").to(bf)
+    kp = torch.randn(B, hp * D, device="cuda").to(bf)
+    outp = torch.empty(B, hp, D, device="cuda")
+    lsep = torch.empty(B, hp, device="cuda")
+    scp = torch.empty(B, T0, hp, device="cuda")
+    massp = torch.rand(B, T0, device="cuda") / T0
+    rankp = torch.empty(B, T0, dtype=torch.int32, device="cuda")
+    idxp = torch.empty(B, T0, dtype=torch.int32, device="cuda")
+    offp = torch.empty(B, 3, dtype=torch.int32, device="cuda")
+    wselp = torch.empty(max(256, ap.ap_select_workspace_bytes(B, T0, 2)), dtype=torch.uint8, device="cuda")
+    wsp = torch.empty(ap.ap_decode_workspace_bytes(B, hp, D, T0, rp, ap.AP_BF16), dtype=torch.uint8, device="cuda")
+
+    def loop_steps(n):
+        for _ in range(n):
+            ap.ap_select_ranks(massp, (rp, 16), (1, 4), 4, rankp, offp, idxp, wselp)
+            ap.ap_decode_step(qp, kp, kp, ckp, cvp, bkp, bvp, outp, wsp, T=T0, sm_scale=1.0 / math.sqrt(D),
+                              rank_v=rankp, bucket_off=offp, bucket_idx=idxp, F=2, lse=lsep, scores=scp)
+            ap.ap_update_importance(scp, lsep, massp, T=T0, alpha=0.9)
+
+    loop_steps(8)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    loop_steps(48)
+    torch.cuda.synchronize()
+    dtp = (time.perf_counter() - t0) / 48
+    extra["attention_aware_loop"] = {
+        "workload": "B=%d H=32 d=128 T=%d R=64 bf16, value ranks 64 (1/4 of the tokens) / 16, re-selected and "
+                    "importance updated on every step" % (B, T0),
+        "steps": 48, "us_per_step": dtp * 1e6, "tokens_per_s": B / dtp,
+        "uncompressed_kv_bytes": 2.0 * B * T0 * hp * D * 2}
+    del ckp, cvp, bkp, bvp, scp, wsp
+
     # ---- yardsticks measured in this run on this machine: a plain device copy (torch) and a plain
     #      streaming read (the library's probe kernel) over one layer's coefficient cache
     src = layers1[0]["Ck"].view(torch.uint8).reshape(-1)
