@@ -325,6 +325,21 @@ ap_status ap_valueonly_attn(const void* q, const void* K, const void* Cv, const 
                             size_t ws_bytes, void* stream);
 
 /* ------------------------------------------------------------------------
+ * Tuning of ap_decode_step (same results either way, up to fp32 summation
+ * order).  A fused step at uniform rank can produce the new value row inside
+ * its expansion pass over B_v (B_v is then read once per step; the pass writes
+ * per-row-block sums that a small extra kernel adds up), or append it in a pass
+ * of its own that runs in the same launch as the key row's (B_v is read twice,
+ * one launch less).  The library takes the first way when the value bases
+ * streamed per step, B * r * H_kv * d * 2 bytes (without the factor B when the
+ * bases are shared), reach 128 MiB, or 96 MiB at r >= 512 (paper Alg. 1 fixes
+ * the result, not the schedule).  min_bytes >= 0 replaces that rule by "at
+ * least min_bytes" (0: always, a huge value: never); a negative value restores
+ * it.  Process-wide, not thread-safe; meant for tests and tuning.
+ * ---------------------------------------------------------------------- */
+void ap_set_fused_value_min_bytes(int64_t min_bytes);
+
+/* ------------------------------------------------------------------------
  * Timing of the dominant kernel (measurement aid, not part of the method).
  * While enabled, every ap_decode_attn / ap_decode_step call on AP_F16 / AP_BF16
  * attaches a pair of HIP events to the launch of its coefficient-streaming

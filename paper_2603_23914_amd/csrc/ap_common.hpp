@@ -124,6 +124,8 @@ ap_status launch_quantize_i8(const void* C, void* codes, void* scales, int B, in
 
 // per-step passes over the bases in 16-bit storage (basis_gemv.hip)
 bool basis_rows_applies(int HD, int B);
+// ap_set_fused_value_min_bytes: -1 = the library's rule
+int64_t fused_value_min_bytes();
 ap_status launch_basis_rows(ap_dtype dt, const void* Bm, int64_t bstride, const void* x,
                             const void* q, void* C, void* Qp, int B, int H, int Hp, int d, int HD,
                             int r, int row0, int T_cap, float scale, hipStream_t stream,

@@ -32,7 +32,10 @@ static bool g_prof_on = false;
 static std::vector<hipEvent_t> g_prof_ev;   // start, stop, start, stop, ...
 static size_t g_prof_used = 0;
 static unsigned g_prof_every = 1, g_prof_seen = 0;
+static int64_t g_fused_value_min_bytes = -1;
 constexpr size_t kProfMax = 2 * 4096;
+
+int64_t fused_value_min_bytes() { return g_fused_value_min_bytes; }
 
 bool prof_events(hipEvent_t* start, hipEvent_t* stop) {
   if (!g_prof_on || g_prof_used + 2 > kProfMax) return false;
@@ -81,6 +84,8 @@ ap_status ap_probe_read(const void* src, size_t bytes, void* sink, void* stream)
   AP_REQUIRE(aligned(src, 16) && aligned(sink, 4), AP_ERR_INVALID_ARG, "ap_probe_read: misaligned pointer");
   return launch_probe_read(src, bytes, (uint32_t*)sink, (hipStream_t)stream);
 }
+
+void ap_set_fused_value_min_bytes(int64_t min_bytes) { g_fused_value_min_bytes = min_bytes < 0 ? -1 : min_bytes; }
 
 void ap_prof_enable(int on) {
   g_prof_on = on > 0;

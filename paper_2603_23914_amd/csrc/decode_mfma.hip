@@ -1331,7 +1331,15 @@ ap_status run_decode(const DecodeArgs& a) {
   // contribution: B_v is read once per step instead of twice.
   const int Hkv = a.H_kv;
   const int HDkv = Hkv * a.d;              // hidden columns of the cache and of the basis rows
-  const bool one_pass_v = a.v_new && !a.rank_k && !a.rank_v && a.T >= 2 && Hkv == a.H;
+  // That pays when a pass over the value bases is long: the expansion then writes and re-reads
+  // per-row-block sums and needs a launch more, which costs more than streaming a small B_v a
+  // second time next to B_k (measured: 47 against 58 us at rank 64, 103 against 110 us at B=32,
+  // r=320; 312 against 361 us at B=64, r=640).
+  const int64_t v_bytes = (int64_t)(a.basis_batch_stride ? a.B : 1) * a.r * HDkv * 2;
+  const int64_t v_min = fused_value_min_bytes();
+  const bool v_long = v_min >= 0 ? v_bytes >= v_min
+                                 : v_bytes >= (128ll << 20) || (a.r >= 512 && v_bytes >= (96ll << 20));
+  const bool one_pass_v = a.v_new && !a.rank_k && !a.rank_v && a.T >= 2 && Hkv == a.H && v_long;
   const bool small = a.dt_coef != AP_I8 && attn_small_applies(a.H, a.r, a.T, one_pass_v);
   const int S = choose_nsplit(a.B, a.T);     // the same count for both kernels (twice the splits for
                                              // the small-rank kernel measured slower)

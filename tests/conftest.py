@@ -25,6 +25,17 @@ def load_golden(name):
     return out
 
 
+@pytest.fixture(params=["in_expansion", "by_rule"])
+def value_path(request):
+    """A fused step at uniform rank produces the new value row either inside its expansion pass
+    or in the launch that appends the key row; the library picks by the size of the value bases.
+    Tests of small cases run both ways."""
+    from paper_2603_23914_amd import binding as ap
+    ap.ap_set_fused_value_min_bytes(0 if request.param == "in_expansion" else -1)
+    yield request.param
+    ap.ap_set_fused_value_min_bytes(-1)
+
+
 @pytest.fixture(scope="session")
 def paper_values():
     return load_golden("paper_values.txt")

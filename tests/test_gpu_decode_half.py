@@ -87,7 +87,7 @@ def test_decode_peaked_softmax_large_logits():
 
 @pytest.mark.parametrize("dtype,B,H,d,r,T0", [("bf16", 2, 40, 128, 640, 150), ("f16", 3, 32, 128, 512, 65),
                                               ("f16", 2, 8, 64, 192, 31)])
-def test_decode_step_equals_compact_then_attend(dtype, B, H, d, r, T0):
+def test_decode_step_equals_compact_then_attend(dtype, B, H, d, r, T0, value_path):
     """ap_decode_step (key append fused with the fold, value append fused with the expansion)
     against ap_compact + ap_decode_attn: the appended key row has the same bits, the value row
     and the outputs agree to fp32 summation order, and both match the oracle."""
@@ -136,7 +136,7 @@ def test_decode_step_equals_compact_then_attend(dtype, B, H, d, r, T0):
     ("bf16", 2, 32, 128, 128, 32),      # the appended token opens a new tile
     ("f16", 8, 32, 128, 64, 4000),      # whole groups of 8 sequences, long
 ])
-def test_decode_small_rank(dtype, B, H, d, r, T):
+def test_decode_small_rank(dtype, B, H, d, r, T, value_path):
     """Ranks 64 and 128 run attn_small (waves work alone on whole tiles), except 64 heads at rank
     128, which stay on the token-split variant of the two-role kernel; checked against the
     oracle on the plain call and on the fused step (whose newest token's value row does not

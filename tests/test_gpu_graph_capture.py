@@ -15,7 +15,7 @@ pytestmark = pytest.mark.gpu
 
 
 @pytest.mark.parametrize("dtype,B,H,d,r,T", [("bf16", 2, 40, 128, 640, 301), ("f16", 3, 32, 128, 128, 200)])
-def test_decode_calls_in_a_captured_graph(dtype, B, H, d, r, T):
+def test_decode_calls_in_a_captured_graph(dtype, B, H, d, r, T, value_path):
     from paper_2603_23914_amd import binding as ap
     case = wl.decode_case(dtype, B, H, d, r, T - 1, steps=1, seed=71, append=True)
     P = lambda x: __import__("oracle").promote(x, dtype)

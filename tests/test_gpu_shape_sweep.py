@@ -55,8 +55,14 @@ def test_shape_sweep(dtype, B, H, d, r, T, mode):
         ref = oracle.decode_attn_batched(P(q), P(case.Ck), P(case.Cv), P(case.Bk), P(case.Bv), T, absorbed=True)
     elif mode == "step":
         kn, vn = wl.step_new_token(case, 0, P(case.Bk), P(case.Bv))
-        ap.ap_decode_step(dq, to_dev(kn, dtype), to_dev(vn, dtype), dCk, dCv, dBk, dBv, out, ws, T=T, sm_scale=scale)
-        torch.cuda.synchronize()
+        # every other case forces the new value row into the expansion pass (small cases would
+        # otherwise all append it next to the key row)
+        ap.ap_set_fused_value_min_bytes(0 if (H + T + r // 64) % 2 else -1)
+        try:
+            ap.ap_decode_step(dq, to_dev(kn, dtype), to_dev(vn, dtype), dCk, dCv, dBk, dBv, out, ws, T=T, sm_scale=scale)
+            torch.cuda.synchronize()
+        finally:
+            ap.ap_set_fused_value_min_bytes(-1)
         bits = (lambda t: t.view(torch.int16).cpu().numpy().view(np.uint16)) if dtype == "bf16" else (lambda t: t.cpu().numpy())
         ref = oracle.decode_attn_batched(P(q), P(bits(dCk)), P(bits(dCv)), P(case.Bk), P(case.Bv), T, absorbed=True)
         c_ref = oracle.compact(P(kn)[0][None], P(case.Bk)[0])[0]
