@@ -1,5 +1,6 @@
 """GPU parity at full batch size for the rows built after the hot path: importance tracking,
-the uncompressed segment and grouped queries, in the launch shapes a 64-sequence decode uses.
+the uncompressed segment, grouped queries, key-only compression and the loop of Alg. 1 at the
+paper's operating point, in the launch shapes a 64-sequence decode uses.
 Inputs are drawn on the GPU with torch (seeded, the law of the benchmark's coefficients); the
 sampled sequences are read back bit for bit and the fp64 oracle computes their results alone."""
 import math
@@ -151,3 +152,53 @@ def test_key_only_compression_full_size():
                                                    return_lse=True, kv_heads=Hkv)
         assert_close(to_host64(out[b]), ref, "bf16", f"key-only, b={b}")
         assert np.abs(to_host64(lse[b]) - ref_lse).max() <= 2e-3 * max(1.0, np.abs(ref_lse).max())
+
+
+def test_attention_aware_loop_full_size():
+    """The paper's loop at its own operating point, in the shapes bench.py times as
+    `attention_aware_loop`: 64 sequences of 4224 tokens, 32 heads, R = 64, a quarter of the tokens
+    at the full value rank and the rest at 16 (Sec. 3.2), two rounds of group selection, fused
+    step with per-token value ranks and the logits written, importance update (Eq. 1).  Sampled
+    sequences: groups bit for bit, appended rows, outputs and masses against the oracle."""
+    from paper_2603_23914_amd import binding as ap
+    B, H, d, r, T, alpha = 64, 32, 128, 64, 4224, 0.9
+    HD = H * d
+    (Ck, Cv, Bk, Bv), g = draw_cache(B, T, r, HD, 67)
+    mass = torch.rand((B, T), generator=g, device="cuda") / T
+    out = torch.empty((B, H, d), dtype=torch.float32, device="cuda")
+    lse = torch.empty((B, H), dtype=torch.float32, device="cuda")
+    scores = torch.empty((B, T, H), dtype=torch.float32, device="cuda")
+    rank = torch.empty((B, T), dtype=torch.int32, device="cuda")
+    idx = torch.empty((B, T), dtype=torch.int32, device="cuda")
+    off = torch.empty((B, 3), dtype=torch.int32, device="cuda")
+    ws = workspace(ap.ap_decode_workspace_bytes(B, H, d, T, r, ap.AP_BF16))
+    wsel = workspace(ap.ap_select_workspace_bytes(B, T, 2))
+    granks, cum, den = (r, 16), (1, 4), 4
+    for rnd in range(2):
+        print(f"attention-aware loop, round {rnd}: 64 sequences at T={T}", flush=True)
+        q = torch.randn((B, H, d), generator=g, device="cuda").to(torch.bfloat16)
+        kn = torch.randn((B, HD), generator=g, device="cuda").to(torch.bfloat16)
+        vn = torch.randn((B, HD), generator=g, device="cuda").to(torch.bfloat16)
+        mass[:, T - 1] = 2.0                               # the token being appended: full rank
+        sel = mass.clone()
+        ap.ap_select_ranks(sel, granks, cum, den, rank, off, idx, wsel)
+        mass[:, T - 1] = 0.0                               # and no history yet (reading of Eq. 1's start)
+        mass0 = mass.clone()
+        ap.ap_decode_step(q, kn, vn, Ck, Cv, Bk, Bv, out, ws, T=T, sm_scale=1.0 / math.sqrt(d),
+                          rank_v=rank, bucket_off=off, bucket_idx=idx, F=2, lse=lse, scores=scores)
+        ap.ap_update_importance(scores, lse, mass, T=T, alpha=alpha)
+        torch.cuda.synchronize()
+        for b in SAMPLE:
+            r_ref, o_ref, i_ref = oracle.select_ranks(sel[b].cpu().numpy(), granks, cum, den)
+            rank_b = rank[b].cpu().numpy()
+            assert (rank_b == r_ref).all() and (off[b].cpu().numpy() == o_ref).all()
+            assert (idx[b].cpu().numpy() == i_ref).all()
+            for C, Bm, x, name in ((Ck, Bk, kn, "key"), (Cv, Bv, vn, "value")):
+                c_ref = oracle.compact(P(x[b])[None], P(Bm[b]))[0]
+                assert np.abs(P(C[b, T - 1]) - c_ref).max() <= 2.0 ** -7 * np.abs(c_ref).max(), f"{name} row, b={b}"
+            ref_out = oracle.decode_attn_absorbed(P(q[b]), P(Ck[b, :T]), P(Cv[b, :T]), P(Bk[b]), P(Bv[b]),
+                                                  rank_v=rank_b)
+            assert_close(to_host64(out[b]), ref_out, "bf16", f"round {rnd} output, b={b}")
+            A = oracle.attention_probs(P(q[b]), P(Ck[b, :T]), P(Bk[b]))
+            ref_mass = oracle.importance_update(mass0[b].cpu().numpy(), A[None], alpha)
+            assert np.abs(mass[b].cpu().numpy() - ref_mass).max() <= 2e-3 * ref_mass.max(), f"mass, b={b}"
