@@ -202,3 +202,40 @@ def test_attention_aware_loop_full_size():
             A = oracle.attention_probs(P(q[b]), P(Ck[b, :T]), P(Bk[b]))
             ref_mass = oracle.importance_update(mass0[b].cpu().numpy(), A[None], alpha)
             assert np.abs(mass[b].cpu().numpy() - ref_mass).max() <= 2e-3 * ref_mass.max(), f"mass, b={b}"
+
+
+def test_shared_basis_step_full_size():
+    """bench.py's `shared_basis` step at full size: one basis pair for all 64 sequences
+    (basis_batch_stride = 0).  With 6.5 MB of value basis the step appends the value row next to
+    the key row and expands with the plain expansion kernel, a different set of launches than
+    the per-sequence headline; forcing the one-pass expansion must give the same result."""
+    from paper_2603_23914_amd import binding as ap
+    B, H, d, r, T = 64, 40, 128, 640, 4224
+    HD = H * d
+    (Ck, Cv, Bk, Bv), g = draw_cache(B, T, r, HD, 71)
+    Bk1, Bv1 = Bk[0].contiguous(), Bv[0].contiguous()
+    del Bk, Bv
+    q = torch.randn((B, H, d), generator=g, device="cuda").to(torch.bfloat16)
+    kn = torch.randn((B, HD), generator=g, device="cuda").to(torch.bfloat16)
+    vn = torch.randn((B, HD), generator=g, device="cuda").to(torch.bfloat16)
+    ws = workspace(ap.ap_decode_workspace_bytes(B, H, d, T, r, ap.AP_BF16))
+    outs = []
+    for force in (False, True):
+        print(f"shared bases, 64 sequences at T={T}, value row {'in the expansion pass' if force else 'by the rule'}", flush=True)
+        Ck2, Cv2 = Ck.clone(), Cv.clone()
+        out = torch.empty((B, H, d), dtype=torch.float32, device="cuda")
+        ap.ap_set_fused_value_min_bytes(0 if force else -1)
+        try:
+            ap.ap_decode_step(q, kn, vn, Ck2, Cv2, Bk1, Bv1, out, ws, T=T, sm_scale=1.0 / math.sqrt(d))
+            torch.cuda.synchronize()
+        finally:
+            ap.ap_set_fused_value_min_bytes(-1)
+        outs.append(out)
+        for b in SAMPLE:
+            for C, Bm, x, name in ((Ck2, Bk1, kn, "key"), (Cv2, Bv1, vn, "value")):
+                c_ref = oracle.compact(P(x[b])[None], P(Bm))[0]
+                assert np.abs(P(C[b, T - 1]) - c_ref).max() <= 2.0 ** -7 * np.abs(c_ref).max(), f"{name} row, b={b}"
+            ref = oracle.decode_attn_absorbed(P(q[b]), P(Ck2[b, :T]), P(Cv2[b, :T]), P(Bk1), P(Bv1))
+            assert_close(to_host64(out[b]), ref, "bf16", f"shared-basis step, b={b}")
+        del Ck2, Cv2
+    assert (outs[0] - outs[1]).abs().max() <= 2e-3 * outs[0].abs().max()
