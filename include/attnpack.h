@@ -100,8 +100,8 @@ ap_status ap_quantize_i8(const void* C, void* codes, void* scales,
                          int B, int T, int T_cap, int r, void* stream);
 
 /* ------------------------------------------------------------------------
- * ap_select_ranks -- attention-aware rank groups (paper Sec. 3.2; Alg. 1
- * "determine the tokens m_f for each group f based on I").
+ * ap_select_ranks -- attention-aware rank groups (paper Sec. 3.2; Alg. 1,
+ * group-selection step).
  *
  * Per batch row: tokens are ordered by (mass descending, token index
  * ascending); group g (0 = most important) takes sorted positions

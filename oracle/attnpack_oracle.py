@@ -299,7 +299,7 @@ def merge_segments(outs, lses):
 
 
 # --------------------------------------------------------------------------
-# attention-aware rank groups (Sec. 3.2; Alg. 1 "determine the tokens m_f")
+# attention-aware rank groups (Sec. 3.2; Alg. 1, group-selection step)
 # --------------------------------------------------------------------------
 
 def select_ranks(mass: np.ndarray, group_rank: Sequence[int], cum_num: Sequence[int],

@@ -1,5 +1,4 @@
-// Attention-aware rank groups (paper Sec. 3.2; Alg. 1 "determine the tokens m_f for each
-// group f based on I").
+// Attention-aware rank groups (paper Sec. 3.2; Alg. 1, group-selection step).
 //
 // Per batch row the tokens are ordered by (importance descending, token index ascending)
 // and cut at fixed sorted positions into F groups.  Nothing is sorted: a group boundary at

@@ -119,6 +119,82 @@ def test_softmax_rows_sum_to_one_and_lse():
         assert abs(lse[h] - scipy.special.logsumexp(s)) < 1e-12
 
 
+def _scalar_loop_weights(q, Ck, Bk, rk, scale, Hkv):
+    """Attention weights written out from Alg. 1's score step with scalar loops:
+    rebuild key element (t, column) from the leading rk[t] coefficients, dot it
+    with the query of head h over the columns of key/value head h // (H/Hkv),
+    scale, library softmax over the tokens."""
+    H, d = q.shape
+    T = Ck.shape[0]
+    A = np.empty((H, T))
+    for h in range(H):
+        g = h // (H // Hkv)
+        s = []
+        for t in range(T):
+            acc = 0.0
+            for i in range(d):
+                acc += q[h, i] * sum(Ck[t, j] * Bk[j, g * d + i] for j in range(rk[t]))
+            s.append(acc * scale)
+        A[h] = scipy.special.softmax(np.array(s))
+    return A
+
+
+def test_attention_probs_against_scalar_loops_and_library_softmax():
+    """Values of the attention weights (the reference of every importance check):
+    per-token key ranks, a scale that is not 1/sqrt(d), fewer key/value heads
+    than query heads."""
+    rng = np.random.default_rng(21)
+    H, Hkv, d, T, r = 4, 2, 4, 7, 5
+    q = rng.standard_normal((H, d))
+    Ck = rng.standard_normal((T, r))
+    Bk = rng.standard_normal((r, Hkv * d))
+    rk = [5, 2, 0, 3, 1, 5, 4]
+    scale = 0.37
+    ref = _scalar_loop_weights(q, Ck, Bk, rk, scale, Hkv)
+    got = oracle.attention_probs(q, Ck, Bk, rank_k=np.array(rk), sm_scale=scale, kv_heads=Hkv)
+    assert np.abs(got - ref).max() < 1e-14
+    # each of the plausible mistakes moves the reference by far more than that
+    assert np.abs(_scalar_loop_weights(q, Ck, Bk, rk, 0.5, Hkv) - ref).max() > 1e-3       # scale
+    assert np.abs(_scalar_loop_weights(q, Ck, Bk, [r] * T, scale, Hkv) - ref).max() > 1e-3  # truncation
+    wrong_heads = _scalar_loop_weights(q[[0, 2, 1, 3]], Ck, Bk, rk, scale, Hkv)[[0, 2, 1, 3]]
+    assert np.abs(wrong_heads - ref).max() > 1e-3                                          # head slice
+    # default scale is 1/sqrt(d) (Alg. 1 divides by the square root of the head width)
+    ref_d = _scalar_loop_weights(q, Ck, Bk, rk, 1.0 / math.sqrt(d), Hkv)
+    got_d = oracle.attention_probs(q, Ck, Bk, rank_k=np.array(rk), kv_heads=Hkv)
+    assert np.abs(got_d - ref_d).max() < 1e-14
+    # multi-head default (kv_heads=None) with uniform rank
+    Bk4 = rng.standard_normal((r, H * d))
+    ref_m = _scalar_loop_weights(q, Ck, Bk4, [r] * T, 1.0 / math.sqrt(d), H)
+    assert np.abs(oracle.attention_probs(q, Ck, Bk4) - ref_m).max() < 1e-14
+
+
+@pytest.mark.parametrize("kv_heads", [None, 1])
+def test_attention_probs_are_exp_of_score_minus_lse(kv_heads):
+    """A[h,t] = exp(s[h,t] - lse[h]) with the log-sum-exp decode_attn returns, and
+    decode_attn's output is A applied to the rebuilt values (ties the weights to
+    the pinned attention output)."""
+    rng = np.random.default_rng(22)
+    H, d, T, r = 3, 8, 12, 6
+    Hkv = H if kv_heads is None else kv_heads
+    q = rng.standard_normal((H, d))
+    Ck = rng.standard_normal((T, r))
+    Cv = rng.standard_normal((T, r))
+    Bk = rng.standard_normal((r, Hkv * d))
+    Bv = rng.standard_normal((r, Hkv * d))
+    rk = rng.integers(0, r + 1, size=T)
+    rv = rng.integers(0, r + 1, size=T)
+    scale = 0.21
+    out, lse = oracle.decode_attn(q, Ck, Cv, Bk, Bv, rk, rv, sm_scale=scale, return_lse=True,
+                                  kv_heads=kv_heads)
+    A = oracle.attention_probs(q, Ck, Bk, rank_k=rk, sm_scale=scale, kv_heads=kv_heads)
+    for h in range(H):
+        g = h // (H // Hkv)
+        s = np.array([(Ck[t, :rk[t]] @ Bk[:rk[t], g * d:(g + 1) * d]) @ q[h] * scale for t in range(T)])
+        assert np.abs(A[h] - np.exp(s - lse[h])).max() < 1e-14
+        Vh = np.array([Cv[t, :rv[t]] @ Bv[:rv[t], g * d:(g + 1) * d] for t in range(T)])
+        assert np.abs(A[h] @ Vh - out[h]).max() < 1e-13
+
+
 def test_single_token_returns_its_value_row():
     """T = 1: the softmax weight is 1, so out_h = Vtilde[0, head h] exactly."""
     q, Ck, Cv, Bk, Bv = small_case(4, T=1)
