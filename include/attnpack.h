@@ -356,6 +356,10 @@ void ap_set_fused_value_min_bytes(int64_t min_bytes);
  * ---------------------------------------------------------------------- */
 void ap_prof_enable(int on);
 ap_status ap_prof_read(float* total_ms, int* launches);
+/* The same records one by one: waits for the last pair, writes the kernel time of the first
+ * min(*launches, cap) timed launches to us[] (HOST array, microseconds, in launch order; -1 for
+ * a pair that could not be read) and the number of pairs recorded to *launches. */
+ap_status ap_prof_read_launches(float* us, int cap, int* launches);
 
 /* ------------------------------------------------------------------------
  * Streaming-read yardstick (measurement aid, not part of the method).

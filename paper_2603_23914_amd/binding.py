@@ -81,12 +81,14 @@ _lib.ap_set_fused_value_min_bytes.restype = None
 _lib.ap_set_fused_value_min_bytes.argtypes = [_c.c_int64]
 _lib.ap_prof_read.restype = _i
 _lib.ap_prof_read.argtypes = [_c.POINTER(_c.c_float), _c.POINTER(_c.c_int)]
+_lib.ap_prof_read_launches.restype = _i
+_lib.ap_prof_read_launches.argtypes = [_c.POINTER(_c.c_float), _i, _c.POINTER(_c.c_int)]
 
 EXPORTS = ("ap_compact", "ap_quantize_i8", "ap_select_ranks", "ap_select_workspace_bytes",
            "ap_decode_attn", "ap_decode_step", "ap_update_importance", "ap_decode_workspace_bytes",
            "ap_raw_workspace_bytes", "ap_raw_attn", "ap_keyonly_workspace_bytes", "ap_keyonly_attn",
            "ap_valueonly_workspace_bytes", "ap_valueonly_attn", "ap_merge_segments", "ap_raw_append", "ap_status_string", "ap_last_error",
-           "ap_version", "ap_set_fused_value_min_bytes", "ap_prof_enable", "ap_prof_read", "ap_probe_read_granule", "ap_probe_read")
+           "ap_version", "ap_set_fused_value_min_bytes", "ap_prof_enable", "ap_prof_read", "ap_prof_read_launches", "ap_probe_read_granule", "ap_probe_read")
 
 _DT = {torch.float32: AP_F32, torch.float16: AP_F16, torch.bfloat16: AP_BF16, torch.int8: AP_I8}
 
@@ -288,6 +290,13 @@ def ap_prof_read():
     ms, cnt = _c.c_float(0), _c.c_int(0)
     _check(_lib.ap_prof_read(_c.byref(ms), _c.byref(cnt)))
     return ms.value, cnt.value
+
+
+def ap_prof_read_launches(cap: int = 4096):
+    """-> list of the timed launches' kernel times in microseconds, in launch order."""
+    buf, cnt = (_c.c_float * cap)(), _c.c_int(0)
+    _check(_lib.ap_prof_read_launches(buf, cap, _c.byref(cnt)))
+    return [buf[i] for i in range(min(cnt.value, cap))]
 
 
 def raw():

@@ -115,6 +115,25 @@ ap_status ap_prof_read(float* total_ms, int* launches) {
   return AP_OK;
 }
 
+ap_status ap_prof_read_launches(float* us, int cap, int* launches) {
+  clear_error();
+  AP_REQUIRE(launches && (us || cap == 0) && cap >= 0, AP_ERR_INVALID_ARG, "ap_prof_read_launches: bad argument");
+  const size_t pairs = g_prof_used / 2;
+  if (pairs) {
+    hipError_t e = hipEventSynchronize(g_prof_ev[2 * pairs - 1]);
+    if (e != hipSuccess) {
+      set_error("ap_prof_read_launches: %s", hipGetErrorString(e));
+      return AP_ERR_HIP;
+    }
+    for (size_t i = 0; i < pairs && i < (size_t)cap; ++i) {
+      float ms = 0.f;
+      us[i] = hipEventElapsedTime(&ms, g_prof_ev[2 * i], g_prof_ev[2 * i + 1]) == hipSuccess ? ms * 1e3f : -1.f;
+    }
+  }
+  *launches = (int)pairs;
+  return AP_OK;
+}
+
 // ---------------------------------------------------------------------------------------------
 ap_status ap_compact(const void* K, const void* V, const void* Bk, const void* Bv, void* Ck,
                      void* Cv, void* scale_k, void* scale_v, int B, int n, int row0, int T_cap,

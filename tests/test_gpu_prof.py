@@ -42,8 +42,11 @@ def test_kernel_timer_counts_launches_and_stays_inside_wall_time():
     for _ in range(7):
         ap.ap_decode_attn(dq, dCk, dCv, dBk, dBv, out1, ws, T=T, sm_scale=scale)
     ms3, n3 = ap.ap_prof_read()
+    each = ap.ap_prof_read_launches()
     ap.ap_prof_enable(False)
     assert n3 == 3 and 0.0 < ms3 / n3 < 1.0
+    assert len(each) == 3 and all(0.0 < u < 1000.0 for u in each)
+    assert abs(sum(each) - ms3 * 1e3) <= 1e-3 * ms3 * 1e3 + 0.01
     ap.ap_prof_enable(True)                 # enabling clears the records
     ms, n = ap.ap_prof_read()
     ap.ap_prof_enable(False)
