@@ -182,6 +182,34 @@ ap_status ap_decode_attn(const void* q, const void* Ck, const void* Cv,
 size_t ap_decode_workspace_bytes(int B, int H, int d, int T, int r, ap_dtype dt);
 
 /* ------------------------------------------------------------------------
+ * ap_decode_attn_static -- ap_decode_attn for callers that cannot allocate device
+ * memory or carry a workspace around: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and the same
+ * results as ap_decode_attn, but the split partials and the folded query live in a
+ * buffer of AP_STATIC_SCRATCH_BYTES bytes that belongs to the library (a device
+ * array in its code object, one copy per GPU, held until the process ends).  The
+ * call allocates and frees nothing and calls no allocating routine.
+ *   - A shape whose ap_decode_workspace_bytes() exceeds AP_STATIC_SCRATCH_BYTES is
+ *     rejected with AP_ERR_WORKSPACE before any launch (the five benchmark shapes
+ *     of this library fit; very long contexts at large batch do not).
+ *   - Every call on a GPU uses that GPU's one buffer and finds the previous call's
+ *     contents in it; nothing in it has to start at zero.  Two calls that overlap
+ *     on one GPU (different streams, or different host threads without ordering)
+ *     race on it: serialise them on one stream, or use ap_decode_attn.
+ *   - The first call on a device looks the buffer's address up (not a stream
+ *     operation): make it once before capturing a graph, as for every entry point.
+ * ---------------------------------------------------------------------- */
+#define AP_STATIC_SCRATCH_BYTES (64u << 20)
+ap_status ap_decode_attn_static(const void* q, const void* Ck, const void* Cv,
+                                const void* scale_k, const void* scale_v,
+                                const void* Bk, const void* Bv, int64_t basis_batch_stride,
+                                const int32_t* rank_k, const int32_t* rank_v,
+                                const int32_t* bucket_off, const int32_t* bucket_idx, int F,
+                                void* out, float* lse, float* scores,
+                                int B, int H, int H_kv, int d, int T, int T_cap, int r, float sm_scale,
+                                ap_dtype dt, ap_dtype dt_coef, ap_dtype dt_out, void* stream);
+
+/* ------------------------------------------------------------------------
  * ap_decode_step -- one decode step with append (paper Alg. 1: the new token's
  * key and value join the cache, then the query attends to every cached token).
  * Computes what

@@ -42,6 +42,9 @@ _lib.ap_select_workspace_bytes.argtypes = [_i, _i, _i]
 _lib.ap_decode_attn.restype = _i
 _lib.ap_decode_attn.argtypes = ([_vp] * 7 + [_i64] + [_vp] * 4 + [_i] + [_vp, _vp, _vp] + [_i] * 7 +
                                 [_f, _i, _i, _i, _vp, _sz, _vp])
+_lib.ap_decode_attn_static.restype = _i
+_lib.ap_decode_attn_static.argtypes = ([_vp] * 7 + [_i64] + [_vp] * 4 + [_i] + [_vp, _vp, _vp] + [_i] * 7 +
+                                       [_f, _i, _i, _i, _vp])
 _lib.ap_decode_step.restype = _i
 _lib.ap_decode_step.argtypes = ([_vp] * 7 + [_i64] + [_vp] * 4 + [_i] + [_vp, _vp, _vp] + [_i] * 7 +
                                 [_f, _i, _i, _vp, _sz, _vp])
@@ -85,7 +88,7 @@ _lib.ap_prof_read_launches.restype = _i
 _lib.ap_prof_read_launches.argtypes = [_c.POINTER(_c.c_float), _i, _c.POINTER(_c.c_int)]
 
 EXPORTS = ("ap_compact", "ap_quantize_i8", "ap_select_ranks", "ap_select_workspace_bytes",
-           "ap_decode_attn", "ap_decode_step", "ap_update_importance", "ap_decode_workspace_bytes",
+           "ap_decode_attn", "ap_decode_attn_static", "ap_decode_step", "ap_update_importance", "ap_decode_workspace_bytes",
            "ap_raw_workspace_bytes", "ap_raw_attn", "ap_keyonly_workspace_bytes", "ap_keyonly_attn",
            "ap_valueonly_workspace_bytes", "ap_valueonly_attn", "ap_merge_segments", "ap_raw_append", "ap_status_string", "ap_last_error",
            "ap_version", "ap_set_fused_value_min_bytes", "ap_prof_enable", "ap_prof_read", "ap_prof_read_launches", "ap_probe_read_granule", "ap_probe_read")
@@ -187,6 +190,23 @@ def ap_decode_attn(q, Ck, Cv, Bk, Bv, out, workspace, *, T: int, sm_scale: float
                                float(sm_scale), _DT[q.dtype], _DT[Ck.dtype], _DT[out.dtype],
                                _p(workspace),
                                workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
+AP_STATIC_SCRATCH_BYTES = 64 << 20
+
+
+def ap_decode_attn_static(q, Ck, Cv, Bk, Bv, out, *, T: int, sm_scale: float,
+                          scale_k=None, scale_v=None, rank_k=None, rank_v=None, bucket_off=None,
+                          bucket_idx=None, F: int = 0, lse=None, scores=None, stream=None) -> None:
+    """ap_decode_attn on the library's own scratch buffer (no workspace argument, no allocation)."""
+    B, H, d = q.shape
+    T_cap, r = Ck.shape[1], Ck.shape[2]
+    H_kv = Bk.shape[-1] // d
+    _check(_lib.ap_decode_attn_static(_p(q), _p(Ck), _p(Cv), _p(scale_k), _p(scale_v), _p(Bk), _p(Bv),
+                                      _bstride(Bk), _p(rank_k), _p(rank_v), _p(bucket_off),
+                                      _p(bucket_idx), F, _p(out), _p(lse), _p(scores), B, H, H_kv, d, T, T_cap,
+                                      r, float(sm_scale), _DT[q.dtype], _DT[Ck.dtype], _DT[out.dtype],
+                                      _stream(stream)))
 
 
 def ap_decode_step(q, k_new, v_new, Ck, Cv, Bk, Bv, out, workspace, *, T: int, sm_scale: float,

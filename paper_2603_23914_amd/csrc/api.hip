@@ -1,10 +1,16 @@
 // C ABI of libattnpack: host-side validation and dispatch.  No kernel lives here.
 #include "ap_common.hpp"
 
+#include <atomic>
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
 #include <vector>
+
+// Scratch of ap_decode_attn_static: the decode workspace as a device array of the library itself.
+// Every GPU that loads the library holds its own copy until the process ends.  In host code the
+// name is only a handle for hipGetSymbolAddress; kernels get the address that call returns.
+static __device__ __align__(256) unsigned char scratch[AP_STATIC_SCRATCH_BYTES];
 
 namespace ap {
 
@@ -52,6 +58,30 @@ bool prof_events(hipEvent_t* start, hipEvent_t* stop) {
 }
 
 static bool half_type(ap_dtype dt) { return dt == AP_F16 || dt == AP_BF16; }
+
+// Address of `scratch` on the current device, looked up once per device.
+constexpr int kMaxDevices = 64;
+static std::atomic<void*> g_scratch_ptr[kMaxDevices];
+
+static ap_status static_scratch(void** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+    set_error("ap_decode_attn_static: no current device (%s)", e != hipSuccess ? hipGetErrorString(e) : "index out of range");
+    return AP_ERR_HIP;
+  }
+  void* ptr = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (!ptr) {
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !ptr) {
+      set_error("ap_decode_attn_static: hipGetSymbolAddress failed (%s)", hipGetErrorString(e));
+      return AP_ERR_HIP;
+    }
+    g_scratch_ptr[dev].store(ptr, std::memory_order_release);
+  }
+  *out = ptr;
+  return AP_OK;
+}
 
 }  // namespace ap
 
@@ -323,6 +353,29 @@ ap_status ap_decode_attn(const void* q, const void* Ck, const void* Cv, const vo
   return decode_entry("ap_decode_attn", q, nullptr, nullptr, Ck, Cv, scale_k, scale_v, Bk, Bv,
                       basis_batch_stride, rank_k, rank_v, bucket_off, bucket_idx, F, out, lse, scores, B, H, H_kv,
                       d, T, T_cap, r, sm_scale, dt, dt_coef, dt_out, workspace, ws_bytes, stream);
+}
+
+ap_status ap_decode_attn_static(const void* q, const void* Ck, const void* Cv, const void* scale_k,
+                                const void* scale_v, const void* Bk, const void* Bv,
+                                int64_t basis_batch_stride, const int32_t* rank_k,
+                                const int32_t* rank_v, const int32_t* bucket_off,
+                                const int32_t* bucket_idx, int F, void* out, float* lse, float* scores,
+                                int B, int H, int H_kv, int d, int T, int T_cap, int r, float sm_scale,
+                                ap_dtype dt, ap_dtype dt_coef, ap_dtype dt_out, void* stream) {
+  clear_error();
+  ap_status s = decode_shape_check(B, H, d, T, r, dt, true);
+  if (s != AP_OK) return s;
+  const size_t need = ap_decode_workspace_bytes(B, H, d, T, r, dt);
+  AP_REQUIRE(need <= (size_t)AP_STATIC_SCRATCH_BYTES, AP_ERR_WORKSPACE,
+             "ap_decode_attn_static: this shape needs %zu bytes of scratch, the library's buffer holds %zu "
+             "(use ap_decode_attn with a workspace of the caller)", need, (size_t)AP_STATIC_SCRATCH_BYTES);
+  void* ws = nullptr;
+  s = static_scratch(&ws);
+  if (s != AP_OK) return s;
+  return decode_entry("ap_decode_attn_static", q, nullptr, nullptr, Ck, Cv, scale_k, scale_v, Bk, Bv,
+                      basis_batch_stride, rank_k, rank_v, bucket_off, bucket_idx, F, out, lse, scores, B, H,
+                      H_kv, d, T, T_cap, r, sm_scale, dt, dt_coef, dt_out, ws, (size_t)AP_STATIC_SCRATCH_BYTES,
+                      stream);
 }
 
 ap_status ap_decode_step(const void* q, const void* k_new, const void* v_new, void* Ck, void* Cv,
