@@ -669,20 +669,34 @@ struct WaveCtx {
   }
 };
 
-// Phase timers and per-tile time stamps for kernel studies (build with -DAP_KERNEL_TIMERS and
-// set AP_DEBUG_ATTN: 4 = phase sums of workgroup (0,0) into the head of part_U, 8 = per-tile
+// Phase timers and per-tile time stamps for kernel studies (build with -DAP_KERNEL_TIMERS=2, or =1
+// for the stamps alone, and set AP_DEBUG_ATTN: 4 = phase sums of workgroup (0,0) into the head of part_U, 8 = per-tile
 // stamps into the bytes after the workspace, which the caller must have allocated).
 #ifdef AP_KERNEL_TIMERS
-#define AP_T_ENTRY const unsigned long long t_entry_ = __builtin_readcyclecounter();
+#define AP_T_ENTRY                                                    \
+  const unsigned long long t_entry_ = __builtin_readcyclecounter();   \
+  const unsigned long long t_entry_rt_ = __builtin_amdgcn_s_memrealtime();
 #define AP_T_START                                         \
   unsigned long long tm[8] = {0, 0, 0, 0, 0, 0, 0, 0};     \
   unsigned long long t0_ = __builtin_readcyclecounter();   \
-  tm[0] = t0_ - t_entry_;
+  tm[0] = t0_ - t_entry_;                                  \
+  if ((cx.dbg & 8) && cx.lane == 0) {                      \
+    unsigned long long* o_ = uni_ptr(p.dbg_out) + 1024 + ((cx.b * cx.nsplit + cx.s) * 8 + cx.w) * 64; \
+    o_[60] = t_entry_rt_;                                  \
+    o_[61] = __builtin_amdgcn_s_memrealtime();             \
+  }
+#if AP_KERNEL_TIMERS >= 2
 #define AP_TICK(k) { const unsigned long long now_ = __builtin_readcyclecounter(); tm[k] += now_ - t0_; t0_ = now_; }
+#else
+#define AP_TICK(k)
+#endif
+// in-loop stamps only from the first score wave (a sum wave counts its outstanding loads by hand,
+// and a store in between would make it wait longer)
 #define AP_T_STAMP(t)                                                                                    \
-  if ((cx.dbg & 8) && cx.lane == 0 && (t) < 64)                                                          \
-    uni_ptr(p.dbg_out)[1024 + ((cx.b * cx.nsplit + cx.s) * 8 + cx.w) * 64 + (t)] = __builtin_readcyclecounter();
+  if ((cx.dbg & 8) && cx.lane == 0 && (t) < 64 && (cx.w == 0 || (t) >= 60))                              \
+    uni_ptr(p.dbg_out)[1024 + ((cx.b * cx.nsplit + cx.s) * 8 + cx.w) * 64 + (t)] = __builtin_amdgcn_s_memrealtime();
 #define AP_T_REPORT                                                        \
+  AP_T_STAMP(63)                                                           \
   if ((cx.dbg & 4) && cx.b == 0 && cx.s == 0 && cx.lane == 0) {            \
     unsigned long long* out_ = uni_ptr(p.dbg_out);                         \
     for (int k = 0; k < 8; ++k) out_[cx.w * 8 + k] = tm[k];                \
@@ -727,7 +741,11 @@ __device__ __forceinline__ void score_role(const AttnParams& p) {
       qhi[i][mt] = z;
       if (SPLIT) qlo[i][mt] = z;
       const int unit = I8 ? i >> 1 : i;
+#ifdef AP_KERNEL_TIMERS
+      if (unit < my_nks && !(cx.dbg & 32)) {
+#else
       if (unit < my_nks) {
+#endif
         const int col = I8 ? (w + 4 * unit) * 64 + g * 16 + (i & 1) * 8 : (ufirst + ustep * i) * 32 + g * 8;
         const uint16_t* qrow = Qp + (((size_t)cx.b * 2) * Hp + (mt * 16 + n)) * r + col;
         qhi[i][mt] = *(const u32x4_t*)qrow;
@@ -886,6 +904,7 @@ __device__ __forceinline__ void score_role(const AttnParams& p) {
     wg_barrier();                                         // weights of tile t ready
     AP_TICK(4)
   }
+  AP_T_STAMP(62)
   cx.store_ml(part_ml);
   AP_TICK(6)
   AP_T_REPORT
@@ -1091,10 +1110,14 @@ __device__ __forceinline__ void sum_role(const AttnParams& p) {
     AP_TICK(5)
   }
   }
+  AP_T_STAMP(62)
   // U of this split, straight from the accumulators.  U[i][j][mt][e] is element (head 16mt+n,
   // column 128i + 32cp + 8g + 2e + j) (int8: column 256i + 64cp + 16g + 4e + j): a lane owns
   // NJ*4 consecutive columns of one head per column group, stored as 16-byte pieces; the four
   // lanes g = 0..3 of a head together cover a full 128-byte (int8: 256-byte) run.
+#ifdef AP_KERNEL_TIMERS
+  if (!(cx.dbg & 16))
+#endif
   {
     float* ubase = part_U + ((size_t)cx.b * cx.nsplit + cx.s) * cx.H * r;
 #pragma unroll
