@@ -247,14 +247,23 @@ def other_configs(torch, ap):
     us16 = _time_us(torch, lambda: ap.ap_compact(kx, vx, bk, bv, c16k, c16v, None, None, n=t5, row0=0), 8, warm=2)
     us8 = _time_us(torch, lambda: ap.ap_compact(kx, vx, bk, bv, c8k, c8v, sk, sv, n=t5, row0=0), 8, warm=2)
     gemm_bytes = 2.0 * b5 * (t5 * hd2 + r5 * hd2 + t5 * r5) * 2
+    # yardsticks measured in this run: the vendor library's batched GEMM (torch.bmm) on the same 2 x 16
+    # products, and on one large square product (what fp16 matrix cores sustain on this card)
+    bkt, bvt = bk.transpose(1, 2), bv.transpose(1, 2)
+    us_lib = _time_us(torch, lambda: (torch.bmm(kx, bkt, out=c16k), torch.bmm(vx, bvt, out=c16v)), 8, warm=2)
+    sq = torch.randn(8192, 8192, device="cuda", dtype=f16)
+    us_sq = _time_us(torch, lambda: torch.matmul(sq, sq), 5, warm=2)
+    del sq
     res["config5_compaction"] = {
         "workload": "B=16 T=4224 HD=4096 r=512 fp16: C_k = K B_k^T and C_v = V B_v^T (32 GEMMs, 567 GFLOP)",
         "ms_per_call_fp16_out": us16 / 1e3, "ms_per_call_int8_out": us8 / 1e3,
         "algorithmic_bytes_per_call": gemm_bytes, "effective_GBps": gemm_bytes / us16 / 1e3,
         "roofline": {"bound": "mfma", "kernel": "compact_gemm", "achieved": flops / us16 / 1e6, "peak": 2500.0,
                      "unit": "TFLOP/s", "frac": flops / us16 / 1e6 / 2500.0, "traffic": None,
-                     "flops_per_launch": flops / 2, "kernel_avg_us": us16 / 2, "launches_per_call": 2,
-                     "timed": "events around 8 calls of 2 launches each"}}
+                     "flops_per_launch": flops, "kernel_avg_us": us16, "launches_per_call": 1,
+                     "timed": "events around 8 calls of one launch each (keys and values in one grid)"},
+        "library_bmm_same_shape_TFLOPs": flops / us_lib / 1e6,
+        "library_matmul_8192_cubed_TFLOPs": 2.0 * 8192 ** 3 / us_sq / 1e6}
     del kx, vx, c16k, c16v
     q5 = torch.randn(b5, h2, D, device="cuda").to(f16)
     out5 = torch.empty(b5, h2, D, device="cuda")

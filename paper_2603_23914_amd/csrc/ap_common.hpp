@@ -118,7 +118,9 @@ struct CompactArgs {
 };
 ap_status launch_compact(const CompactArgs& a);
 bool compact_gemm_applies(const CompactArgs& a);       // matrix-core path (compact_gemm.hip)
-ap_status launch_compact_gemm(const CompactArgs& a);
+// `second`: another projection of the same shape (B, n, row0, T_cap, HD, r, stride, types) that
+// runs in the same launch, or null
+ap_status launch_compact_gemm(const CompactArgs& a, const CompactArgs* second = nullptr);
 ap_status launch_quantize_i8(const void* C, void* codes, void* scales, int B, int T, int T_cap,
                              int r, hipStream_t stream);
 

@@ -201,6 +201,14 @@ ap_status ap_compact(const void* K, const void* V, const void* Bk, const void* B
       AP_REQUIRE(Ss[i] && aligned(Ss[i], 2), AP_ERR_INVALID_ARG,
                  "ap_compact: AP_I8 output needs a scale buffer");
   }
+  if (Xs[0] && Xs[1]) {
+    // keys and values of one prefill: both projections in one matrix-core launch when they qualify
+    CompactArgs ak{Xs[0], Bs[0], Cs[0], Ss[0], B, n, row0, T_cap, HD, r, basis_batch_stride,
+                   dt_in, dt_out, (hipStream_t)stream};
+    CompactArgs av = ak;
+    av.X = Xs[1]; av.Bm = Bs[1]; av.C = Cs[1]; av.scale = Ss[1];
+    if (compact_gemm_applies(ak)) return launch_compact_gemm(ak, &av);
+  }
   for (int i = 0; i < 2; ++i) {
     if (!Xs[i]) continue;
     CompactArgs a{Xs[i], Bs[i], Cs[i], Ss[i], B, n, row0, T_cap, HD, r, basis_batch_stride,

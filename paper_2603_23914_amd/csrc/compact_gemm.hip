@@ -57,6 +57,14 @@ struct GemmParams {
   uint16_t* scale;
   int n, row0, T_cap, HD, r, out_kind;
   int MT, NT, G;            // token tiles, column tiles, workgroups in all
+  // a second projection of the same shape in the same launch (keys and values of one prefill):
+  // tiles G1 .. G-1 belong to it.  One launch of twice the tiles loses half as much to the last,
+  // partly filled round of workgroups as two launches do.
+  const uint16_t* X2;
+  const uint16_t* Bm2;
+  void* C2;
+  uint16_t* scale2;
+  int G1;
 };
 
 template <class Tag>
@@ -66,14 +74,18 @@ __global__ void __launch_bounds__(kThreads) compact_gemm(const GemmParams p) {
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
   // XCD-aware numbering: consecutive workgroup ids go to different XCDs
   const int per_xcd = (p.G + 7) >> 3;
-  const int logical = (int)(blockIdx.x & 7) * per_xcd + (int)(blockIdx.x >> 3);
+  int logical = (int)(blockIdx.x & 7) * per_xcd + (int)(blockIdx.x >> 3);
   if (logical >= p.G) return;
+  const bool second = logical >= p.G1;
+  if (second) logical -= p.G1;
   const int nt = logical % p.NT;
   const int mt = (logical / p.NT) % p.MT;
   const int b = logical / (p.NT * p.MT);
   const int m0 = mt * kBM, n0 = nt * kBN;
-  const char* Xb = (const char*)(p.X + (size_t)b * p.n * p.HD);
-  const char* Bb = (const char*)(p.Bm + (size_t)b * p.bstride);
+  const char* Xb = (const char*)((second ? p.X2 : p.X) + (size_t)b * p.n * p.HD);
+  const char* Bb = (const char*)((second ? p.Bm2 : p.Bm) + (size_t)b * p.bstride);
+  void* const Cout = second ? p.C2 : p.C;
+  uint16_t* const Sout = second ? p.scale2 : p.scale;
 
   // ---- direct-to-LDS loads: per stage 32 KiB of X rows then 16 KiB of basis rows; wave w
   //      issues 1-KiB blocks 4w .. 4w+3 of the former and 2w, 2w+1 of the latter.  Block j,
@@ -216,7 +228,7 @@ __global__ void __launch_bounds__(kThreads) compact_gemm(const GemmParams p) {
     const bool live = t < p.n && col < p.r;
     const size_t row = (size_t)b * p.T_cap + p.row0 + t;
     if (p.out_kind == 0) {
-      if (live) *(u32x4_t*)((uint16_t*)p.C + row * p.r + col) = v;
+      if (live) *(u32x4_t*)((uint16_t*)Cout + row * p.r + col) = v;
     } else {
       // int8 format: amax over the 64-column block (8 lanes x 8 values), fp16 scale, codes
       float x[8];
@@ -239,16 +251,16 @@ __global__ void __launch_bounds__(kThreads) compact_gemm(const GemmParams p) {
       }
       if (live) {
         u32x2_t cw = {lo, hi};
-        *(u32x2_t*)((int8_t*)p.C + row * p.r + col) = cw;
-        if ((c8 & 7) == 0) p.scale[row * (p.r / AP_QBLOCK) + (col >> 6)] = __builtin_bit_cast(uint16_t, sh);
+        *(u32x2_t*)((int8_t*)Cout + row * p.r + col) = cw;
+        if ((c8 & 7) == 0) Sout[row * (p.r / AP_QBLOCK) + (col >> 6)] = __builtin_bit_cast(uint16_t, sh);
       }
     }
   }
 }
 
 template <class Tag>
-ap_status run_gemm(const CompactArgs& a) {
-  GemmParams p;
+ap_status run_gemm(const CompactArgs& a, const CompactArgs* a2) {
+  GemmParams p{};
   p.X = (const uint16_t*)a.X;
   p.Bm = (const uint16_t*)a.Bm;
   p.bstride = a.basis_batch_stride;
@@ -258,9 +270,17 @@ ap_status run_gemm(const CompactArgs& a) {
   p.out_kind = a.dt_out == AP_I8 ? 1 : 0;
   p.MT = (a.n + kBM - 1) / kBM;
   p.NT = (a.r + kBN - 1) / kBN;
-  const int64_t G = (int64_t)a.B * p.MT * p.NT;
+  const int64_t G1 = (int64_t)a.B * p.MT * p.NT;
+  const int64_t G = a2 ? 2 * G1 : G1;
   AP_REQUIRE(G <= (1 << 28), AP_ERR_UNSUPPORTED, "ap_compact: too many tiles");
   p.G = (int)G;
+  p.G1 = (int)G1;
+  if (a2) {
+    p.X2 = (const uint16_t*)a2->X;
+    p.Bm2 = (const uint16_t*)a2->Bm;
+    p.C2 = a2->C;
+    p.scale2 = (uint16_t*)a2->scale;
+  }
   const int grid = ((p.G + 7) / 8) * 8;
   auto kern = compact_gemm<Tag>;
   static bool attr_set = false;
@@ -288,8 +308,8 @@ bool compact_gemm_applies(const CompactArgs& a) {
   return true;
 }
 
-ap_status launch_compact_gemm(const CompactArgs& a) {
-  return a.dt_in == AP_F16 ? run_gemm<F16Tag>(a) : run_gemm<BF16Tag>(a);
+ap_status launch_compact_gemm(const CompactArgs& a, const CompactArgs* second) {
+  return a.dt_in == AP_F16 ? run_gemm<F16Tag>(a, second) : run_gemm<BF16Tag>(a, second);
 }
 
 }  // namespace ap
