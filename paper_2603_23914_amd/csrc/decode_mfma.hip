@@ -21,9 +21,9 @@
 //                                         (v_perm), B = P read back in operand layout
 // For bf16 storage q' and P are split into hi+lo bf16 pairs (two MFMAs) so that the
 // operand rounding stays far inside the 2e-3 tolerance; fp16 needs no split.
-// int8 coefficients (one fp16 scale per token per 64 columns) travel as bytes and are
-// turned into fp16 values code*scale in registers, right in front of the MFMA that uses
-// them; everything else is the fp16 path.
+// int8 coefficients (one fp16 scale per token per 64 columns) travel as bytes and enter the
+// MFMAs as exact fp16 integers; the scale is applied in fp32 (to the block's partial score, and
+// folded into the softmax weight on the value side); everything else is the fp16 path.
 #include "ap_common.hpp"
 #include "mfma_ops.hpp"
 #include <hip/hip_ext.h>
@@ -77,24 +77,25 @@ __device__ __forceinline__ void split_hi_lo(float x, uint16_t& hi, uint16_t& lo)
 }
 
 
-// int8 codes -> fp16 values code*scale, two at a time.  A byte b (two's complement) xor 0x80
-// is b+128 as an unsigned byte u; the fp16 bit pattern 0x6400|u is exactly 1024+u, so
-// subtracting 1152 leaves b exactly, and the product with the scale is rounded once.
+// int8 codes -> the same integers as fp16 values, two at a time, exactly.  A byte b (two's
+// complement) xor 0x80 is b+128 as an unsigned byte u; the fp16 bit pattern 0x6400|u is exactly
+// 1024+u, so subtracting 1152 leaves b.  The matrix cores multiply these integer-valued operands
+// (products and fp32 sums of a 64-column block are exact), and the block's fp16 scale is applied
+// in fp32 afterwards: a coefficient's value is code * fp32(scale), never rounded on its own.
 typedef _Float16 h2_t __attribute__((ext_vector_type(2)));
-__device__ __forceinline__ uint32_t deq2(uint32_t biased /* 0x64uu64uu */, uint32_t scale2) {
+__device__ __forceinline__ uint32_t code2(uint32_t biased /* 0x64uu64uu */) {
   const h2_t off = {(_Float16)-1152.0f, (_Float16)-1152.0f};
-  const h2_t v = (__builtin_bit_cast(h2_t, biased) + off) * __builtin_bit_cast(h2_t, scale2);
-  return __builtin_bit_cast(uint32_t, v);
+  return __builtin_bit_cast(uint32_t, __builtin_bit_cast(h2_t, biased) + off);
 }
-// 8 consecutive codes of one row (two dwords) times one scale -> MFMA operand (8 fp16)
-__device__ __forceinline__ u32x4_t deq_row8(uint32_t c0, uint32_t c1, uint32_t scale2) {
+// 8 consecutive codes of one row (two dwords) -> MFMA operand (8 fp16 integers)
+__device__ __forceinline__ u32x4_t code_row8(uint32_t c0, uint32_t c1) {
   const uint32_t k = 0x64646464u;
   const uint32_t x0 = c0 ^ 0x80808080u, x1 = c1 ^ 0x80808080u;
   u32x4_t o;
-  o[0] = deq2(__builtin_amdgcn_perm(k, x0, 0x04010400u), scale2);
-  o[1] = deq2(__builtin_amdgcn_perm(k, x0, 0x04030402u), scale2);
-  o[2] = deq2(__builtin_amdgcn_perm(k, x1, 0x04010400u), scale2);
-  o[3] = deq2(__builtin_amdgcn_perm(k, x1, 0x04030402u), scale2);
+  o[0] = code2(__builtin_amdgcn_perm(k, x0, 0x04010400u));
+  o[1] = code2(__builtin_amdgcn_perm(k, x0, 0x04030402u));
+  o[2] = code2(__builtin_amdgcn_perm(k, x1, 0x04010400u));
+  o[3] = code2(__builtin_amdgcn_perm(k, x1, 0x04030402u));
   return o;
 }
 
@@ -197,11 +198,13 @@ __device__ __forceinline__ void wsum_tile(const char* vA, const char* vB, int pi
 
 // int8 variant of score_tile.  A wave owns 64-column scale blocks w, w+4, ...; per block and
 // 16-row half it holds the lane's 16 codes (columns 64m + 16g .. +15 of its row) and the
-// row's scale.  Codes 0-7 feed one MFMA and codes 8-15 the next (q' is loaded with the same
-// column order), so a block is two k-steps.
+// scale of its row (token 16 tt + n).  Codes 0-7 feed one MFMA and codes 8-15 the next (q' is
+// loaded with the same column order), so a block is two k-steps.  The block's sum over the
+// integer codes is exact in fp32; it is multiplied by the token's scale in fp32 and added to the
+// scores.  A lane's results belong to tokens 16 tt + 4 g + e, whose scales sit in lanes 4 g + e.
 template <int MT, int NBW>
 __device__ __forceinline__ void score_tile_i8(const u32x4_t (&Araw)[NBW][2],
-                                              const uint32_t (&ksc)[NBW][2],
+                                              const uint32_t (&ksc)[NBW][2], int g,
                                               const u32x4_t (&qhi)[2 * NBW][MT],
                                               f32x4_t (&s)[MT][2]) {
 #pragma unroll
@@ -209,19 +212,30 @@ __device__ __forceinline__ void score_tile_i8(const u32x4_t (&Araw)[NBW][2],
     u32x4_t a0[2], a1[2];
 #pragma unroll
     for (int tt = 0; tt < 2; ++tt) {
-      a0[tt] = deq_row8(Araw[i][tt][0], Araw[i][tt][1], ksc[i][tt]);
-      a1[tt] = deq_row8(Araw[i][tt][2], Araw[i][tt][3], ksc[i][tt]);
+      a0[tt] = code_row8(Araw[i][tt][0], Araw[i][tt][1]);
+      a1[tt] = code_row8(Araw[i][tt][2], Araw[i][tt][3]);
+    }
+    f32x4_t pb[MT][2];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      const f32x4_t z = {0.f, 0.f, 0.f, 0.f};
+      pb[mt][0] = Mfma<F16Tag>::run(a0[0], qhi[2 * i][mt], z);
+      pb[mt][1] = Mfma<F16Tag>::run(a0[1], qhi[2 * i][mt], z);
     }
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
-      s[mt][0] = Mfma<F16Tag>::run(a0[0], qhi[2 * i][mt], s[mt][0]);
-      s[mt][1] = Mfma<F16Tag>::run(a0[1], qhi[2 * i][mt], s[mt][1]);
+      pb[mt][0] = Mfma<F16Tag>::run(a1[0], qhi[2 * i + 1][mt], pb[mt][0]);
+      pb[mt][1] = Mfma<F16Tag>::run(a1[1], qhi[2 * i + 1][mt], pb[mt][1]);
     }
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-      s[mt][0] = Mfma<F16Tag>::run(a1[0], qhi[2 * i + 1][mt], s[mt][0]);
-      s[mt][1] = Mfma<F16Tag>::run(a1[1], qhi[2 * i + 1][mt], s[mt][1]);
-    }
+    for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const uint32_t sb = (uint32_t)__builtin_amdgcn_ds_bpermute(4 * (4 * g + e), (int)ksc[i][tt]);
+        const float sc = bits_to_f32((uint16_t)sb, F16Tag{});
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) s[mt][tt][e] = fmaf(sc, pb[mt][tt][e], s[mt][tt][e]);
+      }
   }
 }
 
@@ -229,10 +243,13 @@ __device__ __forceinline__ void score_tile_i8(const u32x4_t (&Araw)[NBW][2],
 // scale block).  Lane (n, g) reads dword n of those bytes for its 8 tokens: four codes, i.e.
 // columns 4n .. 4n+3 of the wave's 64, one MFMA per byte position.  vs: this tile's value
 // scales in LDS as [scale block][32 tokens] fp16.
+// The codes enter the product as exact integers; a token's scale for the block is folded into
+// its softmax weight in fp32 (P32: the lane's eight weights per head tile, tokens 4g .. 4g+3
+// and 16+4g .. +3), and that product is rounded to fp16 once.
 template <int MT, int NGL>
 __device__ __forceinline__ void wsum_tile_i8(const char* vA, const char* vB, int pitch, int r,
                                              int cp, int g, const uint16_t* vs,
-                                             const u32x4_t (&Phi)[MT], const float (&alpha)[MT],
+                                             const f32x4_t (&P32)[MT][2], const float (&alpha)[MT],
                                              f32x4_t (&U)[NGL][4][MT]) {
 #pragma unroll
   for (int i = 0; i < NGL; ++i) {
@@ -249,6 +266,14 @@ __device__ __forceinline__ void wsum_tile_i8(const char* vA, const char* vB, int
       s23 = *(const u32x2_t*)(vs + blk * kTile + 16 + 4 * g);     // tokens 16+4g .. +3
     }
     const uint32_t sc[4] = {s01[0], s01[1], s23[0], s23[1]};
+    u32x4_t Psc[MT];                           // weight * scale of this block, per head tile
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const float f0 = lo_to_f32(sc[k], F16Tag{}), f1 = hi_to_f32(sc[k], F16Tag{});
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt)
+        Psc[mt][k] = cvt_pack(P32[mt][k >> 1][2 * (k & 1)] * f0, P32[mt][k >> 1][2 * (k & 1) + 1] * f1, F16Tag{});
+    }
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       // byte j of two tokens -> low bytes of the two halves, then bias into 0x64uu
@@ -256,10 +281,10 @@ __device__ __forceinline__ void wsum_tile_i8(const char* vA, const char* vB, int
       u32x4_t op;
 #pragma unroll
       for (int k = 0; k < 4; ++k)
-        op[k] = deq2(__builtin_amdgcn_perm(v[2 * k + 1], v[2 * k], sel) ^ 0x64806480u, sc[k]);
+        op[k] = code2(__builtin_amdgcn_perm(v[2 * k + 1], v[2 * k], sel) ^ 0x64806480u);
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt)
-        U[i][j][mt] = Mfma<F16Tag>::run(op, Phi[mt], U[i][j][mt] * alpha[mt]);
+        U[i][j][mt] = Mfma<F16Tag>::run(op, Psc[mt], U[i][j][mt] * alpha[mt]);
     }
   }
 }
@@ -575,6 +600,15 @@ struct WaveCtx {
       k2 += lo_to_f32(lo[1], Tag{});
       k3 += hi_to_f32(lo[1], Tag{});
     }
+    if (I8) {
+      // int8 coefficients: the weights stay fp32 (the sum waves fold the value scales in before
+      // rounding); the two 16-byte slots of a lane hold tokens 4g .. 4g+3 and 16+4g .. +3
+      l_part += (p0 + p1) + (p2 + p3);
+      const f32x4_t pv = {p0, p1, p2, p3};
+      *(f32x4_t*)(Pbuf + ((sub * MT + o_mt) * 2 + o_tt) * 64 + o_lane) = pv;
+      if ((lane & 7) == 0) abuf[sub * 16 * MT + o_hh] = alpha;
+      return;
+    }
     l_part += (k0 + k1) + (k2 + k3) + pdef;     // the sum uses the values the MFMA will see
     // weights in B-operand layout: lane (n, g) of head tile mt holds tokens 4g..4g+3
     // (dwords 0,1) and 16+4g..+3 (dwords 2,3)
@@ -787,8 +821,7 @@ __device__ __forceinline__ void score_role(const AttnParams& p) {
         const uint16_t* sp_ = Sk_b + (size_t)row * nsb + (my_nks > 0 ? w : 0);
 #pragma unroll
         for (int i = 0; i < NBW; ++i) {
-          const uint32_t sv = sp_[i < my_nks ? 4 * i : 0];
-          ksc[i][tt] = sv | (sv << 16);
+          ksc[i][tt] = sp_[i < my_nks ? 4 * i : 0];
         }
       }
 #pragma unroll
@@ -886,7 +919,7 @@ __device__ __forceinline__ void score_role(const AttnParams& p) {
 #pragma unroll
       for (int j = 0; j < 2; ++j)
         if (vs_e0 + 256 * j < nsb * kTile) vs[vs_e0 + 256 * j] = vsr[j];
-      if (!(cx.dbg & 2)) score_tile_i8<MT, NBW>(A, ksc, qhi, sp);
+      if (!(cx.dbg & 2)) score_tile_i8<MT, NBW>(A, ksc, g, qhi, sp);
     } else {
       if (!(cx.dbg & 2)) score_tile<Tag, MT, SPLIT, NKW>(A, qhi, qlo, sp);
     }
@@ -1098,9 +1131,15 @@ __device__ __forceinline__ void sum_role(const AttnParams& p) {
     const char* vA = cx.ring + slot0 * cx.unit_bytes + (4 * g) * cx.pitch + cp * 64 + n * 4;
     const char* vB = vA + cx.unit_bytes;
     if constexpr (I8) {
+      f32x4_t P32[MT][2];
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) {
+        P32[mt][0] = __builtin_bit_cast(f32x4_t, Phi[mt]);
+        P32[mt][1] = __builtin_bit_cast(f32x4_t, cx.Pbuf[(mt * 2 + 1) * 64 + lane]);
+      }
       if (!(cx.dbg & 2))
         wsum_tile_i8<MT, NGRP>(vA, vB, cx.pitch, RAGGED ? uni(cx.meta[4 * t + 2]) : r, cp, g,
-                               cx.vsb + (t & 1) * (r >> 6) * kTile, Phi, alpha, U);
+                               cx.vsb + (t & 1) * (r >> 6) * kTile, P32, alpha, U);
     } else {
       if (!(cx.dbg & 2))
         wsum_tile<Tag, MT, SPLIT, NGRP>(vA, vB, cx.pitch,

@@ -103,7 +103,9 @@ def test_config5_decode_full_size():
     ref = oracle_i8(q, codes[0], scales[0], codes[1], scales[1], case.Bk, case.Bv, T)
     ref = np.stack([ref[b] for b in range(B)])
     rel = assert_close(got, ref, "f16", "config 5 decode")
-    print(f"  max|err|/||out||inf = {rel:.2e}", flush=True)
+    per_seq = max(np.abs(got[b] - ref[b]).max() / np.abs(ref[b]).max() for b in range(B))
+    print(f"  max|err|/||out||inf = {rel:.2e} over the step's output, {per_seq:.2e} per sequence", flush=True)
+    assert per_seq <= 2e-3          # the stricter norm holds too (scales are applied in fp32)
 
 
 @pytest.mark.parametrize("B,H,d,r,T,granks,cum,den,use_k,use_v", [
