@@ -5,7 +5,7 @@ import torch
 
 import oracle
 from paper_2603_23914_amd import workloads as wl
-from gpu_util import TORCH_DT, to_dev, to_host64
+from gpu_util import TORCH_DT, assert_close, to_dev, to_host64, workspace
 
 pytestmark = pytest.mark.gpu
 
@@ -132,3 +132,47 @@ def test_config5_full_size_sampled():
             rc, rs = oracle.quantize_i8(got16)
             assert (C8[b].cpu().numpy()[rows] == rc).all(), f"codes differ (b={b})"
             assert (s[b].cpu().numpy()[rows].view(np.uint16) == rs.view(np.uint16)).all(), f"scales differ (b={b})"
+
+
+def test_config5_chain_with_true_svd_bases():
+    """Configuration 5 as one chain on one sequence whose bases are the true leading right singular
+    vectors (oracle.bases of the fp16 cache): prefill compaction to fp16 and to int8 on the GPU,
+    then one decode step over the int8 coefficients.  Projection against the fp64 product, codes
+    and scales bit for bit against the oracle's quantiser on the GPU's fp16 coefficients, decode
+    output against the oracle on code * scale."""
+    from paper_2603_23914_amd import binding as ap
+    import math
+    T, H, d, r = 1100, 8, 128, 128
+    HD = H * d
+    K, V, _, _ = wl.config5_sequence(0, seed=3, T=T, HD=HD, r=r)
+    P = lambda x: x.astype(np.float64)
+    Bk = oracle.bases(P(K), r).astype(np.float16)
+    Bv = oracle.bases(P(V), r).astype(np.float16)
+    print("config 5 chain: singular bases computed", flush=True)
+    C16k, C16v, _, _ = run_compact("f16", K[None], V[None], Bk[None], Bv[None], T, 0)
+    C8k, C8v, sk, sv = run_compact("f16", K[None], V[None], Bk[None], Bv[None], T, 0, out_dtype=torch.int8)
+    for C16, C8, s, X, Bm in ((C16k, C8k, sk, K, Bk), (C16v, C8v, sv, V, Bv)):
+        ref = oracle.compact(P(X), P(Bm))
+        got16 = C16[0].cpu().numpy()
+        err = np.abs(P(got16) - ref)
+        assert (err <= ROUND["f16"] * np.abs(ref) + 1e-5 * np.abs(ref).max()).all(), err.max()
+        rc, rs = oracle.quantize_i8(got16)
+        assert (C8[0].cpu().numpy() == rc).all()
+        assert (s[0].cpu().numpy().view(np.uint16) == rs.view(np.uint16)).all()
+    # the coefficients of a singular basis carry the spectrum: column energies do not increase
+    en = (P(C16k[0].cpu().numpy()) ** 2).sum(axis=0)
+    assert (en[1:] <= en[:-1] * 1.02).all()
+    q = wl.store(wl.rng_for(3, 77).standard_normal((1, H, d)), "f16")
+    out = torch.empty((1, H, d), dtype=torch.float32, device="cuda")
+    ws = workspace(ap.ap_decode_workspace_bytes(1, H, d, T, r, ap.AP_F16))
+    ap.ap_decode_attn(to_dev(q, "f16"), C8k, C8v, to_dev(Bk[None], "f16"), to_dev(Bv[None], "f16"), out, ws, T=T,
+                      sm_scale=1.0 / math.sqrt(d), scale_k=sk, scale_v=sv)
+    torch.cuda.synchronize()
+    ck = oracle.dequantize_i8(C8k[0].cpu().numpy(), sk[0].cpu().numpy())
+    cv = oracle.dequantize_i8(C8v[0].cpu().numpy(), sv[0].cpu().numpy())
+    ref = oracle.decode_attn_absorbed(P(q[0]), ck, cv, P(Bk), P(Bv))
+    assert_close(to_host64(out[0]), ref, "f16", "config 5 chain decode")
+    # and the int8 cache stands in for the uncompressed one (sanity, not equality: half of the
+    # planted directions lie beyond the rank kept)
+    plain = oracle.raw_attn(P(q[0]), P(K), P(V))
+    assert np.abs(ref - plain).max() < 0.5 * np.abs(plain).max()

@@ -182,3 +182,37 @@ def test_decode_small_rank(dtype, B, H, d, r, T, value_path):
     Bk0 = P(case.Bk) if case.Bk.ndim == 2 else P(case.Bk)[0]
     A_ref = oracle.attention_probs(P(q)[0], P(Ck_h)[0, :T + 1], Bk0)
     assert np.abs(A - A_ref).max() <= 2e-3 * A_ref.max()
+
+
+@pytest.mark.parametrize("B,H,d,r,T,fused", [(2, 40, 128, 640, 301, False), (3, 16, 64, 128, 97, False),
+                                             (2, 40, 128, 640, 150, True)])
+def test_bf16_output_is_the_fp32_result_rounded_once(B, H, d, r, T, fused, value_path):
+    """dt_out = AP_BF16: the kernels round their fp32 result to bfloat16 (nearest even) on the way
+    out.  bfloat16 keeps 8 significant bits, so the bound against the oracle is one rounding,
+    2^-8 |out|, on top of the fp32 path's 2e-3 ||out||_inf."""
+    from paper_2603_23914_amd import binding as ap
+    dtype = "bf16"
+    case = wl.decode_case(dtype, B, H, d, r, T - 1 if fused else T, steps=1 if fused else 0, seed=44, append=fused)
+    q = wl.step_query(case, 0)
+    P = lambda x: oracle.promote(x, dtype)
+    dq, dBk, dBv = (to_dev(x, dtype) for x in (q, case.Bk, case.Bv))
+    outs = []
+    for odt in (torch.float32, torch.bfloat16):
+        dCk, dCv = to_dev(case.Ck, dtype), to_dev(case.Cv, dtype)
+        out = torch.empty((B, H, d), dtype=odt, device="cuda")
+        ws = workspace(ap.ap_decode_workspace_bytes(B, H, d, T, r, ap.AP_BF16))
+        print(f"bf16 out={odt} B={B} H={H} r={r} T={T} fused={fused}", flush=True)
+        if fused:
+            kn, vn = wl.step_new_token(case, 0, P(case.Bk), P(case.Bv))
+            ap.ap_decode_step(dq, to_dev(kn, dtype), to_dev(vn, dtype), dCk, dCv, dBk, dBv, out, ws, T=T,
+                              sm_scale=1.0 / math.sqrt(d))
+        else:
+            ap.ap_decode_attn(dq, dCk, dCv, dBk, dBv, out, ws, T=T, sm_scale=1.0 / math.sqrt(d))
+        torch.cuda.synchronize()
+        outs.append(out)
+        Ck_h = dCk.view(torch.int16).cpu().numpy().view(np.uint16)
+        Cv_h = dCv.view(torch.int16).cpu().numpy().view(np.uint16)
+    assert torch.equal(outs[1].view(torch.int16), outs[0].to(torch.bfloat16).view(torch.int16))
+    ref = oracle.decode_attn_batched(P(q), P(Ck_h), P(Cv_h), P(case.Bk), P(case.Bv), T, absorbed=True)
+    err = np.abs(to_host64(outs[1]) - ref)
+    assert (err <= 2.0 ** -8 * np.abs(ref) + 2e-3 * np.abs(ref).max()).all(), err.max()

@@ -100,6 +100,8 @@ def test_compressed_plus_uncompressed_under_one_softmax(dtype, B, H, d, r, T, T_
     ap.ap_merge_segments(out_c, lse_c, out_u, lse_u, out_c)                      # in place
     torch.cuda.synchronize()
     assert torch.equal(out, out_c)
+    # the 16-bit output is the fp32 result rounded once, to nearest even
+    assert torch.equal(out16.view(torch.int16), out.to(TORCH_DT[dtype]).view(torch.int16))
     P = lambda x: oracle.promote(x, dtype)
     for b in range(B):
         segs = [dict(Ck=P(case.Ck)[b, :T], Cv=P(case.Cv)[b, :T], Bk=P(case.Bk)[b], Bv=P(case.Bv)[b],
