@@ -30,6 +30,14 @@
  *     Device-side data errors (NaN mass, rank arrays that disagree with the bucket
  *     lists, ranks that are not multiples of the granularity) are undefined
  *     behaviour within the caller's buffers: documented, not checked.
+ *   - State the library keeps per process (everything else lives in the caller's buffers):
+ *     the records and switch of ap_prof_enable, the tuning value of
+ *     ap_set_fused_value_min_bytes, one flag per kernel variant saying that its
+ *     shared-memory limit has been raised (set on the variant's first launch), and the
+ *     per-device address of the scratch buffer of ap_decode_attn_static.  The compute entry
+ *     points may be called from several host threads at once as long as nobody calls
+ *     ap_prof_enable / ap_prof_read / ap_set_fused_value_min_bytes meanwhile and timing is
+ *     off (the flags and the address are written with the same value by whoever comes first).
  */
 #ifndef ATTNPACK_H
 #define ATTNPACK_H
@@ -150,8 +158,12 @@ size_t ap_select_workspace_bytes(int B, int T, int F);
  *            produced for these rank arrays (every token of a group has the same
  *            rank_k and the same rank_v).  Required for AP_F16 / AP_BF16 when a rank
  *            array is given (the kernels walk rank-uniform token tiles); ranks must
- *            then be multiples of 64 in [64, r].  AP_F32 reads the rank arrays directly
- *            (any value in [0, r]) and ignores the bucket lists.
+ *            then be multiples of 16 in [16, r] (the paper's low ranks are 16 and 32),
+ *            multiples of AP_QBLOCK = 64 with int8 coefficients (a scale block is read
+ *            whole or not at all).  Other values are device-side data errors: a rank is
+ *            then applied rounded down to a multiple of 8 (of 64 for int8), nothing is
+ *            read out of bounds.  AP_F32 reads the rank arrays directly (any value in
+ *            [0, r]) and ignores the bucket lists.
  *   out      [B, H, d] dtype dt_out: dt (round-to-nearest-even from fp32) or AP_F32.
  *            bfloat16 keeps 8 significant bits (unit roundoff 2^-8 = 3.9e-3), so a
  *            bf16 output cannot meet a 2e-3 error bound by rounding alone: callers

@@ -855,7 +855,9 @@ __device__ __forceinline__ void score_role(const AttnParams& p) {
     } else {
       // gathered rows; k-steps at or beyond the tile's key rank re-read bytes this wave
       // (or, with no k-step left, its neighbours) fetch anyway
-      const int nks_t = uni(cx.meta[4 * tile + 1]) >> (I8 ? 6 : 5);   // units of 64 bytes
+      // (a key rank that ends inside a 32-column k-step still fetches that k-step; the columns
+      // beyond the rank are zeroed before the product)
+      const int nks_t = I8 ? uni(cx.meta[4 * tile + 1]) >> 6 : (uni(cx.meta[4 * tile + 1]) + 31) >> 5;   // units of 64 bytes
       const uint32_t loff = (uint32_t)((w < nks_t ? w * 64 : 0) + g * 16);
 #pragma unroll
       for (int tt = 0; tt < 2; ++tt) {
@@ -907,10 +909,14 @@ __device__ __forceinline__ void score_role(const AttnParams& p) {
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) { f32x4_t z = {0.f, 0.f, 0.f, 0.f}; sp[mt][0] = z; sp[mt][1] = z; }
     if (RAGGED) {                                         // columns beyond the key rank count as zero
-      const int nks_t = uni(cx.meta[4 * t + 1]) >> (I8 ? 6 : 5);
+      const int rk_t = uni(cx.meta[4 * t + 1]);
 #pragma unroll
-      for (int i = 0; i < NA; ++i)
-        if ((w + 4 * i) >= nks_t) { u32x4_t z = {0, 0, 0, 0}; A[i][0] = z; A[i][1] = z; }
+      for (int i = 0; i < NA; ++i) {
+        // 16-bit: this lane's eight columns of k-step w + 4i start at 32 (w + 4i) + 8 g, and ranks
+        // are multiples of 8 there; int8: whole 64-column scale blocks
+        const bool beyond = I8 ? (w + 4 * i) * 64 >= rk_t : (w + 4 * i) * 32 + g * 8 >= rk_t;
+        if (beyond) { u32x4_t z = {0, 0, 0, 0}; A[i][0] = z; A[i][1] = z; }
+      }
     }
     if constexpr (I8) {
       // hand tile t's value scales to the sum waves (buffer t&1: its previous reader, the

@@ -67,6 +67,9 @@ CASES = [
     ("f16", 2, 64, 32, 64, 1500, (64, 32), (1, 10), 10),          # four head tiles, many tiles per wave
     ("bf16", 8, 32, 128, 128, 2000, (128, 16), (1, 4), 4),         # whole groups of 8 sequences
     ("f16", 1, 8, 128, 64, 20, (64, 16), (1, 2), 2),               # fewer tokens than a tile
+    # ranks that end inside a 32-column product step of the two-role kernel (cache rank above 128)
+    ("bf16", 2, 40, 128, 640, 301, (640, 208, 48, 16), (1, 2, 3, 4), 4),
+    ("f16", 2, 32, 128, 256, 500, (256, 144, 80, 16), (1, 2, 3, 4), 4),
 ]
 
 
