@@ -7,6 +7,9 @@ cpu_baseline leg of bench.py.  It shares no code with the HIP kernels.
 from .attnpack_oracle import (  # noqa: F401
     promote,
     bases,
+    randomized_bases,
+    basis_quality,
+    decompress,
     compact,
     decode_attn,
     decode_attn_absorbed,

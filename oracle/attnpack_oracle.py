@@ -76,6 +76,81 @@ def compact(X: np.ndarray, D: np.ndarray) -> np.ndarray:
     return np.asarray(X, dtype=np.float64) @ np.asarray(D, dtype=np.float64).T
 
 
+def randomized_bases(X: np.ndarray, Omega: np.ndarray, r: int, power_iters: int) -> Tuple[np.ndarray, np.ndarray]:
+    """Randomized low-rank SVD of the head-merged cache X [T, HD] (the appendix's
+    implementation details name randomized SVD for the compression step of
+    Sec. 3.1 / Alg. 1), written out from the published range-finder scheme on the
+    ROW space, the start block passed in:
+
+      P <- Omega                      [l, HD], l = r + oversampling, any full-rank start
+      repeat power_iters + 1 times:   P <- orthonormal rows spanning rows of (P X^T) X
+      Z <- X P^T                      [T, l]   (Rayleigh-Ritz in the span of P)
+      Z = U S W^T  (plain SVD)        D <- (W^T P)[:r],  sigma <- S[:r]
+
+    Returns (D [r, HD] with orthonormal rows ordered by decreasing sigma, sigma [r]).
+    With Omega spanning the leading l right singular vectors, or as power_iters
+    grows, D tends to `bases(X, r)` up to the sign of each row.
+    """
+    X = np.asarray(X, np.float64)
+    P = np.asarray(Omega, np.float64)
+    for _ in range(int(power_iters) + 1):
+        M = (P @ X.T) @ X                                  # [l, HD]
+        Q, _ = np.linalg.qr(M.T)                           # orthonormal columns spanning rows of M
+        P = Q.T
+    Z = X @ P.T
+    _, S, Wt = np.linalg.svd(Z, full_matrices=False)
+    return (Wt @ P)[:r].copy(), S[:r].copy()
+
+
+def basis_quality(X: np.ndarray, D: np.ndarray) -> dict:
+    """How good a rank-r decompression matrix D [r, HD] is for the cache X [T, HD],
+    against what the definition (truncated SVD, Sec. 3.1) achieves.  A basis is
+    only determined up to signs (and rotations inside repeated singular values),
+    so it is judged by what is unique:
+
+      orth_err        max |D D^T - I|                      rows orthonormal
+      residual        ||X - (X D^T) D||_F^2                 what the cache loses
+      optimal         sum_{i>r} sigma_i^2                   Eckart-Young minimum
+      ratio           residual / optimal                    >= 1 for orthonormal rows
+      energy          e_i = ||X d_i||^2                     per row of D
+      lead_capture    min_k sum_{i<=k} e_i / sum_{i<=k} sigma_i^2   (<= 1, Ky Fan): every
+                      leading-k truncation of the basis (attention-aware decompression
+                      reads leading columns) is as good as the best rank-k one
+      order_violation max_i (e_{i+1} - e_i) / e_1, positive part   rows ordered by energy
+      sin_angle       sine of the largest principal angle between the row space of D
+                      and the span of the r leading right singular vectors
+    """
+    X = np.asarray(X, np.float64)
+    D = np.asarray(D, np.float64)
+    r = D.shape[0]
+    _, S, Vt = np.linalg.svd(X, full_matrices=False)
+    C = X @ D.T
+    residual = float(np.linalg.norm(X - C @ D) ** 2)
+    optimal = float(np.sum(S[r:] ** 2))
+    energy = (C ** 2).sum(axis=0)
+    lead = np.cumsum(energy) / np.cumsum(S[:r] ** 2)
+    Q, _ = np.linalg.qr(D.T)                               # orthonormal basis of the row space of D
+    out_of_span = Q - Vt[:r].T @ (Vt[:r] @ Q)
+    return {
+        "orth_err": float(np.abs(D @ D.T - np.eye(r)).max()),
+        "residual": residual,
+        "optimal": optimal,
+        "ratio": residual / optimal if optimal > 0 else (1.0 if residual == 0 else np.inf),
+        "energy": energy,
+        "lead_capture": float(lead.min()),
+        "order_violation": float(max(0.0, np.max(np.diff(energy), initial=0.0)) / energy[0]),
+        "sin_angle": float(np.linalg.norm(out_of_span, 2)),
+        "sigma": S,
+    }
+
+
+def decompress(C: np.ndarray, D: np.ndarray, rank: Optional[np.ndarray] = None) -> np.ndarray:
+    """Alg. 1 "retrieve cache" for a compressed segment on its own: row t is
+    C[t, :rank[t]] D[:rank[t]] (rank None = all r columns).  [T, HD]."""
+    C = np.asarray(C, np.float64)
+    return _partial_decompress(C, np.asarray(D, np.float64), _ranks(rank, C.shape[0], C.shape[1]))
+
+
 # --------------------------------------------------------------------------
 # decode attention (Alg. 1, retrieve / scores / output steps)
 # --------------------------------------------------------------------------
