@@ -99,6 +99,54 @@ ap_status ap_compact(const void* K, const void* V, const void* Bk, const void* B
                      void* stream);
 
 /* ------------------------------------------------------------------------
+ * ap_compute_bases -- the compression step itself (paper Sec. 3.1: low-rank SVD of
+ * the head-merged cache; Alg. 1, compress step; the appendix's implementation
+ * details: randomized SVD).  For every sequence b the rows of Bm[b] are the r
+ * leading right singular vectors of X[b] (approximately: randomized range finder
+ * on the row space with l = r + oversample vectors and power_iters power
+ * iterations, then Rayleigh-Ritz), orthonormal, in decreasing order of singular
+ * value, so that leading rows / coefficient columns carry the most energy.  The
+ * coefficients then follow from ap_compact(X, Bm).
+ *
+ *   X      [B, n, HD]  dt (AP_F16 | AP_BF16), contiguous
+ *   Omega  [l, HD]     dt: the start block (random numbers are the caller's: e.g.
+ *                      i.i.d. Gaussian entries; any block of full row rank works);
+ *                      sequence b reads Omega + b*omega_batch_stride elements
+ *                      (0 = one block for all)
+ *   Bm     [B, r, HD]  dt, written
+ *   sigma  [B, r] fp32 or NULL: the singular values that go with the rows
+ *   power_iters  0 .. 16; 2 is enough for spectra that decay like i^-0.7
+ *   workspace    ap_bases_workspace_bytes(B, n, HD, r, oversample) bytes, 256-byte
+ *                aligned (0 from the query = unsupported shape)
+ * Requires HD % 64 == 0, n % 8 == 0, l even, l <= 1024, l <= n, l <= HD.
+ * A basis is unique only up to the sign of each row (and rotations inside equal
+ * singular values): results are to be judged by what they achieve (orthonormal
+ * rows, residual of the rank-r reconstruction against the optimum), not compared
+ * element by element.  Directions that X does not span (fewer than l independent
+ * rows) come out as zero rows at the end of the order.
+ *
+ * ap_decompress -- Alg. 1 "retrieve cache" as a matrix:
+ *   X[b, t, :] = C[b, t, :rank[b,t]] . Bm[b][:rank[b,t]]        t < T
+ * i.e. what the periodic re-compression decomposes again, next to the uncompressed
+ * tail: write it in front of the tail's rows, call ap_compute_bases and ap_compact
+ * on the whole.
+ *   C     [B, T_cap, r] dt;  Bm [r, HD] dt (+ basis_batch_stride, 0 = shared)
+ *   rank  [B, T] int32 or NULL (= r everywhere)
+ *   X     [B, T, HD] dt, written (fp32 accumulation, rounded to nearest even)
+ *   workspace  ap_decompress_workspace_bytes(B, T, HD, r, rank != NULL), 256-byte aligned
+ * Requires r % 64 == 0, HD % 8 == 0.
+ * ---------------------------------------------------------------------- */
+size_t ap_bases_workspace_bytes(int B, int n, int HD, int r, int oversample);
+ap_status ap_compute_bases(const void* X, const void* Omega, int64_t omega_batch_stride,
+                           void* Bm, float* sigma, int B, int n, int HD, int r, int oversample,
+                           int power_iters, ap_dtype dt, void* workspace, size_t ws_bytes,
+                           void* stream);
+size_t ap_decompress_workspace_bytes(int B, int T, int HD, int r, int with_ranks);
+ap_status ap_decompress(const void* C, const void* Bm, int64_t basis_batch_stride,
+                        const int32_t* rank, void* X, int B, int T, int T_cap, int HD, int r,
+                        ap_dtype dt, void* workspace, size_t ws_bytes, void* stream);
+
+/* ------------------------------------------------------------------------
  * ap_quantize_i8 -- the int8 coefficient format of ap_compact applied to
  * coefficients that already exist in fp16 (same recipe, bit for bit).
  *   C      [B, T_cap, r] fp16, rows 0..T-1 read

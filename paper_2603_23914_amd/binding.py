@@ -33,6 +33,14 @@ _vp, _i, _i64, _sz, _f = _c.c_void_p, _c.c_int, _c.c_int64, _c.c_size_t, _c.c_fl
 
 _lib.ap_compact.restype = _i
 _lib.ap_compact.argtypes = [_vp] * 8 + [_i] * 6 + [_i64, _i, _i, _vp]
+_lib.ap_bases_workspace_bytes.restype = _sz
+_lib.ap_bases_workspace_bytes.argtypes = [_i] * 5
+_lib.ap_compute_bases.restype = _i
+_lib.ap_compute_bases.argtypes = [_vp, _vp, _i64, _vp, _vp] + [_i] * 7 + [_vp, _sz, _vp]
+_lib.ap_decompress_workspace_bytes.restype = _sz
+_lib.ap_decompress_workspace_bytes.argtypes = [_i] * 5
+_lib.ap_decompress.restype = _i
+_lib.ap_decompress.argtypes = [_vp, _vp, _i64, _vp, _vp] + [_i] * 6 + [_vp, _sz, _vp]
 _lib.ap_quantize_i8.restype = _i
 _lib.ap_quantize_i8.argtypes = [_vp, _vp, _vp, _i, _i, _i, _i, _vp]
 _lib.ap_select_ranks.restype = _i
@@ -87,7 +95,8 @@ _lib.ap_prof_read.argtypes = [_c.POINTER(_c.c_float), _c.POINTER(_c.c_int)]
 _lib.ap_prof_read_launches.restype = _i
 _lib.ap_prof_read_launches.argtypes = [_c.POINTER(_c.c_float), _i, _c.POINTER(_c.c_int)]
 
-EXPORTS = ("ap_compact", "ap_quantize_i8", "ap_select_ranks", "ap_select_workspace_bytes",
+EXPORTS = ("ap_compact", "ap_bases_workspace_bytes", "ap_compute_bases", "ap_decompress_workspace_bytes",
+           "ap_decompress", "ap_quantize_i8", "ap_select_ranks", "ap_select_workspace_bytes",
            "ap_decode_attn", "ap_decode_attn_static", "ap_decode_step", "ap_update_importance", "ap_decode_workspace_bytes",
            "ap_raw_workspace_bytes", "ap_raw_attn", "ap_keyonly_workspace_bytes", "ap_keyonly_attn",
            "ap_valueonly_workspace_bytes", "ap_valueonly_attn", "ap_merge_segments", "ap_raw_append", "ap_status_string", "ap_last_error",
@@ -156,6 +165,33 @@ def ap_compact(K, V, Bk, Bv, Ck, Cv, scale_k=None, scale_v=None, *, n: int, row0
     _check(_lib.ap_compact(_p(K), _p(V), _p(Bk), _p(Bv), _p(Ck), _p(Cv), _p(scale_k), _p(scale_v),
                            B, n, row0, T_cap, HD, r, _bstride(Bx), _DT[X.dtype], _DT[Cx.dtype],
                            _stream(stream)))
+
+
+def ap_bases_workspace_bytes(B: int, n: int, HD: int, r: int, oversample: int) -> int:
+    return _lib.ap_bases_workspace_bytes(B, n, HD, r, oversample)
+
+
+def ap_compute_bases(X, Omega, Bm, workspace, *, power_iters: int = 2, sigma=None, stream=None) -> None:
+    """X [B, n, HD]; Omega [l, HD] or [B, l, HD] start block (l = r + oversampling); Bm [B, r, HD] out;
+    sigma [B, r] fp32 out (optional)."""
+    B, n, HD = X.shape
+    r = Bm.shape[1]
+    l = Omega.shape[-2]
+    _check(_lib.ap_compute_bases(_p(X), _p(Omega), 0 if Omega.dim() == 2 else Omega.stride(0), _p(Bm), _p(sigma),
+                                 B, n, HD, r, l - r, int(power_iters), _DT[X.dtype], _p(workspace),
+                                 workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
+def ap_decompress_workspace_bytes(B: int, T: int, HD: int, r: int, with_ranks: bool) -> int:
+    return _lib.ap_decompress_workspace_bytes(B, T, HD, r, int(with_ranks))
+
+
+def ap_decompress(C, Bm, X, workspace, *, T: int, rank=None, stream=None) -> None:
+    """C [B, T_cap, r], Bm [r, HD] or [B, r, HD] -> X [B, T, HD] = C[:, :T, :rank] Bm[:rank]."""
+    B, T_cap, r = C.shape
+    HD = Bm.shape[-1]
+    _check(_lib.ap_decompress(_p(C), _p(Bm), _bstride(Bm), _p(rank), _p(X), B, T, T_cap, HD, r, _DT[C.dtype],
+                              _p(workspace), workspace.numel() * workspace.element_size(), _stream(stream)))
 
 
 def ap_quantize_i8(C, codes, scales, *, T: int, stream=None) -> None:

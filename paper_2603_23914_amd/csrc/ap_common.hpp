@@ -118,6 +118,19 @@ struct CompactArgs {
 };
 ap_status launch_compact(const CompactArgs& a);
 bool compact_gemm_applies(const CompactArgs& a);       // matrix-core path (compact_gemm.hip)
+// General product of two 16-bit matrices that are contiguous along the contraction axis
+// (compact_gemm.hip): C[b][m, j] = sum_k A[b][m, k] B[b][j, k].
+struct NtGemmArgs {
+  const void* A;  int64_t a_bstride; int lda;     // [M][K], elements
+  const void* Bm; int64_t b_bstride; int ldb;     // [N][K] (b_bstride 0 = shared)
+  void* C;        int64_t c_bstride; int ldc;     // [M][N] in elements of the output type
+  void* scale;    int64_t s_bstride;              // out_kind 1: fp16 scales [M][N / 64]
+  int batch, M, N, K;
+  ap_dtype dt;                                    // AP_F16 or AP_BF16 (type of A and B)
+  int out_kind;                                   // 0 = dt, 1 = int8 codes + scales, 2 = fp32
+  hipStream_t stream;
+};
+ap_status launch_gemm_nt(const NtGemmArgs& a, const NtGemmArgs* second = nullptr);
 // `second`: another projection of the same shape (B, n, row0, T_cap, HD, r, stride, types) that
 // runs in the same launch, or null
 ap_status launch_compact_gemm(const CompactArgs& a, const CompactArgs* second = nullptr);
@@ -191,6 +204,24 @@ ap_status launch_select_ranks(const float* mass, int B, int T, int F, const int3
                               const int32_t* bounds_num, int32_t den, int32_t* rank_out,
                               int32_t* bucket_off, int32_t* bucket_idx, void* ws,
                               hipStream_t stream);
+
+// the compression step (bases.hip)
+struct BasesArgs {
+  const void* X;        // [B][n][HD]
+  const void* Omega;    // [l][HD] start block (omega_batch_stride elements apart, 0 = shared)
+  int64_t omega_batch_stride;
+  void* Bm;             // out [B][r][HD]
+  float* sigma;         // out [B][r] or null
+  int B, n, HD, r, oversample, power_iters;
+  ap_dtype dt;
+  void* workspace;
+  hipStream_t stream;
+};
+size_t bases_workspace(int B, int n, int HD, int r, int oversample);
+ap_status launch_compute_bases(const BasesArgs& a);
+size_t decompress_workspace(int B, int T, int HD, int r, bool ranks);
+ap_status launch_decompress(const void* C, const void* Bm, int64_t bstride, const int32_t* rank, void* X, int B,
+                            int T, int T_cap, int HD, int r, ap_dtype dt, void* workspace, hipStream_t stream);
 
 ap_status check_launch(const char* what);
 

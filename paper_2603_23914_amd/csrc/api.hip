@@ -220,6 +220,65 @@ ap_status ap_compact(const void* K, const void* V, const void* Bk, const void* B
 }
 
 // ---------------------------------------------------------------------------------------------
+static bool bases_shape_ok(int B, int n, int HD, int r, int oversample) {
+  const int64_t l = (int64_t)r + oversample;
+  return B > 0 && B <= 65535 && n > 0 && HD > 0 && r > 0 && oversample >= 0 && HD % 64 == 0 && n % 8 == 0 &&
+         l % 2 == 0 && l <= 1024 && l <= n && l <= HD;
+}
+
+size_t ap_bases_workspace_bytes(int B, int n, int HD, int r, int oversample) {
+  return bases_shape_ok(B, n, HD, r, oversample) ? bases_workspace(B, n, HD, r, oversample) : 0;
+}
+
+ap_status ap_compute_bases(const void* X, const void* Omega, int64_t omega_batch_stride, void* Bm, float* sigma,
+                           int B, int n, int HD, int r, int oversample, int power_iters, ap_dtype dt,
+                           void* workspace, size_t ws_bytes, void* stream) {
+  clear_error();
+  AP_REQUIRE(X && Omega && Bm, AP_ERR_INVALID_ARG, "ap_compute_bases: NULL pointer");
+  AP_REQUIRE(half_type(dt), AP_ERR_UNSUPPORTED, "ap_compute_bases: fp16 or bf16 storage only");
+  AP_REQUIRE(B > 0 && n > 0 && HD > 0 && r > 0 && oversample >= 0 && power_iters >= 0 && power_iters <= 16,
+             AP_ERR_INVALID_ARG, "ap_compute_bases: need B, n, HD, r > 0, oversample >= 0, 0 <= power_iters <= 16");
+  AP_REQUIRE(bases_shape_ok(B, n, HD, r, oversample), AP_ERR_UNSUPPORTED,
+             "ap_compute_bases: need HD %% 64 == 0, n %% 8 == 0, l = r + oversample even, l <= 1024, l <= n, "
+             "l <= HD (n=%d HD=%d r=%d oversample=%d)", n, HD, r, oversample);
+  const int64_t l = (int64_t)r + oversample;
+  AP_REQUIRE(omega_batch_stride == 0 || omega_batch_stride >= l * HD, AP_ERR_INVALID_ARG,
+             "ap_compute_bases: omega_batch_stride must be 0 or >= (r + oversample) * HD");
+  AP_REQUIRE(aligned(X, 16) && aligned(Omega, 16) && aligned(Bm, 16) && aligned(workspace, 256), AP_ERR_INVALID_ARG,
+             "ap_compute_bases: X, Omega, Bm must be 16-byte aligned, the workspace 256-byte");
+  const size_t need = bases_workspace(B, n, HD, r, oversample);
+  AP_REQUIRE(workspace && ws_bytes >= need, AP_ERR_WORKSPACE, "ap_compute_bases: workspace %zu bytes, need %zu",
+             ws_bytes, need);
+  BasesArgs a{X, Omega, omega_batch_stride, Bm, sigma, B, n, HD, r, oversample, power_iters, dt, workspace,
+              (hipStream_t)stream};
+  return launch_compute_bases(a);
+}
+
+size_t ap_decompress_workspace_bytes(int B, int T, int HD, int r, int with_ranks) {
+  if (B <= 0 || T <= 0 || HD <= 0 || r <= 0) return 0;
+  return decompress_workspace(B, T, HD, r, with_ranks != 0);
+}
+
+ap_status ap_decompress(const void* C, const void* Bm, int64_t basis_batch_stride, const int32_t* rank, void* X,
+                        int B, int T, int T_cap, int HD, int r, ap_dtype dt, void* workspace, size_t ws_bytes,
+                        void* stream) {
+  clear_error();
+  AP_REQUIRE(C && Bm && X, AP_ERR_INVALID_ARG, "ap_decompress: NULL pointer");
+  AP_REQUIRE(half_type(dt), AP_ERR_UNSUPPORTED, "ap_decompress: fp16 or bf16 storage only");
+  AP_REQUIRE(B > 0 && B <= 65535 && T > 0 && T <= T_cap && HD > 0 && r > 0, AP_ERR_INVALID_ARG,
+             "ap_decompress: need 0 < B <= 65535, 0 < T <= T_cap, HD, r > 0");
+  AP_REQUIRE(r % 64 == 0 && HD % 8 == 0, AP_ERR_UNSUPPORTED, "ap_decompress: need r %% 64 == 0 and HD %% 8 == 0");
+  AP_REQUIRE(basis_batch_stride == 0 || basis_batch_stride >= (int64_t)r * HD, AP_ERR_INVALID_ARG,
+             "ap_decompress: basis_batch_stride must be 0 or >= r*HD");
+  AP_REQUIRE(aligned(C, 16) && aligned(Bm, 16) && aligned(X, 16) && aligned(workspace, 256), AP_ERR_INVALID_ARG,
+             "ap_decompress: C, Bm, X must be 16-byte aligned, the workspace 256-byte");
+  const size_t need = decompress_workspace(B, T, HD, r, rank != nullptr);
+  AP_REQUIRE(workspace && ws_bytes >= need, AP_ERR_WORKSPACE, "ap_decompress: workspace %zu bytes, need %zu", ws_bytes,
+             need);
+  return launch_decompress(C, Bm, basis_batch_stride, rank, X, B, T, T_cap, HD, r, dt, workspace, (hipStream_t)stream);
+}
+
+// ---------------------------------------------------------------------------------------------
 ap_status ap_quantize_i8(const void* C, void* codes, void* scales, int B, int T, int T_cap, int r,
                          void* stream) {
   clear_error();

@@ -2,6 +2,11 @@
 //
 //   C[b, row0 + t, j] = sum_c X[b, t, c] * Bm[b][j, c]         X [n, HD], Bm [r, HD], C [T_cap, r]
 //
+// The kernel is a general "NT" product C[m, j] = sum_k A[m, k] B[j, k] of two 16-bit matrices
+// that are contiguous along the contraction axis (leading dimensions and batch strides of their
+// own, fp32 accumulation, output in the storage type, as int8 codes + scales, or in fp32); the
+// compression step's randomized SVD (bases.hip) uses it for its large products as well.
+//
 // Both operands are contiguous along the contraction axis, so tiles go HBM -> LDS with
 // direct-to-LDS 16-byte loads and come back out as MFMA operands with one ds_read_b128 each.
 // A workgroup (8 waves, 4 x 2) owns a 256-token x 128-column tile and walks the hidden axis
@@ -50,12 +55,13 @@ __device__ __forceinline__ void dma16(const void* gsrc, void* lds_uniform) {
 }
 
 struct GemmParams {
-  const uint16_t* X;
-  const uint16_t* Bm;
-  int64_t bstride;
-  void* C;
-  uint16_t* scale;
-  int n, row0, T_cap, HD, r, out_kind;
+  const uint16_t* X;        // A [n][lda] per batch item (x_bstride elements apart)
+  const uint16_t* Bm;       // B [r][ldb] per batch item (bstride elements apart, 0 = shared)
+  int64_t bstride, x_bstride, c_bstride, s_bstride;
+  void* C;                  // [n][ldc] per batch item, already offset to its first row
+  uint16_t* scale;          // int8 output: [n][r / 64] per batch item, already offset
+  int n, HD, r, out_kind;   // rows of A, contraction length, rows of B; 0 = 16-bit, 1 = int8, 2 = fp32
+  int lda, ldb, ldc;
   int MT, NT, G;            // token tiles, column tiles, workgroups in all
   // a second projection of the same shape in the same launch (keys and values of one prefill):
   // tiles G1 .. G-1 belong to it.  One launch of twice the tiles loses half as much to the last,
@@ -82,10 +88,11 @@ __global__ void __launch_bounds__(kThreads) compact_gemm(const GemmParams p) {
   const int mt = (logical / p.NT) % p.MT;
   const int b = logical / (p.NT * p.MT);
   const int m0 = mt * kBM, n0 = nt * kBN;
-  const char* Xb = (const char*)((second ? p.X2 : p.X) + (size_t)b * p.n * p.HD);
+  const char* Xb = (const char*)((second ? p.X2 : p.X) + (size_t)b * p.x_bstride);
   const char* Bb = (const char*)((second ? p.Bm2 : p.Bm) + (size_t)b * p.bstride);
-  void* const Cout = second ? p.C2 : p.C;
-  uint16_t* const Sout = second ? p.scale2 : p.scale;
+  char* const Cout = (char*)(second ? p.C2 : p.C) +
+                     (size_t)b * p.c_bstride * (p.out_kind == 0 ? 2 : (p.out_kind == 1 ? 1 : 4));
+  uint16_t* const Sout = (second ? p.scale2 : p.scale) + (size_t)b * p.s_bstride;
 
   // ---- direct-to-LDS loads: per stage 32 KiB of X rows then 16 KiB of basis rows; wave w
   //      issues 1-KiB blocks 4w .. 4w+3 of the former and 2w, 2w+1 of the latter.  Block j,
@@ -96,14 +103,14 @@ __global__ void __launch_bounds__(kThreads) compact_gemm(const GemmParams p) {
     const int P = (4 * w + i) * 64 + lane;
     const int row = P >> 3, kc = (P & 7) ^ ((row >> 1) & 7);
     int ra = m0 + row;  ra = ra < p.n ? ra : p.n - 1;        // rows past the end: finite duplicates
-    srcA[i] = ((uint32_t)ra * (uint32_t)p.HD + (uint32_t)kc * 8u) * 2u;
+    srcA[i] = ((uint32_t)ra * (uint32_t)p.lda + (uint32_t)kc * 8u) * 2u;
   }
 #pragma unroll
   for (int i = 0; i < 2; ++i) {
     const int P = (2 * w + i) * 64 + lane;
     const int row = P >> 3, kc = (P & 7) ^ ((row >> 1) & 7);
     int rb = n0 + row;  rb = rb < p.r ? rb : p.r - 1;
-    srcB[i] = ((uint32_t)rb * (uint32_t)p.HD + (uint32_t)kc * 8u) * 2u;
+    srcB[i] = ((uint32_t)rb * (uint32_t)p.ldb + (uint32_t)kc * 8u) * 2u;
   }
   auto issue = [&](int stage, int kb) {
     char* sA = smem + stage * kStageBytes + (4 * w) * 1024;
@@ -202,6 +209,33 @@ __global__ void __launch_bounds__(kThreads) compact_gemm(const GemmParams p) {
   }
   __syncthreads();                                         // the ring becomes the output staging area
 
+  if (p.out_kind == 2) {
+    // ---- fp32 output: stage [token][column] as floats, leave in 16-byte row segments
+    constexpr int kPitch32 = kBN + 4;
+    float* epf = (float*)smem;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int blk = 0; blk < 4; ++blk) {
+          const int col = wn * 64 + i * 32 + 8 * blk + 4 * ohalf;
+          const int tok = wm * 64 + j * 32 + orow;
+          const f32x4_t v = {acc[i][j][4 * blk + 0], acc[i][j][4 * blk + 1], acc[i][j][4 * blk + 2],
+                             acc[i][j][4 * blk + 3]};
+          *(f32x4_t*)(epf + tok * kPitch32 + col) = v;
+        }
+    __syncthreads();
+    const int c4 = tid & 31, colf = n0 + c4 * 4;
+#pragma unroll 1
+    for (int pass = 0; pass < kBM / 16; ++pass) {
+      const int tok = pass * 16 + (tid >> 5);
+      const int t = m0 + tok;
+      if (t < p.n && colf < p.r)      // r is a multiple of 8 on this path: whole 16-byte pieces
+        *(f32x4_t*)((float*)Cout + (size_t)t * p.ldc + colf) = *(const f32x4_t*)(epf + tok * kPitch32 + c4 * 4);
+    }
+    return;
+  }
   // ---- epilogue: round to the storage type, stage [token][column] in LDS
   uint16_t* epi = (uint16_t*)smem;
 #pragma unroll
@@ -226,9 +260,9 @@ __global__ void __launch_bounds__(kThreads) compact_gemm(const GemmParams p) {
     const int t = m0 + tok;
     const u32x4_t v = *(const u32x4_t*)(epi + tok * kEpiPitch + c8 * 8);
     const bool live = t < p.n && col < p.r;
-    const size_t row = (size_t)b * p.T_cap + p.row0 + t;
+    const size_t row = (size_t)t;
     if (p.out_kind == 0) {
-      if (live) *(u32x4_t*)((uint16_t*)Cout + row * p.r + col) = v;
+      if (live) *(u32x4_t*)((uint16_t*)Cout + row * p.ldc + col) = v;
     } else {
       // int8 format: amax over the 64-column block (8 lanes x 8 values), fp16 scale, codes
       float x[8];
@@ -251,7 +285,7 @@ __global__ void __launch_bounds__(kThreads) compact_gemm(const GemmParams p) {
       }
       if (live) {
         u32x2_t cw = {lo, hi};
-        *(u32x2_t*)((int8_t*)Cout + row * p.r + col) = cw;
+        *(u32x2_t*)((int8_t*)Cout + row * p.ldc + col) = cw;
         if ((c8 & 7) == 0) Sout[row * (p.r / AP_QBLOCK) + (col >> 6)] = __builtin_bit_cast(uint16_t, sh);
       }
     }
@@ -259,24 +293,25 @@ __global__ void __launch_bounds__(kThreads) compact_gemm(const GemmParams p) {
 }
 
 template <class Tag>
-ap_status run_gemm(const CompactArgs& a, const CompactArgs* a2) {
+ap_status run_gemm(const NtGemmArgs& a, const NtGemmArgs* a2) {
   GemmParams p{};
-  p.X = (const uint16_t*)a.X;
+  p.X = (const uint16_t*)a.A;
   p.Bm = (const uint16_t*)a.Bm;
-  p.bstride = a.basis_batch_stride;
+  p.bstride = a.b_bstride; p.x_bstride = a.a_bstride; p.c_bstride = a.c_bstride; p.s_bstride = a.s_bstride;
   p.C = a.C;
   p.scale = (uint16_t*)a.scale;
-  p.n = a.n; p.row0 = a.row0; p.T_cap = a.T_cap; p.HD = a.HD; p.r = a.r;
-  p.out_kind = a.dt_out == AP_I8 ? 1 : 0;
-  p.MT = (a.n + kBM - 1) / kBM;
-  p.NT = (a.r + kBN - 1) / kBN;
-  const int64_t G1 = (int64_t)a.B * p.MT * p.NT;
+  p.n = a.M; p.HD = a.K; p.r = a.N;
+  p.lda = a.lda; p.ldb = a.ldb; p.ldc = a.ldc;
+  p.out_kind = a.out_kind;
+  p.MT = (a.M + kBM - 1) / kBM;
+  p.NT = (a.N + kBN - 1) / kBN;
+  const int64_t G1 = (int64_t)a.batch * p.MT * p.NT;
   const int64_t G = a2 ? 2 * G1 : G1;
-  AP_REQUIRE(G <= (1 << 28), AP_ERR_UNSUPPORTED, "ap_compact: too many tiles");
+  AP_REQUIRE(G <= (1 << 28), AP_ERR_UNSUPPORTED, "matrix product: too many tiles");
   p.G = (int)G;
   p.G1 = (int)G1;
   if (a2) {
-    p.X2 = (const uint16_t*)a2->X;
+    p.X2 = (const uint16_t*)a2->A;
     p.Bm2 = (const uint16_t*)a2->Bm;
     p.C2 = a2->C;
     p.scale2 = (uint16_t*)a2->scale;
@@ -294,7 +329,20 @@ ap_status run_gemm(const CompactArgs& a, const CompactArgs* a2) {
     attr_set = true;
   }
   hipLaunchKernelGGL(kern, dim3(grid), dim3(kThreads), kStages * kStageBytes, a.stream, p);
-  return check_launch("ap_compact");
+  return check_launch("matrix product");
+}
+
+NtGemmArgs nt_args_of(const CompactArgs& a) {
+  NtGemmArgs g{};
+  g.A = a.X; g.a_bstride = (int64_t)a.n * a.HD; g.lda = a.HD;
+  g.Bm = a.Bm; g.b_bstride = a.basis_batch_stride; g.ldb = a.HD;
+  const size_t esz = a.dt_out == AP_I8 ? 1 : 2;
+  g.C = (char*)a.C + (size_t)a.row0 * a.r * esz; g.c_bstride = (int64_t)a.T_cap * a.r; g.ldc = a.r;
+  g.scale = a.scale ? (uint16_t*)a.scale + (size_t)a.row0 * (a.r / AP_QBLOCK) : nullptr;
+  g.s_bstride = (int64_t)a.T_cap * (a.r / AP_QBLOCK);
+  g.batch = a.B; g.M = a.n; g.N = a.r; g.K = a.HD;
+  g.dt = a.dt_in; g.out_kind = a.dt_out == AP_I8 ? 1 : 0; g.stream = a.stream;
+  return g;
 }
 
 }  // namespace
@@ -309,7 +357,21 @@ bool compact_gemm_applies(const CompactArgs& a) {
 }
 
 ap_status launch_compact_gemm(const CompactArgs& a, const CompactArgs* second) {
-  return a.dt_in == AP_F16 ? run_gemm<F16Tag>(a, second) : run_gemm<BF16Tag>(a, second);
+  const NtGemmArgs g = nt_args_of(a);
+  if (!second) return launch_gemm_nt(g, nullptr);
+  const NtGemmArgs g2 = nt_args_of(*second);
+  return launch_gemm_nt(g, &g2);
+}
+
+// C[b][m, j] = sum_k A[b][m, k] B[b][j, k]: K a multiple of 64, N a multiple of 8, 16-byte aligned
+// rows, per-item byte offsets below 4 GiB.  `second`: another product of the same shape in the
+// same launch (only its A, Bm, C, scale are read).
+ap_status launch_gemm_nt(const NtGemmArgs& a, const NtGemmArgs* second) {
+  AP_REQUIRE(a.K % kBK == 0 && a.N % 8 == 0 && a.lda % 8 == 0 && a.ldb % 8 == 0 && a.M > 0 && a.N > 0,
+             AP_ERR_UNSUPPORTED, "matrix product: K %% 64, N %% 8 and 16-byte aligned rows are required");
+  AP_REQUIRE((int64_t)a.M * a.lda * 2 < (1ll << 32) && (int64_t)a.N * a.ldb * 2 < (1ll << 32), AP_ERR_UNSUPPORTED,
+             "matrix product: one operand must stay below 4 GiB");
+  return a.dt == AP_F16 ? run_gemm<F16Tag>(a, second) : run_gemm<BF16Tag>(a, second);
 }
 
 }  // namespace ap
