@@ -301,6 +301,11 @@ def main():
     ap_.add_argument("--profile-compact", action="store_true",
                      help="run only the configuration-5 prefill compaction (B=16, T=4224, HD=4096, r=512, fp16) "
                           "three times and exit without a JSON line: the workload behind profiles/compact_gemm_c5_mfma.md")
+    ap_.add_argument("--profile-bases", action="store_true",
+                     help="run only the compression step (ap_compute_bases, 2 power iterations, oversampling 32) "
+                          "twice each on configuration 5's shape (B=16, n=4224, HD=4096, r=512, fp16) and on the "
+                          "paper's image rank at the headline batch (B=64, n=4224, HD=5120, r=64, bf16) and exit "
+                          "without a JSON line: the workload behind profiles/compute_bases_kernel_trace.md")
     ap_.add_argument("--profile-next", action="store_true",
                      help="run only the rows built after the hot path, ten times each at batch 64, and exit "
                           "without a JSON line: importance tracking (decode step with logits out, moving "
@@ -327,6 +332,21 @@ def main():
         for _ in range(3):
             ap.ap_compact(x[0], x[1], bm[0], bm[1], c[0], c[1], None, None, n=t5, row0=0)
         torch.cuda.synchronize()
+        return
+    if args.profile_bases:
+        for (bb, nn, hd, rr, dt_) in ((16, 4224, 4096, 512, torch.float16), (64, 4224, 5120, 64, torch.bfloat16)):
+            x = torch.randn(bb, nn, hd, device="cuda").to(dt_)
+            om = torch.randn(rr + 32, hd, device="cuda").to(dt_)
+            bm = torch.zeros(bb, rr, hd, device="cuda", dtype=dt_)
+            wsb = torch.empty(ap.ap_bases_workspace_bytes(bb, nn, hd, rr, 32), dtype=torch.uint8, device="cuda")
+            for _ in range(2):
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                ap.ap_compute_bases(x, om, bm, wsb, power_iters=2)
+                torch.cuda.synchronize()
+                print("ap_compute_bases B=%d n=%d HD=%d r=%d: %.1f ms" % (bb, nn, hd, rr, (time.perf_counter() - t0) * 1e3),
+                      file=sys.stderr)
+            del x, om, bm, wsb
         return
     if args.profile_next:
         bf = torch.bfloat16

@@ -9,9 +9,10 @@
 //     power_iters + 1 times:   Yt = P X^T   [l, n]      matrix cores (compact_gemm.hip), 16-bit out
 //                              M  = Yt X    [l, HD]     matrix cores, fp32 out (X^T from transpose16)
 //                              P  = rows of M made orthonormal: S = M M^T in fp64 (gram_f64),
-//                                   S = L L^T (chol_linv), P = L^-1 M (gemm_nn, fp64 accumulation)
+//                                   S = L L^T (chol_update / chol_panel, panels of 32 columns),
+//                                   P = L^-1 M (tri_inverse, gemm_nn; fp64 accumulation)
 //     Rayleigh-Ritz:           Zt = P X^T [l, n] fp32,  S = Zt Zt^T [l, l]  (= P X^T X P^T)
-//                              S = J Lambda J^T by one-sided Jacobi on the rows of S (jacobi_step)
+//                              S = J Lambda J^T by one-sided Jacobi on the rows of S (jacobi_block)
 //                              D = (J^T P)[:r] in decreasing order of Lambda,  sigma = sqrt(Lambda)
 //
 // The matrices that lose information when rounded (M, whose singular values span the square of the
@@ -115,58 +116,138 @@ gram_f64(const float* __restrict__ A, int64_t a_bstride, int lda, double* __rest
     }
 }
 
-// ---- Cholesky S = L L^T in place (lower triangle of S becomes L) and X = L^-1, both fp64, one
-//      workgroup of 1024 threads per matrix (the matrix lives in L2).  A pivot that falls below
-//      1e-13 of the largest diagonal entry marks a direction the rows do not span: its row of
-//      L^-1 is zero, so the corresponding row of P = L^-1 M is zero and drops out later.
-__global__ void __launch_bounds__(1024)
-chol_linv(double* __restrict__ S, int64_t s_bstride, double* __restrict__ X, int64_t x_bstride, int l) {
-  double* L = S + (size_t)blockIdx.x * s_bstride;
-  double* Li = X + (size_t)blockIdx.x * x_bstride;
-  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-  __shared__ double s_red[16];
-  double dmax = 0.0;
-  for (int i = tid; i < l; i += 1024) dmax = fmax(dmax, L[(size_t)i * l + i]);
+// ---- Cholesky S = L L^T in place (the lower triangle of S becomes L), fp64, in panels of 32
+//      columns.  Per panel two launches:
+//   chol_update   rows c0 .. l-1 of the panel minus the contribution of the columns left of it:
+//                 S[i][c] -= sum_{j < c0} L[i][j] L[c][j]; a workgroup per 32 x 32 tile
+//   chol_panel    one workgroup per matrix: the 32 x 32 diagonal block is factored in LDS, then
+//                 every row below solves its 32 unknowns against it (a thread per row)
+//      A pivot below 1e-13 of the largest diagonal entry (dmax) marks a direction that the rows
+//      do not span: its column of L and its diagonal entry are zero, its row of L^-1 is zero,
+//      so the corresponding row of P = L^-1 M is zero and drops out later.
+__global__ void __launch_bounds__(256)
+diag_max(const double* __restrict__ S, int64_t s_bstride, int l, double* __restrict__ dmax) {
+  const double* Sb = S + (size_t)blockIdx.x * s_bstride;
+  __shared__ double red[4];
+  double m = 0.0;
+  for (int i = threadIdx.x; i < l; i += 256) m = fmax(m, Sb[(size_t)i * l + i]);
 #pragma unroll
-  for (int o = 32; o > 0; o >>= 1) dmax = fmax(dmax, __shfl_xor(dmax, o));
-  if (lane == 0) s_red[w] = dmax;
+  for (int o = 32; o > 0; o >>= 1) m = fmax(m, __shfl_xor(m, o));
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = m;
   __syncthreads();
-  dmax = s_red[0];
-  for (int i = 1; i < 16; ++i) dmax = fmax(dmax, s_red[i]);
-  const double tol = dmax * 1e-13;
-  __syncthreads();
-  for (int k = 0; k < l; ++k) {
-    // column k, rows k .. l-1 (a wave per row): S[i][k] - sum_{j<k} L[i][j] L[k][j]
-    const double* rowk = L + (size_t)k * l;
-    for (int i = k + w; i < l; i += 16) {
-      const double* rowi = L + (size_t)i * l;
-      double acc = 0.0;
-      for (int j = lane; j < k; j += 64) acc = fma(rowi[j], rowk[j], acc);
-      acc = wave_sum_d(acc);
-      if (lane == 0) L[(size_t)i * l + k] = rowi[k] - acc;
+  if (threadIdx.x == 0) dmax[blockIdx.x] = fmax(fmax(red[0], red[1]), fmax(red[2], red[3]));
+}
+
+// grid (ceil((l - c0) / 32), batch), 256 threads = 16 x 16, 2 x 2 results each
+__global__ void __launch_bounds__(256)
+chol_update(double* __restrict__ S, int64_t s_bstride, int l, int c0) {
+  __shared__ double As[32][33], Bs[32][33];
+  double* L = S + (size_t)blockIdx.y * s_bstride;
+  const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
+  const int i0 = c0 + blockIdx.x * 32;
+  double acc[2][2] = {{0.0, 0.0}, {0.0, 0.0}};
+  for (int k0 = 0; k0 < c0; k0 += 32) {              // c0 is a multiple of 32
+    for (int e = tid; e < 1024; e += 256) {
+      const int rr = e >> 5, kk = e & 31;
+      As[rr][kk] = i0 + rr < l ? L[(size_t)(i0 + rr) * l + k0 + kk] : 0.0;
+      Bs[rr][kk] = c0 + rr < l ? L[(size_t)(c0 + rr) * l + k0 + kk] : 0.0;
     }
     __syncthreads();
-    const double piv = L[(size_t)k * l + k];
-    const bool dead = !(piv > tol);
-    const double inv = dead ? 0.0 : 1.0 / sqrt(piv);
-    __syncthreads();                     // everybody has read the pivot
-    for (int i = k + 1 + tid; i < l; i += 1024) L[(size_t)i * l + k] *= inv;
-    if (tid == 0) L[(size_t)k * l + k] = dead ? 0.0 : sqrt(piv);
+#pragma unroll 8
+    for (int kk = 0; kk < 32; ++kk) {
+      const double a0 = As[2 * ty][kk], a1 = As[2 * ty + 1][kk];
+      const double b0 = Bs[2 * tx][kk], b1 = Bs[2 * tx + 1][kk];
+      acc[0][0] = fma(a0, b0, acc[0][0]);
+      acc[0][1] = fma(a0, b1, acc[0][1]);
+      acc[1][0] = fma(a1, b0, acc[1][0]);
+      acc[1][1] = fma(a1, b1, acc[1][1]);
+    }
     __syncthreads();
   }
-  // X = L^-1, a thread per column j (forward substitution; rows of a dead pivot stay zero)
-  for (int j = tid; j < l; j += 1024) {
-    for (int i = 0; i < l; ++i) {
-      const double dii = L[(size_t)i * l + i];
-      double acc = i == j ? 1.0 : 0.0;
-      if (i > j) {
-        const double* rowi = L + (size_t)i * l;
-        double s = 0.0;
-        for (int k = j; k < i; ++k) s = fma(rowi[k], Li[(size_t)k * l + j], s);
-        acc = -s;
-      }
-      Li[(size_t)i * l + j] = (i < j || dii == 0.0) ? 0.0 : acc / dii;
+#pragma unroll
+  for (int u = 0; u < 2; ++u)
+#pragma unroll
+    for (int v = 0; v < 2; ++v) {
+      const int i = i0 + 2 * ty + u, c = c0 + 2 * tx + v;
+      if (i < l && c < l) L[(size_t)i * l + c] -= acc[u][v];
     }
+}
+
+// grid (batch), 256 threads
+__global__ void __launch_bounds__(256)
+chol_panel(double* __restrict__ S, int64_t s_bstride, int l, int c0, const double* __restrict__ dmax) {
+  __shared__ double Dg[32][33];
+  double* L = S + (size_t)blockIdx.x * s_bstride;
+  const int tid = threadIdx.x;
+  const int nb = l - c0 < 32 ? l - c0 : 32;
+  const double tol = dmax[blockIdx.x] * 1e-13;
+  for (int e = tid; e < 1024; e += 256) {
+    const int rr = e >> 5, cc = e & 31;
+    Dg[rr][cc] = (rr < nb && cc < nb && cc <= rr) ? L[(size_t)(c0 + rr) * l + c0 + cc] : 0.0;
+  }
+  __syncthreads();
+  // unblocked Cholesky of the diagonal block (right-looking, 32 short steps)
+  for (int k = 0; k < nb; ++k) {
+    const double piv = Dg[k][k];
+    const bool dead = !(piv > tol);
+    const double d = dead ? 0.0 : sqrt(piv), inv = dead ? 0.0 : 1.0 / d;
+    __syncthreads();
+    if (tid == 0) Dg[k][k] = d;
+    if (tid > k && tid < nb) Dg[tid][k] *= inv;
+    __syncthreads();
+    for (int e = tid; e < 1024; e += 256) {
+      const int i = e >> 5, j = e & 31;
+      if (i > k && j > k && j <= i && i < nb) Dg[i][j] -= Dg[i][k] * Dg[j][k];
+    }
+    __syncthreads();
+  }
+  for (int e = tid; e < 1024; e += 256) {
+    const int rr = e >> 5, cc = e & 31;
+    if (rr < nb && cc < nb) L[(size_t)(c0 + rr) * l + c0 + cc] = cc <= rr ? Dg[rr][cc] : 0.0;
+  }
+  // rows below the block: x Dg^T = t, forward substitution, a thread per row
+  for (int i = c0 + 32 + tid; i < l; i += 256) {
+    double* row = L + (size_t)i * l + c0;
+    double x[32];
+#pragma unroll
+    for (int c = 0; c < 32; ++c) x[c] = row[c];
+#pragma unroll
+    for (int c = 0; c < 32; ++c) {
+      double v = x[c];
+#pragma unroll
+      for (int j = 0; j < 32; ++j)
+        if (j < c) v = fma(-x[j], Dg[c][j], v);
+      const double d = Dg[c][c];
+      x[c] = d == 0.0 ? 0.0 : v / d;
+    }
+#pragma unroll
+    for (int c = 0; c < 32; ++c) row[c] = x[c];
+  }
+}
+
+// X = L^-1 (lower triangular, fp64), a thread per column j by forward substitution; rows of a
+// dead pivot stay zero.  grid (ceil(l / 64), batch), 64 threads.
+__global__ void __launch_bounds__(64)
+tri_inverse(const double* __restrict__ S, int64_t s_bstride, double* __restrict__ X, int64_t x_bstride, int l) {
+  const double* L = S + (size_t)blockIdx.y * s_bstride;
+  double* Li = X + (size_t)blockIdx.y * x_bstride;
+  const int j = blockIdx.x * 64 + threadIdx.x;
+  if (j >= l) return;
+  for (int i = 0; i < l; ++i) {
+    const double dii = L[(size_t)i * l + i];
+    double acc = i == j ? 1.0 : 0.0;
+    if (i > j) {
+      const double* rowi = L + (size_t)i * l;
+      double s0 = 0.0, s1 = 0.0;
+      int k;
+      for (k = j; k + 1 < i; k += 2) {
+        s0 = fma(rowi[k], Li[(size_t)k * l + j], s0);
+        s1 = fma(rowi[k + 1], Li[(size_t)(k + 1) * l + j], s1);
+      }
+      if (k < i) s0 = fma(rowi[k], Li[(size_t)k * l + j], s0);
+      acc = -(s0 + s1);
+    }
+    Li[(size_t)i * l + j] = (i < j || dii == 0.0) ? 0.0 : acc / dii;
   }
 }
 
@@ -233,57 +314,78 @@ __global__ void to_f32(const double* __restrict__ in, float* __restrict__ out, s
   if (i < n) out[i] = (float)in[i];
 }
 
-// ---- One step of a one-sided Jacobi sweep on the rows of W [l][l] (fp32): l / 2 disjoint row pairs
-//      (round-robin schedule), each rotated in its plane so that the two rows become orthogonal.
-//      For a symmetric positive semi-definite W = S the rows converge to lambda_i j_i^T, the
-//      eigenvectors scaled by their eigenvalues.  state[b]: [0] rotations in this sweep, [1] done.
-//      grid (l / 2, batch), 256 threads; l <= 1024.
-__global__ void __launch_bounds__(256)
-jacobi_step(float* __restrict__ W, int64_t w_bstride, int l, int step, float tol, int* __restrict__ state) {
+// ---- One-sided Jacobi on the rows of W [l][l] (fp32), block version.  The rows are cut into blocks
+//      of BS; one launch takes disjoint pairs of blocks (round-robin over the blocks), a workgroup
+//      per pair: its 2 BS rows come into LDS, one cyclic sweep over all their row pairs runs there
+//      (2 BS - 1 steps of BS disjoint pairs, each rotated in its plane so that the two rows become
+//      orthogonal), and the rows go back.  For a symmetric positive semi-definite W = S the rows
+//      converge to lambda_i j_i^T, the eigenvectors scaled by their eigenvalues.
+//      state[b]: [0] rotations in this sweep, [1] done.  grid (pairs, batch), 1024 threads.
+template <int BS>
+__global__ void __launch_bounds__(1024)
+jacobi_block(float* __restrict__ W, int64_t w_bstride, int l, int nblk, int step, float tol, int* __restrict__ state) {
+  extern __shared__ float rows_lds[];                   // [2 BS][l + 1]
+  constexpr int TPP = 1024 / BS;                        // threads per row pair (32 or 64: within one wave)
   const int b = blockIdx.y, tid = threadIdx.x;
   if (state[2 * b + 1]) return;
-  const int k = blockIdx.x, nm1 = l - 1;
-  int ia, ib;
-  if (k == 0) { ia = nm1; ib = step; }
-  else { ia = (step + k) % nm1; ib = (step + nm1 - k) % nm1; }
-  float* ra = W + (size_t)b * w_bstride + (size_t)ia * l;
-  float* rb = W + (size_t)b * w_bstride + (size_t)ib * l;
-  float x[4], y[4];
-  float al = 0.f, be = 0.f, ga = 0.f;
-#pragma unroll
-  for (int e = 0; e < 4; ++e) {
-    const int c = tid + 256 * e;
-    x[e] = c < l ? ra[c] : 0.f;
-    y[e] = c < l ? rb[c] : 0.f;
-    al = fmaf(x[e], x[e], al);
-    be = fmaf(y[e], y[e], be);
-    ga = fmaf(x[e], y[e], ga);
+  // round-robin over nblk blocks (nblk even; a block index >= the real count is an empty block)
+  const int k = blockIdx.x, nm1 = nblk - 1;
+  int ba, bb;
+  if (k == 0) { ba = nm1; bb = step; }
+  else { ba = (step + k) % nm1; bb = (step + nm1 - k) % nm1; }
+  const int pitch = l + 1;
+  float* Wb = W + (size_t)b * w_bstride;
+  const int nreal = (l + BS - 1) / BS;
+  if (ba >= nreal && bb >= nreal) return;
+  for (int e = tid; e < 2 * BS * l; e += 1024) {
+    const int rr = e / l, c = e - rr * l;
+    const int gr = (rr < BS ? ba * BS + rr : bb * BS + rr - BS);
+    const bool real = (rr < BS ? ba : bb) < nreal && gr < l;
+    rows_lds[rr * pitch + c] = real ? Wb[(size_t)gr * l + c] : 0.f;
   }
-  __shared__ float red[3][4];
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) {
-    al += __shfl_xor(al, o);
-    be += __shfl_xor(be, o);
-    ga += __shfl_xor(ga, o);
-  }
-  if ((tid & 63) == 0) { red[0][tid >> 6] = al; red[1][tid >> 6] = be; red[2][tid >> 6] = ga; }
   __syncthreads();
-  al = red[0][0] + red[0][1] + red[0][2] + red[0][3];
-  be = red[1][0] + red[1][1] + red[1][2] + red[1][3];
-  ga = red[2][0] + red[2][1] + red[2][2] + red[2][3];
-  if (!(fabsf(ga) > tol * sqrtf(al * be))) return;       // already orthogonal (or a zero row)
-  const float zeta = (be - al) / (2.f * ga);
-  const float t = (zeta >= 0.f ? 1.f : -1.f) / (fabsf(zeta) + sqrtf(1.f + zeta * zeta));
-  const float c = 1.f / sqrtf(1.f + t * t), s = c * t;
-#pragma unroll
-  for (int e = 0; e < 4; ++e) {
-    const int col = tid + 256 * e;
-    if (col < l) {
-      ra[col] = c * x[e] - s * y[e];
-      rb[col] = s * x[e] + c * y[e];
+  const int pr = tid / TPP, sub = tid - pr * TPP;
+  int nrot = 0;
+  constexpr int N2 = 2 * BS;
+  for (int s2 = 0; s2 < N2 - 1; ++s2) {
+    int ia, ib;
+    if (pr == 0) { ia = N2 - 1; ib = s2; }
+    else { ia = (s2 + pr) % (N2 - 1); ib = (s2 + N2 - 1 - pr) % (N2 - 1); }
+    float* ra = rows_lds + ia * pitch;
+    float* rb = rows_lds + ib * pitch;
+    float al = 0.f, be = 0.f, ga = 0.f;
+    for (int c = sub; c < l; c += TPP) {
+      const float x = ra[c], y = rb[c];
+      al = fmaf(x, x, al);
+      be = fmaf(y, y, be);
+      ga = fmaf(x, y, ga);
     }
+#pragma unroll
+    for (int o = TPP / 2; o > 0; o >>= 1) {
+      al += __shfl_xor(al, o);
+      be += __shfl_xor(be, o);
+      ga += __shfl_xor(ga, o);
+    }
+    if (fabsf(ga) > tol * sqrtf(al * be)) {               // the same decision in all lanes of the pair
+      const float zeta = (be - al) / (2.f * ga);
+      const float t = (zeta >= 0.f ? 1.f : -1.f) / (fabsf(zeta) + sqrtf(1.f + zeta * zeta));
+      const float cs = 1.f / sqrtf(1.f + t * t), sn = cs * t;
+      for (int c = sub; c < l; c += TPP) {
+        const float x = ra[c], y = rb[c];
+        ra[c] = cs * x - sn * y;
+        rb[c] = sn * x + cs * y;
+      }
+      if (sub == 0) ++nrot;
+    }
+    __syncthreads();
   }
-  if (tid == 0) atomicAdd(&state[2 * b], 1);
+  for (int e = tid; e < 2 * BS * l; e += 1024) {
+    const int rr = e / l, c = e - rr * l;
+    const int gr = (rr < BS ? ba * BS + rr : bb * BS + rr - BS);
+    const bool real = (rr < BS ? ba : bb) < nreal && gr < l;
+    if (real) Wb[(size_t)gr * l + c] = rows_lds[rr * pitch + c];
+  }
+  if (nrot) atomicAdd(&state[2 * b], nrot);
 }
 
 // after a sweep: a matrix without a rotation is done
@@ -334,7 +436,7 @@ eig_select(const float* __restrict__ W, int64_t w_bstride, int l, int r, double*
 constexpr int kJacobiSweeps = 14;
 
 struct BasesLayout {
-  size_t xt, yt, m32, p16, p32, zt, s64, linv, w32, rsel, state, total;
+  size_t xt, yt, m32, p16, p32, zt, s64, linv, w32, rsel, state, dmax, total;
   int n_pad;
 };
 BasesLayout bases_layout(int B, int n, int HD, int l, int r) {
@@ -353,6 +455,7 @@ BasesLayout bases_layout(int B, int n, int HD, int l, int r) {
   w.w32 = take((size_t)B * l * l * 4);
   w.rsel = take((size_t)B * r * l * 8);
   w.state = take((size_t)B * 2 * 4);
+  w.dmax = take((size_t)B * 8);
   w.total = off;
   return w;
 }
@@ -381,6 +484,7 @@ ap_status run_bases(const BasesArgs& a) {
   float* W = (float*)(ws + w.w32);
   double* Rsel = (double*)(ws + w.rsel);
   int* state = (int*)(ws + w.state);
+  double* dmax = (double*)(ws + w.dmax);
   hipStream_t st = a.stream;
   const int np = w.n_pad;
   const ap_dtype dt = a.dt;
@@ -401,7 +505,13 @@ ap_status run_bases(const BasesArgs& a) {
     // rows of M made orthonormal
     hipLaunchKernelGGL(gram_f64, dim3((l + 31) / 32, (l + 31) / 32, B), dim3(256), 0, st, M32, (int64_t)l * HD, HD, S,
                        (int64_t)l * l, l, HD);
-    hipLaunchKernelGGL(chol_linv, dim3(B), dim3(1024), 0, st, S, (int64_t)l * l, Linv, (int64_t)l * l, l);
+    hipLaunchKernelGGL(diag_max, dim3(B), dim3(256), 0, st, S, (int64_t)l * l, l, dmax);
+    for (int c0 = 0; c0 < l; c0 += 32) {
+      if (c0 > 0)
+        hipLaunchKernelGGL(chol_update, dim3((l - c0 + 31) / 32, B), dim3(256), 0, st, S, (int64_t)l * l, l, c0);
+      hipLaunchKernelGGL(chol_panel, dim3(B), dim3(256), 0, st, S, (int64_t)l * l, l, c0, dmax);
+    }
+    hipLaunchKernelGGL(tri_inverse, dim3((l + 63) / 64, B), dim3(64), 0, st, S, (int64_t)l * l, Linv, (int64_t)l * l, l);
     launch_gemm_nn<Tag>(Linv, (int64_t)l * l, l, M32, (int64_t)l * HD, HD, P32, (int64_t)l * HD, P16, (int64_t)l * HD,
                         HD, l, HD, l, 1, B, st);
     Pcur = P16;
@@ -415,10 +525,32 @@ ap_status run_bases(const BasesArgs& a) {
   const size_t nel = (size_t)B * l * l;
   hipLaunchKernelGGL(to_f32, dim3((unsigned)((nel + 255) / 256)), dim3(256), 0, st, S, W, nel);
   hipLaunchKernelGGL(jacobi_reset, dim3((B + 63) / 64), dim3(64), 0, st, state, B);
-  for (int sweep = 0; sweep < kJacobiSweeps; ++sweep) {
-    for (int step = 0; step < l - 1; ++step)
-      hipLaunchKernelGGL(jacobi_step, dim3(l / 2, B), dim3(256), 0, st, W, (int64_t)l * l, l, step, 2e-6f, state);
-    hipLaunchKernelGGL(jacobi_sweep_end, dim3((B + 63) / 64), dim3(64), 0, st, state, B);
+  {
+    // blocks of 32 rows while two of them fit the LDS next to each other, else 16
+    const bool big = (size_t)64 * (l + 1) * 4 <= 150 * 1024;
+    const int bs = big ? 32 : 16;
+    int nblk = (l + bs - 1) / bs;
+    nblk += nblk & 1;                                    // an even number of blocks (the last may be empty)
+    const size_t lds = (size_t)2 * bs * (l + 1) * 4;
+    static bool attr_set = false;
+    if (!attr_set) {
+      hipError_t e1 = hipFuncSetAttribute((const void*)jacobi_block<32>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+      hipError_t e2 = hipFuncSetAttribute((const void*)jacobi_block<16>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+      if (e1 != hipSuccess || e2 != hipSuccess) {
+        set_error("hipFuncSetAttribute: %s", hipGetErrorString(e1 != hipSuccess ? e1 : e2));
+        return AP_ERR_HIP;
+      }
+      attr_set = true;
+    }
+    for (int sweep = 0; sweep < kJacobiSweeps; ++sweep) {
+      for (int step = 0; step < nblk - 1; ++step) {
+        if (big)
+          hipLaunchKernelGGL(jacobi_block<32>, dim3(nblk / 2, B), dim3(1024), lds, st, W, (int64_t)l * l, l, nblk, step, 2e-6f, state);
+        else
+          hipLaunchKernelGGL(jacobi_block<16>, dim3(nblk / 2, B), dim3(1024), lds, st, W, (int64_t)l * l, l, nblk, step, 2e-6f, state);
+      }
+      hipLaunchKernelGGL(jacobi_sweep_end, dim3((B + 63) / 64), dim3(64), 0, st, state, B);
+    }
   }
   hipLaunchKernelGGL(eig_select, dim3(B), dim3(1024), 0, st, W, (int64_t)l * l, l, r, Rsel, (int64_t)r * l, a.sigma,
                      (int64_t)r);
