@@ -264,7 +264,16 @@ def other_configs(torch, ap):
                      "timed": "events around 8 calls of one launch each (keys and values in one grid)"},
         "library_bmm_same_shape_TFLOPs": flops / us_lib / 1e6,
         "library_matmul_8192_cubed_TFLOPs": 2.0 * 8192 ** 3 / us_sq / 1e6}
-    del kx, vx, c16k, c16v
+    # the compression step itself: bases of the keys by randomized SVD on the GPU (oversampling 32,
+    # two power iterations), then the projection above gives the coefficients
+    om5 = torch.randn(r5 + 32, hd2, device="cuda").to(f16)
+    bm5 = torch.empty(b5, r5, hd2, device="cuda", dtype=f16)
+    wsb5 = torch.empty(ap.ap_bases_workspace_bytes(b5, t5, hd2, r5, 32), dtype=torch.uint8, device="cuda")
+    us_bases = _time_us(torch, lambda: ap.ap_compute_bases(kx, om5, bm5, wsb5, power_iters=2), 2, warm=1)
+    res["config5_compaction"]["compute_bases_ms_keys_or_values"] = us_bases / 1e3
+    res["config5_compaction"]["compute_bases_note"] = ("ap_compute_bases on B=16 x [4224, 4096] -> r=512, l=544, 2 power "
+                                                       "iterations; keys and values need one call each")
+    del kx, vx, c16k, c16v, om5, bm5, wsb5
     q5 = torch.randn(b5, h2, D, device="cuda").to(f16)
     out5 = torch.empty(b5, h2, D, device="cuda")
     ws5 = torch.empty(ap.ap_decode_workspace_bytes(b5, h2, D, t5, r5, ap.AP_F16), dtype=torch.uint8, device="cuda")

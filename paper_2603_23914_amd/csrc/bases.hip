@@ -225,29 +225,33 @@ chol_panel(double* __restrict__ S, int64_t s_bstride, int l, int c0, const doubl
   }
 }
 
-// X = L^-1 (lower triangular, fp64), a thread per column j by forward substitution; rows of a
-// dead pivot stay zero.  grid (ceil(l / 64), batch), 64 threads.
-__global__ void __launch_bounds__(64)
+// X = L^-1 (lower triangular, fp64) by forward substitution, a wave per column j: the column's
+// entries found so far sit in LDS, row i's dot product with them is spread over the lanes.  Rows
+// of a dead pivot stay zero.  grid (ceil(l / 4), batch), 256 threads; dynamic LDS 4 * l doubles.
+__global__ void __launch_bounds__(256)
 tri_inverse(const double* __restrict__ S, int64_t s_bstride, double* __restrict__ X, int64_t x_bstride, int l) {
+  extern __shared__ double xcol[];                      // [4][l]
   const double* L = S + (size_t)blockIdx.y * s_bstride;
   double* Li = X + (size_t)blockIdx.y * x_bstride;
-  const int j = blockIdx.x * 64 + threadIdx.x;
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int j = blockIdx.x * 4 + w;
   if (j >= l) return;
-  for (int i = 0; i < l; ++i) {
-    const double dii = L[(size_t)i * l + i];
-    double acc = i == j ? 1.0 : 0.0;
-    if (i > j) {
-      const double* rowi = L + (size_t)i * l;
-      double s0 = 0.0, s1 = 0.0;
-      int k;
-      for (k = j; k + 1 < i; k += 2) {
-        s0 = fma(rowi[k], Li[(size_t)k * l + j], s0);
-        s1 = fma(rowi[k + 1], Li[(size_t)(k + 1) * l + j], s1);
-      }
-      if (k < i) s0 = fma(rowi[k], Li[(size_t)k * l + j], s0);
-      acc = -(s0 + s1);
+  double* x = xcol + (size_t)w * l;
+  for (int i = lane; i < j; i += 64) Li[(size_t)i * l + j] = 0.0;     // above the diagonal
+  for (int i = j; i < l; ++i) {
+    const double* rowi = L + (size_t)i * l;
+    double s = 0.0;
+    for (int k = j + lane; k < i; k += 64) s = fma(rowi[k], x[k], s);
+    s = wave_sum_d(s);
+    const double dii = rowi[i];
+    const double v = dii == 0.0 ? 0.0 : ((i == j ? 1.0 : 0.0) - s) / dii;
+    if (lane == 0) {
+      x[i] = v;
+      Li[(size_t)i * l + j] = v;
     }
-    Li[(size_t)i * l + j] = (i < j || dii == 0.0) ? 0.0 : acc / dii;
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
   }
 }
 
@@ -433,7 +437,8 @@ eig_select(const float* __restrict__ W, int64_t w_bstride, int l, int r, double*
   }
 }
 
-constexpr int kJacobiSweeps = 14;
+constexpr int kJacobiSweeps = 12;      // at most; a matrix without a rotation in a sweep is done
+constexpr float kJacobiTol = 1e-5f;    // |a.b| <= tol |a||b|: far below what 16-bit storage of the result keeps
 
 struct BasesLayout {
   size_t xt, yt, m32, p16, p32, zt, s64, linv, w32, rsel, state, dmax, total;
@@ -511,7 +516,7 @@ ap_status run_bases(const BasesArgs& a) {
         hipLaunchKernelGGL(chol_update, dim3((l - c0 + 31) / 32, B), dim3(256), 0, st, S, (int64_t)l * l, l, c0);
       hipLaunchKernelGGL(chol_panel, dim3(B), dim3(256), 0, st, S, (int64_t)l * l, l, c0, dmax);
     }
-    hipLaunchKernelGGL(tri_inverse, dim3((l + 63) / 64, B), dim3(64), 0, st, S, (int64_t)l * l, Linv, (int64_t)l * l, l);
+    hipLaunchKernelGGL(tri_inverse, dim3((l + 3) / 4, B), dim3(256), (size_t)4 * l * 8, st, S, (int64_t)l * l, Linv, (int64_t)l * l, l);
     launch_gemm_nn<Tag>(Linv, (int64_t)l * l, l, M32, (int64_t)l * HD, HD, P32, (int64_t)l * HD, P16, (int64_t)l * HD,
                         HD, l, HD, l, 1, B, st);
     Pcur = P16;
@@ -545,9 +550,9 @@ ap_status run_bases(const BasesArgs& a) {
     for (int sweep = 0; sweep < kJacobiSweeps; ++sweep) {
       for (int step = 0; step < nblk - 1; ++step) {
         if (big)
-          hipLaunchKernelGGL(jacobi_block<32>, dim3(nblk / 2, B), dim3(1024), lds, st, W, (int64_t)l * l, l, nblk, step, 2e-6f, state);
+          hipLaunchKernelGGL(jacobi_block<32>, dim3(nblk / 2, B), dim3(1024), lds, st, W, (int64_t)l * l, l, nblk, step, kJacobiTol, state);
         else
-          hipLaunchKernelGGL(jacobi_block<16>, dim3(nblk / 2, B), dim3(1024), lds, st, W, (int64_t)l * l, l, nblk, step, 2e-6f, state);
+          hipLaunchKernelGGL(jacobi_block<16>, dim3(nblk / 2, B), dim3(1024), lds, st, W, (int64_t)l * l, l, nblk, step, kJacobiTol, state);
       }
       hipLaunchKernelGGL(jacobi_sweep_end, dim3((B + 63) / 64), dim3(64), 0, st, state, B);
     }
