@@ -21,6 +21,9 @@ from .attnpack_oracle import (  # noqa: F401
     select_ranks,
     quantize_i8,
     dequantize_i8,
+    quantize_i4,
+    unpack_i4,
+    dequantize_i4,
     compression_ratio,
     decompression_flops,
     cache_bytes,

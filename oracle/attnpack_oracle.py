@@ -455,6 +455,57 @@ def dequantize_i8(codes: np.ndarray, scales: np.ndarray, block: int = 64) -> np.
 
 
 # --------------------------------------------------------------------------
+# 4-bit coefficients (Sec. 4.5 and Table 4 combine the method with 4-bit
+# quantisation "following KVQuant"; that scheme's non-uniform, calibrated code
+# book needs data that is not available, so the reading taken here is the plain
+# uniform one, with the block structure of the int8 format)
+# --------------------------------------------------------------------------
+
+def quantize_i4(C: np.ndarray, block: int = 64) -> Tuple[np.ndarray, np.ndarray]:
+    """Per-token, per-`block`-column symmetric 4-bit codes with an fp16 scale.
+
+    amax = max|c| over the block;  scale = fp16(fp32(amax) / 7f);  scale == 0 ->
+    all codes 0;  code = clamp(rint(fp32(c) / fp32(scale)), -7, 7), IEEE
+    division, round-half-to-even.  Two codes per byte: byte i of a row holds
+    column 2i in its low nibble and column 2i+1 in its high nibble, each nibble
+    the code plus 8 (1 .. 15).
+
+    C [T, r] float16 (or float32), r % block == 0.
+    Returns (packed [T, r/2] uint8, scales [T, r/block] float16).
+    """
+    C = np.asarray(C)
+    T, r = C.shape
+    assert r % block == 0 and block % 2 == 0
+    c32 = C.astype(np.float32).reshape(T, r // block, block)
+    amax = np.abs(c32).max(axis=2)
+    scale16 = (amax / np.float32(7.0)).astype(np.float16)
+    s32 = scale16.astype(np.float32)
+    safe = np.where(s32 == 0, np.float32(1.0), s32)
+    code = np.clip(np.rint(c32 / safe[:, :, None]), -7.0, 7.0)
+    code = np.where((s32 == 0)[:, :, None], 0.0, code).astype(np.int32).reshape(T, r)
+    u = (code + 8).astype(np.uint8)
+    packed = (u[:, 0::2] | (u[:, 1::2] << 4)).astype(np.uint8)
+    return packed, scale16
+
+
+def unpack_i4(packed: np.ndarray) -> np.ndarray:
+    """packed [T, r/2] uint8 -> integer codes [T, r] in -7 .. 7 (int32)."""
+    packed = np.asarray(packed, np.uint8)
+    T, half = packed.shape
+    codes = np.empty((T, 2 * half), np.int32)
+    codes[:, 0::2] = (packed & 0x0F).astype(np.int32) - 8
+    codes[:, 1::2] = (packed >> 4).astype(np.int32) - 8
+    return codes
+
+
+def dequantize_i4(packed: np.ndarray, scales: np.ndarray, block: int = 64) -> np.ndarray:
+    """packed [T, r/2] uint8, scales [T, r/block] fp16 -> float64 values code*scale."""
+    codes = unpack_i4(packed)
+    s = np.repeat(scales.astype(np.float64), block, axis=1)
+    return codes.astype(np.float64) * s
+
+
+# --------------------------------------------------------------------------
 # closed-form accounting used in the paper's text and tables
 # --------------------------------------------------------------------------
 
@@ -470,7 +521,7 @@ def decompression_flops(T: int, HD: int, fractions: Sequence[float],
 
 
 def cache_bytes(L: int, HD: int, T_v: int, T_t: int, R_k: Optional[int],
-                R_v: Optional[int], bytes_per_elt: int = 2) -> float:
+                R_v: Optional[int], bytes_per_elt: float = 2) -> float:
     """Whole-model KV cache of one sample: visual tokens compressed to rank
     R_k / R_v (None = uncompressed), textual tokens kept uncompressed
     (experiment setup).  Per layer and per matrix: T_v*R + R*HD (Sec. 3.1)."""

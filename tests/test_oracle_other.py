@@ -170,6 +170,67 @@ def test_quantize_i8_properties():
     assert deq[3, 70] == float(codes[3, 70]) * float(scales[3, 1])
 
 
+def exact_codes4(block):
+    """4-bit recipe in exact rational arithmetic, except where it fixes binary32 / binary16."""
+    vals = [Fraction(float(x)) for x in block]
+    amax = max(abs(v) for v in vals)
+    scale = np.float16(np.float32(float(amax)) / np.float32(7.0))
+    if float(scale) == 0.0:
+        return [0] * len(block), 0.0
+    codes = []
+    for x in block:
+        quo = Fraction(float(np.float32(np.float32(x) / np.float32(scale))))     # the fp32 quotient, exactly
+        fl = quo.numerator // quo.denominator
+        frac = quo - fl
+        near = fl if frac < Fraction(1, 2) else fl + 1
+        if frac == Fraction(1, 2):
+            near = fl if fl % 2 == 0 else fl + 1
+        codes.append(max(-7, min(7, near)))
+    return codes, float(scale)
+
+
+def test_quantize_i4_exact_small_and_packing():
+    rng = np.random.default_rng(2)
+    C = (rng.standard_normal((4, 128)) * np.array([10.0, 1.0, 1e-3, 50.0])[:, None]).astype(np.float16)
+    C[1, 64:] = 0                                  # an all-zero block
+    C[0, :8] = np.array([3.5, -3.5, 7, -7, 0.5, -0.5, 1.5, 2.5], np.float16)   # ties at scale 1 (amax 7)
+    C[0, 8:64] = np.clip(C[0, 8:64], -7, 7)
+    packed, scales = oracle.quantize_i4(C)
+    assert packed.dtype == np.uint8 and packed.shape == (4, 64) and scales.shape == (4, 2)
+    codes = oracle.unpack_i4(packed)
+    for t in range(4):
+        for blk in range(2):
+            ref, sc = exact_codes4(C[t, blk * 64:(blk + 1) * 64])
+            assert codes[t, blk * 64:(blk + 1) * 64].tolist() == ref
+            assert float(scales[t, blk]) == sc
+    # half-to-even at scale exactly 1: 3.5 -> 4, -3.5 -> -4, 0.5 -> 0, 1.5 -> 2, 2.5 -> 2
+    assert float(scales[0, 0]) == 1.0 and codes[0, :8].tolist() == [4, -4, 7, -7, 0, 0, 2, 2]
+    # layout: byte i = (column 2i + 8) | (column 2i+1 + 8) << 4, written out by hand
+    assert packed[0, 0] == (4 + 8) | ((-4 + 8) << 4) and packed[0, 1] == (7 + 8) | ((-7 + 8) << 4)
+    assert (packed[1, 32:] == 0x88).all() and scales[1, 1] == 0 and (codes[1, 64:] == 0).all()
+    assert np.abs(codes).max() <= 7 and packed.min() >= 0x11
+
+
+def test_quantize_i4_properties():
+    rng = np.random.default_rng(3)
+    C = (rng.standard_normal((32, 256)) * rng.uniform(0.01, 40, size=(32, 1))).astype(np.float16)
+    packed, scales = oracle.quantize_i4(C)
+    deq = oracle.dequantize_i4(packed, scales)
+    s = np.repeat(scales.astype(np.float64), 64, axis=1)
+    inside = np.abs(C.astype(np.float64) / s) <= 7.0
+    assert (np.abs(C.astype(np.float64) - deq)[inside] <= 0.5 * s[inside] * (1 + 1e-6)).all()
+    codes = oracle.unpack_i4(packed)
+    blk = np.abs(C.astype(np.float64)).reshape(32, 4, 64)
+    am = np.take_along_axis(np.abs(codes).reshape(32, 4, 64), blk.argmax(axis=2)[..., None], axis=2)
+    assert (am == 7).all()                          # amax/7 rounded to fp16 keeps the largest element at +-7
+    assert deq[3, 70] == float(codes[3, 70]) * float(scales[3, 1])
+    # 4 bits carry less than 8: the error is about 127 / 7 times the int8 one
+    c8, s8 = oracle.quantize_i8(C)
+    e8 = np.abs(oracle.dequantize_i8(c8, s8) - C.astype(np.float64)).mean()
+    e4 = np.abs(deq - C.astype(np.float64)).mean()
+    assert 10 < e4 / e8 < 30
+
+
 # ------------------------------------------------------ the paper's own numbers
 
 def test_paper_closed_forms(paper_values):
@@ -192,6 +253,7 @@ def test_paper_closed_forms(paper_values):
     f7 = oracle.cache_bytes(L, HD, Tv, Tt, None, None)
     check("llava7b_full_MB", f7 / 1e6)
     check("llava7b_R64_MB", oracle.cache_bytes(L, HD, Tv, Tt, 64, 64) / 1e6)
+    check("llava7b_R64_4bit_MB", oracle.cache_bytes(L, HD, Tv, Tt, 64, 64, bytes_per_elt=0.5) / 1e6)
     for R in (128, 64, 32, 16):
         check(f"llava7b_R{R}_reduction", f7 / oracle.cache_bytes(L, HD, Tv, Tt, R, R))
     check("llava7b_Rk64_Rv128_reduction", f7 / oracle.cache_bytes(L, HD, Tv, Tt, 64, 128))
