@@ -289,6 +289,22 @@ def other_configs(torch, ap):
                                          "fp16 bases, attend only",
                              "us_per_step_eager": eager, "us_per_step_graph": graph, "tokens_per_s": b5 / min(eager, graph) * 1e6,
                              "algorithmic_bytes_per_step": byt, "effective_GBps": byt / min(eager, graph) / 1e3}
+    # the same step over 4-bit coefficients (two codes per byte, the same scale blocks)
+    c16 = coeffs(b5, t5, r5, hd2, f16)
+    c4k = torch.empty(b5, t5, r5 // 2, device="cuda", dtype=torch.uint8)
+    c4v = torch.empty_like(c4k)
+    ap.ap_quantize_i4(c16, c4k, sk, T=t5)
+    ap.ap_quantize_i4(c16, c4v, sv, T=t5)
+    us_q4 = _time_us(torch, lambda: ap.ap_quantize_i4(c16, c4k, sk, T=t5), 8, warm=2)
+
+    def c5_step4():
+        ap.ap_decode_attn(q5, c4k, c4v, bk, bv, out5, ws5, T=t5, sm_scale=sc, scale_k=sk, scale_v=sv)
+
+    eager4 = _time_us(torch, c5_step4, 64)
+    byt4 = 2.0 * b5 * t5 * (r5 // 2 + (r5 // 64) * 2) + 2.0 * b5 * r5 * hd2 * 2
+    res["config5_decode_4bit"] = {"workload": "as config5_decode with 4-bit coefficients", "us_per_step_eager": eager4,
+                                  "tokens_per_s": b5 / eager4 * 1e6, "algorithmic_bytes_per_step": byt4,
+                                  "effective_GBps": byt4 / eager4 / 1e3, "us_to_quantize_one_cache": us_q4}
     assert torch.isfinite(out5).all() and torch.isfinite(out4).all() and torch.isfinite(out2).all()
     return res
 

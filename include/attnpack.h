@@ -61,7 +61,8 @@ typedef enum {
   AP_F32 = 0, /* IEEE binary32                                   */
   AP_F16 = 1, /* IEEE binary16                                   */
   AP_BF16 = 2, /* bfloat16 (upper half of a binary32)            */
-  AP_I8 = 3   /* signed 8-bit codes (coefficients only)          */
+  AP_I8 = 3,  /* signed 8-bit codes (coefficients only)          */
+  AP_I4 = 4   /* 4-bit codes, two per byte (coefficients only)   */
 } ap_dtype;
 
 /* Columns per int8 scale (one fp16 scale per token per AP_QBLOCK columns). */
@@ -156,6 +157,24 @@ ap_status ap_quantize_i8(const void* C, void* codes, void* scales,
                          int B, int T, int T_cap, int r, void* stream);
 
 /* ------------------------------------------------------------------------
+ * ap_quantize_i4 -- 4-bit coefficients (paper Sec. 4.5 and Table 4 combine the
+ * method with 4-bit quantisation of the cache; the reading taken for the format
+ * is the uniform one, with the block structure of the int8 format): per token and
+ * per AP_QBLOCK columns  amax = max|c|; scale = fp16(fp32(amax) / 7.0f);
+ * code = clamp(rint_even(fp32(c) / fp32(scale)), -7, 7), all zero when scale == 0.
+ * Two codes per byte: byte i of a row holds column 2i in its low nibble and column
+ * 2i+1 in its high nibble, each nibble the code plus 8.
+ *   C      [B, T_cap, r] fp16, rows 0..T-1 read
+ *   codes  [B, T_cap, r / 2] bytes, scales [B, T_cap, r / AP_QBLOCK] fp16
+ * ap_decode_attn reads the result with dt_coef = AP_I4 (dt = AP_F16): the codes
+ * enter the matrix cores as exact integers, a coefficient's value is code * scale
+ * with the scale applied in fp32, as for AP_I8.  Per-token ranks are multiples of
+ * AP_QBLOCK.
+ * ---------------------------------------------------------------------- */
+ap_status ap_quantize_i4(const void* C, void* codes, void* scales,
+                         int B, int T, int T_cap, int r, void* stream);
+
+/* ------------------------------------------------------------------------
  * ap_select_ranks -- attention-aware rank groups (paper Sec. 3.2; Alg. 1,
  * group-selection step).
  *
@@ -192,10 +211,11 @@ size_t ap_select_workspace_bytes(int B, int T, int F);
  *   lse[b,h]  = log sum_t exp( sm_scale * q[b,h] . Ktilde[t, head h] )   (natural log)
  *
  *   q        [B, H, d] dtype dt
- *   Ck, Cv   [B, T_cap, r] dtype dt_coef (== dt, or AP_I8 with dt == AP_F16);
+ *   Ck, Cv   [B, T_cap, r] dtype dt_coef (== dt, or AP_I8 / AP_I4 with dt == AP_F16;
+ *            AP_I4 rows are r / 2 bytes);
  *            rows 0..T-1 are attended (no mask: the newest token is appended
  *            before attention, as in Alg. 1).
- *   scale_k, scale_v  [B, T_cap, r / AP_QBLOCK] fp16, required iff dt_coef == AP_I8;
+ *   scale_k, scale_v  [B, T_cap, r / AP_QBLOCK] fp16, required iff dt_coef is AP_I8 or AP_I4;
  *            a coefficient's value is code * scale.
  *   Bk, Bv   [r, H_kv*d] dtype dt, batch b at + b*basis_batch_stride elements (0 = shared)
  *   H_kv     key/value heads; must divide H.  With H_kv < H the fused step of

@@ -25,7 +25,7 @@ if not os.path.exists(LIB_PATH):
 _lib = ctypes.CDLL(LIB_PATH)
 
 AP_OK, AP_ERR_INVALID_ARG, AP_ERR_UNSUPPORTED, AP_ERR_WORKSPACE, AP_ERR_HIP = range(5)
-AP_F32, AP_F16, AP_BF16, AP_I8 = range(4)
+AP_F32, AP_F16, AP_BF16, AP_I8, AP_I4 = range(5)
 AP_QBLOCK = 64
 
 _c = ctypes
@@ -43,6 +43,8 @@ _lib.ap_decompress.restype = _i
 _lib.ap_decompress.argtypes = [_vp, _vp, _i64, _vp, _vp] + [_i] * 6 + [_vp, _sz, _vp]
 _lib.ap_quantize_i8.restype = _i
 _lib.ap_quantize_i8.argtypes = [_vp, _vp, _vp, _i, _i, _i, _i, _vp]
+_lib.ap_quantize_i4.restype = _i
+_lib.ap_quantize_i4.argtypes = [_vp, _vp, _vp, _i, _i, _i, _i, _vp]
 _lib.ap_select_ranks.restype = _i
 _lib.ap_select_ranks.argtypes = [_vp, _i, _i, _i, _vp, _vp, _c.c_int32, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.ap_select_workspace_bytes.restype = _sz
@@ -96,13 +98,15 @@ _lib.ap_prof_read_launches.restype = _i
 _lib.ap_prof_read_launches.argtypes = [_c.POINTER(_c.c_float), _i, _c.POINTER(_c.c_int)]
 
 EXPORTS = ("ap_compact", "ap_bases_workspace_bytes", "ap_compute_bases", "ap_decompress_workspace_bytes",
-           "ap_decompress", "ap_quantize_i8", "ap_select_ranks", "ap_select_workspace_bytes",
+           "ap_decompress", "ap_quantize_i4", "ap_quantize_i8", "ap_select_ranks", "ap_select_workspace_bytes",
            "ap_decode_attn", "ap_decode_attn_static", "ap_decode_step", "ap_update_importance", "ap_decode_workspace_bytes",
            "ap_raw_workspace_bytes", "ap_raw_attn", "ap_keyonly_workspace_bytes", "ap_keyonly_attn",
            "ap_valueonly_workspace_bytes", "ap_valueonly_attn", "ap_merge_segments", "ap_raw_append", "ap_status_string", "ap_last_error",
            "ap_version", "ap_set_fused_value_min_bytes", "ap_prof_enable", "ap_prof_read", "ap_prof_read_launches", "ap_probe_read_granule", "ap_probe_read")
 
-_DT = {torch.float32: AP_F32, torch.float16: AP_F16, torch.bfloat16: AP_BF16, torch.int8: AP_I8}
+# coefficient tensors: int8 = one code per byte, uint8 = 4-bit codes, two per byte
+_DT = {torch.float32: AP_F32, torch.float16: AP_F16, torch.bfloat16: AP_BF16, torch.int8: AP_I8,
+       torch.uint8: AP_I4}
 
 
 class AttnPackError(RuntimeError):
@@ -199,6 +203,12 @@ def ap_quantize_i8(C, codes, scales, *, T: int, stream=None) -> None:
     _check(_lib.ap_quantize_i8(_p(C), _p(codes), _p(scales), B, T, T_cap, r, _stream(stream)))
 
 
+def ap_quantize_i4(C, codes, scales, *, T: int, stream=None) -> None:
+    """C [B, T_cap, r] fp16 -> codes [B, T_cap, r/2] uint8 (two 4-bit codes per byte), scales fp16."""
+    B, T_cap, r = C.shape
+    _check(_lib.ap_quantize_i4(_p(C), _p(codes), _p(scales), B, T, T_cap, r, _stream(stream)))
+
+
 def ap_select_ranks(mass, group_rank, cum_num, den: int, rank_out, bucket_off, bucket_idx,
                     workspace, *, stream=None) -> None:
     """mass [B, T] fp32 (GPU); group_rank, cum_num: host sequences of ints."""
@@ -218,7 +228,7 @@ def ap_decode_attn(q, Ck, Cv, Bk, Bv, out, workspace, *, T: int, sm_scale: float
     Bk, Bv [r, H_kv*d] or [B, r, H_kv*d] (H_kv is read off their width);
     scores [B, T_cap, H] fp32 (optional output)."""
     B, H, d = q.shape
-    T_cap, r = Ck.shape[1], Ck.shape[2]
+    T_cap, r = Ck.shape[1], Ck.shape[2] * (2 if Ck.dtype == torch.uint8 else 1)
     H_kv = Bk.shape[-1] // d
     _check(_lib.ap_decode_attn(_p(q), _p(Ck), _p(Cv), _p(scale_k), _p(scale_v), _p(Bk), _p(Bv),
                                _bstride(Bk), _p(rank_k), _p(rank_v), _p(bucket_off),
@@ -236,7 +246,7 @@ def ap_decode_attn_static(q, Ck, Cv, Bk, Bv, out, *, T: int, sm_scale: float,
                           bucket_idx=None, F: int = 0, lse=None, scores=None, stream=None) -> None:
     """ap_decode_attn on the library's own scratch buffer (no workspace argument, no allocation)."""
     B, H, d = q.shape
-    T_cap, r = Ck.shape[1], Ck.shape[2]
+    T_cap, r = Ck.shape[1], Ck.shape[2] * (2 if Ck.dtype == torch.uint8 else 1)
     H_kv = Bk.shape[-1] // d
     _check(_lib.ap_decode_attn_static(_p(q), _p(Ck), _p(Cv), _p(scale_k), _p(scale_v), _p(Bk), _p(Bv),
                                       _bstride(Bk), _p(rank_k), _p(rank_v), _p(bucket_off),

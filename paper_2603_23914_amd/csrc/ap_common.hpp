@@ -26,6 +26,7 @@ inline size_t dtype_size(ap_dtype dt) {
     case AP_F16: return 2;
     case AP_BF16: return 2;
     case AP_I8: return 1;
+    case AP_I4: return 1;   // two coefficients per byte: callers that size rows use r / 2
   }
   return 0;
 }
@@ -135,6 +136,8 @@ ap_status launch_gemm_nt(const NtGemmArgs& a, const NtGemmArgs* second = nullptr
 // runs in the same launch, or null
 ap_status launch_compact_gemm(const CompactArgs& a, const CompactArgs* second = nullptr);
 ap_status launch_quantize_i8(const void* C, void* codes, void* scales, int B, int T, int T_cap,
+                             int r, hipStream_t stream);
+ap_status launch_quantize_i4(const void* C, void* codes, void* scales, int B, int T, int T_cap,
                              int r, hipStream_t stream);
 
 // per-step passes over the bases in 16-bit storage (basis_gemv.hip)

@@ -291,6 +291,18 @@ ap_status ap_quantize_i8(const void* C, void* codes, void* scales, int B, int T,
   return launch_quantize_i8(C, codes, scales, B, T, T_cap, r, (hipStream_t)stream);
 }
 
+ap_status ap_quantize_i4(const void* C, void* codes, void* scales, int B, int T, int T_cap, int r,
+                         void* stream) {
+  clear_error();
+  AP_REQUIRE(C && codes && scales, AP_ERR_INVALID_ARG, "ap_quantize_i4: NULL pointer");
+  AP_REQUIRE(B > 0 && T > 0 && T <= T_cap && r > 0, AP_ERR_INVALID_ARG,
+             "ap_quantize_i4: need B > 0, 0 < T <= T_cap, r > 0");
+  AP_REQUIRE(r % AP_QBLOCK == 0, AP_ERR_INVALID_ARG, "ap_quantize_i4: r %% 64 != 0");
+  AP_REQUIRE(aligned(C, 16) && aligned(codes, 16) && aligned(scales, 2), AP_ERR_INVALID_ARG,
+             "ap_quantize_i4: misaligned pointer");
+  return launch_quantize_i4(C, codes, scales, B, T, T_cap, r, (hipStream_t)stream);
+}
+
 // ---------------------------------------------------------------------------------------------
 size_t ap_select_workspace_bytes(int B, int T, int F) {
   if (B <= 0 || T <= 0 || F <= 0) return 0;
@@ -365,8 +377,8 @@ static ap_status decode_entry(const char* name, const void* q, const void* k_new
   ap_status s = decode_shape_check(B, H, d, T, r, dt, true);
   if (s != AP_OK) return s;
   AP_REQUIRE(T <= T_cap, AP_ERR_INVALID_ARG, "%s: T=%d exceeds T_cap=%d", name, T, T_cap);
-  AP_REQUIRE(dt_coef == dt || (dt_coef == AP_I8 && dt == AP_F16), AP_ERR_INVALID_ARG,
-             "%s: dt_coef must equal dt, or be AP_I8 with dt AP_F16", name);
+  AP_REQUIRE(dt_coef == dt || ((dt_coef == AP_I8 || dt_coef == AP_I4) && dt == AP_F16), AP_ERR_INVALID_ARG,
+             "%s: dt_coef must equal dt, or be AP_I8 / AP_I4 with dt AP_F16", name);
   AP_REQUIRE(dt_out == dt || dt_out == AP_F32, AP_ERR_INVALID_ARG,
              "%s: dt_out must equal dt or be AP_F32", name);
   AP_REQUIRE(sm_scale == sm_scale && sm_scale > 0.f && sm_scale < 1e30f, AP_ERR_INVALID_ARG,
@@ -384,8 +396,8 @@ static ap_status decode_entry(const char* name, const void* q, const void* k_new
     AP_REQUIRE(basis_batch_stride % 8 == 0, AP_ERR_INVALID_ARG,
                "%s: basis_batch_stride must keep rows 16-byte aligned", name);
   }
-  if (dt_coef == AP_I8) {
-    AP_REQUIRE(scale_k && scale_v, AP_ERR_INVALID_ARG, "%s: AP_I8 needs scale buffers", name);
+  if (dt_coef == AP_I8 || dt_coef == AP_I4) {
+    AP_REQUIRE(scale_k && scale_v, AP_ERR_INVALID_ARG, "%s: quantised coefficients need scale buffers", name);
   }
   if (k_new || v_new) {
     AP_REQUIRE(k_new && v_new && aligned(k_new, 16) && aligned(v_new, 16), AP_ERR_INVALID_ARG,

@@ -191,6 +191,43 @@ quantize_i8(const uint16_t* __restrict__ C, int8_t* __restrict__ codes,
   }
 }
 
+// The 4-bit format: the same walk, codes -7 .. 7, two per byte (column 2i in the low nibble of
+// byte i, each nibble the code plus 8).  A lane's 8 columns become one dword.
+__global__ void __launch_bounds__(256)
+quantize_i4(const uint16_t* __restrict__ C, uint8_t* __restrict__ codes,
+            uint16_t* __restrict__ scales, int T, int T_cap, int r) {
+  const int lane = threadIdx.x & 63, t = blockIdx.x * 4 + (threadIdx.x >> 6), b = blockIdx.y;
+  if (t >= T) return;
+  const size_t row = (size_t)b * T_cap + t;
+  for (int c0 = 0; c0 < r; c0 += 512) {
+    const int col = c0 + lane * 8;
+    const bool live = col < r;
+    u32x4_t v = {0, 0, 0, 0};
+    if (live) v = *(const u32x4_t*)(C + row * r + col);
+    float x[8];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) { x[2 * e] = lo_to_f32(v[e], F16Tag{}); x[2 * e + 1] = hi_to_f32(v[e], F16Tag{}); }
+    float amax = 0.f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) amax = fmaxf(amax, fabsf(x[e]));
+#pragma unroll
+    for (int o = 1; o < 8; o <<= 1) amax = fmaxf(amax, __shfl_xor(amax, o));
+    const _Float16 sh = (_Float16)(amax / 7.0f);             // IEEE divide, RNE to fp16
+    const float s = (float)sh;
+    uint32_t word = 0;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      float q = 0.f;
+      if (s != 0.f) q = fminf(fmaxf(rintf(x[e] / s), -7.f), 7.f);
+      word |= (uint32_t)((int)q + 8) << (4 * e);
+    }
+    if (live) {
+      *(uint32_t*)(codes + row * (r >> 1) + (col >> 1)) = word;
+      if ((lane & 7) == 0) scales[row * (r / kCols) + (col >> 6)] = __builtin_bit_cast(uint16_t, sh);
+    }
+  }
+}
+
 template <class Tag>
 ap_status run_compact(const CompactArgs& a) {
   const int out_kind = a.dt_out == AP_I8 ? 1 : 0;
@@ -235,6 +272,14 @@ ap_status launch_quantize_i8(const void* C, void* codes, void* scales, int B, in
   hipLaunchKernelGGL(quantize_i8, dim3((T + 3) / 4, B), dim3(256), 0, stream, (const uint16_t*)C,
                      (int8_t*)codes, (uint16_t*)scales, T, T_cap, r);
   return check_launch("ap_quantize_i8");
+}
+
+ap_status launch_quantize_i4(const void* C, void* codes, void* scales, int B, int T, int T_cap,
+                             int r, hipStream_t stream) {
+  AP_REQUIRE(B <= 65535, AP_ERR_UNSUPPORTED, "ap_quantize_i4: B must be <= 65535");
+  hipLaunchKernelGGL(quantize_i4, dim3((T + 3) / 4, B), dim3(256), 0, stream, (const uint16_t*)C,
+                     (uint8_t*)codes, (uint16_t*)scales, T, T_cap, r);
+  return check_launch("ap_quantize_i4");
 }
 
 }  // namespace ap

@@ -99,6 +99,21 @@ __device__ __forceinline__ u32x4_t code_row8(uint32_t c0, uint32_t c1) {
   return o;
 }
 
+// 4-bit codes (two per byte, each nibble the code plus 8): a dword holds eight codes, nibble j
+// column c0 + j.  0x6400 | u is 1024 + u in fp16, so subtracting 1032 leaves the code exactly.
+__device__ __forceinline__ uint32_t code2_4(uint32_t biased /* 0x640u640u */) {
+  const h2_t off = {(_Float16)-1032.0f, (_Float16)-1032.0f};
+  return __builtin_bit_cast(uint32_t, __builtin_bit_cast(h2_t, biased) + off);
+}
+// eight codes of one row (one dword) -> MFMA operand; operand slots (2k, 2k+1) hold columns
+// (k, k+4) of the eight, so the other operand is loaded in that column order
+__device__ __forceinline__ u32x4_t code_row8_i4(uint32_t d) {
+  u32x4_t o;
+#pragma unroll
+  for (int k = 0; k < 4; ++k) o[k] = code2_4(((d >> (4 * k)) & 0x000f000fu) | 0x64006400u);
+  return o;
+}
+
 // ------------------------------------------------------------------------------------------
 // tile kernels (unrolled to the compile-time maximum, left early on the run-time count)
 // ------------------------------------------------------------------------------------------
@@ -202,7 +217,8 @@ __device__ __forceinline__ void wsum_tile(const char* vA, const char* vB, int pi
 // loaded with the same column order), so a block is two k-steps.  The block's sum over the
 // integer codes is exact in fp32; it is multiplied by the token's scale in fp32 and added to the
 // scores.  A lane's results belong to tokens 16 tt + 4 g + e, whose scales sit in lanes 4 g + e.
-template <int MT, int NBW>
+// 4-bit codes (I4): the lane's 16 codes of a block are two dwords, one per k-step.
+template <int MT, int NBW, bool I4>
 __device__ __forceinline__ void score_tile_i8(const u32x4_t (&Araw)[NBW][2],
                                               const uint32_t (&ksc)[NBW][2], int g,
                                               const u32x4_t (&qhi)[2 * NBW][MT],
@@ -212,8 +228,8 @@ __device__ __forceinline__ void score_tile_i8(const u32x4_t (&Araw)[NBW][2],
     u32x4_t a0[2], a1[2];
 #pragma unroll
     for (int tt = 0; tt < 2; ++tt) {
-      a0[tt] = code_row8(Araw[i][tt][0], Araw[i][tt][1]);
-      a1[tt] = code_row8(Araw[i][tt][2], Araw[i][tt][3]);
+      a0[tt] = I4 ? code_row8_i4(Araw[i][tt][0]) : code_row8(Araw[i][tt][0], Araw[i][tt][1]);
+      a1[tt] = I4 ? code_row8_i4(Araw[i][tt][1]) : code_row8(Araw[i][tt][2], Araw[i][tt][3]);
     }
     f32x4_t pb[MT][2];
 #pragma unroll
@@ -289,6 +305,58 @@ __device__ __forceinline__ void wsum_tile_i8(const char* vA, const char* vB, int
   }
 }
 
+// 4-bit variant.  Column groups are 512 wide (256 bytes); in each the wave owns 64 bytes = two
+// scale blocks of 32 bytes.  A block's eight dwords feed sixteen MFMA rows: row n reads dword
+// n & 7 and takes the nibbles 4 (n >> 3) + j, j = 0..3, one MFMA per j; row n is then column
+// 8 (n & 7) + 4 (n >> 3) + j of the block, so all sixteen rows of a product share one scale block
+// and the token's scale can be folded into its weight as for int8.
+template <int MT, int NGL>
+__device__ __forceinline__ void wsum_tile_i4(const char* vA, const char* vB, int pitch, int r,
+                                             int cp, int n, int g, const uint16_t* vs,
+                                             const f32x4_t (&P32)[MT][2], const float (&alpha)[MT],
+                                             f32x4_t (&U)[NGL][8][MT]) {
+  const int doff = (n & 7) * 4;              // this row's dword inside a block (vA / vB carry no lane offset)
+  const int sh0 = 16 * (n >> 3);             // its first nibble
+#pragma unroll
+  for (int i = 0; i < NGL; ++i) {
+#pragma unroll
+    for (int b2 = 0; b2 < 2; ++b2) {
+      const int blk = 8 * i + 2 * cp + b2;
+      uint32_t v[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+      u32x2_t s01 = {0, 0}, s23 = {0, 0};
+      if (blk * 64 < r) {                     // wave-uniform: the block exists at this rank
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          v[e] = *(const uint32_t*)(vA + e * pitch + i * 256 + b2 * 32 + doff);
+          v[4 + e] = *(const uint32_t*)(vB + e * pitch + i * 256 + b2 * 32 + doff);
+        }
+        s01 = *(const u32x2_t*)(vs + blk * kTile + 4 * g);
+        s23 = *(const u32x2_t*)(vs + blk * kTile + 16 + 4 * g);
+      }
+      const uint32_t sc[4] = {s01[0], s01[1], s23[0], s23[1]};
+      u32x4_t Psc[MT];
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const float f0 = lo_to_f32(sc[k], F16Tag{}), f1 = hi_to_f32(sc[k], F16Tag{});
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+          Psc[mt][k] = cvt_pack(P32[mt][k >> 1][2 * (k & 1)] * f0, P32[mt][k >> 1][2 * (k & 1) + 1] * f1, F16Tag{});
+      }
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int sh = sh0 + 4 * j;
+        u32x4_t op;
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+          op[k] = code2_4(((v[2 * k] >> sh) & 0xfu) | (((v[2 * k + 1] >> sh) & 0xfu) << 16) | 0x64006400u);
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+          U[i][4 * b2 + j][mt] = Mfma<F16Tag>::run(op, Psc[mt], U[i][4 * b2 + j][mt] * alpha[mt]);
+      }
+    }
+  }
+}
+
 // Butterfly steps inside groups of 8 lanes with DPP (VALU speed, no LDS crossbar):
 // xor 1 and xor 2 as quad permutes; the third step mirrors each half-row, which pairs the
 // two quads of an 8-lane group (all lanes of a quad already agree after the first two).
@@ -328,8 +396,9 @@ struct AttnParams {
   const uint16_t* Qp;   // [B][2][Hp][r]
   const uint16_t* Ck;   // [B][T_cap][r]
   const uint16_t* Cv;
-  const uint16_t* Sk;   // int8 coefficients only: fp16 scales [B][T_cap][r/64]
+  const uint16_t* Sk;   // int8 / 4-bit coefficients only: fp16 scales [B][T_cap][r/64]
   const uint16_t* Sv;
+  int qbits;            // 8 or 4 when Sk is given
   float* part_ml;       // [B][S][H][2]   (softmax reference exponent in log2 units, sum)
   float* part_U;        // [B][S][H][r]
   int B, T, T_cap, r, H, nsplit;
@@ -400,11 +469,14 @@ __device__ __forceinline__ void wg_coords(int nsplit, int xcd_aware, int& b, int
 // all of the rank axis, instead of a quarter of the rank axis of every tile.  A score wave's
 // tile is then complete without the other waves' partial sums, and one pair of barriers covers
 // four tiles: at small ranks the tile loop is bound by that dependency chain, not by memory.
-template <class Tag, int MT, bool SPLIT, bool RAGGED, bool I8, bool TS = false>
+// Q: coefficient storage, 0 = 16-bit, 1 = int8 codes, 2 = 4-bit codes (both with fp16 scales).
+template <class Tag, int MT, bool SPLIT, bool RAGGED, int Q, bool TS = false>
 struct WaveCtx {
+  static constexpr bool I8 = Q != 0, I4 = Q == 2;
   static constexpr int NSUB = TS ? 4 : 1;   // tiles per barrier pair
   static constexpr int HPW = 2 * MT;     // heads finalised per wave
-  static constexpr int EB = I8 ? 1 : 2;  // bytes per stored coefficient
+  // bytes of a coefficient row
+  static __device__ __forceinline__ int row_bytes_of(int r) { return I4 ? r >> 1 : (I8 ? r : 2 * r); }
 
   int w, lane, n, g, b, s;
   int r, T, H, nh, nsplit, dbg;
@@ -442,7 +514,7 @@ struct WaveCtx {
     if (scores) scores += (size_t)b * H * T_cap;
     // ring unit geometry: 16 rows of (cpr+1) 16-byte chunks (one pad chunk per row shifts
     // consecutive rows across the LDS banks)
-    const int cpr = (r * EB) >> 4;
+    const int cpr = row_bytes_of(r) >> 4;
     pitch = (cpr + 1) * 16;
     nblk = (kHalf * (cpr + 1) + 63) >> 6;
     unit_bytes = nblk * 1024;
@@ -450,7 +522,7 @@ struct WaveCtx {
     xchg = (f32x4_t*)(smem + nh * unit_bytes);
     Pbuf = (u32x4_t*)(xchg + 4 * 16 * MT * 9);
     abuf = (float*)(Pbuf + NSUB * MT * 2 * 64);
-    row_bytes = (uint32_t)(r * EB);
+    row_bytes = (uint32_t)row_bytes_of(r);
     vsb = (uint16_t*)(abuf + NSUB * 16 * MT);
     if (!RAGGED) {
       const int ntiles = (T + kTile - 1) / kTile;
@@ -743,8 +815,11 @@ struct WaveCtx {
 #define AP_T_REPORT
 #endif
 
-template <class Tag, int MT, int RMAX, bool SPLIT, bool RAGGED, bool I8>
+template <class Tag, int MT, int RMAX, bool SPLIT, bool RAGGED, int Q>
 __device__ __forceinline__ void score_role(const AttnParams& p) {
+  constexpr bool I8 = Q != 0, I4 = Q == 2;
+  constexpr uint32_t UB = I4 ? 32 : 64;                   // bytes of a row per unit (a scale block, or a k-step)
+  constexpr uint32_t LB = I4 ? 8 : 16;                    // bytes of it per lane
   // a score wave owns "units" w, w+4, ... of the rank axis, 64 bytes of a row each:
   // 32-column k-steps for 16-bit storage, 64-column scale blocks (two k-steps) for int8
   constexpr bool TS = !RAGGED && !I8 && RMAX == 128;      // token-split mode (see WaveCtx)
@@ -753,7 +828,7 @@ __device__ __forceinline__ void score_role(const AttnParams& p) {
   constexpr int NA = I8 ? NBW : NKW;                      // 16-byte row loads per 16-row half
   constexpr int Hp = MT * 16;
   AP_T_ENTRY
-  WaveCtx<Tag, MT, SPLIT, RAGGED, I8, TS> cx;
+  WaveCtx<Tag, MT, SPLIT, RAGGED, Q, TS> cx;
   cx.init(p);
   float* part_U = uni_ptr(p.part_U);
   float* part_ml = uni_ptr(p.part_ml);
@@ -784,6 +859,13 @@ __device__ __forceinline__ void score_role(const AttnParams& p) {
         const uint16_t* qrow = Qp + (((size_t)cx.b * 2) * Hp + (mt * 16 + n)) * r + col;
         qhi[i][mt] = *(const u32x4_t*)qrow;
         if (SPLIT) qlo[i][mt] = *(const u32x4_t*)(qrow + (size_t)Hp * r);
+        if (I4) {                                          // the column order of code_row8_i4: 0,4,1,5,2,6,3,7
+          const u32x4_t t = qhi[i][mt];
+          qhi[i][mt][0] = __builtin_amdgcn_perm(t[2], t[0], 0x05040100u);
+          qhi[i][mt][1] = __builtin_amdgcn_perm(t[2], t[0], 0x07060302u);
+          qhi[i][mt][2] = __builtin_amdgcn_perm(t[3], t[1], 0x05040100u);
+          qhi[i][mt][3] = __builtin_amdgcn_perm(t[3], t[1], 0x07060302u);
+        }
       }
     }
   // C_k operands (A operand): lane (n, g) holds 16 bytes of token rows n, 16+n of the tile
@@ -791,13 +873,22 @@ __device__ __forceinline__ void score_role(const AttnParams& p) {
   const char* Ck_b = (const char*)uni_ptr(p.Ck) + (size_t)cx.b * uni(p.T_cap) * cx.row_bytes;
   // units this wave does not own re-read its first chunk (finite data times zero q'):
   // the loads carry no branches, so they issue back to back without waits between them
-  const uint32_t lane_off = (uint32_t)((my_nks > 0 ? ufirst * 64 : 0) + g * 16);
+  const uint32_t lane_off = (uint32_t)(my_nks > 0 ? ufirst : 0) * UB + (uint32_t)g * LB;
   u32x4_t A[NA][2];
 #pragma unroll
   for (int i = 0; i < NA; ++i) { u32x4_t z = {0, 0, 0, 0}; A[i][0] = z; A[i][1] = z; }
   uint32_t koff[NA];
 #pragma unroll
-  for (int i = 0; i < NA; ++i) koff[i] = i < my_nks ? (uint32_t)(i * ustep) * 64u : 0u;
+  for (int i = 0; i < NA; ++i) koff[i] = i < my_nks ? (uint32_t)(i * ustep) * UB : 0u;
+  auto load_piece = [](const char* src) -> u32x4_t {       // this lane's bytes of one unit of one row
+    if constexpr (I4) {
+      const u32x2_t h = *(const u32x2_t*)src;
+      const u32x4_t v = {h[0], h[1], 0u, 0u};
+      return v;
+    } else {
+      return *(const u32x4_t*)src;
+    }
+  };
   // int8: the key scale of the lane's row for every owned block (both halves of a packed
   // pair), and this wave's share of the tile's value scales, which the score waves pass to
   // the sum waves through LDS as [scale block][32 tokens]
@@ -849,7 +940,7 @@ __device__ __forceinline__ void score_role(const AttnParams& p) {
         row = row < T ? row : T - 1;                      // rows beyond T are masked later
         const char* rp = Ck_b + ((uint32_t)row * cx.row_bytes + lane_off);
 #pragma unroll
-        for (int i = 0; i < NA; ++i) A[i][tt] = *(const u32x4_t*)(rp + koff[i]);
+        for (int i = 0; i < NA; ++i) A[i][tt] = load_piece(rp + koff[i]);
       }
       load_scales(tile);
     } else {
@@ -858,14 +949,14 @@ __device__ __forceinline__ void score_role(const AttnParams& p) {
       // (a key rank that ends inside a 32-column k-step still fetches that k-step; the columns
       // beyond the rank are zeroed before the product)
       const int nks_t = I8 ? uni(cx.meta[4 * tile + 1]) >> 6 : (uni(cx.meta[4 * tile + 1]) + 31) >> 5;   // units of 64 bytes
-      const uint32_t loff = (uint32_t)((w < nks_t ? w * 64 : 0) + g * 16);
+      const uint32_t loff = (uint32_t)(w < nks_t ? w : 0) * UB + (uint32_t)g * LB;
 #pragma unroll
       for (int tt = 0; tt < 2; ++tt) {
         const int row = cx.idxb[tile * kTile + 16 * tt + n];
         const char* rp = Ck_b + ((uint32_t)row * cx.row_bytes + loff);
 #pragma unroll
         for (int i = 0; i < NA; ++i)
-          A[i][tt] = *(const u32x4_t*)(rp + ((w + 4 * i) < nks_t ? (uint32_t)i * 256u : 0u));
+          A[i][tt] = load_piece(rp + ((w + 4 * i) < nks_t ? (uint32_t)i * 4u * UB : 0u));
       }
       load_scales(tile);
     }
@@ -915,7 +1006,12 @@ __device__ __forceinline__ void score_role(const AttnParams& p) {
         // 16-bit: this lane's eight columns of k-step w + 4i start at 32 (w + 4i) + 8 g, and ranks
         // are multiples of 8 there; int8: whole 64-column scale blocks
         const bool beyond = I8 ? (w + 4 * i) * 64 >= rk_t : (w + 4 * i) * 32 + g * 8 >= rk_t;
-        if (beyond) { u32x4_t z = {0, 0, 0, 0}; A[i][0] = z; A[i][1] = z; }
+        if (beyond) {                                     // code 0 is the byte 0 for int8, the nibble 8 for 4-bit
+          const uint32_t zc = I4 ? 0x88888888u : 0u;
+          const u32x4_t z = {zc, zc, zc, zc};
+          A[i][0] = z;
+          A[i][1] = z;
+        }
       }
     }
     if constexpr (I8) {
@@ -925,7 +1021,7 @@ __device__ __forceinline__ void score_role(const AttnParams& p) {
 #pragma unroll
       for (int j = 0; j < 2; ++j)
         if (vs_e0 + 256 * j < nsb * kTile) vs[vs_e0 + 256 * j] = vsr[j];
-      if (!(cx.dbg & 2)) score_tile_i8<MT, NBW>(A, ksc, g, qhi, sp);
+      if (!(cx.dbg & 2)) score_tile_i8<MT, NBW, I4>(A, ksc, g, qhi, sp);
     } else {
       if (!(cx.dbg & 2)) score_tile<Tag, MT, SPLIT, NKW>(A, qhi, qlo, sp);
     }
@@ -949,16 +1045,17 @@ __device__ __forceinline__ void score_role(const AttnParams& p) {
   AP_T_REPORT
 }
 
-template <class Tag, int MT, int RMAX, bool SPLIT, bool RAGGED, bool I8>
+template <class Tag, int MT, int RMAX, bool SPLIT, bool RAGGED, int Q>
 __device__ __forceinline__ void sum_role(const AttnParams& p) {
+  constexpr bool I8 = Q != 0, I4 = Q == 2;
   constexpr bool TS = !RAGGED && !I8 && RMAX == 128;              // token-split mode (see WaveCtx)
-  constexpr int EB = I8 ? 1 : 2;
-  constexpr int NGRP = (RMAX * EB + 255) / 256;                   // 256-byte column groups
-  constexpr int NJ = I8 ? 4 : 2;                                  // columns per LDS dword
-  constexpr int MAXBLK = (kHalf * (RMAX * EB / 16 + 1) + 63) / 64;  // 1 KiB blocks per ring unit
+  constexpr int RB = I4 ? RMAX / 2 : (I8 ? RMAX : 2 * RMAX);      // bytes of a coefficient row at most
+  constexpr int NGRP = (RB + 255) / 256;                          // 256-byte column groups
+  constexpr int NJ = I4 ? 8 : (I8 ? 4 : 2);                       // accumulator tiles per group
+  constexpr int MAXBLK = (kHalf * (RB / 16 + 1) + 63) / 64;       // 1 KiB blocks per ring unit
   constexpr int NSLOT = (MAXBLK + 3) / 4;
   AP_T_ENTRY
-  WaveCtx<Tag, MT, SPLIT, RAGGED, I8, TS> cx;
+  WaveCtx<Tag, MT, SPLIT, RAGGED, Q, TS> cx;
   cx.init(p);
   float* part_U = uni_ptr(p.part_U);
   float* part_ml = uni_ptr(p.part_ml);
@@ -968,7 +1065,7 @@ __device__ __forceinline__ void sum_role(const AttnParams& p) {
 
   // ---- this wave's share of a C_v ring unit: 1 KiB blocks cp, cp+4, ...; per lane the
   //      row and the byte offset of its 16-byte chunk from the unit's first row
-  const int cpr = (r * EB) >> 4;
+  const int cpr = (int)cx.row_bytes >> 4;
   const int tot_chunks = kHalf * (cpr + 1);
   uint32_t slot_off[NSLOT];
   uint32_t slot_row[(NSLOT + 3) / 4];
@@ -999,7 +1096,7 @@ __device__ __forceinline__ void sum_role(const AttnParams& p) {
     const int slot0 = 2 * (lt % RT);
     if (RAGGED) {
       // gathered rows; chunks at or beyond the tile's value rank re-read the row's first chunk
-      const uint32_t rv8 = (uint32_t)uni(cx.meta[4 * lt + 2]) >> (I8 ? 4 : 3);   // 16-byte chunks
+      const uint32_t rv8 = (uint32_t)uni(cx.meta[4 * lt + 2]) >> (I4 ? 5 : (I8 ? 4 : 3));   // 16-byte chunks
 #pragma nounroll
       for (int half = 0; half < 2; ++half) {
         char* dst = cx.ring + (slot0 + half) * cx.unit_bytes;
@@ -1143,9 +1240,16 @@ __device__ __forceinline__ void sum_role(const AttnParams& p) {
         P32[mt][0] = __builtin_bit_cast(f32x4_t, Phi[mt]);
         P32[mt][1] = __builtin_bit_cast(f32x4_t, cx.Pbuf[(mt * 2 + 1) * 64 + lane]);
       }
-      if (!(cx.dbg & 2))
-        wsum_tile_i8<MT, NGRP>(vA, vB, cx.pitch, RAGGED ? uni(cx.meta[4 * t + 2]) : r, cp, g,
-                               cx.vsb + (t & 1) * (r >> 6) * kTile, P32, alpha, U);
+      if constexpr (I4) {
+        // the 4-bit reader places its own dword: take the lane's n * 4 off again
+        if (!(cx.dbg & 2))
+          wsum_tile_i4<MT, NGRP>(vA - n * 4, vB - n * 4, cx.pitch, RAGGED ? uni(cx.meta[4 * t + 2]) : r, cp, n, g,
+                                 cx.vsb + (t & 1) * (r >> 6) * kTile, P32, alpha, U);
+      } else {
+        if (!(cx.dbg & 2))
+          wsum_tile_i8<MT, NGRP>(vA, vB, cx.pitch, RAGGED ? uni(cx.meta[4 * t + 2]) : r, cp, g,
+                                 cx.vsb + (t & 1) * (r >> 6) * kTile, P32, alpha, U);
+      }
     } else {
       if (!(cx.dbg & 2))
         wsum_tile<Tag, MT, SPLIT, NGRP>(vA, vB, cx.pitch,
@@ -1173,7 +1277,22 @@ __device__ __forceinline__ void sum_role(const AttnParams& p) {
 #pragma unroll
         for (int i = 0; i < NGRP; ++i) {
           const int col0 = I8 ? i * 256 + cp * 64 + g * 16 : i * 128 + cp * 32 + g * 8;
-          if (col0 < r) {
+          if constexpr (I4) {
+            // accumulator row 4g + e of tile (b2, j) is column 512 i + 128 cp + 64 b2 + 32 (g & 1) + 8 e
+            // + 4 (g >> 1) + j: the four j of one e are consecutive
+#pragma unroll
+            for (int b2 = 0; b2 < 2; ++b2) {
+              const int cb = i * 512 + cp * 128 + b2 * 64 + (g & 1) * 32 + (g >> 1) * 4;
+              if (cb < r) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                  const f32x4_t v = {U[i][4 * b2 + 0][mt][e], U[i][4 * b2 + 1][mt][e], U[i][4 * b2 + 2][mt][e],
+                                     U[i][4 * b2 + 3][mt][e]};
+                  *(f32x4_t*)(urow + cb + 8 * e) = v;
+                }
+              }
+            }
+          } else if (col0 < r) {
             if constexpr (I8) {
 #pragma unroll
               for (int e = 0; e < 4; ++e) {
@@ -1203,16 +1322,16 @@ __device__ __forceinline__ void sum_role(const AttnParams& p) {
 #undef AP_T_STAMP
 #undef AP_T_REPORT
 
-template <class Tag, int MT, int RMAX, bool SPLIT, bool RAGGED, bool I8>
+template <class Tag, int MT, int RMAX, bool SPLIT, bool RAGGED, int Q>
 __device__ __noinline__ void score_role_call(const AttnParams& p) {
-  score_role<Tag, MT, RMAX, SPLIT, RAGGED, I8>(p);
+  score_role<Tag, MT, RMAX, SPLIT, RAGGED, Q>(p);
 }
-template <class Tag, int MT, int RMAX, bool SPLIT, bool RAGGED, bool I8>
+template <class Tag, int MT, int RMAX, bool SPLIT, bool RAGGED, int Q>
 __device__ __noinline__ void sum_role_call(const AttnParams& p) {
-  sum_role<Tag, MT, RMAX, SPLIT, RAGGED, I8>(p);
+  sum_role<Tag, MT, RMAX, SPLIT, RAGGED, Q>(p);
 }
 
-template <class Tag, int MT, int RMAX, bool SPLIT, bool RAGGED, bool I8>
+template <class Tag, int MT, int RMAX, bool SPLIT, bool RAGGED, int Q>
 __global__ void __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2)))
 attn_partial(const AttnParams p) {
   {
@@ -1226,11 +1345,11 @@ attn_partial(const AttnParams p) {
   // do not fit one register allocation without spilling inside the tile loop, keeps the calls.
   constexpr bool kOutline = MT == 4 && RMAX > 512;
   if (__builtin_amdgcn_readfirstlane(threadIdx.x >> 6) < 4) {
-    if constexpr (kOutline) score_role_call<Tag, MT, RMAX, SPLIT, RAGGED, I8>(p);
-    else score_role<Tag, MT, RMAX, SPLIT, RAGGED, I8>(p);
+    if constexpr (kOutline) score_role_call<Tag, MT, RMAX, SPLIT, RAGGED, Q>(p);
+    else score_role<Tag, MT, RMAX, SPLIT, RAGGED, Q>(p);
   } else {
-    if constexpr (kOutline) sum_role_call<Tag, MT, RMAX, SPLIT, RAGGED, I8>(p);
-    else sum_role<Tag, MT, RMAX, SPLIT, RAGGED, I8>(p);
+    if constexpr (kOutline) sum_role_call<Tag, MT, RMAX, SPLIT, RAGGED, Q>(p);
+    else sum_role<Tag, MT, RMAX, SPLIT, RAGGED, Q>(p);
   }
 }
 
@@ -1303,9 +1422,10 @@ WsLayout ws_layout(int B, int H, int d, int T, int r) {
   return w;
 }
 
-template <class Tag, int MT, int RMAX, bool SPLIT, bool RAGGED, bool I8>
+template <class Tag, int MT, int RMAX, bool SPLIT, bool RAGGED, int Q>
 ap_status launch_attn(AttnParams p, int B, hipStream_t stream) {
-  const int cpr = p.r * (I8 ? 1 : 2) / 16;
+  constexpr bool I8 = Q != 0;
+  const int cpr = (Q == 2 ? p.r / 2 : (I8 ? p.r : 2 * p.r)) / 16;
   const size_t unit = (size_t)((kHalf * (cpr + 1) + 63) / 64) * 1024;
   constexpr bool TS = !RAGGED && !I8 && RMAX == 128;
   constexpr int NSUB = TS ? 4 : 1;
@@ -1332,7 +1452,7 @@ ap_status launch_attn(AttnParams p, int B, hipStream_t stream) {
   }
   p.nh = nh;
   size_t lds = (size_t)nh * unit + fixed;
-  auto kern = attn_partial<Tag, MT, RMAX, SPLIT, RAGGED, I8>;
+  auto kern = attn_partial<Tag, MT, RMAX, SPLIT, RAGGED, Q>;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -1357,6 +1477,19 @@ template <class Tag, bool SPLIT>
 ap_status dispatch_attn(const AttnParams& p, int B, hipStream_t stream) {
   const int nw = (p.H + 15) / 16;
   if constexpr (!SPLIT) {                 // fp16 arithmetic: int8 coefficients ride on it
+    if (p.Sk && p.qbits == 4) {
+      switch (nw) {
+#define AP_CASE4(NWV)                                                                  \
+  case NWV:                                                                            \
+    if (p.bucket_idx)                                                                  \
+      return p.r <= 512 ? launch_attn<Tag, NWV, 512, false, true, 2>(p, B, stream)     \
+                        : launch_attn<Tag, NWV, 640, false, true, 2>(p, B, stream);    \
+    return p.r <= 512 ? launch_attn<Tag, NWV, 512, false, false, 2>(p, B, stream)      \
+                      : launch_attn<Tag, NWV, 640, false, false, 2>(p, B, stream);
+        AP_CASE4(1) AP_CASE4(2) AP_CASE4(3) AP_CASE4(4)
+#undef AP_CASE4
+      }
+    }
     if (p.Sk) {
       switch (nw) {
 #define AP_CASE8(NWV)                                                                     \
@@ -1408,7 +1541,8 @@ ap_status run_decode(const DecodeArgs& a) {
   const bool v_long = v_min >= 0 ? v_bytes >= v_min
                                  : v_bytes >= (128ll << 20) || (a.r >= 512 && v_bytes >= (96ll << 20));
   const bool one_pass_v = a.v_new && !a.rank_k && !a.rank_v && a.T >= 2 && Hkv == a.H && v_long;
-  const bool small = a.dt_coef != AP_I8 && attn_small_applies(a.H, a.r, a.T, one_pass_v);
+  const bool quant = a.dt_coef == AP_I8 || a.dt_coef == AP_I4;
+  const bool small = !quant && attn_small_applies(a.H, a.r, a.T, one_pass_v);
   const int S = choose_nsplit(a.B, a.T);     // the same count for both kernels (twice the splits for
                                              // the small-rank kernel measured slower)
   const WsLayout wl = ws_layout(a.B, a.H, a.d, a.T, a.r);
@@ -1453,9 +1587,10 @@ ap_status run_decode(const DecodeArgs& a) {
   p.scores = a.scores;
   p.defer_v = one_pass_v ? 1 : 0;
   p.pnew = (float*)(ws + wl.pn);
-  if (a.dt_coef == AP_I8) {
+  if (quant) {
     p.Sk = (const uint16_t*)a.scale_k;
     p.Sv = (const uint16_t*)a.scale_v;
+    p.qbits = a.dt_coef == AP_I4 ? 4 : 8;
   }
   if (a.rank_k || a.rank_v) {             // rank-ragged: walk the group lists
     p.rank_k = a.rank_k;
