@@ -121,13 +121,16 @@ __device__ __forceinline__ u32x4_t code_row8_i4(uint32_t d) {
 // all MT head tiles.  A[i][tt]: rows 16tt..16tt+15 of the tile at k-step i, in registers.
 // k-steps this wave does not own hold zero rows and zero q' (no branch: the accumulators
 // stay in one straight-line live range).
+// nlive: k-steps of this wave that lie below the tile's key rank (wave-uniform; the others hold
+// zero rows and are skipped: at a quarter of the rank a tile costs a quarter of the products).
 template <class Tag, int MT, bool SPLIT, int NKW>
 __device__ __forceinline__ void score_tile(const u32x4_t (&A)[NKW][2],
                                            const u32x4_t (&qhi)[NKW][MT],
                                            const u32x4_t (&qlo)[SPLIT ? NKW : 1][MT],
-                                           f32x4_t (&s)[MT][2]) {
+                                           f32x4_t (&s)[MT][2], int nlive = NKW) {
 #pragma unroll
   for (int i = 0; i < NKW; ++i) {
+    if (i >= nlive) break;
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
       s[mt][0] = Mfma<Tag>::run(A[i][0], qhi[i][mt], s[mt][0]);
@@ -179,6 +182,7 @@ __device__ __forceinline__ void wsum_tile(const char* vA, const char* vB, int pi
   }
 #pragma unroll
   for (int i = 0; i < NGL; ++i) {
+    if (i * 128 >= cols_left) break;         // wave-uniform: the group lies beyond the value rank
     uint32_t v[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) { v[e] = nx[e]; nx[e] = 0; }
@@ -562,9 +566,20 @@ struct WaveCtx {
     ntl = s < ntot ? (ntot - s + nsplit - 1) / nsplit : 0;
     const int cap = uni(p.ntl_cap);
     ntl = ntl < cap ? ntl : cap;           // never beyond the table (host sizes it for the worst case)
+    // Visiting order: the split's tiles come in group order (high ranks first); walked with a
+    // stride of about ntl / F (coprime to ntl) high- and low-rank tiles alternate, so that the
+    // short tiles' products run while the long tiles' rows are still on their way.
+    int stride = ntl / (F > 0 ? F : 1);
+    stride = stride < 1 ? 1 : stride;
+    for (;; ++stride) {
+      int x = stride, y = ntl;
+      while (y) { const int tmp = x % y; x = y; y = tmp; }
+      if (x == 1 || ntl <= 1) break;
+    }
     for (int e = threadIdx.x; e < ntl * kTile; e += 512) {
       const int i = e >> 5, l = e & 31;
-      const int j = s + i * nsplit;
+      const int isrc = ntl > 1 ? (int)(((int64_t)i * stride) % ntl) : 0;
+      const int j = s + isrc * nsplit;
       int o0 = off[0], o1 = off[1], t0 = 0;
 #pragma unroll
       for (int k = 1; k < 8; ++k)
@@ -1023,7 +1038,12 @@ __device__ __forceinline__ void score_role(const AttnParams& p) {
         if (vs_e0 + 256 * j < nsb * kTile) vs[vs_e0 + 256 * j] = vsr[j];
       if (!(cx.dbg & 2)) score_tile_i8<MT, NBW, I4>(A, ksc, g, qhi, sp);
     } else {
-      if (!(cx.dbg & 2)) score_tile<Tag, MT, SPLIT, NKW>(A, qhi, qlo, sp);
+      int nlive = NKW;
+      if (RAGGED) {                                       // this wave's k-steps w, w + 4, ... below the key rank
+        const int nks_t = (uni(cx.meta[4 * t + 1]) + 31) >> 5;
+        nlive = nks_t > w ? (nks_t - w + 3) >> 2 : 0;
+      }
+      if (!(cx.dbg & 2)) score_tile<Tag, MT, SPLIT, NKW>(A, qhi, qlo, sp, nlive);
     }
     AP_TICK(1)
     if (t + 1 < cx.ntl) load_A(t + 1);                    // lands while the tile is finished
