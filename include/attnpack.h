@@ -190,7 +190,9 @@ ap_status ap_quantize_i4(const void* C, void* codes, void* scales,
  *   rank_out    [B, T] int32: rank of every token
  *   bucket_off  [B, F+1] int32: group g's tokens are bucket_idx[b, off[g] .. off[g+1])
  *   bucket_idx  [B, T] int32: token indices, ascending inside each group
- *   workspace   >= ap_select_workspace_bytes(B, T, F) bytes, 16-byte aligned
+ *   workspace   >= ap_select_workspace_bytes(B, T, F) bytes, 16-byte aligned; its
+ *               contents need not be preserved or cleared between calls (long rows
+ *               in small batches are split over workgroups that meet there)
  * 1 <= F <= 8.  Results are unique, so they are comparable bit for bit.
  * ---------------------------------------------------------------------- */
 ap_status ap_select_ranks(const float* mass, int B, int T, int F,

@@ -737,6 +737,9 @@ ap_status launch_merge_splits(const float* part_ml, const float* part_U, float* 
 }
 int expand_row_blocks(int B, int r) { return (r + expand_rows_per_pair(B, r) - 1) / expand_rows_per_pair(B, r); }
 
+#ifndef AP_EA_NB10
+#define AP_EA_NB10 3
+#endif
 ap_status launch_expand_append(ap_dtype dt, bool out_f32, const void* Bv, int64_t bstride,
                                const void* v_new, void* Cv, const float* part_ml,
                                const float* part_U, const float* pnew, float* pout, void* out,
@@ -754,8 +757,8 @@ ap_status launch_expand_append(ap_dtype dt, bool out_f32, const void* Bv, int64_
     break;                                                                                       \
   }
   do {
-    if (dt == AP_F16) { AP_EA(F16Tag, 2, 3) AP_EA(F16Tag, 4, 3) AP_EA(F16Tag, 8, 3) AP_EA(F16Tag, 10, 3) AP_EA(F16Tag, 16, 2) }
-    else { AP_EA(BF16Tag, 2, 3) AP_EA(BF16Tag, 4, 3) AP_EA(BF16Tag, 8, 3) AP_EA(BF16Tag, 10, 3) AP_EA(BF16Tag, 16, 2) }
+    if (dt == AP_F16) { AP_EA(F16Tag, 2, 3) AP_EA(F16Tag, 4, 3) AP_EA(F16Tag, 8, 3) AP_EA(F16Tag, 10, AP_EA_NB10) AP_EA(F16Tag, 16, 2) }
+    else { AP_EA(BF16Tag, 2, 3) AP_EA(BF16Tag, 4, 3) AP_EA(BF16Tag, 8, 3) AP_EA(BF16Tag, 10, AP_EA_NB10) AP_EA(BF16Tag, 16, 2) }
     set_error("expand: H*d=%d exceeds 8192", p.HD);
     return AP_ERR_UNSUPPORTED;
   } while (0);

@@ -17,10 +17,12 @@
 // copy skips one word after every 32 tokens: a thread's contiguous run of tokens then starts
 // in a different bank than its neighbours' and the walks are free of bank conflicts.  Group
 // ids replace the keys in that copy once they are known, and the ranks leave in a coalesced
-// pass.  All integer work, results are unique.
+// pass.  All integer work, results are unique.  Few, long rows take the same steps with a row
+// split over workgroups (the split_* kernels below).
 #include "ap_common.hpp"
 #include "lane_ops.hpp"
 
+#include <cstdlib>
 namespace ap {
 namespace {
 
@@ -37,6 +39,8 @@ struct SelectParams {
   int32_t* rank_out;
   int32_t* bucket_off;
   int32_t* bucket_idx;
+  uint32_t* split_ws;         // rows split over workgroups: per-row scratch (see SplitLayout), else null
+  int per;                    // ... and the tokens each thread owns there
 #ifdef AP_KERNEL_TIMERS
   unsigned long long* stamps;   // kernel studies: 16 time stamps of row 0's first and last thread (100 MHz counter)
 #endif
@@ -57,8 +61,8 @@ __device__ __forceinline__ uint32_t key_of(float m) {
 
 // Exclusive prefix sums over the workgroup (thread order) of the first n of N values per thread
 // at once (two barriers for all of them; n is the same for every thread, v[k] stays as it is
-// for k >= n).  wave_tot: N * kWaves ints.
-template <int N>
+// for k >= n).  NW waves per workgroup; wave_tot: N * NW ints.
+template <int N, int NW = kWaves>
 __device__ __forceinline__ void block_excl_scan_n(int (&v)[N], int n, int* wave_tot) {
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   int incl[N];
@@ -78,7 +82,7 @@ __device__ __forceinline__ void block_excl_scan_n(int (&v)[N], int n, int* wave_
   if (lane == 63) {
 #pragma unroll
     for (int k = 0; k < N; ++k)
-      if (k < n) wave_tot[k * kWaves + w] = incl[k];
+      if (k < n) wave_tot[k * NW + w] = incl[k];
   }
   __syncthreads();
 #pragma unroll
@@ -86,8 +90,8 @@ __device__ __forceinline__ void block_excl_scan_n(int (&v)[N], int n, int* wave_
     if (k < n) {
       int base = 0;
 #pragma unroll
-      for (int i = 0; i < kWaves; ++i) {
-        const int x = wave_tot[k * kWaves + i];
+      for (int i = 0; i < NW; ++i) {
+        const int x = wave_tot[k * NW + i];
         if (i < w) base += x;
       }
       v[k] = base + incl[k] - v[k];
@@ -97,6 +101,46 @@ __device__ __forceinline__ void block_excl_scan_n(int (&v)[N], int n, int* wave_
 
 constexpr int kCand = 256;             // candidate keys per boundary that the short cut after the first pass takes
 constexpr int kStagedMax = 32768;      // tokens whose keys fit the dynamic LDS slice (132 KiB with padding)
+
+// Rows split over workgroups (long rows, few of them): a workgroup of 256 threads owns a chunk of
+// 256 * per consecutive tokens, a thread `per` consecutive ones.  Per-row scratch in the caller's
+// workspace, in 32-bit words:
+//   hist   [G][4096]  first-digit histogram of every chunk
+//   ctl    [64]       candidate counters, the gave-up flag, and per boundary: first digit, position
+//                     still to find, kappa, quota
+//   cand   [7][cap]   low 20 key bits of the keys that share a boundary's first digit
+//   candt  [7][cap]   their token indices (cap: an eighth of the row, at least 4096)
+//   counts [G][8]     tokens of every group in every chunk
+constexpr int kSplitThreads = 256;
+constexpr int kSplitWaves = kSplitThreads / 64;
+constexpr int kSplitMaxChunks = 64;
+constexpr int kEqMax = 256;            // tokens per boundary that may share kappa itself
+constexpr int kStage = 2048;           // candidates of a boundary that are walked from LDS
+constexpr int kSplitMinT = 24576;      // rows at least this long ...
+constexpr int kSplitMaxB = 32;         // ... in batches of at most this many rows, or rows beyond kStagedMax
+constexpr int kCtlNcand = 0, kCtlGaveUp = 7, kCtlDigit = 8, kCtlNeed = 16, kCtlKappa = 24, kCtlQuota = 32;
+struct SplitLayout {
+  int G, cap;
+  size_t hist, ctl, cand, candt, counts, stride;
+};
+__host__ __device__ inline SplitLayout split_layout(int T, int per) {
+  SplitLayout L;
+  const int chunk = kSplitThreads * per;
+  L.G = (T + chunk - 1) / chunk;
+  L.hist = 0;
+  L.ctl = L.hist + (size_t)L.G * 4096;
+  L.cap = T / 8 < 4096 ? 4096 : (T / 8 + 63) / 64 * 64;
+  L.cand = L.ctl + 64;
+  L.candt = L.cand + (size_t)(kMaxF - 1) * L.cap;
+  L.counts = L.candt + (size_t)(kMaxF - 1) * L.cap;
+  L.stride = L.counts + (size_t)L.G * kMaxF;
+  return L;
+}
+// tokens per thread: eight, or as many as keep a row within kSplitMaxChunks chunks
+inline int split_per(int T) {
+  const int per = (T + kSplitThreads * kSplitMaxChunks - 1) / (kSplitThreads * kSplitMaxChunks);
+  return per < 8 ? 8 : (per + 7) / 8 * 8;
+}
 
 template <bool STAGED>
 __global__ void __launch_bounds__(kThreads) select_ranks_kernel(const SelectParams p) {
@@ -111,6 +155,9 @@ __global__ void __launch_bounds__(kThreads) select_ranks_kernel(const SelectPara
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int b = blockIdx.x, T = p.T, F = p.F, nb = F - 1;
   const float* m = p.mass + (size_t)b * T;
+  // after the split kernels: only the rows they gave up on (too many keys share a boundary's
+  // leading bits) are done here
+  if (p.split_ws && p.split_ws[split_layout(T, p.per).stride * b + split_layout(T, p.per).ctl + kCtlGaveUp] == 0u) return;
   AP_SELECT_STAMP(0);
   auto slot_of = [](int t) -> int { return t + (t >> 5); };      // one pad word per 32 tokens
   if (STAGED) {
@@ -371,6 +418,406 @@ __global__ void __launch_bounds__(kThreads) select_ranks_kernel(const SelectPara
   AP_SELECT_STAMP(15);
 }
 
+
+// ------------------------------------------------------------------------------------------
+// The same selection with a row split over workgroups, for batches too small to fill the chip
+// with one workgroup per row.  Four launches over grid (G chunks, B rows), 256 threads:
+//   split_hist    first-digit (12-bit) histogram of every chunk, to the workspace;
+//   split_cand    every workgroup adds the chunks' histograms up, finds each boundary's first
+//                 digit, and lists the keys of its chunk that share it (with their tokens);
+//   split_groups  every workgroup fixes the other 20 bits of each boundary's kappa from that
+//                 list (a wave per boundary, digits of 8, 8 and 4 bits), notes the tokens whose
+//                 key is kappa itself, gives its tokens their groups and counts them; a token
+//                 whose key equals kappa finds its position among the equal keys by counting the
+//                 noted tokens in front of it;
+//   split_emit    prefix sums of the chunks' group counts place every token in its group's
+//                 ascending index list.
+// A row where more than an eighth of the keys share a boundary's first digit, or more than
+// kEqMax tokens a boundary's kappa, raises a flag instead, and the one-workgroup kernel,
+// launched after these, does exactly the flagged rows.
+// ------------------------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t wave_suffix_sum(uint32_t v) {     // sum over lanes >= lane
+  const int lane = threadIdx.x & 63;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const uint32_t dn = (uint32_t)__shfl_down((int)v, o);
+    if (lane + o < 64) v += dn;
+  }
+  return v;
+}
+// One wave finds the digit that holds the k-th largest entry (1-based) of a histogram of NBINS
+// counters (4096 or 256), and the position left inside that digit.  False when k exceeds the total.
+template <int NBINS>
+__device__ __forceinline__ bool walk_digit(const uint32_t* h, uint32_t k, uint32_t& digit, uint32_t& rest) {
+  constexpr int per = NBINS / 64;
+  const int lane = threadIdx.x & 63;
+  uint32_t tot = 0;
+  for (int j = 0; j < per; ++j) tot += h[lane * per + ((j + lane) & (per - 1))];
+  const uint32_t incl = wave_suffix_sum(tot), above = incl - tot;
+  const unsigned long long owner = __ballot(above < k && k <= incl);
+  if (!owner) return false;
+  const int L = __ffsll(owner) - 1;
+  const uint32_t k2 = k - (uint32_t)__shfl((int)above, L);
+  const uint32_t c = lane < per ? h[L * per + lane] : 0u;
+  const uint32_t incl2 = wave_suffix_sum(c), above2 = incl2 - c;
+  const unsigned long long hit = __ballot(lane < per && above2 < k2 && k2 <= incl2);
+  if (!hit) return false;
+  const int Hh = __ffsll(hit) - 1;
+  digit = (uint32_t)(L * per + Hh);
+  rest = k2 - (uint32_t)__shfl((int)above2, Hh);
+  return true;
+}
+
+struct SplitParams {
+  const float* mass;
+  uint32_t* ws;
+  int T, F, per;
+  int32_t bound[kMaxF + 1];
+  int32_t grank[kMaxF];
+  int32_t* rank_out;
+  int32_t* bucket_off;
+  int32_t* bucket_idx;
+};
+
+// eight of a thread's keys at once (tokens t .. t + 7, those at or beyond t1 read as token t1 - 1)
+__device__ __forceinline__ void load_keys8(const float* m, int t, int t1, uint32_t (&k)[8]) {
+  float v[8];
+#pragma unroll
+  for (int u = 0; u < 8; ++u) v[u] = m[t + u < t1 ? t + u : t1 - 1];
+#pragma unroll
+  for (int u = 0; u < 8; ++u) k[u] = key_of(v[u]);
+}
+
+__global__ void __launch_bounds__(kSplitThreads) split_hist(const SplitParams p) {
+  __shared__ uint32_t h[4096];
+  const int tid = threadIdx.x, c = blockIdx.x, b = blockIdx.y, T = p.T;
+  const SplitLayout L = split_layout(T, p.per);
+  uint32_t* ws = p.ws + L.stride * b;
+  for (int i = tid; i < 4096; i += kSplitThreads) h[i] = 0u;
+  if (c == 0 && tid < 8) ws[L.ctl + tid] = 0u;                // candidate counters and the flag
+  __syncthreads();
+  const float* m = p.mass + (size_t)b * T;
+  const int t0 = min(T, (c * kSplitThreads + tid) * p.per), t1 = min(T, t0 + p.per);
+  for (int t = t0; t < t1; t += 8) {
+    uint32_t k[8];
+    load_keys8(m, t, t1, k);
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+      if (t + u < t1) atomicAdd(&h[k[u] >> 20], 1u);
+  }
+  __syncthreads();
+  uint32_t* dst = ws + L.hist + (size_t)c * 4096;
+  for (int i = tid; i < 4096; i += kSplitThreads) dst[i] = h[i];
+}
+
+__global__ void __launch_bounds__(kSplitThreads) split_cand(const SplitParams p) {
+  __shared__ __attribute__((aligned(16))) uint32_t h[4096];
+  __shared__ uint32_t s_digit[kMaxF - 1], s_need[kMaxF - 1];
+  __shared__ uint32_t s_cnt[kMaxF - 1], s_cnt2[kMaxF - 1], s_base[kMaxF - 1];
+  __shared__ int s_few;
+  const int tid = threadIdx.x, w = tid >> 6, c = blockIdx.x, b = blockIdx.y, T = p.T, nb = p.F - 1;
+  const SplitLayout L = split_layout(T, p.per);
+  uint32_t* ws = p.ws + L.stride * b;
+  // the row's histogram: sixteen counters per thread (four 16-byte words), the chunks' copies
+  // summed, eight chunks' loads in flight at a time
+  {
+    u32x4_t acc[4];
+    const u32x4_t zero = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) acc[i] = zero;
+    const u32x4_t* src = (const u32x4_t*)(ws + L.hist) + tid;
+    for (int g0 = 0; g0 < L.G; g0 += 8) {
+      u32x4_t v[8][4];
+#pragma unroll
+      for (int k = 0; k < 8; ++k)
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          v[k][i] = g0 + k < L.G ? src[(size_t)(g0 + k) * 1024 + i * kSplitThreads] : zero;
+#pragma unroll
+      for (int k = 0; k < 8; ++k)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) acc[i] += v[k][i];
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) *(u32x4_t*)&h[(i * kSplitThreads + tid) * 4] = acc[i];
+  }
+  if (tid == 0) s_few = 1;
+  if (tid < kMaxF - 1) { s_digit[tid] = kNone; s_need[tid] = 0u; s_cnt[tid] = 0u; s_cnt2[tid] = 0u; s_base[tid] = 0u; }
+  __syncthreads();
+  for (int g = w; g < nb; g += kSplitWaves) {                 // a wave per boundary
+    const int cut = p.bound[g + 1];
+    if (cut > 0 && cut < T) {
+      uint32_t digit = 0u, rest = 0u;
+      const bool ok = walk_digit<4096>(h, (uint32_t)cut, digit, rest);
+      if ((tid & 63) == 0) {
+        if (!ok || h[digit] > (uint32_t)L.cap) s_few = 0;
+        else { s_digit[g] = digit; s_need[g] = rest; }
+      }
+    }
+  }
+  __syncthreads();
+  if (!s_few) {
+    if (c == 0 && tid == 0) ws[L.ctl + kCtlGaveUp] = 1u;
+    return;
+  }
+  uint32_t dig[kMaxF - 1];
+#pragma unroll
+  for (int g = 0; g < kMaxF - 1; ++g) dig[g] = s_digit[g];     // kNone: no key has that first digit
+  if (c == 0 && tid < kMaxF - 1) {
+    ws[L.ctl + kCtlDigit + tid] = s_digit[tid];
+    ws[L.ctl + kCtlNeed + tid] = s_need[tid];
+  }
+  // the chunk's candidates are counted first, so that one addition per boundary reserves their
+  // places in the row's lists; the order inside a list is immaterial
+  const float* m = p.mass + (size_t)b * T;
+  const int t0 = min(T, (c * kSplitThreads + tid) * p.per), t1 = min(T, t0 + p.per);
+  for (int t = t0; t < t1; t += 8) {
+    uint32_t k[8];
+    load_keys8(m, t, t1, k);
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      if (t + u < t1) {
+#pragma unroll
+        for (int g = 0; g < kMaxF - 1; ++g)
+          if ((k[u] >> 20) == dig[g]) atomicAdd(&s_cnt[g], 1u);
+      }
+    }
+  }
+  __syncthreads();
+  if (tid < kMaxF - 1 && s_cnt[tid]) s_base[tid] = atomicAdd(&ws[L.ctl + kCtlNcand + tid], s_cnt[tid]);
+  __syncthreads();
+  for (int t = t0; t < t1; t += 8) {
+    uint32_t k[8];
+    load_keys8(m, t, t1, k);
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      if (t + u < t1) {
+#pragma unroll
+        for (int g = 0; g < kMaxF - 1; ++g) {
+          if ((k[u] >> 20) == dig[g]) {
+            const uint32_t at = s_base[g] + atomicAdd(&s_cnt2[g], 1u);
+            if (at < (uint32_t)L.cap) {                        // always true: the count was checked
+              ws[L.cand + (size_t)g * L.cap + at] = k[u] & 0xfffffu;
+              ws[L.candt + (size_t)g * L.cap + at] = (uint32_t)(t + u);
+            }
+          }
+        }
+      }
+    }
+  }
+}
+
+// The group of a token: the first boundary it lies in front of (membership is nested).  A token
+// whose key equals a boundary's kappa counts the listed tokens with that key in front of it.
+__device__ __forceinline__ int group_of(uint32_t key, int t, int nb, const uint32_t (&kappa)[kMaxF - 1],
+                                        const uint32_t (&quota)[kMaxF - 1], const uint32_t* s_eq,
+                                        const uint32_t* s_neq) {
+  int grp = nb;
+#pragma unroll
+  for (int g = kMaxF - 2; g >= 0; --g) {
+    if (g < nb) {
+      bool in_front = key > kappa[g];
+      if (key == kappa[g]) {
+        uint32_t pos = 0;
+        const uint32_t n = s_neq[g];
+        for (uint32_t i = 0; i < n; ++i) pos += s_eq[g * kEqMax + i] < (uint32_t)t ? 1u : 0u;
+        in_front = pos < quota[g];
+      }
+      if (in_front) grp = g;
+    }
+  }
+  return grp;
+}
+
+__global__ void __launch_bounds__(kSplitThreads) split_groups(const SplitParams p) {
+  __shared__ uint32_t hw[kSplitWaves][256];                    // a histogram per wave
+  __shared__ uint32_t s_cl[kSplitWaves][kStage];               // ... and its boundary's candidates
+  __shared__ uint32_t s_eq[(kMaxF - 1) * kEqMax];              // tokens whose key equals kappa
+  __shared__ uint32_t s_neq[kMaxF - 1], s_kappa[kMaxF - 1], s_quota[kMaxF - 1];
+  __shared__ int s_cnt[kMaxF];
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int c = blockIdx.x, b = blockIdx.y, T = p.T, F = p.F, nb = F - 1;
+  const SplitLayout L = split_layout(T, p.per);
+  uint32_t* ws = p.ws + L.stride * b;
+  if (ws[L.ctl + kCtlGaveUp]) return;
+  if (tid < kMaxF) s_cnt[tid] = 0;
+  if (tid < kMaxF - 1) {
+    const int cut = tid < nb ? p.bound[tid + 1] : 0;
+    s_neq[tid] = 0u;
+    // a cut at 0: nobody in front; a cut at T: everybody
+    s_kappa[tid] = (tid < nb && cut >= T) ? 0u : kNone;
+    s_quota[tid] = (tid < nb && cut >= T) ? (uint32_t)T : 0u;
+  }
+  __syncthreads();
+  for (int g = w; g < nb; g += kSplitWaves) {
+    // a wave per boundary: the other 20 bits of kappa, by digits of 8, 8 and 4 bits over the
+    // boundary's candidate list
+    const int cut = p.bound[g + 1];
+    if (cut > 0 && cut < T) {
+      const uint32_t n = min(ws[L.ctl + kCtlNcand + g], (uint32_t)L.cap);
+      const uint32_t* cl = ws + L.cand + (size_t)g * L.cap;
+      const uint32_t* ct = ws + L.candt + (size_t)g * L.cap;
+      uint32_t low = 0u, need = ws[L.ctl + kCtlNeed + g];
+      const uint32_t digit1 = ws[L.ctl + kCtlDigit + g];
+      bool ok = true;
+      auto resolve = [&](auto cand_at) {
+#pragma unroll 1
+        for (int pass = 0; pass < 3; ++pass) {
+          const int shift = pass == 0 ? 12 : (pass == 1 ? 4 : 0);
+          const int width = pass == 2 ? 4 : 8;
+          // the wave's own histogram: its LDS operations complete in program order
+          for (int i = lane; i < 256; i += 64) hw[w][i] = 0u;
+          __builtin_amdgcn_wave_barrier();
+          for (uint32_t i0 = lane; i0 < n; i0 += 512) {          // eight loads in flight
+            uint32_t v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = i0 + 64 * u < n ? cand_at(i0 + 64 * u) : 0u;
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+              if (i0 + 64 * u < n && (v[u] >> (shift + width)) == (low >> (shift + width)))
+                atomicAdd(&hw[w][(v[u] >> shift) & ((1u << width) - 1u)], 1u);
+          }
+          __builtin_amdgcn_wave_barrier();
+          uint32_t digit = 0u, rest = 0u;
+          ok = ok && walk_digit<256>(hw[w], need, digit, rest);
+          low |= digit << shift;
+          need = rest;
+        }
+        for (uint32_t i0 = lane; i0 < n; i0 += 512) {
+          uint32_t v[8];
+#pragma unroll
+          for (int u = 0; u < 8; ++u) v[u] = i0 + 64 * u < n ? cand_at(i0 + 64 * u) : kNone;
+#pragma unroll
+          for (int u = 0; u < 8; ++u) {
+            if (v[u] == low) {                                   // kNone is no 20-bit value
+              const uint32_t at = atomicAdd(&s_neq[g], 1u);
+              if (at < (uint32_t)kEqMax) s_eq[g * kEqMax + at] = ct[i0 + 64 * u];
+            }
+          }
+        }
+      };
+      if (n <= (uint32_t)kStage) {
+        // a list this short moves to LDS first (sixteen loads in flight): the four walks over it
+        // then cost no trips to memory
+        for (uint32_t i0 = lane; i0 < n; i0 += 1024) {
+          uint32_t v[16];
+#pragma unroll
+          for (int u = 0; u < 16; ++u) v[u] = i0 + 64 * u < n ? cl[i0 + 64 * u] : 0u;
+#pragma unroll
+          for (int u = 0; u < 16; ++u)
+            if (i0 + 64 * u < n) s_cl[w][i0 + 64 * u] = v[u];
+        }
+        __builtin_amdgcn_wave_barrier();
+        resolve([&](uint32_t i) { return s_cl[w][i]; });
+      } else {
+        resolve([&](uint32_t i) { return cl[i]; });
+      }
+      if (lane == 0) {
+        s_kappa[g] = (digit1 << 20) | low;
+        s_quota[g] = need;
+        if (!ok) s_neq[g] = kEqMax + 1;                        // cannot happen; treated as giving up
+      }
+    }
+  }
+  __syncthreads();
+  bool fits = true;
+#pragma unroll
+  for (int g = 0; g < kMaxF - 1; ++g) fits = fits && s_neq[g] <= (uint32_t)kEqMax;
+  if (!fits) {                                                 // every workgroup of the row sees the same
+    if (c == 0 && tid == 0) ws[L.ctl + kCtlGaveUp] = 1u;
+    return;
+  }
+  uint32_t kappa[kMaxF - 1], quota[kMaxF - 1];
+#pragma unroll
+  for (int g = 0; g < kMaxF - 1; ++g) { kappa[g] = s_kappa[g]; quota[g] = s_quota[g]; }
+  const float* m = p.mass + (size_t)b * T;
+  int32_t* rank_row = p.rank_out + (size_t)b * T;
+  const int t0 = min(T, (c * kSplitThreads + tid) * p.per), t1 = min(T, t0 + p.per);
+  int cnt[kMaxF];
+#pragma unroll
+  for (int g = 0; g < kMaxF; ++g) cnt[g] = 0;
+  for (int t = t0; t < t1; t += 8) {
+    uint32_t k[8];
+    load_keys8(m, t, t1, k);
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      if (t + u < t1) {
+        const int grp = group_of(k[u], t + u, nb, kappa, quota, s_eq, s_neq);
+        rank_row[t + u] = grp;                                // group id for now, rank in split_emit
+#pragma unroll
+        for (int g = 0; g < kMaxF; ++g) cnt[g] += (grp == g) ? 1 : 0;
+      }
+    }
+  }
+#pragma unroll
+  for (int g = 0; g < kMaxF; ++g)
+    if (g < F && cnt[g]) atomicAdd(&s_cnt[g], cnt[g]);
+  __syncthreads();
+  if (tid < kMaxF) ws[L.counts + (size_t)c * kMaxF + tid] = (uint32_t)s_cnt[tid];
+}
+
+__global__ void __launch_bounds__(kSplitThreads) split_emit(const SplitParams p) {
+  __shared__ int wave_tot[kMaxF * kSplitWaves];
+  __shared__ int s_base[kMaxF];
+  const int tid = threadIdx.x;
+  const int c = blockIdx.x, b = blockIdx.y, T = p.T, F = p.F;
+  const SplitLayout L = split_layout(T, p.per);
+  const uint32_t* ws = p.ws + L.stride * b;
+  if (ws[L.ctl + kCtlGaveUp]) return;
+  if (tid < kMaxF) {
+    int base = 0;
+#pragma unroll
+    for (int g = 0; g < kMaxF; ++g) base = tid == g ? p.bound[g] : base;
+    for (int k0 = 0; k0 < c; k0 += 8) {                        // eight loads in flight
+      uint32_t v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[u] = k0 + u < c ? ws[L.counts + (size_t)(k0 + u) * kMaxF + tid] : 0u;
+#pragma unroll
+      for (int u = 0; u < 8; ++u) base += (int)v[u];
+    }
+    s_base[tid] = base;
+  }
+  int32_t* rank_row = p.rank_out + (size_t)b * T;
+  int32_t* idx_row = p.bucket_idx + (size_t)b * T;
+  const int t0 = min(T, (c * kSplitThreads + tid) * p.per), t1 = min(T, t0 + p.per);
+  int cnt[kMaxF];
+#pragma unroll
+  for (int g = 0; g < kMaxF; ++g) cnt[g] = 0;
+  auto load_groups8 = [&](int t, int (&grp)[8]) {
+#pragma unroll
+    for (int u = 0; u < 8; ++u) grp[u] = rank_row[t + u < t1 ? t + u : t1 - 1];
+  };
+  for (int t = t0; t < t1; t += 8) {
+    int grp[8];
+    load_groups8(t, grp);
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+#pragma unroll
+      for (int g = 0; g < kMaxF; ++g) cnt[g] += (t + u < t1 && grp[u] == g) ? 1 : 0;
+  }
+  block_excl_scan_n<kMaxF, kSplitWaves>(cnt, F, wave_tot);      // its barriers also publish s_base
+  for (int t = t0; t < t1; t += 8) {
+    int grp[8];
+    load_groups8(t, grp);
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      if (t + u < t1) {
+        int slot = T, rk = 0;
+#pragma unroll
+        for (int g = 0; g < kMaxF; ++g) {
+          if (g < F && grp[u] == g) { slot = s_base[g] + cnt[g]; rk = p.grank[g]; cnt[g] += 1; }
+        }
+        rank_row[t + u] = rk;
+        if (slot < T) idx_row[slot] = t + u;   // always true; keeps a logic error inside the buffer
+      }
+    }
+  }
+  int cut = 0;
+#pragma unroll
+  for (int g = 0; g <= kMaxF; ++g) cut = tid == g ? p.bound[g] : cut;
+  if (c == 0 && tid <= F) p.bucket_off[(size_t)b * (F + 1) + tid] = cut;
+}
+
 // Importance update of Eq. 1 for one new query: the attention weights of the query, averaged
 // over the heads, enter the moving average.  scores [B][T_cap][H]: the H logits of a token are
 // contiguous.
@@ -449,7 +896,26 @@ ap_status launch_update_importance(const float* scores, const float* lse, float*
   return check_launch("ap_update_importance");
 }
 
-size_t select_workspace(int, int, int) { return 256; }   // every intermediate lives in LDS
+// One workgroup per row fills the chip when there are many rows, and a short row is done before
+// four more launches would be (each hands its results to the next through memory: about 45 us in
+// all, whatever the length): the split is for few, long rows (measured at four groups: 32768
+// tokens 45-55 us against 92-96, 16384 tokens about even), and for rows too long for the one
+// workgroup's LDS copy, which it would otherwise re-read from memory seven times (131072 tokens:
+// 61-95 us against 650).
+static bool split_applies(int B, int T) {
+#ifdef AP_KERNEL_TIMERS
+  return false;                          // the stamps live where the split's scratch would
+#else
+#ifdef AP_SELECT_SPLIT_ENV
+  if (const char* e = getenv("AP_SELECT_SPLIT")) return atoi(e) != 0;
+#endif
+  return T > kStagedMax || (T >= kSplitMinT && B <= kSplitMaxB);
+#endif
+}
+size_t select_workspace(int B, int T, int) {
+  // without the split every intermediate lives in LDS
+  return split_applies(B, T) ? 256 + (size_t)B * split_layout(T, split_per(T)).stride * 4 : 256;
+}
 
 ap_status launch_select_ranks(const float* mass, int B, int T, int F, const int32_t* group_rank,
                               const int32_t* cum_num, int32_t den, int32_t* rank_out,
@@ -468,11 +934,31 @@ ap_status launch_select_ranks(const float* mass, int B, int T, int F, const int3
   p.rank_out = rank_out;
   p.bucket_off = bucket_off;
   p.bucket_idx = bucket_idx;
+  p.split_ws = nullptr;
+  p.per = 0;
 #ifdef AP_KERNEL_TIMERS
   p.stamps = (unsigned long long*)ws;
-#else
-  (void)ws;
 #endif
+  if (split_applies(B, T)) {
+    SplitParams sp;
+    sp.mass = mass;
+    sp.ws = (uint32_t*)ws;
+    sp.T = T;
+    sp.F = F;
+    sp.per = split_per(T);
+    for (int g = 0; g <= kMaxF; ++g) sp.bound[g] = p.bound[g];
+    for (int g = 0; g < kMaxF; ++g) sp.grank[g] = p.grank[g];
+    sp.rank_out = rank_out;
+    sp.bucket_off = bucket_off;
+    sp.bucket_idx = bucket_idx;
+    const dim3 grid(split_layout(T, sp.per).G, B);
+    hipLaunchKernelGGL(split_hist, grid, dim3(kSplitThreads), 0, stream, sp);
+    hipLaunchKernelGGL(split_cand, grid, dim3(kSplitThreads), 0, stream, sp);
+    hipLaunchKernelGGL(split_groups, grid, dim3(kSplitThreads), 0, stream, sp);
+    hipLaunchKernelGGL(split_emit, grid, dim3(kSplitThreads), 0, stream, sp);
+    p.split_ws = sp.ws;               // the one-workgroup kernel below: flagged rows only
+    p.per = sp.per;
+  }
   if (T <= kStagedMax) {
     static bool attr_set = false;
     if (!attr_set) {

@@ -73,3 +73,66 @@ def test_select_group_shapes():
     check(mass, (512, 256, 128), (0, 5, 5), 5, "empty first and last group")
     check(mass, (512, 512, 448, 384, 320, 256, 128, 64), (1, 2, 3, 5, 8, 13, 21, 34), 34, "F=8 uneven")
     check(mass[:, :3], (512, 256, 128, 64), (1, 2, 3, 4), 4, "fewer tokens than groups")
+
+
+# ---- long rows in small batches (24576 tokens and more in at most 32 rows, or any row beyond
+#      32768 tokens): the row is split over workgroups.  Uniform random values put at most a
+#      sixteenth of the keys on one leading digit, inside the candidate lists; coarse values and long
+#      runs of equal keys are what the lists cannot hold.
+def test_select_split_rows_random_and_odd_lengths():
+    for T, B in ((24576, 1), (25001, 2), (32768, 8), (40000, 3), (70001, 1), (200000, 2), (33000, 40)):
+        rng = wl.rng_for(24, T)
+        mass = rng.random((B, T)).astype(np.float32)
+        check(mass, *QUART, "split rows, uniform random")
+    rng = wl.rng_for(25)
+    mass = (rng.standard_exponential((2, 30000)) * 1e-4).astype(np.float32)
+    check(mass, (512, 512, 448, 384, 320, 256, 128, 64), (1, 2, 3, 5, 8, 13, 21, 34), 34, "split rows, F=8 uneven")
+    check(mass, (640,), (1,), 1, "split rows, F=1")
+    check(mass, (512, 256, 128), (0, 5, 5), 5, "split rows, empty first and last group")
+    check(mass, (640, 64), (1, 10), 10, "split rows, paper-style F=2")
+
+
+def test_select_split_rows_equal_keys_at_the_cuts():
+    """A few tokens share the key a cut falls on: their order is by token index, and which of
+    them lie in front of the cut is decided by counting the listed equal keys."""
+    rng = wl.rng_for(26)
+    T = 27001
+    mass = rng.random((2, T)).astype(np.float32)
+    for b in range(2):
+        order = np.argsort(-mass[b], kind="stable")
+        for cut in (T // 4, T // 2, 3 * T // 4):
+            v = mass[b, order[cut]]
+            # six more tokens with the cut's value, spread over the row (several chunks)
+            mass[b, rng.choice(T, 6, replace=False)] = v
+    check(mass, *QUART, "split rows, equal keys at the cuts")
+    mass[1, 100:140] = mass[1, 5000]                                         # forty equal keys in a row
+    check(mass, *QUART, "split rows, a run of equal keys")
+    mass[0, 2000:2300] = np.sort(mass[0])[T // 2]                            # 300 tokens on the middle cut's key:
+    check(mass, *QUART, "split rows, more equal keys than are listed")      # that row goes to one workgroup
+
+
+def test_select_split_rows_give_way_to_one_workgroup_on_heavy_ties():
+    """More keys share a cut's leading bits than the candidate list holds: the row is flagged and
+    done by the one-workgroup kernel; other rows of the batch stay on the split path."""
+    rng = wl.rng_for(27)
+    T = 32768
+    mass = rng.random((3, T)).astype(np.float32)
+    mass[1] = np.floor(mass[1] * 16) / 16                                    # 16 distinct values
+    check(mass, *QUART, "split rows, one row of coarse values")
+    check(np.full((2, T), 0.25, np.float32), *QUART, "split rows, all equal")
+    z = np.zeros((1, T), np.float32)
+    z[0, ::3] = -0.0
+    z[0, 7] = 1.0
+    check(z, *QUART, "split rows, zeros of both signs")
+    # the workspace is reused: a flagged call is followed by a clean one on the same buffer
+    from paper_2603_23914_amd import binding as ap
+    ws = workspace(ap.ap_select_workspace_bytes(1, T, 4))
+    rank = torch.empty((1, T), dtype=torch.int32, device="cuda")
+    off = torch.empty((1, 5), dtype=torch.int32, device="cuda")
+    idx = torch.empty((1, T), dtype=torch.int32, device="cuda")
+    for row in (np.full((1, T), 0.5, np.float32), mass[:1], mass[1:2], mass[2:3]):
+        ap.ap_select_ranks(torch.from_numpy(row).cuda(), QUART[0], QUART[1], QUART[2], rank, off, idx, ws)
+        torch.cuda.synchronize()
+        r_ref, o_ref, i_ref = oracle.select_ranks(row[0], *QUART)
+        assert (rank[0].cpu().numpy() == r_ref).all() and (idx[0].cpu().numpy() == i_ref).all()
+        assert (off[0].cpu().numpy() == o_ref).all()
