@@ -298,16 +298,17 @@ ap_status ap_decode_attn_static(const void* q, const void* Ck, const void* Cv,
  *     ap_compact(k_new, v_new, Bk, Bv, Ck, Cv, ..., n = 1, row0 = T - 1, ...)
  *     ap_decode_attn(q, Ck, Cv, ..., T, ...)
  * compute, but reads each basis once instead of twice: the key row's projection
- * shares its pass over B_k with the fold of the query, and (with uniform rank)
- * the value row's projection shares its pass over B_v with the expansion of the
- * output, the new token's own contribution being added there.  The appended key
+ * shares its pass over B_k with the fold of the query, and the value row's
+ * projection shares its pass over B_v with the expansion of the output, the new
+ * token's own contribution being added there (limited to the basis rows below its
+ * own value rank when per-token ranks are given).  The appended key
  * row has the same bits as ap_compact's; the value row and the outputs agree with
  * the two-call sequence up to the order of fp32 additions.
  *   k_new, v_new  [B, HD] dtype dt: the new token's merged-head key and value rows.
  *   Ck, Cv        [B, T_cap, r] dtype dt: row T-1 is WRITTEN, rows 0..T-1 attended.
  *   T             tokens cached after the append (1 <= T <= T_cap).
  * AP_F16 / AP_BF16 only (no int8 coefficients).  Rank arrays and group lists, when
- * given, must already cover the new token (the value basis is then read twice).
+ * given, must already cover the new token.
  * Everything else as ap_decode_attn; the workspace query is ap_decode_workspace_bytes.
  * ---------------------------------------------------------------------- */
 ap_status ap_decode_step(const void* q, const void* k_new, const void* v_new, void* Ck, void* Cv,
@@ -436,7 +437,7 @@ ap_status ap_valueonly_attn(const void* q, const void* K, const void* Cv, const 
 
 /* ------------------------------------------------------------------------
  * Tuning of ap_decode_step (same results either way, up to fp32 summation
- * order).  A fused step at uniform rank can produce the new value row inside
+ * order).  A fused step can produce the new value row inside
  * its expansion pass over B_v (B_v is then read once per step; the pass writes
  * per-row-block sums that a small extra kernel adds up), or append it in a pass
  * of its own that runs in the same launch as the key row's (B_v is read twice,

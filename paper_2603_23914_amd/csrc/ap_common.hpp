@@ -151,11 +151,13 @@ ap_status launch_basis_rows(ap_dtype dt, const void* Bm, int64_t bstride, const 
 int expand_row_blocks(int B, int r);   // row blocks (= partial output slices) of expand_append
 ap_status launch_expand_append(ap_dtype dt, bool out_f32, const void* Bv, int64_t bstride,
                                const void* v_new, void* Cv, const float* part_ml,
-                               const float* part_U, const float* pnew, float* pout, void* out,
+                               const float* part_U, const float* pnew, const int* pnew_split,
+                               const int32_t* rank_v, float* pout, void* out,
                                float* lse, int B, int H, int d, int r, int T, int T_cap, int nsplit,
                                hipStream_t stream);
 ap_status launch_merge_splits(const float* part_ml, const float* part_U, float* out_ml, float* out_U,
-                              float* pnew, int B, int H, int r, int S, hipStream_t stream);
+                              float* pnew, const int* pnew_split, int B, int H, int r, int S,
+                              hipStream_t stream);
 ap_status launch_merge_expand(ap_dtype dt, bool out_f32, const float* part_ml, const float* part_U,
                               const void* Bv, int64_t bstride, void* out, float* lse, int B, int H,
                               int H_kv, int d, int r, int nsplit, hipStream_t stream);

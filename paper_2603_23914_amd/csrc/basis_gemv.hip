@@ -339,7 +339,9 @@ struct ExpandParams {
   uint16_t* Cv;             // [B][T_cap][r]: row T-1 is written
   const float* part_ml;     // [B][S][H][2] (reference exponent, sum) over all T tokens
   const float* part_U;      // [B][S][H][r] over tokens 0 .. T-2
-  const float* pnew;        // [B][H] weight of token T-1 relative to split S-1's reference
+  const float* pnew;        // [B][H] weight of token T-1 relative to the reference of the split that holds it
+  const int* pnew_split;    // [B] that split, or null: the last one
+  const int32_t* rank_v;    // [B][T] per-token value ranks, or null: the new token counts at rank r
   float* pout;              // [B][nob][HD] per-row-block column sums
   float* lse;               // [B][H] or null
   int H, d, HD, r, T, T_cap, nsplit, rpw, nob;
@@ -407,6 +409,7 @@ __global__ void __launch_bounds__(128) expand_append(const ExpandParams p) {
       for (int u = 0; u < 8; ++u) m = fmaxf(m, v[u]);
     }
     float L = 0.f, wlast = 0.f;
+    const int snew = p.pnew_split ? p.pnew_split[b] : S - 1;
     for (int s0 = 0; s0 < S; s0 += 8) {
       float v[8], lv[8];
 #pragma unroll
@@ -421,7 +424,7 @@ __global__ void __launch_bounds__(128) expand_append(const ExpandParams p) {
           const float ws = fast_exp2(v[u] - m);
           L += lv[u] * ws;
           if (wsp_fits) wsp[(s0 + u) * H + h] = ws;
-          wlast = ws;
+          if (s0 + u == snew) wlast = ws;
         }
       }
     }
@@ -485,6 +488,12 @@ __global__ void __launch_bounds__(128) expand_append(const ExpandParams p) {
   }
   __syncthreads();
 
+  // the new token's own value rank limits the rows in which its coefficient counts
+  int rvn = r;
+  if (p.rank_v) {
+    rvn = p.rank_v[(size_t)b * p.T + p.T - 1];
+    rvn = rvn < 0 ? 0 : (rvn < r ? rvn : r);
+  }
   const int dshift = 31 - __builtin_clz((unsigned)p.d);
   float bt[KH];
   int arow[KH];                                // A row (head) of this lane's chunk in every pass
@@ -514,7 +523,7 @@ __global__ void __launch_bounds__(128) expand_append(const ExpandParams p) {
     const float c = slot[0] + slot[1];
     const uint16_t cbits = f32_to_bits(c, Tag{});
     if (lane == 0 && half == 0 && live) p.Cv[((size_t)b * p.T_cap + p.T - 1) * r + j0 + i] = cbits;
-    const float cr = live ? bits_to_f32(cbits, Tag{}) : 0.f;   // the stored (rounded) coefficient
+    const float cr = live && j0 + i < rvn ? bits_to_f32(cbits, Tag{}) : 0.f;   // the stored (rounded) coefficient
     const int jc = live ? i : 0;
 #pragma unroll
     for (int pp = 0; pp < KH; ++pp) {
@@ -583,7 +592,7 @@ reduce_out(const float* __restrict__ pout, void* __restrict__ out, int HD, int n
 __global__ void __launch_bounds__(256)
 merge_splits(const float* __restrict__ part_ml, const float* __restrict__ part_U,
              float* __restrict__ out_ml, float* __restrict__ out_U, float* __restrict__ pnew,
-             int H, int r, int S) {
+             const int* __restrict__ pnew_split, int H, int r, int S) {
   extern __shared__ __attribute__((aligned(16))) float lds_ms[];   // [S] weights, then [4][64]
   __shared__ float red[8];
   const int tid = threadIdx.x, lane = tid & 63, grp = tid >> 6;
@@ -630,7 +639,7 @@ merge_splits(const float* __restrict__ part_ml, const float* __restrict__ part_U
   if (blockIdx.x == 0 && tid == 0) {
     out_ml[((size_t)b * H + h) * 2] = m;
     out_ml[((size_t)b * H + h) * 2 + 1] = L;
-    if (pnew) pnew[(size_t)b * H + h] *= wgt[S - 1];        // weight of the last split's reference
+    if (pnew) pnew[(size_t)b * H + h] *= wgt[pnew_split ? pnew_split[b] : S - 1];   // its split's weight
   }
 }
 
@@ -729,10 +738,11 @@ int expand_rows_per_pair(int B, int r) {
 }
 
 ap_status launch_merge_splits(const float* part_ml, const float* part_U, float* out_ml, float* out_U,
-                              float* pnew, int B, int H, int r, int S, hipStream_t stream) {
+                              float* pnew, const int* pnew_split, int B, int H, int r, int S,
+                              hipStream_t stream) {
   const size_t lds = ((size_t)S + 256) * 4;
   hipLaunchKernelGGL(merge_splits, dim3((r + 63) / 64, H, B), dim3(256), lds, stream, part_ml, part_U,
-                     out_ml, out_U, pnew, H, r, S);
+                     out_ml, out_U, pnew, pnew_split, H, r, S);
   return AP_OK;
 }
 int expand_row_blocks(int B, int r) { return (r + expand_rows_per_pair(B, r) - 1) / expand_rows_per_pair(B, r); }
@@ -742,11 +752,12 @@ int expand_row_blocks(int B, int r) { return (r + expand_rows_per_pair(B, r) - 1
 #endif
 ap_status launch_expand_append(ap_dtype dt, bool out_f32, const void* Bv, int64_t bstride,
                                const void* v_new, void* Cv, const float* part_ml,
-                               const float* part_U, const float* pnew, float* pout, void* out,
+                               const float* part_U, const float* pnew, const int* pnew_split,
+                               const int32_t* rank_v, float* pout, void* out,
                                float* lse, int B, int H, int d, int r, int T, int T_cap, int nsplit,
                                hipStream_t stream) {
   ExpandParams p{(const uint16_t*)Bv, bstride, (const uint16_t*)v_new, (uint16_t*)Cv, part_ml, part_U,
-                 pnew, pout, lse, H, d, H * d, r, T, T_cap, nsplit, expand_rows_per_pair(B, r),
+                 pnew, pnew_split, rank_v, pout, lse, H, d, H * d, r, T, T_cap, nsplit, expand_rows_per_pair(B, r),
                  expand_row_blocks(B, r)};
   const dim3 grid(p.nob, B);
   const size_t lds = ((size_t)H * (p.rpw + 1) + 3 * (size_t)H + 4 + (nsplit * H <= 4096 ? (size_t)nsplit * H : 0)) * 4;

@@ -418,7 +418,8 @@ struct AttnParams {
   // fused decode step: the newest token (row T-1) is scored like every other, but its value
   // row does not exist yet; its softmax weight is exported and the expansion pass adds it
   int defer_v;          // 0 or 1
-  float* pnew;          // [B][H] weight of token T-1 relative to the last split's reference
+  float* pnew;          // [B][H] weight of token T-1 relative to the reference of the split that holds it
+  int* pnew_split;      // [B] ... and which split that is
   float* scores;        // [B][T_cap][H] scaled logits in natural-log units, or null
   int dbg;              // kernel studies (AP_KERNEL_TIMERS builds only, else 0): 1 = no loads,
                         // 2 = no math, 4 = phase timers, 8 = per-tile stamps
@@ -491,11 +492,13 @@ struct WaveCtx {
   float* abuf;       // [16*MT] rescale factors
   uint16_t* vsb;     // I8: [2][r/64][32] value scales of the tile in flight (fp16 bits)
   int* idxb;         // RAGGED: [ntl][32] token index of every tile slot (tail slots repeat the last)
-  int* meta;         // RAGGED: [ntl][4] = tokens in the tile, key rank, value rank, unused
+  int* meta;         // RAGGED: [ntl][4] = tokens in the tile, key rank, value rank, 1 + slot of the
+                     // deferred newest token (0: not in this tile)
   uint32_t row_bytes;
   int t_lo, ntl;     // first tile and number of tiles of this split
   int Tv;            // value rows that exist: T, or T-1 while the newest token's row is deferred
   float* pnew;
+  int* pnew_split;
   float* scores;     // this sequence's [T_cap][H] logits, or null
   int T_cap;
   // softmax ownership: lane = 8*head_local + slot, slot = 4*tt + gg covers tokens
@@ -513,6 +516,7 @@ struct WaveCtx {
     wg_coords(nsplit, uni(p.xcd_aware), b, s);
     Tv = T - uni(p.defer_v);
     pnew = uni_ptr(p.pnew);
+    pnew_split = uni_ptr(p.pnew_split);
     T_cap = uni(p.T_cap);
     scores = uni_ptr(p.scores);
     if (scores) scores += (size_t)b * H * T_cap;
@@ -592,6 +596,9 @@ struct WaveCtx {
       int tok = bidx[pos];
       tok = tok < 0 ? 0 : (tok < T ? tok : T - 1);
       idxb[e] = tok;
+      // the 32 slots of a tile are 32 consecutive lanes: the slot of the deferred newest token
+      const unsigned long long hit = __ballot(Tv != T && tok == T - 1 && l < cnt);
+      const uint32_t hit32 = (uint32_t)((lane & 32) ? hit >> 32 : hit);
       if (l == 0) {
         int rk = rk_arr ? rk_arr[(size_t)b * T + tok] : r;
         int rv = rv_arr ? rv_arr[(size_t)b * T + tok] : r;
@@ -600,7 +607,7 @@ struct WaveCtx {
         meta[4 * i + 0] = cnt;
         meta[4 * i + 1] = rk;
         meta[4 * i + 2] = rv;
-        meta[4 * i + 3] = 0;
+        meta[4 * i + 3] = hit32 ? __ffs((int)hit32) : 0;
       }
     }
     wg_barrier();
@@ -619,7 +626,8 @@ struct WaveCtx {
 
   // Slot of the deferred newest token in local tile t (outside [0, 32): not in this tile).
   __device__ __forceinline__ int tile_new(int t) const {
-    if (RAGGED || Tv == T || (TS && t >= ntl)) return -1;
+    if (Tv == T || (TS && t >= ntl)) return -1;
+    if (RAGGED) return uni(meta[4 * t + 3]) - 1;
     return T - 1 - gtile(t) * kTile;
   }
 
@@ -672,7 +680,10 @@ struct WaveCtx {
       if (li == 1) { pdef = p1; p1 = 0.f; }
       if (li == 2) { pdef = p2; p2 = 0.f; }
       if (li == 3) { pdef = p3; p3 = 0.f; }
-      if (li >= 0 && li < 4 && o_hh < H) pnew[(size_t)b * H + o_hh] = pdef;
+      if (li >= 0 && li < 4 && o_hh < H) {
+        pnew[(size_t)b * H + o_hh] = pdef;
+        if (o_hh == 0) pnew_split[b] = s;
+      }
     }
     u32x2_t hi, lo = {0, 0};
     hi[0] = cvt_pack(p0, p1, Tag{});
@@ -756,7 +767,10 @@ struct WaveCtx {
         if (li == 1) { pdef = p1; p1 = 0.f; }
         if (li == 2) { pdef = p2; p2 = 0.f; }
         if (li == 3) { pdef = p3; p3 = 0.f; }
-        if (li >= 0 && li < 4 && o_hh < H) pnew[(size_t)b * H + o_hh] = pdef;
+        if (li >= 0 && li < 4 && o_hh < H) {
+          pnew[(size_t)b * H + o_hh] = pdef;
+          if (o_hh == 0) pnew_split[b] = s;
+        }
       }
       u32x2_t hi, lo = {0, 0};
       hi[0] = cvt_pack(p0, p1, Tag{});
@@ -1127,7 +1141,9 @@ __device__ __forceinline__ void sum_role(const AttnParams& p) {
           if (blk < cx.nblk) {
             const int row = (int)((slot_row[k >> 2] >> (8 * (k & 3))) & 0xffu);
             const uint32_t c = (slot_chk[k >> 2] >> (8 * (k & 3))) & 0xffu;
-            const uint32_t off = (uint32_t)ix[row] * cx.row_bytes + (c < rv8 ? c * 16u : 0u);
+            int tokv = ix[row];
+            tokv = tokv < cx.Tv ? tokv : cx.Tv - 1;           // a deferred row is not there yet: weight 0
+            const uint32_t off = (uint32_t)tokv * cx.row_bytes + (c < rv8 ? c * 16u : 0u);
             dma16(Cv_b + off, dst + blk * 1024);
           }
         }
@@ -1433,7 +1449,7 @@ WsLayout ws_layout(int B, int H, int d, int T, int r) {
   w.po = off;                              // per-row-block output sums of a fused step
   off += round_up((size_t)B * expand_row_blocks(B, r) * H * d * 4, 256);
   w.pn = off;                              // the newest token's softmax weights of a fused step
-  off += round_up((size_t)B * H * 4, 256);
+  off += round_up((size_t)B * H * 4 + (size_t)B * 4, 256);   // ... and the split that holds it
   w.mml = off;                             // many splits: merged (m, l) and U as a single split
   off += round_up((size_t)B * H * 2 * 4, 256);
   w.mu = off;
@@ -1547,7 +1563,7 @@ ap_status dispatch_attn(const AttnParams& p, int B, hipStream_t stream) {
 template <class Tag, bool SPLIT>
 ap_status run_decode(const DecodeArgs& a) {
   const int Hp = (a.H + 15) / 16 * 16;
-  // A fused step with uniform rank scores all T tokens in attn_partial but leaves the newest
+  // A fused step scores all T tokens in attn_partial but leaves the newest
   // token's value row to the expansion pass over B_v, which produces that row and adds its
   // contribution: B_v is read once per step instead of twice.
   const int Hkv = a.H_kv;
@@ -1560,9 +1576,13 @@ ap_status run_decode(const DecodeArgs& a) {
   const int64_t v_min = fused_value_min_bytes();
   const bool v_long = v_min >= 0 ? v_bytes >= v_min
                                  : v_bytes >= (128ll << 20) || (a.r >= 512 && v_bytes >= (96ll << 20));
-  const bool one_pass_v = a.v_new && !a.rank_k && !a.rank_v && a.T >= 2 && Hkv == a.H && v_long;
   const bool quant = a.dt_coef == AP_I8 || a.dt_coef == AP_I4;
+  const bool ragged = a.rank_k || a.rank_v;
+  // (with per-token ranks only on the two-role kernel, whose gathered tiles know the newest token)
+  const bool one_pass_v = a.v_new && a.T >= 2 && Hkv == a.H && v_long &&
+                          !(ragged && attn_small_applies(a.H, a.r, a.T, false));
   const bool small = !quant && attn_small_applies(a.H, a.r, a.T, one_pass_v);
+  int* pnew_split = (int*)((char*)a.workspace + ws_layout(a.B, a.H, a.d, a.T, a.r).pn + (size_t)a.B * a.H * 4);
   const int S = choose_nsplit(a.B, a.T);     // the same count for both kernels (twice the splits for
                                              // the small-rank kernel measured slower)
   const WsLayout wl = ws_layout(a.B, a.H, a.d, a.T, a.r);
@@ -1607,6 +1627,7 @@ ap_status run_decode(const DecodeArgs& a) {
   p.scores = a.scores;
   p.defer_v = one_pass_v ? 1 : 0;
   p.pnew = (float*)(ws + wl.pn);
+  p.pnew_split = pnew_split;
   if (quant) {
     p.Sk = (const uint16_t*)a.scale_k;
     p.Sv = (const uint16_t*)a.scale_v;
@@ -1639,8 +1660,8 @@ ap_status run_decode(const DecodeArgs& a) {
   if (S > (one_pass_v ? kFusedInlineSplits : kInlineMergeSplits)) {
     float* ml1 = (float*)(ws + wl.mml);
     float* U1 = (float*)(ws + wl.mu);
-    st = launch_merge_splits(ml, U, ml1, U1, one_pass_v ? (float*)(ws + wl.pn) : nullptr, a.B, a.H, a.r,
-                             S, a.stream);
+    st = launch_merge_splits(ml, U, ml1, U1, one_pass_v ? (float*)(ws + wl.pn) : nullptr,
+                             one_pass_v && !small ? pnew_split : nullptr, a.B, a.H, a.r, S, a.stream);
     if (st != AP_OK) return st;
     ml = ml1;
     U = U1;
@@ -1648,7 +1669,8 @@ ap_status run_decode(const DecodeArgs& a) {
   }
   if (one_pass_v)
     st = launch_expand_append(a.dt, a.dt_out == AP_F32, a.Bv, a.basis_batch_stride, a.v_new,
-                              (void*)a.Cv, ml, U, (const float*)(ws + wl.pn), (float*)(ws + wl.po),
+                              (void*)a.Cv, ml, U, (const float*)(ws + wl.pn),
+                              !small && S_exp > 1 ? pnew_split : nullptr, a.rank_v, (float*)(ws + wl.po),
                               a.out, a.lse, a.B, a.H, a.d, a.r, a.T, a.T_cap, S_exp, a.stream);
   else
     st = launch_merge_expand(a.dt, a.dt_out == AP_F32, ml, U, a.Bv, a.basis_batch_stride, a.out, a.lse,

@@ -744,7 +744,7 @@ ap_status launch_valueonly_attn(const void* q, const void* K, const void* Cv, co
   if (S > kValueOnlyInlineSplits) {
     float* ml1 = (float*)(ws + w.mml);
     float* U1 = (float*)(ws + w.mu);
-    st = launch_merge_splits(ml, U, ml1, U1, nullptr, B, H, r, S, stream);
+    st = launch_merge_splits(ml, U, ml1, U1, nullptr, nullptr, B, H, r, S, stream);
     if (st != AP_OK) return st;
     ml = ml1; U = U1; S_exp = 1;
   }

@@ -27,7 +27,7 @@ def load_golden(name):
 
 @pytest.fixture(params=["in_expansion", "by_rule"])
 def value_path(request):
-    """A fused step at uniform rank produces the new value row either inside its expansion pass
+    """A fused step produces the new value row either inside its expansion pass
     or in the launch that appends the key row; the library picks by the size of the value bases.
     Tests of small cases run both ways."""
     from paper_2603_23914_amd import binding as ap

@@ -190,12 +190,18 @@ def test_ragged_small_rank_writes_the_logits(dtype, B, H, d, r, T, granks, cum, 
     ("bf16", 3, 40, 40, 128, 640, 90, (640, 128), (1, 4), 4),
     ("f16", 2, 32, 8, 128, 128, 120, (128, 64), (1, 2), 2),        # grouped queries
     ("bf16", 2, 16, 4, 64, 64, 75, (64, 32), (1, 4), 4),           # grouped queries, small rank
+    ("f16", 1, 16, 16, 64, 256, 700, (256, 128, 64), (1, 2, 4), 4),  # one sequence: many token splits, merged first
+    ("bf16", 2, 24, 24, 128, 384, 300, (384, 192, 64, 16), (1, 2, 3, 4), 4),
 ])
-def test_decode_step_with_per_token_ranks(dtype, B, H, Hkv, d, r, T0, granks, cum, den):
-    """Fused steps under per-token ranks: the expansion pass does not produce the new value row
-    then, so it is appended next to the key row.  Both appended rows equal those of ap_compact bit
-    for bit (the same whole-row pass) and the projection of Sec. 3.1 within rounding; the output
-    matches the oracle on the stored bits."""
+def test_decode_step_with_per_token_ranks(dtype, B, H, Hkv, d, r, T0, granks, cum, den, value_path):
+    """Fused steps under per-token ranks.  The new value row is produced either by the expansion
+    pass over B_v (the gathered kernel then scores the new token, leaves its value row out of the
+    sums and exports its weight and the token split that holds it; the new token's own rank
+    limits the basis rows in which its coefficient counts) or in the launch that appends the key
+    row.  The key row equals ap_compact's bit for bit, the value row too when it comes from the
+    same whole-row pass and within one rounding otherwise; both match the projection of Sec. 3.1
+    within rounding, and the output matches the oracle on the stored bits.  The new token sits in
+    the first group, the last group and wherever its random importance puts it."""
     from paper_2603_23914_amd import binding as ap
     steps, F = 3, len(granks)
     case = wl.decode_case(dtype, B, Hkv, d, r, T0, steps=steps, seed=47, append=True)
@@ -209,7 +215,10 @@ def test_decode_step_with_per_token_ranks(dtype, B, H, Hkv, d, r, T0, granks, cu
         T = T0 + step + 1
         print(f"step with ranks {dtype} B={B} H={H}/{Hkv} d={d} r={r} T={T}", flush=True)
         mass = rng.random((B, T)).astype(np.float32)
-        mass[:, T - 1] = 2.0                                  # the token being appended: full rank
+        if step == 0:
+            mass[:, T - 1] = 2.0                              # the token being appended: full rank
+        elif step == 1:
+            mass[:, T - 1] = 0.0                              # ... the lowest rank
         rank, off, idx = gpu_select(mass, granks, cum, den)
         rank_np = rank.cpu().numpy()
         kn, vn = wl.step_new_token(case, step, P(case.Bk), P(case.Bv))
@@ -221,7 +230,13 @@ def test_decode_step_with_per_token_ranks(dtype, B, H, Hkv, d, r, T0, granks, cu
         ap.ap_compact(dkn[:, None, :].contiguous(), dvn[:, None, :].contiguous(), dBk, dBv, dCk2, dCv2, n=1, row0=T - 1)
         torch.cuda.synchronize()
         assert torch.equal(dCk.view(torch.int16), dCk2.view(torch.int16)), f"step {step}: appended key row"
-        assert torch.equal(dCv.view(torch.int16), dCv2.view(torch.int16)), f"step {step}: appended value row"
+        if value_path == "by_rule":
+            assert torch.equal(dCv.view(torch.int16), dCv2.view(torch.int16)), f"step {step}: appended value row"
+        else:                                                 # another order of fp32 additions: one rounding apart
+            a, b2 = P(bits(dCv))[:, T - 1], P(bits(dCv2))[:, T - 1]
+            assert np.abs(a - b2).max() <= (2.0 ** -7 if dtype == "bf16" else 2.0 ** -10) * np.abs(b2).max()
+            assert torch.equal(dCv[:, :T - 1].view(torch.int16), dCv2[:, :T - 1].view(torch.int16))
+            dCv2.copy_(dCv)
         Ck_h, Cv_h = bits(dCk), bits(dCv)
         for C_h, Bm, x in ((Ck_h, case.Bk, kn), (Cv_h, case.Bv, vn)):
             c_ref = oracle.compact(P(x)[0][None], P(Bm)[0])[0]
