@@ -102,7 +102,7 @@ const char* ap_status_string(ap_status s) {
 
 const char* ap_last_error(void) { return g_err; }
 
-int ap_version(void) { return 400; }   // 0.4.0: key-only and value-only compression
+int ap_version(void) { return 500; }   // 0.5.0: compression step, 4-bit coefficients, allocation-free decode entry
 
 size_t ap_probe_read_granule(void) { return probe_read_granule(); }
 
