@@ -239,3 +239,53 @@ def test_shared_basis_step_full_size():
             assert_close(to_host64(out[b]), ref, "bf16", f"shared-basis step, b={b}")
         del Ck2, Cv2
     assert (outs[0] - outs[1]).abs().max() <= 2e-3 * outs[0].abs().max()
+
+
+def test_fused_step_with_per_token_ranks_full_size():
+    """The fused step under attention-aware ranks at the headline shape (64 sequences, r=640,
+    quartile groups 640/320/128/64) in the launch the library picks there: the gathered kernel
+    leaves the new token's value row to the expansion pass.  The new token sits in the first
+    group in the sampled sequence 0 and in the last group in sequence 37; both value paths must
+    agree with each other and with the oracle on the stored bits."""
+    from paper_2603_23914_amd import binding as ap
+    B, H, d, r, T0 = 64, 40, 128, 640, 4223
+    T, HD = T0 + 1, H * d
+    (Ck, Cv, Bk, Bv), g = draw_cache(B, T, r, HD, 67)
+    q = torch.randn((B, H, d), generator=g, device="cuda").to(torch.bfloat16)
+    kn = torch.randn((B, HD), generator=g, device="cuda").to(torch.bfloat16)
+    vn = torch.randn((B, HD), generator=g, device="cuda").to(torch.bfloat16)
+    mass = torch.rand((B, T), generator=g, device="cuda")
+    mass[:, T - 1] = 2.0
+    mass[37, T - 1] = 0.0
+    granks, cum, den = (640, 320, 128, 64), (1, 2, 3, 4), 4
+    rank = torch.empty((B, T), dtype=torch.int32, device="cuda")
+    off = torch.empty((B, 5), dtype=torch.int32, device="cuda")
+    idx = torch.empty((B, T), dtype=torch.int32, device="cuda")
+    ap.ap_select_ranks(mass, granks, cum, den, rank, off, idx, workspace(ap.ap_select_workspace_bytes(B, T, 4)))
+    torch.cuda.synchronize()
+    assert int(rank[0, T - 1]) == 640 and int(rank[37, T - 1]) == 64
+    ws = workspace(ap.ap_decode_workspace_bytes(B, H, d, T, r, ap.AP_BF16))
+    outs = []
+    for force in (-1, 1 << 50):
+        print(f"per-token ranks, 64 sequences at T={T}, value row "
+              f"{'by the rule (in the expansion pass)' if force < 0 else 'next to the key row'}", flush=True)
+        Ck2, Cv2 = Ck.clone(), Cv.clone()
+        out = torch.empty((B, H, d), dtype=torch.float32, device="cuda")
+        ap.ap_set_fused_value_min_bytes(force)
+        try:
+            ap.ap_decode_step(q, kn, vn, Ck2, Cv2, Bk, Bv, out, ws, T=T, sm_scale=1.0 / math.sqrt(d),
+                              rank_k=rank, rank_v=rank, bucket_off=off, bucket_idx=idx, F=4)
+            torch.cuda.synchronize()
+        finally:
+            ap.ap_set_fused_value_min_bytes(-1)
+        outs.append(out)
+        for b in SAMPLE:
+            rk = rank[b].cpu().numpy()
+            for C, Bm, x, name in ((Ck2, Bk, kn, "key"), (Cv2, Bv, vn, "value")):
+                c_ref = oracle.compact(P(x[b])[None], P(Bm[b]))[0]
+                assert np.abs(P(C[b, T - 1]) - c_ref).max() <= 2.0 ** -7 * np.abs(c_ref).max(), f"{name} row, b={b}"
+            ref = oracle.decode_attn_absorbed(P(q[b]), P(Ck2[b, :T]), P(Cv2[b, :T]), P(Bk[b]), P(Bv[b]),
+                                              rank_k=rk, rank_v=rk)
+            assert_close(to_host64(out[b]), ref, "bf16", f"step with per-token ranks, b={b}")
+        del Ck2, Cv2
+    assert (outs[0] - outs[1]).abs().max() <= 2e-3 * outs[0].abs().max()
