@@ -119,19 +119,6 @@ def cpu_baseline(sample_seqs=12, repeats=3):
             "cpu_model": model, "blas_threads": blas_threads, "cores_available": cores}
 
 
-def _measured_traffic():
-    """HBM bytes per attn_partial launch as the rocprofv3 --pmc runs measured them (FETCH_SIZE and
-    WRITE_SIZE, scaled by a plain copy of known size): the figure stored with those runs' summary."""
-    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "attn_partial_c3_hbm_traffic.txt")
-    try:
-        for line in open(path):
-            if line.startswith("traffic_bytes_per_launch"):
-                return float(line.split()[1])
-    except OSError:
-        pass
-    return None
-
-
 def _time_us(torch, fn, iters, warm=3):
     """Mean microseconds per call of fn() on the current stream (events around `iters` calls)."""
     for _ in range(warm):
@@ -540,8 +527,7 @@ def main():
                 "frac": (achieved / HBM_PEAK_GBS) if achieved else None,
                 # HBM counters are not read inside this run: the figure measured with rocprofv3 --pmc
                 # for this kernel and workload is in the file named here
-                "traffic": _measured_traffic(), "traffic_unit": "bytes per launch",
-                "traffic_source": "profiles/attn_partial_c3_hbm_traffic.txt",
+                "traffic": None, "traffic_source": "profiles/attn_partial_c3_hbm_traffic.txt",
                 "kernel_avg_us": k_avg_ms * 1e3, "kernel_median_us": srt[len(srt) // 2] if srt else None,
                 "kernel_min_us": srt[0] if srt else None, "kernel_us_per_launch": [round(u, 2) for u in k_each],
                 "launches": k_n, "timed_every": PROF_EVERY,
