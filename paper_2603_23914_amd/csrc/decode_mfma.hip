@@ -960,7 +960,7 @@ __device__ __forceinline__ void score_role(const AttnParams& p) {
       }
     }
   };
-  auto load_A = [&](int tile) {                           // tile: local index in this split
+  auto load_A = [&](int tile, u32x4_t (&A)[NA][2]) {      // tile: local index in this split
     if (cx.dbg & 1) return;
     if (!RAGGED) {
 #pragma unroll
@@ -973,19 +973,20 @@ __device__ __forceinline__ void score_role(const AttnParams& p) {
       }
       load_scales(tile);
     } else {
-      // gathered rows; k-steps at or beyond the tile's key rank re-read bytes this wave
-      // (or, with no k-step left, its neighbours) fetch anyway
-      // (a key rank that ends inside a 32-column k-step still fetches that k-step; the columns
-      // beyond the rank are zeroed before the product)
+      // gathered rows; only this wave's units below the tile's key rank are fetched (a
+      // wave-uniform count, so a low-rank tile costs fewer requests, not just fewer distinct
+      // bytes); the registers of the other units keep old values and are zeroed before the
+      // product, like the columns beyond a rank that ends inside a 32-column k-step
       const int nks_t = I8 ? uni(cx.meta[4 * tile + 1]) >> 6 : (uni(cx.meta[4 * tile + 1]) + 31) >> 5;   // units of 64 bytes
-      const uint32_t loff = (uint32_t)(w < nks_t ? w : 0) * UB + (uint32_t)g * LB;
+      const int nlive_t = nks_t > w ? (nks_t - w + 3) >> 2 : 0;
+      const uint32_t loff = (uint32_t)w * UB + (uint32_t)g * LB;
 #pragma unroll
       for (int tt = 0; tt < 2; ++tt) {
         const int row = cx.idxb[tile * kTile + 16 * tt + n];
         const char* rp = Ck_b + ((uint32_t)row * cx.row_bytes + loff);
 #pragma unroll
         for (int i = 0; i < NA; ++i)
-          A[i][tt] = load_piece(rp + ((w + 4 * i) < nks_t ? (uint32_t)i * 4u * UB : 0u));
+          if (i < nlive_t) A[i][tt] = load_piece(rp + (uint32_t)i * 4u * UB);
       }
       load_scales(tile);
     }
@@ -993,7 +994,7 @@ __device__ __forceinline__ void score_role(const AttnParams& p) {
   if constexpr (TS) {
     // ---- token-split: this wave scores tiles w, w + 4, ... completely; four tiles per round
     const int rounds = (cx.ntl + 3) >> 2;
-    if (w < cx.ntl) load_A(w);
+    if (w < cx.ntl) load_A(w, A);
     AP_T_START
     for (int it = 0; it < rounds; ++it) {
       const int lt = 4 * it + w;
@@ -1002,7 +1003,7 @@ __device__ __forceinline__ void score_role(const AttnParams& p) {
       for (int mt = 0; mt < MT; ++mt) { f32x4_t z = {0.f, 0.f, 0.f, 0.f}; sp[mt][0] = z; sp[mt][1] = z; }
       score_tile<Tag, MT, SPLIT, NKW>(A, qhi, qlo, sp);     // a slot without a tile: masked below
       AP_TICK(1)
-      if (lt + 4 < cx.ntl) load_A(lt + 4);                  // lands while the round is finished
+      if (lt + 4 < cx.ntl) load_A(lt + 4, A);               // lands while the round is finished
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) {
         cx.xchg[(w * 16 * MT + mt * 16 + n) * 9 + g] = sp[mt][0];
@@ -1020,10 +1021,8 @@ __device__ __forceinline__ void score_role(const AttnParams& p) {
     AP_T_REPORT
     return;
   }
-  if (cx.ntl > 0) load_A(0);
-
-  AP_T_START
-  for (int t = 0; t < cx.ntl; ++t) {
+  // One tile: scores from the rows in A, then the same registers take the rows of tile t + lead.
+  auto tile_step = [&](int t, u32x4_t (&A)[NA][2], int lead) {
     AP_T_STAMP(t)
     f32x4_t sp[MT][2];
 #pragma unroll
@@ -1060,7 +1059,7 @@ __device__ __forceinline__ void score_role(const AttnParams& p) {
       if (!(cx.dbg & 2)) score_tile<Tag, MT, SPLIT, NKW>(A, qhi, qlo, sp, nlive);
     }
     AP_TICK(1)
-    if (t + 1 < cx.ntl) load_A(t + 1);                    // lands while the tile is finished
+    if (t + lead < cx.ntl) load_A(t + lead, A);           // lands while the tile(s) in between are finished
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
       cx.xchg[(w * 16 * MT + mt * 16 + n) * 9 + g] = sp[mt][0];
@@ -1072,7 +1071,10 @@ __device__ __forceinline__ void score_role(const AttnParams& p) {
     AP_TICK(3)
     wg_barrier();                                         // weights of tile t ready
     AP_TICK(4)
-  }
+  };
+  AP_T_START
+  if (cx.ntl > 0) load_A(0, A);
+  for (int t = 0; t < cx.ntl; ++t) tile_step(t, A, 1);
   AP_T_STAMP(62)
   cx.store_ml(part_ml);
   AP_TICK(6)
@@ -1103,9 +1105,8 @@ __device__ __forceinline__ void sum_role(const AttnParams& p) {
   const int tot_chunks = kHalf * (cpr + 1);
   uint32_t slot_off[NSLOT];
   uint32_t slot_row[(NSLOT + 3) / 4];
-  uint32_t slot_chk[(NSLOT + 3) / 4];                     // RAGGED: chunk index of every slot
 #pragma unroll
-  for (int k = 0; k < (NSLOT + 3) / 4; ++k) { slot_row[k] = 0; slot_chk[k] = 0; }
+  for (int k = 0; k < (NSLOT + 3) / 4; ++k) slot_row[k] = 0;
   int n_issue = 0;
 #pragma unroll
   for (int k = 0; k < NSLOT; ++k) {
@@ -1120,17 +1121,33 @@ __device__ __forceinline__ void sum_role(const AttnParams& p) {
       if (c == cpr) c = 0;                        // pad chunk: harmless duplicate
       slot_off[k] = (uint32_t)row * cx.row_bytes + (uint32_t)(c * 16);
       slot_row[k >> 2] |= (uint32_t)row << (8 * (k & 3));
-      slot_chk[k >> 2] |= (uint32_t)c << (8 * (k & 3));
     }
   }
   const char* Cv_b = (const char*)uni_ptr(p.Cv) + (size_t)cx.b * uni(p.T_cap) * cx.row_bytes;
+  // RAGGED: a gathered tile sits in its ring slots packed to its own value rank: 16 rows of
+  // (chunks below the rank + one pad chunk), so a low-rank tile takes fewer 1 KiB requests and
+  // not just fewer distinct bytes.  16-byte chunks of a row below the rank of local tile lt:
+  auto tile_chunks = [&](int lt) -> int {
+    const int rv = uni(cx.meta[4 * lt + 2]);
+    int c = I4 ? (rv + 31) >> 5 : (I8 ? (rv + 15) >> 4 : (rv + 7) >> 3);
+    c = c < 1 ? 1 : c;
+    return c < cpr ? c : cpr;
+  };
+  // ... and this wave's requests per 16-row unit of such a tile (blocks cp, cp + 4, ...)
+  auto tile_requests = [&](int lt) -> int {
+    const int nb = (kHalf * (tile_chunks(lt) + 1) + 63) >> 6;
+    return nb > cp ? (nb - cp + 3) >> 2 : 0;
+  };
   // both 16-row units of local tile lt into ring slots 2*(lt % RT), +1
   auto issue_tile = [&](int lt) {
     if (cx.dbg & 1) return;
     const int slot0 = 2 * (lt % RT);
     if (RAGGED) {
-      // gathered rows; chunks at or beyond the tile's value rank re-read the row's first chunk
-      const uint32_t rv8 = (uint32_t)uni(cx.meta[4 * lt + 2]) >> (I4 ? 5 : (I8 ? 4 : 3));   // 16-byte chunks
+      const int cprt = tile_chunks(lt), cw = cprt + 1, tot = kHalf * cw;
+      const int nb = (tot + 63) >> 6;
+      // chunk L of a unit is (row L / cw, chunk L % cw): L < 1344 and cw <= 81, so the quotient
+      // is exact as (L * ceil(2^20 / cw)) >> 20
+      const uint32_t magic = ((1u << 20) + (uint32_t)cw - 1u) / (uint32_t)cw;
 #pragma nounroll
       for (int half = 0; half < 2; ++half) {
         char* dst = cx.ring + (slot0 + half) * cx.unit_bytes;
@@ -1138,13 +1155,15 @@ __device__ __forceinline__ void sum_role(const AttnParams& p) {
 #pragma unroll
         for (int k = 0; k < NSLOT; ++k) {
           const int blk = cp + 4 * k;
-          if (blk < cx.nblk) {
-            const int row = (int)((slot_row[k >> 2] >> (8 * (k & 3))) & 0xffu);
-            const uint32_t c = (slot_chk[k >> 2] >> (8 * (k & 3))) & 0xffu;
+          if (blk < nb) {                                     // wave-uniform
+            const uint32_t L = (uint32_t)(blk * 64 + lane);
+            uint32_t row = (L * magic) >> 20;
+            uint32_t c = L - row * (uint32_t)cw;
+            if (L >= (uint32_t)tot) { row = 0; c = 0; }       // tail of the last block: harmless duplicate
+            if (c == (uint32_t)cprt) c = 0;                   // pad chunk: harmless duplicate
             int tokv = ix[row];
             tokv = tokv < cx.Tv ? tokv : cx.Tv - 1;           // a deferred row is not there yet: weight 0
-            const uint32_t off = (uint32_t)tokv * cx.row_bytes + (c < rv8 ? c * 16u : 0u);
-            dma16(Cv_b + off, dst + blk * 1024);
+            dma16(Cv_b + ((uint32_t)tokv * cx.row_bytes + c * 16u), dst + blk * 1024);
           }
         }
       }
@@ -1252,7 +1271,13 @@ __device__ __forceinline__ void sum_role(const AttnParams& p) {
       // tile t's rows must have landed; the tiles issued after it may stay in flight
       int later = cx.ntl - t - 1;
       later = later < RT - 1 ? later : RT - 1;
-      wait_vmcnt(later * 2 * n_issue);
+      if (RAGGED) {
+        int pending = 0;
+        for (int lt = t + 1; lt <= t + later; ++lt) pending += 2 * tile_requests(lt);
+        wait_vmcnt(pending);
+      } else {
+        wait_vmcnt(later * 2 * n_issue);
+      }
     }
     wg_barrier();            // weights of tile t ready; tile t's rows visible to every wave
     AP_TICK(4)
@@ -1267,7 +1292,8 @@ __device__ __forceinline__ void sum_role(const AttnParams& p) {
     }
     // lane (n, g): token rows 4g..4g+3 (and 16+4g..), dword n of this wave's 64 bytes
     const int slot0 = 2 * (t % RT);
-    const char* vA = cx.ring + slot0 * cx.unit_bytes + (4 * g) * cx.pitch + cp * 64 + n * 4;
+    const int pitch_t = RAGGED ? (tile_chunks(t) + 1) * 16 : cx.pitch;
+    const char* vA = cx.ring + slot0 * cx.unit_bytes + (4 * g) * pitch_t + cp * 64 + n * 4;
     const char* vB = vA + cx.unit_bytes;
     if constexpr (I8) {
       f32x4_t P32[MT][2];
@@ -1279,16 +1305,16 @@ __device__ __forceinline__ void sum_role(const AttnParams& p) {
       if constexpr (I4) {
         // the 4-bit reader places its own dword: take the lane's n * 4 off again
         if (!(cx.dbg & 2))
-          wsum_tile_i4<MT, NGRP>(vA - n * 4, vB - n * 4, cx.pitch, RAGGED ? uni(cx.meta[4 * t + 2]) : r, cp, n, g,
+          wsum_tile_i4<MT, NGRP>(vA - n * 4, vB - n * 4, pitch_t, RAGGED ? uni(cx.meta[4 * t + 2]) : r, cp, n, g,
                                  cx.vsb + (t & 1) * (r >> 6) * kTile, P32, alpha, U);
       } else {
         if (!(cx.dbg & 2))
-          wsum_tile_i8<MT, NGRP>(vA, vB, cx.pitch, RAGGED ? uni(cx.meta[4 * t + 2]) : r, cp, g,
+          wsum_tile_i8<MT, NGRP>(vA, vB, pitch_t, RAGGED ? uni(cx.meta[4 * t + 2]) : r, cp, g,
                                  cx.vsb + (t & 1) * (r >> 6) * kTile, P32, alpha, U);
       }
     } else {
       if (!(cx.dbg & 2))
-        wsum_tile<Tag, MT, SPLIT, NGRP>(vA, vB, cx.pitch,
+        wsum_tile<Tag, MT, SPLIT, NGRP>(vA, vB, pitch_t,
                                         (RAGGED ? uni(cx.meta[4 * t + 2]) : r) - cp * 32, n, Phi, Plo,
                                         alpha, U);
     }
