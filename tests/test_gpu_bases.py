@@ -179,3 +179,83 @@ def test_bases_full_size_one_sequence():
     assert orth <= ORTH_TOL[dtype] and residual / optimal <= 1.10 and lead >= 0.97
     assert np.max(np.diff(energy)) <= 1e-2 * energy[0]
     assert np.abs(sig[0] - np.sqrt(energy)).max() <= 1e-2 * np.sqrt(energy[0])
+
+
+def test_algorithm1_loop_with_new_bases_at_every_trigger():
+    """Alg. 1 end to end on the GPU entry points: the prompt's keys and values are decomposed
+    (ap_compute_bases) and projected (ap_compact); generated tokens wait in the uncompressed
+    segment and every step attends to both under one softmax; once T_p tokens wait, the retrieved
+    cache (ap_decompress) and the tail are decomposed AGAIN, with new bases, and the tail starts
+    over.  Bases are unique only up to signs, so the oracle takes what the GPU stored (bases and
+    coefficients, bit for bit) and checks (a) every step's output against attention over the
+    union by its definition, (b) at every compression that the new bases serve the retrieved
+    cache as well as its exact truncated SVD and that the coefficients are its projection."""
+    from paper_2603_23914_amd import binding as ap
+    dtype, H, d, r, over, n0, T_p, steps = "f16", 8, 64, 64, 32, 320, 8, 17     # token counts stay multiples of 8
+    HD, T_cap = H * d, n0 + steps + 8
+    P = lambda a: oracle.promote(a, dtype)
+    tdt = TORCH_DT[dtype]
+    Kp, Vp, _, _ = wl.config5_sequence(0, seed=31, T=n0 + steps, HD=HD, r=r, dtype=dtype)
+    K_all, V_all = Kp, Vp
+    Omega = to_dev(wl.store(wl.rng_for(31, 5).standard_normal((r + over, HD)), dtype), dtype)
+    dBk = torch.zeros((1, r, HD), dtype=tdt, device="cuda")
+    dBv = torch.zeros_like(dBk)
+    dCk = torch.zeros((1, T_cap, r), dtype=tdt, device="cuda")
+    dCv = torch.zeros_like(dCk)
+    dK = torch.zeros((1, T_p, HD), dtype=tdt, device="cuda")
+    dV = torch.zeros_like(dK)
+    scale = 1.0 / math.sqrt(d)
+    out_c = torch.empty((1, H, d), dtype=torch.float32, device="cuda")
+    lse_c = torch.empty((1, H), dtype=torch.float32, device="cuda")
+    out_u, lse_u, out = torch.empty_like(out_c), torch.empty_like(lse_c), torch.empty_like(out_c)
+
+    def compress(dXk, dXv, n):
+        """bases of the n rows of dXk / dXv, then their coefficients: rows 0..n-1 of the cache"""
+        wsb = workspace(ap.ap_bases_workspace_bytes(1, n, HD, r, over))
+        ap.ap_compute_bases(dXk, Omega, dBk, wsb, power_iters=2)
+        ap.ap_compute_bases(dXv, Omega, dBv, wsb, power_iters=2)
+        ap.ap_compact(dXk, dXv, dBk, dBv, dCk, dCv, n=n, row0=0)
+        torch.cuda.synchronize()
+        for X, Bm, C, name in ((dXk, dBk, dCk, "keys"), (dXv, dBv, dCv, "values")):
+            Xh, Dh = to_host64(X[0, :n]), to_host64(Bm[0])
+            qv = oracle.basis_quality(Xh, Dh)
+            print(f"  compress {name} n={n}: orth {qv['orth_err']:.1e} residual/optimal {qv['ratio']:.4f}", flush=True)
+            assert qv["orth_err"] <= ORTH_TOL[dtype] and qv["ratio"] <= 1.10, name
+            cref = oracle.compact(Xh, Dh)
+            assert (np.abs(to_host64(C[0, :n]) - cref) <= 2.0 ** -10 * np.abs(cref) + 1e-5 * np.abs(cref).max()).all()
+
+    compress(to_dev(K_all[None, :n0], dtype), to_dev(V_all[None, :n0], dtype), n0)
+    T, T_u, compressions = n0, 0, 1
+    rng = wl.rng_for(31, 77)
+    for step in range(steps):
+        row = n0 + step
+        ap.ap_raw_append(to_dev(K_all[None, row], dtype), to_dev(V_all[None, row], dtype), dK, dV, row=T_u)
+        T_u += 1
+        q = wl.store(rng.standard_normal((1, H, d)), dtype)
+        print(f"Alg. 1 loop step {step}: {T} compressed + {T_u} raw tokens", flush=True)
+        ap.ap_decode_attn(to_dev(q, dtype), dCk, dCv, dBk, dBv, out_c,
+                          workspace(ap.ap_decode_workspace_bytes(1, H, d, T, r, ap.AP_F16)), T=T, sm_scale=scale, lse=lse_c)
+        ap.ap_raw_attn(to_dev(q, dtype), dK, dV, out_u, workspace(ap.ap_raw_workspace_bytes(1, H, d, T_u)), T_u=T_u,
+                       sm_scale=scale, lse=lse_u)
+        ap.ap_merge_segments(out_c, lse_c, out_u, lse_u, out)
+        torch.cuda.synchronize()
+        ref = oracle.decode_attn_segments(P(q)[0], [
+            dict(Ck=to_host64(dCk[0, :T]), Cv=to_host64(dCv[0, :T]), Bk=to_host64(dBk[0]), Bv=to_host64(dBv[0])),
+            dict(K=to_host64(dK[0, :T_u]), V=to_host64(dV[0, :T_u]))])
+        err = np.abs(to_host64(out[0]) - ref).max()
+        assert err <= 2e-3 * np.abs(ref).max(), f"step {step}: {err:.2e}"
+        if T_u == T_p:                  # the trigger: retrieve, join the tail, decompose again
+            n = T + T_u
+            dXk = torch.zeros((1, n, HD), dtype=tdt, device="cuda")
+            dXv = torch.zeros_like(dXk)
+            wsd = workspace(ap.ap_decompress_workspace_bytes(1, T, HD, r, False))
+            headk = torch.zeros((1, T, HD), dtype=tdt, device="cuda")
+            headv = torch.zeros_like(headk)
+            ap.ap_decompress(dCk, dBk, headk, wsd, T=T)
+            ap.ap_decompress(dCv, dBv, headv, wsd, T=T)
+            dXk[:, :T], dXk[:, T:] = headk, dK[:, :T_u]
+            dXv[:, :T], dXv[:, T:] = headv, dV[:, :T_u]
+            compress(dXk, dXv, n)
+            T, T_u = n, 0
+            compressions += 1
+    assert compressions == 3 and T == n0 + 16 and T_u == 1
