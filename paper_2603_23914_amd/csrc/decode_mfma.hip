@@ -495,7 +495,9 @@ struct WaveCtx {
   int* meta;         // RAGGED: [ntl][4] = tokens in the tile, key rank, value rank, 1 + slot of the
                      // deferred newest token (0: not in this tile)
   uint32_t row_bytes;
-  int t_lo, ntl;     // first tile and number of tiles of this split
+  int t_lo, ntl;     // first tile (token-split mode) and number of tiles of this split
+  int tok_a, tok_h, tok_rem;   // contiguous tiles: the split's first token; its first tok_rem tiles
+                               // hold tok_h + 1 tokens, the others tok_h
   int Tv;            // value rows that exist: T, or T-1 while the newest token's row is deferred
   float* pnew;
   int* pnew_split;
@@ -532,10 +534,26 @@ struct WaveCtx {
     abuf = (float*)(Pbuf + NSUB * MT * 2 * 64);
     row_bytes = (uint32_t)row_bytes_of(r);
     vsb = (uint16_t*)(abuf + NSUB * 16 * MT);
-    if (!RAGGED) {
+    tok_a = 0; tok_h = kTile; tok_rem = 0;
+    if (!RAGGED && TS) {
       const int ntiles = (T + kTile - 1) / kTile;
       t_lo = (int)(((int64_t)s * ntiles) / nsplit);
       ntl = (int)(((int64_t)(s + 1) * ntiles) / nsplit) - t_lo;
+    } else if (!RAGGED) {
+      // The splits share the TOKENS evenly, not the 32-token tiles: a split of n tokens walks
+      // ceil(n / 32) tiles of floor(n / tiles) or one more tokens each.  A tile still fetches the
+      // 32 consecutive rows from its first token on; the rows beyond its own count belong to the
+      // next tile, are masked here and come out of L2 there.  With whole tiles dealt out instead,
+      // one split of a sequence owns a tile more than the others whenever the tile count is not a
+      // multiple of the split count (34 against 33 at T = 4240 in four splits).  Measured the
+      // difference is small (126.8 -> 126.4 us at that shape: the longer split's last tile has the
+      // chip to itself and takes half the usual time), but every split now does the same work.
+      t_lo = 0;
+      tok_a = (int)(((int64_t)s * T) / nsplit);
+      const int n_tok = (int)(((int64_t)(s + 1) * T) / nsplit) - tok_a;
+      ntl = (n_tok + kTile - 1) / kTile;
+      tok_h = ntl > 0 ? n_tok / ntl : 0;
+      tok_rem = n_tok - tok_h * ntl;
     } else {
       idxb = (int*)(vsb + (I8 ? 2 * (r >> 6) * kTile : 0));
       meta = idxb + uni(p.ntl_cap) * kTile;
@@ -613,22 +631,27 @@ struct WaveCtx {
     wg_barrier();
   }
 
-  // Global tile index of local tile t.
-  __device__ __forceinline__ int gtile(int t) const { return t_lo + t; }
+  // First token of local tile t (contiguous tiles).
+  __device__ __forceinline__ int tok0(int t) const {
+    if (TS) return (t_lo + t) * kTile;
+    return tok_a + t * tok_h + (t < tok_rem ? t : tok_rem);
+  }
 
-  // Tokens of local tile t that exist (the rest of the 32 slots is masked out of the softmax).
+  // Tokens of local tile t that count (the rest of the 32 slots is masked out of the softmax).
   __device__ __forceinline__ int tile_valid(int t) const {
     if (TS && t >= ntl) return 0;        // a slot of the last round without a tile
     if (RAGGED) return uni(meta[4 * t]);
-    const int left = T - gtile(t) * kTile;
+    if (!TS) return tok_h + (t < tok_rem ? 1 : 0);
+    const int left = T - tok0(t);
     return left < kTile ? left : kTile;
   }
 
-  // Slot of the deferred newest token in local tile t (outside [0, 32): not in this tile).
+  // Slot of the deferred newest token in local tile t, or -1 when it is not one of its tokens.
   __device__ __forceinline__ int tile_new(int t) const {
     if (Tv == T || (TS && t >= ntl)) return -1;
     if (RAGGED) return uni(meta[4 * t + 3]) - 1;
-    return T - 1 - gtile(t) * kTile;
+    const int nl = T - 1 - tok0(t);
+    return nl < tile_valid(t) ? nl : -1;
   }
 
   // Softmax of this wave's heads for a tile whose first `valid` slots hold tokens (after
@@ -652,7 +675,7 @@ struct WaveCtx {
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         if (slot + i < valid) {
-          const int tok = RAGGED ? idxb[t * kTile + slot + i] : gtile(t) * kTile + slot + i;
+          const int tok = RAGGED ? idxb[t * kTile + slot + i] : tok0(t) + slot + i;
           scores[(size_t)tok * H + o_hh] = sc[i] * kLn2;
         }
       }
@@ -738,7 +761,7 @@ struct WaveCtx {
 #pragma unroll
         for (int i = 0; i < 4; ++i)
           if (slot + i < valid[sub])
-            scores[(size_t)(gtile(t0 + sub) * kTile + slot + i) * H + o_hh] = sc[sub][i] * kLn2;
+            scores[(size_t)(tok0(t0 + sub) + slot + i) * H + o_hh] = sc[sub][i] * kLn2;
     }
     float tmax = -INFINITY;
 #pragma unroll
@@ -935,7 +958,7 @@ __device__ __forceinline__ void score_role(const AttnParams& p) {
         if (RAGGED) {
           row = cx.idxb[tile * kTile + 16 * tt + n];
         } else {
-          row = cx.gtile(tile) * kTile + 16 * tt + n;
+          row = cx.tok0(tile) + 16 * tt + n;
           row = row < T ? row : T - 1;
         }
         const uint16_t* sp_ = Sk_b + (size_t)row * nsb + (my_nks > 0 ? w : 0);
@@ -952,7 +975,7 @@ __device__ __forceinline__ void score_role(const AttnParams& p) {
           if (RAGGED) {
             row = cx.idxb[tile * kTile + (e & 31)];
           } else {
-            row = cx.gtile(tile) * kTile + (e & 31);
+            row = cx.tok0(tile) + (e & 31);
             row = row < T ? row : T - 1;
           }
           vsr[j] = Sv_b[(size_t)row * nsb + (e >> 5)];
@@ -965,7 +988,7 @@ __device__ __forceinline__ void score_role(const AttnParams& p) {
     if (!RAGGED) {
 #pragma unroll
       for (int tt = 0; tt < 2; ++tt) {
-        int row = cx.gtile(tile) * kTile + 16 * tt + n;
+        int row = cx.tok0(tile) + 16 * tt + n;
         row = row < T ? row : T - 1;                      // rows beyond T are masked later
         const char* rp = Ck_b + ((uint32_t)row * cx.row_bytes + lane_off);
 #pragma unroll
@@ -1171,7 +1194,7 @@ __device__ __forceinline__ void sum_role(const AttnParams& p) {
     }
 #pragma nounroll
     for (int half = 0; half < 2; ++half) {
-      const int tok_u = cx.gtile(lt) * kTile + half * kHalf;
+      const int tok_u = cx.tok0(lt) + half * kHalf;
       char* dst = cx.ring + (slot0 + half) * cx.unit_bytes;
       const uint32_t base = (uint32_t)tok_u * cx.row_bytes;
       if (tok_u + kHalf <= cx.Tv) {
