@@ -214,7 +214,7 @@ fold_heads(const uint16_t* __restrict__ Bk, int64_t bstride, const uint16_t* __r
 // ------------------------------------------------------------------------------------------
 // merge_expand: grid (ceil(H / 2), B), 256 threads.
 // ------------------------------------------------------------------------------------------
-template <class Tag, bool OUT_F32>
+template <class Tag, bool OUT_F32, int kS>
 __global__ void __launch_bounds__(256)
 merge_expand(const float* __restrict__ part_ml, const float* __restrict__ part_U,
              const uint16_t* __restrict__ Bv, int64_t bstride, void* __restrict__ out,
@@ -224,10 +224,9 @@ merge_expand(const float* __restrict__ part_ml, const float* __restrict__ part_U
   float* red = ustar + 2 * r;              // [rows][2 d]
   const int h0 = blockIdx.x * 2, b = blockIdx.y, tid = threadIdx.x;
   const int nh = H - h0 < 2 ? H - h0 : 2;  // heads of this workgroup
-  // ---- merged, normalised coefficient sums of the two heads.  At most 8 splits arrive here
-  //      (more are merged beforehand); every load of a thread is issued before the first is
-  //      used, so the prologue costs two memory round trips, not one per split.
-  constexpr int kS = 8;
+  // ---- merged, normalised coefficient sums of the two heads.  At most kS (8 or 16) splits
+  //      arrive here (more are merged beforehand); every load of a thread is issued before the
+  //      first is used, so the prologue costs two memory round trips, not one per split.
   for (int i = tid; i < nh * r; i += 256) {
     const int hh = i >= r ? 1 : 0, j = i - hh * r;
     const size_t pb = (size_t)b * nsplit * H + h0 + hh;    // + s*H
@@ -793,13 +792,22 @@ ap_status launch_merge_expand(ap_dtype dt, bool out_f32, const float* part_ml, c
   const size_t lds = ((size_t)2 * r + (size_t)rows * 2 * d) * 4;
   const dim3 grid((H + 1) / 2, B);
   const uint16_t* bv = (const uint16_t*)Bv;
-  if (dt == AP_F16) {
-    if (out_f32) hipLaunchKernelGGL((merge_expand<F16Tag, true>), grid, dim3(256), lds, stream, part_ml, part_U, bv, bstride, out, lse, H, G, d, r, nsplit);
-    else hipLaunchKernelGGL((merge_expand<F16Tag, false>), grid, dim3(256), lds, stream, part_ml, part_U, bv, bstride, out, lse, H, G, d, r, nsplit);
-  } else {
-    if (out_f32) hipLaunchKernelGGL((merge_expand<BF16Tag, true>), grid, dim3(256), lds, stream, part_ml, part_U, bv, bstride, out, lse, H, G, d, r, nsplit);
-    else hipLaunchKernelGGL((merge_expand<BF16Tag, false>), grid, dim3(256), lds, stream, part_ml, part_U, bv, bstride, out, lse, H, G, d, r, nsplit);
+  if (nsplit > 16) {
+    set_error("merge_expand: %d splits (at most 16 are merged inline)", nsplit);
+    return AP_ERR_UNSUPPORTED;
   }
+#define AP_ME(TAG, F32, KS) \
+  hipLaunchKernelGGL((merge_expand<TAG, F32, KS>), grid, dim3(256), lds, stream, part_ml, part_U, bv, bstride, out, lse, H, G, d, r, nsplit)
+#define AP_ME_KS(TAG, F32) do { if (nsplit <= 8) AP_ME(TAG, F32, 8); else AP_ME(TAG, F32, 16); } while (0)
+  if (dt == AP_F16) {
+    if (out_f32) AP_ME_KS(F16Tag, true);
+    else AP_ME_KS(F16Tag, false);
+  } else {
+    if (out_f32) AP_ME_KS(BF16Tag, true);
+    else AP_ME_KS(BF16Tag, false);
+  }
+#undef AP_ME_KS
+#undef AP_ME
   return AP_OK;
 }
 

@@ -1459,7 +1459,7 @@ int device_cus() {
 // query needs no GPU.
 constexpr int kMaxTilesPerSplit = 128;   // bounds the LDS index table of rank-ragged launches
 constexpr int kMaxGroups = 8;
-constexpr int kInlineMergeSplits = 8;    // more splits than this are merged by their own kernel
+constexpr int kInlineMergeSplits = 16;   // more splits than this are merged by their own kernel
 constexpr int kFusedInlineSplits = 16;   // the same limit inside a fused step (measured: merging
                                          // 16 splits inline saves 6-8 us, merging 32 costs 5)
 
