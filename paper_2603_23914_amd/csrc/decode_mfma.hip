@@ -545,9 +545,9 @@ struct WaveCtx {
       // 32 consecutive rows from its first token on; the rows beyond its own count belong to the
       // next tile, are masked here and come out of L2 there.  With whole tiles dealt out instead,
       // one split of a sequence owns a tile more than the others whenever the tile count is not a
-      // multiple of the split count (34 against 33 at T = 4240 in four splits).  Measured the
-      // difference is small (126.8 -> 126.4 us at that shape: the longer split's last tile has the
-      // chip to itself and takes half the usual time), but every split now does the same work.
+      // multiple of the split count (34 against 33 at T = 4240 in four splits).  The launch takes
+      // as long as before (a tile costs the same whether 31 or 32 of its rows count, and the
+      // longest split still walks 34), but every split now does the same work at any T.
       t_lo = 0;
       tok_a = (int)(((int64_t)s * T) / nsplit);
       const int n_tok = (int)(((int64_t)(s + 1) * T) / nsplit) - tok_a;
@@ -1197,7 +1197,8 @@ __device__ __forceinline__ void sum_role(const AttnParams& p) {
       const int tok_u = cx.tok0(lt) + half * kHalf;
       char* dst = cx.ring + (slot0 + half) * cx.unit_bytes;
       const uint32_t base = (uint32_t)tok_u * cx.row_bytes;
-      if (tok_u + kHalf <= cx.Tv) {
+      const int vlim = cx.Tv;
+      if (tok_u + kHalf <= vlim) {
 #pragma unroll
         for (int k = 0; k < NSLOT; ++k) {
           const int blk = cp + 4 * k;
@@ -1210,7 +1211,7 @@ __device__ __forceinline__ void sum_role(const AttnParams& p) {
           if (blk < cx.nblk) {
             const int row = (int)((slot_row[k >> 2] >> (8 * (k & 3))) & 0xffu);
             uint32_t off = base + slot_off[k];
-            if (tok_u + row >= cx.Tv) off -= (uint32_t)(tok_u + row - (cx.Tv - 1)) * cx.row_bytes;
+            if (tok_u + row >= vlim) off -= (uint32_t)(tok_u + row - (vlim - 1)) * cx.row_bytes;
             dma16(Cv_b + off, dst + blk * 1024);
           }
         }
