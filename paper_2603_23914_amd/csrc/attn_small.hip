@@ -401,7 +401,7 @@ attn_small(const SmallParams p) {
   const size_t pb = ((size_t)b * S + su) * H;
   for (int i = threadIdx.x * 4; i < H * R; i += 256 * 4)
     *(f32x4_t*)(p.part_U + pb * R + i) = *(const f32x4_t*)(Ubuf + i);
-  if (threadIdx.x < H) {
+  if ((int)threadIdx.x < H) {
     const int h = threadIdx.x;
     const float ms = fmaxf(fmaxf(st_m[0][h], st_m[1][h]), fmaxf(st_m[2][h], st_m[3][h]));
     float L = 0.f, pn = 0.f;

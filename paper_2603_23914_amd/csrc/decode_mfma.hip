@@ -882,7 +882,6 @@ __device__ __forceinline__ void score_role(const AttnParams& p) {
   AP_T_ENTRY
   WaveCtx<Tag, MT, SPLIT, RAGGED, Q, TS> cx;
   cx.init(p);
-  float* part_U = uni_ptr(p.part_U);
   float* part_ml = uni_ptr(p.part_ml);
   const int w = cx.w, n = cx.n, g = cx.g, r = cx.r, T = cx.T;
   const int nks = I8 ? r >> 6 : r >> 5;                   // all units
@@ -1118,7 +1117,7 @@ __device__ __forceinline__ void sum_role(const AttnParams& p) {
   cx.init(p);
   float* part_U = uni_ptr(p.part_U);
   float* part_ml = uni_ptr(p.part_ml);
-  const int n = cx.n, g = cx.g, r = cx.r, T = cx.T, lane = cx.lane;
+  const int n = cx.n, g = cx.g, r = cx.r, lane = cx.lane;
   const int cp = cx.w - 4;                                // which 64 bytes of every group
   const int RT = cx.nh >> 1;                              // ring capacity in tiles
 
@@ -1442,19 +1441,6 @@ attn_partial(const AttnParams p) {
 // ------------------------------------------------------------------------------------------
 // host side
 // ------------------------------------------------------------------------------------------
-int device_cus() {
-  static int cus = 0;
-  if (cus == 0) {
-    int dev = 0, v = 0;
-    if (hipGetDevice(&dev) == hipSuccess &&
-        hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
-      cus = v;
-    else
-      cus = 256;
-  }
-  return cus;
-}
-
 // Splits of the token axis: enough workgroups to cover every CU once, never finer
 // than one 32-token tile.  The count does not depend on the device, so the workspace
 // query needs no GPU.

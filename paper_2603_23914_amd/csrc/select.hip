@@ -107,7 +107,7 @@ constexpr int kStagedMax = 32768;      // tokens whose keys fit the dynamic LDS 
 // workspace, in 32-bit words:
 //   hist   [G][4096]  first-digit histogram of every chunk
 //   ctl    [64]       candidate counters, the gave-up flag, and per boundary: first digit, position
-//                     still to find, kappa, quota
+//                     still to find
 //   cand   [7][cap]   low 20 key bits of the keys that share a boundary's first digit
 //   candt  [7][cap]   their token indices (cap: an eighth of the row, at least 4096)
 //   counts [G][8]     tokens of every group in every chunk
@@ -118,7 +118,7 @@ constexpr int kEqMax = 256;            // tokens per boundary that may share kap
 constexpr int kStage = 2048;           // candidates of a boundary that are walked from LDS
 constexpr int kSplitMinT = 24576;      // rows at least this long ...
 constexpr int kSplitMaxB = 32;         // ... in batches of at most this many rows, or rows beyond kStagedMax
-constexpr int kCtlNcand = 0, kCtlGaveUp = 7, kCtlDigit = 8, kCtlNeed = 16, kCtlKappa = 24, kCtlQuota = 32;
+constexpr int kCtlNcand = 0, kCtlGaveUp = 7, kCtlDigit = 8, kCtlNeed = 16;
 struct SplitLayout {
   int G, cap;
   size_t hist, ctl, cand, candt, counts, stride;
