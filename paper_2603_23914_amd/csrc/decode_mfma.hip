@@ -271,6 +271,21 @@ __device__ __forceinline__ void wsum_tile_i8(const char* vA, const char* vB, int
                                              int cp, int g, const uint16_t* vs,
                                              const f32x4_t (&P32)[MT][2], const float (&alpha)[MT],
                                              f32x4_t (&U)[NGL][4][MT]) {
+  // alpha is 1 except when a head's softmax reference exponent moved (rare): the rescaling of
+  // the sums is skipped wave-wide otherwise, as in wsum_tile
+  {
+    bool moved = false;
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) moved |= alpha[mt] != 1.0f;
+    if (__builtin_amdgcn_ballot_w64(moved) != 0) {
+#pragma unroll
+      for (int i = 0; i < NGL; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt) U[i][j][mt] *= alpha[mt];
+    }
+  }
 #pragma unroll
   for (int i = 0; i < NGL; ++i) {
     const int blk = 4 * i + cp;
@@ -304,7 +319,7 @@ __device__ __forceinline__ void wsum_tile_i8(const char* vA, const char* vB, int
         op[k] = code2(__builtin_amdgcn_perm(v[2 * k + 1], v[2 * k], sel) ^ 0x64806480u);
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt)
-        U[i][j][mt] = Mfma<F16Tag>::run(op, Psc[mt], U[i][j][mt] * alpha[mt]);
+        U[i][j][mt] = Mfma<F16Tag>::run(op, Psc[mt], U[i][j][mt]);
     }
   }
 }
@@ -321,6 +336,19 @@ __device__ __forceinline__ void wsum_tile_i4(const char* vA, const char* vB, int
                                              f32x4_t (&U)[NGL][8][MT]) {
   const int doff = (n & 7) * 4;              // this row's dword inside a block (vA / vB carry no lane offset)
   const int sh0 = 16 * (n >> 3);             // its first nibble
+  {                                          // rescale only when a reference exponent moved (rare)
+    bool moved = false;
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) moved |= alpha[mt] != 1.0f;
+    if (__builtin_amdgcn_ballot_w64(moved) != 0) {
+#pragma unroll
+      for (int i = 0; i < NGL; ++i)
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt) U[i][j][mt] *= alpha[mt];
+    }
+  }
 #pragma unroll
   for (int i = 0; i < NGL; ++i) {
 #pragma unroll
@@ -355,7 +383,7 @@ __device__ __forceinline__ void wsum_tile_i4(const char* vA, const char* vB, int
           op[k] = code2_4(((v[2 * k] >> sh) & 0xfu) | (((v[2 * k + 1] >> sh) & 0xfu) << 16) | 0x64006400u);
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
-          U[i][4 * b2 + j][mt] = Mfma<F16Tag>::run(op, Psc[mt], U[i][4 * b2 + j][mt] * alpha[mt]);
+          U[i][4 * b2 + j][mt] = Mfma<F16Tag>::run(op, Psc[mt], U[i][4 * b2 + j][mt]);
       }
     }
   }
