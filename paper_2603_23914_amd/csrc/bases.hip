@@ -22,6 +22,7 @@
 // ap_decompress: Alg. 1 "retrieve cache" as a matrix, Xtilde[t] = C[t, :rank_t] D[:rank_t]: what the
 // periodic re-compression decomposes again (next to the uncompressed tail).
 #include "ap_common.hpp"
+#include "lane_ops.hpp"
 
 namespace ap {
 namespace {
@@ -330,6 +331,7 @@ __global__ void __launch_bounds__(1024)
 jacobi_block(float* __restrict__ W, int64_t w_bstride, int l, int nblk, int step, float tol, int* __restrict__ state) {
   extern __shared__ float rows_lds[];                   // [2 BS][l + 1]
   constexpr int TPP = 1024 / BS;                        // threads per row pair (32 or 64: within one wave)
+  constexpr int NC = BS == 32 ? 19 : 16;                // a thread's columns of a row: l <= 599 / l <= 1024
   const int b = blockIdx.y, tid = threadIdx.x;
   if (state[2 * b + 1]) return;
   // round-robin over nblk blocks (nblk even; a block index >= the real count is an empty block)
@@ -357,27 +359,39 @@ jacobi_block(float* __restrict__ W, int64_t w_bstride, int l, int nblk, int step
     else { ia = (s2 + pr) % (N2 - 1); ib = (s2 + N2 - 1 - pr) % (N2 - 1); }
     float* ra = rows_lds + ia * pitch;
     float* rb = rows_lds + ib * pitch;
+    // the pair's two rows stay in registers between the three dot products and the rotation
+    // (one LDS read of each element per step), and the sums cross the pair's lanes on the DPP path
+    float x[NC], y[NC];
     float al = 0.f, be = 0.f, ga = 0.f;
-    for (int c = sub; c < l; c += TPP) {
-      const float x = ra[c], y = rb[c];
-      al = fmaf(x, x, al);
-      be = fmaf(y, y, be);
-      ga = fmaf(x, y, ga);
-    }
 #pragma unroll
-    for (int o = TPP / 2; o > 0; o >>= 1) {
-      al += __shfl_xor(al, o);
-      be += __shfl_xor(be, o);
-      ga += __shfl_xor(ga, o);
+    for (int k = 0; k < NC; ++k) {
+      const int c = sub + k * TPP;
+      const bool in = c < l;
+      x[k] = in ? ra[c] : 0.f;
+      y[k] = in ? rb[c] : 0.f;
+      al = fmaf(x[k], x[k], al);
+      be = fmaf(y[k], y[k], be);
+      ga = fmaf(x[k], y[k], ga);
+    }
+    al = group_sum<32>(al);
+    be = group_sum<32>(be);
+    ga = group_sum<32>(ga);
+    if (TPP == 64) {
+      al += __shfl_xor(al, 32);
+      be += __shfl_xor(be, 32);
+      ga += __shfl_xor(ga, 32);
     }
     if (fabsf(ga) > tol * sqrtf(al * be)) {               // the same decision in all lanes of the pair
       const float zeta = (be - al) / (2.f * ga);
       const float t = (zeta >= 0.f ? 1.f : -1.f) / (fabsf(zeta) + sqrtf(1.f + zeta * zeta));
       const float cs = 1.f / sqrtf(1.f + t * t), sn = cs * t;
-      for (int c = sub; c < l; c += TPP) {
-        const float x = ra[c], y = rb[c];
-        ra[c] = cs * x - sn * y;
-        rb[c] = sn * x + cs * y;
+#pragma unroll
+      for (int k = 0; k < NC; ++k) {
+        const int c = sub + k * TPP;
+        if (c < l) {
+          ra[c] = cs * x[k] - sn * y[k];
+          rb[c] = sn * x[k] + cs * y[k];
+        }
       }
       if (sub == 0) ++nrot;
     }
