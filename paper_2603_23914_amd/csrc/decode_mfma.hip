@@ -324,17 +324,18 @@ __device__ __forceinline__ void wsum_tile_i8(const char* vA, const char* vB, int
   }
 }
 
-// 4-bit variant.  Column groups are 512 wide (256 bytes); in each the wave owns 64 bytes = two
-// scale blocks of 32 bytes.  A block's eight dwords feed sixteen MFMA rows: row n reads dword
-// n & 7 and takes the nibbles 4 (n >> 3) + j, j = 0..3, one MFMA per j; row n is then column
-// 8 (n & 7) + 4 (n >> 3) + j of the block, so all sixteen rows of a product share one scale block
-// and the token's scale can be folded into its weight as for int8.
+// 4-bit variant.  The wave owns the 64-column scale blocks cp, cp + 4, ... (32 bytes of a row
+// each).  A block's eight dwords feed sixteen MFMA rows: row n reads dword n & 7 and takes the
+// nibbles 4 (n >> 3) + j, j = 0..3, one MFMA per j; row n is then column 8 (n & 7) + 4 (n >> 3) + j
+// of the block, so all sixteen rows of a product share one scale block and the token's scale can
+// be folded into its weight as for int8.  vA / vB: rows 0-15 / 16-31 of the tile, offset to the
+// lane's token rows only.
 template <int MT, int NGL>
 __device__ __forceinline__ void wsum_tile_i4(const char* vA, const char* vB, int pitch, int r,
                                              int cp, int n, int g, const uint16_t* vs,
                                              const f32x4_t (&P32)[MT][2], const float (&alpha)[MT],
-                                             f32x4_t (&U)[NGL][8][MT]) {
-  const int doff = (n & 7) * 4;              // this row's dword inside a block (vA / vB carry no lane offset)
+                                             f32x4_t (&U)[NGL][4][MT]) {
+  const int doff = (n & 7) * 4;              // this row's dword inside a block
   const int sh0 = 16 * (n >> 3);             // its first nibble
   {                                          // rescale only when a reference exponent moved (rare)
     bool moved = false;
@@ -344,23 +345,22 @@ __device__ __forceinline__ void wsum_tile_i4(const char* vA, const char* vB, int
 #pragma unroll
       for (int i = 0; i < NGL; ++i)
 #pragma unroll
-        for (int j = 0; j < 8; ++j)
+        for (int j = 0; j < 4; ++j)
 #pragma unroll
           for (int mt = 0; mt < MT; ++mt) U[i][j][mt] *= alpha[mt];
     }
   }
 #pragma unroll
   for (int i = 0; i < NGL; ++i) {
-#pragma unroll
-    for (int b2 = 0; b2 < 2; ++b2) {
-      const int blk = 8 * i + 2 * cp + b2;
+    {
+      const int blk = 4 * i + cp;
       uint32_t v[8] = {0, 0, 0, 0, 0, 0, 0, 0};
       u32x2_t s01 = {0, 0}, s23 = {0, 0};
       if (blk * 64 < r) {                     // wave-uniform: the block exists at this rank
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          v[e] = *(const uint32_t*)(vA + e * pitch + i * 256 + b2 * 32 + doff);
-          v[4 + e] = *(const uint32_t*)(vB + e * pitch + i * 256 + b2 * 32 + doff);
+          v[e] = *(const uint32_t*)(vA + e * pitch + blk * 32 + doff);
+          v[4 + e] = *(const uint32_t*)(vB + e * pitch + blk * 32 + doff);
         }
         s01 = *(const u32x2_t*)(vs + blk * kTile + 4 * g);
         s23 = *(const u32x2_t*)(vs + blk * kTile + 16 + 4 * g);
@@ -383,7 +383,7 @@ __device__ __forceinline__ void wsum_tile_i4(const char* vA, const char* vB, int
           op[k] = code2_4(((v[2 * k] >> sh) & 0xfu) | (((v[2 * k + 1] >> sh) & 0xfu) << 16) | 0x64006400u);
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
-          U[i][4 * b2 + j][mt] = Mfma<F16Tag>::run(op, Psc[mt], U[i][4 * b2 + j][mt]);
+          U[i][j][mt] = Mfma<F16Tag>::run(op, Psc[mt], U[i][j][mt]);
       }
     }
   }
@@ -1136,8 +1136,10 @@ __device__ __forceinline__ void sum_role(const AttnParams& p) {
   constexpr bool I8 = Q != 0, I4 = Q == 2;
   constexpr bool TS = !RAGGED && !I8 && RMAX == 128;              // token-split mode (see WaveCtx)
   constexpr int RB = I4 ? RMAX / 2 : (I8 ? RMAX : 2 * RMAX);      // bytes of a coefficient row at most
-  constexpr int NGRP = (RB + 255) / 256;                          // 256-byte column groups
-  constexpr int NJ = I4 ? 8 : (I8 ? 4 : 2);                       // accumulator tiles per group
+  // column groups of 256 bytes (16-bit, int8: 128 / 256 columns, the wave owns 64 bytes of each);
+  // 4-bit: groups of four 64-column scale blocks (128 bytes), one block per wave
+  constexpr int NGRP = I4 ? (RMAX / 64 + 3) / 4 : (RB + 255) / 256;
+  constexpr int NJ = I8 ? 4 : 2;                                  // accumulator tiles per group
   constexpr int MAXBLK = (kHalf * (RB / 16 + 1) + 63) / 64;       // 1 KiB blocks per ring unit
   constexpr int NSLOT = (MAXBLK + 3) / 4;
   AP_T_ENTRY
@@ -1354,9 +1356,9 @@ __device__ __forceinline__ void sum_role(const AttnParams& p) {
         P32[mt][1] = __builtin_bit_cast(f32x4_t, cx.Pbuf[(mt * 2 + 1) * 64 + lane]);
       }
       if constexpr (I4) {
-        // the 4-bit reader places its own dword: take the lane's n * 4 off again
+        // the 4-bit reader places its own block and dword: take the wave's and the lane's offsets off
         if (!(cx.dbg & 2))
-          wsum_tile_i4<MT, NGRP>(vA - n * 4, vB - n * 4, pitch_t, RAGGED ? uni(cx.meta[4 * t + 2]) : r, cp, n, g,
+          wsum_tile_i4<MT, NGRP>(vA - cp * 64 - n * 4, vB - cp * 64 - n * 4, pitch_t, RAGGED ? uni(cx.meta[4 * t + 2]) : r, cp, n, g,
                                  cx.vsb + (t & 1) * (r >> 6) * kTile, P32, alpha, U);
       } else {
         if (!(cx.dbg & 2))
@@ -1391,18 +1393,14 @@ __device__ __forceinline__ void sum_role(const AttnParams& p) {
         for (int i = 0; i < NGRP; ++i) {
           const int col0 = I8 ? i * 256 + cp * 64 + g * 16 : i * 128 + cp * 32 + g * 8;
           if constexpr (I4) {
-            // accumulator row 4g + e of tile (b2, j) is column 512 i + 128 cp + 64 b2 + 32 (g & 1) + 8 e
-            // + 4 (g >> 1) + j: the four j of one e are consecutive
+            // accumulator row 4g + e of tile j of block 4 i + cp is column 64 (4 i + cp) + 32 (g & 1)
+            // + 8 e + 4 (g >> 1) + j: the four j of one e are consecutive
+            const int cb = (4 * i + cp) * 64 + (g & 1) * 32 + (g >> 1) * 4;
+            if (cb < r) {
 #pragma unroll
-            for (int b2 = 0; b2 < 2; ++b2) {
-              const int cb = i * 512 + cp * 128 + b2 * 64 + (g & 1) * 32 + (g >> 1) * 4;
-              if (cb < r) {
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                  const f32x4_t v = {U[i][4 * b2 + 0][mt][e], U[i][4 * b2 + 1][mt][e], U[i][4 * b2 + 2][mt][e],
-                                     U[i][4 * b2 + 3][mt][e]};
-                  *(f32x4_t*)(urow + cb + 8 * e) = v;
-                }
+              for (int e = 0; e < 4; ++e) {
+                const f32x4_t v = {U[i][0][mt][e], U[i][1][mt][e], U[i][2][mt][e], U[i][3][mt][e]};
+                *(f32x4_t*)(urow + cb + 8 * e) = v;
               }
             }
           } else if (col0 < r) {
