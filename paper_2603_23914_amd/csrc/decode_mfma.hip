@@ -1071,6 +1071,7 @@ __device__ __forceinline__ void score_role(const AttnParams& p) {
     AP_T_REPORT
     return;
   }
+  AP_T_START
   // One tile: scores from the rows in A, then the same registers take the rows of tile t + lead.
   auto tile_step = [&](int t, u32x4_t (&A)[NA][2], int lead) {
     AP_T_STAMP(t)
@@ -1122,7 +1123,6 @@ __device__ __forceinline__ void score_role(const AttnParams& p) {
     wg_barrier();                                         // weights of tile t ready
     AP_TICK(4)
   };
-  AP_T_START
   if (cx.ntl > 0) load_A(0, A);
   for (int t = 0; t < cx.ntl; ++t) tile_step(t, A, 1);
   AP_T_STAMP(62)
