@@ -382,7 +382,9 @@ __global__ void __launch_bounds__(128) expand_append(const ExpandParams p) {
     j = j < r ? j : r - 1;
     const uint16_t* row = Bb + (size_t)j * HD;
 #pragma unroll
-    for (int pp = 0; pp < KH; ++pp) dst[pp] = *(const u32x4_t*)(row + eoff[pp]);
+    // (a basis row is read once per launch: non-temporal, measured 92.2 -> 88.3 us; the same hint
+    // costs basis_rows 7 us and is not used there)
+    for (int pp = 0; pp < KH; ++pp) dst[pp] = __builtin_nontemporal_load((const u32x4_t*)(row + eoff[pp]));
   };
   u32x4_t vs[KH];
 #pragma unroll
