@@ -733,13 +733,14 @@ int basis_rows_per_wave(int B, int r) {
   return rpw < 4 ? 4 : (rpw > 32 ? 32 : rpw);
 }
 // expand_append: about four two-wave workgroups per CU in one round, but never more than 16 row
-// blocks per sequence at large batches and 8 from 64 sequences on (each block writes an HD-wide
-// partial output that reduce_out reads back; measured at 64 sequences of rank 640: 8 blocks
-// 302.3 us per step, 10 blocks 303.2, 16 blocks 305.3); small batches, whose partial outputs are
-// small anyway, take up to 64 blocks so that the launch still fills the chip.
+// blocks per sequence at large batches (each block writes an HD-wide partial output that
+// reduce_out reads back; measured at 64 sequences of rank 640 with the non-temporal row loads:
+// 16 blocks 292 us per step, 10 blocks 292, 8 blocks 295, 32 blocks 310, 5 blocks 328); small
+// batches, whose partial outputs are small anyway, take up to 64 blocks so that the launch still
+// fills the chip.
 int expand_rows_per_pair(int B, int r) {
   int rpw = (int)(((int64_t)B * r + 1023) / 1024);
-  const int nob_max = B >= 64 ? 8 : B >= 32 ? 16 : B >= 16 ? 32 : 64;
+  const int nob_max = B >= 32 ? 16 : B >= 16 ? 32 : 64;
   const int floor_rows = (r + nob_max - 1) / nob_max;
   if (rpw < floor_rows) rpw = floor_rows;
   return rpw < 4 ? 4 : (rpw > 128 ? 128 : rpw);
