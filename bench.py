@@ -616,6 +616,14 @@ def main():
     ev[3].record()
     torch.cuda.synchronize()
     extra["stream_read_GBps"] = nb * 10 / (ev[0].elapsed_time(ev[1]) * 1e-3) / 1e9
+    for _ in range(3):
+        ap.ap_probe_read_stream(src, nb, sink)
+    ev[0].record()
+    for _ in range(10):
+        ap.ap_probe_read_stream(src, nb, sink)
+    ev[1].record()
+    torch.cuda.synchronize()
+    extra["stream_read_nontemporal_GBps"] = nb * 10 / (ev[0].elapsed_time(ev[1]) * 1e-3) / 1e9
     extra["device_copy_GBps"] = 2.0 * nb * 10 / (ev[2].elapsed_time(ev[3]) * 1e-3) / 1e9
     extra["yardstick_bytes"] = nb
     del dst, src

@@ -482,9 +482,13 @@ ap_status ap_prof_read_launches(float* us, int cap, int* launches);
  *   src    device buffer of at least `bytes` bytes, 16-byte aligned
  *   bytes  positive multiple of ap_probe_read_granule()
  *   sink   device buffer of 8192 uint32 (32 KiB), overwritten
+ * ap_probe_read_stream is the same kernel with the non-temporal hint on its loads
+ * (data that is read once): on MI355X it reads about 15 % faster, and it is the
+ * yardstick for the kernels of the library that stream with that hint.
  * ---------------------------------------------------------------------- */
 size_t ap_probe_read_granule(void);
 ap_status ap_probe_read(const void* src, size_t bytes, void* sink, void* stream);
+ap_status ap_probe_read_stream(const void* src, size_t bytes, void* sink, void* stream);
 
 /* Host strings; ap_last_error() is thread-local and describes the most recent
  * non-AP_OK return on the calling thread ("" if none). */

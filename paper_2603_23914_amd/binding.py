@@ -88,6 +88,8 @@ _lib.ap_probe_read_granule.restype = _sz
 _lib.ap_probe_read_granule.argtypes = []
 _lib.ap_probe_read.restype = _i
 _lib.ap_probe_read.argtypes = [_vp, _sz, _vp, _vp]
+_lib.ap_probe_read_stream.restype = _i
+_lib.ap_probe_read_stream.argtypes = [_vp, _sz, _vp, _vp]
 _lib.ap_prof_enable.restype = None
 _lib.ap_prof_enable.argtypes = [_i]
 _lib.ap_set_fused_value_min_bytes.restype = None
@@ -102,7 +104,7 @@ EXPORTS = ("ap_compact", "ap_bases_workspace_bytes", "ap_compute_bases", "ap_dec
            "ap_decode_attn", "ap_decode_attn_static", "ap_decode_step", "ap_update_importance", "ap_decode_workspace_bytes",
            "ap_raw_workspace_bytes", "ap_raw_attn", "ap_keyonly_workspace_bytes", "ap_keyonly_attn",
            "ap_valueonly_workspace_bytes", "ap_valueonly_attn", "ap_merge_segments", "ap_raw_append", "ap_status_string", "ap_last_error",
-           "ap_version", "ap_set_fused_value_min_bytes", "ap_prof_enable", "ap_prof_read", "ap_prof_read_launches", "ap_probe_read_granule", "ap_probe_read")
+           "ap_version", "ap_set_fused_value_min_bytes", "ap_prof_enable", "ap_prof_read", "ap_prof_read_launches", "ap_probe_read_granule", "ap_probe_read", "ap_probe_read_stream")
 
 # coefficient tensors: int8 = one code per byte, uint8 = 4-bit codes, two per byte
 _DT = {torch.float32: AP_F32, torch.float16: AP_F16, torch.bfloat16: AP_BF16, torch.int8: AP_I8,
@@ -338,6 +340,11 @@ def ap_probe_read_granule() -> int:
 def ap_probe_read(src, nbytes: int, sink, *, stream=None) -> None:
     """Plain streaming read of the first nbytes of src (measurement aid); sink: 8192 int32."""
     _check(_lib.ap_probe_read(_p(src), nbytes, _p(sink), _stream(stream)))
+
+
+def ap_probe_read_stream(src, nbytes: int, sink, *, stream=None) -> None:
+    """Plain streaming read of the first nbytes of src (measurement aid); sink: 8192 int32."""
+    _check(_lib.ap_probe_read_stream(_p(src), nbytes, _p(sink), _stream(stream)))
 
 
 def ap_set_fused_value_min_bytes(min_bytes: int) -> None:

@@ -170,7 +170,7 @@ ap_status launch_update_importance(const float* scores, const float* lse, float*
 
 // measurement aid (probe.hip): plain streaming read
 size_t probe_read_granule();
-ap_status launch_probe_read(const void* src, size_t bytes, uint32_t* sink, hipStream_t stream);
+ap_status launch_probe_read(const void* src, size_t bytes, uint32_t* sink, bool non_temporal, hipStream_t stream);
 
 size_t valueonly_attn_workspace(int B, int H, int H_kv, int d, int T, int r);
 bool valueonly_rank_ok(int d, int r);

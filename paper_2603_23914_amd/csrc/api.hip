@@ -112,7 +112,16 @@ ap_status ap_probe_read(const void* src, size_t bytes, void* sink, void* stream)
   AP_REQUIRE(bytes > 0 && bytes % probe_read_granule() == 0, AP_ERR_INVALID_ARG,
              "ap_probe_read: bytes must be a positive multiple of %zu", probe_read_granule());
   AP_REQUIRE(aligned(src, 16) && aligned(sink, 4), AP_ERR_INVALID_ARG, "ap_probe_read: misaligned pointer");
-  return launch_probe_read(src, bytes, (uint32_t*)sink, (hipStream_t)stream);
+  return launch_probe_read(src, bytes, (uint32_t*)sink, false, (hipStream_t)stream);
+}
+
+ap_status ap_probe_read_stream(const void* src, size_t bytes, void* sink, void* stream) {
+  clear_error();
+  AP_REQUIRE(src && sink, AP_ERR_INVALID_ARG, "ap_probe_read_stream: NULL pointer");
+  AP_REQUIRE(bytes > 0 && bytes % probe_read_granule() == 0, AP_ERR_INVALID_ARG,
+             "ap_probe_read_stream: bytes must be a positive multiple of %zu", probe_read_granule());
+  AP_REQUIRE(aligned(src, 16) && aligned(sink, 4), AP_ERR_INVALID_ARG, "ap_probe_read_stream: misaligned pointer");
+  return launch_probe_read(src, bytes, (uint32_t*)sink, true, (hipStream_t)stream);
 }
 
 void ap_set_fused_value_min_bytes(int64_t min_bytes) { g_fused_value_min_bytes = min_bytes < 0 ? -1 : min_bytes; }

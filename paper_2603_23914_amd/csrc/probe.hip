@@ -12,6 +12,8 @@ constexpr int kProbeUnroll = 8;         // 16-byte loads in flight per thread
 // grid kProbeWgs, 256 threads: workgroup w reads chunks [w * per, (w + 1) * per) of 16 bytes,
 // `per` a multiple of 256 * kProbeUnroll.  The XOR of everything a wave read goes to
 // sink[4 w + wave], so the loads cannot be dropped.
+// NT: the loads carry the non-temporal hint (a stream that is read once).
+template <bool NT>
 __global__ void __launch_bounds__(256)
 stream_read(const u32x4_t* __restrict__ src, uint32_t* __restrict__ sink, size_t per) {
   const u32x4_t* p = src + (size_t)blockIdx.x * per;
@@ -19,7 +21,7 @@ stream_read(const u32x4_t* __restrict__ src, uint32_t* __restrict__ sink, size_t
   for (size_t i = threadIdx.x; i < per; i += 256 * kProbeUnroll) {
     u32x4_t v[kProbeUnroll];
 #pragma unroll
-    for (int u = 0; u < kProbeUnroll; ++u) v[u] = p[i + u * 256];
+    for (int u = 0; u < kProbeUnroll; ++u) v[u] = NT ? __builtin_nontemporal_load(p + i + u * 256) : p[i + u * 256];
 #pragma unroll
     for (int u = 0; u < kProbeUnroll; ++u) acc ^= v[u];
   }
@@ -33,9 +35,12 @@ stream_read(const u32x4_t* __restrict__ src, uint32_t* __restrict__ sink, size_t
 
 size_t probe_read_granule() { return (size_t)kProbeWgs * 256 * kProbeUnroll * 16; }
 
-ap_status launch_probe_read(const void* src, size_t bytes, uint32_t* sink, hipStream_t stream) {
+ap_status launch_probe_read(const void* src, size_t bytes, uint32_t* sink, bool non_temporal, hipStream_t stream) {
   const size_t per = bytes / 16 / kProbeWgs;
-  hipLaunchKernelGGL(stream_read, dim3(kProbeWgs), dim3(256), 0, stream, (const u32x4_t*)src, sink, per);
+  if (non_temporal)
+    hipLaunchKernelGGL(stream_read<true>, dim3(kProbeWgs), dim3(256), 0, stream, (const u32x4_t*)src, sink, per);
+  else
+    hipLaunchKernelGGL(stream_read<false>, dim3(kProbeWgs), dim3(256), 0, stream, (const u32x4_t*)src, sink, per);
   return check_launch("ap_probe_read");
 }
 

@@ -75,3 +75,7 @@ def test_stream_read_probe_reads_every_byte():
     assert np.bitwise_xor.reduce(s0.cpu().numpy().view(np.uint32)) == ref
     with pytest.raises(RuntimeError):
         ap.ap_probe_read(buf, gran - 16, s1)
+    s2 = torch.zeros_like(s0)
+    ap.ap_probe_read_stream(buf, gran, s2)                  # the non-temporal variant reads the same bytes
+    torch.cuda.synchronize()
+    assert torch.equal(s0, s2)
